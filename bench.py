@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the vectorized CNN layer path on one MI355X.
+
+A "step" is one full training step (forward, cost, backward, SGD) of a synthetic network whose
+inputs and weights are already resident in HBM.  The headline line reports images/s on the small
+recognition CNN (workload cfg2); per-layer GFLOP/s of every convolution pass, the roofline figure of
+the dominant call, the other workloads and the CPU-oracle baseline ride along in the same JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--others cfg3,cfg4,cfg5]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+if str(ROOT) not in sys.path:
+    sys.path.insert(0, str(ROOT))
+
+HBM_PEAK_GBS = 8000.0
+MFMA_F32_PEAK_TFLOPS = 157.3
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def conv_geom(net, li):
+    from paper_1501_07338_amd.workloads import Conv
+    L = net.layers[li]
+    assert isinstance(L, Conv)
+    n, c, h, w = net.in_shape(li)
+    _, k, oh, ow = net.shapes[li]
+    return dict(n=n, c=c, h=h, w=w, k=k, r=L.kh, s=L.kw, oh=oh, ow=ow, M=k, K=c * L.kh * L.kw, N=n * oh * ow)
+
+
+def time_calls(fn, iters, stream):
+    """Average duration in ms of `fn` over `iters` back-to-back enqueues, measured with events on
+    the stream the kernels are launched on."""
+    import torch
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    fn()
+    stream.synchronize()
+    start.record(stream)
+    for _ in range(iters):
+        fn()
+    stop.record(stream)
+    stop.synchronize()
+    return start.elapsed_time(stop) / iters
+
+
+def run_workload(name, steps, warmup, per_layer=True, layer_iters=10):
+    import torch
+    from paper_1501_07338_amd import vcnn, workloads as wl
+    from paper_1501_07338_amd.net import TrainStep
+
+    net = wl.make_net(name)
+    inputs, params = wl.make_inputs(net), wl.make_params(net)
+    ts = TrainStep(net, params, inputs, device="cuda:0", first_layer_dx=False)
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        ts.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record(stream)
+    for _ in range(steps):
+        ts.step()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    gpu_ms = ev0.elapsed_time(ev1) / steps
+    ms = max(wall_ms, gpu_ms)
+    res = {"workload": name, "batch": net.batch, "ms_per_step": ms, "gpu_ms_per_step": gpu_ms,
+           "images_per_s": net.batch / (ms * 1e-3), "loss": float(ts.loss.item())}
+    if not per_layer:
+        return res, ts
+
+    layers = []
+    conv_flops = conv_ms = 0.0
+    for li, L in enumerate(net.layers):
+        if not isinstance(L, wl.Conv):
+            continue
+        g = conv_geom(net, li)
+        d = ts.descs[li]
+        w, b = ts.params[li]
+        dw, db = ts.grads[li]
+        a_in, a_out, dy = ts.acts[li], ts.acts[li + 1], ts.dacts[li + 1]
+        flops = 2.0 * g["M"] * g["K"] * g["N"]
+        passes = {
+            "fwd": lambda: vcnn.conv_fwd(d, a_in, w, b, a_out, ts.workspace),
+            "bwd_filter": lambda: vcnn.conv_bwd_filter(d, a_in, dy, dw, db, ts.workspace),
+            "bwd_data": lambda: vcnn.conv_bwd_data(d, w, dy, ts.dacts[li], ts.workspace),
+        }
+        for pname, fn in passes.items():
+            t = time_calls(fn, layer_iters, stream)
+            in_b = 4.0 * g["n"] * g["c"] * g["h"] * g["w"]
+            out_b = 4.0 * g["M"] * g["N"]
+            w_b = 4.0 * g["M"] * g["K"]
+            layers.append({"layer": f"conv{li}", "pass": pname, "M": g["M"], "K": g["K"], "N": g["N"], "ms": t,
+                           "gflops": flops / (t * 1e6), "pct_mfma_f32_peak": 100.0 * flops / (t * 1e9) / MFMA_F32_PEAK_TFLOPS,
+                           "implicit_bytes": in_b + out_b + w_b,
+                           "implicit_gbs": (in_b + out_b + w_b) / (t * 1e6)})
+            if not (li == 0 and pname == "bwd_data"):
+                conv_flops += flops
+                conv_ms += t
+    res["conv_layers"] = layers
+    res["conv_gflops_fwd_bwd"] = conv_flops / (conv_ms * 1e6) if conv_ms else None
+    res["conv_pct_mfma_f32_peak"] = 100.0 * res["conv_gflops_fwd_bwd"] / (MFMA_F32_PEAK_TFLOPS * 1e3) if conv_ms else None
+    return res, ts
+
+
+def dominant_roofline(res):
+    """Roofline record of the call that takes the most time in the step."""
+    layers = res.get("conv_layers") or []
+    if not layers:
+        return None
+    top = max(layers, key=lambda r: r["ms"])
+    flops = 2.0 * top["M"] * top["K"] * top["N"]
+    ai = flops / top["implicit_bytes"]
+    if ai >= MFMA_F32_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS:  # above the machine balance: matrix-core bound
+        ach = flops / (top["ms"] * 1e9)
+        return {"kernel": f"{top['layer']}.{top['pass']}", "bound": "mfma", "achieved": ach, "peak": MFMA_F32_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": ach / MFMA_F32_PEAK_TFLOPS, "traffic": None}
+    ach = top["implicit_bytes"] / (top["ms"] * 1e6)
+    return {"kernel": f"{top['layer']}.{top['pass']}", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None}
+
+
+def cpu_baseline(name, budget_s=20.0):
+    """The fp64 oracle, as it stands, timed on this host's cores on the same workload."""
+    import oracle
+    from oracle.net import train_step
+    from paper_1501_07338_amd import workloads as wl
+    net = wl.make_net(name)
+    inputs, params = wl.make_inputs(net), wl.make_params(net)
+    train_step(net, inputs, params)  # warm-up (loads the library, touches memory)
+    times = []
+    t_all = time.perf_counter()
+    while len(times) < 3 or (time.perf_counter() - t_all < 0.5 * budget_s and len(times) < 15):
+        t0 = time.perf_counter()
+        train_step(net, inputs, params)
+        times.append(time.perf_counter() - t0)
+        if time.perf_counter() - t_all > budget_s:
+            break
+    times.sort()
+    med = times[len(times) // 2]
+    return {"value": net.batch / med, "unit": "images/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"{len(times)} full training steps of {name} (batch {net.batch}), median", "s_per_step": med}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--others", default="cfg1,cfg3,cfg4,cfg5", help="comma list of further workloads to report ('' for none)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the layer path is single-GPU); use --gpus 1")
+
+    import torch
+    from paper_1501_07338_amd import vcnn
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    vcnn.lib()
+
+    main_res, _ = run_workload(args.workload, args.steps, args.warmup)
+    others = {}
+    for name in [s for s in args.others.split(",") if s and s != args.workload]:
+        k = max(3, min(args.steps, 10)) if name in ("cfg4", "cfg5") else args.steps
+        r, ts = run_workload(name, k, max(2, min(args.warmup, 3)), layer_iters=5 if name in ("cfg4", "cfg5") else 10)
+        r["roofline"] = dominant_roofline(r)
+        others[name] = r
+        del ts
+        torch.cuda.empty_cache()
+
+    out = {
+        "metric": "images/sec per training step (conv fwd+bwd GFLOP/s and % MFMA peak alongside)",
+        "value": main_res["images_per_s"], "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: small recognition CNN, batch {main_res['batch']}, full training step "
+                               "(fwd + softmax-CE + bwd + SGD)" if args.workload == "cfg2" else args.workload},
+        "conv_gflops_fwd_bwd": main_res.get("conv_gflops_fwd_bwd"),
+        "conv_pct_mfma_f32_peak": main_res.get("conv_pct_mfma_f32_peak"),
+        "roofline": dominant_roofline(main_res),
+        "conv_layers": main_res.get("conv_layers"),
+        "other_workloads": others,
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(args.workload)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,364 @@
+// C-ABI entry points: argument validation, shape algebra, workspace layout and kernel selection.
+// Validation never touches the HIP runtime, so error paths can be exercised on a host without a GPU.
+#include <atomic>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "common.h"
+
+namespace vcnn {
+
+static thread_local char g_err[512] = "";
+static std::atomic<int> g_conv_algo{VCNN_ALGO_AUTO};
+
+vcnn_status fail(vcnn_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+vcnn_status check_launch(const char* what) {
+  const hipError_t e = hipGetLastError();
+  if (e == hipSuccess) return VCNN_OK;
+  return fail(VCNN_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+static inline size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+static vcnn_status make_geom(const vcnn_conv_desc* d, ConvGeom* g) {
+  if (!d) return fail(VCNN_ERR_NULL, "conv descriptor is NULL");
+  if (d->n <= 0 || d->c <= 0 || d->h <= 0 || d->w <= 0 || d->k <= 0 || d->r <= 0 || d->s <= 0)
+    return fail(VCNN_ERR_SHAPE, "conv: non-positive dimension (n=%d c=%d h=%d w=%d k=%d r=%d s=%d)", d->n, d->c, d->h,
+                d->w, d->k, d->r, d->s);
+  if (d->pad_h < 0 || d->pad_w < 0) return fail(VCNN_ERR_SHAPE, "conv: negative padding");
+  if (d->stride_h <= 0 || d->stride_w <= 0) return fail(VCNN_ERR_SHAPE, "conv: non-positive stride");
+  if (d->r > d->h + 2 * d->pad_h || d->s > d->w + 2 * d->pad_w)
+    return fail(VCNN_ERR_SHAPE, "conv: kernel %dx%d larger than padded input %dx%d", d->r, d->s, d->h + 2 * d->pad_h,
+                d->w + 2 * d->pad_w);
+  if (d->dtype != VCNN_F32 && d->dtype != VCNN_BF16) return fail(VCNN_ERR_UNSUPPORTED, "conv: unknown dtype %d", d->dtype);
+  if (d->act != VCNN_ACT_NONE && d->act != VCNN_ACT_RELU)
+    return fail(VCNN_ERR_UNSUPPORTED, "conv: unknown activation %d", d->act);
+  if (d->stride_h != 1 || d->stride_w != 1)
+    return fail(VCNN_ERR_UNSUPPORTED, "conv: only stride 1 is built (got %dx%d)", d->stride_h, d->stride_w);
+  g->n = d->n, g->c = d->c, g->h = d->h, g->w = d->w, g->k = d->k, g->r = d->r, g->s = d->s;
+  g->ph = d->pad_h, g->pw = d->pad_w;
+  g->oh = d->h + 2 * d->pad_h - d->r + 1;
+  g->ow = d->w + 2 * d->pad_w - d->s + 1;
+  g->P = (int64_t)g->oh * g->ow;
+  g->M = d->k;
+  g->K = (int64_t)d->c * d->r * d->s;
+  g->N = (int64_t)d->n * g->P;
+  if (g->N > 0x7fffffffLL || g->K > 0x7fffffffLL || (int64_t)d->n * d->c * d->h * d->w > 0x7fffffffLL * 4)
+    return fail(VCNN_ERR_UNSUPPORTED, "conv: problem too large (N=%lld K=%lld)", (long long)g->N, (long long)g->K);
+  return VCNN_OK;
+}
+
+static vcnn_status need_f32(int32_t dtype, const char* what) {
+  if (dtype == VCNN_F32) return VCNN_OK;
+  if (dtype == VCNN_BF16) return fail(VCNN_ERR_UNSUPPORTED, "%s: the bfloat16 variant is not built", what);
+  return fail(VCNN_ERR_UNSUPPORTED, "%s: unknown dtype %d", what, dtype);
+}
+
+static vcnn_status check_ws(const void* ws, size_t have, size_t need, const char* what) {
+  if (need == 0) return VCNN_OK;
+  if (!ws) return fail(VCNN_ERR_WORKSPACE, "%s: workspace is NULL but %zu bytes are needed", what, need);
+  if (reinterpret_cast<uintptr_t>(ws) & 255) return fail(VCNN_ERR_WORKSPACE, "%s: workspace is not 256-byte aligned", what);
+  if (have < need) return fail(VCNN_ERR_WORKSPACE, "%s: workspace has %zu bytes, %zu needed", what, have, need);
+  return VCNN_OK;
+}
+
+// The 1x1, unpadded layer's patch matrix is the input itself (per sample), so no unroll is needed.
+static bool is_pointwise(const ConvGeom& g) { return g.r == 1 && g.s == 1 && g.ph == 0 && g.pw == 0; }
+
+static size_t col_bytes(const ConvGeom& g) { return align256((size_t)g.K * g.N * sizeof(float)); }
+
+static size_t workspace_need(const ConvGeom& g, int pass) {
+  switch (pass) {
+    case VCNN_PASS_FWD:
+      return is_pointwise(g) ? 0 : col_bytes(g);
+    case VCNN_PASS_BWD_FILTER:
+      return col_bytes(g) + align256(bwd_filter_partial_bytes(g));
+    case VCNN_PASS_BWD_DATA:
+      return is_pointwise(g) ? 0 : col_bytes(g);
+    default:
+      return 0;
+  }
+}
+
+}  // namespace vcnn
+
+using namespace vcnn;
+
+extern "C" {
+
+const char* vcnn_status_string(vcnn_status st) {
+  switch (st) {
+    case VCNN_OK: return "ok";
+    case VCNN_ERR_NULL: return "null pointer";
+    case VCNN_ERR_SHAPE: return "bad shape";
+    case VCNN_ERR_WORKSPACE: return "bad workspace";
+    case VCNN_ERR_UNSUPPORTED: return "unsupported";
+    case VCNN_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+const char* vcnn_last_error(void) { return g_err; }
+int32_t vcnn_version(void) { return 100; }
+
+vcnn_status vcnn_set_conv_algo(int32_t algo) {
+  if (algo != VCNN_ALGO_AUTO && algo != VCNN_ALGO_EXPLICIT && algo != VCNN_ALGO_IMPLICIT)
+    return fail(VCNN_ERR_UNSUPPORTED, "unknown conv algorithm %d", algo);
+  g_conv_algo.store(algo);
+  return VCNN_OK;
+}
+
+vcnn_status vcnn_conv_out_shape(const vcnn_conv_desc* d, int32_t* oh, int32_t* ow) {
+  if (!oh || !ow) return fail(VCNN_ERR_NULL, "conv_out_shape: NULL out-parameter");
+  ConvGeom g;
+  if (vcnn_status s = make_geom(d, &g)) return s;
+  *oh = g.oh, *ow = g.ow;
+  return VCNN_OK;
+}
+
+vcnn_status vcnn_conv_workspace_bytes(const vcnn_conv_desc* d, int32_t pass, size_t* bytes) {
+  if (!bytes) return fail(VCNN_ERR_NULL, "conv_workspace_bytes: NULL out-parameter");
+  ConvGeom g;
+  if (vcnn_status s = make_geom(d, &g)) return s;
+  if (pass < VCNN_PASS_FWD || pass > VCNN_PASS_BWD_DATA) return fail(VCNN_ERR_UNSUPPORTED, "unknown pass %d", pass);
+  *bytes = workspace_need(g, pass);
+  return VCNN_OK;
+}
+
+vcnn_status vcnn_im2col(const vcnn_conv_desc* d, const void* x, void* col, void* stream) {
+  ConvGeom g;
+  if (vcnn_status s = make_geom(d, &g)) return s;
+  if (!x || !col) return fail(VCNN_ERR_NULL, "im2col: NULL tensor");
+  if (vcnn_status s = need_f32(d->dtype, "im2col")) return s;
+  return launch_im2col_f32(g, (const float*)x, (float*)col, (hipStream_t)stream);
+}
+
+vcnn_status vcnn_col2im(const vcnn_conv_desc* d, const float* col, void* dx, void* stream) {
+  ConvGeom g;
+  if (vcnn_status s = make_geom(d, &g)) return s;
+  if (!col || !dx) return fail(VCNN_ERR_NULL, "col2im: NULL tensor");
+  if (vcnn_status s = need_f32(d->dtype, "col2im")) return s;
+  return launch_col2im_f32(g, col, (float*)dx, (hipStream_t)stream);
+}
+
+vcnn_status vcnn_conv_fwd(const vcnn_conv_desc* d, const void* x, const void* w, const float* bias, void* y,
+                          void* workspace, size_t workspace_bytes, void* stream) {
+  ConvGeom g;
+  if (vcnn_status s = make_geom(d, &g)) return s;
+  if (!x || !w || !y) return fail(VCNN_ERR_NULL, "conv_fwd: NULL tensor");
+  if (vcnn_status s = need_f32(d->dtype, "conv_fwd")) return s;
+  if (vcnn_status s = check_ws(workspace, workspace_bytes, workspace_need(g, VCNN_PASS_FWD), "conv_fwd")) return s;
+  hipStream_t st = (hipStream_t)stream;
+
+  GemmArgs a{};
+  a.A = (const float*)w, a.C = (float*)y, a.bias = bias;
+  a.M = (int)g.M, a.N = (int)g.N, a.K = (int)g.K;
+  a.a_si = g.K, a.a_sk = 1;
+  a.c_si = g.P, a.c_sj = 1, a.c_P = (int)g.P, a.c_simg = g.M * g.P;
+  a.relu = d->act == VCNN_ACT_RELU;
+  if (is_pointwise(g)) {
+    // patch matrix == input: B(k, j) = x[n][k][p]
+    a.B = (const float*)x;
+    a.b_sk = g.P, a.b_sj = 1, a.b_P = (int)g.P, a.b_simg = g.K * g.P;
+  } else {
+    float* col = (float*)workspace;
+    if (vcnn_status s = launch_im2col_f32(g, (const float*)x, col, st)) return s;
+    a.B = col;
+    a.b_sk = g.N, a.b_sj = 1, a.b_P = 0, a.b_simg = 0;
+  }
+  return launch_gemm_f32(a, st);
+}
+
+vcnn_status vcnn_conv_bwd_filter(const vcnn_conv_desc* d, const void* x, const void* dy, float* dw, float* dbias,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+  ConvGeom g;
+  if (vcnn_status s = make_geom(d, &g)) return s;
+  if (!x || !dy || !dw) return fail(VCNN_ERR_NULL, "conv_bwd_filter: NULL tensor");
+  if (vcnn_status s = need_f32(d->dtype, "conv_bwd_filter")) return s;
+  if (vcnn_status s = check_ws(workspace, workspace_bytes, workspace_need(g, VCNN_PASS_BWD_FILTER), "conv_bwd_filter"))
+    return s;
+  hipStream_t st = (hipStream_t)stream;
+  float* col = (float*)workspace;
+  float* partial = (float*)((char*)workspace + col_bytes(g));
+  if (vcnn_status s = launch_im2col_f32(g, (const float*)x, col, st)) return s;
+  if (vcnn_status s = launch_bwd_filter_gemm_f32(g, (const float*)dy, col, dw, partial, st)) return s;
+  if (dbias) return launch_bias_grad_f32(g, (const float*)dy, dbias, st);
+  return VCNN_OK;
+}
+
+vcnn_status vcnn_conv_bwd_data(const vcnn_conv_desc* d, const void* w, const void* dy, void* dx, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+  ConvGeom g;
+  if (vcnn_status s = make_geom(d, &g)) return s;
+  if (!w || !dy || !dx) return fail(VCNN_ERR_NULL, "conv_bwd_data: NULL tensor");
+  if (vcnn_status s = need_f32(d->dtype, "conv_bwd_data")) return s;
+  if (vcnn_status s = check_ws(workspace, workspace_bytes, workspace_need(g, VCNN_PASS_BWD_DATA), "conv_bwd_data"))
+    return s;
+  hipStream_t st = (hipStream_t)stream;
+  float* dcol = (float*)workspace;
+  // dcol[k][j] = sum_m W[m][k] * dY(m, j)
+  GemmArgs a{};
+  a.A = (const float*)w, a.B = (const float*)dy, a.C = dcol, a.bias = nullptr;
+  a.M = (int)g.K, a.N = (int)g.N, a.K = (int)g.M;
+  a.a_si = 1, a.a_sk = g.K;
+  a.b_sk = g.P, a.b_sj = 1, a.b_P = (int)g.P, a.b_simg = g.M * g.P;
+  a.relu = 0;
+  if (is_pointwise(g)) {
+    // phi_c^{-1} is the identity per sample: store the product straight into dx[n][c][p].
+    a.C = (float*)dx;
+    a.c_si = g.P, a.c_sj = 1, a.c_P = (int)g.P, a.c_simg = g.K * g.P;
+    return launch_gemm_f32(a, st);
+  }
+  a.c_si = g.N, a.c_sj = 1, a.c_P = 0, a.c_simg = 0;
+  if (vcnn_status s = launch_gemm_f32(a, st)) return s;
+  return launch_col2im_f32(g, dcol, (float*)dx, st);
+}
+
+static vcnn_status check_pool(const vcnn_pool_desc* d, int* oh, int* ow) {
+  if (!d) return fail(VCNN_ERR_NULL, "pool descriptor is NULL");
+  if (d->n <= 0 || d->c <= 0 || d->h <= 0 || d->w <= 0 || d->win_h <= 0 || d->win_w <= 0 || d->stride_h <= 0 ||
+      d->stride_w <= 0)
+    return fail(VCNN_ERR_SHAPE, "pool: non-positive dimension");
+  if (d->win_h > d->h || d->win_w > d->w)
+    return fail(VCNN_ERR_SHAPE, "pool: window %dx%d larger than input %dx%d", d->win_h, d->win_w, d->h, d->w);
+  if ((int64_t)d->h * d->w > 0x7fffffffLL) return fail(VCNN_ERR_UNSUPPORTED, "pool: plane too large for int32 indices");
+  *oh = (d->h - d->win_h) / d->stride_h + 1;
+  *ow = (d->w - d->win_w) / d->stride_w + 1;
+  return VCNN_OK;
+}
+
+vcnn_status vcnn_pool_out_shape(const vcnn_pool_desc* d, int32_t* oh, int32_t* ow) {
+  if (!oh || !ow) return fail(VCNN_ERR_NULL, "pool_out_shape: NULL out-parameter");
+  int a, b;
+  if (vcnn_status s = check_pool(d, &a, &b)) return s;
+  *oh = a, *ow = b;
+  return VCNN_OK;
+}
+
+vcnn_status vcnn_pool_fwd(const vcnn_pool_desc* d, const void* x, void* y, int32_t* argmax, void* stream) {
+  int oh, ow;
+  if (vcnn_status s = check_pool(d, &oh, &ow)) return s;
+  if (!x || !y || !argmax) return fail(VCNN_ERR_NULL, "pool_fwd: NULL tensor");
+  if (vcnn_status s = need_f32(d->dtype, "pool_fwd")) return s;
+  return launch_pool_fwd_f32(*d, oh, ow, (const float*)x, (float*)y, argmax, (hipStream_t)stream);
+}
+
+vcnn_status vcnn_pool_bwd(const vcnn_pool_desc* d, const void* dy, const int32_t* argmax, void* dx, void* stream) {
+  int oh, ow;
+  if (vcnn_status s = check_pool(d, &oh, &ow)) return s;
+  if (!dy || !dx || !argmax) return fail(VCNN_ERR_NULL, "pool_bwd: NULL tensor");
+  if (vcnn_status s = need_f32(d->dtype, "pool_bwd")) return s;
+  return launch_pool_bwd_f32(*d, oh, ow, (const float*)dy, argmax, (float*)dx, (hipStream_t)stream);
+}
+
+vcnn_status vcnn_act_fwd(int32_t act, int32_t dtype, size_t count, const void* x, void* y, void* stream) {
+  if (act != VCNN_ACT_RELU) return fail(VCNN_ERR_UNSUPPORTED, "act_fwd: activation %d is not built", act);
+  if (vcnn_status s = need_f32(dtype, "act_fwd")) return s;
+  if (count == 0) return VCNN_OK;
+  if (!x || !y) return fail(VCNN_ERR_NULL, "act_fwd: NULL tensor");
+  return launch_relu_fwd_f32(count, (const float*)x, (float*)y, (hipStream_t)stream);
+}
+
+vcnn_status vcnn_act_bwd(int32_t act, int32_t dtype, size_t count, const void* ref, const void* dy, void* dx,
+                         void* stream) {
+  if (act != VCNN_ACT_RELU) return fail(VCNN_ERR_UNSUPPORTED, "act_bwd: activation %d is not built", act);
+  if (vcnn_status s = need_f32(dtype, "act_bwd")) return s;
+  if (count == 0) return VCNN_OK;
+  if (!ref || !dy || !dx) return fail(VCNN_ERR_NULL, "act_bwd: NULL tensor");
+  return launch_relu_bwd_f32(count, (const float*)ref, (const float*)dy, (float*)dx, (hipStream_t)stream);
+}
+
+static vcnn_status check_fc(int32_t batch, int32_t in_f, int32_t out_f) {
+  if (batch <= 0 || in_f <= 0 || out_f <= 0)
+    return fail(VCNN_ERR_SHAPE, "fc: non-positive dimension (batch=%d in=%d out=%d)", batch, in_f, out_f);
+  return VCNN_OK;
+}
+
+vcnn_status vcnn_fc_fwd(int32_t dtype, int32_t batch, int32_t in_f, int32_t out_f, int32_t act, const void* x,
+                        const void* w, const float* bias, void* y, void* stream) {
+  if (vcnn_status s = check_fc(batch, in_f, out_f)) return s;
+  if (act != VCNN_ACT_NONE && act != VCNN_ACT_RELU) return fail(VCNN_ERR_UNSUPPORTED, "fc_fwd: unknown activation %d", act);
+  if (vcnn_status s = need_f32(dtype, "fc_fwd")) return s;
+  if (!x || !w || !y) return fail(VCNN_ERR_NULL, "fc_fwd: NULL tensor");
+  // C(i = o, j = b) = sum_k W[o][k] * X[b][k], stored at y[b*O + o]
+  GemmArgs a{};
+  a.A = (const float*)w, a.B = (const float*)x, a.C = (float*)y, a.bias = bias;
+  a.M = out_f, a.N = batch, a.K = in_f;
+  a.a_si = in_f, a.a_sk = 1;
+  a.b_sk = 1, a.b_sj = in_f, a.b_P = 0;
+  a.c_si = 1, a.c_sj = out_f, a.c_P = 0;
+  a.relu = act == VCNN_ACT_RELU;
+  return launch_gemm_f32(a, (hipStream_t)stream);
+}
+
+vcnn_status vcnn_fc_bwd(int32_t dtype, int32_t batch, int32_t in_f, int32_t out_f, const void* x, const void* w,
+                        const void* dy, float* dw, float* dbias, void* dx, void* stream) {
+  if (vcnn_status s = check_fc(batch, in_f, out_f)) return s;
+  if (vcnn_status s = need_f32(dtype, "fc_bwd")) return s;
+  if (!x || !w || !dy || !dw) return fail(VCNN_ERR_NULL, "fc_bwd: NULL tensor");
+  hipStream_t st = (hipStream_t)stream;
+  {  // dW(i = o, j = i_) = sum_b dY[b][o] * X[b][i_]
+    GemmArgs a{};
+    a.A = (const float*)dy, a.B = (const float*)x, a.C = dw;
+    a.M = out_f, a.N = in_f, a.K = batch;
+    a.a_si = 1, a.a_sk = out_f;
+    a.b_sk = in_f, a.b_sj = 1, a.b_P = 0;
+    a.c_si = in_f, a.c_sj = 1, a.c_P = 0;
+    if (vcnn_status s = launch_gemm_f32(a, st)) return s;
+  }
+  if (dbias)
+    if (vcnn_status s = launch_col_sum_f32(batch, out_f, (const float*)dy, dbias, st)) return s;
+  if (dx) {  // dX(i = b, j = i_) = sum_o dY[b][o] * W[o][i_]
+    GemmArgs a{};
+    a.A = (const float*)dy, a.B = (const float*)w, a.C = (float*)dx;
+    a.M = batch, a.N = in_f, a.K = out_f;
+    a.a_si = out_f, a.a_sk = 1;
+    a.b_sk = in_f, a.b_sj = 1, a.b_P = 0;
+    a.c_si = in_f, a.c_sj = 1, a.c_P = 0;
+    if (vcnn_status s = launch_gemm_f32(a, st)) return s;
+  }
+  return VCNN_OK;
+}
+
+vcnn_status vcnn_softmax_loss(int32_t batch, int32_t classes, const float* logits, const int32_t* labels, float* loss,
+                              float* dlogits, void* stream) {
+  if (batch <= 0 || classes <= 0) return fail(VCNN_ERR_SHAPE, "softmax_loss: non-positive dimension");
+  if (!logits || !labels || !loss) return fail(VCNN_ERR_NULL, "softmax_loss: NULL tensor");
+  return launch_softmax_loss_f32(batch, classes, logits, labels, loss, dlogits, (hipStream_t)stream);
+}
+
+vcnn_status vcnn_l2_loss(int32_t dtype, size_t count, int32_t batch, const void* y, const float* target, float* loss,
+                         void* dy, void* stream) {
+  if (batch <= 0 || count == 0) return fail(VCNN_ERR_SHAPE, "l2_loss: empty tensor");
+  if (vcnn_status s = need_f32(dtype, "l2_loss")) return s;
+  if (!y || !target) return fail(VCNN_ERR_NULL, "l2_loss: NULL tensor");
+  return launch_l2_loss_f32(count, batch, (const float*)y, target, loss, (float*)dy, (hipStream_t)stream);
+}
+
+vcnn_status vcnn_sgd_update(size_t count, float lr, float* w, const float* dw, void* stream) {
+  if (count == 0) return VCNN_OK;
+  if (!w || !dw) return fail(VCNN_ERR_NULL, "sgd_update: NULL tensor");
+  return launch_sgd_f32(count, lr, w, dw, (hipStream_t)stream);
+}
+
+vcnn_status vcnn_f32_to_bf16(size_t count, const float* src, void* dst, void* stream) {
+  if (count == 0) return VCNN_OK;
+  if (!src || !dst) return fail(VCNN_ERR_NULL, "f32_to_bf16: NULL tensor");
+  return launch_f32_to_bf16(count, src, (uint16_t*)dst, (hipStream_t)stream);
+}
+
+vcnn_status vcnn_bf16_to_f32(size_t count, const void* src, float* dst, void* stream) {
+  if (count == 0) return VCNN_OK;
+  if (!src || !dst) return fail(VCNN_ERR_NULL, "bf16_to_f32: NULL tensor");
+  return launch_bf16_to_f32(count, (const uint16_t*)src, dst, (hipStream_t)stream);
+}
+
+}  // extern "C"

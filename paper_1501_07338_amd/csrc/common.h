@@ -1,0 +1,76 @@
+// Internal declarations shared by the vcnn translation units (not part of the public ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/vcnn.h"
+
+namespace vcnn {
+
+// Records a formatted message for vcnn_last_error() and returns `st`.
+vcnn_status fail(vcnn_status st, const char* fmt, ...);
+// Converts the HIP error state after a launch into a status.
+vcnn_status check_launch(const char* what);
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Shape of one convolution layer in the paper's matrix terms: the kernel matrix is M x K, the patch
+// matrix K x N, the feature-map matrix M x N (Fig. 2 / Fig. 5: one feature map per row, samples side
+// by side).
+struct ConvGeom {
+  int n, c, h, w, k, r, s, ph, pw, oh, ow;
+  int64_t P;      // oh*ow: columns per sample
+  int64_t M, K, N;
+};
+
+// ---- unroll.hip ---------------------------------------------------------------------------------
+vcnn_status launch_im2col_f32(const ConvGeom& g, const float* x, float* col, hipStream_t st);
+vcnn_status launch_col2im_f32(const ConvGeom& g, const float* col, float* dx, hipStream_t st);
+
+// ---- gemm.hip -----------------------------------------------------------------------------------
+// Generic strided product C(i,j) = act(bias[i] + sum_k A(i,k) B(k,j)), fp32 MFMA.
+//   A(i,k) = A[i*a_si + k*a_sk]
+//   B(k,j) = B[k*b_sk + jmap_b(j)],  jmap(j) = P ? (j / P)*s_img + (j % P)*s_j : j*s_j
+//   C(i,j) = C[i*c_si + jmap_c(j)]
+// Exactly one of (a_si, a_sk) and one of (b_sk, b_sj) should be 1 for coalesced loads.
+struct GemmArgs {
+  const float* A;
+  const float* B;
+  float* C;
+  const float* bias;  // per row i, nullable
+  int M, N, K;
+  int64_t a_si, a_sk;
+  int64_t b_sk, b_sj, b_simg;
+  int b_P;
+  int64_t c_si, c_sj, c_simg;
+  int c_P;
+  int relu;
+};
+vcnn_status launch_gemm_f32(const GemmArgs& a, hipStream_t st);
+
+// Filter-gradient product: dW[m][k] = sum_j dY(m,j) * col[k][j] with dY in [N][M][P] layout, contraction
+// split over `splits` column ranges whose partial sums are combined in a fixed order.
+int bwd_filter_splits(const ConvGeom& g);
+size_t bwd_filter_partial_bytes(const ConvGeom& g);
+vcnn_status launch_bwd_filter_gemm_f32(const ConvGeom& g, const float* dy, const float* col, float* dw,
+                                       float* partial, hipStream_t st);
+
+// ---- pointwise.hip ------------------------------------------------------------------------------
+vcnn_status launch_bias_grad_f32(const ConvGeom& g, const float* dy, float* db, hipStream_t st);
+vcnn_status launch_relu_fwd_f32(size_t count, const float* x, float* y, hipStream_t st);
+vcnn_status launch_relu_bwd_f32(size_t count, const float* ref, const float* dy, float* dx, hipStream_t st);
+vcnn_status launch_pool_fwd_f32(const vcnn_pool_desc& d, int oh, int ow, const float* x, float* y, int32_t* argmax,
+                                hipStream_t st);
+vcnn_status launch_pool_bwd_f32(const vcnn_pool_desc& d, int oh, int ow, const float* dy, const int32_t* argmax,
+                                float* dx, hipStream_t st);
+vcnn_status launch_col_sum_f32(int rows, int cols, const float* a, float* out, hipStream_t st);  // out[c] = sum_r a[r][c]
+vcnn_status launch_softmax_loss_f32(int batch, int classes, const float* z, const int32_t* labels, float* loss,
+                                    float* dz, hipStream_t st);
+vcnn_status launch_l2_loss_f32(size_t count, int batch, const float* y, const float* t, float* loss, float* dy,
+                               hipStream_t st);
+vcnn_status launch_sgd_f32(size_t count, float lr, float* w, const float* dw, hipStream_t st);
+vcnn_status launch_f32_to_bf16(size_t count, const float* src, uint16_t* dst, hipStream_t st);
+vcnn_status launch_bf16_to_f32(size_t count, const uint16_t* src, float* dst, hipStream_t st);
+
+}  // namespace vcnn

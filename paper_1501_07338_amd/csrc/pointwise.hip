@@ -1,0 +1,300 @@
+// Bandwidth-bound operators around the convolution: sigma (ReLU), max pooling with argmax record
+// (phi_p of Eq. 3 with the max operation), bias gradient, cost functions and the SGD update.
+#include "common.h"
+
+namespace vcnn {
+
+static constexpr int kThreads = 256;
+
+// ---- ReLU ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void relu_fwd_f32_kernel(size_t count, const float* x, float* y) {
+  const size_t i = ((size_t)blockIdx.x * kThreads + threadIdx.x) * 4;
+  if (i + 3 < count && ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y)) & 15) == 0) {
+    float4 v = *reinterpret_cast<const float4*>(x + i);
+    v.x = fmaxf(v.x, 0.f), v.y = fmaxf(v.y, 0.f), v.z = fmaxf(v.z, 0.f), v.w = fmaxf(v.w, 0.f);
+    *reinterpret_cast<float4*>(y + i) = v;
+  } else {
+    for (size_t e = i; e < count && e < i + 4; ++e) y[e] = fmaxf(x[e], 0.f);
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void relu_bwd_f32_kernel(size_t count, const float* ref, const float* dy,
+                                                                float* dx) {
+  const size_t i = ((size_t)blockIdx.x * kThreads + threadIdx.x) * 4;
+  const uintptr_t al = reinterpret_cast<uintptr_t>(ref) | reinterpret_cast<uintptr_t>(dy) | reinterpret_cast<uintptr_t>(dx);
+  if (i + 3 < count && (al & 15) == 0) {
+    const float4 r = *reinterpret_cast<const float4*>(ref + i);
+    float4 g = *reinterpret_cast<const float4*>(dy + i);
+    g.x = r.x > 0.f ? g.x : 0.f, g.y = r.y > 0.f ? g.y : 0.f, g.z = r.z > 0.f ? g.z : 0.f, g.w = r.w > 0.f ? g.w : 0.f;
+    *reinterpret_cast<float4*>(dx + i) = g;
+  } else {
+    for (size_t e = i; e < count && e < i + 4; ++e) dx[e] = ref[e] > 0.f ? dy[e] : 0.f;
+  }
+}
+
+static vcnn_status grid_for(size_t work_items, unsigned* blocks) {
+  const size_t b = (work_items + kThreads - 1) / kThreads;
+  if (b > 0x7fffffffULL) return fail(VCNN_ERR_UNSUPPORTED, "tensor too large for one launch");
+  *blocks = (unsigned)(b ? b : 1);
+  return VCNN_OK;
+}
+
+vcnn_status launch_relu_fwd_f32(size_t count, const float* x, float* y, hipStream_t st) {
+  unsigned blocks;
+  if (vcnn_status s = grid_for((count + 3) / 4, &blocks)) return s;
+  hipLaunchKernelGGL(relu_fwd_f32_kernel, dim3(blocks), dim3(kThreads), 0, st, count, x, y);
+  return check_launch("relu_fwd_f32");
+}
+
+vcnn_status launch_relu_bwd_f32(size_t count, const float* ref, const float* dy, float* dx, hipStream_t st) {
+  unsigned blocks;
+  if (vcnn_status s = grid_for((count + 3) / 4, &blocks)) return s;
+  hipLaunchKernelGGL(relu_bwd_f32_kernel, dim3(blocks), dim3(kThreads), 0, st, count, ref, dy, dx);
+  return check_launch("relu_bwd_f32");
+}
+
+// ---- max pooling --------------------------------------------------------------------------------
+// One thread per output element, ow fastest.  Row-major scan with a strict '>' keeps the lowest
+// flat index among equal maxima.
+__global__ __launch_bounds__(kThreads) void pool_fwd_f32_kernel(vcnn_pool_desc d, int oh_n, int ow_n,
+                                                                const float* __restrict__ x, float* __restrict__ y,
+                                                                int32_t* __restrict__ argmax, int64_t total) {
+  const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= total) return;
+  const int ow = (int)(idx % ow_n);
+  const int64_t t = idx / ow_n;
+  const int oh = (int)(t % oh_n);
+  const int64_t nc = t / oh_n;
+  const float* xp = x + nc * d.h * d.w;
+  const int h0 = oh * d.stride_h, w0 = ow * d.stride_w;
+  float best = xp[h0 * d.w + w0];
+  int bi = h0 * d.w + w0;
+  for (int i = 0; i < d.win_h; ++i)
+    for (int j = 0; j < d.win_w; ++j) {
+      const int pos = (h0 + i) * d.w + w0 + j;
+      const float v = xp[pos];
+      if (v > best) {
+        best = v;
+        bi = pos;
+      }
+    }
+  y[idx] = best;
+  argmax[idx] = bi;
+}
+
+// One thread per input element: sums, in ascending window order, the gradients of the windows that
+// cover it and recorded it.  Gather form, so no atomics and every dx element is written.
+__global__ __launch_bounds__(kThreads) void pool_bwd_f32_kernel(vcnn_pool_desc d, int oh_n, int ow_n,
+                                                                const float* __restrict__ dy,
+                                                                const int32_t* __restrict__ argmax,
+                                                                float* __restrict__ dx, int64_t total) {
+  const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= total) return;
+  const int wi = (int)(idx % d.w);
+  const int64_t t = idx / d.w;
+  const int hi = (int)(t % d.h);
+  const int64_t nc = t / d.h;
+  const int pos = hi * d.w + wi;
+  // windows oh with oh*stride <= hi <= oh*stride + win - 1
+  int oh_lo = hi - d.win_h + 1;
+  oh_lo = oh_lo > 0 ? (oh_lo + d.stride_h - 1) / d.stride_h : 0;
+  const int oh_hi = min(oh_n - 1, hi / d.stride_h);
+  int ow_lo = wi - d.win_w + 1;
+  ow_lo = ow_lo > 0 ? (ow_lo + d.stride_w - 1) / d.stride_w : 0;
+  const int ow_hi = min(ow_n - 1, wi / d.stride_w);
+  const int64_t base = nc * oh_n * ow_n;
+  float acc = 0.f;
+  for (int oh = oh_lo; oh <= oh_hi; ++oh)
+    for (int ow = ow_lo; ow <= ow_hi; ++ow) {
+      const int64_t o = base + (int64_t)oh * ow_n + ow;
+      if (argmax[o] == pos) acc += dy[o];
+    }
+  dx[idx] = acc;
+}
+
+vcnn_status launch_pool_fwd_f32(const vcnn_pool_desc& d, int oh, int ow, const float* x, float* y, int32_t* argmax,
+                                hipStream_t st) {
+  const int64_t total = (int64_t)d.n * d.c * oh * ow;
+  unsigned blocks;
+  if (vcnn_status s = grid_for((size_t)total, &blocks)) return s;
+  hipLaunchKernelGGL(pool_fwd_f32_kernel, dim3(blocks), dim3(kThreads), 0, st, d, oh, ow, x, y, argmax, total);
+  return check_launch("pool_fwd_f32");
+}
+
+vcnn_status launch_pool_bwd_f32(const vcnn_pool_desc& d, int oh, int ow, const float* dy, const int32_t* argmax,
+                                float* dx, hipStream_t st) {
+  const int64_t total = (int64_t)d.n * d.c * d.h * d.w;
+  unsigned blocks;
+  if (vcnn_status s = grid_for((size_t)total, &blocks)) return s;
+  hipLaunchKernelGGL(pool_bwd_f32_kernel, dim3(blocks), dim3(kThreads), 0, st, d, oh, ow, dy, argmax, dx, total);
+  return check_launch("pool_bwd_f32");
+}
+
+// ---- block reduction in a fixed order --------------------------------------------------------------
+__device__ __forceinline__ float block_sum(float v, float* sm) {
+  sm[threadIdx.x] = v;
+  __syncthreads();
+  for (int s = kThreads / 2; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) sm[threadIdx.x] += sm[threadIdx.x + s];
+    __syncthreads();
+  }
+  const float r = sm[0];
+  __syncthreads();
+  return r;
+}
+
+// db[m] = sum over samples and positions of dy[n][m][p]: one block per output map.
+__global__ __launch_bounds__(kThreads) void bias_grad_f32_kernel(int n, int M, int64_t P, const float* __restrict__ dy,
+                                                                 float* __restrict__ db) {
+  __shared__ float sm[kThreads];
+  const int m = blockIdx.x;
+  float acc = 0.f;
+  for (int i = 0; i < n; ++i) {
+    const float* row = dy + ((int64_t)i * M + m) * P;
+    for (int64_t p = threadIdx.x; p < P; p += kThreads) acc += row[p];
+  }
+  const float total = block_sum(acc, sm);
+  if (threadIdx.x == 0) db[m] = total;
+}
+
+vcnn_status launch_bias_grad_f32(const ConvGeom& g, const float* dy, float* db, hipStream_t st) {
+  hipLaunchKernelGGL(bias_grad_f32_kernel, dim3((unsigned)g.M), dim3(kThreads), 0, st, g.n, (int)g.M, g.P, dy, db);
+  return check_launch("bias_grad_f32");
+}
+
+// out[c] = sum_r a[r][c]  (fully connected bias gradient): one thread per column, rows in order.
+__global__ __launch_bounds__(kThreads) void col_sum_f32_kernel(int rows, int cols, const float* __restrict__ a,
+                                                               float* __restrict__ out) {
+  const int c = blockIdx.x * kThreads + threadIdx.x;
+  if (c >= cols) return;
+  float acc = 0.f;
+  for (int r = 0; r < rows; ++r) acc += a[(int64_t)r * cols + c];
+  out[c] = acc;
+}
+
+vcnn_status launch_col_sum_f32(int rows, int cols, const float* a, float* out, hipStream_t st) {
+  hipLaunchKernelGGL(col_sum_f32_kernel, dim3((unsigned)ceil_div(cols, kThreads)), dim3(kThreads), 0, st, rows, cols,
+                     a, out);
+  return check_launch("col_sum_f32");
+}
+
+// ---- costs --------------------------------------------------------------------------------------
+// Single block: thread t handles rows t, t+256, ...; the per-row losses are combined with the fixed
+// tree of block_sum.
+__global__ __launch_bounds__(kThreads) void softmax_loss_f32_kernel(int batch, int classes, const float* __restrict__ z,
+                                                                    const int32_t* __restrict__ labels,
+                                                                    float* __restrict__ loss, float* __restrict__ dz) {
+  __shared__ float sm[kThreads];
+  float acc = 0.f;
+  const float inv_b = 1.f / (float)batch;
+  for (int b = threadIdx.x; b < batch; b += kThreads) {
+    const float* zb = z + (int64_t)b * classes;
+    float m = zb[0];
+    for (int j = 1; j < classes; ++j) m = fmaxf(m, zb[j]);
+    float se = 0.f;
+    for (int j = 0; j < classes; ++j) se += expf(zb[j] - m);
+    const float lse = m + logf(se);
+    const int lab = labels[b];
+    acc += lse - zb[lab];
+    if (dz)
+      for (int j = 0; j < classes; ++j)
+        dz[(int64_t)b * classes + j] = (expf(zb[j] - lse) - (j == lab ? 1.f : 0.f)) * inv_b;
+  }
+  const float total = block_sum(acc, sm);
+  if (threadIdx.x == 0 && loss) *loss = total * inv_b;
+}
+
+vcnn_status launch_softmax_loss_f32(int batch, int classes, const float* z, const int32_t* labels, float* loss,
+                                    float* dz, hipStream_t st) {
+  hipLaunchKernelGGL(softmax_loss_f32_kernel, dim3(1), dim3(kThreads), 0, st, batch, classes, z, labels, loss, dz);
+  return check_launch("softmax_loss_f32");
+}
+
+__global__ __launch_bounds__(kThreads) void l2_grad_f32_kernel(size_t count, float inv_b, const float* __restrict__ y,
+                                                               const float* __restrict__ t, float* __restrict__ dy) {
+  const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i < count) dy[i] = (y[i] - t[i]) * inv_b;
+}
+
+static constexpr int kL2Threads = 1024;
+__global__ __launch_bounds__(kL2Threads) void l2_loss_f32_kernel(size_t count, float scale, const float* __restrict__ y,
+                                                                 const float* __restrict__ t, float* __restrict__ loss) {
+  __shared__ float sm[kL2Threads];
+  float acc = 0.f;
+  for (size_t i = threadIdx.x; i < count; i += kL2Threads) {
+    const float dlt = y[i] - t[i];
+    acc += dlt * dlt;
+  }
+  sm[threadIdx.x] = acc;
+  __syncthreads();
+  for (int s = kL2Threads / 2; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) sm[threadIdx.x] += sm[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *loss = sm[0] * scale;
+}
+
+vcnn_status launch_l2_loss_f32(size_t count, int batch, const float* y, const float* t, float* loss, float* dy,
+                               hipStream_t st) {
+  if (dy) {
+    unsigned blocks;
+    if (vcnn_status s = grid_for(count, &blocks)) return s;
+    hipLaunchKernelGGL(l2_grad_f32_kernel, dim3(blocks), dim3(kThreads), 0, st, count, 1.f / (float)batch, y, t, dy);
+    if (vcnn_status s = check_launch("l2_grad_f32")) return s;
+  }
+  if (loss) {
+    hipLaunchKernelGGL(l2_loss_f32_kernel, dim3(1), dim3(kL2Threads), 0, st, count, 0.5f / (float)batch, y, t, loss);
+    return check_launch("l2_loss_f32");
+  }
+  return VCNN_OK;
+}
+
+// ---- SGD ----------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void sgd_f32_kernel(size_t count, float lr, float* __restrict__ w,
+                                                           const float* __restrict__ dw) {
+  const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i < count) w[i] = w[i] - lr * dw[i];
+}
+
+vcnn_status launch_sgd_f32(size_t count, float lr, float* w, const float* dw, hipStream_t st) {
+  unsigned blocks;
+  if (vcnn_status s = grid_for(count, &blocks)) return s;
+  hipLaunchKernelGGL(sgd_f32_kernel, dim3(blocks), dim3(kThreads), 0, st, count, lr, w, dw);
+  return check_launch("sgd_f32");
+}
+
+// ---- bfloat16 conversion --------------------------------------------------------------------------
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // quiet NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+__global__ __launch_bounds__(kThreads) void f32_to_bf16_kernel(size_t count, const float* __restrict__ src,
+                                                               uint16_t* __restrict__ dst) {
+  const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i < count) dst[i] = f32_to_bf16_rne(src[i]);
+}
+
+__global__ __launch_bounds__(kThreads) void bf16_to_f32_kernel(size_t count, const uint16_t* __restrict__ src,
+                                                               float* __restrict__ dst) {
+  const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i < count) dst[i] = __uint_as_float((uint32_t)src[i] << 16);
+}
+
+vcnn_status launch_f32_to_bf16(size_t count, const float* src, uint16_t* dst, hipStream_t st) {
+  unsigned blocks;
+  if (vcnn_status s = grid_for(count, &blocks)) return s;
+  hipLaunchKernelGGL(f32_to_bf16_kernel, dim3(blocks), dim3(kThreads), 0, st, count, src, dst);
+  return check_launch("f32_to_bf16");
+}
+
+vcnn_status launch_bf16_to_f32(size_t count, const uint16_t* src, float* dst, hipStream_t st) {
+  unsigned blocks;
+  if (vcnn_status s = grid_for(count, &blocks)) return s;
+  hipLaunchKernelGGL(bf16_to_f32_kernel, dim3(blocks), dim3(kThreads), 0, st, count, src, dst);
+  return check_launch("bf16_to_f32");
+}
+
+}  // namespace vcnn

@@ -1,0 +1,120 @@
+"""Sequences the C-ABI layer calls into one training step of a layer chain (forward, cost, backward,
+SGD) on one GPU.  This module only owns buffers (torch device tensors) and call order; every
+arithmetic step runs inside libvcnn's kernels.
+"""
+from __future__ import annotations
+
+from typing import List, Optional
+
+import numpy as np
+import torch
+
+from . import vcnn
+from .workloads import FC, Conv, Net, Pool
+
+
+class TrainStep:
+    """Device-resident state of one network: parameters, activations, gradients, workspace."""
+
+    def __init__(self, net: Net, params: list, inputs: dict, device: str = "cuda:0", first_layer_dx: bool = False,
+                 dtype: int = vcnn.F32):
+        if dtype != vcnn.F32:
+            raise NotImplementedError("only the fp32 chain is wired up")
+        self.net, self.dev, self.dtype = net, torch.device(device), dtype
+        self.first_layer_dx = first_layer_dx
+        f32 = dict(dtype=torch.float32, device=self.dev)
+        self.x = torch.from_numpy(np.ascontiguousarray(inputs["x"])).to(self.dev)
+        self.labels = torch.from_numpy(inputs["labels"]).to(self.dev) if "labels" in inputs else None
+        self.target = torch.from_numpy(inputs["target"]).to(self.dev) if "target" in inputs else None
+        self.upstream = torch.from_numpy(inputs["upstream"]).to(self.dev) if "upstream" in inputs else None
+        self.params: List[Optional[tuple]] = [
+            None if p is None else (torch.from_numpy(p[0]).to(self.dev), torch.from_numpy(p[1]).to(self.dev))
+            for p in params]
+        self.grads = [None if p is None else (torch.empty_like(p[0]), torch.empty_like(p[1])) for p in self.params]
+        self.acts = [self.x] + [torch.empty(s, **f32) for s in net.shapes]
+        self.dacts = [torch.empty_like(a) for a in self.acts]
+        self.argmax = {li: torch.empty(net.shapes[li], dtype=torch.int32, device=self.dev)
+                       for li, L in enumerate(net.layers) if isinstance(L, Pool)}
+        self.loss = torch.zeros((), **f32)
+        self.descs = {}
+        ws_bytes, dpre_elems = 0, 0
+        for li, L in enumerate(net.layers):
+            ishape = net.in_shape(li)
+            if isinstance(L, Conv):
+                d = vcnn.conv_desc(ishape[0], ishape[1], ishape[2], ishape[3], L.cout, L.kh, L.kw, L.pad_h, L.pad_w,
+                                   dtype=dtype, act=vcnn.ACT_RELU if L.relu else vcnn.ACT_NONE)
+                self.descs[li] = d
+                ws_bytes = max(ws_bytes, *(vcnn.conv_workspace_bytes(d, p) for p in
+                                           (vcnn.PASS_FWD, vcnn.PASS_BWD_FILTER, vcnn.PASS_BWD_DATA)))
+            elif isinstance(L, Pool):
+                self.descs[li] = vcnn.pool_desc(ishape[0], ishape[1], ishape[2], ishape[3], L.win, L.win, L.stride,
+                                                L.stride, dtype=dtype)
+            if getattr(L, "relu", False):
+                dpre_elems = max(dpre_elems, int(np.prod(net.shapes[li])))
+        self.workspace = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=self.dev)
+        self.dpre = torch.empty(max(dpre_elems, 1), **f32)
+
+    # ---- one pass each ---------------------------------------------------------------------------
+    def forward(self, stream=None):
+        net = self.net
+        for li, L in enumerate(net.layers):
+            a_in, a_out = self.acts[li], self.acts[li + 1]
+            if isinstance(L, Conv):
+                w, b = self.params[li]
+                vcnn.conv_fwd(self.descs[li], a_in, w, b, a_out, self.workspace, stream)
+            elif isinstance(L, Pool):
+                vcnn.pool_fwd(self.descs[li], a_in, a_out, self.argmax[li], stream)
+            else:
+                w, b = self.params[li]
+                bsz = a_in.shape[0]
+                vcnn.fc_fwd(self.dtype, bsz, a_in.numel() // bsz, L.out, vcnn.ACT_RELU if L.relu else vcnn.ACT_NONE,
+                            a_in, w, b, a_out, stream)
+
+    def cost(self, stream=None):
+        net, out, dout = self.net, self.acts[-1], self.dacts[-1]
+        if net.loss == "softmax":
+            vcnn.softmax_loss(out.shape[0], out.shape[1], out, self.labels, self.loss, dout, stream)
+        elif net.loss == "l2":
+            vcnn.l2_loss(self.dtype, out.numel(), out.shape[0], out, self.target, self.loss, dout, stream)
+        elif net.loss == "upstream":
+            dout.copy_(self.upstream)  # a device-to-device copy of the given gradient, no arithmetic
+        else:
+            raise ValueError(net.loss)
+
+    def backward(self, stream=None):
+        net = self.net
+        for li in range(len(net.layers) - 1, -1, -1):
+            L = net.layers[li]
+            a_in, a_out, d = self.acts[li], self.acts[li + 1], self.dacts[li + 1]
+            need_dx = li > 0 or self.first_layer_dx
+            if getattr(L, "relu", False):
+                dpre = self.dpre[:d.numel()]
+                vcnn.act_bwd(vcnn.ACT_RELU, self.dtype, d.numel(), a_out, d, dpre, stream)
+                d = dpre
+            if isinstance(L, Conv):
+                w, _ = self.params[li]
+                dw, db = self.grads[li]
+                vcnn.conv_bwd_filter(self.descs[li], a_in, d, dw, db, self.workspace, stream)
+                if need_dx:
+                    vcnn.conv_bwd_data(self.descs[li], w, d, self.dacts[li], self.workspace, stream)
+            elif isinstance(L, Pool):
+                if need_dx:
+                    vcnn.pool_bwd(self.descs[li], d, self.argmax[li], self.dacts[li], stream)
+            else:
+                w, _ = self.params[li]
+                dw, db = self.grads[li]
+                bsz = a_in.shape[0]
+                vcnn.fc_bwd(self.dtype, bsz, a_in.numel() // bsz, L.out, a_in, w, d, dw, db,
+                            self.dacts[li] if need_dx else None, stream)
+
+    def update(self, stream=None):
+        for p, g in zip(self.params, self.grads):
+            if p is not None:
+                vcnn.sgd_update(p[0].numel(), self.net.lr, p[0], g[0], stream)
+                vcnn.sgd_update(p[1].numel(), self.net.lr, p[1], g[1], stream)
+
+    def step(self, stream=None):
+        self.forward(stream)
+        self.cost(stream)
+        self.backward(stream)
+        self.update(stream)

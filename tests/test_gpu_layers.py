@@ -1,0 +1,256 @@
+"""Per-operator parity of the HIP path (through the C ABI) against the fp64 oracle, on seeded inputs
+whose sizes span several tiles and leave ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from paper_1501_07338_amd import vcnn
+from paper_1501_07338_amd.workloads import random_tensor
+from util import TOL_F32, assert_close, rel_err, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+# (n, c, h, w, k, r, s, ph, pw): ragged everything; M below / at / above one MFMA tile; K and N not
+# multiples of the tile sizes; odd N (scalar store path); 1x1; tall and wide kernels.
+CONV_SHAPES = [
+    (2, 1, 9, 9, 3, 2, 2, 0, 0),
+    (3, 5, 19, 23, 37, 3, 5, 1, 2),
+    (8, 1, 28, 28, 6, 5, 5, 0, 0),
+    (5, 3, 17, 15, 1, 5, 5, 2, 2),
+    (3, 7, 13, 11, 130, 3, 3, 1, 1),
+    (2, 20, 12, 12, 50, 5, 5, 0, 0),
+    (4, 33, 10, 10, 40, 1, 1, 0, 0),
+    (1, 2, 40, 9, 5, 21, 1, 0, 0),
+    (1, 3, 9, 40, 5, 1, 21, 0, 0),
+    (2, 4, 20, 20, 64, 9, 9, 4, 4),
+    (3, 2, 6, 7, 4, 1, 1, 1, 1),
+    (1, 1, 5, 5, 1, 5, 5, 0, 0),
+]
+
+
+def ws_for(d, which):
+    need = vcnn.conv_workspace_bytes(d, which)
+    return torch.empty(max(need, 256), dtype=torch.uint8, device=DEV)
+
+
+def conv_case(shape, seed):
+    n, c, h, w, k, r, s, ph, pw = shape
+    x = random_tensor(seed, (n, c, h, w))
+    wt = random_tensor(seed + 1, (k, c, r, s), scale=(2.0 / (c * r * s)) ** 0.5)
+    b = random_tensor(seed + 2, (k,), scale=0.1)
+    oh, ow = h + 2 * ph - r + 1, w + 2 * pw - s + 1
+    dy = random_tensor(seed + 3, (n, k, oh, ow))
+    return x, wt, b, dy
+
+
+@pytest.mark.parametrize("shape", CONV_SHAPES)
+def test_im2col_bit_exact(shape):
+    n, c, h, w, k, r, s, ph, pw = shape
+    x, *_ = conv_case(shape, 100)
+    d = vcnn.conv_desc(n, c, h, w, k, r, s, ph, pw)
+    oh, ow = vcnn.conv_out_shape(d)
+    col = torch.full((c * r * s, n * oh * ow), float("nan"), device=DEV)
+    vcnn.im2col(d, to_dev(x), col)
+    ref = O.im2col(x, (r, s), pad=(ph, pw)).astype(np.float32)
+    np.testing.assert_array_equal(to_np(col), ref)
+
+
+@pytest.mark.parametrize("shape", CONV_SHAPES)
+def test_col2im(shape):
+    n, c, h, w, k, r, s, ph, pw = shape
+    d = vcnn.conv_desc(n, c, h, w, k, r, s, ph, pw)
+    oh, ow = vcnn.conv_out_shape(d)
+    col = random_tensor(200, (c * r * s, n * oh * ow))
+    dx = torch.full((n, c, h, w), float("nan"), device=DEV)
+    vcnn.col2im(d, to_dev(col), dx)
+    assert_close(to_np(dx), O.col2im(col, (n, c, h, w), (r, s), pad=(ph, pw)), 1e-6, "col2im")
+
+
+def test_unroll_adjoint_identity_on_gpu():
+    """<im2col(x), y> = <x, col2im(y)> with both operators from the HIP path."""
+    n, c, h, w, r, s, ph, pw = 3, 4, 14, 13, 5, 3, 2, 1
+    d = vcnn.conv_desc(n, c, h, w, 1, r, s, ph, pw)
+    oh, ow = vcnn.conv_out_shape(d)
+    x = random_tensor(300, (n, c, h, w))
+    yy = random_tensor(301, (c * r * s, n * oh * ow))
+    col = torch.empty((c * r * s, n * oh * ow), device=DEV)
+    back = torch.empty((n, c, h, w), device=DEV)
+    vcnn.im2col(d, to_dev(x), col)
+    vcnn.col2im(d, to_dev(yy), back)
+    lhs = float(np.sum(to_np(col).astype(np.float64) * yy))
+    rhs = float(np.sum(x.astype(np.float64) * to_np(back)))
+    assert abs(lhs - rhs) <= 1e-5 * abs(lhs)
+
+
+@pytest.mark.parametrize("relu", [False, True])
+@pytest.mark.parametrize("shape", CONV_SHAPES)
+def test_conv_fwd(shape, relu):
+    n, c, h, w, k, r, s, ph, pw = shape
+    x, wt, b, _ = conv_case(shape, 400)
+    d = vcnn.conv_desc(n, c, h, w, k, r, s, ph, pw, act=vcnn.ACT_RELU if relu else vcnn.ACT_NONE)
+    oh, ow = vcnn.conv_out_shape(d)
+    y = torch.full((n, k, oh, ow), float("nan"), device=DEV)
+    vcnn.conv_fwd(d, to_dev(x), to_dev(wt), to_dev(b), y, ws_for(d, vcnn.PASS_FWD))
+    assert_close(to_np(y), O.conv_fwd(x, wt, b, pad=(ph, pw), relu=relu), TOL_F32, "conv_fwd")
+    if not relu:  # bias is optional
+        vcnn.conv_fwd(d, to_dev(x), to_dev(wt), None, y, ws_for(d, vcnn.PASS_FWD))
+        assert_close(to_np(y), O.conv_fwd(x, wt, None, pad=(ph, pw)), TOL_F32, "conv_fwd without bias")
+
+
+@pytest.mark.parametrize("shape", CONV_SHAPES)
+def test_conv_bwd_filter(shape):
+    n, c, h, w, k, r, s, ph, pw = shape
+    x, _, _, dy = conv_case(shape, 500)
+    d = vcnn.conv_desc(n, c, h, w, k, r, s, ph, pw)
+    dw = torch.full((k, c, r, s), float("nan"), device=DEV)
+    db = torch.full((k,), float("nan"), device=DEV)
+    ws = ws_for(d, vcnn.PASS_BWD_FILTER)
+    vcnn.conv_bwd_filter(d, to_dev(x), to_dev(dy), dw, db, ws)
+    rdw, rdb = O.conv_bwd_filter(x, dy, (r, s), pad=(ph, pw))
+    assert_close(to_np(dw), rdw, TOL_F32, "dw")
+    assert_close(to_np(db), rdb, TOL_F32, "db")
+    # run-to-run bit identity (no floating-point atomics, fixed reduction order)
+    first = to_np(dw).copy()
+    dw.fill_(float("nan"))
+    vcnn.conv_bwd_filter(d, to_dev(x), to_dev(dy), dw, None, ws)
+    np.testing.assert_array_equal(to_np(dw), first)
+
+
+@pytest.mark.parametrize("shape", CONV_SHAPES)
+def test_conv_bwd_data(shape):
+    n, c, h, w, k, r, s, ph, pw = shape
+    _, wt, _, dy = conv_case(shape, 600)
+    d = vcnn.conv_desc(n, c, h, w, k, r, s, ph, pw)
+    dx = torch.full((n, c, h, w), float("nan"), device=DEV)
+    vcnn.conv_bwd_data(d, to_dev(wt), to_dev(dy), dx, ws_for(d, vcnn.PASS_BWD_DATA))
+    assert_close(to_np(dx), O.conv_bwd_data(wt, dy, (h, w), pad=(ph, pw)), TOL_F32, "dx")
+
+
+def test_bwd_filter_split_contraction_many_columns():
+    """Long contraction (N = 8*61*67 columns) so the filter gradient is split into several partial sums."""
+    shape = (8, 3, 63, 69, 10, 3, 3, 0, 0)
+    n, c, h, w, k, r, s, ph, pw = shape
+    x, _, _, dy = conv_case(shape, 700)
+    d = vcnn.conv_desc(n, c, h, w, k, r, s, ph, pw)
+    dw = torch.empty((k, c, r, s), device=DEV)
+    db = torch.empty((k,), device=DEV)
+    vcnn.conv_bwd_filter(d, to_dev(x), to_dev(dy), dw, db, ws_for(d, vcnn.PASS_BWD_FILTER))
+    rdw, rdb = O.conv_bwd_filter(x, dy, (r, s))
+    assert_close(to_np(dw), rdw, TOL_F32, "dw")
+    assert_close(to_np(db), rdb, TOL_F32, "db")
+
+
+POOL_SHAPES = [(2, 3, 4, 4, 2, 2), (3, 5, 24, 24, 2, 2), (2, 7, 32, 32, 3, 2), (3, 4, 15, 15, 3, 2), (2, 2, 7, 7, 3, 2),
+               (1, 3, 9, 11, 2, 1), (2, 2, 5, 6, 5, 1), (1, 1, 3, 3, 3, 3)]
+
+
+@pytest.mark.parametrize("ties", [False, True])
+@pytest.mark.parametrize("shape", POOL_SHAPES)
+def test_pool_fwd_bwd(shape, ties):
+    n, c, h, w, win, st = shape
+    x = random_tensor(800, (n, c, h, w))
+    if ties:  # few distinct values (as after a ReLU): equal maxima must resolve to the lowest index
+        x = np.maximum(np.round(x * 2) / 2, 0).astype(np.float32)
+    d = vcnn.pool_desc(n, c, h, w, win, win, st, st)
+    oh, ow = vcnn.pool_out_shape(d)
+    y = torch.full((n, c, oh, ow), float("nan"), device=DEV)
+    am = torch.full((n, c, oh, ow), -7, dtype=torch.int32, device=DEV)
+    vcnn.pool_fwd(d, to_dev(x), y, am)
+    ry, ram = O.maxpool_fwd(x, (win, win), (st, st))
+    np.testing.assert_array_equal(to_np(am), ram)
+    np.testing.assert_array_equal(to_np(y), ry.astype(np.float32))
+    dy = random_tensor(801, (n, c, oh, ow))
+    dx = torch.full((n, c, h, w), float("nan"), device=DEV)
+    vcnn.pool_bwd(d, to_dev(dy), am, dx)
+    assert_close(to_np(dx), O.maxpool_bwd(dy, ram, (h, w)), 1e-6, "pool dx")
+
+
+@pytest.mark.parametrize("count", [1, 3, 4, 1023, 4099])
+def test_act(count):
+    x = random_tensor(900, (count,))
+    x[::5] = 0.0
+    dy = random_tensor(901, (count,))
+    y = torch.full((count,), float("nan"), device=DEV)
+    vcnn.act_fwd(vcnn.ACT_RELU, vcnn.F32, count, to_dev(x), y)
+    np.testing.assert_array_equal(to_np(y), O.relu_fwd(x).astype(np.float32))
+    dx = torch.full((count,), float("nan"), device=DEV)
+    vcnn.act_bwd(vcnn.ACT_RELU, vcnn.F32, count, to_dev(x), to_dev(dy), dx)
+    np.testing.assert_array_equal(to_np(dx), O.relu_bwd(x, dy).astype(np.float32))
+    # in place, with the forward output as reference
+    g = to_dev(dy)
+    vcnn.act_bwd(vcnn.ACT_RELU, vcnn.F32, count, y, g, g)
+    np.testing.assert_array_equal(to_np(g), O.relu_bwd(x, dy).astype(np.float32))
+    xin = to_dev(x)
+    vcnn.act_fwd(vcnn.ACT_RELU, vcnn.F32, count, xin, xin)
+    np.testing.assert_array_equal(to_np(xin), O.relu_fwd(x).astype(np.float32))
+
+
+@pytest.mark.parametrize("b,i,o", [(128, 800, 500), (128, 500, 10), (7, 33, 5), (1, 1, 1), (130, 70, 131), (128, 576, 64)])
+@pytest.mark.parametrize("relu", [False, True])
+def test_fc(b, i, o, relu):
+    x, w, bias = random_tensor(1000, (b, i)), random_tensor(1001, (o, i), scale=(2.0 / i) ** 0.5), random_tensor(1002, (o,))
+    dy = random_tensor(1003, (b, o))
+    y = torch.full((b, o), float("nan"), device=DEV)
+    vcnn.fc_fwd(vcnn.F32, b, i, o, vcnn.ACT_RELU if relu else vcnn.ACT_NONE, to_dev(x), to_dev(w), to_dev(bias), y)
+    assert_close(to_np(y), O.fc_fwd(x, w, bias, relu=relu), TOL_F32, "fc y")
+    dw = torch.full((o, i), float("nan"), device=DEV)
+    db = torch.full((o,), float("nan"), device=DEV)
+    dx = torch.full((b, i), float("nan"), device=DEV)
+    vcnn.fc_bwd(vcnn.F32, b, i, o, to_dev(x), to_dev(w), to_dev(dy), dw, db, dx)
+    rdw, rdb, rdx = O.fc_bwd(x, w, dy)
+    assert_close(to_np(dw), rdw, TOL_F32, "fc dw")
+    assert_close(to_np(db), rdb, TOL_F32, "fc db")
+    assert_close(to_np(dx), rdx, TOL_F32, "fc dx")
+
+
+@pytest.mark.parametrize("b,c", [(128, 10), (1, 10), (300, 7), (5, 1)])
+def test_softmax_loss(b, c):
+    z = random_tensor(1100, (b, c), scale=3.0)
+    labels = (np.arange(b) * 7 % c).astype(np.int32)
+    loss = torch.full((), float("nan"), device=DEV)
+    dz = torch.full((b, c), float("nan"), device=DEV)
+    vcnn.softmax_loss(b, c, to_dev(z), to_dev(labels), loss, dz)
+    rl, rdz = O.softmax_loss(z, labels)
+    assert abs(float(to_np(loss)) - rl) <= TOL_F32 * max(abs(rl), 1e-3)
+    if c > 1:
+        assert_close(to_np(dz), rdz, TOL_F32, "dlogits")
+    else:
+        assert np.max(np.abs(to_np(dz))) < 1e-7
+
+
+def test_softmax_loss_uniform_logits_is_log_classes():
+    z = np.full((64, 10), 1.5, dtype=np.float32)
+    loss = torch.empty((), device=DEV)
+    vcnn.softmax_loss(64, 10, to_dev(z), to_dev(np.zeros(64, dtype=np.int32)), loss, None)
+    assert abs(float(to_np(loss)) - np.log(10.0)) < 1e-6
+
+
+@pytest.mark.parametrize("shape", [(4, 1, 5, 7), (64, 1, 64, 64), (16, 1, 42, 42)])
+def test_l2_loss_and_sgd(shape):
+    y, t = random_tensor(1200, shape), random_tensor(1201, shape)
+    loss = torch.full((), float("nan"), device=DEV)
+    dy = torch.full(shape, float("nan"), device=DEV)
+    vcnn.l2_loss(vcnn.F32, y.size, shape[0], to_dev(y), to_dev(t), loss, dy)
+    rl, rdy = O.l2_loss(y, t)
+    assert abs(float(to_np(loss)) - rl) <= TOL_F32 * abs(rl)
+    assert_close(to_np(dy), rdy, 1e-6, "l2 dy")
+    w = to_dev(y)
+    vcnn.sgd_update(y.size, 0.01, w, to_dev(t))
+    assert_close(to_np(w), O.sgd_update(y, t, 0.01), 1e-6, "sgd")
+
+
+def test_gpu_launch_of_bad_arguments_is_rejected_cleanly():
+    d = vcnn.conv_desc(2, 3, 8, 8, 4, 3, 3)
+    x = torch.zeros((2, 3, 8, 8), device=DEV)
+    w = torch.zeros((4, 3, 3, 3), device=DEV)
+    y = torch.zeros((2, 4, 6, 6), device=DEV)
+    if vcnn.conv_workspace_bytes(d, vcnn.PASS_FWD):
+        with pytest.raises(vcnn.VcnnError) as e:
+            vcnn.conv_fwd(d, x, w, None, y, None)
+        assert e.value.status == vcnn.ERR_WORKSPACE
+    with pytest.raises(vcnn.VcnnError) as e:
+        vcnn.conv_fwd(vcnn.conv_desc(2, 3, 8, 8, 4, 3, 3, dtype=5), x, w, None, y, None)
+    assert e.value.status == vcnn.ERR_UNSUPPORTED
