@@ -75,18 +75,57 @@ static bool is_pointwise(const ConvGeom& g) { return g.r == 1 && g.s == 1 && g.p
 
 static size_t col_bytes(const ConvGeom& g) { return align256((size_t)g.K * g.N * sizeof(float)); }
 
-static size_t workspace_need(const ConvGeom& g, int pass) {
-  switch (pass) {
-    case VCNN_PASS_FWD:
-      return is_pointwise(g) ? 0 : col_bytes(g);
-    case VCNN_PASS_BWD_FILTER:
-      return col_bytes(g) + align256(bwd_filter_partial_bytes(g));
-    case VCNN_PASS_BWD_DATA:
-      return is_pointwise(g) ? 0 : col_bytes(g);
-    default:
-      return 0;
+// Which realisation a pass uses for a given shape.  The same decision drives the workspace query and
+// the launch, so the two always agree.
+enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER };
+struct Plan {
+  Path path;
+  DirectGeom dg;
+  int split;        // channel slices (few-out), output-map group size (few-in) or batch slices (filter gradient)
+  size_t partial_bytes;
+  size_t workspace_bytes;
+};
+
+static Plan make_plan(const ConvGeom& g, int pass) {
+  Plan p{};
+  p.path = PATH_EXPLICIT;
+  const bool allow_direct = g_conv_algo.load() != VCNN_ALGO_EXPLICIT;
+  if (pass == VCNN_PASS_FWD) {
+    if (allow_direct && g.k <= 4 && direct_fwd_geom(g, &p.dg) && direct_few_out_plan(&p.dg, &p.split, &p.partial_bytes)) {
+      p.path = PATH_FEW_OUT;
+      p.workspace_bytes = align256(p.partial_bytes);
+    } else if (is_pointwise(g)) {
+      p.path = PATH_POINTWISE;
+    } else if (allow_direct && g.c <= 4 && direct_fwd_geom(g, &p.dg) && direct_few_in_plan(&p.dg, &p.split)) {
+      p.path = PATH_FEW_IN;
+    } else {
+      p.workspace_bytes = col_bytes(g);
+    }
+  } else if (pass == VCNN_PASS_BWD_DATA) {
+    // the input gradient is a correlation of dy (k channels) with the flipped kernels into c maps
+    if (allow_direct && g.c <= 4 && direct_bwd_data_geom(g, &p.dg) &&
+        direct_few_out_plan(&p.dg, &p.split, &p.partial_bytes)) {
+      p.path = PATH_FEW_OUT;
+      p.workspace_bytes = align256(p.partial_bytes);
+    } else if (is_pointwise(g)) {
+      p.path = PATH_POINTWISE;
+    } else if (allow_direct && g.k <= 4 && direct_bwd_data_geom(g, &p.dg) && direct_few_in_plan(&p.dg, &p.split)) {
+      p.path = PATH_FEW_IN;
+    } else {
+      p.workspace_bytes = col_bytes(g);
+    }
+  } else {
+    if (allow_direct && direct_filter_grad_plan(g, &p.dg, &p.split, &p.partial_bytes)) {
+      p.path = PATH_DIRECT_FILTER;
+      p.workspace_bytes = align256(p.partial_bytes);
+    } else {
+      p.workspace_bytes = col_bytes(g) + align256(bwd_filter_partial_bytes(g));
+    }
   }
+  return p;
 }
+
+static size_t workspace_need(const ConvGeom& g, int pass) { return make_plan(g, pass).workspace_bytes; }
 
 }  // namespace vcnn
 
@@ -155,8 +194,15 @@ vcnn_status vcnn_conv_fwd(const vcnn_conv_desc* d, const void* x, const void* w,
   if (vcnn_status s = make_geom(d, &g)) return s;
   if (!x || !w || !y) return fail(VCNN_ERR_NULL, "conv_fwd: NULL tensor");
   if (vcnn_status s = need_f32(d->dtype, "conv_fwd")) return s;
-  if (vcnn_status s = check_ws(workspace, workspace_bytes, workspace_need(g, VCNN_PASS_FWD), "conv_fwd")) return s;
+  const Plan plan = make_plan(g, VCNN_PASS_FWD);
+  if (vcnn_status s = check_ws(workspace, workspace_bytes, plan.workspace_bytes, "conv_fwd")) return s;
   hipStream_t st = (hipStream_t)stream;
+  const int relu = d->act == VCNN_ACT_RELU;
+  if (plan.path == PATH_FEW_OUT)
+    return launch_direct_few_out(plan.dg, plan.split, (const float*)x, (const float*)w, bias, (float*)y,
+                                 (float*)workspace, relu, st);
+  if (plan.path == PATH_FEW_IN)
+    return launch_direct_few_in(plan.dg, plan.split, (const float*)x, (const float*)w, bias, (float*)y, relu, st);
 
   GemmArgs a{};
   a.A = (const float*)w, a.C = (float*)y, a.bias = bias;
@@ -164,7 +210,7 @@ vcnn_status vcnn_conv_fwd(const vcnn_conv_desc* d, const void* x, const void* w,
   a.a_si = g.K, a.a_sk = 1;
   a.c_si = g.P, a.c_sj = 1, a.c_P = (int)g.P, a.c_simg = g.M * g.P;
   a.relu = d->act == VCNN_ACT_RELU;
-  if (is_pointwise(g)) {
+  if (plan.path == PATH_POINTWISE) {
     // patch matrix == input: B(k, j) = x[n][k][p]
     a.B = (const float*)x;
     a.b_sk = g.P, a.b_sj = 1, a.b_P = (int)g.P, a.b_simg = g.K * g.P;
@@ -183,9 +229,16 @@ vcnn_status vcnn_conv_bwd_filter(const vcnn_conv_desc* d, const void* x, const v
   if (vcnn_status s = make_geom(d, &g)) return s;
   if (!x || !dy || !dw) return fail(VCNN_ERR_NULL, "conv_bwd_filter: NULL tensor");
   if (vcnn_status s = need_f32(d->dtype, "conv_bwd_filter")) return s;
-  if (vcnn_status s = check_ws(workspace, workspace_bytes, workspace_need(g, VCNN_PASS_BWD_FILTER), "conv_bwd_filter"))
-    return s;
+  const Plan plan = make_plan(g, VCNN_PASS_BWD_FILTER);
+  if (vcnn_status s = check_ws(workspace, workspace_bytes, plan.workspace_bytes, "conv_bwd_filter")) return s;
   hipStream_t st = (hipStream_t)stream;
+  if (plan.path == PATH_DIRECT_FILTER) {
+    if (vcnn_status s = launch_direct_filter_grad(plan.dg, plan.split, (const float*)x, (const float*)dy, dw,
+                                                  (float*)workspace, st))
+      return s;
+    if (dbias) return launch_bias_grad_f32(g, (const float*)dy, dbias, st);
+    return VCNN_OK;
+  }
   float* col = (float*)workspace;
   float* partial = (float*)((char*)workspace + col_bytes(g));
   if (vcnn_status s = launch_im2col_f32(g, (const float*)x, col, st)) return s;
@@ -200,9 +253,14 @@ vcnn_status vcnn_conv_bwd_data(const vcnn_conv_desc* d, const void* w, const voi
   if (vcnn_status s = make_geom(d, &g)) return s;
   if (!w || !dy || !dx) return fail(VCNN_ERR_NULL, "conv_bwd_data: NULL tensor");
   if (vcnn_status s = need_f32(d->dtype, "conv_bwd_data")) return s;
-  if (vcnn_status s = check_ws(workspace, workspace_bytes, workspace_need(g, VCNN_PASS_BWD_DATA), "conv_bwd_data"))
-    return s;
+  const Plan plan = make_plan(g, VCNN_PASS_BWD_DATA);
+  if (vcnn_status s = check_ws(workspace, workspace_bytes, plan.workspace_bytes, "conv_bwd_data")) return s;
   hipStream_t st = (hipStream_t)stream;
+  if (plan.path == PATH_FEW_OUT)
+    return launch_direct_few_out(plan.dg, plan.split, (const float*)dy, (const float*)w, nullptr, (float*)dx,
+                                 (float*)workspace, 0, st);
+  if (plan.path == PATH_FEW_IN)
+    return launch_direct_few_in(plan.dg, plan.split, (const float*)dy, (const float*)w, nullptr, (float*)dx, 0, st);
   float* dcol = (float*)workspace;
   // dcol[k][j] = sum_m W[m][k] * dY(m, j)
   GemmArgs a{};
@@ -211,7 +269,7 @@ vcnn_status vcnn_conv_bwd_data(const vcnn_conv_desc* d, const void* w, const voi
   a.a_si = 1, a.a_sk = g.K;
   a.b_sk = g.P, a.b_sj = 1, a.b_P = (int)g.P, a.b_simg = g.M * g.P;
   a.relu = 0;
-  if (is_pointwise(g)) {
+  if (plan.path == PATH_POINTWISE) {
     // phi_c^{-1} is the identity per sample: store the product straight into dx[n][c][p].
     a.C = (float*)dx;
     a.c_si = g.P, a.c_sj = 1, a.c_P = (int)g.P, a.c_simg = g.K * g.P;

@@ -56,6 +56,27 @@ size_t bwd_filter_partial_bytes(const ConvGeom& g);
 vcnn_status launch_bwd_filter_gemm_f32(const ConvGeom& g, const float* dy, const float* col, float* dw,
                                        float* partial, hipStream_t st);
 
+// ---- direct.hip ---------------------------------------------------------------------------------
+// Generic correlation out[n][o][y][x] = sum_{i,r,s} wgt(o,i,r,s) * in[n][i][y+r-py][x+s-px] used by the
+// direct kernels; wgt(o,i,r,s) = w[o*w_so + i*w_si + tap], tap = r*S+s or, flipped, (R-1-r)*S+(S-1-s).
+struct DirectGeom {
+  int n, ci, ih, iw, co, oh, ow, r, s, py, px;
+  int64_t w_so, w_si;
+  int flip;
+  int bh, bands, twp, groups;  // band height, number of bands, LDS row pitch, 4-pixel groups per row
+};
+bool direct_fwd_geom(const ConvGeom& c, DirectGeom* g);
+bool direct_bwd_data_geom(const ConvGeom& c, DirectGeom* g);
+bool direct_few_out_plan(DirectGeom* g, int* isplit, size_t* partial_bytes);
+bool direct_few_in_plan(DirectGeom* g, int* ogroup);
+bool direct_filter_grad_plan(const ConvGeom& c, DirectGeom* g, int* slices, size_t* partial_bytes);
+vcnn_status launch_direct_few_out(const DirectGeom& g, int isplit, const float* in, const float* w, const float* bias,
+                                  float* out, float* partial, int relu, hipStream_t st);
+vcnn_status launch_direct_few_in(const DirectGeom& g, int ogroup, const float* in, const float* w, const float* bias,
+                                 float* out, int relu, hipStream_t st);
+vcnn_status launch_direct_filter_grad(const DirectGeom& g, int slices, const float* x, const float* dy, float* dw,
+                                      float* partial, hipStream_t st);
+
 // ---- pointwise.hip ------------------------------------------------------------------------------
 vcnn_status launch_bias_grad_f32(const ConvGeom& g, const float* dy, float* db, hipStream_t st);
 vcnn_status launch_relu_fwd_f32(size_t count, const float* x, float* y, hipStream_t st);

@@ -1,0 +1,427 @@
+// Direct (non-matrix-core) kernels for layers whose kernel matrix is degenerate: one to four output
+// maps, or one to four input channels.  With M = 1 the product of Eq. 2 is a matrix-vector product
+// and the patch matrix would be written and read once per use, so these layers are bound by memory,
+// not by the matrix cores; here each block stages an input band (with its halo) in LDS once and
+// every loaded value feeds up to 4 x (taps) multiply-adds from registers.
+//
+// All three kernels are written for the generic correlation
+//     out[n][o][y][x] = sum_i sum_r sum_s wgt(o,i,r,s) * in[n][i][y + r - py][x + s - px]   (zero outside)
+// so that the forward pass and the input gradient (a correlation of dy with the flipped kernels,
+// i.e. phi_c^{-1} applied to the transposed product, evaluated in gather form) share them.
+#include "common.h"
+
+namespace vcnn {
+
+static constexpr int kThreads = 256;
+static constexpr int kPx = 4;                 // consecutive output pixels per thread
+static constexpr size_t kMaxLds = 64 * 1024;  // static launch limit without opting in to more
+
+__device__ __forceinline__ int tap_index(const DirectGeom& g, int r, int s) {
+  return g.flip ? (g.r - 1 - r) * g.s + (g.s - 1 - s) : r * g.s + s;
+}
+
+// Stages rows [y0 - py, y0 - py + rows) of one input plane into LDS, columns shifted by px, zero filled.
+__device__ __forceinline__ void stage_plane(const DirectGeom& g, const float* __restrict__ plane, int y0, int rows,
+                                            float* tile) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int ry = wave; ry < rows; ry += kThreads / 64) {
+    const int iy = y0 + ry - g.py;
+    const bool row_ok = iy >= 0 && iy < g.ih;
+    for (int rx = lane; rx < g.twp; rx += 64) {
+      const int ix = rx - g.px;
+      float v = 0.f;
+      if (row_ok && ix >= 0 && ix < g.iw) v = plane[(int64_t)iy * g.iw + ix];
+      tile[ry * g.twp + rx] = v;
+    }
+  }
+}
+
+// acc[o][j] += sum_s w_o[s] * row[j + s] for one tile row, sliding a register window along s.
+template <int CO>
+__device__ __forceinline__ void row_taps(const DirectGeom& g, const float* row, const float* const (&wrow)[CO],
+                                         float (&acc)[CO][kPx]) {
+  float x0 = row[0], x1 = row[1], x2 = row[2];
+  const int S = g.s;
+  const int dir = g.flip ? -1 : 1;  // flipped kernels are walked backwards
+  int s = 0;
+#define VCNN_TAP(XA, XB, XC, XD, SS)                 \
+  _Pragma("unroll") for (int o = 0; o < CO; ++o) {   \
+    const float wv = wrow[o][dir * (SS)];            \
+    acc[o][0] = fmaf(wv, XA, acc[o][0]);             \
+    acc[o][1] = fmaf(wv, XB, acc[o][1]);             \
+    acc[o][2] = fmaf(wv, XC, acc[o][2]);             \
+    acc[o][3] = fmaf(wv, XD, acc[o][3]);             \
+  }
+  for (; s + 4 <= S; s += 4) {
+    const float x3 = row[s + 3], x4 = row[s + 4], x5 = row[s + 5], x6 = row[s + 6];
+    VCNN_TAP(x0, x1, x2, x3, s)
+    VCNN_TAP(x1, x2, x3, x4, s + 1)
+    VCNN_TAP(x2, x3, x4, x5, s + 2)
+    VCNN_TAP(x3, x4, x5, x6, s + 3)
+    x0 = x4, x1 = x5, x2 = x6;
+  }
+  for (; s < S; ++s) {
+    const float x3 = row[s + 3];
+    VCNN_TAP(x0, x1, x2, x3, s)
+    x0 = x1, x1 = x2, x2 = x3;
+  }
+#undef VCNN_TAP
+}
+
+// ---- few output maps (CO <= 4), any number of input channels -----------------------------------------
+// Block = (sample, band of output rows, slice of the input channels).  Partial sums over channel
+// slices go to `out` as [slice][n][co][oh][ow] when isplit > 1 and are combined by finish_partials.
+template <int CO>
+__global__ __launch_bounds__(kThreads) void direct_few_out_kernel(DirectGeom g, const float* __restrict__ in,
+                                                                  const float* __restrict__ w,
+                                                                  const float* __restrict__ bias,
+                                                                  float* __restrict__ out, int isplit, int relu) {
+  extern __shared__ float tile[];
+  int b = blockIdx.x;
+  const int is = b % isplit;
+  b /= isplit;
+  const int band = b % g.bands;
+  const int n = b / g.bands;
+  const int y0 = band * g.bh;
+  const int bh_eff = min(g.bh, g.oh - y0);
+  const int rows = bh_eff + g.r - 1;
+  const int per = (g.ci + isplit - 1) / isplit;
+  const int i0 = is * per, i1 = min(g.ci, i0 + per);
+  const int ty = threadIdx.x / g.groups, gx = threadIdx.x - ty * g.groups;
+  const bool active = ty < bh_eff;
+
+  float acc[CO][kPx];
+#pragma unroll
+  for (int o = 0; o < CO; ++o)
+#pragma unroll
+    for (int j = 0; j < kPx; ++j) acc[o][j] = 0.f;
+
+  for (int i = i0; i < i1; ++i) {
+    __syncthreads();
+    stage_plane(g, in + ((int64_t)n * g.ci + i) * g.ih * g.iw, y0, rows, tile);
+    __syncthreads();
+    if (active) {
+      for (int r = 0; r < g.r; ++r) {
+        const float* wrow[CO];
+#pragma unroll
+        for (int o = 0; o < CO; ++o) wrow[o] = w + (int64_t)o * g.w_so + (int64_t)i * g.w_si + tap_index(g, r, 0);
+        row_taps<CO>(g, tile + (ty + r) * g.twp + gx * kPx, wrow, acc);
+      }
+    }
+  }
+  if (!active) return;
+  const int y = y0 + ty;
+#pragma unroll
+  for (int o = 0; o < CO; ++o) {
+    float* dst = out + ((((int64_t)is * g.n + n) * g.co + o) * g.oh + y) * g.ow;
+#pragma unroll
+    for (int j = 0; j < kPx; ++j) {
+      const int x = gx * kPx + j;
+      if (x < g.ow) {
+        float v = acc[o][j];
+        if (isplit == 1) {
+          if (bias) v += bias[o];
+          if (relu) v = fmaxf(v, 0.f);
+        }
+        dst[x] = v;
+      }
+    }
+  }
+}
+
+// out[idx] = act(bias[map(idx)] + sum_s partial[s][idx]), slices added in ascending order.
+__global__ __launch_bounds__(kThreads) void finish_partials_kernel(const float* __restrict__ partial,
+                                                                   const float* __restrict__ bias,
+                                                                   float* __restrict__ out, int64_t count, int splits,
+                                                                   int64_t plane, int maps, int relu) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= count) return;
+  float acc = 0.f;
+  for (int s = 0; s < splits; ++s) acc += partial[(int64_t)s * count + i];
+  if (bias) acc += bias[(i / plane) % maps];
+  if (relu) acc = fmaxf(acc, 0.f);
+  out[i] = acc;
+}
+
+// ---- few input channels (CI <= 4), any number of output maps -----------------------------------------
+// Block = (sample, band, group of output maps).  All CI input bands sit in LDS; output maps are
+// produced four at a time so that every LDS read feeds 16 multiply-adds.
+template <int CI>
+__global__ __launch_bounds__(kThreads) void direct_few_in_kernel(DirectGeom g, const float* __restrict__ in,
+                                                                 const float* __restrict__ w,
+                                                                 const float* __restrict__ bias,
+                                                                 float* __restrict__ out, int ogroup, int ogroups,
+                                                                 int relu) {
+  extern __shared__ float tile[];
+  int b = blockIdx.x;
+  const int og = b % ogroups;
+  b /= ogroups;
+  const int band = b % g.bands;
+  const int n = b / g.bands;
+  const int y0 = band * g.bh;
+  const int bh_eff = min(g.bh, g.oh - y0);
+  const int rows = bh_eff + g.r - 1;
+  const int plane_lds = (g.bh + g.r - 1) * g.twp;
+  const int ty = threadIdx.x / g.groups, gx = threadIdx.x - ty * g.groups;
+  const bool active = ty < bh_eff;
+
+#pragma unroll
+  for (int i = 0; i < CI; ++i) stage_plane(g, in + ((int64_t)n * CI + i) * g.ih * g.iw, y0, rows, tile + i * plane_lds);
+  __syncthreads();
+  if (!active) return;
+
+  const int o_end = min(g.co, (og + 1) * ogroup);
+  const int y = y0 + ty;
+  for (int o0 = og * ogroup; o0 < o_end; o0 += 4) {
+    float acc[4][kPx];
+#pragma unroll
+    for (int o = 0; o < 4; ++o)
+#pragma unroll
+      for (int j = 0; j < kPx; ++j) acc[o][j] = 0.f;
+#pragma unroll
+    for (int i = 0; i < CI; ++i)
+      for (int r = 0; r < g.r; ++r) {
+        const float* wrow[4];
+#pragma unroll
+        for (int o = 0; o < 4; ++o)  // maps past the end reuse the last valid one; their results are dropped
+          wrow[o] = w + (int64_t)min(o0 + o, g.co - 1) * g.w_so + (int64_t)i * g.w_si + tap_index(g, r, 0);
+        row_taps<4>(g, tile + i * plane_lds + (ty + r) * g.twp + gx * kPx, wrow, acc);
+      }
+#pragma unroll
+    for (int o = 0; o < 4; ++o) {
+      if (o0 + o >= o_end) break;
+      float* dst = out + (((int64_t)n * g.co + o0 + o) * g.oh + y) * g.ow;
+      const float bv = bias ? bias[o0 + o] : 0.f;
+#pragma unroll
+      for (int j = 0; j < kPx; ++j) {
+        const int x = gx * kPx + j;
+        if (x < g.ow) {
+          float v = acc[o][j] + bv;
+          if (relu) v = fmaxf(v, 0.f);
+          dst[x] = v;
+        }
+      }
+    }
+  }
+}
+
+// ---- planning ------------------------------------------------------------------------------------------
+static bool plan_bands(DirectGeom* g, int planes_in_lds, int min_pitch) {
+  g->groups = (g->ow + kPx - 1) / kPx;
+  if (g->groups > kThreads) return false;
+  g->twp = g->groups * kPx + g->s - 1;
+  if (g->twp < min_pitch) g->twp = min_pitch;
+  int bh = kThreads / g->groups;
+  if (bh > g->oh) bh = g->oh;
+  while (bh >= 1 && (size_t)planes_in_lds * (bh + g->r - 1) * g->twp * sizeof(float) > kMaxLds - 4096) --bh;
+  if (bh < 1) return false;
+  g->bh = bh;
+  g->bands = (g->oh + bh - 1) / bh;
+  return true;
+}
+
+bool direct_fwd_geom(const ConvGeom& c, DirectGeom* g) {
+  *g = DirectGeom{};
+  g->n = c.n, g->ci = c.c, g->ih = c.h, g->iw = c.w, g->co = c.k, g->oh = c.oh, g->ow = c.ow;
+  g->r = c.r, g->s = c.s, g->py = c.ph, g->px = c.pw;
+  g->w_so = c.K, g->w_si = (int64_t)c.r * c.s, g->flip = 0;
+  return true;
+}
+
+bool direct_bwd_data_geom(const ConvGeom& c, DirectGeom* g) {
+  *g = DirectGeom{};
+  g->n = c.n, g->ci = c.k, g->ih = c.oh, g->iw = c.ow, g->co = c.c, g->oh = c.h, g->ow = c.w;
+  g->r = c.r, g->s = c.s, g->py = c.r - 1 - c.ph, g->px = c.s - 1 - c.pw;
+  g->w_so = (int64_t)c.r * c.s, g->w_si = c.K, g->flip = 1;
+  return true;
+}
+
+// Channel slices for the few-output kernel: enough blocks to fill the chip, at least 8 channels each.
+static int few_out_split(const DirectGeom& g) {
+  const int64_t base = (int64_t)g.n * g.bands;
+  int split = (int)ceil_div(768, base);
+  const int max_split = g.ci / 8 > 0 ? g.ci / 8 : 1;
+  if (split > max_split) split = max_split;
+  if (split < 1) split = 1;
+  return split;
+}
+
+bool direct_few_out_plan(DirectGeom* g, int* isplit, size_t* partial_bytes) {
+  if (g->co < 1 || g->co > 4) return false;
+  if (!plan_bands(g, 1, 0)) return false;
+  *isplit = few_out_split(*g);
+  *partial_bytes = *isplit > 1 ? (size_t)*isplit * g->n * g->co * g->oh * g->ow * sizeof(float) : 0;
+  return true;
+}
+
+vcnn_status launch_direct_few_out(const DirectGeom& g, int isplit, const float* in, const float* w, const float* bias,
+                                  float* out, float* partial, int relu, hipStream_t st) {
+  const size_t lds = (size_t)(g.bh + g.r - 1) * g.twp * sizeof(float);
+  const dim3 grid((unsigned)((int64_t)g.n * g.bands * isplit)), block(kThreads);
+  float* dst = isplit > 1 ? partial : out;
+  switch (g.co) {
+    case 1: hipLaunchKernelGGL(direct_few_out_kernel<1>, grid, block, lds, st, g, in, w, bias, dst, isplit, relu); break;
+    case 2: hipLaunchKernelGGL(direct_few_out_kernel<2>, grid, block, lds, st, g, in, w, bias, dst, isplit, relu); break;
+    case 3: hipLaunchKernelGGL(direct_few_out_kernel<3>, grid, block, lds, st, g, in, w, bias, dst, isplit, relu); break;
+    default: hipLaunchKernelGGL(direct_few_out_kernel<4>, grid, block, lds, st, g, in, w, bias, dst, isplit, relu); break;
+  }
+  if (vcnn_status s = check_launch("direct_few_out")) return s;
+  if (isplit == 1) return VCNN_OK;
+  const int64_t count = (int64_t)g.n * g.co * g.oh * g.ow;
+  hipLaunchKernelGGL(finish_partials_kernel, dim3((unsigned)ceil_div(count, kThreads)), block, 0, st, partial, bias, out,
+                     count, isplit, (int64_t)g.oh * g.ow, g.co, relu);
+  return check_launch("finish_partials");
+}
+
+bool direct_few_in_plan(DirectGeom* g, int* ogroup) {
+  if (g->ci < 1 || g->ci > 4) return false;
+  if (!plan_bands(g, g->ci, 0)) return false;
+  // groups of output maps: multiples of 4, enough blocks to fill the chip
+  const int64_t base = (int64_t)g->n * g->bands;
+  int groups_wanted = (int)ceil_div(1024, base);
+  int og = (int)ceil_div(g->co, groups_wanted);
+  og = (int)ceil_div(og, 4) * 4;
+  if (og < 4) og = 4;
+  *ogroup = og;
+  return true;
+}
+
+vcnn_status launch_direct_few_in(const DirectGeom& g, int ogroup, const float* in, const float* w, const float* bias,
+                                 float* out, int relu, hipStream_t st) {
+  const size_t lds = (size_t)g.ci * (g.bh + g.r - 1) * g.twp * sizeof(float);
+  const int ogroups = (int)ceil_div(g.co, ogroup);
+  const dim3 grid((unsigned)((int64_t)g.n * g.bands * ogroups)), block(kThreads);
+  switch (g.ci) {
+    case 1: hipLaunchKernelGGL(direct_few_in_kernel<1>, grid, block, lds, st, g, in, w, bias, out, ogroup, ogroups, relu); break;
+    case 2: hipLaunchKernelGGL(direct_few_in_kernel<2>, grid, block, lds, st, g, in, w, bias, out, ogroup, ogroups, relu); break;
+    case 3: hipLaunchKernelGGL(direct_few_in_kernel<3>, grid, block, lds, st, g, in, w, bias, out, ogroup, ogroups, relu); break;
+    default: hipLaunchKernelGGL(direct_few_in_kernel<4>, grid, block, lds, st, g, in, w, bias, out, ogroup, ogroups, relu); break;
+  }
+  return check_launch("direct_few_in");
+}
+
+// ---- filter gradient for degenerate channel counts ------------------------------------------------------
+// dw[m][c][r][s] = sum_{n,y,x} dy[n][m][y][x] * xpad[n][c][y + r - ph][x + s - pw].
+// Block = (m, c, four tap chunks, slice of the batch).  A tap chunk is 8 consecutive s at one r; each
+// wave owns one chunk and its lanes sweep the pixels of the staged band, four per step, keeping the 8
+// partial sums in registers.  Lanes are combined with a fixed butterfly, batch slices by the caller.
+static constexpr int kTapChunk = 8;
+
+__global__ __launch_bounds__(kThreads) void direct_filter_grad_kernel(DirectGeom g, const float* __restrict__ x,
+                                                                      const float* __restrict__ dy,
+                                                                      float* __restrict__ partial, int tap_blocks,
+                                                                      int imgs_per_slice) {
+  // geometry: in = x [n][ci][ih][iw]; dy = [n][co][oh][ow]; taps r x s; py/px = padding
+  extern __shared__ float lds[];
+  const int sch = (g.s + kTapChunk - 1) / kTapChunk;
+  const int nch = g.r * sch;
+  int b = blockIdx.x;
+  const int tb = b % tap_blocks;
+  b /= tap_blocks;
+  const int mc = b % (g.co * g.ci);
+  const int slice = b / (g.co * g.ci);
+  const int m = mc / g.ci, c = mc - m * g.ci;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int q = tb * 4 + wave;
+  const bool valid = q < nch;
+  const int r = valid ? q / sch : 0;
+  const int s0 = valid ? (q - r * sch) * kTapChunk : 0;
+  const int dyp = g.groups * kPx;  // dy band pitch
+  float* xt = lds;
+  float* dt = lds + (g.bh + g.r - 1) * g.twp;
+
+  float acc[kTapChunk];
+#pragma unroll
+  for (int t = 0; t < kTapChunk; ++t) acc[t] = 0.f;
+
+  const int n0 = slice * imgs_per_slice, n1 = min(g.n, n0 + imgs_per_slice);
+  for (int n = n0; n < n1; ++n) {
+    const float* xp = x + ((int64_t)n * g.ci + c) * g.ih * g.iw;
+    const float* dp = dy + ((int64_t)n * g.co + m) * g.oh * g.ow;
+    for (int band = 0; band < g.bands; ++band) {
+      const int y0 = band * g.bh;
+      const int bh_eff = min(g.bh, g.oh - y0);
+      __syncthreads();
+      stage_plane(g, xp, y0, bh_eff + g.r - 1, xt);
+      for (int ry = wave; ry < bh_eff; ry += kThreads / 64)
+        for (int rx = lane; rx < dyp; rx += 64) dt[ry * dyp + rx] = rx < g.ow ? dp[(int64_t)(y0 + ry) * g.ow + rx] : 0.f;
+      __syncthreads();
+      if (valid) {
+        const int npg = bh_eff * g.groups;
+        for (int pg = lane; pg < npg; pg += 64) {
+          const int ty = pg / g.groups, gx = pg - ty * g.groups;
+          const float* dr = dt + ty * dyp + gx * kPx;
+          const float d0 = dr[0], d1 = dr[1], d2 = dr[2], d3 = dr[3];
+          const float* row = xt + (ty + r) * g.twp + gx * kPx + s0;
+          float xs[kTapChunk + 3];
+#pragma unroll
+          for (int t = 0; t < kTapChunk + 3; ++t) xs[t] = row[t];
+#pragma unroll
+          for (int t = 0; t < kTapChunk; ++t)
+            acc[t] = fmaf(d3, xs[t + 3], fmaf(d2, xs[t + 2], fmaf(d1, xs[t + 1], fmaf(d0, xs[t], acc[t]))));
+        }
+      }
+    }
+  }
+  if (!valid) return;
+#pragma unroll
+  for (int t = 0; t < kTapChunk; ++t) {
+    float v = acc[t];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    acc[t] = v;
+  }
+  if (lane == 0) {
+    float* dst = partial + ((int64_t)slice * g.co * g.ci + mc) * g.r * g.s + (int64_t)r * g.s + s0;
+#pragma unroll
+    for (int t = 0; t < kTapChunk; ++t)
+      if (s0 + t < g.s) dst[t] = acc[t];
+  }
+}
+
+bool direct_filter_grad_plan(const ConvGeom& c, DirectGeom* g, int* slices, size_t* partial_bytes) {
+  if (!(c.k <= 4 || c.c <= 4)) return false;
+  direct_fwd_geom(c, g);
+  const int sch = (c.s + kTapChunk - 1) / kTapChunk;
+  g->groups = (g->ow + kPx - 1) / kPx;
+  const int pitch = g->groups * kPx + kTapChunk * sch - 1 + 3;  // widest window any lane reads
+  g->twp = pitch;
+  if (g->s * 4 < kTapChunk * sch && g->r * g->s > 16) return false;  // mostly padding taps (e.g. 121x1): not worth it
+  // rows per band: as many as fit in LDS next to the dy band
+  int bh = g->oh;
+  auto bytes = [&](int h) { return ((size_t)(h + g->r - 1) * g->twp + (size_t)h * g->groups * kPx) * sizeof(float); };
+  while (bh >= 1 && bytes(bh) > kMaxLds - 4096) --bh;
+  if (bh < 1) return false;
+  g->bh = bh;
+  g->bands = (g->oh + bh - 1) / bh;
+  const int tap_blocks = (int)ceil_div((int64_t)g->r * sch, 4);
+  const int64_t base = (int64_t)c.k * c.c * tap_blocks;
+  int want = (int)ceil_div(2048, base);
+  if (want > c.n) want = c.n;
+  if (want < 1) want = 1;
+  const int per = (int)ceil_div(c.n, want);
+  *slices = (int)ceil_div(c.n, per);
+  *partial_bytes = *slices > 1 ? (size_t)*slices * c.M * c.K * sizeof(float) : 0;
+  return true;
+}
+
+vcnn_status launch_direct_filter_grad(const DirectGeom& g, int slices, const float* x, const float* dy, float* dw,
+                                      float* partial, hipStream_t st) {
+  const int sch = (g.s + kTapChunk - 1) / kTapChunk;
+  const int tap_blocks = (int)ceil_div((int64_t)g.r * sch, 4);
+  const int per = (int)ceil_div(g.n, slices);
+  const size_t lds = ((size_t)(g.bh + g.r - 1) * g.twp + (size_t)g.bh * g.groups * kPx) * sizeof(float);
+  const int64_t blocks = (int64_t)g.co * g.ci * tap_blocks * slices;
+  if (blocks > 0x7fffffffLL) return fail(VCNN_ERR_UNSUPPORTED, "direct filter gradient: too many blocks");
+  float* dst = slices > 1 ? partial : dw;
+  hipLaunchKernelGGL(direct_filter_grad_kernel, dim3((unsigned)blocks), dim3(kThreads), lds, st, g, x, dy, dst,
+                     tap_blocks, per);
+  if (vcnn_status s = check_launch("direct_filter_grad")) return s;
+  if (slices == 1) return VCNN_OK;
+  const int64_t count = (int64_t)g.co * g.ci * g.r * g.s;
+  hipLaunchKernelGGL(finish_partials_kernel, dim3((unsigned)ceil_div(count, kThreads)), dim3(kThreads), 0, st, partial,
+                     (const float*)nullptr, dw, count, slices, (int64_t)1, 1, 0);
+  return check_launch("finish_partials");
+}
+
+}  // namespace vcnn

@@ -28,7 +28,21 @@ CONV_SHAPES = [
     (2, 4, 20, 20, 64, 9, 9, 4, 4),
     (3, 2, 6, 7, 4, 1, 1, 1, 1),
     (1, 1, 5, 5, 1, 5, 5, 0, 0),
+    (3, 19, 21, 22, 1, 8, 8, 0, 0),     # one output map, many channels (channel slices)
+    (2, 9, 30, 13, 3, 5, 4, 2, 1),      # three output maps
+    (2, 2, 33, 70, 21, 3, 9, 1, 4),     # two input channels, wide rows
+    (5, 4, 12, 12, 9, 16, 16, 8, 8),    # kernel larger than the image interior
+    (2, 1, 70, 70, 7, 21, 1, 0, 0),     # tall single-column kernel
 ]
+
+
+@pytest.fixture(params=["auto", "explicit"])
+def algo(request):
+    """Runs a test once with the per-shape kernel choice and once with the unroll forced explicit
+    (phi_c as its own kernel + matrix product), so both realisations stay covered."""
+    vcnn.set_conv_algo(vcnn.ALGO_EXPLICIT if request.param == "explicit" else vcnn.ALGO_AUTO)
+    yield request.param
+    vcnn.set_conv_algo(vcnn.ALGO_AUTO)
 
 
 def ws_for(d, which):
@@ -87,7 +101,7 @@ def test_unroll_adjoint_identity_on_gpu():
 
 @pytest.mark.parametrize("relu", [False, True])
 @pytest.mark.parametrize("shape", CONV_SHAPES)
-def test_conv_fwd(shape, relu):
+def test_conv_fwd(shape, relu, algo):
     n, c, h, w, k, r, s, ph, pw = shape
     x, wt, b, _ = conv_case(shape, 400)
     d = vcnn.conv_desc(n, c, h, w, k, r, s, ph, pw, act=vcnn.ACT_RELU if relu else vcnn.ACT_NONE)
@@ -101,7 +115,7 @@ def test_conv_fwd(shape, relu):
 
 
 @pytest.mark.parametrize("shape", CONV_SHAPES)
-def test_conv_bwd_filter(shape):
+def test_conv_bwd_filter(shape, algo):
     n, c, h, w, k, r, s, ph, pw = shape
     x, _, _, dy = conv_case(shape, 500)
     d = vcnn.conv_desc(n, c, h, w, k, r, s, ph, pw)
@@ -120,7 +134,7 @@ def test_conv_bwd_filter(shape):
 
 
 @pytest.mark.parametrize("shape", CONV_SHAPES)
-def test_conv_bwd_data(shape):
+def test_conv_bwd_data(shape, algo):
     n, c, h, w, k, r, s, ph, pw = shape
     _, wt, _, dy = conv_case(shape, 600)
     d = vcnn.conv_desc(n, c, h, w, k, r, s, ph, pw)
