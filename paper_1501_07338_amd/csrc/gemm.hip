@@ -5,16 +5,17 @@
 //   bwd filter:                 dW[M x K]   = dY * col^T  (contraction over the N = batch*OH*OW axis)
 //   fully connected layers: the same products with plain row-major operands.
 //
-// All of them run v_mfma_f32_32x32x2_f32 on LDS-staged tiles.  LDS tiles are stored k-major
-// ([BK][BM], [BK][BN]) so that the 32 lanes of a half-wave read 32 consecutive floats.
+// All of them run v_mfma_f32_32x32x2_f32 on LDS-staged, double-buffered slabs (see mma_core.h): the
+// global loads of slab t+1 are issued before the MFMAs of slab t and written to the other LDS buffer
+// afterwards, so a block synchronises once per slab.
+#include <cstdlib>
+
 #include "common.h"
+#include "mma_core.h"
 
 namespace vcnn {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
 static constexpr int kThreads = 256;
-static constexpr int BK = 16;
 
 __device__ __forceinline__ int64_t jmap(int j, int P, int64_t s_img, int64_t s_j) {
   if (P > 0) {
@@ -24,113 +25,103 @@ __device__ __forceinline__ int64_t jmap(int j, int P, int64_t s_img, int64_t s_j
   return (int64_t)j * s_j;
 }
 
-// Multiply-accumulate one BK-deep pair of LDS tiles into the wave's accumulators.
-// Operand layout of the 32x32x2 instruction: lane l supplies A[row l%32][k l/32] and B[k l/32][col l%32].
-template <int LDA, int LDB, int TM, int TN>
-__device__ __forceinline__ void mma_tile(const float* As, const float* Bs, int wm0, int wn0, int lane,
-                                         f32x16 (&acc)[TM][TN]) {
-  const int l32 = lane & 31;
-  const int half = lane >> 5;
-#pragma unroll
-  for (int kk = 0; kk < BK; kk += 2) {
-    float av[TM], bv[TN];
-#pragma unroll
-    for (int mi = 0; mi < TM; ++mi) av[mi] = As[(kk + half) * LDA + wm0 + mi * 32 + l32];
-#pragma unroll
-    for (int ni = 0; ni < TN; ++ni) bv[ni] = Bs[(kk + half) * LDB + wn0 + ni * 32 + l32];
-#pragma unroll
-    for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-      for (int ni = 0; ni < TN; ++ni)
-        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mi], bv[ni], acc[mi][ni], 0, 0, 0);
-  }
+// Consecutive block ids are dealt round-robin to the 8 XCDs (each with its own L2).  Remap so that a
+// run of consecutive tile ids - which share operand panels - stays on one XCD.
+__device__ __forceinline__ int xcd_remap(int bid, int total) {
+  constexpr int X = 8;
+  const int per = total / X;           // tiles per XCD in the evenly divisible part
+  const int body = per * X;
+  if (bid >= body) return bid;         // ragged tail keeps its id
+  return (bid % X) * per + bid / X;
 }
 
-// Accumulator layout of the 32x32 result: register q of lane l holds row 8*(q/4) + 4*(l/32) + q%4, column l%32.
-__device__ __forceinline__ int acc_row(int q, int lane) { return 8 * (q >> 2) + 4 * (lane >> 5) + (q & 3); }
-
-template <int BM, int BN, int WM, int WN, bool A_KC, bool B_KC>
-__global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmArgs a, int tiles_m) {
+template <int BM, int BN, int BK, int WM, int WN, bool A_KC, bool B_KC, bool A_VEC, bool B_VEC>
+__global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmArgs a, int tiles_m, int tiles_total) {
   static_assert((BM / WM) * (BN / WN) * 64 == kThreads, "four waves per block");
-  constexpr int LDA = BM + (A_KC ? 1 : 0);
-  constexpr int LDB = BN + (B_KC ? 1 : 0);
-  constexpr int NA = BM * BK / kThreads;
-  constexpr int NB = BN * BK / kThreads;
+  using LA = LdsTile<BM, BK, A_KC>;
+  using LB = LdsTile<BN, BK, B_KC>;
+  using SA = Stager<BM, BK, kThreads, A_KC, A_VEC>;
+  using SB = Stager<BN, BK, kThreads, B_KC, B_VEC>;
   constexpr int TM = WM / 32, TN = WN / 32;
-  __shared__ float As[BK * LDA];
-  __shared__ float Bs[BK * LDB];
+  extern __shared__ float4 smem4[];
+  float* smem = reinterpret_cast<float*>(smem4);
+  // Buffers are addressed as smem + offset (not through a pointer table) so that the compiler keeps
+  // them in the LDS address space and emits ds_read/ds_write rather than flat accesses.
+  float* const As0 = smem;
+  float* const Bs0 = smem + 2 * LA::SIZE;
 
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int tm = blockIdx.x % tiles_m;
-  const int tn = blockIdx.x / tiles_m;
-  const int i0 = tm * BM;
-  const int j0 = tn * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tile = xcd_remap(blockIdx.x, tiles_total);
+  const int i0 = (tile % tiles_m) * BM;
+  const int j0 = (tile / tiles_m) * BN;
   const int wm0 = (wave % (BM / WM)) * WM;
   const int wn0 = (wave / (BM / WM)) * WN;
 
-  // Per-thread load slots.  The fastest-varying thread index walks the operand's contiguous axis.
-  int a_il[NA], a_kl[NA];
-  int64_t a_off[NA];
-  bool a_ok[NA];
+  SA sa;
+  SB sb;
+  sa.init(tid);
+  sb.init(tid);
+  // Element offsets of every slot at k = 0.  Slots whose row lies outside the matrix point at row 0 and
+  // are zeroed when the slab is written to LDS, so the loads themselves are unconditional and
+  // branch-free (they stay in flight across the MFMAs of the current slab).
+  int64_t a_off[SA::SLOTS], b_off[SB::SLOTS];
+  bool a_row_ok[SA::SLOTS], b_row_ok[SB::SLOTS];
 #pragma unroll
-  for (int e = 0; e < NA; ++e) {
-    if (A_KC) {
-      a_kl[e] = tid % BK;
-      a_il[e] = tid / BK + e * (kThreads / BK);
-    } else {
-      a_il[e] = tid % BM;
-      a_kl[e] = tid / BM + e * (kThreads / BM);
-    }
-    a_ok[e] = (i0 + a_il[e]) < a.M;
-    a_off[e] = (int64_t)(i0 + a_il[e]) * a.a_si + (int64_t)a_kl[e] * a.a_sk;
+  for (int e = 0; e < SA::SLOTS; ++e) {
+    const int i = i0 + sa.row_of(e, 0);
+    a_row_ok[e] = i < a.M;
+    a_off[e] = (int64_t)(a_row_ok[e] ? i : 0) * a.a_si;
   }
-  int b_jl[NB], b_kl[NB];
-  int64_t b_off[NB];
-  bool b_ok[NB];
 #pragma unroll
-  for (int e = 0; e < NB; ++e) {
-    if (B_KC) {
-      b_kl[e] = tid % BK;
-      b_jl[e] = tid / BK + e * (kThreads / BK);
-    } else {
-      b_jl[e] = tid % BN;
-      b_kl[e] = tid / BN + e * (kThreads / BN);
-    }
-    const int j = j0 + b_jl[e];
-    b_ok[e] = j < a.N;
-    b_off[e] = (b_ok[e] ? jmap(j, a.b_P, a.b_simg, a.b_sj) : 0) + (int64_t)b_kl[e] * a.b_sk;
+  for (int e = 0; e < SB::SLOTS; ++e) {
+    const int j = j0 + sb.row_of(e, 0);
+    b_row_ok[e] = j < a.N;
+    b_off[e] = jmap(b_row_ok[e] ? j : 0, a.b_P, a.b_simg, a.b_sj);
   }
 
-  f32x16 acc[TM][TN];
-#pragma unroll
-  for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < TN; ++ni)
-#pragma unroll
-      for (int q = 0; q < 16; ++q) acc[mi][ni][q] = 0.f;
-
-  float ra[NA], rb[NB];
   auto fetch = [&](int k0) {
 #pragma unroll
-    for (int e = 0; e < NA; ++e)
-      ra[e] = (a_ok[e] && (k0 + a_kl[e]) < a.K) ? a.A[a_off[e] + (int64_t)k0 * a.a_sk] : 0.f;
+    for (int e = 0; e < SA::SLOTS; ++e) {
+      const int k = k0 + sa.k_of(e, 0);
+      sa.ok[e] = a_row_ok[e] && k < a.K;
+      const float* src = a.A + a_off[e] + (int64_t)min(k, (A_VEC && A_KC) ? a.K - 4 : a.K - 1) * a.a_sk;
+      if (A_VEC) {
+        const float4 t = *reinterpret_cast<const float4*>(src);
+        sa.v[e][0] = t.x, sa.v[e][1] = t.y, sa.v[e][2] = t.z, sa.v[e][3] = t.w;
+      } else {
+        sa.v[e][0] = *src;
+      }
+    }
 #pragma unroll
-    for (int e = 0; e < NB; ++e)
-      rb[e] = (b_ok[e] && (k0 + b_kl[e]) < a.K) ? a.B[b_off[e] + (int64_t)k0 * a.b_sk] : 0.f;
+    for (int e = 0; e < SB::SLOTS; ++e) {
+      const int k = k0 + sb.k_of(e, 0);
+      sb.ok[e] = b_row_ok[e] && k < a.K;
+      const float* src = a.B + b_off[e] + (int64_t)min(k, (B_VEC && B_KC) ? a.K - 4 : a.K - 1) * a.b_sk;
+      if (B_VEC) {
+        const float4 t = *reinterpret_cast<const float4*>(src);
+        sb.v[e][0] = t.x, sb.v[e][1] = t.y, sb.v[e][2] = t.z, sb.v[e][3] = t.w;
+      } else {
+        sb.v[e][0] = *src;
+      }
+    }
   };
+
+  f32x16 acc[TM][TN];
+  zero_acc<TM, TN>(acc);
 
   const int ktiles = (a.K + BK - 1) / BK;
   fetch(0);
+  sa.store(As0);
+  sb.store(Bs0);
+  __syncthreads();
   for (int kt = 0; kt < ktiles; ++kt) {
-#pragma unroll
-    for (int e = 0; e < NA; ++e) As[a_kl[e] * LDA + a_il[e]] = ra[e];
-#pragma unroll
-    for (int e = 0; e < NB; ++e) Bs[b_kl[e] * LDB + b_jl[e]] = rb[e];
-    __syncthreads();
+    const int cur = kt & 1;
     if (kt + 1 < ktiles) fetch((kt + 1) * BK);
-    mma_tile<LDA, LDB, TM, TN>(As, Bs, wm0, wn0, lane, acc);
+    mma_slab<BM, BN, BK, TM, TN, A_KC, B_KC>(As0 + cur * LA::SIZE, Bs0 + cur * LB::SIZE, wm0, wn0, lane, acc);
+    if (kt + 1 < ktiles) {
+      sa.store(As0 + (cur ^ 1) * LA::SIZE);
+      sb.store(Bs0 + (cur ^ 1) * LB::SIZE);
+    }
     __syncthreads();
   }
 
@@ -155,31 +146,83 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmArgs a, int tile
   }
 }
 
-template <int BM, int BN, int WM, int WN>
-static void launch_cfg(const GemmArgs& a, bool a_kc, bool b_kc, hipStream_t st) {
+template <int BM, int BN, int BK, bool A_KC, bool B_KC>
+static constexpr size_t gemm_lds_bytes() {
+  return 2 * (size_t)(LdsTile<BM, BK, A_KC>::SIZE + LdsTile<BN, BK, B_KC>::SIZE) * sizeof(float);
+}
+
+// Opts a kernel in to more than the default dynamic LDS limit, once per kernel.
+template <typename K>
+static void allow_lds(K kernel, size_t bytes, bool& done) {
+  if (bytes > 48 * 1024 && !done) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)bytes);
+    done = true;
+  }
+}
+
+template <int BM, int BN, int BK, int WM, int WN, bool A_KC, bool B_KC, bool A_VEC, bool B_VEC>
+static void launch_one(const GemmArgs& a, hipStream_t st) {
   const int tiles_m = (int)ceil_div(a.M, BM);
   const int64_t blocks = (int64_t)tiles_m * ceil_div(a.N, BN);
-  const dim3 grid((unsigned)blocks), block(kThreads);
-  if (a_kc && b_kc)
-    hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, WM, WN, true, true>), grid, block, 0, st, a, tiles_m);
-  else if (a_kc)
-    hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, WM, WN, true, false>), grid, block, 0, st, a, tiles_m);
-  else if (b_kc)
-    hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, WM, WN, false, true>), grid, block, 0, st, a, tiles_m);
-  else
-    hipLaunchKernelGGL((gemm_f32_kernel<BM, BN, WM, WN, false, false>), grid, block, 0, st, a, tiles_m);
+  const size_t lds = gemm_lds_bytes<BM, BN, BK, A_KC, B_KC>();
+  auto kernel = gemm_f32_kernel<BM, BN, BK, WM, WN, A_KC, B_KC, A_VEC, B_VEC>;
+  static bool opted_in = false;  // one flag per instantiation of this launcher, i.e. per kernel
+  allow_lds(kernel, lds, opted_in);
+  hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kThreads), lds, st, a, tiles_m, (int)blocks);
 }
+
+template <int BM, int BN, int BK, int WM, int WN, bool A_KC, bool B_KC>
+static void launch_vec(const GemmArgs& a, bool av, bool bv, hipStream_t st) {
+  if (av && bv)
+    launch_one<BM, BN, BK, WM, WN, A_KC, B_KC, true, true>(a, st);
+  else if (av)
+    launch_one<BM, BN, BK, WM, WN, A_KC, B_KC, true, false>(a, st);
+  else if (bv)
+    launch_one<BM, BN, BK, WM, WN, A_KC, B_KC, false, true>(a, st);
+  else
+    launch_one<BM, BN, BK, WM, WN, A_KC, B_KC, false, false>(a, st);
+}
+
+template <int BM, int BN, int BK, int WM, int WN>
+static void launch_cfg(const GemmArgs& a, bool a_kc, bool b_kc, bool av, bool bv, hipStream_t st) {
+  if (a_kc && b_kc)
+    launch_vec<BM, BN, BK, WM, WN, true, true>(a, av, bv, st);
+  else if (a_kc)
+    launch_vec<BM, BN, BK, WM, WN, true, false>(a, av, bv, st);
+  else if (b_kc)
+    launch_vec<BM, BN, BK, WM, WN, false, true>(a, av, bv, st);
+  else
+    launch_vec<BM, BN, BK, WM, WN, false, false>(a, av, bv, st);
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 vcnn_status launch_gemm_f32(const GemmArgs& a, hipStream_t st) {
   if (a.M <= 0 || a.N <= 0 || a.K <= 0) return fail(VCNN_ERR_SHAPE, "gemm: empty operand");
   const bool a_kc = (a.a_sk == 1) && (a.a_si != 1);
   const bool b_kc = (a.b_sk == 1) && (a.b_sj != 1);
-  if (a.M <= 32)
-    launch_cfg<32, 256, 32, 64>(a, a_kc, b_kc, st);
-  else if (a.M <= 64)
-    launch_cfg<64, 256, 64, 64>(a, a_kc, b_kc, st);
+  // 16-byte loads need the contiguous axis to come in aligned groups of four that never straddle a
+  // row (or, for the [N][M][P] maps, a sample) boundary.
+  bool av, bv;
+  if (a_kc)
+    av = aligned16(a.A) && a.a_si % 4 == 0 && a.K % 4 == 0;
   else
-    launch_cfg<128, 128, 64, 64>(a, a_kc, b_kc, st);
+    av = aligned16(a.A) && a.a_si == 1 && a.a_sk % 4 == 0 && a.M % 4 == 0;
+  if (b_kc)
+    bv = aligned16(a.B) && a.b_P == 0 && a.b_sj % 4 == 0 && a.K % 4 == 0;
+  else
+    bv = aligned16(a.B) && a.b_sj == 1 && a.b_sk % 4 == 0 && a.N % 4 == 0 &&
+         (a.b_P == 0 || (a.b_P % 4 == 0 && a.b_simg % 4 == 0));
+  static const int tune_bk = getenv("VCNN_TUNE_BK") ? atoi(getenv("VCNN_TUNE_BK")) : 32;
+  if (a.M <= 32)
+    launch_cfg<32, 256, 32, 32, 64>(a, a_kc, b_kc, av, bv, st);
+  else if (a.M <= 64)
+    launch_cfg<64, 256, 32, 64, 64>(a, a_kc, b_kc, av, bv, st);
+  else if (tune_bk == 16)
+    launch_cfg<128, 128, 16, 64, 64>(a, a_kc, b_kc, av, bv, st);
+  else
+    launch_cfg<128, 128, 32, 64, 64>(a, a_kc, b_kc, av, bv, st);
   return check_launch("gemm_f32");
 }
 
@@ -189,16 +232,22 @@ vcnn_status launch_gemm_f32(const GemmArgs& a, hipStream_t st) {
 // blockIdx.y selects a range of columns; each range writes its own partial product and a second
 // kernel adds the partials in ascending order, which keeps the result independent of scheduling.
 // -------------------------------------------------------------------------------------------------
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int BK, int WM, int WN, bool VEC>
 __global__ __launch_bounds__(kThreads) void bwd_filter_f32_kernel(ConvGeom g, const float* __restrict__ dy,
                                                                   const float* __restrict__ col,
                                                                   float* __restrict__ out, int tiles_m, int chunk) {
   static_assert((BM / WM) * (BN / WN) * 64 == kThreads, "four waves per block");
-  constexpr int LDA = BM + 1, LDB = BN + 1;
-  constexpr int NA = BM * BK / kThreads, NB = BN * BK / kThreads;
+  using LA = LdsTile<BM, BK, true>;
+  using LB = LdsTile<BN, BK, true>;
+  using SA = Stager<BM, BK, kThreads, true, VEC>;
+  using SB = Stager<BN, BK, kThreads, true, VEC>;
   constexpr int TM = WM / 32, TN = WN / 32;
-  __shared__ float As[BK * LDA];
-  __shared__ float Bs[BK * LDB];
+  extern __shared__ float4 smem4[];
+  float* smem = reinterpret_cast<float*>(smem4);
+  // Buffers are addressed as smem + offset (not through a pointer table) so that the compiler keeps
+  // them in the LDS address space and emits ds_read/ds_write rather than flat accesses.
+  float* const As0 = smem;
+  float* const Bs0 = smem + 2 * LA::SIZE;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int tm = blockIdx.x % tiles_m, tn = blockIdx.x / tiles_m;
@@ -210,33 +259,44 @@ __global__ __launch_bounds__(kThreads) void bwd_filter_f32_kernel(ConvGeom g, co
   const int M = (int)g.M, K = (int)g.K;
   const int P = (int)g.P;
 
-  const int kl = tid % BK;       // position along the contraction axis inside a BK slab
-  const int rl = tid / BK;       // first tile row this thread loads; further rows at +16
-  // (n, p) of this thread's first contraction index.
-  int64_t j = js + kl;
+  SA sa;
+  SB sb;
+  sa.init(tid);
+  sb.init(tid);
+  // (n, p) of this thread's first contraction index (sa.c == sb.c: same position inside the slab).
+  int64_t j = js + sa.c;
   int n = (int)(j / P);
   int p = (int)(j - (int64_t)n * P);
 
-  f32x16 acc[TM][TN];
-#pragma unroll
-  for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < TN; ++ni)
-#pragma unroll
-      for (int q = 0; q < 16; ++q) acc[mi][ni][q] = 0.f;
-
-  float ra[NA], rb[NB];
   auto fetch = [&]() {
+    // With VEC, je - js and P are multiples of 4, so a group of four is inside or outside as a whole.
+    // Out-of-range slots load from a clamped, valid address and are zeroed when written to LDS.
     const bool jin = j < je;
+    const int nn = jin ? n : 0, pp = jin ? p : 0;
+    const int64_t jj = jin ? j : 0;
 #pragma unroll
-    for (int e = 0; e < NA; ++e) {
-      const int m = i0 + rl + e * (kThreads / BK);
-      ra[e] = (jin && m < M) ? dy[((int64_t)n * M + m) * P + p] : 0.f;
+    for (int e = 0; e < SA::SLOTS; ++e) {
+      const int m = i0 + sa.line(e);
+      sa.ok[e] = jin && m < M;
+      const float* src = dy + ((int64_t)nn * M + min(m, M - 1)) * P + pp;
+      if (VEC) {
+        const float4 t = *reinterpret_cast<const float4*>(src);
+        sa.v[e][0] = t.x, sa.v[e][1] = t.y, sa.v[e][2] = t.z, sa.v[e][3] = t.w;
+      } else {
+        sa.v[e][0] = *src;
+      }
     }
 #pragma unroll
-    for (int e = 0; e < NB; ++e) {
-      const int k = k0 + rl + e * (kThreads / BK);
-      rb[e] = (jin && k < K) ? col[(int64_t)k * g.N + j] : 0.f;
+    for (int e = 0; e < SB::SLOTS; ++e) {
+      const int k = k0 + sb.line(e);
+      sb.ok[e] = jin && k < K;
+      const float* src = col + (int64_t)min(k, K - 1) * g.N + jj;
+      if (VEC) {
+        const float4 t = *reinterpret_cast<const float4*>(src);
+        sb.v[e][0] = t.x, sb.v[e][1] = t.y, sb.v[e][2] = t.z, sb.v[e][3] = t.w;
+      } else {
+        sb.v[e][0] = *src;
+      }
     }
     j += BK;
     p += BK;
@@ -246,16 +306,24 @@ __global__ __launch_bounds__(kThreads) void bwd_filter_f32_kernel(ConvGeom g, co
     }
   };
 
+  f32x16 acc[TM][TN];
+  zero_acc<TM, TN>(acc);
+
   const int ktiles = (int)((je - js + BK - 1) / BK);
-  if (ktiles > 0) fetch();
+  if (ktiles > 0) {
+    fetch();
+    sa.store(As0);
+    sb.store(Bs0);
+  }
+  __syncthreads();
   for (int kt = 0; kt < ktiles; ++kt) {
-#pragma unroll
-    for (int e = 0; e < NA; ++e) As[kl * LDA + rl + e * (kThreads / BK)] = ra[e];
-#pragma unroll
-    for (int e = 0; e < NB; ++e) Bs[kl * LDB + rl + e * (kThreads / BK)] = rb[e];
-    __syncthreads();
+    const int cur = kt & 1;
     if (kt + 1 < ktiles) fetch();
-    mma_tile<LDA, LDB, TM, TN>(As, Bs, wm0, wn0, lane, acc);
+    mma_slab<BM, BN, BK, TM, TN, true, true>(As0 + cur * LA::SIZE, Bs0 + cur * LB::SIZE, wm0, wn0, lane, acc);
+    if (kt + 1 < ktiles) {
+      sa.store(As0 + (cur ^ 1) * LA::SIZE);
+      sb.store(Bs0 + (cur ^ 1) * LB::SIZE);
+    }
     __syncthreads();
   }
 
@@ -284,8 +352,9 @@ __global__ __launch_bounds__(kThreads) void sum_partials_kernel(const float* __r
   out[i] = acc;
 }
 
+static constexpr int kBfBK = 32;
 static int bwd_filter_bm(const ConvGeom& g) { return g.M <= 32 ? 32 : (g.M <= 64 ? 64 : 128); }
-static int bwd_filter_bn(const ConvGeom& g) { return g.M <= 64 ? 128 : 128; }
+static int bwd_filter_bn(const ConvGeom&) { return 128; }
 
 static int bwd_filter_chunk(const ConvGeom& g) {
   const int64_t tiles = ceil_div(g.M, bwd_filter_bm(g)) * ceil_div(g.K, bwd_filter_bn(g));
@@ -294,7 +363,7 @@ static int bwd_filter_chunk(const ConvGeom& g) {
   if (want < 1) want = 1;
   if (want > max_splits) want = max_splits;
   int64_t chunk = ceil_div(g.N, want);
-  chunk = ceil_div(chunk, BK) * BK;
+  chunk = ceil_div(chunk, kBfBK) * kBfBK;
   return (int)chunk;
 }
 
@@ -305,6 +374,23 @@ size_t bwd_filter_partial_bytes(const ConvGeom& g) {
   return splits > 1 ? (size_t)splits * g.M * g.K * sizeof(float) : 0;
 }
 
+template <int BM, int BN, int WM, int WN>
+static void launch_bf(const ConvGeom& g, const float* dy, const float* col, float* out, int tiles_m, int chunk,
+                      dim3 grid, bool vec, hipStream_t st) {
+  const size_t lds = gemm_lds_bytes<BM, BN, kBfBK, true, true>();
+  if (vec) {
+    auto kernel = bwd_filter_f32_kernel<BM, BN, kBfBK, WM, WN, true>;
+    static bool opted_in = false;
+    allow_lds(kernel, lds, opted_in);
+    hipLaunchKernelGGL(kernel, grid, dim3(kThreads), lds, st, g, dy, col, out, tiles_m, chunk);
+  } else {
+    auto kernel = bwd_filter_f32_kernel<BM, BN, kBfBK, WM, WN, false>;
+    static bool opted_in = false;
+    allow_lds(kernel, lds, opted_in);
+    hipLaunchKernelGGL(kernel, grid, dim3(kThreads), lds, st, g, dy, col, out, tiles_m, chunk);
+  }
+}
+
 vcnn_status launch_bwd_filter_gemm_f32(const ConvGeom& g, const float* dy, const float* col, float* dw,
                                        float* partial, hipStream_t st) {
   const int chunk = bwd_filter_chunk(g);
@@ -313,19 +399,20 @@ vcnn_status launch_bwd_filter_gemm_f32(const ConvGeom& g, const float* dy, const
   const int bm = bwd_filter_bm(g);
   const int tiles_m = (int)ceil_div(g.M, bm);
   const int64_t tiles = (int64_t)tiles_m * ceil_div(g.K, bwd_filter_bn(g));
-  const dim3 grid((unsigned)tiles, (unsigned)splits), block(kThreads);
+  const dim3 grid((unsigned)tiles, (unsigned)splits);
   if (splits > 65535) return fail(VCNN_ERR_UNSUPPORTED, "bwd_filter: too many contraction splits");
+  const bool vec = g.P % 4 == 0 && aligned16(dy) && aligned16(col);
   if (bm == 32)
-    hipLaunchKernelGGL((bwd_filter_f32_kernel<32, 128, 32, 32>), grid, block, 0, st, g, dy, col, out, tiles_m, chunk);
+    launch_bf<32, 128, 32, 32>(g, dy, col, out, tiles_m, chunk, grid, vec, st);
   else if (bm == 64)
-    hipLaunchKernelGGL((bwd_filter_f32_kernel<64, 128, 32, 64>), grid, block, 0, st, g, dy, col, out, tiles_m, chunk);
+    launch_bf<64, 128, 32, 64>(g, dy, col, out, tiles_m, chunk, grid, vec, st);
   else
-    hipLaunchKernelGGL((bwd_filter_f32_kernel<128, 128, 64, 64>), grid, block, 0, st, g, dy, col, out, tiles_m, chunk);
+    launch_bf<128, 128, 64, 64>(g, dy, col, out, tiles_m, chunk, grid, vec, st);
   vcnn_status s = check_launch("bwd_filter_f32");
   if (s != VCNN_OK || splits == 1) return s;
   const int64_t count = g.M * g.K;
-  hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)ceil_div(count, kThreads)), block, 0, st, partial, dw, count,
-                     splits);
+  hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)ceil_div(count, kThreads)), dim3(kThreads), 0, st, partial, dw,
+                     count, splits);
   return check_launch("sum_partials");
 }
 
