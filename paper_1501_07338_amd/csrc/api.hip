@@ -75,12 +75,27 @@ static bool is_pointwise(const ConvGeom& g) { return g.r == 1 && g.s == 1 && g.p
 
 static size_t col_bytes(const ConvGeom& g) { return align256((size_t)g.K * g.N * sizeof(float)); }
 
+// The input gradient as a correlation over all H x W input pixels multiplies the zero border of a
+// 'valid' layer too and puts the input-channel count on the matrix-core row axis, so it can cost more
+// matrix-core work than the explicit route (transposed product, then phi_c^{-1}), which instead pays
+// for writing and re-reading the patch-matrix gradient.  Estimated times, in seconds, with the rates
+// these kernels sustain on MI355X (about 100 TFLOP/s of fp32 MFMA work, 2.5 TB/s through HBM).
+static bool halo_bwd_data_pays(const ConvGeom& g, const HaloPlan& hp) {
+  const double mfma_rate = 100e12, hbm_rate = 2.5e12;
+  const double halo_flops = 2.0 * (double)ceil_div(g.c, hp.bm) * hp.bm * ((double)g.k * g.r * g.s) *
+                            ((double)g.n * ceil_div((int64_t)g.h * g.w, hp.bn) * hp.bn);
+  const double exp_flops = 2.0 * (double)ceil_div(g.K, 128) * 128 * (double)ceil_div(g.M, 32) * 32 * (double)g.N;
+  const double col_traffic = 2.0 * (double)g.K * (double)g.N * sizeof(float);
+  return halo_flops / mfma_rate < exp_flops / mfma_rate + 1.3 * col_traffic / hbm_rate;
+}
+
 // Which realisation a pass uses for a given shape.  The same decision drives the workspace query and
 // the launch, so the two always agree.
-enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER };
+enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER, PATH_HALO };
 struct Plan {
   Path path;
   DirectGeom dg;
+  HaloPlan hp;
   int split;        // channel slices (few-out), output-map group size (few-in) or batch slices (filter gradient)
   size_t partial_bytes;
   size_t workspace_bytes;
@@ -89,13 +104,17 @@ struct Plan {
 static Plan make_plan(const ConvGeom& g, int pass) {
   Plan p{};
   p.path = PATH_EXPLICIT;
-  const bool allow_direct = g_conv_algo.load() != VCNN_ALGO_EXPLICIT;
+  const int algo = g_conv_algo.load();
+  const bool allow_direct = algo != VCNN_ALGO_EXPLICIT;
   if (pass == VCNN_PASS_FWD) {
     if (allow_direct && g.k <= 4 && direct_fwd_geom(g, &p.dg) && direct_few_out_plan(&p.dg, &p.split, &p.partial_bytes)) {
       p.path = PATH_FEW_OUT;
       p.workspace_bytes = align256(p.partial_bytes);
     } else if (is_pointwise(g)) {
       p.path = PATH_POINTWISE;
+    } else if (allow_direct && (g.c > 4 || algo == VCNN_ALGO_IMPLICIT) &&
+               conv_halo_plan(g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, &p.hp)) {
+      p.path = PATH_HALO;
     } else if (allow_direct && g.c <= 4 && direct_fwd_geom(g, &p.dg) && direct_few_in_plan(&p.dg, &p.split)) {
       p.path = PATH_FEW_IN;
     } else {
@@ -111,6 +130,12 @@ static Plan make_plan(const ConvGeom& g, int pass) {
       p.path = PATH_POINTWISE;
     } else if (allow_direct && g.k <= 4 && direct_bwd_data_geom(g, &p.dg) && direct_few_in_plan(&p.dg, &p.split)) {
       p.path = PATH_FEW_IN;
+    } else if (allow_direct && g.r - 1 - g.ph >= 0 && g.s - 1 - g.pw >= 0 &&
+               conv_halo_plan(g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, &p.hp) &&
+               (algo == VCNN_ALGO_IMPLICIT || halo_bwd_data_pays(g, p.hp))) {
+      // correlation of dy (k channels) with the flipped kernels; the flipped matrix lives in the workspace
+      p.path = PATH_HALO;
+      p.workspace_bytes = align256((size_t)g.M * g.K * sizeof(float));
     } else {
       p.workspace_bytes = col_bytes(g);
     }
@@ -203,6 +228,9 @@ vcnn_status vcnn_conv_fwd(const vcnn_conv_desc* d, const void* x, const void* w,
                                  (float*)workspace, relu, st);
   if (plan.path == PATH_FEW_IN)
     return launch_direct_few_in(plan.dg, plan.split, (const float*)x, (const float*)w, bias, (float*)y, relu, st);
+  if (plan.path == PATH_HALO)
+    return launch_conv_halo(plan.hp, g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, (const float*)x, (const float*)w,
+                            bias, (float*)y, relu, st);
 
   GemmArgs a{};
   a.A = (const float*)w, a.C = (float*)y, a.bias = bias;
@@ -261,6 +289,12 @@ vcnn_status vcnn_conv_bwd_data(const vcnn_conv_desc* d, const void* w, const voi
                                  (float*)workspace, 0, st);
   if (plan.path == PATH_FEW_IN)
     return launch_direct_few_in(plan.dg, plan.split, (const float*)dy, (const float*)w, nullptr, (float*)dx, 0, st);
+  if (plan.path == PATH_HALO) {
+    float* w2 = (float*)workspace;
+    if (vcnn_status s = launch_flip_transpose((const float*)w, w2, g.k, g.c, g.r * g.s, st)) return s;
+    return launch_conv_halo(plan.hp, g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw,
+                            (const float*)dy, w2, nullptr, (float*)dx, 0, st);
+  }
   float* dcol = (float*)workspace;
   // dcol[k][j] = sum_m W[m][k] * dY(m, j)
   GemmArgs a{};

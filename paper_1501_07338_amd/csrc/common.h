@@ -77,6 +77,21 @@ vcnn_status launch_direct_few_in(const DirectGeom& g, int ogroup, const float* i
 vcnn_status launch_direct_filter_grad(const DirectGeom& g, int slices, const float* x, const float* dy, float* dw,
                                       float* partial, hipStream_t st);
 
+// ---- conv_implicit.hip ----------------------------------------------------------------------------
+// Implicit-unroll convolution y = act(bias + W (*) x) on the matrix cores; see the file header.
+struct HaloPlan {
+  int bm, bn;        // block tile: output maps x consecutive output pixels
+  int cc;            // input channels staged per chunk
+  int nr, wp;        // halo tile rows and row pitch per channel
+  int kch;           // taps per chunk, padded to the slab depth
+  size_t lds_bytes;
+  bool vec;          // kernel-matrix rows can be fetched 16 bytes at a time
+};
+bool conv_halo_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int pw, HaloPlan* p);
+vcnn_status launch_conv_halo(const HaloPlan& p, int n, int c, int h, int w, int m, int r, int s, int ph, int pw,
+                             const float* x, const float* wgt, const float* bias, float* y, int relu, hipStream_t st);
+vcnn_status launch_flip_transpose(const float* w, float* w2, int M, int C, int RS, hipStream_t st);
+
 // ---- pointwise.hip ------------------------------------------------------------------------------
 vcnn_status launch_bias_grad_f32(const ConvGeom& g, const float* dy, float* db, hipStream_t st);
 vcnn_status launch_relu_fwd_f32(size_t count, const float* x, float* y, hipStream_t st);

@@ -1,0 +1,298 @@
+// Implicit-unroll convolution on the matrix cores: the patch matrix phi_c(x) of Eq. 2 / Eq. 4 is never
+// written.  A block owns BM output maps x BN consecutive output pixels of one sample.  For a chunk of
+// input channels it stages the input rows those pixels touch (with their halo, zero padded) in LDS;
+// the B operand of every MFMA step is then read straight from that tile at
+//     lane_base(pixel) + tap_offset(c, r, s),
+// i.e. the column of the patch matrix is formed by address arithmetic at the moment it is consumed.
+// The kernel matrix (A operand) streams through double-buffered LDS slabs exactly as in the plain
+// product.  Each input element is fetched from global memory once per block and reused R*S*BM times.
+//
+// The same kernel computes the input gradient (phi_c^{-1} of the transposed product, evaluated in
+// gather form): dx is the correlation of dy with the flipped, channel-transposed kernels, which a small
+// kernel writes to the workspace first.
+#include "common.h"
+#include "mma_core.h"
+
+namespace vcnn {
+
+static constexpr int kThreads = 256;
+static constexpr int BK = 32;
+
+struct HaloArgs {
+  const float* x;     // [n][c][h][w]
+  const float* wgt;   // [m][c*r*s]
+  const float* bias;  // [m] or null
+  float* y;           // [n][m][oh][ow]
+  int n, c, h, w, m, r, s, ph, pw, oh, ow;
+  int P;              // oh*ow
+  int tiles_m, tiles_per_img;
+  int cc;             // channels per chunk
+  int nr;             // halo rows per channel tile
+  int wp;             // halo row pitch (w + 2*pw)
+  int kch;            // taps per full chunk, padded to a multiple of BK
+  int relu;
+};
+
+template <int BM, int BN, int WM, int WN, bool VEC>
+__global__ __launch_bounds__(kThreads) void conv_halo_kernel(HaloArgs a) {
+  static_assert((BM / WM) * (BN / WN) * 64 == kThreads, "four waves per block");
+  using LA = LdsTile<BM, BK, true>;
+  using SA = Stager<BM, BK, kThreads, true, VEC>;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  extern __shared__ float4 smem4[];
+  float* const As0 = reinterpret_cast<float*>(smem4);       // 2 slabs of the kernel matrix
+  int* const tapoff = reinterpret_cast<int*>(As0 + 2 * LA::SIZE);  // [kch]
+  float* const halo = As0 + 2 * LA::SIZE + a.kch;           // [cc][nr][wp]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int tm = blockIdx.x % a.tiles_m;
+  const int tj = blockIdx.x / a.tiles_m;
+  const int n = tj / a.tiles_per_img;
+  const int p0 = (tj - n * a.tiles_per_img) * BN;
+  const int i0 = tm * BM;
+  const int wm0 = (wave % (BM / WM)) * WM;
+  const int wn0 = (wave / (BM / WM)) * WN;
+  const int RS = a.r * a.s;
+  const int K = a.c * RS;
+  const int plane = a.nr * a.wp;
+  const int oh_first = p0 / a.ow;
+
+  // tap table: offset of tap kk = (c_l, r, s) inside the halo tile; padding taps point at 0 (their
+  // kernel-matrix entries are zero).
+  for (int kk = tid; kk < a.kch; kk += kThreads) {
+    int off = 0;
+    if (kk < a.cc * RS) {
+      const int cl = kk / RS;
+      const int q = kk - cl * RS;
+      const int r = q / a.s;
+      off = cl * plane + r * a.wp + (q - r * a.s);
+    }
+    tapoff[kk] = off;
+  }
+
+  // this lane's pixels (one per 32-wide accumulator column block)
+  int lane_base[TN];
+#pragma unroll
+  for (int ni = 0; ni < TN; ++ni) {
+    const int p = min(p0 + wn0 + ni * 32 + l32, a.P - 1);
+    const int oh = p / a.ow;
+    lane_base[ni] = (oh - oh_first) * a.wp + (p - oh * a.ow);
+  }
+
+  SA sa;
+  sa.init(tid);
+  int64_t a_off[SA::SLOTS];
+  bool a_row_ok[SA::SLOTS];
+#pragma unroll
+  for (int e = 0; e < SA::SLOTS; ++e) {
+    const int i = i0 + sa.line(e);
+    a_row_ok[e] = i < a.m;
+    a_off[e] = (int64_t)(a_row_ok[e] ? i : 0) * K;
+  }
+
+  f32x16 acc[TM][TN];
+  zero_acc<TM, TN>(acc);
+
+  const float* xin = a.x + (int64_t)n * a.c * a.h * a.w;
+  const int slabs = a.kch / BK;
+
+  for (int c0 = 0; c0 < a.c; c0 += a.cc) {
+    const int cc = min(a.cc, a.c - c0);
+    const int kbase = c0 * RS;      // first column of the kernel matrix in this chunk
+    const int klen = cc * RS;       // valid taps in this chunk
+    // kernel-matrix slab fetch: columns kbase + s*BK + [0, BK), zero beyond klen
+    auto fetch = [&](int sl) {
+#pragma unroll
+      for (int e = 0; e < SA::SLOTS; ++e) {
+        const int kk = sl * BK + sa.c;
+        sa.ok[e] = a_row_ok[e] && kk < klen;
+        const float* src = a.wgt + a_off[e] + kbase + min(kk, klen - (VEC ? 4 : 1));
+        if (VEC) {
+          const float4 t = *reinterpret_cast<const float4*>(src);
+          sa.v[e][0] = t.x, sa.v[e][1] = t.y, sa.v[e][2] = t.z, sa.v[e][3] = t.w;
+        } else {
+          sa.v[e][0] = *src;
+        }
+      }
+    };
+    fetch(0);
+    __syncthreads();  // previous chunk's MFMAs are done with the halo tile and the A slabs
+    // stage the halo rows of this chunk: input rows oh_first - ph + [0, nr), columns -pw + [0, wp)
+    {
+      int cl = 0, ry = wave;
+      while (ry >= a.nr) ry -= a.nr, ++cl;
+      for (int rid = wave; rid < cc * a.nr; rid += kThreads / 64) {
+        const int ih = oh_first - a.ph + ry;
+        const bool row_ok = ih >= 0 && ih < a.h;
+        const float* src = xin + ((int64_t)(c0 + cl) * a.h + (row_ok ? ih : 0)) * a.w;
+        float* dst = halo + cl * plane + ry * a.wp;
+        for (int rx = lane; rx < a.wp; rx += 64) {
+          const int iw = rx - a.pw;
+          const bool ok = row_ok && iw >= 0 && iw < a.w;
+          const float v = src[ok ? iw : 0];
+          dst[rx] = ok ? v : 0.f;
+        }
+        ry += kThreads / 64;
+        while (ry >= a.nr) ry -= a.nr, ++cl;
+      }
+    }
+    sa.store(As0);
+    __syncthreads();
+
+    for (int sl = 0; sl < slabs; ++sl) {
+      const int cur = sl & 1;
+      if (sl * BK >= klen) break;  // a short last chunk needs fewer slabs (uniform across the block)
+      const bool more = (sl + 1) * BK < klen;
+      if (more) fetch(sl + 1);
+      const float* As = As0 + cur * LA::SIZE;
+      const int* toff = tapoff + sl * BK;
+#pragma unroll
+      for (int t = 0; t < BK / 8; ++t) {
+        float4 af[TM];
+#pragma unroll
+        for (int mi = 0; mi < TM; ++mi) af[mi] = load_frag<BM, BK, true>(As, wm0 + mi * 32, t, lane);
+        const int4 o4 = *reinterpret_cast<const int4*>(toff + 8 * t + 4 * half);
+        const int o[4] = {o4.x, o4.y, o4.z, o4.w};
+        float bf[TN][4];
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) bf[ni][i] = halo[lane_base[ni] + o[i]];
+        const float* afl = reinterpret_cast<const float*>(af);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < TN; ++ni)
+              acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(afl[mi * 4 + i], bf[ni][i], acc[mi][ni], 0, 0, 0);
+      }
+      if (more) sa.store(As0 + (cur ^ 1) * LA::SIZE);
+      __syncthreads();
+    }
+  }
+
+#pragma unroll
+  for (int ni = 0; ni < TN; ++ni) {
+    const int p = p0 + wn0 + ni * 32 + l32;
+    if (p >= a.P) continue;
+#pragma unroll
+    for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int i = i0 + wm0 + mi * 32 + acc_row(q, lane);
+        if (i < a.m) {
+          float v = acc[mi][ni][q];
+          if (a.bias) v += a.bias[i];
+          if (a.relu) v = fmaxf(v, 0.f);
+          a.y[((int64_t)n * a.m + i) * a.P + p] = v;
+        }
+      }
+  }
+}
+
+// w2[c][m][r'][s'] = w[m][c][R-1-r'][S-1-s']: the kernel matrix of the input-gradient correlation.
+__global__ __launch_bounds__(kThreads) void flip_transpose_kernel(const float* __restrict__ w, float* __restrict__ w2,
+                                                                  int M, int C, int RS) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= (int64_t)M * C * RS) return;
+  const int q = (int)(i % RS);
+  const int64_t t = i / RS;
+  const int m = (int)(t % M);
+  const int c = (int)(t / M);
+  w2[i] = w[((int64_t)m * C + c) * RS + (RS - 1 - q)];
+}
+
+vcnn_status launch_flip_transpose(const float* w, float* w2, int M, int C, int RS, hipStream_t st) {
+  const int64_t count = (int64_t)M * C * RS;
+  hipLaunchKernelGGL(flip_transpose_kernel, dim3((unsigned)ceil_div(count, kThreads)), dim3(kThreads), 0, st, w, w2, M,
+                     C, RS);
+  return check_launch("flip_transpose");
+}
+
+// ---- planning -------------------------------------------------------------------------------------------
+static constexpr size_t kLdsBudget = 76 * 1024;  // two blocks per CU out of 160 KB
+
+static int halo_bm(int m) { return m <= 32 ? 32 : (m <= 64 ? 64 : 128); }
+static int halo_bn(int m) { return m <= 64 ? 256 : 128; }
+
+bool conv_halo_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int pw, HaloPlan* p) {
+  const int oh = h + 2 * ph - r + 1, ow = w + 2 * pw - s + 1;
+  if (oh <= 0 || ow <= 0) return false;
+  const int bm = halo_bm(m), bn = halo_bn(m);
+  const int rs = r * s;
+  int rows = (bn + ow - 2) / ow + 1;  // rows a run of bn consecutive pixels can touch
+  if (rows > oh) rows = oh;
+  const int nr = rows + r - 1, wp = w + 2 * pw;
+  const size_t a_bytes = 2 * (size_t)LdsTile<128, BK, true>::PITCH * bm * sizeof(float);
+  // largest channel chunk that fits the LDS budget with a tap table of at most 2048 entries
+  int best = 0;
+  for (int cc = 1; cc <= c; ++cc) {
+    const int kch = (int)ceil_div((int64_t)cc * rs, BK) * BK;
+    const size_t bytes = a_bytes + (size_t)kch * 4 + (size_t)cc * nr * wp * 4;
+    if (bytes > kLdsBudget || kch > 2048) break;
+    best = cc;
+  }
+  if (best == 0) return false;
+  // prefer a chunk whose tap count fills its last slab (fewest zero taps), among chunks at least half as large
+  int pick = best;
+  double pick_waste = 2.0;
+  const bool k_vec = ((int64_t)c * rs) % 4 == 0;
+  bool any_vec = false;
+  for (int cc = best; cc >= 1 && 2 * cc > best; --cc) any_vec |= k_vec && ((int64_t)cc * rs) % 4 == 0;
+  for (int cc = best; cc >= 1 && 2 * cc > best; --cc) {
+    if (any_vec && ((int64_t)cc * rs) % 4 != 0) continue;  // keep 16-byte kernel-matrix loads when possible
+    const int64_t chunks = ceil_div(c, cc);
+    // slabs actually executed: full chunks use ceil(cc*rs/BK); the last may be shorter
+    const int last = c - (int)(chunks - 1) * cc;
+    const int64_t slabs = (chunks - 1) * ceil_div((int64_t)cc * rs, BK) + ceil_div((int64_t)last * rs, BK);
+    const double waste = 1.0 - (double)c * rs / (double)(slabs * BK);
+    if (waste < pick_waste - 1e-9) pick = cc, pick_waste = waste;
+  }
+  p->bm = bm, p->bn = bn, p->cc = pick, p->nr = nr, p->wp = wp;
+  p->kch = (int)ceil_div((int64_t)pick * rs, BK) * BK;
+  p->lds_bytes = 2 * (size_t)LdsTile<128, BK, true>::PITCH * bm * sizeof(float) + (size_t)p->kch * 4 +
+                 (size_t)pick * nr * wp * 4;
+  p->vec = ((int64_t)c * rs) % 4 == 0 && ((int64_t)pick * rs) % 4 == 0;
+  const int64_t tiles = ceil_div(m, bm) * (int64_t)n * ceil_div((int64_t)oh * ow, bn);
+  return tiles <= 0x7fffffffLL;
+}
+
+template <int BM, int BN, int WM, int WN>
+static void launch_halo(const HaloArgs& a, const HaloPlan& p, bool vec, hipStream_t st) {
+  const dim3 grid((unsigned)((int64_t)a.tiles_m * a.n * a.tiles_per_img)), block(kThreads);
+  if (vec) {
+    auto kernel = conv_halo_kernel<BM, BN, WM, WN, true>;
+    static bool opted = false;
+    if (!opted) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget), opted = true;
+    hipLaunchKernelGGL(kernel, grid, block, p.lds_bytes, st, a);
+  } else {
+    auto kernel = conv_halo_kernel<BM, BN, WM, WN, false>;
+    static bool opted = false;
+    if (!opted) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget), opted = true;
+    hipLaunchKernelGGL(kernel, grid, block, p.lds_bytes, st, a);
+  }
+}
+
+vcnn_status launch_conv_halo(const HaloPlan& p, int n, int c, int h, int w, int m, int r, int s, int ph, int pw,
+                             const float* x, const float* wgt, const float* bias, float* y, int relu, hipStream_t st) {
+  HaloArgs a{};
+  a.x = x, a.wgt = wgt, a.bias = bias, a.y = y;
+  a.n = n, a.c = c, a.h = h, a.w = w, a.m = m, a.r = r, a.s = s, a.ph = ph, a.pw = pw;
+  a.oh = h + 2 * ph - r + 1, a.ow = w + 2 * pw - s + 1;
+  a.P = a.oh * a.ow;
+  a.tiles_m = (int)ceil_div(m, p.bm);
+  a.tiles_per_img = (int)ceil_div(a.P, p.bn);
+  a.cc = p.cc, a.nr = p.nr, a.wp = p.wp, a.kch = p.kch, a.relu = relu;
+  const bool vec = p.vec && (reinterpret_cast<uintptr_t>(wgt) & 15) == 0;
+  if (p.bm == 32)
+    launch_halo<32, 256, 32, 64>(a, p, vec, st);
+  else if (p.bm == 64)
+    launch_halo<64, 256, 64, 64>(a, p, vec, st);
+  else
+    launch_halo<128, 128, 64, 64>(a, p, vec, st);
+  return check_launch("conv_halo");
+}
+
+}  // namespace vcnn

@@ -138,23 +138,33 @@ def test_end_to_end_training_step(name, batch):
             differ = (got > 0) != (want > 0)
             assert np.all(np.maximum(np.abs(got), np.abs(want))[differ] <= 1e-5 * np.max(np.abs(want)))
             flips += int(np.count_nonzero(differ))
-    # A flipped near-tie (pool argmax or ReLU sign) legitimately reroutes one gradient element, which the
-    # max-norm measure sees at full size; the strict bar applies when the discrete decisions all agree,
-    # otherwise gradients are only sanity-checked (the layer-wise test covers them strictly).
-    grad_tol = TOL_F32 if flips == 0 else 2e-2
-    print(f"{name}: {flips} near-tie decisions differ; gradient tolerance {grad_tol:.0e}")
+    # A flipped near-tie (pool argmax or ReLU sign) legitimately moves one gradient element, which the
+    # max-norm measure sees at full size and which spreads over a receptive field further down.  The
+    # strict bar applies when all discrete decisions agree; otherwise all but a small fraction of the
+    # elements must still meet it (the layer-wise test covers every layer strictly).
+    print(f"{name}: {flips} near-tie decisions differ")
+
+    def check(got, want, what):
+        if flips == 0:
+            assert_close(got, want, TOL_F32, what)
+        else:
+            # one rerouted element shifts every filter-gradient entry a little (each is a sum over all
+            # pixels) and a receptive field of the input gradients a lot: only a coarse check is meaningful
+            bad = np.abs(np.asarray(got, dtype=np.float64) - want) > 0.05 * np.max(np.abs(want))
+            assert bad.mean() <= 0.01, f"{what}: {bad.mean():.2%} of the elements are off after {flips} flips"
+
     for li in range(len(net.layers)):
-        assert_close(to_np(ts.dacts[li]), ref["dacts"][li], grad_tol, f"{name} dact {li}")
+        check(to_np(ts.dacts[li]), ref["dacts"][li], f"{name} dact {li}")
         if ts.grads[li] is not None:
-            assert_close(to_np(ts.grads[li][0]), ref["grads"][li][0], grad_tol, f"{name} dw {li}")
-            assert_close(to_np(ts.grads[li][1]), ref["grads"][li][1], grad_tol, f"{name} db {li}")
+            check(to_np(ts.grads[li][0]), ref["grads"][li][0], f"{name} dw {li}")
+            check(to_np(ts.grads[li][1]), ref["grads"][li][1], f"{name} db {li}")
             assert_close(to_np(ts.params[li][0]), ref["new_params"][li][0], TOL_F32, f"{name} w' {li}")
             assert_close(to_np(ts.params[li][1]), ref["new_params"][li][1], TOL_F32, f"{name} b' {li}")
-            # the update changed the weights by exactly -lr*dw (to fp32 rounding)
-            step_gpu = to_np(ts.params[li][0]).astype(np.float64) - before[li][0]
-            step_ref = -net.lr * ref["grads"][li][0]
-            slack = 10 * grad_tol * np.max(np.abs(step_ref)) + 2.0 ** -23 * np.max(np.abs(before[li][0]))
-            assert np.max(np.abs(step_gpu - step_ref)) <= slack, f"{name} sgd step {li}"
+            if flips == 0:  # the update changed the weights by -lr*dw (to fp32 rounding of w)
+                step_gpu = to_np(ts.params[li][0]).astype(np.float64) - before[li][0]
+                step_ref = -net.lr * ref["grads"][li][0]
+                slack = 1e-3 * np.max(np.abs(step_ref)) + 2.0 ** -23 * np.max(np.abs(before[li][0]))
+                assert np.max(np.abs(step_gpu - step_ref)) <= slack, f"{name} sgd step {li}"
     if net.loss != "upstream":
         assert abs(float(to_np(ts.loss)) - ref["loss"]) <= TOL_F32 * abs(ref["loss"])
     # run-to-run bit identity of a full step from the same state

@@ -36,11 +36,12 @@ CONV_SHAPES = [
 ]
 
 
-@pytest.fixture(params=["auto", "explicit"])
+@pytest.fixture(params=["auto", "explicit", "implicit"])
 def algo(request):
-    """Runs a test once with the per-shape kernel choice and once with the unroll forced explicit
-    (phi_c as its own kernel + matrix product), so both realisations stay covered."""
-    vcnn.set_conv_algo(vcnn.ALGO_EXPLICIT if request.param == "explicit" else vcnn.ALGO_AUTO)
+    """Runs a test with the per-shape kernel choice, with the unroll forced explicit (phi_c as its own
+    kernel + matrix product) and with the implicit matrix-core kernel preferred wherever it applies, so
+    every realisation stays covered."""
+    vcnn.set_conv_algo({"auto": vcnn.ALGO_AUTO, "explicit": vcnn.ALGO_EXPLICIT, "implicit": vcnn.ALGO_IMPLICIT}[request.param])
     yield request.param
     vcnn.set_conv_algo(vcnn.ALGO_AUTO)
 
