@@ -91,11 +91,12 @@ static bool halo_bwd_data_pays(const ConvGeom& g, const HaloPlan& hp) {
 
 // Which realisation a pass uses for a given shape.  The same decision drives the workspace query and
 // the launch, so the two always agree.
-enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER, PATH_HALO };
+enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER, PATH_HALO, PATH_HALO_FILTER };
 struct Plan {
   Path path;
   DirectGeom dg;
   HaloPlan hp;
+  HaloFilterPlan hfp;
   int split;        // channel slices (few-out), output-map group size (few-in) or batch slices (filter gradient)
   size_t partial_bytes;
   size_t workspace_bytes;
@@ -140,7 +141,13 @@ static Plan make_plan(const ConvGeom& g, int pass) {
       p.workspace_bytes = col_bytes(g);
     }
   } else {
-    if (allow_direct && direct_filter_grad_plan(g, &p.dg, &p.split, &p.partial_bytes)) {
+    if (allow_direct && g.k <= 4 && direct_filter_grad_plan(g, &p.dg, &p.split, &p.partial_bytes)) {
+      p.path = PATH_DIRECT_FILTER;
+      p.workspace_bytes = align256(p.partial_bytes);
+    } else if (allow_direct && (g.c > 4 || algo == VCNN_ALGO_IMPLICIT) && conv_halo_filter_plan(g, &p.hfp)) {
+      p.path = PATH_HALO_FILTER;
+      p.workspace_bytes = align256(p.hfp.partial_bytes);
+    } else if (allow_direct && direct_filter_grad_plan(g, &p.dg, &p.split, &p.partial_bytes)) {
       p.path = PATH_DIRECT_FILTER;
       p.workspace_bytes = align256(p.partial_bytes);
     } else {
@@ -263,6 +270,12 @@ vcnn_status vcnn_conv_bwd_filter(const vcnn_conv_desc* d, const void* x, const v
   if (plan.path == PATH_DIRECT_FILTER) {
     if (vcnn_status s = launch_direct_filter_grad(plan.dg, plan.split, (const float*)x, (const float*)dy, dw,
                                                   (float*)workspace, st))
+      return s;
+    if (dbias) return launch_bias_grad_f32(g, (const float*)dy, dbias, st);
+    return VCNN_OK;
+  }
+  if (plan.path == PATH_HALO_FILTER) {
+    if (vcnn_status s = launch_conv_halo_filter(plan.hfp, g, (const float*)x, (const float*)dy, dw, (float*)workspace, st))
       return s;
     if (dbias) return launch_bias_grad_f32(g, (const float*)dy, dbias, st);
     return VCNN_OK;

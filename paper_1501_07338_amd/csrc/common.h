@@ -90,6 +90,17 @@ struct HaloPlan {
 bool conv_halo_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int pw, HaloPlan* p);
 vcnn_status launch_conv_halo(const HaloPlan& p, int n, int c, int h, int w, int m, int r, int s, int ph, int pw,
                              const float* x, const float* wgt, const float* bias, float* y, int relu, hipStream_t st);
+struct HaloFilterPlan {
+  int bm, bnk;       // block tile: output maps x kernel-matrix columns
+  int bp;            // output pixels per staged run
+  int ccs, nr, wp;   // channels, rows and row pitch of the halo tile
+  int runs_per_img, runs_per_split, splits;
+  size_t lds_bytes, partial_bytes;
+  bool vec;
+};
+bool conv_halo_filter_plan(const ConvGeom& g, HaloFilterPlan* p);
+vcnn_status launch_conv_halo_filter(const HaloFilterPlan& p, const ConvGeom& g, const float* x, const float* dy,
+                                    float* dw, float* partial, hipStream_t st);
 vcnn_status launch_flip_transpose(const float* w, float* w2, int M, int C, int RS, hipStream_t st);
 
 // ---- pointwise.hip ------------------------------------------------------------------------------

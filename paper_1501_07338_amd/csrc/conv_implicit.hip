@@ -10,6 +10,8 @@
 // The same kernel computes the input gradient (phi_c^{-1} of the transposed product, evaluated in
 // gather form): dx is the correlation of dy with the flipped, channel-transposed kernels, which a small
 // kernel writes to the workspace first.
+#include <algorithm>
+
 #include "common.h"
 #include "mma_core.h"
 
@@ -293,6 +295,264 @@ vcnn_status launch_conv_halo(const HaloPlan& p, int n, int c, int h, int w, int 
   else
     launch_halo<128, 128, 64, 64>(a, p, vec, st);
   return check_launch("conv_halo");
+}
+
+}  // namespace vcnn
+
+// =========================================================================================================
+// Implicit-unroll filter gradient: dW[m][(c,r,s)] = sum_{n,pixel} dY[n][m][pixel] * xpad[n][c][pixel + (r,s)].
+// The product dY * phi_c(x)^T without phi_c(x): a block owns BM output maps x BNK columns of the kernel
+// matrix (a run of taps, possibly spanning several input channels) and walks over runs of BP output
+// pixels.  Per run it stages the input rows (with halo) of the channels it needs in LDS; dY streams
+// through double-buffered slabs as the A operand (contraction index = pixel), and the B operand is read
+// from the halo tile at tap_base(lane) + pixel_offset(step).  The contraction is split over blocks
+// (blockIdx.y); the partial products are added in a fixed order by a second kernel.
+// =========================================================================================================
+namespace vcnn {
+
+struct HaloFilterArgs {
+  const float* x;    // [n][c][h][w]
+  const float* dy;   // [n][m][oh][ow]
+  float* out;        // [splits][m][c*r*s]
+  int n, c, h, w, m, r, s, ph, pw, oh, ow, P;
+  int tiles_m;
+  int bp;            // pixels per run (multiple of BK)
+  int runs_per_img;
+  int runs_per_split;
+  int ccs;           // channels a block's column range can span
+  int nr, wp;
+};
+
+template <int BM, int BNK, int WM, int WN, bool VEC>
+__global__ __launch_bounds__(kThreads) void conv_halo_filter_kernel(HaloFilterArgs a) {
+  static_assert((BM / WM) * (BNK / WN) * 64 == kThreads, "four waves per block");
+  using LA = LdsTile<BM, BK, true>;
+  using SA = Stager<BM, BK, kThreads, true, VEC>;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  extern __shared__ float4 smem4[];
+  float* const As0 = reinterpret_cast<float*>(smem4);
+  int* const pixoff = reinterpret_cast<int*>(As0 + 2 * LA::SIZE);  // [bp]
+  float* const halo = As0 + 2 * LA::SIZE + a.bp;                   // [ccs][nr][wp]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int tm = blockIdx.x % a.tiles_m;
+  const int tk = blockIdx.x / a.tiles_m;
+  const int i0 = tm * BM, k0 = tk * BNK;
+  const int wm0 = (wave % (BM / WM)) * WM;
+  const int wn0 = (wave / (BM / WM)) * WN;
+  const int RS = a.r * a.s;
+  const int K = a.c * RS;
+  const int plane = a.nr * a.wp;
+  const int c_first = k0 / RS;
+
+  // this lane's kernel-matrix columns: offset of tap (c, r, s) inside the halo tile
+  int tap_base[TN];
+#pragma unroll
+  for (int ni = 0; ni < TN; ++ni) {
+    const int col = min(k0 + wn0 + ni * 32 + l32, K - 1);
+    const int c = col / RS;
+    const int q = col - c * RS;
+    const int r = q / a.s;
+    tap_base[ni] = (c - c_first) * plane + r * a.wp + (q - r * a.s);
+  }
+
+  SA sa;
+  sa.init(tid);
+
+  f32x16 acc[TM][TN];
+  zero_acc<TM, TN>(acc);
+
+  const int total_runs = a.n * a.runs_per_img;
+  const int run0 = blockIdx.y * a.runs_per_split;
+  const int run1 = min(total_runs, run0 + a.runs_per_split);
+  const int slabs_per_run = a.bp / BK;
+
+  for (int run = run0; run < run1; ++run) {
+    const int n = run / a.runs_per_img;
+    const int p0 = (run - n * a.runs_per_img) * a.bp;
+    const int plen = min(a.bp, a.P - p0);  // valid pixels in this run
+    const int oh_first = p0 / a.ow;
+    const float* dyn = a.dy + (int64_t)n * a.m * a.P + p0;
+    auto fetch = [&](int sl) {
+      const int pk = sl * BK + sa.c;  // pixel inside the run
+#pragma unroll
+      for (int e = 0; e < SA::SLOTS; ++e) {
+        const int m = i0 + sa.line(e);
+        sa.ok[e] = m < a.m && pk < plen;
+        const float* src = dyn + (int64_t)min(m, a.m - 1) * a.P + min(pk, plen - (VEC ? 4 : 1));
+        if (VEC) {
+          const float4 t = *reinterpret_cast<const float4*>(src);
+          sa.v[e][0] = t.x, sa.v[e][1] = t.y, sa.v[e][2] = t.z, sa.v[e][3] = t.w;
+        } else {
+          sa.v[e][0] = *src;
+        }
+      }
+    };
+    fetch(0);
+    __syncthreads();  // the previous run's MFMAs are done with the halo tile, the table and the slabs
+    for (int pk = tid; pk < a.bp; pk += kThreads) {
+      const int p = min(p0 + pk, a.P - 1);
+      const int oh = p / a.ow;
+      pixoff[pk] = (oh - oh_first) * a.wp + (p - oh * a.ow);
+    }
+    {
+      const float* xin = a.x + (int64_t)n * a.c * a.h * a.w;
+      int cl = 0, ry = wave;
+      while (ry >= a.nr) ry -= a.nr, ++cl;
+      for (int rid = wave; rid < a.ccs * a.nr; rid += kThreads / 64) {
+        const int ih = oh_first - a.ph + ry;
+        const bool row_ok = ih >= 0 && ih < a.h;
+        const int c = min(c_first + cl, a.c - 1);
+        const float* src = xin + ((int64_t)c * a.h + (row_ok ? ih : 0)) * a.w;
+        float* dst = halo + cl * plane + ry * a.wp;
+        for (int rx = lane; rx < a.wp; rx += 64) {
+          const int iw = rx - a.pw;
+          const bool ok = row_ok && iw >= 0 && iw < a.w;
+          const float v = src[ok ? iw : 0];
+          dst[rx] = ok ? v : 0.f;
+        }
+        ry += kThreads / 64;
+        while (ry >= a.nr) ry -= a.nr, ++cl;
+      }
+    }
+    sa.store(As0);
+    __syncthreads();
+
+    for (int sl = 0; sl < slabs_per_run; ++sl) {
+      const int cur = sl & 1;
+      if (sl * BK >= plen) break;
+      const bool more = (sl + 1) * BK < plen;
+      if (more) fetch(sl + 1);
+      const float* As = As0 + cur * LA::SIZE;
+      const int* poff = pixoff + sl * BK;
+#pragma unroll
+      for (int t = 0; t < BK / 8; ++t) {
+        float4 af[TM];
+#pragma unroll
+        for (int mi = 0; mi < TM; ++mi) af[mi] = load_frag<BM, BK, true>(As, wm0 + mi * 32, t, lane);
+        const int4 o4 = *reinterpret_cast<const int4*>(poff + 8 * t + 4 * half);
+        const int o[4] = {o4.x, o4.y, o4.z, o4.w};
+        float bf[TN][4];
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) bf[ni][i] = halo[tap_base[ni] + o[i]];
+        const float* afl = reinterpret_cast<const float*>(af);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < TN; ++ni)
+              acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(afl[mi * 4 + i], bf[ni][i], acc[mi][ni], 0, 0, 0);
+      }
+      if (more) sa.store(As0 + (cur ^ 1) * LA::SIZE);
+      __syncthreads();
+    }
+  }
+
+  float* dst = a.out + (int64_t)blockIdx.y * a.m * K;
+#pragma unroll
+  for (int ni = 0; ni < TN; ++ni) {
+    const int col = k0 + wn0 + ni * 32 + l32;
+    if (col >= K) continue;
+#pragma unroll
+    for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int m = i0 + wm0 + mi * 32 + acc_row(q, lane);
+        if (m < a.m) dst[(int64_t)m * K + col] = acc[mi][ni][q];
+      }
+  }
+}
+
+bool conv_halo_filter_plan(const ConvGeom& g, HaloFilterPlan* p) {
+  const int rs = g.r * g.s;
+  p->bm = g.M <= 32 ? 32 : (g.M <= 64 ? 64 : 128);
+  p->bnk = g.M <= 64 ? 256 : 128;
+  p->wp = g.w + 2 * g.pw;
+  // channels a run of bnk consecutive kernel-matrix columns can touch
+  p->ccs = (int)std::min<int64_t>(g.c, (p->bnk + rs - 2) / rs + 1);
+  const size_t a_bytes = 2 * (size_t)LdsTile<128, BK, true>::PITCH * p->bm * sizeof(float);
+  // longest pixel run (multiple of BK, at most 1024 and at most one sample) whose halo fits the budget
+  int best = 0;
+  for (int bp = BK; bp <= 1024; bp += BK) {
+    int rows = (bp + g.ow - 2) / g.ow + 1;
+    if (rows > g.oh) rows = g.oh;
+    const int nr = rows + g.r - 1;
+    const size_t bytes = a_bytes + (size_t)bp * 4 + (size_t)p->ccs * nr * p->wp * 4;
+    if (bytes > kLdsBudget) break;
+    best = bp;
+    if (bp >= g.P) break;
+  }
+  if (best == 0) return false;
+  p->bp = best;
+  int rows = (best + g.ow - 2) / g.ow + 1;
+  if (rows > g.oh) rows = g.oh;
+  p->nr = rows + g.r - 1;
+  p->lds_bytes = a_bytes + (size_t)best * 4 + (size_t)p->ccs * p->nr * p->wp * 4;
+  p->runs_per_img = (int)ceil_div(g.P, best);
+  const int64_t tiles = ceil_div(g.M, p->bm) * ceil_div(g.K, p->bnk);
+  const int64_t total_runs = (int64_t)g.n * p->runs_per_img;
+  int64_t want = ceil_div(1024, tiles);
+  if (want > total_runs) want = total_runs;
+  if (want < 1) want = 1;
+  p->runs_per_split = (int)ceil_div(total_runs, want);
+  p->splits = (int)ceil_div(total_runs, p->runs_per_split);
+  p->partial_bytes = p->splits > 1 ? (size_t)p->splits * g.M * g.K * sizeof(float) : 0;
+  p->vec = g.P % 4 == 0;
+  return tiles <= 0x7fffffffLL && p->splits <= 65535;
+}
+
+template <int BM, int BNK, int WM, int WN>
+static void launch_halo_filter(const HaloFilterArgs& a, const HaloFilterPlan& p, bool vec, int tiles, hipStream_t st) {
+  const dim3 grid((unsigned)tiles, (unsigned)p.splits), block(kThreads);
+  if (vec) {
+    auto kernel = conv_halo_filter_kernel<BM, BNK, WM, WN, true>;
+    static bool opted = false;
+    if (!opted) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget), opted = true;
+    hipLaunchKernelGGL(kernel, grid, block, p.lds_bytes, st, a);
+  } else {
+    auto kernel = conv_halo_filter_kernel<BM, BNK, WM, WN, false>;
+    static bool opted = false;
+    if (!opted) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget), opted = true;
+    hipLaunchKernelGGL(kernel, grid, block, p.lds_bytes, st, a);
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void sum_splits_kernel(const float* __restrict__ partial, float* __restrict__ out,
+                                                              int64_t count, int splits) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= count) return;
+  float acc = 0.f;
+  for (int s = 0; s < splits; ++s) acc += partial[(int64_t)s * count + i];
+  out[i] = acc;
+}
+
+vcnn_status launch_conv_halo_filter(const HaloFilterPlan& p, const ConvGeom& g, const float* x, const float* dy,
+                                    float* dw, float* partial, hipStream_t st) {
+  HaloFilterArgs a{};
+  a.x = x, a.dy = dy, a.out = p.splits > 1 ? partial : dw;
+  a.n = g.n, a.c = g.c, a.h = g.h, a.w = g.w, a.m = g.k, a.r = g.r, a.s = g.s, a.ph = g.ph, a.pw = g.pw;
+  a.oh = g.oh, a.ow = g.ow, a.P = (int)g.P;
+  a.tiles_m = (int)ceil_div(g.M, p.bm);
+  a.bp = p.bp, a.runs_per_img = p.runs_per_img, a.runs_per_split = p.runs_per_split;
+  a.ccs = p.ccs, a.nr = p.nr, a.wp = p.wp;
+  const int tiles = a.tiles_m * (int)ceil_div(g.K, p.bnk);
+  const bool vec = p.vec && (reinterpret_cast<uintptr_t>(dy) & 15) == 0;
+  if (p.bm == 32)
+    launch_halo_filter<32, 256, 32, 64>(a, p, vec, tiles, st);
+  else if (p.bm == 64)
+    launch_halo_filter<64, 256, 64, 64>(a, p, vec, tiles, st);
+  else
+    launch_halo_filter<128, 128, 64, 64>(a, p, vec, tiles, st);
+  if (vcnn_status s = check_launch("conv_halo_filter")) return s;
+  if (p.splits == 1) return VCNN_OK;
+  const int64_t count = g.M * g.K;
+  hipLaunchKernelGGL(sum_splits_kernel, dim3((unsigned)ceil_div(count, kThreads)), dim3(kThreads), 0, st, partial, dw,
+                     count, p.splits);
+  return check_launch("sum_splits");
 }
 
 }  // namespace vcnn

@@ -158,8 +158,8 @@ def test_end_to_end_training_step(name, batch):
         if ts.grads[li] is not None:
             check(to_np(ts.grads[li][0]), ref["grads"][li][0], f"{name} dw {li}")
             check(to_np(ts.grads[li][1]), ref["grads"][li][1], f"{name} db {li}")
-            assert_close(to_np(ts.params[li][0]), ref["new_params"][li][0], TOL_F32, f"{name} w' {li}")
-            assert_close(to_np(ts.params[li][1]), ref["new_params"][li][1], TOL_F32, f"{name} b' {li}")
+            check(to_np(ts.params[li][0]), ref["new_params"][li][0], f"{name} w' {li}")
+            check(to_np(ts.params[li][1]), ref["new_params"][li][1], f"{name} b' {li}")
             if flips == 0:  # the update changed the weights by -lr*dw (to fp32 rounding of w)
                 step_gpu = to_np(ts.params[li][0]).astype(np.float64) - before[li][0]
                 step_ref = -net.lr * ref["grads"][li][0]
