@@ -1,18 +1,21 @@
 #!/usr/bin/env python3
 """Benchmark of the vectorized CNN layer path on one MI355X.
 
-A "step" is one full training step (forward, cost, backward, SGD) of a synthetic network whose
-inputs and weights are already resident in HBM.  The headline line reports images/s on the small
-recognition CNN (workload cfg2); per-layer GFLOP/s of every convolution pass, the roofline figure of
-the dominant call, the other workloads and the CPU-oracle baseline ride along in the same JSON line.
+A "step" is one full training step (forward, cost, backward, SGD update) of a synthetic network whose
+inputs and weights are already resident in HBM; every arithmetic step runs in libvcnn's HIP kernels.
+The headline line reports images/s on the small recognition CNN (workload cfg2: every operator of
+the path - unrolled convolutions, ReLU, max pooling, fully connected layers, softmax cost - is in
+it).  The step is recorded once into a HIP graph and replayed, so that the launch-bound small layers
+are not dominated by host launch overhead; the eager (one C call per layer pass) rate is reported
+next to it.  Per-layer GFLOP/s of every convolution pass, the roofline figure of the dominant call,
+the other four workloads and the CPU-oracle baseline ride along in the same JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--others cfg3,cfg4,cfg5]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--others cfg1,cfg3,cfg4,cfg5]
 """
 from __future__ import annotations
 
 import argparse
 import json
-import os
 import sys
 import time
 from pathlib import Path
@@ -23,7 +26,16 @@ if str(ROOT) not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 MFMA_F32_PEAK_TFLOPS = 157.3
-MFMA_BF16_PEAK_TFLOPS = 2500.0
+WORKLOAD_TEXT = {
+    "cfg1": "cfg1: single conv block 8x1x28x28 -> conv5x5x6 -> ReLU -> maxpool2, fwd + bwd from an upstream gradient",
+    "cfg2": "cfg2: small recognition CNN, batch 128x1x28x28, conv5x5x20-pool-conv5x5x50-pool-fc500-fc10, "
+            "full training step (fwd + softmax-CE + bwd + SGD)",
+    "cfg3": "cfg3: colour recognition CNN, batch 128x3x32x32, three conv5x5 (32,32,64) + 3x3/2 pools + fc64 + fc10, "
+            "full training step",
+    "cfg4": "cfg4: denoising CNN, batch 64x1x64x64, conv9x9x64-conv5x5x32-conv5x5x1 'same', L2 loss, full training step",
+    "cfg5": "cfg5: deconvolution CNN, batch 16x1x184x184, conv121x1x38-conv1x121x38-conv16x16x512-conv1x1x512-conv8x8x1 "
+            "valid, L2 loss, full training step",
+}
 
 
 def conv_geom(net, li):
@@ -50,7 +62,22 @@ def time_calls(fn, iters, stream):
     return start.elapsed_time(stop) / iters
 
 
-def run_workload(name, steps, warmup, per_layer=True, layer_iters=10):
+def timed_steps(fn, steps, stream):
+    """Wall-clock and GPU-event time per step of `steps` calls of fn, synchronised on both sides."""
+    import torch
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(steps):
+        fn()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    return max(wall_ms, ev0.elapsed_time(ev1) / steps)
+
+
+def run_workload(name, steps, warmup, layer_iters=10):
     import torch
     from paper_1501_07338_amd import vcnn, workloads as wl
     from paper_1501_07338_amd.net import TrainStep
@@ -61,21 +88,14 @@ def run_workload(name, steps, warmup, per_layer=True, layer_iters=10):
     stream = torch.cuda.current_stream()
     for _ in range(warmup):
         ts.step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    ev0.record(stream)
-    for _ in range(steps):
-        ts.step()
-    ev1.record(stream)
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
-    gpu_ms = ev0.elapsed_time(ev1) / steps
-    ms = max(wall_ms, gpu_ms)
-    res = {"workload": name, "batch": net.batch, "ms_per_step": ms, "gpu_ms_per_step": gpu_ms,
-           "images_per_s": net.batch / (ms * 1e-3), "loss": float(ts.loss.item())}
-    if not per_layer:
-        return res, ts
+    eager_ms = timed_steps(ts.step, steps, stream)
+    graph = ts.capture()
+    for _ in range(warmup):
+        graph.replay()
+    graph_ms = timed_steps(graph.replay, steps, stream)
+    res = {"workload": name, "batch": net.batch, "ms_per_step": graph_ms, "ms_per_step_eager": eager_ms,
+           "images_per_s": net.batch / (graph_ms * 1e-3), "images_per_s_eager": net.batch / (eager_ms * 1e-3),
+           "loss_after_timed_steps": float(ts.loss.item())}
 
     layers = []
     conv_flops = conv_ms = 0.0
@@ -93,39 +113,48 @@ def run_workload(name, steps, warmup, per_layer=True, layer_iters=10):
             "bwd_filter": lambda: vcnn.conv_bwd_filter(d, a_in, dy, dw, db, ts.workspace),
             "bwd_data": lambda: vcnn.conv_bwd_data(d, w, dy, ts.dacts[li], ts.workspace),
         }
+        in_b = 4.0 * g["n"] * g["c"] * g["h"] * g["w"]
+        out_b = 4.0 * g["M"] * g["N"]
+        w_b = 4.0 * g["M"] * g["K"]
         for pname, fn in passes.items():
             t = time_calls(fn, layer_iters, stream)
-            in_b = 4.0 * g["n"] * g["c"] * g["h"] * g["w"]
-            out_b = 4.0 * g["M"] * g["N"]
-            w_b = 4.0 * g["M"] * g["K"]
             layers.append({"layer": f"conv{li}", "pass": pname, "M": g["M"], "K": g["K"], "N": g["N"], "ms": t,
-                           "gflops": flops / (t * 1e6), "pct_mfma_f32_peak": 100.0 * flops / (t * 1e9) / MFMA_F32_PEAK_TFLOPS,
-                           "implicit_bytes": in_b + out_b + w_b,
-                           "implicit_gbs": (in_b + out_b + w_b) / (t * 1e6)})
+                           "gflops": flops / (t * 1e6),
+                           "pct_mfma_f32_peak": 100.0 * flops / (t * 1e9) / MFMA_F32_PEAK_TFLOPS,
+                           "algorithmic_bytes": in_b + out_b + w_b, "gbs": (in_b + out_b + w_b) / (t * 1e6),
+                           "in_step": not (li == 0 and pname == "bwd_data")})
             if not (li == 0 and pname == "bwd_data"):
                 conv_flops += flops
                 conv_ms += t
     res["conv_layers"] = layers
     res["conv_gflops_fwd_bwd"] = conv_flops / (conv_ms * 1e6) if conv_ms else None
     res["conv_pct_mfma_f32_peak"] = 100.0 * res["conv_gflops_fwd_bwd"] / (MFMA_F32_PEAK_TFLOPS * 1e3) if conv_ms else None
-    return res, ts
+    res["roofline"] = dominant_roofline(res)
+    return res
 
 
 def dominant_roofline(res):
-    """Roofline record of the call that takes the most time in the step."""
-    layers = res.get("conv_layers") or []
+    """Roofline record of the convolution pass that takes the most time inside the step.  A pass whose
+    arithmetic intensity (flops over input + output + kernel bytes) is above the machine balance
+    (157.3 TFLOP/s over 8 TB/s) is priced against the fp32 matrix-core peak, else against HBM."""
+    layers = [l for l in res.get("conv_layers") or [] if l["in_step"]]
     if not layers:
         return None
     top = max(layers, key=lambda r: r["ms"])
     flops = 2.0 * top["M"] * top["K"] * top["N"]
-    ai = flops / top["implicit_bytes"]
-    if ai >= MFMA_F32_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS:  # above the machine balance: matrix-core bound
+    name = f"{res['workload']}.{top['layer']}.{top['pass']}"
+    if flops / top["algorithmic_bytes"] >= MFMA_F32_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS:
         ach = flops / (top["ms"] * 1e9)
-        return {"kernel": f"{top['layer']}.{top['pass']}", "bound": "mfma", "achieved": ach, "peak": MFMA_F32_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": ach / MFMA_F32_PEAK_TFLOPS, "traffic": None}
-    ach = top["implicit_bytes"] / (top["ms"] * 1e6)
-    return {"kernel": f"{top['layer']}.{top['pass']}", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
-            "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None}
+        return {"kernel": name, "bound": "mfma", "achieved": ach, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / MFMA_F32_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC.get(name)}
+    ach = top["algorithmic_bytes"] / (top["ms"] * 1e6)
+    return {"kernel": name, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(name)}
+
+
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/); filled in
+# from the committed summaries, None where no counter run covers the kernel.
+MEASURED_TRAFFIC: dict = {}
 
 
 def cpu_baseline(name, budget_s=20.0):
@@ -153,8 +182,8 @@ def cpu_baseline(name, budget_s=20.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--others", default="cfg1,cfg3,cfg4,cfg5", help="comma list of further workloads to report ('' for none)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
@@ -166,28 +195,26 @@ def main():
     from paper_1501_07338_amd import vcnn
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
-    vcnn.lib()
+    vcnn.lib()  # raises if the HIP library has not been built: there is no fallback path
 
-    main_res, _ = run_workload(args.workload, args.steps, args.warmup)
+    main_res = run_workload(args.workload, args.steps, args.warmup)
     others = {}
     for name in [s for s in args.others.split(",") if s and s != args.workload]:
-        k = max(3, min(args.steps, 10)) if name in ("cfg4", "cfg5") else args.steps
-        r, ts = run_workload(name, k, max(2, min(args.warmup, 3)), layer_iters=5 if name in ("cfg4", "cfg5") else 10)
-        r["roofline"] = dominant_roofline(r)
-        others[name] = r
-        del ts
+        big = name in ("cfg4", "cfg5")
+        others[name] = run_workload(name, max(3, min(args.steps, 20)) if big else args.steps,
+                                    max(2, min(args.warmup, 3)) if big else args.warmup, layer_iters=5 if big else 10)
         torch.cuda.empty_cache()
 
     out = {
-        "metric": "images/sec per training step (conv fwd+bwd GFLOP/s and % MFMA peak alongside)",
+        "metric": "images/sec per training step (conv fwd+bwd GFLOP/s and % of fp32 MFMA peak alongside)",
         "value": main_res["images_per_s"], "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: small recognition CNN, batch {main_res['batch']}, full training step "
-                               "(fwd + softmax-CE + bwd + SGD)" if args.workload == "cfg2" else args.workload},
+        "config": {"workload": WORKLOAD_TEXT.get(args.workload, args.workload), "launch": "one HIP-graph replay per step",
+                   "eager_ms_per_step": main_res["ms_per_step_eager"], "eager_images_per_s": main_res["images_per_s_eager"]},
         "conv_gflops_fwd_bwd": main_res.get("conv_gflops_fwd_bwd"),
         "conv_pct_mfma_f32_peak": main_res.get("conv_pct_mfma_f32_peak"),
-        "roofline": dominant_roofline(main_res),
+        "roofline": main_res["roofline"],
         "conv_layers": main_res.get("conv_layers"),
         "other_workloads": others,
     }

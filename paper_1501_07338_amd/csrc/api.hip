@@ -100,6 +100,7 @@ struct Plan {
   int split;        // channel slices (few-out), output-map group size (few-in) or batch slices (filter gradient)
   size_t partial_bytes;
   size_t workspace_bytes;
+  size_t bias_offset;  // filter-gradient pass: where the bias-gradient partial sums live in the workspace
 };
 
 static Plan make_plan(const ConvGeom& g, int pass) {
@@ -153,6 +154,10 @@ static Plan make_plan(const ConvGeom& g, int pass) {
     } else {
       p.workspace_bytes = col_bytes(g) + align256(bwd_filter_partial_bytes(g));
     }
+  }
+  if (pass == VCNN_PASS_BWD_FILTER) {
+    p.bias_offset = p.workspace_bytes;
+    p.workspace_bytes += align256(bias_grad_partial_bytes(g));
   }
   return p;
 }
@@ -271,20 +276,20 @@ vcnn_status vcnn_conv_bwd_filter(const vcnn_conv_desc* d, const void* x, const v
     if (vcnn_status s = launch_direct_filter_grad(plan.dg, plan.split, (const float*)x, (const float*)dy, dw,
                                                   (float*)workspace, st))
       return s;
-    if (dbias) return launch_bias_grad_f32(g, (const float*)dy, dbias, st);
+    if (dbias) return launch_bias_grad_f32(g, (const float*)dy, dbias, (float*)((char*)workspace + plan.bias_offset), st);
     return VCNN_OK;
   }
   if (plan.path == PATH_HALO_FILTER) {
     if (vcnn_status s = launch_conv_halo_filter(plan.hfp, g, (const float*)x, (const float*)dy, dw, (float*)workspace, st))
       return s;
-    if (dbias) return launch_bias_grad_f32(g, (const float*)dy, dbias, st);
+    if (dbias) return launch_bias_grad_f32(g, (const float*)dy, dbias, (float*)((char*)workspace + plan.bias_offset), st);
     return VCNN_OK;
   }
   float* col = (float*)workspace;
   float* partial = (float*)((char*)workspace + col_bytes(g));
   if (vcnn_status s = launch_im2col_f32(g, (const float*)x, col, st)) return s;
   if (vcnn_status s = launch_bwd_filter_gemm_f32(g, (const float*)dy, col, dw, partial, st)) return s;
-  if (dbias) return launch_bias_grad_f32(g, (const float*)dy, dbias, st);
+  if (dbias) return launch_bias_grad_f32(g, (const float*)dy, dbias, (float*)((char*)workspace + plan.bias_offset), st);
   return VCNN_OK;
 }
 

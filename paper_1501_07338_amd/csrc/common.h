@@ -104,7 +104,11 @@ vcnn_status launch_conv_halo_filter(const HaloFilterPlan& p, const ConvGeom& g, 
 vcnn_status launch_flip_transpose(const float* w, float* w2, int M, int C, int RS, hipStream_t st);
 
 // ---- pointwise.hip ------------------------------------------------------------------------------
-vcnn_status launch_bias_grad_f32(const ConvGeom& g, const float* dy, float* db, hipStream_t st);
+size_t bias_grad_partial_bytes(const ConvGeom& g);
+vcnn_status launch_bias_grad_f32(const ConvGeom& g, const float* dy, float* db, float* partial, hipStream_t st);
+// out[i] = act(bias[(i / plane) % maps] + sum_s partial[s][i]), slices added in ascending order (bias nullable)
+vcnn_status launch_sum_slices(const float* partial, const float* bias, float* out, int64_t count, int splits,
+                              int64_t plane, int maps, int relu, hipStream_t st);
 vcnn_status launch_relu_fwd_f32(size_t count, const float* x, float* y, hipStream_t st);
 vcnn_status launch_relu_bwd_f32(size_t count, const float* ref, const float* dy, float* dx, hipStream_t st);
 vcnn_status launch_pool_fwd_f32(const vcnn_pool_desc& d, int oh, int ow, const float* x, float* y, int32_t* argmax,

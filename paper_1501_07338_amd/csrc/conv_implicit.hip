@@ -521,15 +521,6 @@ static void launch_halo_filter(const HaloFilterArgs& a, const HaloFilterPlan& p,
   }
 }
 
-__global__ __launch_bounds__(kThreads) void sum_splits_kernel(const float* __restrict__ partial, float* __restrict__ out,
-                                                              int64_t count, int splits) {
-  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  if (i >= count) return;
-  float acc = 0.f;
-  for (int s = 0; s < splits; ++s) acc += partial[(int64_t)s * count + i];
-  out[i] = acc;
-}
-
 vcnn_status launch_conv_halo_filter(const HaloFilterPlan& p, const ConvGeom& g, const float* x, const float* dy,
                                     float* dw, float* partial, hipStream_t st) {
   HaloFilterArgs a{};
@@ -549,10 +540,7 @@ vcnn_status launch_conv_halo_filter(const HaloFilterPlan& p, const ConvGeom& g, 
     launch_halo_filter<128, 128, 64, 64>(a, p, vec, tiles, st);
   if (vcnn_status s = check_launch("conv_halo_filter")) return s;
   if (p.splits == 1) return VCNN_OK;
-  const int64_t count = g.M * g.K;
-  hipLaunchKernelGGL(sum_splits_kernel, dim3((unsigned)ceil_div(count, kThreads)), dim3(kThreads), 0, st, partial, dw,
-                     count, p.splits);
-  return check_launch("sum_splits");
+  return launch_sum_slices(partial, nullptr, dw, g.M * g.K, p.splits, 1, 1, 0, st);
 }
 
 }  // namespace vcnn

@@ -70,7 +70,7 @@ __device__ __forceinline__ void row_taps(const DirectGeom& g, const float* row, 
 
 // ---- few output maps (CO <= 4), any number of input channels -----------------------------------------
 // Block = (sample, band of output rows, slice of the input channels).  Partial sums over channel
-// slices go to `out` as [slice][n][co][oh][ow] when isplit > 1 and are combined by finish_partials.
+// slices go to `out` as [slice][n][co][oh][ow] when isplit > 1 and are combined by sum_slices_kernel.
 template <int CO>
 __global__ __launch_bounds__(kThreads) void direct_few_out_kernel(DirectGeom g, const float* __restrict__ in,
                                                                   const float* __restrict__ w,
@@ -129,18 +129,32 @@ __global__ __launch_bounds__(kThreads) void direct_few_out_kernel(DirectGeom g, 
   }
 }
 
-// out[idx] = act(bias[map(idx)] + sum_s partial[s][idx]), slices added in ascending order.
-__global__ __launch_bounds__(kThreads) void finish_partials_kernel(const float* __restrict__ partial,
-                                                                   const float* __restrict__ bias,
-                                                                   float* __restrict__ out, int64_t count, int splits,
-                                                                   int64_t plane, int maps, int relu) {
+// out[idx] = act(bias[map(idx)] + sum_s partial[s][idx]), slices added in ascending order with four
+// independent loads in flight.
+__global__ __launch_bounds__(kThreads) void sum_slices_kernel(const float* __restrict__ partial,
+                                                              const float* __restrict__ bias, float* __restrict__ out,
+                                                              int64_t count, int splits, int64_t plane, int maps,
+                                                              int relu) {
   const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   if (i >= count) return;
   float acc = 0.f;
-  for (int s = 0; s < splits; ++s) acc += partial[(int64_t)s * count + i];
+  int s = 0;
+  for (; s + 4 <= splits; s += 4) {
+    const float v0 = partial[(int64_t)s * count + i], v1 = partial[(int64_t)(s + 1) * count + i];
+    const float v2 = partial[(int64_t)(s + 2) * count + i], v3 = partial[(int64_t)(s + 3) * count + i];
+    acc = (((acc + v0) + v1) + v2) + v3;
+  }
+  for (; s < splits; ++s) acc += partial[(int64_t)s * count + i];
   if (bias) acc += bias[(i / plane) % maps];
   if (relu) acc = fmaxf(acc, 0.f);
   out[i] = acc;
+}
+
+vcnn_status launch_sum_slices(const float* partial, const float* bias, float* out, int64_t count, int splits,
+                              int64_t plane, int maps, int relu, hipStream_t st) {
+  hipLaunchKernelGGL(sum_slices_kernel, dim3((unsigned)ceil_div(count, kThreads)), dim3(kThreads), 0, st, partial, bias,
+                     out, count, splits, plane, maps, relu);
+  return check_launch("sum_slices");
 }
 
 // ---- few input channels (CI <= 4), any number of output maps -----------------------------------------
@@ -267,10 +281,8 @@ vcnn_status launch_direct_few_out(const DirectGeom& g, int isplit, const float* 
   }
   if (vcnn_status s = check_launch("direct_few_out")) return s;
   if (isplit == 1) return VCNN_OK;
-  const int64_t count = (int64_t)g.n * g.co * g.oh * g.ow;
-  hipLaunchKernelGGL(finish_partials_kernel, dim3((unsigned)ceil_div(count, kThreads)), block, 0, st, partial, bias, out,
-                     count, isplit, (int64_t)g.oh * g.ow, g.co, relu);
-  return check_launch("finish_partials");
+  return launch_sum_slices(partial, bias, out, (int64_t)g.n * g.co * g.oh * g.ow, isplit, (int64_t)g.oh * g.ow, g.co, relu,
+                           st);
 }
 
 bool direct_few_in_plan(DirectGeom* g, int* ogroup) {
@@ -418,10 +430,7 @@ vcnn_status launch_direct_filter_grad(const DirectGeom& g, int slices, const flo
                      tap_blocks, per);
   if (vcnn_status s = check_launch("direct_filter_grad")) return s;
   if (slices == 1) return VCNN_OK;
-  const int64_t count = (int64_t)g.co * g.ci * g.r * g.s;
-  hipLaunchKernelGGL(finish_partials_kernel, dim3((unsigned)ceil_div(count, kThreads)), dim3(kThreads), 0, st, partial,
-                     (const float*)nullptr, dw, count, slices, (int64_t)1, 1, 0);
-  return check_launch("finish_partials");
+  return launch_sum_slices(partial, nullptr, dw, (int64_t)g.co * g.ci * g.r * g.s, slices, 1, 1, 0, st);
 }
 
 }  // namespace vcnn

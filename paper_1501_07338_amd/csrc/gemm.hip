@@ -214,13 +214,15 @@ vcnn_status launch_gemm_f32(const GemmArgs& a, hipStream_t st) {
   else
     bv = aligned16(a.B) && a.b_sj == 1 && a.b_sk % 4 == 0 && a.N % 4 == 0 &&
          (a.b_P == 0 || (a.b_P % 4 == 0 && a.b_simg % 4 == 0));
-  static const int tune_bk = getenv("VCNN_TUNE_BK") ? atoi(getenv("VCNN_TUNE_BK")) : 32;
-  if (a.M <= 32)
+  // Small products (the fully connected layers at batch 128) would fill only a handful of large
+  // tiles; 64x64 tiles spread them over more compute units.
+  const int64_t big_tiles = ceil_div(a.M, 128) * ceil_div(a.N, 128);
+  if (a.M > 32 && a.N <= 4096 && big_tiles < 128)
+    launch_cfg<64, 64, 32, 32, 32>(a, a_kc, b_kc, av, bv, st);
+  else if (a.M <= 32)
     launch_cfg<32, 256, 32, 32, 64>(a, a_kc, b_kc, av, bv, st);
   else if (a.M <= 64)
     launch_cfg<64, 256, 32, 64, 64>(a, a_kc, b_kc, av, bv, st);
-  else if (tune_bk == 16)
-    launch_cfg<128, 128, 16, 64, 64>(a, a_kc, b_kc, av, bv, st);
   else
     launch_cfg<128, 128, 32, 64, 64>(a, a_kc, b_kc, av, bv, st);
   return check_launch("gemm_f32");
@@ -343,15 +345,6 @@ __global__ __launch_bounds__(kThreads) void bwd_filter_f32_kernel(ConvGeom g, co
   }
 }
 
-__global__ __launch_bounds__(kThreads) void sum_partials_kernel(const float* __restrict__ partial,
-                                                                float* __restrict__ out, int64_t count, int splits) {
-  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  if (i >= count) return;
-  float acc = 0.f;
-  for (int s = 0; s < splits; ++s) acc += partial[(int64_t)s * count + i];
-  out[i] = acc;
-}
-
 static constexpr int kBfBK = 32;
 static int bwd_filter_bm(const ConvGeom& g) { return g.M <= 32 ? 32 : (g.M <= 64 ? 64 : 128); }
 static int bwd_filter_bn(const ConvGeom&) { return 128; }
@@ -410,10 +403,7 @@ vcnn_status launch_bwd_filter_gemm_f32(const ConvGeom& g, const float* dy, const
     launch_bf<128, 128, 64, 64>(g, dy, col, out, tiles_m, chunk, grid, vec, st);
   vcnn_status s = check_launch("bwd_filter_f32");
   if (s != VCNN_OK || splits == 1) return s;
-  const int64_t count = g.M * g.K;
-  hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)ceil_div(count, kThreads)), dim3(kThreads), 0, st, partial, dw,
-                     count, splits);
-  return check_launch("sum_partials");
+  return launch_sum_slices(partial, nullptr, dw, g.M * g.K, splits, 1, 1, 0, st);
 }
 
 }  // namespace vcnn

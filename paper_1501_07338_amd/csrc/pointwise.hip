@@ -143,23 +143,60 @@ __device__ __forceinline__ float block_sum(float v, float* sm) {
   return r;
 }
 
-// db[m] = sum over samples and positions of dy[n][m][p]: one block per output map.
-__global__ __launch_bounds__(kThreads) void bias_grad_f32_kernel(int n, int M, int64_t P, const float* __restrict__ dy,
-                                                                 float* __restrict__ db) {
+// db[m] = sum over samples and positions of dy[n][m][p].  Stage 1: block (m, slice) sums the samples of
+// its slice, four independent loads in flight per thread, then the fixed block tree; stage 2 adds the
+// slices in ascending order.  With one slice stage 1 writes db directly.
+__global__ __launch_bounds__(kThreads) void bias_grad_f32_kernel(int n, int M, int64_t P, int per_slice,
+                                                                 const float* __restrict__ dy, float* __restrict__ out) {
   __shared__ float sm[kThreads];
-  const int m = blockIdx.x;
-  float acc = 0.f;
-  for (int i = 0; i < n; ++i) {
+  const int m = blockIdx.x, slice = blockIdx.y;
+  const int n0 = slice * per_slice, n1 = min(n, n0 + per_slice);
+  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+  for (int i = n0; i < n1; ++i) {
     const float* row = dy + ((int64_t)i * M + m) * P;
-    for (int64_t p = threadIdx.x; p < P; p += kThreads) acc += row[p];
+    int64_t p = threadIdx.x;
+    for (; p + 3 * kThreads < P; p += 4 * kThreads) {
+      const float v0 = row[p], v1 = row[p + kThreads], v2 = row[p + 2 * kThreads], v3 = row[p + 3 * kThreads];
+      a0 += v0, a1 += v1, a2 += v2, a3 += v3;
+    }
+    for (; p < P; p += kThreads) a0 += row[p];
   }
-  const float total = block_sum(acc, sm);
-  if (threadIdx.x == 0) db[m] = total;
+  const float total = block_sum((a0 + a1) + (a2 + a3), sm);
+  if (threadIdx.x == 0) out[(int64_t)slice * M + m] = total;
 }
 
-vcnn_status launch_bias_grad_f32(const ConvGeom& g, const float* dy, float* db, hipStream_t st) {
-  hipLaunchKernelGGL(bias_grad_f32_kernel, dim3((unsigned)g.M), dim3(kThreads), 0, st, g.n, (int)g.M, g.P, dy, db);
-  return check_launch("bias_grad_f32");
+__global__ __launch_bounds__(kThreads) void bias_grad_finish_kernel(int M, int slices, const float* __restrict__ part,
+                                                                    float* __restrict__ db) {
+  const int m = blockIdx.x * kThreads + threadIdx.x;
+  if (m >= M) return;
+  float acc = 0.f;
+  for (int s = 0; s < slices; ++s) acc += part[(int64_t)s * M + m];
+  db[m] = acc;
+}
+
+int bias_grad_slices(const ConvGeom& g) {
+  int64_t s = ceil_div(512, g.M);
+  if (s > g.n) s = g.n;
+  return (int)(s < 1 ? 1 : s);
+}
+
+size_t bias_grad_partial_bytes(const ConvGeom& g) {
+  const int s = bias_grad_slices(g);
+  return s > 1 ? (size_t)s * g.M * sizeof(float) : 0;
+}
+
+vcnn_status launch_bias_grad_f32(const ConvGeom& g, const float* dy, float* db, float* partial, hipStream_t st) {
+  const int want = bias_grad_slices(g);
+  const int per = (int)ceil_div(g.n, want);
+  const int slices = (int)ceil_div(g.n, per);
+  float* out = slices > 1 ? partial : db;
+  hipLaunchKernelGGL(bias_grad_f32_kernel, dim3((unsigned)g.M, (unsigned)slices), dim3(kThreads), 0, st, g.n, (int)g.M,
+                     g.P, per, dy, out);
+  if (vcnn_status s = check_launch("bias_grad_f32")) return s;
+  if (slices == 1) return VCNN_OK;
+  hipLaunchKernelGGL(bias_grad_finish_kernel, dim3((unsigned)ceil_div(g.M, kThreads)), dim3(kThreads), 0, st, (int)g.M,
+                     slices, partial, db);
+  return check_launch("bias_grad_finish");
 }
 
 // out[c] = sum_r a[r][c]  (fully connected bias gradient): one thread per column, rows in order.
@@ -168,7 +205,13 @@ __global__ __launch_bounds__(kThreads) void col_sum_f32_kernel(int rows, int col
   const int c = blockIdx.x * kThreads + threadIdx.x;
   if (c >= cols) return;
   float acc = 0.f;
-  for (int r = 0; r < rows; ++r) acc += a[(int64_t)r * cols + c];
+  int r = 0;
+  for (; r + 4 <= rows; r += 4) {  // four independent loads in flight, added in ascending order
+    const float v0 = a[(int64_t)r * cols + c], v1 = a[(int64_t)(r + 1) * cols + c];
+    const float v2 = a[(int64_t)(r + 2) * cols + c], v3 = a[(int64_t)(r + 3) * cols + c];
+    acc = (((acc + v0) + v1) + v2) + v3;
+  }
+  for (; r < rows; ++r) acc += a[(int64_t)r * cols + c];
   out[c] = acc;
 }
 

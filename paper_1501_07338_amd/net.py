@@ -118,3 +118,15 @@ class TrainStep:
         self.cost(stream)
         self.backward(stream)
         self.update(stream)
+
+    # ---- HIP graph ---------------------------------------------------------------------------------
+    def capture(self):
+        """Records one full step (forward, cost, backward, SGD) into a HIP graph and returns the
+        graph; `graph.replay()` then re-issues the whole launch sequence with one call.  The step
+        is run eagerly once first so that one-time kernel attribute set-up happens outside the capture."""
+        self.step()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.step()
+        return graph

@@ -174,3 +174,29 @@ def test_end_to_end_training_step(name, batch):
         if ts.grads[li] is not None:
             np.testing.assert_array_equal(to_np(ts.grads[li][0]), to_np(ts2.grads[li][0]))
         np.testing.assert_array_equal(to_np(ts.dacts[li]), to_np(ts2.dacts[li]))
+
+
+@pytest.mark.parametrize("name,batch", [("cfg2", 32), ("cfg3", 16)])
+def test_hip_graph_replay_matches_eager(name, batch):
+    """The benchmark replays a recorded step; every replay must leave exactly the state the eager
+    call sequence leaves, with other work and synchronisations between the replays."""
+    net = wl.make_net(name, batch)
+    inputs, params = wl.make_inputs(net), wl.make_params(net)
+    eager = TrainStep(net, params, inputs, device=DEV)
+    graphed = TrainStep(net, params, inputs, device=DEV)
+    graph = graphed.capture()  # runs one eager step, then records (and thereby runs) nothing more
+    eager.step()
+    torch.cuda.synchronize()
+    for replay in range(4):
+        eager.step()
+        graph.replay()
+        torch.cuda.synchronize()
+        scratch = torch.randn(1 << 16, device=DEV).sum().item()  # unrelated eager work between replays
+        assert np.isfinite(scratch)
+        for li in range(len(net.layers)):
+            if eager.grads[li] is not None:
+                np.testing.assert_array_equal(to_np(graphed.grads[li][0]), to_np(eager.grads[li][0]),
+                                              err_msg=f"replay {replay} dw {li}")
+                np.testing.assert_array_equal(to_np(graphed.params[li][0]), to_np(eager.params[li][0]),
+                                              err_msg=f"replay {replay} w {li}")
+        assert float(to_np(graphed.loss)) == float(to_np(eager.loss))
