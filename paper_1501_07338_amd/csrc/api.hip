@@ -56,9 +56,8 @@ static vcnn_status make_geom(const vcnn_conv_desc* d, ConvGeom* g) {
   return VCNN_OK;
 }
 
-static vcnn_status need_f32(int32_t dtype, const char* what) {
-  if (dtype == VCNN_F32) return VCNN_OK;
-  if (dtype == VCNN_BF16) return fail(VCNN_ERR_UNSUPPORTED, "%s: the bfloat16 variant is not built", what);
+static vcnn_status check_dtype(int32_t dtype, const char* what) {
+  if (dtype == VCNN_F32 || dtype == VCNN_BF16) return VCNN_OK;
   return fail(VCNN_ERR_UNSUPPORTED, "%s: unknown dtype %d", what, dtype);
 }
 
@@ -213,16 +212,14 @@ vcnn_status vcnn_im2col(const vcnn_conv_desc* d, const void* x, void* col, void*
   ConvGeom g;
   if (vcnn_status s = make_geom(d, &g)) return s;
   if (!x || !col) return fail(VCNN_ERR_NULL, "im2col: NULL tensor");
-  if (vcnn_status s = need_f32(d->dtype, "im2col")) return s;
-  return launch_im2col_f32(g, (const float*)x, (float*)col, (hipStream_t)stream);
+  return launch_im2col(g, d->dtype, x, col, (hipStream_t)stream);
 }
 
 vcnn_status vcnn_col2im(const vcnn_conv_desc* d, const float* col, void* dx, void* stream) {
   ConvGeom g;
   if (vcnn_status s = make_geom(d, &g)) return s;
   if (!col || !dx) return fail(VCNN_ERR_NULL, "col2im: NULL tensor");
-  if (vcnn_status s = need_f32(d->dtype, "col2im")) return s;
-  return launch_col2im_f32(g, col, (float*)dx, (hipStream_t)stream);
+  return launch_col2im(g, d->dtype, col, dx, (hipStream_t)stream);
 }
 
 vcnn_status vcnn_conv_fwd(const vcnn_conv_desc* d, const void* x, const void* w, const float* bias, void* y,
@@ -230,34 +227,31 @@ vcnn_status vcnn_conv_fwd(const vcnn_conv_desc* d, const void* x, const void* w,
   ConvGeom g;
   if (vcnn_status s = make_geom(d, &g)) return s;
   if (!x || !w || !y) return fail(VCNN_ERR_NULL, "conv_fwd: NULL tensor");
-  if (vcnn_status s = need_f32(d->dtype, "conv_fwd")) return s;
   const Plan plan = make_plan(g, VCNN_PASS_FWD);
   if (vcnn_status s = check_ws(workspace, workspace_bytes, plan.workspace_bytes, "conv_fwd")) return s;
   hipStream_t st = (hipStream_t)stream;
   const int relu = d->act == VCNN_ACT_RELU;
+  const int dt = d->dtype;
   if (plan.path == PATH_FEW_OUT)
-    return launch_direct_few_out(plan.dg, plan.split, (const float*)x, (const float*)w, bias, (float*)y,
-                                 (float*)workspace, relu, st);
-  if (plan.path == PATH_FEW_IN)
-    return launch_direct_few_in(plan.dg, plan.split, (const float*)x, (const float*)w, bias, (float*)y, relu, st);
+    return launch_direct_few_out(plan.dg, dt, plan.split, x, w, bias, y, (float*)workspace, relu, st);
+  if (plan.path == PATH_FEW_IN) return launch_direct_few_in(plan.dg, dt, plan.split, x, w, bias, y, relu, st);
   if (plan.path == PATH_HALO)
-    return launch_conv_halo(plan.hp, g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, (const float*)x, (const float*)w,
-                            bias, (float*)y, relu, st);
+    return launch_conv_halo(plan.hp, dt, g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, x, w, bias, y, relu, st);
 
   GemmArgs a{};
-  a.A = (const float*)w, a.C = (float*)y, a.bias = bias;
+  a.A = w, a.C = y, a.bias = bias;
+  a.in_dtype = dt, a.out_dtype = dt;
   a.M = (int)g.M, a.N = (int)g.N, a.K = (int)g.K;
   a.a_si = g.K, a.a_sk = 1;
   a.c_si = g.P, a.c_sj = 1, a.c_P = (int)g.P, a.c_simg = g.M * g.P;
-  a.relu = d->act == VCNN_ACT_RELU;
+  a.relu = relu;
   if (plan.path == PATH_POINTWISE) {
     // patch matrix == input: B(k, j) = x[n][k][p]
-    a.B = (const float*)x;
+    a.B = x;
     a.b_sk = g.P, a.b_sj = 1, a.b_P = (int)g.P, a.b_simg = g.K * g.P;
   } else {
-    float* col = (float*)workspace;
-    if (vcnn_status s = launch_im2col_f32(g, (const float*)x, col, st)) return s;
-    a.B = col;
+    if (vcnn_status s = launch_im2col(g, dt, x, workspace, st)) return s;
+    a.B = workspace;
     a.b_sk = g.N, a.b_sj = 1, a.b_P = 0, a.b_simg = 0;
   }
   return launch_gemm_f32(a, st);
@@ -268,28 +262,21 @@ vcnn_status vcnn_conv_bwd_filter(const vcnn_conv_desc* d, const void* x, const v
   ConvGeom g;
   if (vcnn_status s = make_geom(d, &g)) return s;
   if (!x || !dy || !dw) return fail(VCNN_ERR_NULL, "conv_bwd_filter: NULL tensor");
-  if (vcnn_status s = need_f32(d->dtype, "conv_bwd_filter")) return s;
   const Plan plan = make_plan(g, VCNN_PASS_BWD_FILTER);
   if (vcnn_status s = check_ws(workspace, workspace_bytes, plan.workspace_bytes, "conv_bwd_filter")) return s;
   hipStream_t st = (hipStream_t)stream;
+  const int dt = d->dtype;
+  float* bias_partial = (float*)((char*)workspace + plan.bias_offset);
   if (plan.path == PATH_DIRECT_FILTER) {
-    if (vcnn_status s = launch_direct_filter_grad(plan.dg, plan.split, (const float*)x, (const float*)dy, dw,
-                                                  (float*)workspace, st))
-      return s;
-    if (dbias) return launch_bias_grad_f32(g, (const float*)dy, dbias, (float*)((char*)workspace + plan.bias_offset), st);
-    return VCNN_OK;
+    if (vcnn_status s = launch_direct_filter_grad(plan.dg, dt, plan.split, x, dy, dw, (float*)workspace, st)) return s;
+  } else if (plan.path == PATH_HALO_FILTER) {
+    if (vcnn_status s = launch_conv_halo_filter(plan.hfp, dt, g, x, dy, dw, (float*)workspace, st)) return s;
+  } else {
+    float* partial = (float*)((char*)workspace + col_bytes(g));
+    if (vcnn_status s = launch_im2col(g, dt, x, workspace, st)) return s;
+    if (vcnn_status s = launch_bwd_filter_gemm_f32(g, dt, dy, workspace, dw, partial, st)) return s;
   }
-  if (plan.path == PATH_HALO_FILTER) {
-    if (vcnn_status s = launch_conv_halo_filter(plan.hfp, g, (const float*)x, (const float*)dy, dw, (float*)workspace, st))
-      return s;
-    if (dbias) return launch_bias_grad_f32(g, (const float*)dy, dbias, (float*)((char*)workspace + plan.bias_offset), st);
-    return VCNN_OK;
-  }
-  float* col = (float*)workspace;
-  float* partial = (float*)((char*)workspace + col_bytes(g));
-  if (vcnn_status s = launch_im2col_f32(g, (const float*)x, col, st)) return s;
-  if (vcnn_status s = launch_bwd_filter_gemm_f32(g, (const float*)dy, col, dw, partial, st)) return s;
-  if (dbias) return launch_bias_grad_f32(g, (const float*)dy, dbias, (float*)((char*)workspace + plan.bias_offset), st);
+  if (dbias) return launch_bias_grad(g, dt, dy, dbias, bias_partial, st);
   return VCNN_OK;
 }
 
@@ -298,38 +285,36 @@ vcnn_status vcnn_conv_bwd_data(const vcnn_conv_desc* d, const void* w, const voi
   ConvGeom g;
   if (vcnn_status s = make_geom(d, &g)) return s;
   if (!w || !dy || !dx) return fail(VCNN_ERR_NULL, "conv_bwd_data: NULL tensor");
-  if (vcnn_status s = need_f32(d->dtype, "conv_bwd_data")) return s;
   const Plan plan = make_plan(g, VCNN_PASS_BWD_DATA);
   if (vcnn_status s = check_ws(workspace, workspace_bytes, plan.workspace_bytes, "conv_bwd_data")) return s;
   hipStream_t st = (hipStream_t)stream;
+  const int dt = d->dtype;
   if (plan.path == PATH_FEW_OUT)
-    return launch_direct_few_out(plan.dg, plan.split, (const float*)dy, (const float*)w, nullptr, (float*)dx,
-                                 (float*)workspace, 0, st);
-  if (plan.path == PATH_FEW_IN)
-    return launch_direct_few_in(plan.dg, plan.split, (const float*)dy, (const float*)w, nullptr, (float*)dx, 0, st);
+    return launch_direct_few_out(plan.dg, dt, plan.split, dy, w, nullptr, dx, (float*)workspace, 0, st);
+  if (plan.path == PATH_FEW_IN) return launch_direct_few_in(plan.dg, dt, plan.split, dy, w, nullptr, dx, 0, st);
   if (plan.path == PATH_HALO) {
-    float* w2 = (float*)workspace;
-    if (vcnn_status s = launch_flip_transpose((const float*)w, w2, g.k, g.c, g.r * g.s, st)) return s;
-    return launch_conv_halo(plan.hp, g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw,
-                            (const float*)dy, w2, nullptr, (float*)dx, 0, st);
+    if (vcnn_status s = launch_flip_transpose(dt, w, workspace, g.k, g.c, g.r * g.s, st)) return s;
+    return launch_conv_halo(plan.hp, dt, g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, dy,
+                            workspace, nullptr, dx, 0, st);
   }
-  float* dcol = (float*)workspace;
   // dcol[k][j] = sum_m W[m][k] * dY(m, j)
   GemmArgs a{};
-  a.A = (const float*)w, a.B = (const float*)dy, a.C = dcol, a.bias = nullptr;
+  a.A = w, a.B = dy, a.bias = nullptr;
+  a.in_dtype = dt;
   a.M = (int)g.K, a.N = (int)g.N, a.K = (int)g.M;
   a.a_si = 1, a.a_sk = g.K;
   a.b_sk = g.P, a.b_sj = 1, a.b_P = (int)g.P, a.b_simg = g.M * g.P;
   a.relu = 0;
   if (plan.path == PATH_POINTWISE) {
     // phi_c^{-1} is the identity per sample: store the product straight into dx[n][c][p].
-    a.C = (float*)dx;
+    a.C = dx, a.out_dtype = dt;
     a.c_si = g.P, a.c_sj = 1, a.c_P = (int)g.P, a.c_simg = g.K * g.P;
     return launch_gemm_f32(a, st);
   }
+  a.C = workspace, a.out_dtype = VCNN_F32;  // the patch-matrix gradient is kept in float
   a.c_si = g.N, a.c_sj = 1, a.c_P = 0, a.c_simg = 0;
   if (vcnn_status s = launch_gemm_f32(a, st)) return s;
-  return launch_col2im_f32(g, dcol, (float*)dx, st);
+  return launch_col2im(g, dt, (const float*)workspace, dx, st);
 }
 
 static vcnn_status check_pool(const vcnn_pool_desc* d, int* oh, int* ow) {
@@ -340,6 +325,7 @@ static vcnn_status check_pool(const vcnn_pool_desc* d, int* oh, int* ow) {
   if (d->win_h > d->h || d->win_w > d->w)
     return fail(VCNN_ERR_SHAPE, "pool: window %dx%d larger than input %dx%d", d->win_h, d->win_w, d->h, d->w);
   if ((int64_t)d->h * d->w > 0x7fffffffLL) return fail(VCNN_ERR_UNSUPPORTED, "pool: plane too large for int32 indices");
+  if (vcnn_status s = check_dtype(d->dtype, "pool")) return s;
   *oh = (d->h - d->win_h) / d->stride_h + 1;
   *ow = (d->w - d->win_w) / d->stride_w + 1;
   return VCNN_OK;
@@ -357,33 +343,31 @@ vcnn_status vcnn_pool_fwd(const vcnn_pool_desc* d, const void* x, void* y, int32
   int oh, ow;
   if (vcnn_status s = check_pool(d, &oh, &ow)) return s;
   if (!x || !y || !argmax) return fail(VCNN_ERR_NULL, "pool_fwd: NULL tensor");
-  if (vcnn_status s = need_f32(d->dtype, "pool_fwd")) return s;
-  return launch_pool_fwd_f32(*d, oh, ow, (const float*)x, (float*)y, argmax, (hipStream_t)stream);
+  return launch_pool_fwd(*d, oh, ow, x, y, argmax, (hipStream_t)stream);
 }
 
 vcnn_status vcnn_pool_bwd(const vcnn_pool_desc* d, const void* dy, const int32_t* argmax, void* dx, void* stream) {
   int oh, ow;
   if (vcnn_status s = check_pool(d, &oh, &ow)) return s;
   if (!dy || !dx || !argmax) return fail(VCNN_ERR_NULL, "pool_bwd: NULL tensor");
-  if (vcnn_status s = need_f32(d->dtype, "pool_bwd")) return s;
-  return launch_pool_bwd_f32(*d, oh, ow, (const float*)dy, argmax, (float*)dx, (hipStream_t)stream);
+  return launch_pool_bwd(*d, oh, ow, dy, argmax, dx, (hipStream_t)stream);
 }
 
 vcnn_status vcnn_act_fwd(int32_t act, int32_t dtype, size_t count, const void* x, void* y, void* stream) {
   if (act != VCNN_ACT_RELU) return fail(VCNN_ERR_UNSUPPORTED, "act_fwd: activation %d is not built", act);
-  if (vcnn_status s = need_f32(dtype, "act_fwd")) return s;
+  if (vcnn_status s = check_dtype(dtype, "act_fwd")) return s;
   if (count == 0) return VCNN_OK;
   if (!x || !y) return fail(VCNN_ERR_NULL, "act_fwd: NULL tensor");
-  return launch_relu_fwd_f32(count, (const float*)x, (float*)y, (hipStream_t)stream);
+  return launch_relu_fwd(dtype, count, x, y, (hipStream_t)stream);
 }
 
 vcnn_status vcnn_act_bwd(int32_t act, int32_t dtype, size_t count, const void* ref, const void* dy, void* dx,
                          void* stream) {
   if (act != VCNN_ACT_RELU) return fail(VCNN_ERR_UNSUPPORTED, "act_bwd: activation %d is not built", act);
-  if (vcnn_status s = need_f32(dtype, "act_bwd")) return s;
+  if (vcnn_status s = check_dtype(dtype, "act_bwd")) return s;
   if (count == 0) return VCNN_OK;
   if (!ref || !dy || !dx) return fail(VCNN_ERR_NULL, "act_bwd: NULL tensor");
-  return launch_relu_bwd_f32(count, (const float*)ref, (const float*)dy, (float*)dx, (hipStream_t)stream);
+  return launch_relu_bwd(dtype, count, ref, dy, dx, (hipStream_t)stream);
 }
 
 static vcnn_status check_fc(int32_t batch, int32_t in_f, int32_t out_f) {
@@ -396,11 +380,12 @@ vcnn_status vcnn_fc_fwd(int32_t dtype, int32_t batch, int32_t in_f, int32_t out_
                         const void* w, const float* bias, void* y, void* stream) {
   if (vcnn_status s = check_fc(batch, in_f, out_f)) return s;
   if (act != VCNN_ACT_NONE && act != VCNN_ACT_RELU) return fail(VCNN_ERR_UNSUPPORTED, "fc_fwd: unknown activation %d", act);
-  if (vcnn_status s = need_f32(dtype, "fc_fwd")) return s;
+  if (vcnn_status s = check_dtype(dtype, "fc_fwd")) return s;
   if (!x || !w || !y) return fail(VCNN_ERR_NULL, "fc_fwd: NULL tensor");
   // C(i = o, j = b) = sum_k W[o][k] * X[b][k], stored at y[b*O + o]
   GemmArgs a{};
-  a.A = (const float*)w, a.B = (const float*)x, a.C = (float*)y, a.bias = bias;
+  a.A = w, a.B = x, a.C = y, a.bias = bias;
+  a.in_dtype = dtype, a.out_dtype = dtype;
   a.M = out_f, a.N = batch, a.K = in_f;
   a.a_si = in_f, a.a_sk = 1;
   a.b_sk = 1, a.b_sj = in_f, a.b_P = 0;
@@ -412,12 +397,13 @@ vcnn_status vcnn_fc_fwd(int32_t dtype, int32_t batch, int32_t in_f, int32_t out_
 vcnn_status vcnn_fc_bwd(int32_t dtype, int32_t batch, int32_t in_f, int32_t out_f, const void* x, const void* w,
                         const void* dy, float* dw, float* dbias, void* dx, void* stream) {
   if (vcnn_status s = check_fc(batch, in_f, out_f)) return s;
-  if (vcnn_status s = need_f32(dtype, "fc_bwd")) return s;
+  if (vcnn_status s = check_dtype(dtype, "fc_bwd")) return s;
   if (!x || !w || !dy || !dw) return fail(VCNN_ERR_NULL, "fc_bwd: NULL tensor");
   hipStream_t st = (hipStream_t)stream;
   {  // dW(i = o, j = i_) = sum_b dY[b][o] * X[b][i_]
     GemmArgs a{};
-    a.A = (const float*)dy, a.B = (const float*)x, a.C = dw;
+    a.A = dy, a.B = x, a.C = dw;
+    a.in_dtype = dtype, a.out_dtype = VCNN_F32;
     a.M = out_f, a.N = in_f, a.K = batch;
     a.a_si = 1, a.a_sk = out_f;
     a.b_sk = in_f, a.b_sj = 1, a.b_P = 0;
@@ -425,10 +411,11 @@ vcnn_status vcnn_fc_bwd(int32_t dtype, int32_t batch, int32_t in_f, int32_t out_
     if (vcnn_status s = launch_gemm_f32(a, st)) return s;
   }
   if (dbias)
-    if (vcnn_status s = launch_col_sum_f32(batch, out_f, (const float*)dy, dbias, st)) return s;
+    if (vcnn_status s = launch_col_sum(dtype, batch, out_f, dy, dbias, st)) return s;
   if (dx) {  // dX(i = b, j = i_) = sum_o dY[b][o] * W[o][i_]
     GemmArgs a{};
-    a.A = (const float*)dy, a.B = (const float*)w, a.C = (float*)dx;
+    a.A = dy, a.B = w, a.C = dx;
+    a.in_dtype = dtype, a.out_dtype = dtype;
     a.M = batch, a.N = in_f, a.K = out_f;
     a.a_si = out_f, a.a_sk = 1;
     a.b_sk = in_f, a.b_sj = 1, a.b_P = 0;
@@ -448,9 +435,9 @@ vcnn_status vcnn_softmax_loss(int32_t batch, int32_t classes, const float* logit
 vcnn_status vcnn_l2_loss(int32_t dtype, size_t count, int32_t batch, const void* y, const float* target, float* loss,
                          void* dy, void* stream) {
   if (batch <= 0 || count == 0) return fail(VCNN_ERR_SHAPE, "l2_loss: empty tensor");
-  if (vcnn_status s = need_f32(dtype, "l2_loss")) return s;
+  if (vcnn_status s = check_dtype(dtype, "l2_loss")) return s;
   if (!y || !target) return fail(VCNN_ERR_NULL, "l2_loss: NULL tensor");
-  return launch_l2_loss_f32(count, batch, (const float*)y, target, loss, (float*)dy, (hipStream_t)stream);
+  return launch_l2_loss(dtype, count, batch, y, target, loss, dy, (hipStream_t)stream);
 }
 
 vcnn_status vcnn_sgd_update(size_t count, float lr, float* w, const float* dw, void* stream) {

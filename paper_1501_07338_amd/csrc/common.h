@@ -25,8 +25,9 @@ struct ConvGeom {
 };
 
 // ---- unroll.hip ---------------------------------------------------------------------------------
-vcnn_status launch_im2col_f32(const ConvGeom& g, const float* x, float* col, hipStream_t st);
-vcnn_status launch_col2im_f32(const ConvGeom& g, const float* col, float* dx, hipStream_t st);
+// dtype = element type of x and of the patch matrix (im2col); of dx (col2im, whose patch matrix is float)
+vcnn_status launch_im2col(const ConvGeom& g, int dtype, const void* x, void* col, hipStream_t st);
+vcnn_status launch_col2im(const ConvGeom& g, int dtype, const float* col, void* dx, hipStream_t st);
 
 // ---- gemm.hip -----------------------------------------------------------------------------------
 // Generic strided product C(i,j) = act(bias[i] + sum_k A(i,k) B(k,j)), fp32 MFMA.
@@ -35,10 +36,11 @@ vcnn_status launch_col2im_f32(const ConvGeom& g, const float* col, float* dx, hi
 //   C(i,j) = C[i*c_si + jmap_c(j)]
 // Exactly one of (a_si, a_sk) and one of (b_sk, b_sj) should be 1 for coalesced loads.
 struct GemmArgs {
-  const float* A;
-  const float* B;
-  float* C;
+  const void* A;      // elements of in_dtype
+  const void* B;      // elements of in_dtype
+  void* C;            // elements of out_dtype
   const float* bias;  // per row i, nullable
+  int in_dtype, out_dtype;  // VCNN_F32 | VCNN_BF16 (VCNN_F32 == 0 is the zero-initialised default)
   int M, N, K;
   int64_t a_si, a_sk;
   int64_t b_sk, b_sj, b_simg;
@@ -53,7 +55,7 @@ vcnn_status launch_gemm_f32(const GemmArgs& a, hipStream_t st);
 // split over `splits` column ranges whose partial sums are combined in a fixed order.
 int bwd_filter_splits(const ConvGeom& g);
 size_t bwd_filter_partial_bytes(const ConvGeom& g);
-vcnn_status launch_bwd_filter_gemm_f32(const ConvGeom& g, const float* dy, const float* col, float* dw,
+vcnn_status launch_bwd_filter_gemm_f32(const ConvGeom& g, int dtype, const void* dy, const void* col, float* dw,
                                        float* partial, hipStream_t st);
 
 // ---- direct.hip ---------------------------------------------------------------------------------
@@ -70,12 +72,12 @@ bool direct_bwd_data_geom(const ConvGeom& c, DirectGeom* g);
 bool direct_few_out_plan(DirectGeom* g, int* isplit, size_t* partial_bytes);
 bool direct_few_in_plan(DirectGeom* g, int* ogroup);
 bool direct_filter_grad_plan(const ConvGeom& c, DirectGeom* g, int* slices, size_t* partial_bytes);
-vcnn_status launch_direct_few_out(const DirectGeom& g, int isplit, const float* in, const float* w, const float* bias,
-                                  float* out, float* partial, int relu, hipStream_t st);
-vcnn_status launch_direct_few_in(const DirectGeom& g, int ogroup, const float* in, const float* w, const float* bias,
-                                 float* out, int relu, hipStream_t st);
-vcnn_status launch_direct_filter_grad(const DirectGeom& g, int slices, const float* x, const float* dy, float* dw,
-                                      float* partial, hipStream_t st);
+vcnn_status launch_direct_few_out(const DirectGeom& g, int dtype, int isplit, const void* in, const void* w,
+                                  const float* bias, void* out, float* partial, int relu, hipStream_t st);
+vcnn_status launch_direct_few_in(const DirectGeom& g, int dtype, int ogroup, const void* in, const void* w,
+                                 const float* bias, void* out, int relu, hipStream_t st);
+vcnn_status launch_direct_filter_grad(const DirectGeom& g, int dtype, int slices, const void* x, const void* dy,
+                                      float* dw, float* partial, hipStream_t st);
 
 // ---- conv_implicit.hip ----------------------------------------------------------------------------
 // Implicit-unroll convolution y = act(bias + W (*) x) on the matrix cores; see the file header.
@@ -88,8 +90,9 @@ struct HaloPlan {
   bool vec;          // kernel-matrix rows can be fetched 16 bytes at a time
 };
 bool conv_halo_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int pw, HaloPlan* p);
-vcnn_status launch_conv_halo(const HaloPlan& p, int n, int c, int h, int w, int m, int r, int s, int ph, int pw,
-                             const float* x, const float* wgt, const float* bias, float* y, int relu, hipStream_t st);
+vcnn_status launch_conv_halo(const HaloPlan& p, int dtype, int n, int c, int h, int w, int m, int r, int s, int ph,
+                             int pw, const void* x, const void* wgt, const float* bias, void* y, int relu,
+                             hipStream_t st);
 struct HaloFilterPlan {
   int bm, bnk;       // block tile: output maps x kernel-matrix columns
   int bp;            // output pixels per staged run
@@ -99,27 +102,29 @@ struct HaloFilterPlan {
   bool vec;
 };
 bool conv_halo_filter_plan(const ConvGeom& g, HaloFilterPlan* p);
-vcnn_status launch_conv_halo_filter(const HaloFilterPlan& p, const ConvGeom& g, const float* x, const float* dy,
+vcnn_status launch_conv_halo_filter(const HaloFilterPlan& p, int dtype, const ConvGeom& g, const void* x, const void* dy,
                                     float* dw, float* partial, hipStream_t st);
-vcnn_status launch_flip_transpose(const float* w, float* w2, int M, int C, int RS, hipStream_t st);
+vcnn_status launch_flip_transpose(int dtype, const void* w, void* w2, int M, int C, int RS, hipStream_t st);
+
+// out[i] = act(bias[(i / plane) % maps] + sum_s partial[s][i]), slices added in ascending order (bias nullable)
+vcnn_status launch_sum_slices(const float* partial, const float* bias, void* out, int out_dtype, int64_t count,
+                              int splits, int64_t plane, int maps, int relu, hipStream_t st);
 
 // ---- pointwise.hip ------------------------------------------------------------------------------
+// dtype selects the element type (VCNN_F32 / VCNN_BF16) of the activation tensors passed as void*.
 size_t bias_grad_partial_bytes(const ConvGeom& g);
-vcnn_status launch_bias_grad_f32(const ConvGeom& g, const float* dy, float* db, float* partial, hipStream_t st);
-// out[i] = act(bias[(i / plane) % maps] + sum_s partial[s][i]), slices added in ascending order (bias nullable)
-vcnn_status launch_sum_slices(const float* partial, const float* bias, float* out, int64_t count, int splits,
-                              int64_t plane, int maps, int relu, hipStream_t st);
-vcnn_status launch_relu_fwd_f32(size_t count, const float* x, float* y, hipStream_t st);
-vcnn_status launch_relu_bwd_f32(size_t count, const float* ref, const float* dy, float* dx, hipStream_t st);
-vcnn_status launch_pool_fwd_f32(const vcnn_pool_desc& d, int oh, int ow, const float* x, float* y, int32_t* argmax,
-                                hipStream_t st);
-vcnn_status launch_pool_bwd_f32(const vcnn_pool_desc& d, int oh, int ow, const float* dy, const int32_t* argmax,
-                                float* dx, hipStream_t st);
-vcnn_status launch_col_sum_f32(int rows, int cols, const float* a, float* out, hipStream_t st);  // out[c] = sum_r a[r][c]
+vcnn_status launch_bias_grad(const ConvGeom& g, int dtype, const void* dy, float* db, float* partial, hipStream_t st);
+vcnn_status launch_relu_fwd(int dtype, size_t count, const void* x, void* y, hipStream_t st);
+vcnn_status launch_relu_bwd(int dtype, size_t count, const void* ref, const void* dy, void* dx, hipStream_t st);
+vcnn_status launch_pool_fwd(const vcnn_pool_desc& d, int oh, int ow, const void* x, void* y, int32_t* argmax,
+                            hipStream_t st);
+vcnn_status launch_pool_bwd(const vcnn_pool_desc& d, int oh, int ow, const void* dy, const int32_t* argmax, void* dx,
+                            hipStream_t st);
+vcnn_status launch_col_sum(int dtype, int rows, int cols, const void* a, float* out, hipStream_t st);  // out[c] = sum_r a[r][c]
 vcnn_status launch_softmax_loss_f32(int batch, int classes, const float* z, const int32_t* labels, float* loss,
                                     float* dz, hipStream_t st);
-vcnn_status launch_l2_loss_f32(size_t count, int batch, const float* y, const float* t, float* loss, float* dy,
-                               hipStream_t st);
+vcnn_status launch_l2_loss(int dtype, size_t count, int batch, const void* y, const float* t, float* loss, void* dy,
+                           hipStream_t st);
 vcnn_status launch_sgd_f32(size_t count, float lr, float* w, const float* dw, hipStream_t st);
 vcnn_status launch_f32_to_bf16(size_t count, const float* src, uint16_t* dst, hipStream_t st);
 vcnn_status launch_bf16_to_f32(size_t count, const uint16_t* src, float* dst, hipStream_t st);

@@ -13,6 +13,7 @@
 #include <algorithm>
 
 #include "common.h"
+#include "elem.h"
 #include "mma_core.h"
 
 namespace vcnn {
@@ -21,10 +22,10 @@ static constexpr int kThreads = 256;
 static constexpr int BK = 32;
 
 struct HaloArgs {
-  const float* x;     // [n][c][h][w]
-  const float* wgt;   // [m][c*r*s]
+  const void* x;      // [n][c][h][w]       element type T (float or bf16)
+  const void* wgt;    // [m][c*r*s]         element type T
   const float* bias;  // [m] or null
-  float* y;           // [n][m][oh][ow]
+  void* y;            // [n][m][oh][ow]     element type T
   int n, c, h, w, m, r, s, ph, pw, oh, ow;
   int P;              // oh*ow
   int tiles_m, tiles_per_img;
@@ -35,7 +36,7 @@ struct HaloArgs {
   int relu;
 };
 
-template <int BM, int BN, int WM, int WN, bool VEC>
+template <int BM, int BN, int WM, int WN, bool VEC, typename T>
 __global__ __launch_bounds__(kThreads) void conv_halo_kernel(HaloArgs a) {
   static_assert((BM / WM) * (BN / WN) * 64 == kThreads, "four waves per block");
   using LA = LdsTile<BM, BK, true>;
@@ -96,7 +97,9 @@ __global__ __launch_bounds__(kThreads) void conv_halo_kernel(HaloArgs a) {
   f32x16 acc[TM][TN];
   zero_acc<TM, TN>(acc);
 
-  const float* xin = a.x + (int64_t)n * a.c * a.h * a.w;
+  const T* xin = static_cast<const T*>(a.x) + (int64_t)n * a.c * a.h * a.w;
+  const T* wgt = static_cast<const T*>(a.wgt);
+  T* yout = static_cast<T*>(a.y);
   const int slabs = a.kch / BK;
 
   for (int c0 = 0; c0 < a.c; c0 += a.cc) {
@@ -109,12 +112,12 @@ __global__ __launch_bounds__(kThreads) void conv_halo_kernel(HaloArgs a) {
       for (int e = 0; e < SA::SLOTS; ++e) {
         const int kk = sl * BK + sa.c;
         sa.ok[e] = a_row_ok[e] && kk < klen;
-        const float* src = a.wgt + a_off[e] + kbase + min(kk, klen - (VEC ? 4 : 1));
+        const T* src = wgt + a_off[e] + kbase + min(kk, klen - (VEC ? 4 : 1));
         if (VEC) {
-          const float4 t = *reinterpret_cast<const float4*>(src);
+          const float4 t = ld4(src);
           sa.v[e][0] = t.x, sa.v[e][1] = t.y, sa.v[e][2] = t.z, sa.v[e][3] = t.w;
         } else {
-          sa.v[e][0] = *src;
+          sa.v[e][0] = ld(src);
         }
       }
     };
@@ -127,12 +130,12 @@ __global__ __launch_bounds__(kThreads) void conv_halo_kernel(HaloArgs a) {
       for (int rid = wave; rid < cc * a.nr; rid += kThreads / 64) {
         const int ih = oh_first - a.ph + ry;
         const bool row_ok = ih >= 0 && ih < a.h;
-        const float* src = xin + ((int64_t)(c0 + cl) * a.h + (row_ok ? ih : 0)) * a.w;
+        const T* src = xin + ((int64_t)(c0 + cl) * a.h + (row_ok ? ih : 0)) * a.w;
         float* dst = halo + cl * plane + ry * a.wp;
         for (int rx = lane; rx < a.wp; rx += 64) {
           const int iw = rx - a.pw;
           const bool ok = row_ok && iw >= 0 && iw < a.w;
-          const float v = src[ok ? iw : 0];
+          const float v = ld(src + (ok ? iw : 0));
           dst[rx] = ok ? v : 0.f;
         }
         ry += kThreads / 64;
@@ -188,15 +191,16 @@ __global__ __launch_bounds__(kThreads) void conv_halo_kernel(HaloArgs a) {
           float v = acc[mi][ni][q];
           if (a.bias) v += a.bias[i];
           if (a.relu) v = fmaxf(v, 0.f);
-          a.y[((int64_t)n * a.m + i) * a.P + p] = v;
+          st(yout + ((int64_t)n * a.m + i) * a.P + p, v);
         }
       }
   }
 }
 
 // w2[c][m][r'][s'] = w[m][c][R-1-r'][S-1-s']: the kernel matrix of the input-gradient correlation.
-__global__ __launch_bounds__(kThreads) void flip_transpose_kernel(const float* __restrict__ w, float* __restrict__ w2,
-                                                                  int M, int C, int RS) {
+template <typename T>
+__global__ __launch_bounds__(kThreads) void flip_transpose_kernel(const T* __restrict__ w, T* __restrict__ w2, int M,
+                                                                  int C, int RS) {
   const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   if (i >= (int64_t)M * C * RS) return;
   const int q = (int)(i % RS);
@@ -206,10 +210,13 @@ __global__ __launch_bounds__(kThreads) void flip_transpose_kernel(const float* _
   w2[i] = w[((int64_t)m * C + c) * RS + (RS - 1 - q)];
 }
 
-vcnn_status launch_flip_transpose(const float* w, float* w2, int M, int C, int RS, hipStream_t st) {
+vcnn_status launch_flip_transpose(int dtype, const void* w, void* w2, int M, int C, int RS, hipStream_t st) {
   const int64_t count = (int64_t)M * C * RS;
-  hipLaunchKernelGGL(flip_transpose_kernel, dim3((unsigned)ceil_div(count, kThreads)), dim3(kThreads), 0, st, w, w2, M,
-                     C, RS);
+  const dim3 grid((unsigned)ceil_div(count, kThreads)), block(kThreads);
+  if (dtype == VCNN_BF16)
+    hipLaunchKernelGGL(flip_transpose_kernel<bf16>, grid, block, 0, st, (const bf16*)w, (bf16*)w2, M, C, RS);
+  else
+    hipLaunchKernelGGL(flip_transpose_kernel<float>, grid, block, 0, st, (const float*)w, (float*)w2, M, C, RS);
   return check_launch("flip_transpose");
 }
 
@@ -261,24 +268,33 @@ bool conv_halo_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int
   return tiles <= 0x7fffffffLL;
 }
 
-template <int BM, int BN, int WM, int WN>
-static void launch_halo(const HaloArgs& a, const HaloPlan& p, bool vec, hipStream_t st) {
+template <int BM, int BN, int WM, int WN, bool VEC, typename T>
+static void launch_halo_one(const HaloArgs& a, const HaloPlan& p, hipStream_t st) {
   const dim3 grid((unsigned)((int64_t)a.tiles_m * a.n * a.tiles_per_img)), block(kThreads);
-  if (vec) {
-    auto kernel = conv_halo_kernel<BM, BN, WM, WN, true>;
-    static bool opted = false;
-    if (!opted) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget), opted = true;
-    hipLaunchKernelGGL(kernel, grid, block, p.lds_bytes, st, a);
+  auto kernel = conv_halo_kernel<BM, BN, WM, WN, VEC, T>;
+  static bool opted = false;  // one flag per instantiation, i.e. per kernel
+  if (!opted) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)kLdsBudget);
+    opted = true;
+  }
+  hipLaunchKernelGGL(kernel, grid, block, p.lds_bytes, st, a);
+}
+
+template <int BM, int BN, int WM, int WN>
+static void launch_halo(const HaloArgs& a, const HaloPlan& p, bool vec, int dtype, hipStream_t st) {
+  if (dtype == VCNN_BF16) {
+    if (vec) launch_halo_one<BM, BN, WM, WN, true, bf16>(a, p, st);
+    else launch_halo_one<BM, BN, WM, WN, false, bf16>(a, p, st);
   } else {
-    auto kernel = conv_halo_kernel<BM, BN, WM, WN, false>;
-    static bool opted = false;
-    if (!opted) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget), opted = true;
-    hipLaunchKernelGGL(kernel, grid, block, p.lds_bytes, st, a);
+    if (vec) launch_halo_one<BM, BN, WM, WN, true, float>(a, p, st);
+    else launch_halo_one<BM, BN, WM, WN, false, float>(a, p, st);
   }
 }
 
-vcnn_status launch_conv_halo(const HaloPlan& p, int n, int c, int h, int w, int m, int r, int s, int ph, int pw,
-                             const float* x, const float* wgt, const float* bias, float* y, int relu, hipStream_t st) {
+vcnn_status launch_conv_halo(const HaloPlan& p, int dtype, int n, int c, int h, int w, int m, int r, int s, int ph,
+                             int pw, const void* x, const void* wgt, const float* bias, void* y, int relu,
+                             hipStream_t st) {
   HaloArgs a{};
   a.x = x, a.wgt = wgt, a.bias = bias, a.y = y;
   a.n = n, a.c = c, a.h = h, a.w = w, a.m = m, a.r = r, a.s = s, a.ph = ph, a.pw = pw;
@@ -287,13 +303,13 @@ vcnn_status launch_conv_halo(const HaloPlan& p, int n, int c, int h, int w, int 
   a.tiles_m = (int)ceil_div(m, p.bm);
   a.tiles_per_img = (int)ceil_div(a.P, p.bn);
   a.cc = p.cc, a.nr = p.nr, a.wp = p.wp, a.kch = p.kch, a.relu = relu;
-  const bool vec = p.vec && (reinterpret_cast<uintptr_t>(wgt) & 15) == 0;
+  const bool vec = p.vec && (dtype == VCNN_BF16 ? group_aligned<bf16>(wgt) : group_aligned<float>(wgt));
   if (p.bm == 32)
-    launch_halo<32, 256, 32, 64>(a, p, vec, st);
+    launch_halo<32, 256, 32, 64>(a, p, vec, dtype, st);
   else if (p.bm == 64)
-    launch_halo<64, 256, 64, 64>(a, p, vec, st);
+    launch_halo<64, 256, 64, 64>(a, p, vec, dtype, st);
   else
-    launch_halo<128, 128, 64, 64>(a, p, vec, st);
+    launch_halo<128, 128, 64, 64>(a, p, vec, dtype, st);
   return check_launch("conv_halo");
 }
 
@@ -311,8 +327,8 @@ vcnn_status launch_conv_halo(const HaloPlan& p, int n, int c, int h, int w, int 
 namespace vcnn {
 
 struct HaloFilterArgs {
-  const float* x;    // [n][c][h][w]
-  const float* dy;   // [n][m][oh][ow]
+  const void* x;     // [n][c][h][w]     element type T (float or bf16)
+  const void* dy;    // [n][m][oh][ow]   element type T
   float* out;        // [splits][m][c*r*s]
   int n, c, h, w, m, r, s, ph, pw, oh, ow, P;
   int tiles_m;
@@ -323,7 +339,7 @@ struct HaloFilterArgs {
   int nr, wp;
 };
 
-template <int BM, int BNK, int WM, int WN, bool VEC>
+template <int BM, int BNK, int WM, int WN, bool VEC, typename T>
 __global__ __launch_bounds__(kThreads) void conv_halo_filter_kernel(HaloFilterArgs a) {
   static_assert((BM / WM) * (BNK / WN) * 64 == kThreads, "four waves per block");
   using LA = LdsTile<BM, BK, true>;
@@ -373,19 +389,19 @@ __global__ __launch_bounds__(kThreads) void conv_halo_filter_kernel(HaloFilterAr
     const int p0 = (run - n * a.runs_per_img) * a.bp;
     const int plen = min(a.bp, a.P - p0);  // valid pixels in this run
     const int oh_first = p0 / a.ow;
-    const float* dyn = a.dy + (int64_t)n * a.m * a.P + p0;
+    const T* dyn = static_cast<const T*>(a.dy) + (int64_t)n * a.m * a.P + p0;
     auto fetch = [&](int sl) {
       const int pk = sl * BK + sa.c;  // pixel inside the run
 #pragma unroll
       for (int e = 0; e < SA::SLOTS; ++e) {
         const int m = i0 + sa.line(e);
         sa.ok[e] = m < a.m && pk < plen;
-        const float* src = dyn + (int64_t)min(m, a.m - 1) * a.P + min(pk, plen - (VEC ? 4 : 1));
+        const T* src = dyn + (int64_t)min(m, a.m - 1) * a.P + min(pk, plen - (VEC ? 4 : 1));
         if (VEC) {
-          const float4 t = *reinterpret_cast<const float4*>(src);
+          const float4 t = ld4(src);
           sa.v[e][0] = t.x, sa.v[e][1] = t.y, sa.v[e][2] = t.z, sa.v[e][3] = t.w;
         } else {
-          sa.v[e][0] = *src;
+          sa.v[e][0] = ld(src);
         }
       }
     };
@@ -397,19 +413,19 @@ __global__ __launch_bounds__(kThreads) void conv_halo_filter_kernel(HaloFilterAr
       pixoff[pk] = (oh - oh_first) * a.wp + (p - oh * a.ow);
     }
     {
-      const float* xin = a.x + (int64_t)n * a.c * a.h * a.w;
+      const T* xin = static_cast<const T*>(a.x) + (int64_t)n * a.c * a.h * a.w;
       int cl = 0, ry = wave;
       while (ry >= a.nr) ry -= a.nr, ++cl;
       for (int rid = wave; rid < a.ccs * a.nr; rid += kThreads / 64) {
         const int ih = oh_first - a.ph + ry;
         const bool row_ok = ih >= 0 && ih < a.h;
         const int c = min(c_first + cl, a.c - 1);
-        const float* src = xin + ((int64_t)c * a.h + (row_ok ? ih : 0)) * a.w;
+        const T* src = xin + ((int64_t)c * a.h + (row_ok ? ih : 0)) * a.w;
         float* dst = halo + cl * plane + ry * a.wp;
         for (int rx = lane; rx < a.wp; rx += 64) {
           const int iw = rx - a.pw;
           const bool ok = row_ok && iw >= 0 && iw < a.w;
-          const float v = src[ok ? iw : 0];
+          const float v = ld(src + (ok ? iw : 0));
           dst[rx] = ok ? v : 0.f;
         }
         ry += kThreads / 64;
@@ -505,23 +521,32 @@ bool conv_halo_filter_plan(const ConvGeom& g, HaloFilterPlan* p) {
   return tiles <= 0x7fffffffLL && p->splits <= 65535;
 }
 
-template <int BM, int BNK, int WM, int WN>
-static void launch_halo_filter(const HaloFilterArgs& a, const HaloFilterPlan& p, bool vec, int tiles, hipStream_t st) {
+template <int BM, int BNK, int WM, int WN, bool VEC, typename T>
+static void launch_halo_filter_one(const HaloFilterArgs& a, const HaloFilterPlan& p, int tiles, hipStream_t st) {
   const dim3 grid((unsigned)tiles, (unsigned)p.splits), block(kThreads);
-  if (vec) {
-    auto kernel = conv_halo_filter_kernel<BM, BNK, WM, WN, true>;
-    static bool opted = false;
-    if (!opted) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget), opted = true;
-    hipLaunchKernelGGL(kernel, grid, block, p.lds_bytes, st, a);
+  auto kernel = conv_halo_filter_kernel<BM, BNK, WM, WN, VEC, T>;
+  static bool opted = false;
+  if (!opted) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)kLdsBudget);
+    opted = true;
+  }
+  hipLaunchKernelGGL(kernel, grid, block, p.lds_bytes, st, a);
+}
+
+template <int BM, int BNK, int WM, int WN>
+static void launch_halo_filter(const HaloFilterArgs& a, const HaloFilterPlan& p, bool vec, int dtype, int tiles,
+                               hipStream_t st) {
+  if (dtype == VCNN_BF16) {
+    if (vec) launch_halo_filter_one<BM, BNK, WM, WN, true, bf16>(a, p, tiles, st);
+    else launch_halo_filter_one<BM, BNK, WM, WN, false, bf16>(a, p, tiles, st);
   } else {
-    auto kernel = conv_halo_filter_kernel<BM, BNK, WM, WN, false>;
-    static bool opted = false;
-    if (!opted) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget), opted = true;
-    hipLaunchKernelGGL(kernel, grid, block, p.lds_bytes, st, a);
+    if (vec) launch_halo_filter_one<BM, BNK, WM, WN, true, float>(a, p, tiles, st);
+    else launch_halo_filter_one<BM, BNK, WM, WN, false, float>(a, p, tiles, st);
   }
 }
 
-vcnn_status launch_conv_halo_filter(const HaloFilterPlan& p, const ConvGeom& g, const float* x, const float* dy,
+vcnn_status launch_conv_halo_filter(const HaloFilterPlan& p, int dtype, const ConvGeom& g, const void* x, const void* dy,
                                     float* dw, float* partial, hipStream_t st) {
   HaloFilterArgs a{};
   a.x = x, a.dy = dy, a.out = p.splits > 1 ? partial : dw;
@@ -531,16 +556,16 @@ vcnn_status launch_conv_halo_filter(const HaloFilterPlan& p, const ConvGeom& g, 
   a.bp = p.bp, a.runs_per_img = p.runs_per_img, a.runs_per_split = p.runs_per_split;
   a.ccs = p.ccs, a.nr = p.nr, a.wp = p.wp;
   const int tiles = a.tiles_m * (int)ceil_div(g.K, p.bnk);
-  const bool vec = p.vec && (reinterpret_cast<uintptr_t>(dy) & 15) == 0;
+  const bool vec = p.vec && (dtype == VCNN_BF16 ? group_aligned<bf16>(dy) : group_aligned<float>(dy));
   if (p.bm == 32)
-    launch_halo_filter<32, 256, 32, 64>(a, p, vec, tiles, st);
+    launch_halo_filter<32, 256, 32, 64>(a, p, vec, dtype, tiles, st);
   else if (p.bm == 64)
-    launch_halo_filter<64, 256, 64, 64>(a, p, vec, tiles, st);
+    launch_halo_filter<64, 256, 64, 64>(a, p, vec, dtype, tiles, st);
   else
-    launch_halo_filter<128, 128, 64, 64>(a, p, vec, tiles, st);
+    launch_halo_filter<128, 128, 64, 64>(a, p, vec, dtype, tiles, st);
   if (vcnn_status s = check_launch("conv_halo_filter")) return s;
   if (p.splits == 1) return VCNN_OK;
-  return launch_sum_slices(partial, nullptr, dw, g.M * g.K, p.splits, 1, 1, 0, st);
+  return launch_sum_slices(partial, nullptr, dw, VCNN_F32, g.M * g.K, p.splits, 1, 1, 0, st);
 }
 
 }  // namespace vcnn

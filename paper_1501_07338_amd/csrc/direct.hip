@@ -9,6 +9,7 @@
 // so that the forward pass and the input gradient (a correlation of dy with the flipped kernels,
 // i.e. phi_c^{-1} applied to the transposed product, evaluated in gather form) share them.
 #include "common.h"
+#include "elem.h"
 
 namespace vcnn {
 
@@ -21,7 +22,8 @@ __device__ __forceinline__ int tap_index(const DirectGeom& g, int r, int s) {
 }
 
 // Stages rows [y0 - py, y0 - py + rows) of one input plane into LDS, columns shifted by px, zero filled.
-__device__ __forceinline__ void stage_plane(const DirectGeom& g, const float* __restrict__ plane, int y0, int rows,
+template <typename T>
+__device__ __forceinline__ void stage_plane(const DirectGeom& g, const T* __restrict__ plane, int y0, int rows,
                                             float* tile) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   for (int ry = wave; ry < rows; ry += kThreads / 64) {
@@ -30,15 +32,15 @@ __device__ __forceinline__ void stage_plane(const DirectGeom& g, const float* __
     for (int rx = lane; rx < g.twp; rx += 64) {
       const int ix = rx - g.px;
       float v = 0.f;
-      if (row_ok && ix >= 0 && ix < g.iw) v = plane[(int64_t)iy * g.iw + ix];
+      if (row_ok && ix >= 0 && ix < g.iw) v = ld(plane + (int64_t)iy * g.iw + ix);
       tile[ry * g.twp + rx] = v;
     }
   }
 }
 
 // acc[o][j] += sum_s w_o[s] * row[j + s] for one tile row, sliding a register window along s.
-template <int CO>
-__device__ __forceinline__ void row_taps(const DirectGeom& g, const float* row, const float* const (&wrow)[CO],
+template <int CO, typename T>
+__device__ __forceinline__ void row_taps(const DirectGeom& g, const float* row, const T* const (&wrow)[CO],
                                          float (&acc)[CO][kPx]) {
   float x0 = row[0], x1 = row[1], x2 = row[2];
   const int S = g.s;
@@ -46,7 +48,7 @@ __device__ __forceinline__ void row_taps(const DirectGeom& g, const float* row, 
   int s = 0;
 #define VCNN_TAP(XA, XB, XC, XD, SS)                 \
   _Pragma("unroll") for (int o = 0; o < CO; ++o) {   \
-    const float wv = wrow[o][dir * (SS)];            \
+    const float wv = ld(wrow[o] + dir * (SS));       \
     acc[o][0] = fmaf(wv, XA, acc[o][0]);             \
     acc[o][1] = fmaf(wv, XB, acc[o][1]);             \
     acc[o][2] = fmaf(wv, XC, acc[o][2]);             \
@@ -71,11 +73,12 @@ __device__ __forceinline__ void row_taps(const DirectGeom& g, const float* row, 
 // ---- few output maps (CO <= 4), any number of input channels -----------------------------------------
 // Block = (sample, band of output rows, slice of the input channels).  Partial sums over channel
 // slices go to `out` as [slice][n][co][oh][ow] when isplit > 1 and are combined by sum_slices_kernel.
-template <int CO>
-__global__ __launch_bounds__(kThreads) void direct_few_out_kernel(DirectGeom g, const float* __restrict__ in,
-                                                                  const float* __restrict__ w,
+// T: element type of in and w; TO: element type of out (float when out holds partial sums).
+template <int CO, typename T, typename TO>
+__global__ __launch_bounds__(kThreads) void direct_few_out_kernel(DirectGeom g, const T* __restrict__ in,
+                                                                  const T* __restrict__ w,
                                                                   const float* __restrict__ bias,
-                                                                  float* __restrict__ out, int isplit, int relu) {
+                                                                  TO* __restrict__ out, int isplit, int relu) {
   extern __shared__ float tile[];
   int b = blockIdx.x;
   const int is = b % isplit;
@@ -102,10 +105,10 @@ __global__ __launch_bounds__(kThreads) void direct_few_out_kernel(DirectGeom g, 
     __syncthreads();
     if (active) {
       for (int r = 0; r < g.r; ++r) {
-        const float* wrow[CO];
+        const T* wrow[CO];
 #pragma unroll
         for (int o = 0; o < CO; ++o) wrow[o] = w + (int64_t)o * g.w_so + (int64_t)i * g.w_si + tap_index(g, r, 0);
-        row_taps<CO>(g, tile + (ty + r) * g.twp + gx * kPx, wrow, acc);
+        row_taps<CO, T>(g, tile + (ty + r) * g.twp + gx * kPx, wrow, acc);
       }
     }
   }
@@ -113,7 +116,7 @@ __global__ __launch_bounds__(kThreads) void direct_few_out_kernel(DirectGeom g, 
   const int y = y0 + ty;
 #pragma unroll
   for (int o = 0; o < CO; ++o) {
-    float* dst = out + ((((int64_t)is * g.n + n) * g.co + o) * g.oh + y) * g.ow;
+    TO* dst = out + ((((int64_t)is * g.n + n) * g.co + o) * g.oh + y) * g.ow;
 #pragma unroll
     for (int j = 0; j < kPx; ++j) {
       const int x = gx * kPx + j;
@@ -123,7 +126,7 @@ __global__ __launch_bounds__(kThreads) void direct_few_out_kernel(DirectGeom g, 
           if (bias) v += bias[o];
           if (relu) v = fmaxf(v, 0.f);
         }
-        dst[x] = v;
+        st(dst + x, v);
       }
     }
   }
@@ -131,8 +134,9 @@ __global__ __launch_bounds__(kThreads) void direct_few_out_kernel(DirectGeom g, 
 
 // out[idx] = act(bias[map(idx)] + sum_s partial[s][idx]), slices added in ascending order with four
 // independent loads in flight.
+template <typename TO>
 __global__ __launch_bounds__(kThreads) void sum_slices_kernel(const float* __restrict__ partial,
-                                                              const float* __restrict__ bias, float* __restrict__ out,
+                                                              const float* __restrict__ bias, TO* __restrict__ out,
                                                               int64_t count, int splits, int64_t plane, int maps,
                                                               int relu) {
   const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
@@ -147,24 +151,29 @@ __global__ __launch_bounds__(kThreads) void sum_slices_kernel(const float* __res
   for (; s < splits; ++s) acc += partial[(int64_t)s * count + i];
   if (bias) acc += bias[(i / plane) % maps];
   if (relu) acc = fmaxf(acc, 0.f);
-  out[i] = acc;
+  st(out + i, acc);
 }
 
-vcnn_status launch_sum_slices(const float* partial, const float* bias, float* out, int64_t count, int splits,
-                              int64_t plane, int maps, int relu, hipStream_t st) {
-  hipLaunchKernelGGL(sum_slices_kernel, dim3((unsigned)ceil_div(count, kThreads)), dim3(kThreads), 0, st, partial, bias,
-                     out, count, splits, plane, maps, relu);
+vcnn_status launch_sum_slices(const float* partial, const float* bias, void* out, int out_dtype, int64_t count,
+                              int splits, int64_t plane, int maps, int relu, hipStream_t st) {
+  const dim3 grid((unsigned)ceil_div(count, kThreads)), block(kThreads);
+  if (out_dtype == VCNN_BF16)
+    hipLaunchKernelGGL(sum_slices_kernel<bf16>, grid, block, 0, st, partial, bias, (bf16*)out, count, splits, plane, maps,
+                       relu);
+  else
+    hipLaunchKernelGGL(sum_slices_kernel<float>, grid, block, 0, st, partial, bias, (float*)out, count, splits, plane,
+                       maps, relu);
   return check_launch("sum_slices");
 }
 
 // ---- few input channels (CI <= 4), any number of output maps -----------------------------------------
 // Block = (sample, band, group of output maps).  All CI input bands sit in LDS; output maps are
 // produced four at a time so that every LDS read feeds 16 multiply-adds.
-template <int CI>
-__global__ __launch_bounds__(kThreads) void direct_few_in_kernel(DirectGeom g, const float* __restrict__ in,
-                                                                 const float* __restrict__ w,
+template <int CI, typename T>
+__global__ __launch_bounds__(kThreads) void direct_few_in_kernel(DirectGeom g, const T* __restrict__ in,
+                                                                 const T* __restrict__ w,
                                                                  const float* __restrict__ bias,
-                                                                 float* __restrict__ out, int ogroup, int ogroups,
+                                                                 T* __restrict__ out, int ogroup, int ogroups,
                                                                  int relu) {
   extern __shared__ float tile[];
   int b = blockIdx.x;
@@ -195,16 +204,16 @@ __global__ __launch_bounds__(kThreads) void direct_few_in_kernel(DirectGeom g, c
 #pragma unroll
     for (int i = 0; i < CI; ++i)
       for (int r = 0; r < g.r; ++r) {
-        const float* wrow[4];
+        const T* wrow[4];
 #pragma unroll
         for (int o = 0; o < 4; ++o)  // maps past the end reuse the last valid one; their results are dropped
           wrow[o] = w + (int64_t)min(o0 + o, g.co - 1) * g.w_so + (int64_t)i * g.w_si + tap_index(g, r, 0);
-        row_taps<4>(g, tile + i * plane_lds + (ty + r) * g.twp + gx * kPx, wrow, acc);
+        row_taps<4, T>(g, tile + i * plane_lds + (ty + r) * g.twp + gx * kPx, wrow, acc);
       }
 #pragma unroll
     for (int o = 0; o < 4; ++o) {
       if (o0 + o >= o_end) break;
-      float* dst = out + (((int64_t)n * g.co + o0 + o) * g.oh + y) * g.ow;
+      T* dst = out + (((int64_t)n * g.co + o0 + o) * g.oh + y) * g.ow;
       const float bv = bias ? bias[o0 + o] : 0.f;
 #pragma unroll
       for (int j = 0; j < kPx; ++j) {
@@ -212,7 +221,7 @@ __global__ __launch_bounds__(kThreads) void direct_few_in_kernel(DirectGeom g, c
         if (x < g.ow) {
           float v = acc[o][j] + bv;
           if (relu) v = fmaxf(v, 0.f);
-          dst[x] = v;
+          st(dst + x, v);
         }
       }
     }
@@ -268,21 +277,34 @@ bool direct_few_out_plan(DirectGeom* g, int* isplit, size_t* partial_bytes) {
   return true;
 }
 
-vcnn_status launch_direct_few_out(const DirectGeom& g, int isplit, const float* in, const float* w, const float* bias,
-                                  float* out, float* partial, int relu, hipStream_t st) {
+template <typename T, typename TO>
+static void launch_few_out_typed(const DirectGeom& g, int isplit, const void* in, const void* w, const float* bias,
+                                 void* dst, int relu, hipStream_t st) {
   const size_t lds = (size_t)(g.bh + g.r - 1) * g.twp * sizeof(float);
   const dim3 grid((unsigned)((int64_t)g.n * g.bands * isplit)), block(kThreads);
-  float* dst = isplit > 1 ? partial : out;
+  const T* i = (const T*)in;
+  const T* k = (const T*)w;
+  TO* o = (TO*)dst;
   switch (g.co) {
-    case 1: hipLaunchKernelGGL(direct_few_out_kernel<1>, grid, block, lds, st, g, in, w, bias, dst, isplit, relu); break;
-    case 2: hipLaunchKernelGGL(direct_few_out_kernel<2>, grid, block, lds, st, g, in, w, bias, dst, isplit, relu); break;
-    case 3: hipLaunchKernelGGL(direct_few_out_kernel<3>, grid, block, lds, st, g, in, w, bias, dst, isplit, relu); break;
-    default: hipLaunchKernelGGL(direct_few_out_kernel<4>, grid, block, lds, st, g, in, w, bias, dst, isplit, relu); break;
+    case 1: hipLaunchKernelGGL((direct_few_out_kernel<1, T, TO>), grid, block, lds, st, g, i, k, bias, o, isplit, relu); break;
+    case 2: hipLaunchKernelGGL((direct_few_out_kernel<2, T, TO>), grid, block, lds, st, g, i, k, bias, o, isplit, relu); break;
+    case 3: hipLaunchKernelGGL((direct_few_out_kernel<3, T, TO>), grid, block, lds, st, g, i, k, bias, o, isplit, relu); break;
+    default: hipLaunchKernelGGL((direct_few_out_kernel<4, T, TO>), grid, block, lds, st, g, i, k, bias, o, isplit, relu); break;
+  }
+}
+
+vcnn_status launch_direct_few_out(const DirectGeom& g, int dtype, int isplit, const void* in, const void* w,
+                                  const float* bias, void* out, float* partial, int relu, hipStream_t st) {
+  if (dtype == VCNN_BF16) {
+    if (isplit > 1) launch_few_out_typed<bf16, float>(g, isplit, in, w, bias, partial, relu, st);
+    else launch_few_out_typed<bf16, bf16>(g, isplit, in, w, bias, out, relu, st);
+  } else {
+    launch_few_out_typed<float, float>(g, isplit, in, w, bias, isplit > 1 ? (void*)partial : out, relu, st);
   }
   if (vcnn_status s = check_launch("direct_few_out")) return s;
   if (isplit == 1) return VCNN_OK;
-  return launch_sum_slices(partial, bias, out, (int64_t)g.n * g.co * g.oh * g.ow, isplit, (int64_t)g.oh * g.ow, g.co, relu,
-                           st);
+  return launch_sum_slices(partial, bias, out, dtype, (int64_t)g.n * g.co * g.oh * g.ow, isplit, (int64_t)g.oh * g.ow,
+                           g.co, relu, st);
 }
 
 bool direct_few_in_plan(DirectGeom* g, int* ogroup) {
@@ -298,17 +320,27 @@ bool direct_few_in_plan(DirectGeom* g, int* ogroup) {
   return true;
 }
 
-vcnn_status launch_direct_few_in(const DirectGeom& g, int ogroup, const float* in, const float* w, const float* bias,
-                                 float* out, int relu, hipStream_t st) {
+template <typename T>
+static void launch_few_in_typed(const DirectGeom& g, int ogroup, const void* in, const void* w, const float* bias,
+                                void* out, int relu, hipStream_t st) {
   const size_t lds = (size_t)g.ci * (g.bh + g.r - 1) * g.twp * sizeof(float);
   const int ogroups = (int)ceil_div(g.co, ogroup);
   const dim3 grid((unsigned)((int64_t)g.n * g.bands * ogroups)), block(kThreads);
+  const T* i = (const T*)in;
+  const T* k = (const T*)w;
+  T* o = (T*)out;
   switch (g.ci) {
-    case 1: hipLaunchKernelGGL(direct_few_in_kernel<1>, grid, block, lds, st, g, in, w, bias, out, ogroup, ogroups, relu); break;
-    case 2: hipLaunchKernelGGL(direct_few_in_kernel<2>, grid, block, lds, st, g, in, w, bias, out, ogroup, ogroups, relu); break;
-    case 3: hipLaunchKernelGGL(direct_few_in_kernel<3>, grid, block, lds, st, g, in, w, bias, out, ogroup, ogroups, relu); break;
-    default: hipLaunchKernelGGL(direct_few_in_kernel<4>, grid, block, lds, st, g, in, w, bias, out, ogroup, ogroups, relu); break;
+    case 1: hipLaunchKernelGGL((direct_few_in_kernel<1, T>), grid, block, lds, st, g, i, k, bias, o, ogroup, ogroups, relu); break;
+    case 2: hipLaunchKernelGGL((direct_few_in_kernel<2, T>), grid, block, lds, st, g, i, k, bias, o, ogroup, ogroups, relu); break;
+    case 3: hipLaunchKernelGGL((direct_few_in_kernel<3, T>), grid, block, lds, st, g, i, k, bias, o, ogroup, ogroups, relu); break;
+    default: hipLaunchKernelGGL((direct_few_in_kernel<4, T>), grid, block, lds, st, g, i, k, bias, o, ogroup, ogroups, relu); break;
   }
+}
+
+vcnn_status launch_direct_few_in(const DirectGeom& g, int dtype, int ogroup, const void* in, const void* w,
+                                 const float* bias, void* out, int relu, hipStream_t st) {
+  if (dtype == VCNN_BF16) launch_few_in_typed<bf16>(g, ogroup, in, w, bias, out, relu, st);
+  else launch_few_in_typed<float>(g, ogroup, in, w, bias, out, relu, st);
   return check_launch("direct_few_in");
 }
 
@@ -319,8 +351,9 @@ vcnn_status launch_direct_few_in(const DirectGeom& g, int ogroup, const float* i
 // partial sums in registers.  Lanes are combined with a fixed butterfly, batch slices by the caller.
 static constexpr int kTapChunk = 8;
 
-__global__ __launch_bounds__(kThreads) void direct_filter_grad_kernel(DirectGeom g, const float* __restrict__ x,
-                                                                      const float* __restrict__ dy,
+template <typename T>
+__global__ __launch_bounds__(kThreads) void direct_filter_grad_kernel(DirectGeom g, const T* __restrict__ x,
+                                                                      const T* __restrict__ dy,
                                                                       float* __restrict__ partial, int tap_blocks,
                                                                       int imgs_per_slice) {
   // geometry: in = x [n][ci][ih][iw]; dy = [n][co][oh][ow]; taps r x s; py/px = padding
@@ -348,15 +381,16 @@ __global__ __launch_bounds__(kThreads) void direct_filter_grad_kernel(DirectGeom
 
   const int n0 = slice * imgs_per_slice, n1 = min(g.n, n0 + imgs_per_slice);
   for (int n = n0; n < n1; ++n) {
-    const float* xp = x + ((int64_t)n * g.ci + c) * g.ih * g.iw;
-    const float* dp = dy + ((int64_t)n * g.co + m) * g.oh * g.ow;
+    const T* xp = x + ((int64_t)n * g.ci + c) * g.ih * g.iw;
+    const T* dp = dy + ((int64_t)n * g.co + m) * g.oh * g.ow;
     for (int band = 0; band < g.bands; ++band) {
       const int y0 = band * g.bh;
       const int bh_eff = min(g.bh, g.oh - y0);
       __syncthreads();
       stage_plane(g, xp, y0, bh_eff + g.r - 1, xt);
       for (int ry = wave; ry < bh_eff; ry += kThreads / 64)
-        for (int rx = lane; rx < dyp; rx += 64) dt[ry * dyp + rx] = rx < g.ow ? dp[(int64_t)(y0 + ry) * g.ow + rx] : 0.f;
+        for (int rx = lane; rx < dyp; rx += 64)
+          dt[ry * dyp + rx] = rx < g.ow ? ld(dp + (int64_t)(y0 + ry) * g.ow + rx) : 0.f;
       __syncthreads();
       if (valid) {
         const int npg = bh_eff * g.groups;
@@ -417,8 +451,8 @@ bool direct_filter_grad_plan(const ConvGeom& c, DirectGeom* g, int* slices, size
   return true;
 }
 
-vcnn_status launch_direct_filter_grad(const DirectGeom& g, int slices, const float* x, const float* dy, float* dw,
-                                      float* partial, hipStream_t st) {
+vcnn_status launch_direct_filter_grad(const DirectGeom& g, int dtype, int slices, const void* x, const void* dy,
+                                      float* dw, float* partial, hipStream_t st) {
   const int sch = (g.s + kTapChunk - 1) / kTapChunk;
   const int tap_blocks = (int)ceil_div((int64_t)g.r * sch, 4);
   const int per = (int)ceil_div(g.n, slices);
@@ -426,11 +460,15 @@ vcnn_status launch_direct_filter_grad(const DirectGeom& g, int slices, const flo
   const int64_t blocks = (int64_t)g.co * g.ci * tap_blocks * slices;
   if (blocks > 0x7fffffffLL) return fail(VCNN_ERR_UNSUPPORTED, "direct filter gradient: too many blocks");
   float* dst = slices > 1 ? partial : dw;
-  hipLaunchKernelGGL(direct_filter_grad_kernel, dim3((unsigned)blocks), dim3(kThreads), lds, st, g, x, dy, dst,
-                     tap_blocks, per);
+  if (dtype == VCNN_BF16)
+    hipLaunchKernelGGL(direct_filter_grad_kernel<bf16>, dim3((unsigned)blocks), dim3(kThreads), lds, st, g,
+                       (const bf16*)x, (const bf16*)dy, dst, tap_blocks, per);
+  else
+    hipLaunchKernelGGL(direct_filter_grad_kernel<float>, dim3((unsigned)blocks), dim3(kThreads), lds, st, g,
+                       (const float*)x, (const float*)dy, dst, tap_blocks, per);
   if (vcnn_status s = check_launch("direct_filter_grad")) return s;
   if (slices == 1) return VCNN_OK;
-  return launch_sum_slices(partial, nullptr, dw, (int64_t)g.co * g.ci * g.r * g.s, slices, 1, 1, 0, st);
+  return launch_sum_slices(partial, nullptr, dw, VCNN_F32, (int64_t)g.co * g.ci * g.r * g.s, slices, 1, 1, 0, st);
 }
 
 }  // namespace vcnn

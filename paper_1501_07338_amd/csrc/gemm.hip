@@ -11,6 +11,7 @@
 #include <cstdlib>
 
 #include "common.h"
+#include "elem.h"
 #include "mma_core.h"
 
 namespace vcnn {
@@ -35,7 +36,8 @@ __device__ __forceinline__ int xcd_remap(int bid, int total) {
   return (bid % X) * per + bid / X;
 }
 
-template <int BM, int BN, int BK, int WM, int WN, bool A_KC, bool B_KC, bool A_VEC, bool B_VEC>
+// TI: element type of A and B in memory (float or bf16); TO: element type of C.  All arithmetic is fp32.
+template <int BM, int BN, int BK, int WM, int WN, bool A_KC, bool B_KC, bool A_VEC, bool B_VEC, typename TI, typename TO>
 __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmArgs a, int tiles_m, int tiles_total) {
   static_assert((BM / WM) * (BN / WN) * 64 == kThreads, "four waves per block");
   using LA = LdsTile<BM, BK, A_KC>;
@@ -50,6 +52,9 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmArgs a, int tile
   float* const As0 = smem;
   float* const Bs0 = smem + 2 * LA::SIZE;
 
+  const TI* gA = static_cast<const TI*>(a.A);
+  const TI* gB = static_cast<const TI*>(a.B);
+  TO* gC = static_cast<TO*>(a.C);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int tile = xcd_remap(blockIdx.x, tiles_total);
   const int i0 = (tile % tiles_m) * BM;
@@ -84,24 +89,24 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmArgs a, int tile
     for (int e = 0; e < SA::SLOTS; ++e) {
       const int k = k0 + sa.k_of(e, 0);
       sa.ok[e] = a_row_ok[e] && k < a.K;
-      const float* src = a.A + a_off[e] + (int64_t)min(k, (A_VEC && A_KC) ? a.K - 4 : a.K - 1) * a.a_sk;
+      const TI* src = gA + a_off[e] + (int64_t)min(k, (A_VEC && A_KC) ? a.K - 4 : a.K - 1) * a.a_sk;
       if (A_VEC) {
-        const float4 t = *reinterpret_cast<const float4*>(src);
+        const float4 t = ld4(src);
         sa.v[e][0] = t.x, sa.v[e][1] = t.y, sa.v[e][2] = t.z, sa.v[e][3] = t.w;
       } else {
-        sa.v[e][0] = *src;
+        sa.v[e][0] = ld(src);
       }
     }
 #pragma unroll
     for (int e = 0; e < SB::SLOTS; ++e) {
       const int k = k0 + sb.k_of(e, 0);
       sb.ok[e] = b_row_ok[e] && k < a.K;
-      const float* src = a.B + b_off[e] + (int64_t)min(k, (B_VEC && B_KC) ? a.K - 4 : a.K - 1) * a.b_sk;
+      const TI* src = gB + b_off[e] + (int64_t)min(k, (B_VEC && B_KC) ? a.K - 4 : a.K - 1) * a.b_sk;
       if (B_VEC) {
-        const float4 t = *reinterpret_cast<const float4*>(src);
+        const float4 t = ld4(src);
         sb.v[e][0] = t.x, sb.v[e][1] = t.y, sb.v[e][2] = t.z, sb.v[e][3] = t.w;
       } else {
-        sb.v[e][0] = *src;
+        sb.v[e][0] = ld(src);
       }
     }
   };
@@ -140,7 +145,7 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmArgs a, int tile
           float v = acc[mi][ni][q];
           if (a.bias) v += a.bias[i];
           if (a.relu) v = fmaxf(v, 0.f);
-          a.C[(int64_t)i * a.c_si + cj] = v;
+          st(gC + (int64_t)i * a.c_si + cj, v);
         }
       }
   }
@@ -161,27 +166,39 @@ static void allow_lds(K kernel, size_t bytes, bool& done) {
   }
 }
 
-template <int BM, int BN, int BK, int WM, int WN, bool A_KC, bool B_KC, bool A_VEC, bool B_VEC>
+template <int BM, int BN, int BK, int WM, int WN, bool A_KC, bool B_KC, bool A_VEC, bool B_VEC, typename TI, typename TO>
 static void launch_one(const GemmArgs& a, hipStream_t st) {
   const int tiles_m = (int)ceil_div(a.M, BM);
   const int64_t blocks = (int64_t)tiles_m * ceil_div(a.N, BN);
   const size_t lds = gemm_lds_bytes<BM, BN, BK, A_KC, B_KC>();
-  auto kernel = gemm_f32_kernel<BM, BN, BK, WM, WN, A_KC, B_KC, A_VEC, B_VEC>;
+  auto kernel = gemm_f32_kernel<BM, BN, BK, WM, WN, A_KC, B_KC, A_VEC, B_VEC, TI, TO>;
   static bool opted_in = false;  // one flag per instantiation of this launcher, i.e. per kernel
   allow_lds(kernel, lds, opted_in);
   hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kThreads), lds, st, a, tiles_m, (int)blocks);
 }
 
+template <int BM, int BN, int BK, int WM, int WN, bool A_KC, bool B_KC, bool A_VEC, bool B_VEC>
+static void launch_typed(const GemmArgs& a, hipStream_t st) {
+  if (a.in_dtype == VCNN_BF16) {
+    if (a.out_dtype == VCNN_BF16)
+      launch_one<BM, BN, BK, WM, WN, A_KC, B_KC, A_VEC, B_VEC, bf16, bf16>(a, st);
+    else
+      launch_one<BM, BN, BK, WM, WN, A_KC, B_KC, A_VEC, B_VEC, bf16, float>(a, st);
+  } else {
+    launch_one<BM, BN, BK, WM, WN, A_KC, B_KC, A_VEC, B_VEC, float, float>(a, st);
+  }
+}
+
 template <int BM, int BN, int BK, int WM, int WN, bool A_KC, bool B_KC>
 static void launch_vec(const GemmArgs& a, bool av, bool bv, hipStream_t st) {
   if (av && bv)
-    launch_one<BM, BN, BK, WM, WN, A_KC, B_KC, true, true>(a, st);
+    launch_typed<BM, BN, BK, WM, WN, A_KC, B_KC, true, true>(a, st);
   else if (av)
-    launch_one<BM, BN, BK, WM, WN, A_KC, B_KC, true, false>(a, st);
+    launch_typed<BM, BN, BK, WM, WN, A_KC, B_KC, true, false>(a, st);
   else if (bv)
-    launch_one<BM, BN, BK, WM, WN, A_KC, B_KC, false, true>(a, st);
+    launch_typed<BM, BN, BK, WM, WN, A_KC, B_KC, false, true>(a, st);
   else
-    launch_one<BM, BN, BK, WM, WN, A_KC, B_KC, false, false>(a, st);
+    launch_typed<BM, BN, BK, WM, WN, A_KC, B_KC, false, false>(a, st);
 }
 
 template <int BM, int BN, int BK, int WM, int WN>
@@ -197,6 +214,7 @@ static void launch_cfg(const GemmArgs& a, bool a_kc, bool b_kc, bool av, bool bv
 }
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+static bool in_aligned(const void* p, int dtype) { return dtype == VCNN_BF16 ? group_aligned<bf16>(p) : group_aligned<float>(p); }
 
 vcnn_status launch_gemm_f32(const GemmArgs& a, hipStream_t st) {
   if (a.M <= 0 || a.N <= 0 || a.K <= 0) return fail(VCNN_ERR_SHAPE, "gemm: empty operand");
@@ -206,13 +224,13 @@ vcnn_status launch_gemm_f32(const GemmArgs& a, hipStream_t st) {
   // row (or, for the [N][M][P] maps, a sample) boundary.
   bool av, bv;
   if (a_kc)
-    av = aligned16(a.A) && a.a_si % 4 == 0 && a.K % 4 == 0;
+    av = in_aligned(a.A, a.in_dtype) && a.a_si % 4 == 0 && a.K % 4 == 0;
   else
-    av = aligned16(a.A) && a.a_si == 1 && a.a_sk % 4 == 0 && a.M % 4 == 0;
+    av = in_aligned(a.A, a.in_dtype) && a.a_si == 1 && a.a_sk % 4 == 0 && a.M % 4 == 0;
   if (b_kc)
-    bv = aligned16(a.B) && a.b_P == 0 && a.b_sj % 4 == 0 && a.K % 4 == 0;
+    bv = in_aligned(a.B, a.in_dtype) && a.b_P == 0 && a.b_sj % 4 == 0 && a.K % 4 == 0;
   else
-    bv = aligned16(a.B) && a.b_sj == 1 && a.b_sk % 4 == 0 && a.N % 4 == 0 &&
+    bv = in_aligned(a.B, a.in_dtype) && a.b_sj == 1 && a.b_sk % 4 == 0 && a.N % 4 == 0 &&
          (a.b_P == 0 || (a.b_P % 4 == 0 && a.b_simg % 4 == 0));
   // Small products (the fully connected layers at batch 128) would fill only a handful of large
   // tiles; 64x64 tiles spread them over more compute units.
@@ -234,9 +252,9 @@ vcnn_status launch_gemm_f32(const GemmArgs& a, hipStream_t st) {
 // blockIdx.y selects a range of columns; each range writes its own partial product and a second
 // kernel adds the partials in ascending order, which keeps the result independent of scheduling.
 // -------------------------------------------------------------------------------------------------
-template <int BM, int BN, int BK, int WM, int WN, bool VEC>
-__global__ __launch_bounds__(kThreads) void bwd_filter_f32_kernel(ConvGeom g, const float* __restrict__ dy,
-                                                                  const float* __restrict__ col,
+template <int BM, int BN, int BK, int WM, int WN, bool VEC, typename T>
+__global__ __launch_bounds__(kThreads) void bwd_filter_f32_kernel(ConvGeom g, const T* __restrict__ dy,
+                                                                  const T* __restrict__ col,
                                                                   float* __restrict__ out, int tiles_m, int chunk) {
   static_assert((BM / WM) * (BN / WN) * 64 == kThreads, "four waves per block");
   using LA = LdsTile<BM, BK, true>;
@@ -280,24 +298,24 @@ __global__ __launch_bounds__(kThreads) void bwd_filter_f32_kernel(ConvGeom g, co
     for (int e = 0; e < SA::SLOTS; ++e) {
       const int m = i0 + sa.line(e);
       sa.ok[e] = jin && m < M;
-      const float* src = dy + ((int64_t)nn * M + min(m, M - 1)) * P + pp;
+      const T* src = dy + ((int64_t)nn * M + min(m, M - 1)) * P + pp;
       if (VEC) {
-        const float4 t = *reinterpret_cast<const float4*>(src);
+        const float4 t = ld4(src);
         sa.v[e][0] = t.x, sa.v[e][1] = t.y, sa.v[e][2] = t.z, sa.v[e][3] = t.w;
       } else {
-        sa.v[e][0] = *src;
+        sa.v[e][0] = ld(src);
       }
     }
 #pragma unroll
     for (int e = 0; e < SB::SLOTS; ++e) {
       const int k = k0 + sb.line(e);
       sb.ok[e] = jin && k < K;
-      const float* src = col + (int64_t)min(k, K - 1) * g.N + jj;
+      const T* src = col + (int64_t)min(k, K - 1) * g.N + jj;
       if (VEC) {
-        const float4 t = *reinterpret_cast<const float4*>(src);
+        const float4 t = ld4(src);
         sb.v[e][0] = t.x, sb.v[e][1] = t.y, sb.v[e][2] = t.z, sb.v[e][3] = t.w;
       } else {
-        sb.v[e][0] = *src;
+        sb.v[e][0] = ld(src);
       }
     }
     j += BK;
@@ -367,24 +385,29 @@ size_t bwd_filter_partial_bytes(const ConvGeom& g) {
   return splits > 1 ? (size_t)splits * g.M * g.K * sizeof(float) : 0;
 }
 
-template <int BM, int BN, int WM, int WN>
-static void launch_bf(const ConvGeom& g, const float* dy, const float* col, float* out, int tiles_m, int chunk,
-                      dim3 grid, bool vec, hipStream_t st) {
+template <int BM, int BN, int WM, int WN, bool VEC, typename T>
+static void launch_bf_one(const ConvGeom& g, const void* dy, const void* col, float* out, int tiles_m, int chunk,
+                          dim3 grid, hipStream_t st) {
   const size_t lds = gemm_lds_bytes<BM, BN, kBfBK, true, true>();
-  if (vec) {
-    auto kernel = bwd_filter_f32_kernel<BM, BN, kBfBK, WM, WN, true>;
-    static bool opted_in = false;
-    allow_lds(kernel, lds, opted_in);
-    hipLaunchKernelGGL(kernel, grid, dim3(kThreads), lds, st, g, dy, col, out, tiles_m, chunk);
+  auto kernel = bwd_filter_f32_kernel<BM, BN, kBfBK, WM, WN, VEC, T>;
+  static bool opted_in = false;
+  allow_lds(kernel, lds, opted_in);
+  hipLaunchKernelGGL(kernel, grid, dim3(kThreads), lds, st, g, (const T*)dy, (const T*)col, out, tiles_m, chunk);
+}
+
+template <int BM, int BN, int WM, int WN>
+static void launch_bf(const ConvGeom& g, int dtype, const void* dy, const void* col, float* out, int tiles_m, int chunk,
+                      dim3 grid, bool vec, hipStream_t st) {
+  if (dtype == VCNN_BF16) {
+    if (vec) launch_bf_one<BM, BN, WM, WN, true, bf16>(g, dy, col, out, tiles_m, chunk, grid, st);
+    else launch_bf_one<BM, BN, WM, WN, false, bf16>(g, dy, col, out, tiles_m, chunk, grid, st);
   } else {
-    auto kernel = bwd_filter_f32_kernel<BM, BN, kBfBK, WM, WN, false>;
-    static bool opted_in = false;
-    allow_lds(kernel, lds, opted_in);
-    hipLaunchKernelGGL(kernel, grid, dim3(kThreads), lds, st, g, dy, col, out, tiles_m, chunk);
+    if (vec) launch_bf_one<BM, BN, WM, WN, true, float>(g, dy, col, out, tiles_m, chunk, grid, st);
+    else launch_bf_one<BM, BN, WM, WN, false, float>(g, dy, col, out, tiles_m, chunk, grid, st);
   }
 }
 
-vcnn_status launch_bwd_filter_gemm_f32(const ConvGeom& g, const float* dy, const float* col, float* dw,
+vcnn_status launch_bwd_filter_gemm_f32(const ConvGeom& g, int dtype, const void* dy, const void* col, float* dw,
                                        float* partial, hipStream_t st) {
   const int chunk = bwd_filter_chunk(g);
   const int splits = bwd_filter_splits(g);
@@ -394,16 +417,16 @@ vcnn_status launch_bwd_filter_gemm_f32(const ConvGeom& g, const float* dy, const
   const int64_t tiles = (int64_t)tiles_m * ceil_div(g.K, bwd_filter_bn(g));
   const dim3 grid((unsigned)tiles, (unsigned)splits);
   if (splits > 65535) return fail(VCNN_ERR_UNSUPPORTED, "bwd_filter: too many contraction splits");
-  const bool vec = g.P % 4 == 0 && aligned16(dy) && aligned16(col);
+  const bool vec = g.P % 4 == 0 && in_aligned(dy, dtype) && in_aligned(col, dtype);
   if (bm == 32)
-    launch_bf<32, 128, 32, 32>(g, dy, col, out, tiles_m, chunk, grid, vec, st);
+    launch_bf<32, 128, 32, 32>(g, dtype, dy, col, out, tiles_m, chunk, grid, vec, st);
   else if (bm == 64)
-    launch_bf<64, 128, 32, 64>(g, dy, col, out, tiles_m, chunk, grid, vec, st);
+    launch_bf<64, 128, 32, 64>(g, dtype, dy, col, out, tiles_m, chunk, grid, vec, st);
   else
-    launch_bf<128, 128, 64, 64>(g, dy, col, out, tiles_m, chunk, grid, vec, st);
+    launch_bf<128, 128, 64, 64>(g, dtype, dy, col, out, tiles_m, chunk, grid, vec, st);
   vcnn_status s = check_launch("bwd_filter_f32");
   if (s != VCNN_OK || splits == 1) return s;
-  return launch_sum_slices(partial, nullptr, dw, g.M * g.K, splits, 1, 1, 0, st);
+  return launch_sum_slices(partial, nullptr, dw, VCNN_F32, g.M * g.K, splits, 1, 1, 0, st);
 }
 
 }  // namespace vcnn

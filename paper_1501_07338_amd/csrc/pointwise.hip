@@ -1,36 +1,13 @@
 // Bandwidth-bound operators around the convolution: sigma (ReLU), max pooling with argmax record
 // (phi_p of Eq. 3 with the max operation), bias gradient, cost functions and the SGD update.
+// Kernels are templates on the element type of the activation tensors (float or bf16); sums,
+// comparisons and costs are computed on float values.
 #include "common.h"
+#include "elem.h"
 
 namespace vcnn {
 
 static constexpr int kThreads = 256;
-
-// ---- ReLU ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void relu_fwd_f32_kernel(size_t count, const float* x, float* y) {
-  const size_t i = ((size_t)blockIdx.x * kThreads + threadIdx.x) * 4;
-  if (i + 3 < count && ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y)) & 15) == 0) {
-    float4 v = *reinterpret_cast<const float4*>(x + i);
-    v.x = fmaxf(v.x, 0.f), v.y = fmaxf(v.y, 0.f), v.z = fmaxf(v.z, 0.f), v.w = fmaxf(v.w, 0.f);
-    *reinterpret_cast<float4*>(y + i) = v;
-  } else {
-    for (size_t e = i; e < count && e < i + 4; ++e) y[e] = fmaxf(x[e], 0.f);
-  }
-}
-
-__global__ __launch_bounds__(kThreads) void relu_bwd_f32_kernel(size_t count, const float* ref, const float* dy,
-                                                                float* dx) {
-  const size_t i = ((size_t)blockIdx.x * kThreads + threadIdx.x) * 4;
-  const uintptr_t al = reinterpret_cast<uintptr_t>(ref) | reinterpret_cast<uintptr_t>(dy) | reinterpret_cast<uintptr_t>(dx);
-  if (i + 3 < count && (al & 15) == 0) {
-    const float4 r = *reinterpret_cast<const float4*>(ref + i);
-    float4 g = *reinterpret_cast<const float4*>(dy + i);
-    g.x = r.x > 0.f ? g.x : 0.f, g.y = r.y > 0.f ? g.y : 0.f, g.z = r.z > 0.f ? g.z : 0.f, g.w = r.w > 0.f ? g.w : 0.f;
-    *reinterpret_cast<float4*>(dx + i) = g;
-  } else {
-    for (size_t e = i; e < count && e < i + 4; ++e) dx[e] = ref[e] > 0.f ? dy[e] : 0.f;
-  }
-}
 
 static vcnn_status grid_for(size_t work_items, unsigned* blocks) {
   const size_t b = (work_items + kThreads - 1) / kThreads;
@@ -39,55 +16,99 @@ static vcnn_status grid_for(size_t work_items, unsigned* blocks) {
   return VCNN_OK;
 }
 
-vcnn_status launch_relu_fwd_f32(size_t count, const float* x, float* y, hipStream_t st) {
-  unsigned blocks;
-  if (vcnn_status s = grid_for((count + 3) / 4, &blocks)) return s;
-  hipLaunchKernelGGL(relu_fwd_f32_kernel, dim3(blocks), dim3(kThreads), 0, st, count, x, y);
-  return check_launch("relu_fwd_f32");
+// ---- ReLU ---------------------------------------------------------------------------------------
+// Four elements per thread (16-byte / 8-byte accesses) when the tensors are aligned; the ragged
+// tail and unaligned tensors take the scalar path.  In-place use (y == x, dx == dy) is allowed, so no
+// __restrict__ here.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void relu_fwd_kernel(size_t count, const T* x, T* y, int vec) {
+  const size_t i = ((size_t)blockIdx.x * kThreads + threadIdx.x) * 4;
+  if (vec && i + 3 < count) {
+    float4 v = ld4(x + i);
+    v.x = fmaxf(v.x, 0.f), v.y = fmaxf(v.y, 0.f), v.z = fmaxf(v.z, 0.f), v.w = fmaxf(v.w, 0.f);
+    st4(y + i, v);
+  } else {
+    for (size_t e = i; e < count && e < i + 4; ++e) st(y + e, fmaxf(ld(x + e), 0.f));
+  }
 }
 
-vcnn_status launch_relu_bwd_f32(size_t count, const float* ref, const float* dy, float* dx, hipStream_t st) {
+template <typename T>
+__global__ __launch_bounds__(kThreads) void relu_bwd_kernel(size_t count, const T* ref, const T* dy, T* dx, int vec) {
+  const size_t i = ((size_t)blockIdx.x * kThreads + threadIdx.x) * 4;
+  if (vec && i + 3 < count) {
+    const float4 r = ld4(ref + i);
+    float4 g = ld4(dy + i);
+    g.x = r.x > 0.f ? g.x : 0.f, g.y = r.y > 0.f ? g.y : 0.f, g.z = r.z > 0.f ? g.z : 0.f, g.w = r.w > 0.f ? g.w : 0.f;
+    st4(dx + i, g);
+  } else {
+    for (size_t e = i; e < count && e < i + 4; ++e) st(dx + e, ld(ref + e) > 0.f ? ld(dy + e) : 0.f);
+  }
+}
+
+template <typename T>
+static vcnn_status relu_fwd_typed(size_t count, const void* x, void* y, hipStream_t st) {
   unsigned blocks;
   if (vcnn_status s = grid_for((count + 3) / 4, &blocks)) return s;
-  hipLaunchKernelGGL(relu_bwd_f32_kernel, dim3(blocks), dim3(kThreads), 0, st, count, ref, dy, dx);
-  return check_launch("relu_bwd_f32");
+  const int vec = group_aligned<T>(x) && group_aligned<T>(y);
+  hipLaunchKernelGGL(relu_fwd_kernel<T>, dim3(blocks), dim3(kThreads), 0, st, count, (const T*)x, (T*)y, vec);
+  return check_launch("relu_fwd");
+}
+
+template <typename T>
+static vcnn_status relu_bwd_typed(size_t count, const void* ref, const void* dy, void* dx, hipStream_t st) {
+  unsigned blocks;
+  if (vcnn_status s = grid_for((count + 3) / 4, &blocks)) return s;
+  const int vec = group_aligned<T>(ref) && group_aligned<T>(dy) && group_aligned<T>(dx);
+  hipLaunchKernelGGL(relu_bwd_kernel<T>, dim3(blocks), dim3(kThreads), 0, st, count, (const T*)ref, (const T*)dy, (T*)dx,
+                     vec);
+  return check_launch("relu_bwd");
+}
+
+vcnn_status launch_relu_fwd(int dtype, size_t count, const void* x, void* y, hipStream_t st) {
+  return dtype == VCNN_BF16 ? relu_fwd_typed<bf16>(count, x, y, st) : relu_fwd_typed<float>(count, x, y, st);
+}
+
+vcnn_status launch_relu_bwd(int dtype, size_t count, const void* ref, const void* dy, void* dx, hipStream_t st) {
+  return dtype == VCNN_BF16 ? relu_bwd_typed<bf16>(count, ref, dy, dx, st) : relu_bwd_typed<float>(count, ref, dy, dx, st);
 }
 
 // ---- max pooling --------------------------------------------------------------------------------
 // One thread per output element, ow fastest.  Row-major scan with a strict '>' keeps the lowest
 // flat index among equal maxima.
-__global__ __launch_bounds__(kThreads) void pool_fwd_f32_kernel(vcnn_pool_desc d, int oh_n, int ow_n,
-                                                                const float* __restrict__ x, float* __restrict__ y,
-                                                                int32_t* __restrict__ argmax, int64_t total) {
+template <typename T>
+__global__ __launch_bounds__(kThreads) void pool_fwd_kernel(vcnn_pool_desc d, int oh_n, int ow_n,
+                                                            const T* __restrict__ x, T* __restrict__ y,
+                                                            int32_t* __restrict__ argmax, int64_t total) {
   const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   if (idx >= total) return;
   const int ow = (int)(idx % ow_n);
   const int64_t t = idx / ow_n;
   const int oh = (int)(t % oh_n);
   const int64_t nc = t / oh_n;
-  const float* xp = x + nc * d.h * d.w;
+  const T* xp = x + nc * d.h * d.w;
   const int h0 = oh * d.stride_h, w0 = ow * d.stride_w;
-  float best = xp[h0 * d.w + w0];
+  float best = ld(xp + h0 * d.w + w0);
   int bi = h0 * d.w + w0;
   for (int i = 0; i < d.win_h; ++i)
     for (int j = 0; j < d.win_w; ++j) {
       const int pos = (h0 + i) * d.w + w0 + j;
-      const float v = xp[pos];
+      const float v = ld(xp + pos);
       if (v > best) {
         best = v;
         bi = pos;
       }
     }
-  y[idx] = best;
+  st(y + idx, best);
   argmax[idx] = bi;
 }
 
 // One thread per input element: sums, in ascending window order, the gradients of the windows that
 // cover it and recorded it.  Gather form, so no atomics and every dx element is written.
-__global__ __launch_bounds__(kThreads) void pool_bwd_f32_kernel(vcnn_pool_desc d, int oh_n, int ow_n,
-                                                                const float* __restrict__ dy,
-                                                                const int32_t* __restrict__ argmax,
-                                                                float* __restrict__ dx, int64_t total) {
+template <typename T>
+__global__ __launch_bounds__(kThreads) void pool_bwd_kernel(vcnn_pool_desc d, int oh_n, int ow_n,
+                                                            const T* __restrict__ dy,
+                                                            const int32_t* __restrict__ argmax, T* __restrict__ dx,
+                                                            int64_t total) {
   const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   if (idx >= total) return;
   const int wi = (int)(idx % d.w);
@@ -107,34 +128,45 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_f32_kernel(vcnn_pool_desc d
   for (int oh = oh_lo; oh <= oh_hi; ++oh)
     for (int ow = ow_lo; ow <= ow_hi; ++ow) {
       const int64_t o = base + (int64_t)oh * ow_n + ow;
-      if (argmax[o] == pos) acc += dy[o];
+      if (argmax[o] == pos) acc += ld(dy + o);
     }
-  dx[idx] = acc;
+  st(dx + idx, acc);
 }
 
-vcnn_status launch_pool_fwd_f32(const vcnn_pool_desc& d, int oh, int ow, const float* x, float* y, int32_t* argmax,
-                                hipStream_t st) {
+vcnn_status launch_pool_fwd(const vcnn_pool_desc& d, int oh, int ow, const void* x, void* y, int32_t* argmax,
+                            hipStream_t st) {
   const int64_t total = (int64_t)d.n * d.c * oh * ow;
   unsigned blocks;
   if (vcnn_status s = grid_for((size_t)total, &blocks)) return s;
-  hipLaunchKernelGGL(pool_fwd_f32_kernel, dim3(blocks), dim3(kThreads), 0, st, d, oh, ow, x, y, argmax, total);
-  return check_launch("pool_fwd_f32");
+  if (d.dtype == VCNN_BF16)
+    hipLaunchKernelGGL(pool_fwd_kernel<bf16>, dim3(blocks), dim3(kThreads), 0, st, d, oh, ow, (const bf16*)x, (bf16*)y,
+                       argmax, total);
+  else
+    hipLaunchKernelGGL(pool_fwd_kernel<float>, dim3(blocks), dim3(kThreads), 0, st, d, oh, ow, (const float*)x, (float*)y,
+                       argmax, total);
+  return check_launch("pool_fwd");
 }
 
-vcnn_status launch_pool_bwd_f32(const vcnn_pool_desc& d, int oh, int ow, const float* dy, const int32_t* argmax,
-                                float* dx, hipStream_t st) {
+vcnn_status launch_pool_bwd(const vcnn_pool_desc& d, int oh, int ow, const void* dy, const int32_t* argmax, void* dx,
+                            hipStream_t st) {
   const int64_t total = (int64_t)d.n * d.c * d.h * d.w;
   unsigned blocks;
   if (vcnn_status s = grid_for((size_t)total, &blocks)) return s;
-  hipLaunchKernelGGL(pool_bwd_f32_kernel, dim3(blocks), dim3(kThreads), 0, st, d, oh, ow, dy, argmax, dx, total);
-  return check_launch("pool_bwd_f32");
+  if (d.dtype == VCNN_BF16)
+    hipLaunchKernelGGL(pool_bwd_kernel<bf16>, dim3(blocks), dim3(kThreads), 0, st, d, oh, ow, (const bf16*)dy, argmax,
+                       (bf16*)dx, total);
+  else
+    hipLaunchKernelGGL(pool_bwd_kernel<float>, dim3(blocks), dim3(kThreads), 0, st, d, oh, ow, (const float*)dy, argmax,
+                       (float*)dx, total);
+  return check_launch("pool_bwd");
 }
 
 // ---- block reduction in a fixed order --------------------------------------------------------------
+template <int THREADS>
 __device__ __forceinline__ float block_sum(float v, float* sm) {
   sm[threadIdx.x] = v;
   __syncthreads();
-  for (int s = kThreads / 2; s > 0; s >>= 1) {
+  for (int s = THREADS / 2; s > 0; s >>= 1) {
     if ((int)threadIdx.x < s) sm[threadIdx.x] += sm[threadIdx.x + s];
     __syncthreads();
   }
@@ -146,22 +178,24 @@ __device__ __forceinline__ float block_sum(float v, float* sm) {
 // db[m] = sum over samples and positions of dy[n][m][p].  Stage 1: block (m, slice) sums the samples of
 // its slice, four independent loads in flight per thread, then the fixed block tree; stage 2 adds the
 // slices in ascending order.  With one slice stage 1 writes db directly.
-__global__ __launch_bounds__(kThreads) void bias_grad_f32_kernel(int n, int M, int64_t P, int per_slice,
-                                                                 const float* __restrict__ dy, float* __restrict__ out) {
+template <typename T>
+__global__ __launch_bounds__(kThreads) void bias_grad_kernel(int n, int M, int64_t P, int per_slice,
+                                                             const T* __restrict__ dy, float* __restrict__ out) {
   __shared__ float sm[kThreads];
   const int m = blockIdx.x, slice = blockIdx.y;
   const int n0 = slice * per_slice, n1 = min(n, n0 + per_slice);
   float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
   for (int i = n0; i < n1; ++i) {
-    const float* row = dy + ((int64_t)i * M + m) * P;
+    const T* row = dy + ((int64_t)i * M + m) * P;
     int64_t p = threadIdx.x;
     for (; p + 3 * kThreads < P; p += 4 * kThreads) {
-      const float v0 = row[p], v1 = row[p + kThreads], v2 = row[p + 2 * kThreads], v3 = row[p + 3 * kThreads];
+      const float v0 = ld(row + p), v1 = ld(row + p + kThreads), v2 = ld(row + p + 2 * kThreads),
+                  v3 = ld(row + p + 3 * kThreads);
       a0 += v0, a1 += v1, a2 += v2, a3 += v3;
     }
-    for (; p < P; p += kThreads) a0 += row[p];
+    for (; p < P; p += kThreads) a0 += ld(row + p);
   }
-  const float total = block_sum((a0 + a1) + (a2 + a3), sm);
+  const float total = block_sum<kThreads>((a0 + a1) + (a2 + a3), sm);
   if (threadIdx.x == 0) out[(int64_t)slice * M + m] = total;
 }
 
@@ -185,40 +219,47 @@ size_t bias_grad_partial_bytes(const ConvGeom& g) {
   return s > 1 ? (size_t)s * g.M * sizeof(float) : 0;
 }
 
-vcnn_status launch_bias_grad_f32(const ConvGeom& g, const float* dy, float* db, float* partial, hipStream_t st) {
+vcnn_status launch_bias_grad(const ConvGeom& g, int dtype, const void* dy, float* db, float* partial, hipStream_t st) {
   const int want = bias_grad_slices(g);
   const int per = (int)ceil_div(g.n, want);
   const int slices = (int)ceil_div(g.n, per);
   float* out = slices > 1 ? partial : db;
-  hipLaunchKernelGGL(bias_grad_f32_kernel, dim3((unsigned)g.M, (unsigned)slices), dim3(kThreads), 0, st, g.n, (int)g.M,
-                     g.P, per, dy, out);
-  if (vcnn_status s = check_launch("bias_grad_f32")) return s;
+  const dim3 grid((unsigned)g.M, (unsigned)slices), block(kThreads);
+  if (dtype == VCNN_BF16)
+    hipLaunchKernelGGL(bias_grad_kernel<bf16>, grid, block, 0, st, g.n, (int)g.M, g.P, per, (const bf16*)dy, out);
+  else
+    hipLaunchKernelGGL(bias_grad_kernel<float>, grid, block, 0, st, g.n, (int)g.M, g.P, per, (const float*)dy, out);
+  if (vcnn_status s = check_launch("bias_grad")) return s;
   if (slices == 1) return VCNN_OK;
-  hipLaunchKernelGGL(bias_grad_finish_kernel, dim3((unsigned)ceil_div(g.M, kThreads)), dim3(kThreads), 0, st, (int)g.M,
-                     slices, partial, db);
+  hipLaunchKernelGGL(bias_grad_finish_kernel, dim3((unsigned)ceil_div(g.M, kThreads)), block, 0, st, (int)g.M, slices,
+                     partial, db);
   return check_launch("bias_grad_finish");
 }
 
 // out[c] = sum_r a[r][c]  (fully connected bias gradient): one thread per column, rows in order.
-__global__ __launch_bounds__(kThreads) void col_sum_f32_kernel(int rows, int cols, const float* __restrict__ a,
-                                                               float* __restrict__ out) {
+template <typename T>
+__global__ __launch_bounds__(kThreads) void col_sum_kernel(int rows, int cols, const T* __restrict__ a,
+                                                           float* __restrict__ out) {
   const int c = blockIdx.x * kThreads + threadIdx.x;
   if (c >= cols) return;
   float acc = 0.f;
   int r = 0;
   for (; r + 4 <= rows; r += 4) {  // four independent loads in flight, added in ascending order
-    const float v0 = a[(int64_t)r * cols + c], v1 = a[(int64_t)(r + 1) * cols + c];
-    const float v2 = a[(int64_t)(r + 2) * cols + c], v3 = a[(int64_t)(r + 3) * cols + c];
+    const float v0 = ld(a + (int64_t)r * cols + c), v1 = ld(a + (int64_t)(r + 1) * cols + c);
+    const float v2 = ld(a + (int64_t)(r + 2) * cols + c), v3 = ld(a + (int64_t)(r + 3) * cols + c);
     acc = (((acc + v0) + v1) + v2) + v3;
   }
-  for (; r < rows; ++r) acc += a[(int64_t)r * cols + c];
+  for (; r < rows; ++r) acc += ld(a + (int64_t)r * cols + c);
   out[c] = acc;
 }
 
-vcnn_status launch_col_sum_f32(int rows, int cols, const float* a, float* out, hipStream_t st) {
-  hipLaunchKernelGGL(col_sum_f32_kernel, dim3((unsigned)ceil_div(cols, kThreads)), dim3(kThreads), 0, st, rows, cols,
-                     a, out);
-  return check_launch("col_sum_f32");
+vcnn_status launch_col_sum(int dtype, int rows, int cols, const void* a, float* out, hipStream_t st) {
+  const dim3 grid((unsigned)ceil_div(cols, kThreads)), block(kThreads);
+  if (dtype == VCNN_BF16)
+    hipLaunchKernelGGL(col_sum_kernel<bf16>, grid, block, 0, st, rows, cols, (const bf16*)a, out);
+  else
+    hipLaunchKernelGGL(col_sum_kernel<float>, grid, block, 0, st, rows, cols, (const float*)a, out);
+  return check_launch("col_sum");
 }
 
 // ---- costs --------------------------------------------------------------------------------------
@@ -243,7 +284,7 @@ __global__ __launch_bounds__(kThreads) void softmax_loss_f32_kernel(int batch, i
       for (int j = 0; j < classes; ++j)
         dz[(int64_t)b * classes + j] = (expf(zb[j] - lse) - (j == lab ? 1.f : 0.f)) * inv_b;
   }
-  const float total = block_sum(acc, sm);
+  const float total = block_sum<kThreads>(acc, sm);
   if (threadIdx.x == 0 && loss) *loss = total * inv_b;
 }
 
@@ -253,41 +294,53 @@ vcnn_status launch_softmax_loss_f32(int batch, int classes, const float* z, cons
   return check_launch("softmax_loss_f32");
 }
 
-__global__ __launch_bounds__(kThreads) void l2_grad_f32_kernel(size_t count, float inv_b, const float* __restrict__ y,
-                                                               const float* __restrict__ t, float* __restrict__ dy) {
+template <typename T>
+__global__ __launch_bounds__(kThreads) void l2_grad_kernel(size_t count, float inv_b, const T* __restrict__ y,
+                                                           const float* __restrict__ t, T* __restrict__ dy) {
   const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
-  if (i < count) dy[i] = (y[i] - t[i]) * inv_b;
+  if (i < count) st(dy + i, (ld(y + i) - t[i]) * inv_b);
 }
 
 static constexpr int kL2Threads = 1024;
-__global__ __launch_bounds__(kL2Threads) void l2_loss_f32_kernel(size_t count, float scale, const float* __restrict__ y,
-                                                                 const float* __restrict__ t, float* __restrict__ loss) {
+template <typename T>
+__global__ __launch_bounds__(kL2Threads) void l2_loss_kernel(size_t count, float scale, const T* __restrict__ y,
+                                                             const float* __restrict__ t, float* __restrict__ loss) {
   __shared__ float sm[kL2Threads];
-  float acc = 0.f;
-  for (size_t i = threadIdx.x; i < count; i += kL2Threads) {
-    const float dlt = y[i] - t[i];
-    acc += dlt * dlt;
+  float a0 = 0.f, a1 = 0.f;
+  size_t i = threadIdx.x;
+  for (; i + kL2Threads < count; i += 2 * kL2Threads) {  // two independent loads in flight
+    const float d0 = ld(y + i) - t[i], d1 = ld(y + i + kL2Threads) - t[i + kL2Threads];
+    a0 += d0 * d0, a1 += d1 * d1;
   }
-  sm[threadIdx.x] = acc;
-  __syncthreads();
-  for (int s = kL2Threads / 2; s > 0; s >>= 1) {
-    if ((int)threadIdx.x < s) sm[threadIdx.x] += sm[threadIdx.x + s];
-    __syncthreads();
+  for (; i < count; i += kL2Threads) {
+    const float d0 = ld(y + i) - t[i];
+    a0 += d0 * d0;
   }
-  if (threadIdx.x == 0) *loss = sm[0] * scale;
+  const float total = block_sum<kL2Threads>(a0 + a1, sm);
+  if (threadIdx.x == 0) *loss = total * scale;
 }
 
-vcnn_status launch_l2_loss_f32(size_t count, int batch, const float* y, const float* t, float* loss, float* dy,
-                               hipStream_t st) {
+vcnn_status launch_l2_loss(int dtype, size_t count, int batch, const void* y, const float* t, float* loss, void* dy,
+                           hipStream_t st) {
   if (dy) {
     unsigned blocks;
     if (vcnn_status s = grid_for(count, &blocks)) return s;
-    hipLaunchKernelGGL(l2_grad_f32_kernel, dim3(blocks), dim3(kThreads), 0, st, count, 1.f / (float)batch, y, t, dy);
-    if (vcnn_status s = check_launch("l2_grad_f32")) return s;
+    if (dtype == VCNN_BF16)
+      hipLaunchKernelGGL(l2_grad_kernel<bf16>, dim3(blocks), dim3(kThreads), 0, st, count, 1.f / (float)batch,
+                         (const bf16*)y, t, (bf16*)dy);
+    else
+      hipLaunchKernelGGL(l2_grad_kernel<float>, dim3(blocks), dim3(kThreads), 0, st, count, 1.f / (float)batch,
+                         (const float*)y, t, (float*)dy);
+    if (vcnn_status s = check_launch("l2_grad")) return s;
   }
   if (loss) {
-    hipLaunchKernelGGL(l2_loss_f32_kernel, dim3(1), dim3(kL2Threads), 0, st, count, 0.5f / (float)batch, y, t, loss);
-    return check_launch("l2_loss_f32");
+    if (dtype == VCNN_BF16)
+      hipLaunchKernelGGL(l2_loss_kernel<bf16>, dim3(1), dim3(kL2Threads), 0, st, count, 0.5f / (float)batch,
+                         (const bf16*)y, t, loss);
+    else
+      hipLaunchKernelGGL(l2_loss_kernel<float>, dim3(1), dim3(kL2Threads), 0, st, count, 0.5f / (float)batch,
+                         (const float*)y, t, loss);
+    return check_launch("l2_loss");
   }
   return VCNN_OK;
 }
@@ -307,36 +360,30 @@ vcnn_status launch_sgd_f32(size_t count, float lr, float* w, const float* dw, hi
 }
 
 // ---- bfloat16 conversion --------------------------------------------------------------------------
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // quiet NaN
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
-
 __global__ __launch_bounds__(kThreads) void f32_to_bf16_kernel(size_t count, const float* __restrict__ src,
-                                                               uint16_t* __restrict__ dst) {
+                                                               bf16* __restrict__ dst) {
   const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
-  if (i < count) dst[i] = f32_to_bf16_rne(src[i]);
+  if (i < count) st(dst + i, src[i]);
 }
 
-__global__ __launch_bounds__(kThreads) void bf16_to_f32_kernel(size_t count, const uint16_t* __restrict__ src,
+__global__ __launch_bounds__(kThreads) void bf16_to_f32_kernel(size_t count, const bf16* __restrict__ src,
                                                                float* __restrict__ dst) {
   const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
-  if (i < count) dst[i] = __uint_as_float((uint32_t)src[i] << 16);
+  if (i < count) dst[i] = ld(src + i);
 }
 
 vcnn_status launch_f32_to_bf16(size_t count, const float* src, uint16_t* dst, hipStream_t st) {
   unsigned blocks;
   if (vcnn_status s = grid_for(count, &blocks)) return s;
-  hipLaunchKernelGGL(f32_to_bf16_kernel, dim3(blocks), dim3(kThreads), 0, st, count, src, dst);
+  hipLaunchKernelGGL(f32_to_bf16_kernel, dim3(blocks), dim3(kThreads), 0, st, count, src, reinterpret_cast<bf16*>(dst));
   return check_launch("f32_to_bf16");
 }
 
 vcnn_status launch_bf16_to_f32(size_t count, const uint16_t* src, float* dst, hipStream_t st) {
   unsigned blocks;
   if (vcnn_status s = grid_for(count, &blocks)) return s;
-  hipLaunchKernelGGL(bf16_to_f32_kernel, dim3(blocks), dim3(kThreads), 0, st, count, src, dst);
+  hipLaunchKernelGGL(bf16_to_f32_kernel, dim3(blocks), dim3(kThreads), 0, st, count, reinterpret_cast<const bf16*>(src),
+                     dst);
   return check_launch("bf16_to_f32");
 }
 

@@ -18,12 +18,16 @@ class TrainStep:
 
     def __init__(self, net: Net, params: list, inputs: dict, device: str = "cuda:0", first_layer_dx: bool = False,
                  dtype: int = vcnn.F32):
-        if dtype != vcnn.F32:
-            raise NotImplementedError("only the fp32 chain is wired up")
         self.net, self.dev, self.dtype = net, torch.device(device), dtype
         self.first_layer_dx = first_layer_dx
         f32 = dict(dtype=torch.float32, device=self.dev)
+        # element type of activations and their gradients; parameters, their gradients and the loss stay fp32
+        act = dict(dtype=torch.bfloat16 if dtype == vcnn.BF16 else torch.float32, device=self.dev)
         self.x = torch.from_numpy(np.ascontiguousarray(inputs["x"])).to(self.dev)
+        if dtype == vcnn.BF16:  # a storage-format change of the given input, done by the library's own kernel
+            x16 = torch.empty(self.x.shape, **act)
+            vcnn.f32_to_bf16(self.x.numel(), self.x, x16)
+            self.x = x16
         self.labels = torch.from_numpy(inputs["labels"]).to(self.dev) if "labels" in inputs else None
         self.target = torch.from_numpy(inputs["target"]).to(self.dev) if "target" in inputs else None
         self.upstream = torch.from_numpy(inputs["upstream"]).to(self.dev) if "upstream" in inputs else None
@@ -31,7 +35,9 @@ class TrainStep:
             None if p is None else (torch.from_numpy(p[0]).to(self.dev), torch.from_numpy(p[1]).to(self.dev))
             for p in params]
         self.grads = [None if p is None else (torch.empty_like(p[0]), torch.empty_like(p[1])) for p in self.params]
-        self.acts = [self.x] + [torch.empty(s, **f32) for s in net.shapes]
+        # bf16 variant: fp32 master weights plus a bf16 copy refreshed after every update
+        self.params16 = [None if p is None or dtype != vcnn.BF16 else torch.empty(p[0].shape, **act) for p in self.params]
+        self.acts = [self.x] + [torch.empty(s, **act) for s in net.shapes]
         self.dacts = [torch.empty_like(a) for a in self.acts]
         self.argmax = {li: torch.empty(net.shapes[li], dtype=torch.int32, device=self.dev)
                        for li, L in enumerate(net.layers) if isinstance(L, Pool)}
@@ -52,7 +58,21 @@ class TrainStep:
             if getattr(L, "relu", False):
                 dpre_elems = max(dpre_elems, int(np.prod(net.shapes[li])))
         self.workspace = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=self.dev)
-        self.dpre = torch.empty(max(dpre_elems, 1), **f32)
+        self.dpre = torch.empty(max(dpre_elems, 1), **act)
+        if dtype == vcnn.BF16 and net.loss == "softmax":  # the cost works on float logits
+            self.logits32 = torch.empty(net.out_shape, **f32)
+            self.dlogits32 = torch.empty(net.out_shape, **f32)
+        self.refresh_weights()
+
+    def weights(self, li):
+        """The weight tensor the layer kernels read: the fp32 parameters, or their bf16 copy."""
+        return self.params16[li] if self.dtype == vcnn.BF16 else self.params[li][0]
+
+    def refresh_weights(self, stream=None):
+        if self.dtype == vcnn.BF16:
+            for p, p16 in zip(self.params, self.params16):
+                if p is not None:
+                    vcnn.f32_to_bf16(p[0].numel(), p[0], p16, stream)
 
     # ---- one pass each ---------------------------------------------------------------------------
     def forward(self, stream=None):
@@ -60,24 +80,31 @@ class TrainStep:
         for li, L in enumerate(net.layers):
             a_in, a_out = self.acts[li], self.acts[li + 1]
             if isinstance(L, Conv):
-                w, b = self.params[li]
+                w, b = self.weights(li), self.params[li][1]
                 vcnn.conv_fwd(self.descs[li], a_in, w, b, a_out, self.workspace, stream)
             elif isinstance(L, Pool):
                 vcnn.pool_fwd(self.descs[li], a_in, a_out, self.argmax[li], stream)
             else:
-                w, b = self.params[li]
+                w, b = self.weights(li), self.params[li][1]
                 bsz = a_in.shape[0]
                 vcnn.fc_fwd(self.dtype, bsz, a_in.numel() // bsz, L.out, vcnn.ACT_RELU if L.relu else vcnn.ACT_NONE,
                             a_in, w, b, a_out, stream)
 
     def cost(self, stream=None):
         net, out, dout = self.net, self.acts[-1], self.dacts[-1]
-        if net.loss == "softmax":
+        if net.loss == "softmax" and self.dtype == vcnn.BF16:
+            vcnn.bf16_to_f32(out.numel(), out, self.logits32, stream)
+            vcnn.softmax_loss(out.shape[0], out.shape[1], self.logits32, self.labels, self.loss, self.dlogits32, stream)
+            vcnn.f32_to_bf16(out.numel(), self.dlogits32, dout, stream)
+        elif net.loss == "softmax":
             vcnn.softmax_loss(out.shape[0], out.shape[1], out, self.labels, self.loss, dout, stream)
         elif net.loss == "l2":
             vcnn.l2_loss(self.dtype, out.numel(), out.shape[0], out, self.target, self.loss, dout, stream)
         elif net.loss == "upstream":
-            dout.copy_(self.upstream)  # a device-to-device copy of the given gradient, no arithmetic
+            if self.dtype == vcnn.BF16:
+                vcnn.f32_to_bf16(dout.numel(), self.upstream, dout, stream)
+            else:
+                dout.copy_(self.upstream)  # a device-to-device copy of the given gradient, no arithmetic
         else:
             raise ValueError(net.loss)
 
@@ -92,7 +119,7 @@ class TrainStep:
                 vcnn.act_bwd(vcnn.ACT_RELU, self.dtype, d.numel(), a_out, d, dpre, stream)
                 d = dpre
             if isinstance(L, Conv):
-                w, _ = self.params[li]
+                w = self.weights(li)
                 dw, db = self.grads[li]
                 vcnn.conv_bwd_filter(self.descs[li], a_in, d, dw, db, self.workspace, stream)
                 if need_dx:
@@ -101,7 +128,7 @@ class TrainStep:
                 if need_dx:
                     vcnn.pool_bwd(self.descs[li], d, self.argmax[li], self.dacts[li], stream)
             else:
-                w, _ = self.params[li]
+                w = self.weights(li)
                 dw, db = self.grads[li]
                 bsz = a_in.shape[0]
                 vcnn.fc_bwd(self.dtype, bsz, a_in.numel() // bsz, L.out, a_in, w, d, dw, db,
@@ -112,6 +139,7 @@ class TrainStep:
             if p is not None:
                 vcnn.sgd_update(p[0].numel(), self.net.lr, p[0], g[0], stream)
                 vcnn.sgd_update(p[1].numel(), self.net.lr, p[1], g[1], stream)
+        self.refresh_weights(stream)
 
     def step(self, stream=None):
         self.forward(stream)
