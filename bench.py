@@ -78,13 +78,16 @@ def timed_steps(fn, steps, stream):
 
 
 def run_workload(name, steps, warmup, layer_iters=10):
+    """`name` is a workload, optionally suffixed `_bf16` for the bfloat16-storage variant."""
     import torch
     from paper_1501_07338_amd import vcnn, workloads as wl
     from paper_1501_07338_amd.net import TrainStep
 
-    net = wl.make_net(name)
+    bf16 = name.endswith("_bf16")
+    net = wl.make_net(name[:-5] if bf16 else name)
     inputs, params = wl.make_inputs(net), wl.make_params(net)
-    ts = TrainStep(net, params, inputs, device="cuda:0", first_layer_dx=False)
+    ts = TrainStep(net, params, inputs, device="cuda:0", first_layer_dx=False, dtype=vcnn.BF16 if bf16 else vcnn.F32)
+    esize = 2.0 if bf16 else 4.0
     stream = torch.cuda.current_stream()
     for _ in range(warmup):
         ts.step()
@@ -93,7 +96,7 @@ def run_workload(name, steps, warmup, layer_iters=10):
     for _ in range(warmup):
         graph.replay()
     graph_ms = timed_steps(graph.replay, steps, stream)
-    res = {"workload": name, "batch": net.batch, "ms_per_step": graph_ms, "ms_per_step_eager": eager_ms,
+    res = {"workload": name, "batch": net.batch, "storage_dtype": "bf16" if bf16 else "f32", "ms_per_step": graph_ms, "ms_per_step_eager": eager_ms,
            "images_per_s": net.batch / (graph_ms * 1e-3), "images_per_s_eager": net.batch / (eager_ms * 1e-3),
            "loss_after_timed_steps": float(ts.loss.item())}
 
@@ -104,7 +107,7 @@ def run_workload(name, steps, warmup, layer_iters=10):
             continue
         g = conv_geom(net, li)
         d = ts.descs[li]
-        w, b = ts.params[li]
+        w, b = ts.weights(li), ts.params[li][1]
         dw, db = ts.grads[li]
         a_in, a_out, dy = ts.acts[li], ts.acts[li + 1], ts.dacts[li + 1]
         flops = 2.0 * g["M"] * g["K"] * g["N"]
@@ -113,9 +116,9 @@ def run_workload(name, steps, warmup, layer_iters=10):
             "bwd_filter": lambda: vcnn.conv_bwd_filter(d, a_in, dy, dw, db, ts.workspace),
             "bwd_data": lambda: vcnn.conv_bwd_data(d, w, dy, ts.dacts[li], ts.workspace),
         }
-        in_b = 4.0 * g["n"] * g["c"] * g["h"] * g["w"]
-        out_b = 4.0 * g["M"] * g["N"]
-        w_b = 4.0 * g["M"] * g["K"]
+        in_b = esize * g["n"] * g["c"] * g["h"] * g["w"]
+        out_b = esize * g["M"] * g["N"]
+        w_b = esize * g["M"] * g["K"]
         for pname, fn in passes.items():
             t = time_calls(fn, layer_iters, stream)
             layers.append({"layer": f"conv{li}", "pass": pname, "M": g["M"], "K": g["K"], "N": g["N"], "ms": t,
@@ -185,7 +188,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg2")
-    ap.add_argument("--others", default="cfg1,cfg3,cfg4,cfg5", help="comma list of further workloads to report ('' for none)")
+    ap.add_argument("--others", default="cfg1,cfg3,cfg4,cfg5,cfg5_bf16", help="comma list of further workloads to report ('' for none)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -200,7 +203,7 @@ def main():
     main_res = run_workload(args.workload, args.steps, args.warmup)
     others = {}
     for name in [s for s in args.others.split(",") if s and s != args.workload]:
-        big = name in ("cfg4", "cfg5")
+        big = name.startswith(("cfg4", "cfg5"))
         others[name] = run_workload(name, max(3, min(args.steps, 20)) if big else args.steps,
                                     max(2, min(args.warmup, 3)) if big else args.warmup, layer_iters=5 if big else 10)
         torch.cuda.empty_cache()

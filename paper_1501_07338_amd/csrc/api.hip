@@ -113,7 +113,7 @@ static Plan make_plan(const ConvGeom& g, int pass) {
       p.workspace_bytes = align256(p.partial_bytes);
     } else if (is_pointwise(g)) {
       p.path = PATH_POINTWISE;
-    } else if (allow_direct && (g.c > 4 || algo == VCNN_ALGO_IMPLICIT) &&
+    } else if (allow_direct && (g.c > 4 || g.k >= 32 || algo == VCNN_ALGO_IMPLICIT) &&
                conv_halo_plan(g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, &p.hp)) {
       p.path = PATH_HALO;
     } else if (allow_direct && g.c <= 4 && direct_fwd_geom(g, &p.dg) && direct_few_in_plan(&p.dg, &p.split)) {
@@ -144,7 +144,7 @@ static Plan make_plan(const ConvGeom& g, int pass) {
     if (allow_direct && g.k <= 4 && direct_filter_grad_plan(g, &p.dg, &p.split, &p.partial_bytes)) {
       p.path = PATH_DIRECT_FILTER;
       p.workspace_bytes = align256(p.partial_bytes);
-    } else if (allow_direct && (g.c > 4 || algo == VCNN_ALGO_IMPLICIT) && conv_halo_filter_plan(g, &p.hfp)) {
+    } else if (allow_direct && (g.c > 4 || g.k >= 32 || algo == VCNN_ALGO_IMPLICIT) && conv_halo_filter_plan(g, &p.hfp)) {
       p.path = PATH_HALO_FILTER;
       p.workspace_bytes = align256(p.hfp.partial_bytes);
     } else if (allow_direct && direct_filter_grad_plan(g, &p.dg, &p.split, &p.partial_bytes)) {
