@@ -90,23 +90,47 @@ static bool halo_bwd_data_pays(const ConvGeom& g, const HaloPlan& hp) {
 
 // Which realisation a pass uses for a given shape.  The same decision drives the workspace query and
 // the launch, so the two always agree.
-enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER, PATH_HALO, PATH_HALO_FILTER };
+enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER, PATH_HALO, PATH_HALO_FILTER, PATH_HALO_BF16, PATH_FILTER_BF16 };
 struct Plan {
   Path path;
   DirectGeom dg;
   HaloPlan hp;
   HaloFilterPlan hfp;
+  HaloBf16Plan hb;
+  BwdFilterBf16Plan fb;
   int split;        // channel slices (few-out), output-map group size (few-in) or batch slices (filter gradient)
   size_t partial_bytes;
   size_t workspace_bytes;
   size_t bias_offset;  // filter-gradient pass: where the bias-gradient partial sums live in the workspace
 };
 
-static Plan make_plan(const ConvGeom& g, int pass) {
+static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
   Plan p{};
   p.path = PATH_EXPLICIT;
   const int algo = g_conv_algo.load();
   const bool allow_direct = algo != VCNN_ALGO_EXPLICIT;
+  // bf16 variant, default route: the bf16 matrix-core kernels wherever the layer has enough maps / channels
+  const bool bf16_mfma = dtype == VCNN_BF16 && algo == VCNN_ALGO_AUTO;
+  // (1x1 layers stay on the plain product: they reuse no input element across taps, so staging would dominate)
+  if (bf16_mfma && pass == VCNN_PASS_FWD && g.k > 4 && !is_pointwise(g) &&
+      conv_halo_bf16_plan(g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, &p.hb)) {
+    p.path = PATH_HALO_BF16;
+    p.workspace_bytes = align256(reordered_weight_bytes(g.k, g.c, g.r * g.s));
+    return p;
+  }
+  if (bf16_mfma && pass == VCNN_PASS_BWD_DATA && g.c > 4 && !is_pointwise(g) && g.r - 1 - g.ph >= 0 && g.s - 1 - g.pw >= 0 &&
+      conv_halo_bf16_plan(g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, &p.hb)) {
+    p.path = PATH_HALO_BF16;
+    p.workspace_bytes = align256(reordered_weight_bytes(g.c, g.k, g.r * g.s));
+    return p;
+  }
+  if (bf16_mfma && pass == VCNN_PASS_BWD_FILTER && bwd_filter_bf16_plan(g, &p.fb)) {
+    p.path = PATH_FILTER_BF16;
+    p.workspace_bytes = p.fb.dyt_bytes + p.fb.col_bytes + align256(p.fb.partial_bytes);
+    p.bias_offset = p.workspace_bytes;
+    p.workspace_bytes += align256(bias_grad_partial_bytes(g));
+    return p;
+  }
   if (pass == VCNN_PASS_FWD) {
     if (allow_direct && g.k <= 4 && direct_fwd_geom(g, &p.dg) && direct_few_out_plan(&p.dg, &p.split, &p.partial_bytes)) {
       p.path = PATH_FEW_OUT;
@@ -161,7 +185,7 @@ static Plan make_plan(const ConvGeom& g, int pass) {
   return p;
 }
 
-static size_t workspace_need(const ConvGeom& g, int pass) { return make_plan(g, pass).workspace_bytes; }
+static size_t workspace_need(const ConvGeom& g, int pass, int dtype) { return make_plan(g, pass, dtype).workspace_bytes; }
 
 }  // namespace vcnn
 
@@ -204,7 +228,7 @@ vcnn_status vcnn_conv_workspace_bytes(const vcnn_conv_desc* d, int32_t pass, siz
   ConvGeom g;
   if (vcnn_status s = make_geom(d, &g)) return s;
   if (pass < VCNN_PASS_FWD || pass > VCNN_PASS_BWD_DATA) return fail(VCNN_ERR_UNSUPPORTED, "unknown pass %d", pass);
-  *bytes = workspace_need(g, pass);
+  *bytes = workspace_need(g, pass, d->dtype);
   return VCNN_OK;
 }
 
@@ -227,7 +251,7 @@ vcnn_status vcnn_conv_fwd(const vcnn_conv_desc* d, const void* x, const void* w,
   ConvGeom g;
   if (vcnn_status s = make_geom(d, &g)) return s;
   if (!x || !w || !y) return fail(VCNN_ERR_NULL, "conv_fwd: NULL tensor");
-  const Plan plan = make_plan(g, VCNN_PASS_FWD);
+  const Plan plan = make_plan(g, VCNN_PASS_FWD, d->dtype);
   if (vcnn_status s = check_ws(workspace, workspace_bytes, plan.workspace_bytes, "conv_fwd")) return s;
   hipStream_t st = (hipStream_t)stream;
   const int relu = d->act == VCNN_ACT_RELU;
@@ -237,6 +261,10 @@ vcnn_status vcnn_conv_fwd(const vcnn_conv_desc* d, const void* x, const void* w,
   if (plan.path == PATH_FEW_IN) return launch_direct_few_in(plan.dg, dt, plan.split, x, w, bias, y, relu, st);
   if (plan.path == PATH_HALO)
     return launch_conv_halo(plan.hp, dt, g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, x, w, bias, y, relu, st);
+  if (plan.path == PATH_HALO_BF16) {
+    if (vcnn_status s = launch_reorder_weights(w, workspace, g.k, g.c, g.r * g.s, g.K, (int64_t)g.r * g.s, 0, st)) return s;
+    return launch_conv_halo_bf16(plan.hb, g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, x, workspace, bias, y, relu, st);
+  }
 
   GemmArgs a{};
   a.A = w, a.C = y, a.bias = bias;
@@ -262,13 +290,15 @@ vcnn_status vcnn_conv_bwd_filter(const vcnn_conv_desc* d, const void* x, const v
   ConvGeom g;
   if (vcnn_status s = make_geom(d, &g)) return s;
   if (!x || !dy || !dw) return fail(VCNN_ERR_NULL, "conv_bwd_filter: NULL tensor");
-  const Plan plan = make_plan(g, VCNN_PASS_BWD_FILTER);
+  const Plan plan = make_plan(g, VCNN_PASS_BWD_FILTER, d->dtype);
   if (vcnn_status s = check_ws(workspace, workspace_bytes, plan.workspace_bytes, "conv_bwd_filter")) return s;
   hipStream_t st = (hipStream_t)stream;
   const int dt = d->dtype;
   float* bias_partial = (float*)((char*)workspace + plan.bias_offset);
   if (plan.path == PATH_DIRECT_FILTER) {
     if (vcnn_status s = launch_direct_filter_grad(plan.dg, dt, plan.split, x, dy, dw, (float*)workspace, st)) return s;
+  } else if (plan.path == PATH_FILTER_BF16) {
+    if (vcnn_status s = launch_bwd_filter_bf16(plan.fb, g, x, dy, dw, workspace, st)) return s;
   } else if (plan.path == PATH_HALO_FILTER) {
     if (vcnn_status s = launch_conv_halo_filter(plan.hfp, dt, g, x, dy, dw, (float*)workspace, st)) return s;
   } else {
@@ -285,13 +315,19 @@ vcnn_status vcnn_conv_bwd_data(const vcnn_conv_desc* d, const void* w, const voi
   ConvGeom g;
   if (vcnn_status s = make_geom(d, &g)) return s;
   if (!w || !dy || !dx) return fail(VCNN_ERR_NULL, "conv_bwd_data: NULL tensor");
-  const Plan plan = make_plan(g, VCNN_PASS_BWD_DATA);
+  const Plan plan = make_plan(g, VCNN_PASS_BWD_DATA, d->dtype);
   if (vcnn_status s = check_ws(workspace, workspace_bytes, plan.workspace_bytes, "conv_bwd_data")) return s;
   hipStream_t st = (hipStream_t)stream;
   const int dt = d->dtype;
   if (plan.path == PATH_FEW_OUT)
     return launch_direct_few_out(plan.dg, dt, plan.split, dy, w, nullptr, dx, (float*)workspace, 0, st);
   if (plan.path == PATH_FEW_IN) return launch_direct_few_in(plan.dg, dt, plan.split, dy, w, nullptr, dx, 0, st);
+  if (plan.path == PATH_HALO_BF16) {
+    // correlation of dy (k channels) with the flipped kernels into c maps: re-order, flip and transpose in one pass
+    if (vcnn_status s = launch_reorder_weights(w, workspace, g.c, g.k, g.r * g.s, (int64_t)g.r * g.s, g.K, 1, st)) return s;
+    return launch_conv_halo_bf16(plan.hb, g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, dy, workspace,
+                                 nullptr, dx, 0, st);
+  }
   if (plan.path == PATH_HALO) {
     if (vcnn_status s = launch_flip_transpose(dt, w, workspace, g.k, g.c, g.r * g.s, st)) return s;
     return launch_conv_halo(plan.hp, dt, g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, dy,

@@ -106,6 +106,30 @@ vcnn_status launch_conv_halo_filter(const HaloFilterPlan& p, int dtype, const Co
                                     float* dw, float* partial, hipStream_t st);
 vcnn_status launch_flip_transpose(int dtype, const void* w, void* w2, int M, int C, int RS, hipStream_t st);
 
+// ---- bf16_mfma.hip --------------------------------------------------------------------------------
+struct HaloBf16Plan {
+  int bm, bn;
+  int cg, cgc;       // channel groups of 8: total, staged per chunk
+  int nr, wp;        // halo rows and row pitch (positions of 8 channels) per group
+  int uch;           // (group, tap) pairs per chunk, padded to a multiple of 8
+  size_t lds_bytes;
+};
+struct BwdFilterBf16Plan {
+  int bm, splits;
+  int64_t chunk;
+  size_t dyt_bytes, col_bytes, partial_bytes;
+};
+size_t reordered_weight_bytes(int co, int ci, int rs);
+bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int pw, HaloBf16Plan* p);
+// out[o][g][q][c8] = in[o*so + (8g+c8)*si + (flip ? rs-1-q : q)], zero for padding channels (bf16 elements)
+vcnn_status launch_reorder_weights(const void* w, void* out, int co, int ci, int rs, int64_t so, int64_t si, int flip,
+                                   hipStream_t st);
+vcnn_status launch_conv_halo_bf16(const HaloBf16Plan& p, int n, int c, int h, int w, int m, int r, int s, int ph, int pw,
+                                  const void* x, const void* wre, const float* bias, void* y, int relu, hipStream_t st);
+bool bwd_filter_bf16_plan(const ConvGeom& g, BwdFilterBf16Plan* p);
+vcnn_status launch_bwd_filter_bf16(const BwdFilterBf16Plan& p, const ConvGeom& g, const void* x, const void* dy, float* dw,
+                                   void* workspace, hipStream_t st);
+
 // out[i] = act(bias[(i / plane) % maps] + sum_s partial[s][i]), slices added in ascending order (bias nullable)
 vcnn_status launch_sum_slices(const float* partial, const float* bias, void* out, int out_dtype, int64_t count,
                               int splits, int64_t plane, int maps, int relu, hipStream_t st);

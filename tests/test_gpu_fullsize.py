@@ -110,3 +110,57 @@ def test_unroll_full_size_properties():
     lhs = float(torch.sum(col.double() * col.double()))
     rhs = float(torch.sum(xd.double() * back.double()))
     assert abs(lhs - rhs) <= 1e-6 * abs(lhs)
+
+
+@pytest.mark.parametrize("li", [li for li, _, _ in conv_layers("cfg5")])
+def test_cfg5_layer_full_size_bf16_sampled(li):
+    """The bf16 variant at cfg5's full batch (the configuration the benchmark times): bf16 matrix-core
+    kernels for the forward pass and both gradients, sampled against the oracle's probes evaluated on
+    the same bf16-rounded tensors."""
+    from util import TOL_BF16
+    net = wl.make_net("cfg5")
+    L = net.layers[li]
+    n, c, h, w = net.in_shape(li)
+    _, k, oh, ow = net.shapes[li]
+    pad = (L.pad_h, L.pad_w)
+    seed = 6000 + li
+    x = wl.bf16_round(np.abs(wl.random_tensor(seed, (n, c, h, w))) if li > 0 else wl.random_tensor(seed, (n, c, h, w)))
+    wt = wl.bf16_round(wl.random_tensor(seed + 1, (k, c, L.kh, L.kw), scale=(2.0 / (c * L.kh * L.kw)) ** 0.5))
+    b = wl.random_tensor(seed + 2, (k,), scale=0.1)
+    dy = wl.bf16_round(wl.random_tensor(seed + 3, (n, k, oh, ow)))
+    rng = np.random.default_rng(seed)
+    dev16 = lambda a: torch.from_numpy(a).to(DEV).to(torch.bfloat16)
+    host = lambda t: (torch.cuda.synchronize(), t.float().cpu().numpy())[1]
+
+    d = vcnn.conv_desc(n, c, h, w, k, L.kh, L.kw, L.pad_h, L.pad_w, dtype=vcnn.BF16,
+                       act=vcnn.ACT_RELU if L.relu else vcnn.ACT_NONE)
+    ws = torch.empty(max(256, *(vcnn.conv_workspace_bytes(d, p) for p in range(3))), dtype=torch.uint8, device=DEV)
+    xd, wd, bd, dyd = dev16(x), dev16(wt), to_dev(b), dev16(dy)
+
+    def check(got, want, tol, what):
+        want = np.asarray(want, dtype=np.float64)
+        err = np.max(np.abs(np.asarray(got, dtype=np.float64) - want)) / max(np.max(np.abs(want)), 1e-30)
+        assert err <= tol, f"{what}: sampled max-norm relative error {err:.3e}"
+
+    y = torch.full((n, k, oh, ow), float("nan"), dtype=torch.bfloat16, device=DEV)
+    vcnn.conv_fwd(d, xd, wd, bd, y, ws)
+    yh = host(y)
+    assert np.all(np.isfinite(yh))
+    idx = sample_idx(rng, yh.shape)
+    check([yh[i] for i in idx], O.conv_fwd_at(x, wt, b, pad, idx, relu=L.relu), TOL_BF16, f"cfg5 bf16 conv{li} fwd")
+
+    dw = torch.full(wt.shape, float("nan"), device=DEV)
+    db = torch.full((k,), float("nan"), device=DEV)
+    vcnn.conv_bwd_filter(d, xd, dyd, dw, db, ws)
+    dwh = to_np(dw)
+    assert np.all(np.isfinite(dwh))
+    idx = sample_idx(rng, dwh.shape)
+    check([dwh[i] for i in idx], O.conv_bwd_filter_at(x, dy, (L.kh, L.kw), pad, idx), TOL_F32, f"cfg5 bf16 conv{li} dw")
+    check(to_np(db), dy.astype(np.float64).sum(axis=(0, 2, 3)), TOL_F32, f"cfg5 bf16 conv{li} db")
+
+    dx = torch.full((n, c, h, w), float("nan"), dtype=torch.bfloat16, device=DEV)
+    vcnn.conv_bwd_data(d, wd, dyd, dx, ws)
+    dxh = host(dx)
+    assert np.all(np.isfinite(dxh))
+    idx = sample_idx(rng, dxh.shape, [(0, 0, 0, w - 1), (n - 1, c - 1, h - 1, 0)])
+    check([dxh[i] for i in idx], O.conv_bwd_data_at(wt, dy, pad, idx), TOL_BF16, f"cfg5 bf16 conv{li} dx")
