@@ -155,6 +155,50 @@ def dominant_roofline(res):
             "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(name)}
 
 
+def hbm_kernels(stream):
+    """Achieved GB/s of the bandwidth-bound kernels at the largest shapes of the workloads: the explicit
+    unroll phi_c / phi_c^{-1} (cfg4 c2: 1.68 GB patch matrix; cfg5 c5: 3.7 GB), max pooling (cfg3 p1)
+    and ReLU (cfg4 c1 output).  Algorithmic bytes over the median of three timing loops."""
+    import torch
+    from paper_1501_07338_amd import vcnn
+    out = []
+
+    def timed(fn):
+        ts = sorted(time_calls(fn, 10, stream) for _ in range(3))
+        return ts[1]
+
+    def rec(kernel, shape, nbytes, ms):
+        out.append({"kernel": kernel, "shape": shape, "algorithmic_bytes": nbytes, "ms": ms, "gbs": nbytes / (ms * 1e6),
+                    "frac_hbm_peak": nbytes / (ms * 1e6) / HBM_PEAK_GBS})
+
+    for name, (n, c, h, w, k, r, s, ph, pw) in {"cfg4.c2": (64, 64, 64, 64, 32, 5, 5, 2, 2),
+                                                 "cfg5.c5": (16, 512, 49, 49, 1, 8, 8, 0, 0)}.items():
+        d = vcnn.conv_desc(n, c, h, w, k, r, s, ph, pw)
+        oh, ow = vcnn.conv_out_shape(d)
+        K, N = c * r * s, n * oh * ow
+        x = torch.randn(n, c, h, w, device="cuda")
+        col = torch.empty(K, N, device="cuda")
+        dx = torch.empty_like(x)
+        nbytes = 4.0 * (K * N + x.numel())
+        rec("im2col", name, nbytes, timed(lambda: vcnn.im2col(d, x, col)))
+        rec("col2im", name, nbytes, timed(lambda: vcnn.col2im(d, col, dx)))
+        del x, col, dx
+    n, c, h, w = 128, 32, 32, 32  # cfg3 p1: 3x3 stride 2
+    d = vcnn.pool_desc(n, c, h, w, 3, 3, 2, 2)
+    oh, ow = vcnn.pool_out_shape(d)
+    x = torch.randn(n, c, h, w, device="cuda")
+    y = torch.empty(n, c, oh, ow, device="cuda")
+    am = torch.empty(n, c, oh, ow, dtype=torch.int32, device="cuda")
+    dy, dx = torch.randn_like(y), torch.empty_like(x)
+    rec("pool_fwd", "cfg3.p1", 4.0 * (x.numel() + 2 * y.numel()), timed(lambda: vcnn.pool_fwd(d, x, y, am)))
+    rec("pool_bwd", "cfg3.p1", 4.0 * (x.numel() + 2 * y.numel()), timed(lambda: vcnn.pool_bwd(d, dy, am, dx)))
+    t = torch.randn(64, 64, 64, 64, device="cuda")  # cfg4 c1 output
+    g, o = torch.randn_like(t), torch.empty_like(t)
+    rec("relu_bwd", "cfg4.c1 output", 12.0 * t.numel(), timed(lambda: vcnn.act_bwd(vcnn.ACT_RELU, vcnn.F32, t.numel(), t, g, o)))
+    torch.cuda.empty_cache()
+    return out
+
+
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/); filled in
 # from the committed summaries, None where no counter run covers the kernel.
 MEASURED_TRAFFIC: dict = {}
@@ -219,6 +263,7 @@ def main():
         "conv_pct_mfma_f32_peak": main_res.get("conv_pct_mfma_f32_peak"),
         "roofline": main_res["roofline"],
         "conv_layers": main_res.get("conv_layers"),
+        "hbm_kernels": hbm_kernels(torch.cuda.current_stream()),
         "other_workloads": others,
     }
     if not args.no_cpu:

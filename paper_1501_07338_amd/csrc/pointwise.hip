@@ -73,24 +73,26 @@ vcnn_status launch_relu_bwd(int dtype, size_t count, const void* ref, const void
 }
 
 // ---- max pooling --------------------------------------------------------------------------------
-// One thread per output element, ow fastest.  Row-major scan with a strict '>' keeps the lowest
-// flat index among equal maxima.
-template <typename T>
+// blockIdx.y = (n, c) plane, one thread per output element of the plane (ow fastest), 32-bit index
+// arithmetic.  WIN / STRIDE are compile-time for the common square cases (2/2, 3/2), 0 = run-time
+// values from the descriptor.  Row-major scan with a strict '>' keeps the lowest flat index among
+// equal maxima.
+template <typename T, int WIN, int STRIDE>
 __global__ __launch_bounds__(kThreads) void pool_fwd_kernel(vcnn_pool_desc d, int oh_n, int ow_n,
                                                             const T* __restrict__ x, T* __restrict__ y,
-                                                            int32_t* __restrict__ argmax, int64_t total) {
-  const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  if (idx >= total) return;
-  const int ow = (int)(idx % ow_n);
-  const int64_t t = idx / ow_n;
-  const int oh = (int)(t % oh_n);
-  const int64_t nc = t / oh_n;
+                                                            int32_t* __restrict__ argmax) {
+  const int o = blockIdx.x * kThreads + threadIdx.x;
+  if (o >= oh_n * ow_n) return;
+  const int win_h = WIN ? WIN : d.win_h, win_w = WIN ? WIN : d.win_w;
+  const int sh = STRIDE ? STRIDE : d.stride_h, sw = STRIDE ? STRIDE : d.stride_w;
+  const int oh = o / ow_n, ow = o - oh * ow_n;
+  const int64_t nc = blockIdx.y;
   const T* xp = x + nc * d.h * d.w;
-  const int h0 = oh * d.stride_h, w0 = ow * d.stride_w;
+  const int h0 = oh * sh, w0 = ow * sw;
   float best = ld(xp + h0 * d.w + w0);
   int bi = h0 * d.w + w0;
-  for (int i = 0; i < d.win_h; ++i)
-    for (int j = 0; j < d.win_w; ++j) {
+  for (int i = 0; i < win_h; ++i)  // compile-time bounds in the specialised instantiations: fully unrolled
+    for (int j = 0; j < win_w; ++j) {
       const int pos = (h0 + i) * d.w + w0 + j;
       const float v = ld(xp + pos);
       if (v > best) {
@@ -98,66 +100,96 @@ __global__ __launch_bounds__(kThreads) void pool_fwd_kernel(vcnn_pool_desc d, in
         bi = pos;
       }
     }
+  const int64_t idx = nc * oh_n * ow_n + o;
   st(y + idx, best);
   argmax[idx] = bi;
 }
 
-// One thread per input element: sums, in ascending window order, the gradients of the windows that
-// cover it and recorded it.  Gather form, so no atomics and every dx element is written.
-template <typename T>
+// One thread per input element of the plane: sums, in ascending window order, the gradients of the
+// windows that cover it and recorded it.  Gather form, so no atomics and every dx element is written.
+template <typename T, int WIN, int STRIDE>
 __global__ __launch_bounds__(kThreads) void pool_bwd_kernel(vcnn_pool_desc d, int oh_n, int ow_n,
                                                             const T* __restrict__ dy,
-                                                            const int32_t* __restrict__ argmax, T* __restrict__ dx,
-                                                            int64_t total) {
-  const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  if (idx >= total) return;
-  const int wi = (int)(idx % d.w);
-  const int64_t t = idx / d.w;
-  const int hi = (int)(t % d.h);
-  const int64_t nc = t / d.h;
-  const int pos = hi * d.w + wi;
+                                                            const int32_t* __restrict__ argmax, T* __restrict__ dx) {
+  const int pos = blockIdx.x * kThreads + threadIdx.x;
+  if (pos >= d.h * d.w) return;
+  const int win_h = WIN ? WIN : d.win_h, win_w = WIN ? WIN : d.win_w;
+  const int sh = STRIDE ? STRIDE : d.stride_h, sw = STRIDE ? STRIDE : d.stride_w;
+  const int hi = pos / d.w, wi = pos - hi * d.w;
+  const int64_t nc = blockIdx.y;
   // windows oh with oh*stride <= hi <= oh*stride + win - 1
-  int oh_lo = hi - d.win_h + 1;
-  oh_lo = oh_lo > 0 ? (oh_lo + d.stride_h - 1) / d.stride_h : 0;
-  const int oh_hi = min(oh_n - 1, hi / d.stride_h);
-  int ow_lo = wi - d.win_w + 1;
-  ow_lo = ow_lo > 0 ? (ow_lo + d.stride_w - 1) / d.stride_w : 0;
-  const int ow_hi = min(ow_n - 1, wi / d.stride_w);
+  int oh_lo = hi - win_h + 1;
+  oh_lo = oh_lo > 0 ? (oh_lo + sh - 1) / sh : 0;
+  const int oh_hi = min(oh_n - 1, hi / sh);
+  int ow_lo = wi - win_w + 1;
+  ow_lo = ow_lo > 0 ? (ow_lo + sw - 1) / sw : 0;
+  const int ow_hi = min(ow_n - 1, wi / sw);
   const int64_t base = nc * oh_n * ow_n;
   float acc = 0.f;
-  for (int oh = oh_lo; oh <= oh_hi; ++oh)
-    for (int ow = ow_lo; ow <= ow_hi; ++ow) {
-      const int64_t o = base + (int64_t)oh * ow_n + ow;
-      if (argmax[o] == pos) acc += ld(dy + o);
-    }
-  st(dx + idx, acc);
+  if (WIN && STRIDE) {
+    // at most ceil(WIN/STRIDE) windows per axis cover a pixel: visit that fixed set with a predicate so
+    // that all (argmax, dy) loads are independent and in flight together
+    constexpr int CAND = WIN && STRIDE ? (WIN + STRIDE - 1) / STRIDE : 1;
+#pragma unroll
+    for (int a = 0; a < CAND; ++a)
+#pragma unroll
+      for (int b = 0; b < CAND; ++b) {
+        const int oh = oh_lo + a, ow = ow_lo + b;
+        const bool ok = oh <= oh_hi && ow <= ow_hi;
+        const int64_t o = base + (ok ? oh * ow_n + ow : 0);
+        const int am = argmax[o];
+        const float g = ld(dy + o);
+        acc += (ok && am == pos) ? g : 0.f;
+      }
+  } else {
+    for (int oh = oh_lo; oh <= oh_hi; ++oh)
+      for (int ow = ow_lo; ow <= ow_hi; ++ow) {
+        const int64_t o = base + oh * ow_n + ow;
+        if (argmax[o] == pos) acc += ld(dy + o);
+      }
+  }
+  st(dx + nc * d.h * d.w + pos, acc);
+}
+
+template <typename T>
+static void pool_fwd_typed(const vcnn_pool_desc& d, int oh, int ow, const void* x, void* y, int32_t* argmax,
+                           hipStream_t st) {
+  const dim3 grid((unsigned)ceil_div((int64_t)oh * ow, kThreads), (unsigned)(d.n * d.c)), block(kThreads);
+  const bool square = d.win_h == d.win_w && d.stride_h == d.stride_w;
+  if (square && d.win_h == 2 && d.stride_h == 2)
+    hipLaunchKernelGGL((pool_fwd_kernel<T, 2, 2>), grid, block, 0, st, d, oh, ow, (const T*)x, (T*)y, argmax);
+  else if (square && d.win_h == 3 && d.stride_h == 2)
+    hipLaunchKernelGGL((pool_fwd_kernel<T, 3, 2>), grid, block, 0, st, d, oh, ow, (const T*)x, (T*)y, argmax);
+  else
+    hipLaunchKernelGGL((pool_fwd_kernel<T, 0, 0>), grid, block, 0, st, d, oh, ow, (const T*)x, (T*)y, argmax);
+}
+
+template <typename T>
+static void pool_bwd_typed(const vcnn_pool_desc& d, int oh, int ow, const void* dy, const int32_t* argmax, void* dx,
+                           hipStream_t st) {
+  const dim3 grid((unsigned)ceil_div((int64_t)d.h * d.w, kThreads), (unsigned)(d.n * d.c)), block(kThreads);
+  const bool square = d.win_h == d.win_w && d.stride_h == d.stride_w;
+  if (square && d.win_h == 2 && d.stride_h == 2)
+    hipLaunchKernelGGL((pool_bwd_kernel<T, 2, 2>), grid, block, 0, st, d, oh, ow, (const T*)dy, argmax, (T*)dx);
+  else if (square && d.win_h == 3 && d.stride_h == 2)
+    hipLaunchKernelGGL((pool_bwd_kernel<T, 3, 2>), grid, block, 0, st, d, oh, ow, (const T*)dy, argmax, (T*)dx);
+  else
+    hipLaunchKernelGGL((pool_bwd_kernel<T, 0, 0>), grid, block, 0, st, d, oh, ow, (const T*)dy, argmax, (T*)dx);
 }
 
 vcnn_status launch_pool_fwd(const vcnn_pool_desc& d, int oh, int ow, const void* x, void* y, int32_t* argmax,
                             hipStream_t st) {
-  const int64_t total = (int64_t)d.n * d.c * oh * ow;
-  unsigned blocks;
-  if (vcnn_status s = grid_for((size_t)total, &blocks)) return s;
-  if (d.dtype == VCNN_BF16)
-    hipLaunchKernelGGL(pool_fwd_kernel<bf16>, dim3(blocks), dim3(kThreads), 0, st, d, oh, ow, (const bf16*)x, (bf16*)y,
-                       argmax, total);
-  else
-    hipLaunchKernelGGL(pool_fwd_kernel<float>, dim3(blocks), dim3(kThreads), 0, st, d, oh, ow, (const float*)x, (float*)y,
-                       argmax, total);
+  if ((int64_t)d.n * d.c > 65535) return fail(VCNN_ERR_UNSUPPORTED, "pool: more than 65535 planes in one call");
+  if (d.dtype == VCNN_BF16) pool_fwd_typed<bf16>(d, oh, ow, x, y, argmax, st);
+  else pool_fwd_typed<float>(d, oh, ow, x, y, argmax, st);
   return check_launch("pool_fwd");
 }
 
 vcnn_status launch_pool_bwd(const vcnn_pool_desc& d, int oh, int ow, const void* dy, const int32_t* argmax, void* dx,
                             hipStream_t st) {
-  const int64_t total = (int64_t)d.n * d.c * d.h * d.w;
-  unsigned blocks;
-  if (vcnn_status s = grid_for((size_t)total, &blocks)) return s;
-  if (d.dtype == VCNN_BF16)
-    hipLaunchKernelGGL(pool_bwd_kernel<bf16>, dim3(blocks), dim3(kThreads), 0, st, d, oh, ow, (const bf16*)dy, argmax,
-                       (bf16*)dx, total);
-  else
-    hipLaunchKernelGGL(pool_bwd_kernel<float>, dim3(blocks), dim3(kThreads), 0, st, d, oh, ow, (const float*)dy, argmax,
-                       (float*)dx, total);
+  if ((int64_t)d.n * d.c > 65535) return fail(VCNN_ERR_UNSUPPORTED, "pool: more than 65535 planes in one call");
+  if (d.dtype == VCNN_BF16) pool_bwd_typed<bf16>(d, oh, ow, dy, argmax, dx, st);
+  else pool_bwd_typed<float>(d, oh, ow, dy, argmax, dx, st);
   return check_launch("pool_bwd");
 }
 
