@@ -115,13 +115,13 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
   if (bf16_mfma && pass == VCNN_PASS_FWD && g.k > 4 && !is_pointwise(g) &&
       conv_halo_bf16_plan(g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, &p.hb)) {
     p.path = PATH_HALO_BF16;
-    p.workspace_bytes = align256(reordered_weight_bytes(g.k, g.c, g.r * g.s));
+    p.workspace_bytes = p.hb.x8_bytes + p.hb.wf_bytes;
     return p;
   }
   if (bf16_mfma && pass == VCNN_PASS_BWD_DATA && g.c > 4 && !is_pointwise(g) && g.r - 1 - g.ph >= 0 && g.s - 1 - g.pw >= 0 &&
       conv_halo_bf16_plan(g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, &p.hb)) {
     p.path = PATH_HALO_BF16;
-    p.workspace_bytes = align256(reordered_weight_bytes(g.c, g.k, g.r * g.s));
+    p.workspace_bytes = p.hb.x8_bytes + p.hb.wf_bytes;
     return p;
   }
   if (bf16_mfma && pass == VCNN_PASS_BWD_FILTER && bwd_filter_bf16_plan(g, &p.fb)) {
@@ -262,8 +262,8 @@ vcnn_status vcnn_conv_fwd(const vcnn_conv_desc* d, const void* x, const void* w,
   if (plan.path == PATH_HALO)
     return launch_conv_halo(plan.hp, dt, g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, x, w, bias, y, relu, st);
   if (plan.path == PATH_HALO_BF16) {
-    if (vcnn_status s = launch_reorder_weights(w, workspace, g.k, g.c, g.r * g.s, g.K, (int64_t)g.r * g.s, 0, st)) return s;
-    return launch_conv_halo_bf16(plan.hb, g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, x, workspace, bias, y, relu, st);
+    return launch_conv_halo_bf16(plan.hb, g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, x, w, g.K, (int64_t)g.r * g.s, 0,
+                                 bias, y, relu, workspace, st);
   }
 
   GemmArgs a{};
@@ -323,10 +323,9 @@ vcnn_status vcnn_conv_bwd_data(const vcnn_conv_desc* d, const void* w, const voi
     return launch_direct_few_out(plan.dg, dt, plan.split, dy, w, nullptr, dx, (float*)workspace, 0, st);
   if (plan.path == PATH_FEW_IN) return launch_direct_few_in(plan.dg, dt, plan.split, dy, w, nullptr, dx, 0, st);
   if (plan.path == PATH_HALO_BF16) {
-    // correlation of dy (k channels) with the flipped kernels into c maps: re-order, flip and transpose in one pass
-    if (vcnn_status s = launch_reorder_weights(w, workspace, g.c, g.k, g.r * g.s, (int64_t)g.r * g.s, g.K, 1, st)) return s;
-    return launch_conv_halo_bf16(plan.hb, g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, dy, workspace,
-                                 nullptr, dx, 0, st);
+    // correlation of dy (k channels) with the flipped kernels into c maps: the re-ordering pass flips and transposes
+    return launch_conv_halo_bf16(plan.hb, g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, dy, w,
+                                 (int64_t)g.r * g.s, g.K, 1, nullptr, dx, 0, workspace, st);
   }
   if (plan.path == PATH_HALO) {
     if (vcnn_status s = launch_flip_transpose(dt, w, workspace, g.k, g.c, g.r * g.s, st)) return s;

@@ -1,0 +1,386 @@
+// Implicit-unroll convolution of the bf16 variant on v_mfma_f32_32x32x16_bf16 (fp32 accumulate).
+//
+// As in the fp32 kernel the patch matrix phi_c(x) of Eq. 2 / Eq. 4 is never formed: a block stages the
+// input rows its output pixels touch (with halo, zero padded) in LDS and reads the B operand of every
+// MFMA at lane_base(pixel) + tap_offset.  What differs is how the two operands reach the matrix cores:
+//
+//  * The input is first re-laid channel-interleaved, x8[n][c/8][h][w][8] (one small pass over the
+//    tensor), so that a halo position is one 16-byte word holding the 8 contraction elements a lane
+//    feeds to one MFMA, and staging is one 16-byte load + one 16-byte LDS store per position.
+//  * The kernel matrix never goes through LDS.  It is re-ordered once per call into MFMA fragment order,
+//    wf[row tile][chunk][step][lane][8]: the A operand of a step is one fully coalesced 1 KB read per
+//    wave straight from L2 into registers, prefetched one slab (4 steps) ahead.  Without a shared A
+//    slab the main loop has no barrier; blocks synchronise only when the halo tile changes.
+//  * A wave owns 64 output maps x 32*TN pixels (LDS traffic per MFMA falls with the tile size).  The four
+//    waves of a block either take different maps (many maps) or split the contraction between them (few
+//    maps; partial sums are added in a fixed order through LDS at the end).
+//
+// Contraction order: (channel group of 8, r, s, channel in group); a step contracts two (group, tap)
+// pairs, lanes 0-31 the even one and lanes 32-63 the odd one.  The input gradient is the same kernel
+// run on dy with the flipped, transposed kernels (the re-ordering pass does the flip).
+#include <algorithm>
+
+#include "common.h"
+#include "elem.h"
+
+namespace vcnn {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+static constexpr int kThreads = 256;
+static constexpr size_t kLdsBudget = 78 * 1024;  // two blocks per CU
+
+__device__ __forceinline__ f32x16 mfma_bf16(uint4 a, uint4 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// x8[n][g][pos][c8] = x[n][8g + c8][pos], zero for channels >= C
+__global__ __launch_bounds__(kThreads) void interleave_channels_kernel(const bf16* __restrict__ x, uint4* __restrict__ x8,
+                                                                       int C, int CG, int HW, int64_t total) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= total) return;
+  const int pos = (int)(i % HW);
+  const int64_t t = i / HW;
+  const int g = (int)(t % CG);
+  const int64_t n = t / CG;
+  const bf16* src = x + (n * C + g * 8) * HW + pos;
+  uint32_t v[8];
+#pragma unroll
+  for (int c8 = 0; c8 < 8; ++c8) {
+    const bool ok = g * 8 + c8 < C;
+    const uint16_t b = src[ok ? (int64_t)c8 * HW : 0].bits;
+    v[c8] = ok ? b : 0u;
+  }
+  x8[i] = make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
+}
+
+// wf[mt][ch][jl][lane][c8] = w(row = 32 mt + lane % 32, channel = 8 (ch*cgc + gl) + c8, tap q) where
+// (gl, q) = divmod(2 jl + lane / 32, RS); zero outside the matrix or the chunk.
+// w(row, channel, q) = in[row*so + channel*si + (flip ? RS-1-q : q)].
+__global__ __launch_bounds__(kThreads) void reorder_weights_frag_kernel(const bf16* __restrict__ in, bf16* __restrict__ out,
+                                                                        int CO, int CI, int RS, int64_t so, int64_t si,
+                                                                        int flip, int cgc, int nchunks, int steps,
+                                                                        int64_t total) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= total) return;
+  const int c8 = (int)(i & 7);
+  const int lane = (int)(i >> 3) & 63;
+  int64_t t = i >> 9;
+  const int jl = (int)(t % steps);
+  t /= steps;
+  const int ch = (int)(t % nchunks);
+  const int mt = (int)(t / nchunks);
+  const int row = mt * 32 + (lane & 31);
+  const int u = 2 * jl + (lane >> 5);
+  const int gl = u / RS, q = u - gl * RS;
+  const int c = (ch * cgc + gl) * 8 + c8;
+  bf16 v;
+  v.bits = 0;
+  if (row < CO && gl < cgc && c < CI) v = in[(int64_t)row * so + (int64_t)c * si + (flip ? RS - 1 - q : q)];
+  out[i] = v;
+}
+
+struct HaloBf16Args {
+  const uint4* x8;    // [n][cg][h][w] positions of 8 channels
+  const uint4* wf;    // [mt][chunk][step][64 lanes] fragments
+  const float* bias;  // [m] or null
+  bf16* y;            // [n][m][oh][ow]
+  int n, h, w, m, r, s, ph, pw, oh, ow, P;
+  int tiles_m, tiles_per_img;
+  int cg, cgc, nchunks;
+  int nr, wp;         // halo rows and row pitch (positions) per group
+  int uch;            // (group, tap) pairs per chunk, padded to a multiple of 8
+  int relu;
+};
+
+template <int WAVES_M, int WAVES_K, int TN>
+__global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Args a) {
+  static_assert(WAVES_M * WAVES_K * 64 == kThreads, "four waves per block");
+  constexpr int TM = 2;
+  constexpr int BM = 32 * TM * WAVES_M, BN = 32 * TN;
+  extern __shared__ uint4 smem16[];
+  int* const tbl = reinterpret_cast<int*>(smem16);  // [uch], per slab of 8 pairs: [half][4]
+  uint4* const halo = smem16 + a.uch / 4;           // [cgc][nr][wp]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int wave_m = wave % WAVES_M, wave_k = wave / WAVES_M;
+  const int tm = blockIdx.x % a.tiles_m;
+  const int tj = blockIdx.x / a.tiles_m;
+  const int n = tj / a.tiles_per_img;
+  const int p0 = (tj - n * a.tiles_per_img) * BN;
+  const int i0 = tm * BM + wave_m * 32 * TM;  // first output map of this wave
+  const int RS = a.r * a.s;
+  const int plane = a.nr * a.wp;
+  const int oh_first = p0 / a.ow;
+
+  // table: position offset of pair u = (group gl, tap q) inside the halo tile; padding pairs point at 0
+  // (their kernel-matrix entries are zero).  Entry u = 8*sl + 2*i + h is stored at 8*sl + 4*h + i.
+  for (int u = tid; u < a.uch; u += kThreads) {
+    int off = 0;
+    if (u < a.cgc * RS) {
+      const int gl = u / RS;
+      const int q = u - gl * RS;
+      const int r = q / a.s;
+      off = gl * plane + r * a.wp + (q - r * a.s);
+    }
+    const int sl = u >> 3, w8 = u & 7;
+    tbl[sl * 8 + (w8 & 1) * 4 + (w8 >> 1)] = off;
+  }
+
+  int lane_base[TN];
+#pragma unroll
+  for (int ni = 0; ni < TN; ++ni) {
+    const int p = min(p0 + ni * 32 + l32, a.P - 1);
+    const int oh = p / a.ow;
+    lane_base[ni] = (oh - oh_first) * a.wp + (p - oh * a.ow);
+  }
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[mi][ni][q] = 0.f;
+
+  const uint4* x8n = a.x8 + (int64_t)n * a.cg * a.h * a.w;
+  const int steps = a.uch / 2;                               // fragment steps per chunk
+  const int chunk_slabs = a.uch / 8;
+  const int64_t mstride = (int64_t)a.nchunks * steps * 64;   // fragments per row tile
+  const uint4* wf0 = a.wf + (int64_t)(i0 / 32) * mstride + lane;
+
+  // A fragments of the slab this wave works on next: af[step in slab][row tile]
+  uint4 af[4][TM];
+  auto load_a = [&](int ch, int sl) {
+    const uint4* src = wf0 + ((int64_t)ch * steps + sl * 4) * 64;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int mi = 0; mi < TM; ++mi) af[i][mi] = src[mi * mstride + i * 64];
+  };
+  const int first_sl = min(wave_k, chunk_slabs - 1);
+  load_a(0, first_sl);
+
+  // flat position walk of the staging loop (same for every chunk)
+  const int dq = kThreads / a.wp, dr = kThreads - dq * a.wp;
+  const int row_s = tid / a.wp, rx_s = tid - row_s * a.wp;
+  const int gl_s = row_s / a.nr, ry_s = row_s - gl_s * a.nr;
+
+  for (int ch = 0; ch < a.nchunks; ++ch) {
+    const int g0 = ch * a.cgc;
+    const int cgc = min(a.cgc, a.cg - g0);
+    const int ulen = cgc * RS;  // valid (group, tap) pairs in this chunk
+    const int slabs = (ulen + 7) >> 3;
+    __syncthreads();  // the previous chunk's MFMAs are done with the halo tile (first pass: the table is complete)
+    {
+      const int npos = cgc * plane;
+      int rx = rx_s, ry = ry_s, gl = gl_s;
+      for (int e0 = tid; e0 < npos; e0 += 4 * kThreads) {
+        uint4 v[4];
+        bool ok[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int ih = oh_first - a.ph + ry, iw = rx - a.pw;
+          ok[u] = e0 + u * kThreads < npos && ih >= 0 && ih < a.h && iw >= 0 && iw < a.w;
+          v[u] = x8n[ok[u] ? ((g0 + gl) * a.h + ih) * a.w + iw : 0];
+          rx += dr;
+          ry += dq;
+          if (rx >= a.wp) rx -= a.wp, ++ry;
+          while (ry >= a.nr) ry -= a.nr, ++gl;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (e0 + u * kThreads < npos) halo[e0 + u * kThreads] = ok[u] ? v[u] : make_uint4(0u, 0u, 0u, 0u);
+      }
+    }
+    __syncthreads();
+
+    for (int sl = wave_k; sl < slabs; sl += WAVES_K) {
+      // where this wave continues: next slab of this chunk, else its first slab of the next chunk (the
+      // fragment loads do not depend on the halo tile, so they stay in flight across the chunk change)
+      int nch = ch, nsl = sl + WAVES_K;
+      if (nsl >= slabs) {
+        if (ch + 1 < a.nchunks) nch = ch + 1, nsl = first_sl;
+        else nsl = sl;
+      }
+      const uint4* nsrc = wf0 + ((int64_t)nch * steps + nsl * 4) * 64;
+      const int4 o4 = *reinterpret_cast<const int4*>(tbl + sl * 8 + half * 4);
+      const int o[4] = {o4.x, o4.y, o4.z, o4.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        uint4 bfr[TN], cur[TM];
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni) bfr[ni] = halo[lane_base[ni] + o[i]];
+#pragma unroll
+        for (int mi = 0; mi < TM; ++mi) {
+          cur[mi] = af[i][mi];
+          af[i][mi] = nsrc[mi * mstride + i * 64];
+        }
+#pragma unroll
+        for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < TN; ++ni) acc[mi][ni] = mfma_bf16(cur[mi], bfr[ni], acc[mi][ni]);
+      }
+    }
+  }
+
+  // contraction split between waves: add the partial sums in wave order through LDS
+  if (WAVES_K > 1) {
+    float* red = reinterpret_cast<float*>(smem16);  // [TM*TN*16][64 lanes]
+#pragma unroll 1
+    for (int k = 1; k < WAVES_K; ++k) {
+      __syncthreads();
+      if (wave_k == k) {
+#pragma unroll
+        for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) red[(((wave_m * TM + mi) * TN + ni) * 16 + q) * 64 + lane] = acc[mi][ni][q];
+      }
+      __syncthreads();
+      if (wave_k == 0) {
+#pragma unroll
+        for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[mi][ni][q] += red[(((wave_m * TM + mi) * TN + ni) * 16 + q) * 64 + lane];
+      }
+    }
+    if (wave_k != 0) return;
+  }
+
+#pragma unroll
+  for (int ni = 0; ni < TN; ++ni) {
+    const int p = p0 + ni * 32 + l32;
+    if (p >= a.P) continue;
+#pragma unroll
+    for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int i = i0 + mi * 32 + 8 * (q >> 2) + 4 * half + (q & 3);
+        if (i < a.m) {
+          float v = acc[mi][ni][q];
+          if (a.bias) v += a.bias[i];
+          if (a.relu) v = fmaxf(v, 0.f);
+          st(a.y + ((int64_t)n * a.m + i) * a.P + p, v);
+        }
+      }
+  }
+}
+
+// ---- planning ---------------------------------------------------------------------------------------------
+static constexpr int kTnChoices[] = {2, 4, 5};
+
+bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int pw, HaloBf16Plan* p) {
+  const int oh = h + 2 * ph - r + 1, ow = w + 2 * pw - s + 1;
+  if (oh <= 0 || ow <= 0) return false;
+  const int rs = r * s;
+  const int cg = (c + 7) / 8;
+  if ((int64_t)cg * h * w > 0x7fffffffLL) return false;  // 32-bit position offsets inside a sample
+  p->waves_m = m > 128 ? 4 : (m > 64 ? 2 : 1);
+  const int waves_k = 4 / p->waves_m;
+  const int bm = 64 * p->waves_m;
+  const int tiles_m = (int)ceil_div(m, bm);
+  const int wp = w + 2 * pw;
+  // pixel tile: fewest rounds of 512 resident blocks, weighted by the tile width (time per tile)
+  const int64_t P = (int64_t)oh * ow;
+  int best_tn = 0, best_cgc = 0, best_nr = 0;
+  double best_cost = 0;
+  for (int tn : kTnChoices) {
+    const int bn = 32 * tn;
+    int rows = (bn + ow - 2) / ow + 1;
+    if (rows > oh) rows = oh;
+    const int nr = rows + r - 1;
+    const size_t red_bytes = waves_k > 1 ? (size_t)p->waves_m * 2 * tn * 16 * 64 * sizeof(float) : 0;
+    if (red_bytes > kLdsBudget) continue;
+    int cgc = 0;
+    for (int t = 1; t <= cg; ++t) {
+      const int uch = (int)ceil_div((int64_t)t * rs, 8) * 8;
+      if ((size_t)uch * 4 + (size_t)t * nr * wp * 16 > kLdsBudget || uch > 4096) break;
+      cgc = t;
+    }
+    if (cgc == 0) continue;
+    const int64_t tiles = (int64_t)tiles_m * n * ceil_div(P, bn);
+    if (tiles > 0x7fffffffLL) continue;
+    const double cost = (double)ceil_div(tiles, 512) * tn * (1.0 + 0.5 / tn);  // wider tiles reuse A fragments better
+    if (best_tn == 0 || cost < best_cost - 1e-9) best_tn = tn, best_cgc = cgc, best_nr = nr, best_cost = cost;
+  }
+  if (best_tn == 0) return false;
+  // among chunk sizes at least half the largest, take the one that pads the fewest (group, tap) pairs
+  int pick = best_cgc;
+  double pick_waste = 2.0;
+  for (int t = best_cgc; t >= 1 && 2 * t > best_cgc; --t) {
+    const int64_t chunks = ceil_div(cg, t);
+    const int last = cg - (int)(chunks - 1) * t;
+    const int64_t slabs = (chunks - 1) * ceil_div((int64_t)t * rs, 8) + ceil_div((int64_t)last * rs, 8);
+    const double waste = 1.0 - (double)cg * rs / (double)(slabs * 8);
+    if (waste < pick_waste - 1e-9) pick = t, pick_waste = waste;
+  }
+  p->tn = best_tn, p->cg = cg, p->cgc = pick, p->nchunks = (int)ceil_div(cg, pick), p->nr = best_nr, p->wp = wp;
+  p->uch = (int)ceil_div((int64_t)pick * rs, 8) * 8;
+  const size_t red_bytes = waves_k > 1 ? (size_t)p->waves_m * 2 * best_tn * 16 * 64 * sizeof(float) : 0;
+  p->lds_bytes = std::max((size_t)p->uch * 4 + (size_t)pick * best_nr * wp * 16, red_bytes);
+  p->x8_bytes = ((size_t)n * cg * h * w * 16 + 255) & ~(size_t)255;
+  p->wf_bytes = ((size_t)tiles_m * (bm / 32) * p->nchunks * (p->uch / 2) * 64 * 16 + 255) & ~(size_t)255;
+  return true;
+}
+
+template <int WAVES_M, int WAVES_K, int TN>
+static void launch_one(const HaloBf16Args& a, size_t lds, hipStream_t st) {
+  const dim3 grid((unsigned)((int64_t)a.tiles_m * a.n * a.tiles_per_img)), block(kThreads);
+  auto kernel = conv_halo_bf16_kernel<WAVES_M, WAVES_K, TN>;
+  static bool opted = false;  // one flag per instantiation, i.e. per kernel
+  if (!opted) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)kLdsBudget);
+    opted = true;
+  }
+  hipLaunchKernelGGL(kernel, grid, block, lds, st, a);
+}
+
+template <int TN>
+static void launch_tn(const HaloBf16Args& a, int waves_m, size_t lds, hipStream_t st) {
+  if (waves_m == 4) launch_one<4, 1, TN>(a, lds, st);
+  else if (waves_m == 2) launch_one<2, 2, TN>(a, lds, st);
+  else launch_one<1, 4, TN>(a, lds, st);
+}
+
+vcnn_status launch_conv_halo_bf16(const HaloBf16Plan& p, int n, int c, int h, int w, int m, int r, int s, int ph, int pw,
+                                  const void* x, const void* wgt, int64_t w_so, int64_t w_si, int flip, const float* bias,
+                                  void* y, int relu, void* workspace, hipStream_t st) {
+  uint4* x8 = (uint4*)workspace;
+  bf16* wf = (bf16*)((char*)workspace + p.x8_bytes);
+  const int rs = r * s;
+  {
+    const int64_t total = (int64_t)n * p.cg * h * w;
+    hipLaunchKernelGGL(interleave_channels_kernel, dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, st,
+                       (const bf16*)x, x8, c, p.cg, h * w, total);
+    if (vcnn_status e = check_launch("interleave_channels")) return e;
+  }
+  const int bm = 64 * p.waves_m;
+  const int tiles_m = (int)ceil_div(m, bm);
+  {
+    const int64_t total = (int64_t)tiles_m * (bm / 32) * p.nchunks * (p.uch / 2) * 512;
+    hipLaunchKernelGGL(reorder_weights_frag_kernel, dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, st,
+                       (const bf16*)wgt, wf, m, c, rs, w_so, w_si, flip, p.cgc, p.nchunks, p.uch / 2, total);
+    if (vcnn_status e = check_launch("reorder_weights_frag")) return e;
+  }
+  HaloBf16Args a{};
+  a.x8 = x8, a.wf = (const uint4*)wf, a.bias = bias, a.y = (bf16*)y;
+  a.n = n, a.h = h, a.w = w, a.m = m, a.r = r, a.s = s, a.ph = ph, a.pw = pw;
+  a.oh = h + 2 * ph - r + 1, a.ow = w + 2 * pw - s + 1;
+  a.P = a.oh * a.ow;
+  a.tiles_m = tiles_m;
+  a.tiles_per_img = (int)ceil_div(a.P, 32 * p.tn);
+  a.cg = p.cg, a.cgc = p.cgc, a.nchunks = p.nchunks, a.nr = p.nr, a.wp = p.wp, a.uch = p.uch, a.relu = relu;
+  if (p.tn == 2) launch_tn<2>(a, p.waves_m, p.lds_bytes, st);
+  else if (p.tn == 4) launch_tn<4>(a, p.waves_m, p.lds_bytes, st);
+  else launch_tn<5>(a, p.waves_m, p.lds_bytes, st);
+  return check_launch("conv_halo_bf16");
+}
+
+}  // namespace vcnn

@@ -83,6 +83,7 @@ vcnn_status launch_direct_filter_grad(const DirectGeom& g, int dtype, int slices
 // Implicit-unroll convolution y = act(bias + W (*) x) on the matrix cores; see the file header.
 struct HaloPlan {
   int bm, bn;        // block tile: output maps x consecutive output pixels
+  int bk;            // slab depth of the kernel-matrix operand
   int cc;            // input channels staged per chunk
   int nr, wp;        // halo tile rows and row pitch per channel
   int kch;           // taps per chunk, padded to the slab depth
@@ -106,26 +107,28 @@ vcnn_status launch_conv_halo_filter(const HaloFilterPlan& p, int dtype, const Co
                                     float* dw, float* partial, hipStream_t st);
 vcnn_status launch_flip_transpose(int dtype, const void* w, void* w2, int M, int C, int RS, hipStream_t st);
 
-// ---- bf16_mfma.hip --------------------------------------------------------------------------------
+// ---- bf16_conv.hip / bf16_mfma.hip -----------------------------------------------------------------
 struct HaloBf16Plan {
-  int bm, bn;
+  int waves_m;       // waves of a block along the output maps (the other 4 / waves_m split the contraction)
+  int tn;            // 32-pixel column tiles per wave
   int cg, cgc;       // channel groups of 8: total, staged per chunk
+  int nchunks;
   int nr, wp;        // halo rows and row pitch (positions of 8 channels) per group
   int uch;           // (group, tap) pairs per chunk, padded to a multiple of 8
   size_t lds_bytes;
+  size_t x8_bytes, wf_bytes;  // workspace: channel-interleaved input, fragment-ordered kernel matrix
 };
 struct BwdFilterBf16Plan {
   int bm, splits;
   int64_t chunk;
   size_t dyt_bytes, col_bytes, partial_bytes;
 };
-size_t reordered_weight_bytes(int co, int ci, int rs);
 bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int pw, HaloBf16Plan* p);
-// out[o][g][q][c8] = in[o*so + (8g+c8)*si + (flip ? rs-1-q : q)], zero for padding channels (bf16 elements)
-vcnn_status launch_reorder_weights(const void* w, void* out, int co, int ci, int rs, int64_t so, int64_t si, int flip,
-                                   hipStream_t st);
+// y = act(bias + W (*) x) with W(o, i, q) = wgt[o*w_so + i*w_si + (flip ? r*s-1-q : q)]; the workspace holds
+// x8_bytes + wf_bytes
 vcnn_status launch_conv_halo_bf16(const HaloBf16Plan& p, int n, int c, int h, int w, int m, int r, int s, int ph, int pw,
-                                  const void* x, const void* wre, const float* bias, void* y, int relu, hipStream_t st);
+                                  const void* x, const void* wgt, int64_t w_so, int64_t w_si, int flip, const float* bias,
+                                  void* y, int relu, void* workspace, hipStream_t st);
 bool bwd_filter_bf16_plan(const ConvGeom& g, BwdFilterBf16Plan* p);
 vcnn_status launch_bwd_filter_bf16(const BwdFilterBf16Plan& p, const ConvGeom& g, const void* x, const void* dy, float* dw,
                                    void* workspace, hipStream_t st);

@@ -36,7 +36,39 @@ struct HaloArgs {
   int relu;
 };
 
-template <int BM, int BN, int WM, int WN, bool VEC, typename T>
+// Copies channels [0, cc) x rows ih0 + [0, nr) x columns -pw + [0, wp) of one sample's planes x[.][h][w]
+// into the LDS tile [cc][nr][wp]; positions outside the image, and channels at or beyond cvalid, become
+// zero.  Elements are taken in flat tile order so every thread stays busy whatever the row length, and
+// each thread issues U global loads before it stores any of them (the loads overlap their latencies).
+template <int U, typename T>
+__device__ __forceinline__ void stage_halo(float* halo, const T* x, int cc, int cvalid, int nr, int wp, int h, int w,
+                                           int ih0, int pw, int tid) {
+  const int total = cc * nr * wp;
+  const int dq = kThreads / wp, dr = kThreads - dq * wp;
+  int row = tid / wp;
+  int rx = tid - row * wp;
+  int cl = row / nr;
+  int ry = row - cl * nr;
+  for (int e0 = tid; e0 < total; e0 += U * kThreads) {
+    float v[U];
+    bool ok[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int ih = ih0 + ry, iw = rx - pw;
+      ok[u] = e0 + u * kThreads < total && cl < cvalid && ih >= 0 && ih < h && iw >= 0 && iw < w;
+      v[u] = ld(x + (ok[u] ? (cl * h + ih) * w + iw : 0));
+      rx += dr;
+      ry += dq;
+      if (rx >= wp) rx -= wp, ++ry;
+      while (ry >= nr) ry -= nr, ++cl;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (e0 + u * kThreads < total) halo[e0 + u * kThreads] = ok[u] ? v[u] : 0.f;
+  }
+}
+
+template <int BM, int BN, int WM, int WN, int BK, bool VEC, typename T>
 __global__ __launch_bounds__(kThreads) void conv_halo_kernel(HaloArgs a) {
   static_assert((BM / WM) * (BN / WN) * 64 == kThreads, "four waves per block");
   using LA = LdsTile<BM, BK, true>;
@@ -124,24 +156,7 @@ __global__ __launch_bounds__(kThreads) void conv_halo_kernel(HaloArgs a) {
     fetch(0);
     __syncthreads();  // previous chunk's MFMAs are done with the halo tile and the A slabs
     // stage the halo rows of this chunk: input rows oh_first - ph + [0, nr), columns -pw + [0, wp)
-    {
-      int cl = 0, ry = wave;
-      while (ry >= a.nr) ry -= a.nr, ++cl;
-      for (int rid = wave; rid < cc * a.nr; rid += kThreads / 64) {
-        const int ih = oh_first - a.ph + ry;
-        const bool row_ok = ih >= 0 && ih < a.h;
-        const T* src = xin + ((int64_t)(c0 + cl) * a.h + (row_ok ? ih : 0)) * a.w;
-        float* dst = halo + cl * plane + ry * a.wp;
-        for (int rx = lane; rx < a.wp; rx += 64) {
-          const int iw = rx - a.pw;
-          const bool ok = row_ok && iw >= 0 && iw < a.w;
-          const float v = ld(src + (ok ? iw : 0));
-          dst[rx] = ok ? v : 0.f;
-        }
-        ry += kThreads / 64;
-        while (ry >= a.nr) ry -= a.nr, ++cl;
-      }
-    }
+    stage_halo<8>(halo, xin + (int64_t)c0 * a.h * a.w, cc, cc, a.nr, a.wp, a.h, a.w, oh_first - a.ph, a.pw, tid);
     sa.store(As0);
     __syncthreads();
 
@@ -225,16 +240,18 @@ static constexpr size_t kLdsBudget = 76 * 1024;  // two blocks per CU out of 160
 
 static int halo_bm(int m) { return m <= 32 ? 32 : (m <= 64 ? 64 : 128); }
 static int halo_bn(int m) { return m <= 64 ? 256 : 128; }
+// Slab depth: narrow row tiles do few MFMAs per slab, so they take deeper slabs (fewer barriers per MFMA).
+static int halo_bk(int m) { return m <= 64 ? 64 : 32; }
 
 bool conv_halo_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int pw, HaloPlan* p) {
   const int oh = h + 2 * ph - r + 1, ow = w + 2 * pw - s + 1;
-  if (oh <= 0 || ow <= 0) return false;
-  const int bm = halo_bm(m), bn = halo_bn(m);
+  if (oh <= 0 || ow <= 0 || (int64_t)c * h * w > 0x7fffffffLL) return false;  // 32-bit offsets inside a sample
+  const int bm = halo_bm(m), bn = halo_bn(m), BK = halo_bk(m);
   const int rs = r * s;
   int rows = (bn + ow - 2) / ow + 1;  // rows a run of bn consecutive pixels can touch
   if (rows > oh) rows = oh;
   const int nr = rows + r - 1, wp = w + 2 * pw;
-  const size_t a_bytes = 2 * (size_t)LdsTile<128, BK, true>::PITCH * bm * sizeof(float);
+  const size_t a_bytes = 2 * (size_t)(BK + 4) * bm * sizeof(float);
   // largest channel chunk that fits the LDS budget with a tap table of at most 2048 entries
   int best = 0;
   for (int cc = 1; cc <= c; ++cc) {
@@ -259,19 +276,18 @@ bool conv_halo_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int
     const double waste = 1.0 - (double)c * rs / (double)(slabs * BK);
     if (waste < pick_waste - 1e-9) pick = cc, pick_waste = waste;
   }
-  p->bm = bm, p->bn = bn, p->cc = pick, p->nr = nr, p->wp = wp;
+  p->bm = bm, p->bn = bn, p->bk = BK, p->cc = pick, p->nr = nr, p->wp = wp;
   p->kch = (int)ceil_div((int64_t)pick * rs, BK) * BK;
-  p->lds_bytes = 2 * (size_t)LdsTile<128, BK, true>::PITCH * bm * sizeof(float) + (size_t)p->kch * 4 +
-                 (size_t)pick * nr * wp * 4;
+  p->lds_bytes = a_bytes + (size_t)p->kch * 4 + (size_t)pick * nr * wp * 4;
   p->vec = ((int64_t)c * rs) % 4 == 0 && ((int64_t)pick * rs) % 4 == 0;
   const int64_t tiles = ceil_div(m, bm) * (int64_t)n * ceil_div((int64_t)oh * ow, bn);
   return tiles <= 0x7fffffffLL;
 }
 
-template <int BM, int BN, int WM, int WN, bool VEC, typename T>
+template <int BM, int BN, int WM, int WN, int BK, bool VEC, typename T>
 static void launch_halo_one(const HaloArgs& a, const HaloPlan& p, hipStream_t st) {
   const dim3 grid((unsigned)((int64_t)a.tiles_m * a.n * a.tiles_per_img)), block(kThreads);
-  auto kernel = conv_halo_kernel<BM, BN, WM, WN, VEC, T>;
+  auto kernel = conv_halo_kernel<BM, BN, WM, WN, BK, VEC, T>;
   static bool opted = false;  // one flag per instantiation, i.e. per kernel
   if (!opted) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -281,14 +297,14 @@ static void launch_halo_one(const HaloArgs& a, const HaloPlan& p, hipStream_t st
   hipLaunchKernelGGL(kernel, grid, block, p.lds_bytes, st, a);
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, int BK>
 static void launch_halo(const HaloArgs& a, const HaloPlan& p, bool vec, int dtype, hipStream_t st) {
   if (dtype == VCNN_BF16) {
-    if (vec) launch_halo_one<BM, BN, WM, WN, true, bf16>(a, p, st);
-    else launch_halo_one<BM, BN, WM, WN, false, bf16>(a, p, st);
+    if (vec) launch_halo_one<BM, BN, WM, WN, BK, true, bf16>(a, p, st);
+    else launch_halo_one<BM, BN, WM, WN, BK, false, bf16>(a, p, st);
   } else {
-    if (vec) launch_halo_one<BM, BN, WM, WN, true, float>(a, p, st);
-    else launch_halo_one<BM, BN, WM, WN, false, float>(a, p, st);
+    if (vec) launch_halo_one<BM, BN, WM, WN, BK, true, float>(a, p, st);
+    else launch_halo_one<BM, BN, WM, WN, BK, false, float>(a, p, st);
   }
 }
 
@@ -305,11 +321,11 @@ vcnn_status launch_conv_halo(const HaloPlan& p, int dtype, int n, int c, int h, 
   a.cc = p.cc, a.nr = p.nr, a.wp = p.wp, a.kch = p.kch, a.relu = relu;
   const bool vec = p.vec && (dtype == VCNN_BF16 ? group_aligned<bf16>(wgt) : group_aligned<float>(wgt));
   if (p.bm == 32)
-    launch_halo<32, 256, 32, 64>(a, p, vec, dtype, st);
+    launch_halo<32, 256, 32, 64, 64>(a, p, vec, dtype, st);
   else if (p.bm == 64)
-    launch_halo<64, 256, 64, 64>(a, p, vec, dtype, st);
+    launch_halo<64, 256, 64, 64, 64>(a, p, vec, dtype, st);
   else
-    launch_halo<128, 128, 64, 64>(a, p, vec, dtype, st);
+    launch_halo<128, 128, 64, 64, 32>(a, p, vec, dtype, st);
   return check_launch("conv_halo");
 }
 
@@ -412,26 +428,8 @@ __global__ __launch_bounds__(kThreads) void conv_halo_filter_kernel(HaloFilterAr
       const int oh = p / a.ow;
       pixoff[pk] = (oh - oh_first) * a.wp + (p - oh * a.ow);
     }
-    {
-      const T* xin = static_cast<const T*>(a.x) + (int64_t)n * a.c * a.h * a.w;
-      int cl = 0, ry = wave;
-      while (ry >= a.nr) ry -= a.nr, ++cl;
-      for (int rid = wave; rid < a.ccs * a.nr; rid += kThreads / 64) {
-        const int ih = oh_first - a.ph + ry;
-        const bool row_ok = ih >= 0 && ih < a.h;
-        const int c = min(c_first + cl, a.c - 1);
-        const T* src = xin + ((int64_t)c * a.h + (row_ok ? ih : 0)) * a.w;
-        float* dst = halo + cl * plane + ry * a.wp;
-        for (int rx = lane; rx < a.wp; rx += 64) {
-          const int iw = rx - a.pw;
-          const bool ok = row_ok && iw >= 0 && iw < a.w;
-          const float v = ld(src + (ok ? iw : 0));
-          dst[rx] = ok ? v : 0.f;
-        }
-        ry += kThreads / 64;
-        while (ry >= a.nr) ry -= a.nr, ++cl;
-      }
-    }
+    stage_halo<8>(halo, static_cast<const T*>(a.x) + ((int64_t)n * a.c + c_first) * a.h * a.w, a.ccs, a.c - c_first,
+                  a.nr, a.wp, a.h, a.w, oh_first - a.ph, a.pw, tid);
     sa.store(As0);
     __syncthreads();
 
@@ -485,6 +483,7 @@ __global__ __launch_bounds__(kThreads) void conv_halo_filter_kernel(HaloFilterAr
 
 bool conv_halo_filter_plan(const ConvGeom& g, HaloFilterPlan* p) {
   const int rs = g.r * g.s;
+  if ((int64_t)g.c * g.h * g.w > 0x7fffffffLL) return false;  // 32-bit offsets inside a sample
   p->bm = g.M <= 32 ? 32 : (g.M <= 64 ? 64 : 128);
   p->bnk = g.M <= 64 ? 256 : 128;
   p->wp = g.w + 2 * g.pw;
