@@ -113,7 +113,7 @@ def run_workload(name, steps, warmup, layer_iters=10):
         flops = 2.0 * g["M"] * g["K"] * g["N"]
         passes = {
             "fwd": lambda: vcnn.conv_fwd(d, a_in, w, b, a_out, ts.workspace),
-            "bwd_filter": lambda: vcnn.conv_bwd_filter(d, a_in, dy, dw, db, ts.workspace),
+            "bwd_filter": lambda: vcnn.conv_bwd_filter(d, a_in, dy, dw, db, ts.workspace_side),
             "bwd_data": lambda: vcnn.conv_bwd_data(d, w, dy, ts.dacts[li], ts.workspace),
         }
         in_b = esize * g["n"] * g["c"] * g["h"] * g["w"]

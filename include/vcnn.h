@@ -123,8 +123,10 @@ vcnn_status vcnn_act_bwd(int32_t act, int32_t dtype, size_t count, const void* r
  * y[b][o] = act(bias[o] + sum_i x[b][i]*w[o][i]);  x is [batch][in_f], w [out_f][in_f], y [batch][out_f]. */
 vcnn_status vcnn_fc_fwd(int32_t dtype, int32_t batch, int32_t in_f, int32_t out_f, int32_t act, const void* x,
                         const void* w, const float* bias, void* y, void* stream);
-/* dw[o][i] = sum_b dy[b][o]*x[b][i];  dbias[o] = sum_b dy[b][o] (nullable);  dx[b][i] = sum_o dy[b][o]*w[o][i]
- * (nullable).  dy is w.r.t. the pre-activation.  Needs no workspace. */
+/* dw[o][i] = sum_b dy[b][o]*x[b][i];  dbias[o] = sum_b dy[b][o];  dx[b][i] = sum_o dy[b][o]*w[o][i].
+ * Each of dw, dbias, dx may be NULL and is then not computed (so the parameter gradients and the input
+ * gradient can be issued on different streams); x is read only for dw, w only for dx.  dy is w.r.t. the
+ * pre-activation.  Needs no workspace. */
 vcnn_status vcnn_fc_bwd(int32_t dtype, int32_t batch, int32_t in_f, int32_t out_f, const void* x, const void* w,
                         const void* dy, float* dw, float* dbias, void* dx, void* stream);
 
@@ -139,6 +141,13 @@ vcnn_status vcnn_l2_loss(int32_t dtype, size_t count, int32_t batch, const void*
                          float* loss, void* dy, void* stream);
 /* Plain SGD on float parameters: w[i] -= lr * dw[i]. */
 vcnn_status vcnn_sgd_update(size_t count, float lr, float* w, const float* dw, void* stream);
+/* The same update for `tensors` parameter tensors in one launch (the experiments' networks have 4 to 10):
+ * w[t][i] -= lr * dw[t][i] for i < counts[t].  counts, w, dw and w_bf16 are HOST arrays of length `tensors`
+ * holding element counts and DEVICE pointers; they are read before the call returns.  w_bf16 may be NULL;
+ * a non-NULL w_bf16[t] receives the updated tensor rounded to bfloat16 (the working copy of the bf16
+ * variant).  Tensors with count 0 are skipped. */
+vcnn_status vcnn_sgd_update_multi(int32_t tensors, const size_t* counts, float* const* w, const float* const* dw,
+                                  void* const* w_bf16, float lr, void* stream);
 /* Rounds a float tensor to bfloat16 (nearest even) and back: dst_bf16[i] = bf16(src[i]);  src_f32[i] = float(bf16). */
 vcnn_status vcnn_f32_to_bf16(size_t count, const float* src, void* dst, void* stream);
 vcnn_status vcnn_bf16_to_f32(size_t count, const void* src, float* dst, void* stream);

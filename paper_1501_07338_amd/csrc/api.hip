@@ -433,9 +433,9 @@ vcnn_status vcnn_fc_bwd(int32_t dtype, int32_t batch, int32_t in_f, int32_t out_
                         const void* dy, float* dw, float* dbias, void* dx, void* stream) {
   if (vcnn_status s = check_fc(batch, in_f, out_f)) return s;
   if (vcnn_status s = check_dtype(dtype, "fc_bwd")) return s;
-  if (!x || !w || !dy || !dw) return fail(VCNN_ERR_NULL, "fc_bwd: NULL tensor");
+  if (!dy || (dw && !x) || (dx && !w)) return fail(VCNN_ERR_NULL, "fc_bwd: NULL tensor");
   hipStream_t st = (hipStream_t)stream;
-  {  // dW(i = o, j = i_) = sum_b dY[b][o] * X[b][i_]
+  if (dw) {  // dW(i = o, j = i_) = sum_b dY[b][o] * X[b][i_]
     GemmArgs a{};
     a.A = dy, a.B = x, a.C = dw;
     a.in_dtype = dtype, a.out_dtype = VCNN_F32;
@@ -479,6 +479,32 @@ vcnn_status vcnn_sgd_update(size_t count, float lr, float* w, const float* dw, v
   if (count == 0) return VCNN_OK;
   if (!w || !dw) return fail(VCNN_ERR_NULL, "sgd_update: NULL tensor");
   return launch_sgd_f32(count, lr, w, dw, (hipStream_t)stream);
+}
+
+vcnn_status vcnn_sgd_update_multi(int32_t tensors, const size_t* counts, float* const* w, const float* const* dw,
+                                  void* const* w_bf16, float lr, void* stream) {
+  if (tensors < 0) return fail(VCNN_ERR_SHAPE, "sgd_update_multi: negative tensor count");
+  if (tensors == 0) return VCNN_OK;
+  if (!counts || !w || !dw) return fail(VCNN_ERR_NULL, "sgd_update_multi: NULL argument array");
+  for (int t = 0; t < tensors; ++t)
+    if (counts[t] > 0 && (!w[t] || !dw[t])) return fail(VCNN_ERR_NULL, "sgd_update_multi: NULL tensor %d", t);
+  for (int t0 = 0; t0 < tensors; t0 += kSgdBatch) {
+    SgdBatch a{};
+    a.lr = lr;
+    uint64_t blocks = 0;
+    for (int t = t0; t < tensors && a.tensors < kSgdBatch; ++t) {
+      if (counts[t] == 0) continue;
+      const int k = a.tensors++;
+      a.w[k] = w[t], a.dw[k] = dw[t], a.w16[k] = w_bf16 ? w_bf16[t] : nullptr, a.count[k] = counts[t];
+      a.first[k] = (unsigned)blocks;
+      blocks += (counts[t] + 255) / 256;
+      if (blocks > 0x7fffffffULL) return fail(VCNN_ERR_SHAPE, "sgd_update_multi: too many elements for one launch");
+    }
+    if (a.tensors == 0) continue;
+    a.first[a.tensors] = (unsigned)blocks;
+    if (vcnn_status s = launch_sgd_multi(a, (hipStream_t)stream)) return s;
+  }
+  return VCNN_OK;
 }
 
 vcnn_status vcnn_f32_to_bf16(size_t count, const float* src, void* dst, void* stream) {

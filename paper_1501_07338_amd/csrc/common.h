@@ -153,6 +153,18 @@ vcnn_status launch_softmax_loss_f32(int batch, int classes, const float* z, cons
 vcnn_status launch_l2_loss(int dtype, size_t count, int batch, const void* y, const float* t, float* loss, void* dy,
                            hipStream_t st);
 vcnn_status launch_sgd_f32(size_t count, float lr, float* w, const float* dw, hipStream_t st);
+// up to kSgdBatch tensors per launch; first[t] = index of tensor t's first block, first[tensors] = grid size
+static constexpr int kSgdBatch = 16;
+struct SgdBatch {
+  float* w[kSgdBatch];
+  const float* dw[kSgdBatch];
+  void* w16[kSgdBatch];  // optional bfloat16 copy of the updated tensor
+  size_t count[kSgdBatch];
+  unsigned first[kSgdBatch + 1];
+  int tensors;
+  float lr;
+};
+vcnn_status launch_sgd_multi(const SgdBatch& a, hipStream_t st);
 vcnn_status launch_f32_to_bf16(size_t count, const float* src, uint16_t* dst, hipStream_t st);
 vcnn_status launch_bf16_to_f32(size_t count, const uint16_t* src, float* dst, hipStream_t st);
 

@@ -239,14 +239,26 @@ vcnn_status launch_flip_transpose(int dtype, const void* w, void* w2, int M, int
 static constexpr size_t kLdsBudget = 76 * 1024;  // two blocks per CU out of 160 KB
 
 static int halo_bm(int m) { return m <= 32 ? 32 : (m <= 64 ? 64 : 128); }
-static int halo_bn(int m) { return m <= 64 ? 256 : 128; }
+// Pixel tile: the widest tile unless a narrower one pads a small image much less (narrow tiles do fewer
+// MFMAs per LDS read, hence the handicap).
+static int halo_bn(int m, int64_t P) {
+  const int widest = m <= 64 ? 256 : 128;
+  int best = widest;
+  double best_cost = (double)ceil_div(P, widest) * widest;
+  for (int bn = widest / 2; bn >= 64; bn /= 2) {
+    if (m <= 32 && bn < 128) break;  // 32-row tiles keep their four waves side by side
+    const double cost = (double)ceil_div(P, bn) * bn * (bn == 64 ? 1.25 : 1.1);
+    if (cost < best_cost) best = bn, best_cost = cost;
+  }
+  return best;
+}
 // Slab depth: narrow row tiles do few MFMAs per slab, so they take deeper slabs (fewer barriers per MFMA).
 static int halo_bk(int m) { return m <= 64 ? 64 : 32; }
 
 bool conv_halo_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int pw, HaloPlan* p) {
   const int oh = h + 2 * ph - r + 1, ow = w + 2 * pw - s + 1;
   if (oh <= 0 || ow <= 0 || (int64_t)c * h * w > 0x7fffffffLL) return false;  // 32-bit offsets inside a sample
-  const int bm = halo_bm(m), bn = halo_bn(m), BK = halo_bk(m);
+  const int bm = halo_bm(m), bn = halo_bn(m, (int64_t)oh * ow), BK = halo_bk(m);
   const int rs = r * s;
   int rows = (bn + ow - 2) / ow + 1;  // rows a run of bn consecutive pixels can touch
   if (rows > oh) rows = oh;
@@ -320,12 +332,20 @@ vcnn_status launch_conv_halo(const HaloPlan& p, int dtype, int n, int c, int h, 
   a.tiles_per_img = (int)ceil_div(a.P, p.bn);
   a.cc = p.cc, a.nr = p.nr, a.wp = p.wp, a.kch = p.kch, a.relu = relu;
   const bool vec = p.vec && (dtype == VCNN_BF16 ? group_aligned<bf16>(wgt) : group_aligned<float>(wgt));
-  if (p.bm == 32)
+  if (p.bm == 32 && p.bn == 256)
     launch_halo<32, 256, 32, 64, 64>(a, p, vec, dtype, st);
-  else if (p.bm == 64)
+  else if (p.bm == 32)
+    launch_halo<32, 128, 32, 32, 64>(a, p, vec, dtype, st);
+  else if (p.bm == 64 && p.bn == 256)
     launch_halo<64, 256, 64, 64, 64>(a, p, vec, dtype, st);
-  else
+  else if (p.bm == 64 && p.bn == 128)
+    launch_halo<64, 128, 32, 64, 64>(a, p, vec, dtype, st);
+  else if (p.bm == 64)
+    launch_halo<64, 64, 32, 32, 64>(a, p, vec, dtype, st);
+  else if (p.bn == 128)
     launch_halo<128, 128, 64, 64, 32>(a, p, vec, dtype, st);
+  else
+    launch_halo<128, 64, 32, 64, 32>(a, p, vec, dtype, st);
   return check_launch("conv_halo");
 }
 

@@ -391,6 +391,22 @@ vcnn_status launch_sgd_f32(size_t count, float lr, float* w, const float* dw, hi
   return check_launch("sgd_f32");
 }
 
+// Several parameter tensors in one launch: block b works on tensor t with first[t] <= b < first[t+1].
+__global__ __launch_bounds__(kThreads) void sgd_multi_kernel(SgdBatch a) {
+  int t = 0;
+  while (t + 1 < a.tensors && blockIdx.x >= a.first[t + 1]) ++t;
+  const size_t i = (size_t)(blockIdx.x - a.first[t]) * kThreads + threadIdx.x;
+  if (i >= a.count[t]) return;
+  const float v = a.w[t][i] - a.lr * a.dw[t][i];
+  a.w[t][i] = v;
+  if (a.w16[t]) st(reinterpret_cast<bf16*>(a.w16[t]) + i, v);
+}
+
+vcnn_status launch_sgd_multi(const SgdBatch& a, hipStream_t st) {
+  hipLaunchKernelGGL(sgd_multi_kernel, dim3(a.first[a.tensors]), dim3(kThreads), 0, st, a);
+  return check_launch("sgd_multi");
+}
+
 // ---- bfloat16 conversion --------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void f32_to_bf16_kernel(size_t count, const float* __restrict__ src,
                                                                bf16* __restrict__ dst) {

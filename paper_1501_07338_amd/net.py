@@ -1,6 +1,12 @@
 """Sequences the C-ABI layer calls into one training step of a layer chain (forward, cost, backward,
-SGD) on one GPU.  This module only owns buffers (torch device tensors) and call order; every
+SGD) on one GPU.  This module only owns buffers (torch device tensors), streams and call order; every
 arithmetic step runs inside libvcnn's kernels.
+
+The backward pass has two independent strands per layer: the input gradient, which the next layer
+down waits for, and the parameter gradients, which only the update at the end of the step needs.
+With `overlap=True` the parameter gradients are issued on a second stream (own workspace), forked
+after each layer's pre-activation gradient is ready and joined before the update, so the small layers'
+launch-bound kernels run side by side.  Captured into a HIP graph the fork/join become graph edges.
 """
 from __future__ import annotations
 
@@ -17,9 +23,10 @@ class TrainStep:
     """Device-resident state of one network: parameters, activations, gradients, workspace."""
 
     def __init__(self, net: Net, params: list, inputs: dict, device: str = "cuda:0", first_layer_dx: bool = False,
-                 dtype: int = vcnn.F32):
+                 dtype: int = vcnn.F32, overlap: bool = True):
         self.net, self.dev, self.dtype = net, torch.device(device), dtype
         self.first_layer_dx = first_layer_dx
+        self.side = torch.cuda.Stream(self.dev) if overlap else None  # default priority
         f32 = dict(dtype=torch.float32, device=self.dev)
         # element type of activations and their gradients; parameters, their gradients and the loss stay fp32
         act = dict(dtype=torch.bfloat16 if dtype == vcnn.BF16 else torch.float32, device=self.dev)
@@ -43,22 +50,25 @@ class TrainStep:
                        for li, L in enumerate(net.layers) if isinstance(L, Pool)}
         self.loss = torch.zeros((), **f32)
         self.descs = {}
-        ws_bytes, dpre_elems = 0, 0
+        ws_bytes, ws_side_bytes = 0, 0
+        self.dpre, self.forked = {}, {}
         for li, L in enumerate(net.layers):
             ishape = net.in_shape(li)
             if isinstance(L, Conv):
                 d = vcnn.conv_desc(ishape[0], ishape[1], ishape[2], ishape[3], L.cout, L.kh, L.kw, L.pad_h, L.pad_w,
                                    dtype=dtype, act=vcnn.ACT_RELU if L.relu else vcnn.ACT_NONE)
                 self.descs[li] = d
-                ws_bytes = max(ws_bytes, *(vcnn.conv_workspace_bytes(d, p) for p in
-                                           (vcnn.PASS_FWD, vcnn.PASS_BWD_FILTER, vcnn.PASS_BWD_DATA)))
+                ws_bytes = max(ws_bytes, *(vcnn.conv_workspace_bytes(d, p) for p in (vcnn.PASS_FWD, vcnn.PASS_BWD_DATA)))
+                ws_side_bytes = max(ws_side_bytes, vcnn.conv_workspace_bytes(d, vcnn.PASS_BWD_FILTER))
             elif isinstance(L, Pool):
                 self.descs[li] = vcnn.pool_desc(ishape[0], ishape[1], ishape[2], ishape[3], L.win, L.win, L.stride,
                                                 L.stride, dtype=dtype)
-            if getattr(L, "relu", False):
-                dpre_elems = max(dpre_elems, int(np.prod(net.shapes[li])))
+            if getattr(L, "relu", False):  # gradient w.r.t. the pre-activation, read by both strands
+                self.dpre[li] = torch.empty(net.shapes[li], **act)
+            if isinstance(L, (Conv, FC)):
+                self.forked[li] = torch.cuda.Event()
         self.workspace = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=self.dev)
-        self.dpre = torch.empty(max(dpre_elems, 1), **act)
+        self.workspace_side = torch.empty(max(ws_side_bytes, 256), dtype=torch.uint8, device=self.dev)
         if dtype == vcnn.BF16 and net.loss == "softmax":  # the cost works on float logits
             self.logits32 = torch.empty(net.out_shape, **f32)
             self.dlogits32 = torch.empty(net.out_shape, **f32)
@@ -110,36 +120,43 @@ class TrainStep:
 
     def backward(self, stream=None):
         net = self.net
+        main = stream if stream is not None else torch.cuda.current_stream()
+        side = self.side if self.side is not None else main
         for li in range(len(net.layers) - 1, -1, -1):
             L = net.layers[li]
             a_in, a_out, d = self.acts[li], self.acts[li + 1], self.dacts[li + 1]
             need_dx = li > 0 or self.first_layer_dx
             if getattr(L, "relu", False):
-                dpre = self.dpre[:d.numel()]
-                vcnn.act_bwd(vcnn.ACT_RELU, self.dtype, d.numel(), a_out, d, dpre, stream)
-                d = dpre
+                vcnn.act_bwd(vcnn.ACT_RELU, self.dtype, d.numel(), a_out, d, self.dpre[li], main)
+                d = self.dpre[li]
+            if isinstance(L, Pool):
+                if need_dx:
+                    vcnn.pool_bwd(self.descs[li], d, self.argmax[li], self.dacts[li], main)
+                continue
+            if side is not main:  # fork: the parameter-gradient strand starts once d is complete
+                self.forked[li].record(main)
+                side.wait_event(self.forked[li])
+            w = self.weights(li)
+            dw, db = self.grads[li]
             if isinstance(L, Conv):
-                w = self.weights(li)
-                dw, db = self.grads[li]
-                vcnn.conv_bwd_filter(self.descs[li], a_in, d, dw, db, self.workspace, stream)
+                vcnn.conv_bwd_filter(self.descs[li], a_in, d, dw, db, self.workspace_side, side)
                 if need_dx:
-                    vcnn.conv_bwd_data(self.descs[li], w, d, self.dacts[li], self.workspace, stream)
-            elif isinstance(L, Pool):
-                if need_dx:
-                    vcnn.pool_bwd(self.descs[li], d, self.argmax[li], self.dacts[li], stream)
+                    vcnn.conv_bwd_data(self.descs[li], w, d, self.dacts[li], self.workspace, main)
             else:
-                w = self.weights(li)
-                dw, db = self.grads[li]
                 bsz = a_in.shape[0]
-                vcnn.fc_bwd(self.dtype, bsz, a_in.numel() // bsz, L.out, a_in, w, d, dw, db,
-                            self.dacts[li] if need_dx else None, stream)
+                vcnn.fc_bwd(self.dtype, bsz, a_in.numel() // bsz, L.out, a_in, w, d, dw, db, None, side)
+                if need_dx:
+                    vcnn.fc_bwd(self.dtype, bsz, a_in.numel() // bsz, L.out, a_in, w, d, None, None, self.dacts[li], main)
+        if side is not main:  # join before anything reads the parameter gradients
+            main.wait_stream(side)
 
     def update(self, stream=None):
-        for p, g in zip(self.params, self.grads):
-            if p is not None:
-                vcnn.sgd_update(p[0].numel(), self.net.lr, p[0], g[0], stream)
-                vcnn.sgd_update(p[1].numel(), self.net.lr, p[1], g[1], stream)
-        self.refresh_weights(stream)
+        ws = [t for p in self.params if p is not None for t in p]
+        gs = [t for g in self.grads if g is not None for t in g]
+        w16 = None
+        if self.dtype == vcnn.BF16:  # the weights' bf16 working copies are refreshed by the same launch
+            w16 = [t for p, h in zip(self.params, self.params16) if p is not None for t in (h, None)]
+        vcnn.sgd_update_multi(self.net.lr, ws, gs, w16, stream)
 
     def step(self, stream=None):
         self.forward(stream)

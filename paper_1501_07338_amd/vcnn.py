@@ -60,6 +60,7 @@ _SIGNATURES = {
     "vcnn_softmax_loss": (c_int32, [c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
     "vcnn_l2_loss": (c_int32, [c_int32, c_size_t, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
     "vcnn_sgd_update": (c_int32, [c_size_t, c_float, c_void_p, c_void_p, c_void_p]),
+    "vcnn_sgd_update_multi": (c_int32, [c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_float, c_void_p]),
     "vcnn_f32_to_bf16": (c_int32, [c_size_t, c_void_p, c_void_p, c_void_p]),
     "vcnn_bf16_to_f32": (c_int32, [c_size_t, c_void_p, c_void_p, c_void_p]),
 }
@@ -204,6 +205,16 @@ def l2_loss(dtype, count, batch, y, target, loss, dy, stream=None):
 
 def sgd_update(count, lr, w, dw, stream=None):
     _check(lib().vcnn_sgd_update(count, lr, _ptr(w), _ptr(dw), _stream(stream)))
+
+
+def sgd_update_multi(lr, ws, dws, w16s=None, stream=None):
+    """One launch for a list of parameter tensors; w16s (optional) are their bfloat16 working copies."""
+    n = len(ws)
+    counts = (c_size_t * n)(*[w.numel() for w in ws])
+    wp = (c_void_p * n)(*[_ptr(w) for w in ws])
+    dp = (c_void_p * n)(*[_ptr(g) for g in dws])
+    hp = None if w16s is None else (c_void_p * n)(*[_ptr(h) for h in w16s])
+    _check(lib().vcnn_sgd_update_multi(n, counts, wp, dp, hp, lr, _stream(stream)))
 
 
 def f32_to_bf16(count, src, dst, stream=None):

@@ -219,6 +219,11 @@ def test_fc(b, i, o, relu):
     assert_close(to_np(dw), rdw, TOL_F32, "fc dw")
     assert_close(to_np(db), rdb, TOL_F32, "fc db")
     assert_close(to_np(dx), rdx, TOL_F32, "fc dx")
+    # the two strands issued separately (parameter gradients / input gradient) give the same bits
+    dw2, db2, dx2 = torch.full_like(dw, float("nan")), torch.full_like(db, float("nan")), torch.full_like(dx, float("nan"))
+    vcnn.fc_bwd(vcnn.F32, b, i, o, to_dev(x), None, to_dev(dy), dw2, db2, None)
+    vcnn.fc_bwd(vcnn.F32, b, i, o, None, to_dev(w), to_dev(dy), None, None, dx2)
+    assert torch.equal(dw, dw2) and torch.equal(db, db2) and torch.equal(dx, dx2)
 
 
 @pytest.mark.parametrize("b,c", [(128, 10), (1, 10), (300, 7), (5, 1)])
@@ -255,6 +260,33 @@ def test_l2_loss_and_sgd(shape):
     w = to_dev(y)
     vcnn.sgd_update(y.size, 0.01, w, to_dev(t))
     assert_close(to_np(w), O.sgd_update(y, t, 0.01), 1e-6, "sgd")
+
+
+def test_sgd_update_multi_matches_oracle_per_tensor():
+    """Several parameter tensors of ragged sizes in one launch (one of them empty), with and without the
+    bfloat16 working copy."""
+    shapes = [(500, 800), (500,), (1,), (0,), (50, 20, 5, 5), (257,), (10, 500), (3, 3)]
+    ws = [random_tensor(1300 + k, sh) for k, sh in enumerate(shapes)]
+    gs = [random_tensor(1400 + k, sh) for k, sh in enumerate(shapes)]
+    wd, gd = [to_dev(w) for w in ws], [to_dev(g) for g in gs]
+    w16 = [torch.full(sh, float("nan"), dtype=torch.bfloat16, device=DEV) if k % 2 == 0 else None
+           for k, sh in enumerate(shapes)]
+    vcnn.sgd_update_multi(0.01, wd, gd, w16)
+    for k, (w, g) in enumerate(zip(ws, gs)):
+        if w.size == 0:
+            continue
+        ref = O.sgd_update(w, g, 0.01)
+        assert_close(to_np(wd[k]), ref, 1e-6, f"sgd tensor {k}")
+        if w16[k] is not None:  # the copy is the rounding of the updated fp32 value: bit-exact against torch's rounding
+            torch.cuda.synchronize()
+            assert torch.equal(w16[k], wd[k].to(torch.bfloat16))
+    # more tensors than one launch holds
+    many = [to_dev(random_tensor(1500 + k, (33 + k,))) for k in range(40)]
+    grads = [to_dev(random_tensor(1600 + k, (33 + k,))) for k in range(40)]
+    before = [to_np(t).copy() for t in many]
+    vcnn.sgd_update_multi(0.5, many, grads)
+    for k in range(40):
+        assert_close(to_np(many[k]), O.sgd_update(before[k], to_np(grads[k]), 0.5), 1e-6, f"sgd many {k}")
 
 
 def test_gpu_launch_of_bad_arguments_is_rejected_cleanly():
