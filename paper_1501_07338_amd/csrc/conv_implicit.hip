@@ -239,16 +239,20 @@ vcnn_status launch_flip_transpose(int dtype, const void* w, void* w2, int M, int
 static constexpr size_t kLdsBudget = 76 * 1024;  // two blocks per CU out of 160 KB
 
 static int halo_bm(int m) { return m <= 32 ? 32 : (m <= 64 ? 64 : 128); }
-// Pixel tile: the widest tile unless a narrower one pads a small image much less (narrow tiles do fewer
-// MFMAs per LDS read, hence the handicap).
-static int halo_bn(int m, int64_t P) {
+// Pixel tile: the widest tile unless a narrower one pads a small image less.  Narrow tiles do fewer MFMAs
+// per LDS read, so they carry a handicap - but only once the launch fills the chip; below that, more and
+// shorter blocks win.
+static int halo_bn(int m, int64_t P, int n) {
   const int widest = m <= 64 ? 256 : 128;
-  int best = widest;
-  double best_cost = (double)ceil_div(P, widest) * widest;
-  for (int bn = widest / 2; bn >= 64; bn /= 2) {
+  const int64_t row_tiles = ceil_div(m, halo_bm(m));
+  int best = 0;
+  double best_cost = 0;
+  for (int bn = widest; bn >= 64; bn /= 2) {
     if (m <= 32 && bn < 128) break;  // 32-row tiles keep their four waves side by side
-    const double cost = (double)ceil_div(P, bn) * bn * (bn == 64 ? 1.25 : 1.1);
-    if (cost < best_cost) best = bn, best_cost = cost;
+    const int64_t tiles = row_tiles * n * ceil_div(P, bn);
+    const double handicap = tiles >= 512 ? (bn == widest ? 1.0 : (2 * bn == widest ? 1.1 : 1.25)) : 1.0;
+    const double cost = (double)ceil_div(P, bn) * bn * handicap;
+    if (best == 0 || cost < best_cost - 1e-9 || (cost < best_cost + 1e-9 && tiles <= 1024)) best = bn, best_cost = cost;
   }
   return best;
 }
@@ -258,7 +262,7 @@ static int halo_bk(int m) { return m <= 64 ? 64 : 32; }
 bool conv_halo_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int pw, HaloPlan* p) {
   const int oh = h + 2 * ph - r + 1, ow = w + 2 * pw - s + 1;
   if (oh <= 0 || ow <= 0 || (int64_t)c * h * w > 0x7fffffffLL) return false;  // 32-bit offsets inside a sample
-  const int bm = halo_bm(m), bn = halo_bn(m, (int64_t)oh * ow), BK = halo_bk(m);
+  const int bm = halo_bm(m), bn = halo_bn(m, (int64_t)oh * ow, n), BK = halo_bk(m);
   const int rs = r * s;
   int rows = (bn + ow - 2) / ow + 1;  // rows a run of bn consecutive pixels can touch
   if (rows > oh) rows = oh;
