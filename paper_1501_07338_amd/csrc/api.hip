@@ -111,14 +111,14 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
   const bool allow_direct = algo != VCNN_ALGO_EXPLICIT;
   // bf16 variant, default route: the bf16 matrix-core kernels wherever the layer has enough maps / channels
   const bool bf16_mfma = dtype == VCNN_BF16 && algo == VCNN_ALGO_AUTO;
-  // (1x1 layers stay on the plain product: they reuse no input element across taps, so staging would dominate)
-  if (bf16_mfma && pass == VCNN_PASS_FWD && g.k > 4 && !is_pointwise(g) &&
+  // (1x1 layers included: with asynchronous staging they are a plain bf16 product through the same kernel)
+  if (bf16_mfma && pass == VCNN_PASS_FWD && g.k > 4 &&
       conv_halo_bf16_plan(g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, &p.hb)) {
     p.path = PATH_HALO_BF16;
     p.workspace_bytes = p.hb.x8_bytes + p.hb.wf_bytes;
     return p;
   }
-  if (bf16_mfma && pass == VCNN_PASS_BWD_DATA && g.c > 4 && !is_pointwise(g) && g.r - 1 - g.ph >= 0 && g.s - 1 - g.pw >= 0 &&
+  if (bf16_mfma && pass == VCNN_PASS_BWD_DATA && g.c > 4 && g.r - 1 - g.ph >= 0 && g.s - 1 - g.pw >= 0 &&
       conv_halo_bf16_plan(g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, &p.hb)) {
     p.path = PATH_HALO_BF16;
     p.workspace_bytes = p.hb.x8_bytes + p.hb.wf_bytes;

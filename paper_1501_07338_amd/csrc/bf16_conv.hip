@@ -6,7 +6,10 @@
 //
 //  * The input is first re-laid channel-interleaved, x8[n][c/8][h][w][8] (one small pass over the
 //    tensor), so that a halo position is one 16-byte word holding the 8 contraction elements a lane
-//    feeds to one MFMA, and staging is one 16-byte load + one 16-byte LDS store per position.
+//    feeds to one MFMA.  The halo tile is double buffered and filled with direct global->LDS loads
+//    (global_load_lds_dwordx4: lane i of a wave deposits its 16 bytes at base + 16 i), issued for the
+//    next chunk of channel groups before the MFMAs of the current one, so staging overlaps compute and
+//    a chunk change costs one barrier.  Positions outside the image read a 16-byte block of zeros.
 //  * The kernel matrix never goes through LDS.  It is re-ordered once per call into MFMA fragment order,
 //    wf[row tile][chunk][step][lane][8]: the A operand of a step is one fully coalesced 1 KB read per
 //    wave straight from L2 into registers, prefetched one slab (4 steps) ahead.  Without a shared A
@@ -35,10 +38,11 @@ __device__ __forceinline__ f32x16 mfma_bf16(uint4 a, uint4 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
-// x8[n][g][pos][c8] = x[n][8g + c8][pos], zero for channels >= C
+// x8[n][g][pos][c8] = x[n][8g + c8][pos], zero for channels >= C; x8[total] = 0 (the padding source)
 __global__ __launch_bounds__(kThreads) void interleave_channels_kernel(const bf16* __restrict__ x, uint4* __restrict__ x8,
                                                                        int C, int CG, int HW, int64_t total) {
   const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i == 0) x8[total] = make_uint4(0u, 0u, 0u, 0u);
   if (i >= total) return;
   const int pos = (int)(i % HW);
   const int64_t t = i / HW;
@@ -83,6 +87,7 @@ __global__ __launch_bounds__(kThreads) void reorder_weights_frag_kernel(const bf
 
 struct HaloBf16Args {
   const uint4* x8;    // [n][cg][h][w] positions of 8 channels
+  const uint4* zero;  // 16 zero bytes
   const uint4* wf;    // [mt][chunk][step][64 lanes] fragments
   const float* bias;  // [m] or null
   bf16* y;            // [n][m][oh][ow]
@@ -91,6 +96,7 @@ struct HaloBf16Args {
   int cg, cgc, nchunks;
   int nr, wp;         // halo rows and row pitch (positions) per group
   int uch;            // (group, tap) pairs per chunk, padded to a multiple of 8
+  int hpos;           // positions per halo buffer (cgc*nr*wp rounded up to a multiple of 64)
   int relu;
 };
 
@@ -101,7 +107,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
   constexpr int BM = 32 * TM * WAVES_M, BN = 32 * TN;
   extern __shared__ uint4 smem16[];
   int* const tbl = reinterpret_cast<int*>(smem16);  // [uch], per slab of 8 pairs: [half][4]
-  uint4* const halo = smem16 + a.uch / 4;           // [cgc][nr][wp]
+  uint4* const hbuf = smem16 + a.uch / 4;           // 2 x [cgc][nr][wp], each padded to hpos positions
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
@@ -163,39 +169,37 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
   const int first_sl = min(wave_k, chunk_slabs - 1);
   load_a(0, first_sl);
 
-  // flat position walk of the staging loop (same for every chunk)
+  // Asynchronous halo staging: positions in flat tile order, 64 consecutive positions per wave and
+  // load instruction; the walk (rx, ry, gl) is the same for every chunk.
   const int dq = kThreads / a.wp, dr = kThreads - dq * a.wp;
   const int row_s = tid / a.wp, rx_s = tid - row_s * a.wp;
   const int gl_s = row_s / a.nr, ry_s = row_s - gl_s * a.nr;
+  auto stage = [&](int ch, uint4* dst) {
+    const int g0 = ch * a.cgc;
+    const int npos = min(a.cgc, a.cg - g0) * plane;
+    int rx = rx_s, ry = ry_s, gl = gl_s;
+    for (int b0 = wave * 64; b0 < npos; b0 += kThreads) {  // b0: first position of this wave's 64 (uniform)
+      const int ih = oh_first - a.ph + ry, iw = rx - a.pw;
+      const bool ok = b0 + lane < npos && ih >= 0 && ih < a.h && iw >= 0 && iw < a.w;
+      const uint4* src = ok ? x8n + ((g0 + gl) * a.h + ih) * a.w + iw : a.zero;
+      __builtin_amdgcn_global_load_lds(src, dst + b0, 16, 0, 0);
+      rx += dr;
+      ry += dq;
+      if (rx >= a.wp) rx -= a.wp, ++ry;
+      while (ry >= a.nr) ry -= a.nr, ++gl;
+    }
+  };
+  stage(0, hbuf);
 
   for (int ch = 0; ch < a.nchunks; ++ch) {
-    const int g0 = ch * a.cgc;
-    const int cgc = min(a.cgc, a.cg - g0);
-    const int ulen = cgc * RS;  // valid (group, tap) pairs in this chunk
+    const int ulen = min(a.cgc, a.cg - ch * a.cgc) * RS;  // valid (group, tap) pairs in this chunk
     const int slabs = (ulen + 7) >> 3;
-    __syncthreads();  // the previous chunk's MFMAs are done with the halo tile (first pass: the table is complete)
-    {
-      const int npos = cgc * plane;
-      int rx = rx_s, ry = ry_s, gl = gl_s;
-      for (int e0 = tid; e0 < npos; e0 += 4 * kThreads) {
-        uint4 v[4];
-        bool ok[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int ih = oh_first - a.ph + ry, iw = rx - a.pw;
-          ok[u] = e0 + u * kThreads < npos && ih >= 0 && ih < a.h && iw >= 0 && iw < a.w;
-          v[u] = x8n[ok[u] ? ((g0 + gl) * a.h + ih) * a.w + iw : 0];
-          rx += dr;
-          ry += dq;
-          if (rx >= a.wp) rx -= a.wp, ++ry;
-          while (ry >= a.nr) ry -= a.nr, ++gl;
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-          if (e0 + u * kThreads < npos) halo[e0 + u * kThreads] = ok[u] ? v[u] : make_uint4(0u, 0u, 0u, 0u);
-      }
-    }
+    const uint4* halo = hbuf + (ch & 1) * a.hpos;
+    // this chunk's tile has landed (every wave waits for its own loads, the barrier publishes them) and
+    // every wave is done with the other buffer (first pass: the table is complete)
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     __syncthreads();
+    if (ch + 1 < a.nchunks) stage(ch + 1, hbuf + ((ch + 1) & 1) * a.hpos);
 
     for (int sl = wave_k; sl < slabs; sl += WAVES_K) {
       // where this wave continues: next slab of this chunk, else its first slab of the next chunk (the
@@ -300,7 +304,8 @@ bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph
     int cgc = 0;
     for (int t = 1; t <= cg; ++t) {
       const int uch = (int)ceil_div((int64_t)t * rs, 8) * 8;
-      if ((size_t)uch * 4 + (size_t)t * nr * wp * 16 > kLdsBudget || uch > 4096) break;
+      const size_t hpos = ((size_t)t * nr * wp + 63) & ~(size_t)63;
+      if ((size_t)uch * 4 + 2 * hpos * 16 > kLdsBudget || uch > 4096) break;
       cgc = t;
     }
     if (cgc == 0) continue;
@@ -323,8 +328,9 @@ bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph
   p->tn = best_tn, p->cg = cg, p->cgc = pick, p->nchunks = (int)ceil_div(cg, pick), p->nr = best_nr, p->wp = wp;
   p->uch = (int)ceil_div((int64_t)pick * rs, 8) * 8;
   const size_t red_bytes = waves_k > 1 ? (size_t)p->waves_m * 2 * best_tn * 16 * 64 * sizeof(float) : 0;
-  p->lds_bytes = std::max((size_t)p->uch * 4 + (size_t)pick * best_nr * wp * 16, red_bytes);
-  p->x8_bytes = ((size_t)n * cg * h * w * 16 + 255) & ~(size_t)255;
+  p->hpos = (int)(((size_t)pick * best_nr * wp + 63) & ~(size_t)63);
+  p->lds_bytes = std::max((size_t)p->uch * 4 + 2 * (size_t)p->hpos * 16, red_bytes);
+  p->x8_bytes = (((size_t)n * cg * h * w + 1) * 16 + 255) & ~(size_t)255;  // + the block of zeros
   p->wf_bytes = ((size_t)tiles_m * (bm / 32) * p->nchunks * (p->uch / 2) * 64 * 16 + 255) & ~(size_t)255;
   return true;
 }
@@ -370,13 +376,13 @@ vcnn_status launch_conv_halo_bf16(const HaloBf16Plan& p, int n, int c, int h, in
     if (vcnn_status e = check_launch("reorder_weights_frag")) return e;
   }
   HaloBf16Args a{};
-  a.x8 = x8, a.wf = (const uint4*)wf, a.bias = bias, a.y = (bf16*)y;
+  a.x8 = x8, a.zero = x8 + (int64_t)n * p.cg * h * w, a.wf = (const uint4*)wf, a.bias = bias, a.y = (bf16*)y;
   a.n = n, a.h = h, a.w = w, a.m = m, a.r = r, a.s = s, a.ph = ph, a.pw = pw;
   a.oh = h + 2 * ph - r + 1, a.ow = w + 2 * pw - s + 1;
   a.P = a.oh * a.ow;
   a.tiles_m = tiles_m;
   a.tiles_per_img = (int)ceil_div(a.P, 32 * p.tn);
-  a.cg = p.cg, a.cgc = p.cgc, a.nchunks = p.nchunks, a.nr = p.nr, a.wp = p.wp, a.uch = p.uch, a.relu = relu;
+  a.cg = p.cg, a.cgc = p.cgc, a.nchunks = p.nchunks, a.nr = p.nr, a.wp = p.wp, a.uch = p.uch, a.hpos = p.hpos, a.relu = relu;
   if (p.tn == 2) launch_tn<2>(a, p.waves_m, p.lds_bytes, st);
   else if (p.tn == 4) launch_tn<4>(a, p.waves_m, p.lds_bytes, st);
   else launch_tn<5>(a, p.waves_m, p.lds_bytes, st);

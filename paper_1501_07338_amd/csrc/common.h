@@ -115,6 +115,7 @@ struct HaloBf16Plan {
   int nchunks;
   int nr, wp;        // halo rows and row pitch (positions of 8 channels) per group
   int uch;           // (group, tap) pairs per chunk, padded to a multiple of 8
+  int hpos;          // positions per halo buffer
   size_t lds_bytes;
   size_t x8_bytes, wf_bytes;  // workspace: channel-interleaved input, fragment-ordered kernel matrix
 };
