@@ -90,7 +90,7 @@ static bool halo_bwd_data_pays(const ConvGeom& g, const HaloPlan& hp) {
 
 // Which realisation a pass uses for a given shape.  The same decision drives the workspace query and
 // the launch, so the two always agree.
-enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER, PATH_HALO, PATH_HALO_FILTER, PATH_HALO_BF16, PATH_FILTER_BF16 };
+enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER, PATH_HALO, PATH_HALO_FILTER, PATH_HALO_BF16, PATH_FILTER_BF16, PATH_HALO_FILTER_BF16 };
 struct Plan {
   Path path;
   DirectGeom dg;
@@ -98,6 +98,7 @@ struct Plan {
   HaloFilterPlan hfp;
   HaloBf16Plan hb;
   BwdFilterBf16Plan fb;
+  FilterGradBf16Plan hfb;
   int split;        // channel slices (few-out), output-map group size (few-in) or batch slices (filter gradient)
   size_t partial_bytes;
   size_t workspace_bytes;
@@ -122,6 +123,13 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
       conv_halo_bf16_plan(g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, &p.hb)) {
     p.path = PATH_HALO_BF16;
     p.workspace_bytes = p.hb.x8_bytes + p.hb.wf_bytes;
+    return p;
+  }
+  if (bf16_mfma && pass == VCNN_PASS_BWD_FILTER && g.k > 4 && g.c > 4 && filter_grad_bf16_plan(g, &p.hfb)) {
+    p.path = PATH_HALO_FILTER_BF16;
+    p.workspace_bytes = p.hfb.x8n_bytes + p.hfb.dyf_bytes + align256(p.hfb.partial_bytes);
+    p.bias_offset = p.workspace_bytes;
+    p.workspace_bytes += align256(bias_grad_partial_bytes(g));
     return p;
   }
   if (bf16_mfma && pass == VCNN_PASS_BWD_FILTER && bwd_filter_bf16_plan(g, &p.fb)) {
@@ -297,6 +305,8 @@ vcnn_status vcnn_conv_bwd_filter(const vcnn_conv_desc* d, const void* x, const v
   float* bias_partial = (float*)((char*)workspace + plan.bias_offset);
   if (plan.path == PATH_DIRECT_FILTER) {
     if (vcnn_status s = launch_direct_filter_grad(plan.dg, dt, plan.split, x, dy, dw, (float*)workspace, st)) return s;
+  } else if (plan.path == PATH_HALO_FILTER_BF16) {
+    if (vcnn_status s = launch_filter_grad_bf16(plan.hfb, g, x, dy, dw, workspace, st)) return s;
   } else if (plan.path == PATH_FILTER_BF16) {
     if (vcnn_status s = launch_bwd_filter_bf16(plan.fb, g, x, dy, dw, workspace, st)) return s;
   } else if (plan.path == PATH_HALO_FILTER) {

@@ -389,4 +389,345 @@ vcnn_status launch_conv_halo_bf16(const HaloBf16Plan& p, int n, int c, int h, in
   return check_launch("conv_halo_bf16");
 }
 
+// =========================================================================================================
+// Filter gradient of the bf16 variant, dW[m][(c,r,s)] = sum_{n,pixel} dY[n][m][pixel] * xpad[n][c][pixel + (r,s)],
+// as the mirror image of the kernel above: output maps on the MFMA rows, kernel-matrix columns (c,r,s) on
+// the MFMA columns, contraction over (image, pixel).  The 8 contraction elements a lane feeds to one MFMA
+// are the same pixel of 8 consecutive images, so both tensors are first re-laid image-interleaved:
+//   x8n[n/8][c][h][w][8]                       staged (rows + halo) in LDS, read at tap_base(column) + pixel_offset(step);
+//   dyf[n/8][row tile][run][step][lane][8]     dY in MFMA fragment order, read straight from L2.
+// A chunk of the contraction is (image group, run of bh output rows); chunks are split over blockIdx.y and
+// the partial products added in a fixed order by a second kernel.
+// =========================================================================================================
+
+// x8n[ng][pos][i8] = x[8 ng + i8][pos] (pos runs over c, h, w), zero for images >= N; x8n[total] = 0
+__global__ __launch_bounds__(kThreads) void interleave_images_kernel(const bf16* __restrict__ x, uint4* __restrict__ x8n,
+                                                                     int N, int64_t CHW, int64_t total) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i == 0) x8n[total] = make_uint4(0u, 0u, 0u, 0u);
+  if (i >= total) return;
+  const int64_t pos = i % CHW;
+  const int ng = (int)(i / CHW);
+  uint32_t v[8];
+#pragma unroll
+  for (int i8 = 0; i8 < 8; ++i8) {
+    const int img = ng * 8 + i8;
+    const bool ok = img < N;
+    const uint16_t b = x[ok ? (int64_t)img * CHW + pos : 0].bits;
+    v[i8] = ok ? b : 0u;
+  }
+  x8n[i] = make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
+}
+
+// dyf[ng][mt][run][jl][lane][i8] = dy[8 ng + i8][32 mt + lane % 32][run*bp + 2 jl + lane / 32] for pixels inside
+// the run and the image, zero otherwise.
+__global__ __launch_bounds__(kThreads) void dy_fragments_kernel(const bf16* __restrict__ dy, uint4* __restrict__ dyf, int N,
+                                                                int M, int P, int MT, int runs, int bp, int steps,
+                                                                int64_t total) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= total) return;
+  const int lane = (int)(i & 63);
+  int64_t t = i >> 6;
+  const int jl = (int)(t % steps);
+  t /= steps;
+  const int run = (int)(t % runs);
+  t /= runs;
+  const int mt = (int)(t % MT);
+  const int ng = (int)(t / MT);
+  const int m = mt * 32 + (lane & 31);
+  const int u = 2 * jl + (lane >> 5);
+  const int p = run * bp + u;
+  const bool inside = m < M && u < bp && p < P;
+  uint32_t v[8];
+#pragma unroll
+  for (int i8 = 0; i8 < 8; ++i8) {
+    const int img = ng * 8 + i8;
+    const bool ok = inside && img < N;
+    const uint16_t b = dy[ok ? ((int64_t)img * M + m) * P + p : 0].bits;
+    v[i8] = ok ? b : 0u;
+  }
+  dyf[i] = make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
+}
+
+struct FilterBf16Args {
+  const uint4* x8n;   // [ng][c][h][w] positions of 8 images
+  const uint4* zero;  // 16 zero bytes
+  const uint4* dyf;   // [ng][mt][run][step][64 lanes] fragments
+  float* out;         // [splits][m][K]
+  int c, h, w, m, r, s, ph, pw, oh, ow;
+  int K;              // c*r*s
+  int tiles_m, mt_total;
+  int runs, bh, bp;   // runs per image, output rows and pixels per run
+  int uch, hpos, ccs, nr, wp;
+  int chunks, chunks_per_split;  // chunk = (image group, run)
+};
+
+template <int WAVES_M, int WAVES_K, int TN>
+__global__ __launch_bounds__(kThreads, 2) void filter_grad_bf16_kernel(FilterBf16Args a) {
+  static_assert(WAVES_M * WAVES_K * 64 == kThreads, "four waves per block");
+  constexpr int TM = 2;
+  constexpr int BM = 32 * TM * WAVES_M, BN = 32 * TN;
+  extern __shared__ uint4 smem16[];
+  int* const tbl = reinterpret_cast<int*>(smem16);  // [uch], per slab of 8 pixels: [half][4]
+  uint4* const hbuf = smem16 + a.uch / 4;           // 2 x [ccs][nr][wp], each padded to hpos positions
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int wave_m = wave % WAVES_M, wave_k = wave / WAVES_M;
+  const int tm = blockIdx.x % a.tiles_m;
+  const int tk = blockIdx.x / a.tiles_m;
+  const int i0 = tm * BM + wave_m * 32 * TM;  // first output map of this wave
+  const int k0 = tk * BN;                     // first kernel-matrix column of the block
+  const int RS = a.r * a.s;
+  const int plane = a.nr * a.wp;
+  const int c_first = k0 / RS;
+
+  // table: offset of pixel u of a run inside the halo tile; pixels beyond the run point at 0 (dY is zero there)
+  for (int u = tid; u < a.uch; u += kThreads) {
+    int off = 0;
+    if (u < a.bp) {
+      const int row = u / a.ow;
+      off = row * a.wp + (u - row * a.ow);
+    }
+    const int sl = u >> 3, w8 = u & 7;
+    tbl[sl * 8 + (w8 & 1) * 4 + (w8 >> 1)] = off;
+  }
+
+  int tap_base[TN];
+#pragma unroll
+  for (int ni = 0; ni < TN; ++ni) {
+    const int col = min(k0 + ni * 32 + l32, a.K - 1);
+    const int c = col / RS;
+    const int q = col - c * RS;
+    const int r = q / a.s;
+    tap_base[ni] = (c - c_first) * plane + r * a.wp + (q - r * a.s);
+  }
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[mi][ni][q] = 0.f;
+
+  const int id0 = blockIdx.y * a.chunks_per_split;
+  const int id1 = min(a.chunks, id0 + a.chunks_per_split);
+  const int steps = a.uch / 2;
+  const int chunk_slabs = a.uch / 8;
+  const int64_t mstride = (int64_t)a.runs * steps * 64;  // fragments per row tile of one image group
+  auto frag_ptr = [&](int id, int sl) {
+    const int ng = id / a.runs, run = id - ng * a.runs;
+    return a.dyf + (((int64_t)ng * a.mt_total + i0 / 32) * a.runs + run) * steps * 64 + sl * 256 + lane;
+  };
+
+  uint4 af[4][TM];
+  const int first_sl = min(wave_k, chunk_slabs - 1);
+  {
+    const uint4* src = frag_ptr(id0, first_sl);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int mi = 0; mi < TM; ++mi) af[i][mi] = src[mi * mstride + i * 64];
+  }
+
+  const int dq = kThreads / a.wp, dr = kThreads - dq * a.wp;
+  const int row_s = tid / a.wp, rx_s = tid - row_s * a.wp;
+  const int cl_s = row_s / a.nr, ry_s = row_s - cl_s * a.nr;
+  const int npos = a.ccs * plane;
+  auto stage = [&](int id, uint4* dst) {
+    const int ng = id / a.runs, run = id - ng * a.runs;
+    const int ih0 = run * a.bh - a.ph;
+    const uint4* xg = a.x8n + (int64_t)ng * a.c * a.h * a.w;
+    int rx = rx_s, ry = ry_s, cl = cl_s;
+    for (int b0 = wave * 64; b0 < npos; b0 += kThreads) {
+      const int ih = ih0 + ry, iw = rx - a.pw, ch = c_first + cl;
+      const bool ok = b0 + lane < npos && ch < a.c && ih >= 0 && ih < a.h && iw >= 0 && iw < a.w;
+      const uint4* src = ok ? xg + (ch * a.h + ih) * a.w + iw : a.zero;
+      __builtin_amdgcn_global_load_lds(src, dst + b0, 16, 0, 0);
+      rx += dr;
+      ry += dq;
+      if (rx >= a.wp) rx -= a.wp, ++ry;
+      while (ry >= a.nr) ry -= a.nr, ++cl;
+    }
+  };
+  stage(id0, hbuf);
+
+  for (int id = id0; id < id1; ++id) {
+    const int run = id % a.runs;
+    const int ulen = min(a.bh, a.oh - run * a.bh) * a.ow;  // valid pixels in this run
+    const int slabs = (ulen + 7) >> 3;
+    const uint4* halo = hbuf + ((id - id0) & 1) * a.hpos;
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of the tile has landed
+    __syncthreads();
+    if (id + 1 < id1) stage(id + 1, hbuf + ((id + 1 - id0) & 1) * a.hpos);
+
+    for (int sl = wave_k; sl < slabs; sl += WAVES_K) {
+      const int nsl = sl + WAVES_K;
+      const uint4* nsrc = nsl < slabs ? frag_ptr(id, nsl) : (id + 1 < id1 ? frag_ptr(id + 1, first_sl) : frag_ptr(id, sl));
+      const int4 o4 = *reinterpret_cast<const int4*>(tbl + sl * 8 + half * 4);
+      const int o[4] = {o4.x, o4.y, o4.z, o4.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        uint4 bfr[TN], cur[TM];
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni) bfr[ni] = halo[tap_base[ni] + o[i]];
+#pragma unroll
+        for (int mi = 0; mi < TM; ++mi) {
+          cur[mi] = af[i][mi];
+          af[i][mi] = nsrc[mi * mstride + i * 64];
+        }
+#pragma unroll
+        for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < TN; ++ni) acc[mi][ni] = mfma_bf16(cur[mi], bfr[ni], acc[mi][ni]);
+      }
+    }
+  }
+
+  if (WAVES_K > 1) {  // contraction split between waves: add the partial sums in wave order through LDS
+    float* red = reinterpret_cast<float*>(smem16);  // [TM*TN*16][64 lanes]
+#pragma unroll 1
+    for (int k = 1; k < WAVES_K; ++k) {
+      __syncthreads();
+      if (wave_k == k) {
+#pragma unroll
+        for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) red[(((wave_m * TM + mi) * TN + ni) * 16 + q) * 64 + lane] = acc[mi][ni][q];
+      }
+      __syncthreads();
+      if (wave_k == 0) {
+#pragma unroll
+        for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[mi][ni][q] += red[(((wave_m * TM + mi) * TN + ni) * 16 + q) * 64 + lane];
+      }
+    }
+    if (wave_k != 0) return;
+  }
+
+  float* dst = a.out + (int64_t)blockIdx.y * a.m * a.K;
+#pragma unroll
+  for (int ni = 0; ni < TN; ++ni) {
+    const int col = k0 + ni * 32 + l32;
+    if (col >= a.K) continue;
+#pragma unroll
+    for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int m = i0 + mi * 32 + 8 * (q >> 2) + 4 * half + (q & 3);
+        if (m < a.m) dst[(int64_t)m * a.K + col] = acc[mi][ni][q];
+      }
+  }
+}
+
+bool filter_grad_bf16_plan(const ConvGeom& g, FilterGradBf16Plan* p) {
+  const int rs = g.r * g.s;
+  if ((int64_t)g.c * g.h * g.w > 0x7fffffffLL || g.K > 0x7fffffffLL) return false;
+  p->waves_m = g.M > 128 ? 4 : (g.M > 64 ? 2 : 1);
+  const int waves_k = 4 / p->waves_m;
+  const int bm = 64 * p->waves_m;
+  const int tiles_m = (int)ceil_div(g.M, bm);
+  // column tile: least padding of the kernel-matrix width, wider on ties
+  int tn = 0;
+  int64_t padded = 0;
+  for (int t : kTnChoices) {
+    const int64_t pd = ceil_div(g.K, 32 * t) * 32 * t;
+    if (tn == 0 || pd <= padded) tn = t, padded = pd;
+  }
+  const int bn = 32 * tn;
+  p->tn = tn;
+  p->wp = g.w + 2 * g.pw;
+  p->ccs = (int)std::min<int64_t>(g.c, (bn + rs - 2) / rs + 1);  // channels a run of bn columns can touch
+  const size_t red_bytes = waves_k > 1 ? (size_t)p->waves_m * 2 * tn * 16 * 64 * sizeof(float) : 0;
+  if (red_bytes > kLdsBudget) return false;
+  // most output rows per run whose double-buffered halo tile fits
+  int bh = 0;
+  for (int t = 1; t <= g.oh; ++t) {
+    const int uch = (int)ceil_div((int64_t)t * g.ow, 8) * 8;
+    const size_t hpos = ((size_t)p->ccs * (t + g.r - 1) * p->wp + 63) & ~(size_t)63;
+    if ((size_t)uch * 4 + 2 * hpos * 16 > kLdsBudget || uch > 4096) break;
+    bh = t;
+  }
+  if (bh == 0) return false;
+  p->bh = bh, p->bp = bh * g.ow, p->nr = bh + g.r - 1;
+  p->uch = (int)ceil_div((int64_t)p->bp, 8) * 8;
+  p->hpos = (int)(((size_t)p->ccs * p->nr * p->wp + 63) & ~(size_t)63);
+  p->lds_bytes = std::max((size_t)p->uch * 4 + 2 * (size_t)p->hpos * 16, red_bytes);
+  p->runs = (int)ceil_div(g.oh, bh);
+  p->ngroups = (g.n + 7) / 8;
+  p->chunks = p->ngroups * p->runs;
+  const int64_t tiles = (int64_t)tiles_m * ceil_div(g.K, bn);
+  int64_t want = ceil_div(512, tiles);
+  if (want > p->chunks) want = p->chunks;
+  if (want < 1) want = 1;
+  p->chunks_per_split = (int)ceil_div(p->chunks, want);
+  p->splits = (int)ceil_div(p->chunks, p->chunks_per_split);
+  p->mt_total = tiles_m * (bm / 32);
+  p->x8n_bytes = (((size_t)p->ngroups * g.c * g.h * g.w + 1) * 16 + 255) & ~(size_t)255;
+  p->dyf_bytes = ((size_t)p->ngroups * p->mt_total * p->runs * (p->uch / 2) * 64 * 16 + 255) & ~(size_t)255;
+  p->partial_bytes = p->splits > 1 ? (size_t)p->splits * g.M * g.K * sizeof(float) : 0;
+  return tiles <= 0x7fffffffLL && p->splits <= 65535;
+}
+
+template <int WAVES_M, int WAVES_K, int TN>
+static void launch_filter_one(const FilterBf16Args& a, unsigned tiles, unsigned splits, size_t lds, hipStream_t st) {
+  auto kernel = filter_grad_bf16_kernel<WAVES_M, WAVES_K, TN>;
+  static bool opted = false;
+  if (!opted) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)kLdsBudget);
+    opted = true;
+  }
+  hipLaunchKernelGGL(kernel, dim3(tiles, splits), dim3(kThreads), lds, st, a);
+}
+
+template <int TN>
+static void launch_filter_tn(const FilterBf16Args& a, int waves_m, unsigned tiles, unsigned splits, size_t lds,
+                             hipStream_t st) {
+  if (waves_m == 4) launch_filter_one<4, 1, TN>(a, tiles, splits, lds, st);
+  else if (waves_m == 2) launch_filter_one<2, 2, TN>(a, tiles, splits, lds, st);
+  else launch_filter_one<1, 4, TN>(a, tiles, splits, lds, st);
+}
+
+vcnn_status launch_filter_grad_bf16(const FilterGradBf16Plan& p, const ConvGeom& g, const void* x, const void* dy,
+                                    float* dw, void* workspace, hipStream_t st) {
+  uint4* x8n = (uint4*)workspace;
+  uint4* dyf = (uint4*)((char*)workspace + p.x8n_bytes);
+  float* partial = (float*)((char*)workspace + p.x8n_bytes + p.dyf_bytes);
+  const int64_t chw = (int64_t)g.c * g.h * g.w;
+  {
+    const int64_t total = (int64_t)p.ngroups * chw;
+    hipLaunchKernelGGL(interleave_images_kernel, dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, st,
+                       (const bf16*)x, x8n, g.n, chw, total);
+    if (vcnn_status e = check_launch("interleave_images")) return e;
+  }
+  {
+    const int64_t total = (int64_t)p.ngroups * p.mt_total * p.runs * (p.uch / 2) * 64;
+    hipLaunchKernelGGL(dy_fragments_kernel, dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, st,
+                       (const bf16*)dy, dyf, g.n, (int)g.M, (int)g.P, p.mt_total, p.runs, p.bp, p.uch / 2, total);
+    if (vcnn_status e = check_launch("dy_fragments")) return e;
+  }
+  FilterBf16Args a{};
+  a.x8n = x8n, a.zero = x8n + (int64_t)p.ngroups * chw, a.dyf = dyf, a.out = p.splits > 1 ? partial : dw;
+  a.c = g.c, a.h = g.h, a.w = g.w, a.m = g.k, a.r = g.r, a.s = g.s, a.ph = g.ph, a.pw = g.pw, a.oh = g.oh, a.ow = g.ow;
+  a.K = (int)g.K;
+  a.tiles_m = (int)ceil_div(g.M, 64 * p.waves_m), a.mt_total = p.mt_total;
+  a.runs = p.runs, a.bh = p.bh, a.bp = p.bp;
+  a.uch = p.uch, a.hpos = p.hpos, a.ccs = p.ccs, a.nr = p.nr, a.wp = p.wp;
+  a.chunks = p.chunks, a.chunks_per_split = p.chunks_per_split;
+  const unsigned tiles = (unsigned)(a.tiles_m * ceil_div(g.K, 32 * p.tn));
+  if (p.tn == 2) launch_filter_tn<2>(a, p.waves_m, tiles, (unsigned)p.splits, p.lds_bytes, st);
+  else if (p.tn == 4) launch_filter_tn<4>(a, p.waves_m, tiles, (unsigned)p.splits, p.lds_bytes, st);
+  else launch_filter_tn<5>(a, p.waves_m, tiles, (unsigned)p.splits, p.lds_bytes, st);
+  if (vcnn_status e = check_launch("filter_grad_bf16")) return e;
+  if (p.splits == 1) return VCNN_OK;
+  return launch_sum_slices(partial, nullptr, dw, VCNN_F32, g.M * g.K, p.splits, 1, 1, 0, st);
+}
+
 }  // namespace vcnn

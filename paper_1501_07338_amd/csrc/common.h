@@ -130,6 +130,20 @@ bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph
 vcnn_status launch_conv_halo_bf16(const HaloBf16Plan& p, int n, int c, int h, int w, int m, int r, int s, int ph, int pw,
                                   const void* x, const void* wgt, int64_t w_so, int64_t w_si, int flip, const float* bias,
                                   void* y, int relu, void* workspace, hipStream_t st);
+struct FilterGradBf16Plan {
+  int waves_m, tn;
+  int ccs, nr, wp;   // channels, rows and row pitch of the halo tile
+  int bh, bp, runs;  // output rows / pixels per run, runs per image
+  int ngroups;       // image groups of 8
+  int uch, hpos;
+  int chunks, chunks_per_split, splits;
+  int mt_total;
+  size_t lds_bytes, x8n_bytes, dyf_bytes, partial_bytes;
+};
+bool filter_grad_bf16_plan(const ConvGeom& g, FilterGradBf16Plan* p);
+// workspace: x8n_bytes + dyf_bytes + partial_bytes
+vcnn_status launch_filter_grad_bf16(const FilterGradBf16Plan& p, const ConvGeom& g, const void* x, const void* dy,
+                                    float* dw, void* workspace, hipStream_t st);
 bool bwd_filter_bf16_plan(const ConvGeom& g, BwdFilterBf16Plan* p);
 vcnn_status launch_bwd_filter_bf16(const BwdFilterBf16Plan& p, const ConvGeom& g, const void* x, const void* dy, float* dw,
                                    void* workspace, hipStream_t st);
