@@ -107,7 +107,8 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
   constexpr int BM = 32 * TM * WAVES_M, BN = 32 * TN;
   extern __shared__ uint4 smem16[];
   int* const tbl = reinterpret_cast<int*>(smem16);  // [uch], per slab of 8 pairs: [half][4]
-  uint4* const hbuf = smem16 + a.uch / 4;           // 2 x [cgc][nr][wp], each padded to hpos positions
+  int* const nxt = tbl + a.uch;                     // [uch/8 + 4]: next slab with work, first such slab per wave
+  uint4* const hbuf = smem16 + a.uch / 4 + (a.uch / 8 + 7) / 4;  // 2 x [cgc][nr][wp], each padded to hpos positions
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
@@ -143,6 +144,29 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
     lane_base[ni] = (oh - oh_first) * a.wp + (p - oh * a.ow);
   }
 
+  // Slabs whose 8 (group, tap) pairs all lie on kernel rows that meet only the zero border for every
+  // output row of this tile contribute nothing (the input gradient of a 'valid' layer is a fully padded
+  // correlation, where this is a quarter of the work).  nxt[sl] = next slab of the same wave that has
+  // work (>= uch/8: none), nxt[uch/8 + k] = first such slab of wave k.
+  {
+    const int chunk_slabs = a.uch / 8;
+    const int oh_last = min(p0 + BN - 1, a.P - 1) / a.ow;
+    const int r_lo = a.ph - oh_last, r_hi = a.h - 1 + a.ph - oh_first;  // kernel rows that reach the image
+    auto has_work = [&](int sl) {
+      const int u0 = sl * 8, u1 = min(u0 + 7, a.cgc * RS - 1);
+      if (u0 > u1) return false;  // padding slab
+      const int g0 = u0 / RS, g1 = u1 / RS;
+      if (g0 != g1) return true;
+      const int r0 = (u0 - g0 * RS) / a.s, r1 = (u1 - g0 * RS) / a.s;
+      return r1 >= r_lo && r0 <= r_hi;
+    };
+    for (int sl = tid; sl < chunk_slabs + WAVES_K; sl += kThreads) {
+      int t = sl < chunk_slabs ? sl + WAVES_K : sl - chunk_slabs;
+      while (t < chunk_slabs && !has_work(t)) t += WAVES_K;
+      nxt[sl] = min(t, chunk_slabs);
+    }
+  }
+
   f32x16 acc[TM][TN];
 #pragma unroll
   for (int mi = 0; mi < TM; ++mi)
@@ -166,7 +190,9 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
 #pragma unroll
       for (int mi = 0; mi < TM; ++mi) af[i][mi] = src[mi * mstride + i * 64];
   };
-  const int first_sl = min(wave_k, chunk_slabs - 1);
+  __syncthreads();  // nxt is complete
+  const int first_work = nxt[chunk_slabs + wave_k];  // this wave's first slab with work in any chunk
+  const int first_sl = min(first_work, chunk_slabs - 1);
   load_a(0, first_sl);
 
   // Asynchronous halo staging: positions in flat tile order, 64 consecutive positions per wave and
@@ -201,10 +227,11 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
     __syncthreads();
     if (ch + 1 < a.nchunks) stage(ch + 1, hbuf + ((ch + 1) & 1) * a.hpos);
 
-    for (int sl = wave_k; sl < slabs; sl += WAVES_K) {
-      // where this wave continues: next slab of this chunk, else its first slab of the next chunk (the
-      // fragment loads do not depend on the halo tile, so they stay in flight across the chunk change)
-      int nch = ch, nsl = sl + WAVES_K;
+    for (int sl = first_work; sl < slabs;) {
+      // where this wave continues: its next slab with work in this chunk, else its first one in the next
+      // chunk (the fragment loads do not depend on the halo tile, so they stay in flight across the change)
+      const int after = nxt[sl];
+      int nch = ch, nsl = after;
       if (nsl >= slabs) {
         if (ch + 1 < a.nchunks) nch = ch + 1, nsl = first_sl;
         else nsl = sl;
@@ -227,6 +254,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
 #pragma unroll
           for (int ni = 0; ni < TN; ++ni) acc[mi][ni] = mfma_bf16(cur[mi], bfr[ni], acc[mi][ni]);
       }
+      sl = after;
     }
   }
 
@@ -305,7 +333,7 @@ bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph
     for (int t = 1; t <= cg; ++t) {
       const int uch = (int)ceil_div((int64_t)t * rs, 8) * 8;
       const size_t hpos = ((size_t)t * nr * wp + 63) & ~(size_t)63;
-      if ((size_t)uch * 4 + 2 * hpos * 16 > kLdsBudget || uch > 4096) break;
+      if ((size_t)uch * 4 + ((size_t)uch / 8 + 7) / 4 * 16 + 2 * hpos * 16 > kLdsBudget || uch > 4096) break;
       cgc = t;
     }
     if (cgc == 0) continue;
@@ -329,7 +357,7 @@ bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph
   p->uch = (int)ceil_div((int64_t)pick * rs, 8) * 8;
   const size_t red_bytes = waves_k > 1 ? (size_t)p->waves_m * 2 * best_tn * 16 * 64 * sizeof(float) : 0;
   p->hpos = (int)(((size_t)pick * best_nr * wp + 63) & ~(size_t)63);
-  p->lds_bytes = std::max((size_t)p->uch * 4 + 2 * (size_t)p->hpos * 16, red_bytes);
+  p->lds_bytes = std::max((size_t)p->uch * 4 + ((size_t)p->uch / 8 + 7) / 4 * 16 + 2 * (size_t)p->hpos * 16, red_bytes);
   p->x8_bytes = (((size_t)n * cg * h * w + 1) * 16 + 255) & ~(size_t)255;  // + the block of zeros
   p->wf_bytes = ((size_t)tiles_m * (bm / 32) * p->nchunks * (p->uch / 2) * 64 * 16 + 255) & ~(size_t)255;
   return true;
