@@ -201,12 +201,14 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
   const int row_s = tid / a.wp, rx_s = tid - row_s * a.wp;
   const int gl_s = row_s / a.nr, ry_s = row_s - gl_s * a.nr;
   auto stage = [&](int ch, uint4* dst) {
+    // every chunk fills the whole tile: groups beyond the last one become zeros, because the padding
+    // pairs of a short last chunk still read their positions (times zero weights)
     const int g0 = ch * a.cgc;
-    const int npos = min(a.cgc, a.cg - g0) * plane;
+    const int npos = a.cgc * plane;
     int rx = rx_s, ry = ry_s, gl = gl_s;
     for (int b0 = wave * 64; b0 < npos; b0 += kThreads) {  // b0: first position of this wave's 64 (uniform)
       const int ih = oh_first - a.ph + ry, iw = rx - a.pw;
-      const bool ok = b0 + lane < npos && ih >= 0 && ih < a.h && iw >= 0 && iw < a.w;
+      const bool ok = b0 + lane < npos && g0 + gl < a.cg && ih >= 0 && ih < a.h && iw >= 0 && iw < a.w;
       const uint4* src = ok ? x8n + ((g0 + gl) * a.h + ih) * a.w + iw : a.zero;
       __builtin_amdgcn_global_load_lds(src, dst + b0, 16, 0, 0);
       rx += dr;

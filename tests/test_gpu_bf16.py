@@ -74,6 +74,44 @@ def test_conv_bf16(shape, algo):
     assert_close(f32_of(dx), O.conv_bwd_data(wt, dy, (h, w), pad=(ph, pw)), TOL_BF16, "bf16 dx")
 
 
+def _check_bf16_layer(n, c, h, w, k, r, s, ph, pw, seed):
+    x, xd = b16(wl.random_tensor(seed, (n, c, h, w)))
+    wt, wd = b16(wl.random_tensor(seed + 1, (k, c, r, s), scale=(2.0 / (c * r * s)) ** 0.5))
+    b = wl.random_tensor(seed + 2, (k,), scale=0.1)
+    oh, ow = h + 2 * ph - r + 1, w + 2 * pw - s + 1
+    dy, dyd = b16(wl.random_tensor(seed + 3, (n, k, oh, ow)))
+    d = vcnn.conv_desc(n, c, h, w, k, r, s, ph, pw, dtype=vcnn.BF16, act=vcnn.ACT_NONE)
+    ws = torch.empty(max(256, *(vcnn.conv_workspace_bytes(d, p) for p in range(3))), dtype=torch.uint8, device=DEV)
+    y = torch.full((n, k, oh, ow), float("nan"), dtype=torch.bfloat16, device=DEV)
+    vcnn.conv_fwd(d, xd, wd, torch.from_numpy(b).to(DEV), y, ws)
+    assert_close(f32_of(y), O.conv_fwd(x, wt, b, pad=(ph, pw)), TOL_BF16, "bf16 conv_fwd")
+    dw = torch.full((k, c, r, s), float("nan"), device=DEV)
+    db = torch.full((k,), float("nan"), device=DEV)
+    vcnn.conv_bwd_filter(d, xd, dyd, dw, db, ws)
+    rdw, rdb = O.conv_bwd_filter(x, dy, (r, s), pad=(ph, pw))
+    assert_close(to_np(dw), rdw, TOL_F32, "bf16 dw (fp32 result)")
+    assert_close(to_np(db), rdb, TOL_F32, "bf16 db (fp32 result)")
+    dx = torch.full((n, c, h, w), float("nan"), dtype=torch.bfloat16, device=DEV)
+    vcnn.conv_bwd_data(d, wd, dyd, dx, ws)
+    assert_close(f32_of(dx), O.conv_bwd_data(wt, dy, (h, w), pad=(ph, pw)), TOL_BF16, "bf16 dx")
+
+
+@pytest.mark.parametrize("k", [40, 100, 200])           # waves of a block: all on the contraction, 2 x 2, all on the maps
+@pytest.mark.parametrize("hw", [(40, 64), (64, 80)])    # pixel tiles of 128 and of 160 win the tile choice
+def test_conv_bf16_wide_pixel_tiles(k, hw):
+    """Shapes large enough that the bf16 matrix-core kernel picks its 128- and 160-pixel wave tiles, for each
+    arrangement of the four waves; 12 channels = one full and one half-empty group of 8."""
+    _check_bf16_layer(16, 12, hw[0], hw[1], k, 3, 3, 1, 1, seed=2300 + k)
+
+
+@pytest.mark.parametrize("k", [40, 100, 200])
+@pytest.mark.parametrize("c", [7, 13, 17])              # kernel-matrix widths 63, 117, 153: column tiles of 64, 128, 160
+def test_filter_grad_bf16_column_tiles(k, c):
+    """Filter gradient of the bf16 variant for each column-tile width and wave arrangement, with a batch that
+    is not a multiple of the 8-image interleave and several pixel runs per image."""
+    _check_bf16_layer(11, c, 30, 26, k, 3, 3, 1, 1, seed=2400 + 10 * c + k)
+
+
 def test_unroll_bf16_bit_exact():
     n, c, h, w, r, s, ph, pw = 3, 5, 14, 13, 5, 3, 2, 1
     d = vcnn.conv_desc(n, c, h, w, 1, r, s, ph, pw, dtype=vcnn.BF16)
