@@ -183,15 +183,19 @@ def hbm_kernels(stream):
         rec("im2col", name, nbytes, timed(lambda: vcnn.im2col(d, x, col)))
         rec("col2im", name, nbytes, timed(lambda: vcnn.col2im(d, col, dx)))
         del x, col, dx
-    n, c, h, w = 128, 32, 32, 32  # cfg3 p1: 3x3 stride 2
-    d = vcnn.pool_desc(n, c, h, w, 3, 3, 2, 2)
-    oh, ow = vcnn.pool_out_shape(d)
-    x = torch.randn(n, c, h, w, device="cuda")
-    y = torch.empty(n, c, oh, ow, device="cuda")
-    am = torch.empty(n, c, oh, ow, dtype=torch.int32, device="cuda")
-    dy, dx = torch.randn_like(y), torch.empty_like(x)
-    rec("pool_fwd", "cfg3.p1", 4.0 * (x.numel() + 2 * y.numel()), timed(lambda: vcnn.pool_fwd(d, x, y, am)))
-    rec("pool_bwd", "cfg3.p1", 4.0 * (x.numel() + 2 * y.numel()), timed(lambda: vcnn.pool_bwd(d, dy, am, dx)))
+    # cfg3 p1 (3x3 stride 2, 24 MB: launch-latency sized) and the same layer at 16x the batch, where the
+    # tensor is large enough for the bandwidth to show
+    for name, n in {"cfg3.p1": 128, "cfg3.p1 at batch 2048": 2048}.items():
+        c, h, w = 32, 32, 32
+        d = vcnn.pool_desc(n, c, h, w, 3, 3, 2, 2)
+        oh, ow = vcnn.pool_out_shape(d)
+        x = torch.randn(n, c, h, w, device="cuda")
+        y = torch.empty(n, c, oh, ow, device="cuda")
+        am = torch.empty(n, c, oh, ow, dtype=torch.int32, device="cuda")
+        dy, dx = torch.randn_like(y), torch.empty_like(x)
+        rec("pool_fwd", name, 4.0 * (x.numel() + 2 * y.numel()), timed(lambda: vcnn.pool_fwd(d, x, y, am)))
+        rec("pool_bwd", name, 4.0 * (x.numel() + 2 * y.numel()), timed(lambda: vcnn.pool_bwd(d, dy, am, dx)))
+        del x, y, am, dy, dx
     t = torch.randn(64, 64, 64, 64, device="cuda")  # cfg4 c1 output
     g, o = torch.randn_like(t), torch.empty_like(t)
     rec("relu_bwd", "cfg4.c1 output", 12.0 * t.numel(), timed(lambda: vcnn.act_bwd(vcnn.ACT_RELU, vcnn.F32, t.numel(), t, g, o)))

@@ -2,6 +2,8 @@
 // (phi_p of Eq. 3 with the max operation), bias gradient, cost functions and the SGD update.
 // Kernels are templates on the element type of the activation tensors (float or bf16); sums,
 // comparisons and costs are computed on float values.
+#include <algorithm>
+
 #include "common.h"
 #include "elem.h"
 
@@ -86,7 +88,8 @@ __global__ __launch_bounds__(kThreads) void pool_fwd_kernel(vcnn_pool_desc d, in
   const int win_h = WIN ? WIN : d.win_h, win_w = WIN ? WIN : d.win_w;
   const int sh = STRIDE ? STRIDE : d.stride_h, sw = STRIDE ? STRIDE : d.stride_w;
   const int oh = o / ow_n, ow = o - oh * ow_n;
-  const int64_t nc = blockIdx.y;
+  const int64_t nc = (int64_t)blockIdx.z * gridDim.y + blockIdx.y;  // plane (n, c)
+  if (nc >= (int64_t)d.n * d.c) return;
   const T* xp = x + nc * d.h * d.w;
   const int h0 = oh * sh, w0 = ow * sw;
   float best = ld(xp + h0 * d.w + w0);
@@ -116,7 +119,8 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_kernel(vcnn_pool_desc d, in
   const int win_h = WIN ? WIN : d.win_h, win_w = WIN ? WIN : d.win_w;
   const int sh = STRIDE ? STRIDE : d.stride_h, sw = STRIDE ? STRIDE : d.stride_w;
   const int hi = pos / d.w, wi = pos - hi * d.w;
-  const int64_t nc = blockIdx.y;
+  const int64_t nc = (int64_t)blockIdx.z * gridDim.y + blockIdx.y;  // plane (n, c)
+  if (nc >= (int64_t)d.n * d.c) return;
   // windows oh with oh*stride <= hi <= oh*stride + win - 1
   int oh_lo = hi - win_h + 1;
   oh_lo = oh_lo > 0 ? (oh_lo + sh - 1) / sh : 0;
@@ -154,7 +158,9 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_kernel(vcnn_pool_desc d, in
 template <typename T>
 static void pool_fwd_typed(const vcnn_pool_desc& d, int oh, int ow, const void* x, void* y, int32_t* argmax,
                            hipStream_t st) {
-  const dim3 grid((unsigned)ceil_div((int64_t)oh * ow, kThreads), (unsigned)(d.n * d.c)), block(kThreads);
+  const int64_t planes = (int64_t)d.n * d.c;
+  const unsigned gy = (unsigned)std::min<int64_t>(planes, 32768);
+  const dim3 grid((unsigned)ceil_div((int64_t)oh * ow, kThreads), gy, (unsigned)ceil_div(planes, gy)), block(kThreads);
   const bool square = d.win_h == d.win_w && d.stride_h == d.stride_w;
   if (square && d.win_h == 2 && d.stride_h == 2)
     hipLaunchKernelGGL((pool_fwd_kernel<T, 2, 2>), grid, block, 0, st, d, oh, ow, (const T*)x, (T*)y, argmax);
@@ -164,14 +170,110 @@ static void pool_fwd_typed(const vcnn_pool_desc& d, int oh, int ow, const void* 
     hipLaunchKernelGGL((pool_fwd_kernel<T, 0, 0>), grid, block, 0, st, d, oh, ow, (const T*)x, (T*)y, argmax);
 }
 
+// The same gather for small planes, staged: a block takes `pb` consecutive planes, copies their dy and
+// argmax records into LDS with coalesced loads (each record is needed by up to ceil(k/s)^2 input pixels)
+// and then produces the dx elements of those planes from LDS, in the same window order as above.
+template <typename T, int WIN, int STRIDE>
+__global__ __launch_bounds__(kThreads) void pool_bwd_staged_kernel(vcnn_pool_desc d, int oh_n, int ow_n, int pb, int vec,
+                                                                   const T* __restrict__ dy,
+                                                                   const int32_t* __restrict__ argmax,
+                                                                   T* __restrict__ dx) {
+  extern __shared__ float pool_lds[];
+  const int64_t planes = (int64_t)d.n * d.c;
+  const int64_t nc0 = (int64_t)blockIdx.x * pb;
+  const int np = (int)min((int64_t)pb, planes - nc0);
+  const int out_plane = oh_n * ow_n, in_plane = d.h * d.w;
+  float* dy_s = pool_lds;
+  int* am_s = reinterpret_cast<int*>(pool_lds + pb * out_plane);
+  for (int i = threadIdx.x; i < np * out_plane; i += kThreads) {
+    dy_s[i] = ld(dy + nc0 * out_plane + i);
+    am_s[i] = argmax[nc0 * out_plane + i];
+  }
+  __syncthreads();
+  const int win_h = WIN ? WIN : d.win_h, win_w = WIN ? WIN : d.win_w;
+  const int sh = STRIDE ? STRIDE : d.stride_h, sw = STRIDE ? STRIDE : d.stride_w;
+  if (WIN && STRIDE && vec) {  // vec: rows are a multiple of 4 pixels and dx is aligned for 4-element stores
+    // four consecutive pixels of a row per thread: the windows that can have recorded any of them are a
+    // fixed small set, visited in ascending (row, column) order; a window's gradient goes to the pixel
+    // whose index it recorded.  One 16-byte store per thread.
+    constexpr int ROWS = WIN && STRIDE ? (WIN + STRIDE - 1) / STRIDE : 1;
+    constexpr int COLS = WIN && STRIDE ? (WIN + 2) / STRIDE + 1 : 1;
+    const int wq = d.w / 4, items = d.h * wq;
+    for (int e = threadIdx.x; e < np * items; e += kThreads) {
+      const int pl = e / items, rem = e - pl * items;
+      const int hi = rem / wq, w0 = (rem - hi * wq) * 4;
+      int oh_lo = hi - WIN + 1;
+      oh_lo = oh_lo > 0 ? (oh_lo + STRIDE - 1) / STRIDE : 0;
+      const int oh_hi = min(oh_n - 1, hi / STRIDE);
+      int ow_lo = w0 - WIN + 1;
+      ow_lo = ow_lo > 0 ? (ow_lo + STRIDE - 1) / STRIDE : 0;
+      const int ow_hi = min(ow_n - 1, (w0 + 3) / STRIDE);
+      const int base = pl * out_plane, pos0 = hi * d.w + w0;
+      float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int a = 0; a < ROWS; ++a)
+#pragma unroll
+        for (int b = 0; b < COLS; ++b) {
+          const int oh = oh_lo + a, ow = ow_lo + b;
+          const bool ok = oh <= oh_hi && ow <= ow_hi;
+          const int o = base + (ok ? oh * ow_n + ow : 0);
+          const int j = am_s[o] - pos0;
+          const float g = ok ? dy_s[o] : 0.f;
+#pragma unroll
+          for (int t = 0; t < 4; ++t) acc[t] += j == t ? g : 0.f;
+        }
+      st4(dx + nc0 * in_plane + (int64_t)pl * in_plane + pos0, make_float4(acc[0], acc[1], acc[2], acc[3]));
+    }
+    return;
+  }
+  for (int e = threadIdx.x; e < np * in_plane; e += kThreads) {
+    const int pl = e / in_plane, pos = e - pl * in_plane;
+    const int hi = pos / d.w, wi = pos - hi * d.w;
+    int oh_lo = hi - win_h + 1;
+    oh_lo = oh_lo > 0 ? (oh_lo + sh - 1) / sh : 0;
+    const int oh_hi = min(oh_n - 1, hi / sh);
+    int ow_lo = wi - win_w + 1;
+    ow_lo = ow_lo > 0 ? (ow_lo + sw - 1) / sw : 0;
+    const int ow_hi = min(ow_n - 1, wi / sw);
+    const int base = pl * out_plane;
+    float acc = 0.f;
+    for (int oh = oh_lo; oh <= oh_hi; ++oh)
+      for (int ow = ow_lo; ow <= ow_hi; ++ow) {
+        const int o = base + oh * ow_n + ow;
+        if (am_s[o] == pos) acc += dy_s[o];
+      }
+    st(dx + nc0 * in_plane + e, acc);
+  }
+}
+
 template <typename T>
 static void pool_bwd_typed(const vcnn_pool_desc& d, int oh, int ow, const void* dy, const int32_t* argmax, void* dx,
                            hipStream_t st) {
-  const dim3 grid((unsigned)ceil_div((int64_t)d.h * d.w, kThreads), (unsigned)(d.n * d.c)), block(kThreads);
+  const int64_t planes = (int64_t)d.n * d.c;
   const bool square = d.win_h == d.win_w && d.stride_h == d.stride_w;
-  if (square && d.win_h == 2 && d.stride_h == 2)
+  const int which = square && d.win_h == 2 && d.stride_h == 2 ? 2 : (square && d.win_h == 3 && d.stride_h == 2 ? 3 : 0);
+  // staged form: planes per block so that a block writes about 4096 dx elements and its records fit 32 KB of LDS
+  const int64_t in_plane = (int64_t)d.h * d.w, out_plane = (int64_t)oh * ow;
+  int64_t pb = std::max<int64_t>(1, 4096 / in_plane);
+  pb = std::min(pb, std::max<int64_t>(1, (32 * 1024) / (8 * out_plane)));
+  pb = std::min(pb, planes);
+  if (in_plane <= 16384 && out_plane * 8 <= 32 * 1024 && ceil_div(planes, pb) <= 0x7fffffffLL) {
+    const dim3 grid((unsigned)ceil_div(planes, pb)), block(kThreads);
+    const size_t lds = (size_t)pb * out_plane * 8;
+    const int vec = d.w % 4 == 0 && group_aligned<T>(dx);
+    if (which == 2)
+      hipLaunchKernelGGL((pool_bwd_staged_kernel<T, 2, 2>), grid, block, lds, st, d, oh, ow, (int)pb, vec, (const T*)dy, argmax, (T*)dx);
+    else if (which == 3)
+      hipLaunchKernelGGL((pool_bwd_staged_kernel<T, 3, 2>), grid, block, lds, st, d, oh, ow, (int)pb, vec, (const T*)dy, argmax, (T*)dx);
+    else
+      hipLaunchKernelGGL((pool_bwd_staged_kernel<T, 0, 0>), grid, block, lds, st, d, oh, ow, (int)pb, vec, (const T*)dy, argmax, (T*)dx);
+    return;
+  }
+  const unsigned gy = (unsigned)std::min<int64_t>(planes, 32768);
+  const dim3 grid((unsigned)ceil_div((int64_t)d.h * d.w, kThreads), gy, (unsigned)ceil_div(planes, gy)), block(kThreads);
+  if (which == 2)
     hipLaunchKernelGGL((pool_bwd_kernel<T, 2, 2>), grid, block, 0, st, d, oh, ow, (const T*)dy, argmax, (T*)dx);
-  else if (square && d.win_h == 3 && d.stride_h == 2)
+  else if (which == 3)
     hipLaunchKernelGGL((pool_bwd_kernel<T, 3, 2>), grid, block, 0, st, d, oh, ow, (const T*)dy, argmax, (T*)dx);
   else
     hipLaunchKernelGGL((pool_bwd_kernel<T, 0, 0>), grid, block, 0, st, d, oh, ow, (const T*)dy, argmax, (T*)dx);
@@ -179,7 +281,7 @@ static void pool_bwd_typed(const vcnn_pool_desc& d, int oh, int ow, const void* 
 
 vcnn_status launch_pool_fwd(const vcnn_pool_desc& d, int oh, int ow, const void* x, void* y, int32_t* argmax,
                             hipStream_t st) {
-  if ((int64_t)d.n * d.c > 65535) return fail(VCNN_ERR_UNSUPPORTED, "pool: more than 65535 planes in one call");
+  if ((int64_t)d.n * d.c > 32768LL * 65535) return fail(VCNN_ERR_UNSUPPORTED, "pool: too many planes for one launch");
   if (d.dtype == VCNN_BF16) pool_fwd_typed<bf16>(d, oh, ow, x, y, argmax, st);
   else pool_fwd_typed<float>(d, oh, ow, x, y, argmax, st);
   return check_launch("pool_fwd");
@@ -187,7 +289,7 @@ vcnn_status launch_pool_fwd(const vcnn_pool_desc& d, int oh, int ow, const void*
 
 vcnn_status launch_pool_bwd(const vcnn_pool_desc& d, int oh, int ow, const void* dy, const int32_t* argmax, void* dx,
                             hipStream_t st) {
-  if ((int64_t)d.n * d.c > 65535) return fail(VCNN_ERR_UNSUPPORTED, "pool: more than 65535 planes in one call");
+  if ((int64_t)d.n * d.c > 32768LL * 65535) return fail(VCNN_ERR_UNSUPPORTED, "pool: too many planes for one launch");
   if (d.dtype == VCNN_BF16) pool_bwd_typed<bf16>(d, oh, ow, dy, argmax, dx, st);
   else pool_bwd_typed<float>(d, oh, ow, dy, argmax, dx, st);
   return check_launch("pool_bwd");
