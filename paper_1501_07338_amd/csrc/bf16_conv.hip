@@ -656,7 +656,19 @@ __global__ __launch_bounds__(kThreads, 2) void filter_grad_bf16_kernel(FilterBf1
   }
 }
 
-bool filter_grad_bf16_plan(const ConvGeom& g, FilterGradBf16Plan* p) {
+// A 1x1 unpadded layer does not care how its pixels are arranged: seen as a P x 1 image, a "run of rows" is
+// any run of pixels, which keeps the LDS tile (channels x run) small however wide the image is.
+static ConvGeom flatten_pointwise(const ConvGeom& g) {
+  ConvGeom f = g;
+  if (g.r == 1 && g.s == 1 && g.ph == 0 && g.pw == 0 && g.P <= 0x7fffffffLL) {
+    f.h = f.oh = (int)g.P;
+    f.w = f.ow = 1;
+  }
+  return f;
+}
+
+bool filter_grad_bf16_plan(const ConvGeom& g0, FilterGradBf16Plan* p) {
+  const ConvGeom g = flatten_pointwise(g0);
   const int rs = g.r * g.s;
   if ((int64_t)g.c * g.h * g.w > 0x7fffffffLL || g.K > 0x7fffffffLL) return false;
   p->waves_m = g.M > 128 ? 4 : (g.M > 64 ? 2 : 1);
@@ -725,8 +737,9 @@ static void launch_filter_tn(const FilterBf16Args& a, int waves_m, unsigned tile
   else launch_filter_one<1, 4, TN>(a, tiles, splits, lds, st);
 }
 
-vcnn_status launch_filter_grad_bf16(const FilterGradBf16Plan& p, const ConvGeom& g, const void* x, const void* dy,
+vcnn_status launch_filter_grad_bf16(const FilterGradBf16Plan& p, const ConvGeom& g0, const void* x, const void* dy,
                                     float* dw, void* workspace, hipStream_t st) {
+  const ConvGeom g = flatten_pointwise(g0);
   uint4* x8n = (uint4*)workspace;
   uint4* dyf = (uint4*)((char*)workspace + p.x8n_bytes);
   float* partial = (float*)((char*)workspace + p.x8n_bytes + p.dyf_bytes);
