@@ -113,7 +113,7 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
   // bf16 variant, default route: the bf16 matrix-core kernels wherever the layer has enough maps / channels
   const bool bf16_mfma = dtype == VCNN_BF16 && algo == VCNN_ALGO_AUTO;
   // (1x1 layers included: with asynchronous staging they are a plain bf16 product through the same kernel)
-  if (bf16_mfma && pass == VCNN_PASS_FWD && g.k > 4 &&
+  if (bf16_mfma && pass == VCNN_PASS_FWD && (g.k > 4 || g.c >= 64) &&
       conv_halo_bf16_plan(g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, &p.hb)) {
     p.path = PATH_HALO_BF16;
     p.workspace_bytes = p.hb.x8_bytes + p.hb.wf_bytes;
@@ -125,7 +125,7 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
     p.workspace_bytes = p.hb.x8_bytes + p.hb.wf_bytes;
     return p;
   }
-  if (bf16_mfma && pass == VCNN_PASS_BWD_FILTER && g.k > 4 && g.c > 4 && filter_grad_bf16_plan(g, &p.hfb)) {
+  if (bf16_mfma && pass == VCNN_PASS_BWD_FILTER && (g.k > 4 || g.c >= 64) && g.c > 4 && filter_grad_bf16_plan(g, &p.hfb)) {
     p.path = PATH_HALO_FILTER_BF16;
     p.workspace_bytes = p.hfb.x8n_bytes + p.hfb.dyf_bytes + align256(p.hfb.partial_bytes);
     p.bias_offset = p.workspace_bytes;

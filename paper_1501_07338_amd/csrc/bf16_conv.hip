@@ -100,10 +100,9 @@ struct HaloBf16Args {
   int relu;
 };
 
-template <int WAVES_M, int WAVES_K, int TN>
+template <int WAVES_M, int WAVES_K, int TM, int TN>
 __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Args a) {
   static_assert(WAVES_M * WAVES_K * 64 == kThreads, "four waves per block");
-  constexpr int TM = 2;
   constexpr int BM = 32 * TM * WAVES_M, BN = 32 * TN;
   extern __shared__ uint4 smem16[];
   int* const tbl = reinterpret_cast<int*>(smem16);  // [uch], per slab of 8 pairs: [half][4]
@@ -316,8 +315,9 @@ bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph
   const int cg = (c + 7) / 8;
   if ((int64_t)cg * h * w > 0x7fffffffLL) return false;  // 32-bit position offsets inside a sample
   p->waves_m = m > 128 ? 4 : (m > 64 ? 2 : 1);
+  p->tm = m <= 32 ? 1 : 2;  // 32-row tiles per wave
   const int waves_k = 4 / p->waves_m;
-  const int bm = 64 * p->waves_m;
+  const int bm = 32 * p->tm * p->waves_m;
   const int tiles_m = (int)ceil_div(m, bm);
   const int wp = w + 2 * pw;
   // pixel tile: fewest rounds of 512 resident blocks, weighted by the tile width (time per tile)
@@ -329,7 +329,7 @@ bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph
     int rows = (bn + ow - 2) / ow + 1;
     if (rows > oh) rows = oh;
     const int nr = rows + r - 1;
-    const size_t red_bytes = waves_k > 1 ? (size_t)p->waves_m * 2 * tn * 16 * 64 * sizeof(float) : 0;
+    const size_t red_bytes = waves_k > 1 ? (size_t)p->waves_m * p->tm * tn * 16 * 64 * sizeof(float) : 0;
     if (red_bytes > kLdsBudget) continue;
     int cgc = 0;
     for (int t = 1; t <= cg; ++t) {
@@ -357,7 +357,7 @@ bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph
   }
   p->tn = best_tn, p->cg = cg, p->cgc = pick, p->nchunks = (int)ceil_div(cg, pick), p->nr = best_nr, p->wp = wp;
   p->uch = (int)ceil_div((int64_t)pick * rs, 8) * 8;
-  const size_t red_bytes = waves_k > 1 ? (size_t)p->waves_m * 2 * best_tn * 16 * 64 * sizeof(float) : 0;
+  const size_t red_bytes = waves_k > 1 ? (size_t)p->waves_m * p->tm * best_tn * 16 * 64 * sizeof(float) : 0;
   p->hpos = (int)(((size_t)pick * best_nr * wp + 63) & ~(size_t)63);
   p->lds_bytes = std::max((size_t)p->uch * 4 + ((size_t)p->uch / 8 + 7) / 4 * 16 + 2 * (size_t)p->hpos * 16, red_bytes);
   p->x8_bytes = (((size_t)n * cg * h * w + 1) * 16 + 255) & ~(size_t)255;  // + the block of zeros
@@ -365,10 +365,10 @@ bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph
   return true;
 }
 
-template <int WAVES_M, int WAVES_K, int TN>
+template <int WAVES_M, int WAVES_K, int TM, int TN>
 static void launch_one(const HaloBf16Args& a, size_t lds, hipStream_t st) {
   const dim3 grid((unsigned)((int64_t)a.tiles_m * a.n * a.tiles_per_img)), block(kThreads);
-  auto kernel = conv_halo_bf16_kernel<WAVES_M, WAVES_K, TN>;
+  auto kernel = conv_halo_bf16_kernel<WAVES_M, WAVES_K, TM, TN>;
   static bool opted = false;  // one flag per instantiation, i.e. per kernel
   if (!opted) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -379,10 +379,11 @@ static void launch_one(const HaloBf16Args& a, size_t lds, hipStream_t st) {
 }
 
 template <int TN>
-static void launch_tn(const HaloBf16Args& a, int waves_m, size_t lds, hipStream_t st) {
-  if (waves_m == 4) launch_one<4, 1, TN>(a, lds, st);
-  else if (waves_m == 2) launch_one<2, 2, TN>(a, lds, st);
-  else launch_one<1, 4, TN>(a, lds, st);
+static void launch_tn(const HaloBf16Args& a, int waves_m, int tm, size_t lds, hipStream_t st) {
+  if (waves_m == 4) launch_one<4, 1, 2, TN>(a, lds, st);
+  else if (waves_m == 2) launch_one<2, 2, 2, TN>(a, lds, st);
+  else if (tm == 2) launch_one<1, 4, 2, TN>(a, lds, st);
+  else launch_one<1, 4, 1, TN>(a, lds, st);
 }
 
 vcnn_status launch_conv_halo_bf16(const HaloBf16Plan& p, int n, int c, int h, int w, int m, int r, int s, int ph, int pw,
@@ -397,7 +398,7 @@ vcnn_status launch_conv_halo_bf16(const HaloBf16Plan& p, int n, int c, int h, in
                        (const bf16*)x, x8, c, p.cg, h * w, total);
     if (vcnn_status e = check_launch("interleave_channels")) return e;
   }
-  const int bm = 64 * p.waves_m;
+  const int bm = 32 * p.tm * p.waves_m;
   const int tiles_m = (int)ceil_div(m, bm);
   {
     const int64_t total = (int64_t)tiles_m * (bm / 32) * p.nchunks * (p.uch / 2) * 512;
@@ -413,9 +414,9 @@ vcnn_status launch_conv_halo_bf16(const HaloBf16Plan& p, int n, int c, int h, in
   a.tiles_m = tiles_m;
   a.tiles_per_img = (int)ceil_div(a.P, 32 * p.tn);
   a.cg = p.cg, a.cgc = p.cgc, a.nchunks = p.nchunks, a.nr = p.nr, a.wp = p.wp, a.uch = p.uch, a.hpos = p.hpos, a.relu = relu;
-  if (p.tn == 2) launch_tn<2>(a, p.waves_m, p.lds_bytes, st);
-  else if (p.tn == 4) launch_tn<4>(a, p.waves_m, p.lds_bytes, st);
-  else launch_tn<5>(a, p.waves_m, p.lds_bytes, st);
+  if (p.tn == 2) launch_tn<2>(a, p.waves_m, p.tm, p.lds_bytes, st);
+  else if (p.tn == 4) launch_tn<4>(a, p.waves_m, p.tm, p.lds_bytes, st);
+  else launch_tn<5>(a, p.waves_m, p.tm, p.lds_bytes, st);
   return check_launch("conv_halo_bf16");
 }
 
@@ -492,10 +493,9 @@ struct FilterBf16Args {
   int chunks, chunks_per_split;  // chunk = (image group, run)
 };
 
-template <int WAVES_M, int WAVES_K, int TN>
+template <int WAVES_M, int WAVES_K, int TM, int TN>
 __global__ __launch_bounds__(kThreads, 2) void filter_grad_bf16_kernel(FilterBf16Args a) {
   static_assert(WAVES_M * WAVES_K * 64 == kThreads, "four waves per block");
-  constexpr int TM = 2;
   constexpr int BM = 32 * TM * WAVES_M, BN = 32 * TN;
   extern __shared__ uint4 smem16[];
   int* const tbl = reinterpret_cast<int*>(smem16);  // [uch], per slab of 8 pixels: [half][4]
@@ -672,8 +672,9 @@ bool filter_grad_bf16_plan(const ConvGeom& g0, FilterGradBf16Plan* p) {
   const int rs = g.r * g.s;
   if ((int64_t)g.c * g.h * g.w > 0x7fffffffLL || g.K > 0x7fffffffLL) return false;
   p->waves_m = g.M > 128 ? 4 : (g.M > 64 ? 2 : 1);
+  p->tm = g.M <= 32 ? 1 : 2;
   const int waves_k = 4 / p->waves_m;
-  const int bm = 64 * p->waves_m;
+  const int bm = 32 * p->tm * p->waves_m;
   const int tiles_m = (int)ceil_div(g.M, bm);
   // column tile: least padding of the kernel-matrix width, wider on ties
   int tn = 0;
@@ -686,7 +687,7 @@ bool filter_grad_bf16_plan(const ConvGeom& g0, FilterGradBf16Plan* p) {
   p->tn = tn;
   p->wp = g.w + 2 * g.pw;
   p->ccs = (int)std::min<int64_t>(g.c, (bn + rs - 2) / rs + 1);  // channels a run of bn columns can touch
-  const size_t red_bytes = waves_k > 1 ? (size_t)p->waves_m * 2 * tn * 16 * 64 * sizeof(float) : 0;
+  const size_t red_bytes = waves_k > 1 ? (size_t)p->waves_m * p->tm * tn * 16 * 64 * sizeof(float) : 0;
   if (red_bytes > kLdsBudget) return false;
   // most output rows per run whose double-buffered halo tile fits
   int bh = 0;
@@ -717,9 +718,9 @@ bool filter_grad_bf16_plan(const ConvGeom& g0, FilterGradBf16Plan* p) {
   return tiles <= 0x7fffffffLL && p->splits <= 65535;
 }
 
-template <int WAVES_M, int WAVES_K, int TN>
+template <int WAVES_M, int WAVES_K, int TM, int TN>
 static void launch_filter_one(const FilterBf16Args& a, unsigned tiles, unsigned splits, size_t lds, hipStream_t st) {
-  auto kernel = filter_grad_bf16_kernel<WAVES_M, WAVES_K, TN>;
+  auto kernel = filter_grad_bf16_kernel<WAVES_M, WAVES_K, TM, TN>;
   static bool opted = false;
   if (!opted) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -730,11 +731,12 @@ static void launch_filter_one(const FilterBf16Args& a, unsigned tiles, unsigned 
 }
 
 template <int TN>
-static void launch_filter_tn(const FilterBf16Args& a, int waves_m, unsigned tiles, unsigned splits, size_t lds,
+static void launch_filter_tn(const FilterBf16Args& a, int waves_m, int tm, unsigned tiles, unsigned splits, size_t lds,
                              hipStream_t st) {
-  if (waves_m == 4) launch_filter_one<4, 1, TN>(a, tiles, splits, lds, st);
-  else if (waves_m == 2) launch_filter_one<2, 2, TN>(a, tiles, splits, lds, st);
-  else launch_filter_one<1, 4, TN>(a, tiles, splits, lds, st);
+  if (waves_m == 4) launch_filter_one<4, 1, 2, TN>(a, tiles, splits, lds, st);
+  else if (waves_m == 2) launch_filter_one<2, 2, 2, TN>(a, tiles, splits, lds, st);
+  else if (tm == 2) launch_filter_one<1, 4, 2, TN>(a, tiles, splits, lds, st);
+  else launch_filter_one<1, 4, 1, TN>(a, tiles, splits, lds, st);
 }
 
 vcnn_status launch_filter_grad_bf16(const FilterGradBf16Plan& p, const ConvGeom& g0, const void* x, const void* dy,
@@ -760,14 +762,14 @@ vcnn_status launch_filter_grad_bf16(const FilterGradBf16Plan& p, const ConvGeom&
   a.x8n = x8n, a.zero = x8n + (int64_t)p.ngroups * chw, a.dyf = dyf, a.out = p.splits > 1 ? partial : dw;
   a.c = g.c, a.h = g.h, a.w = g.w, a.m = g.k, a.r = g.r, a.s = g.s, a.ph = g.ph, a.pw = g.pw, a.oh = g.oh, a.ow = g.ow;
   a.K = (int)g.K;
-  a.tiles_m = (int)ceil_div(g.M, 64 * p.waves_m), a.mt_total = p.mt_total;
+  a.tiles_m = (int)ceil_div(g.M, 32 * p.tm * p.waves_m), a.mt_total = p.mt_total;
   a.runs = p.runs, a.bh = p.bh, a.bp = p.bp;
   a.uch = p.uch, a.hpos = p.hpos, a.ccs = p.ccs, a.nr = p.nr, a.wp = p.wp;
   a.chunks = p.chunks, a.chunks_per_split = p.chunks_per_split;
   const unsigned tiles = (unsigned)(a.tiles_m * ceil_div(g.K, 32 * p.tn));
-  if (p.tn == 2) launch_filter_tn<2>(a, p.waves_m, tiles, (unsigned)p.splits, p.lds_bytes, st);
-  else if (p.tn == 4) launch_filter_tn<4>(a, p.waves_m, tiles, (unsigned)p.splits, p.lds_bytes, st);
-  else launch_filter_tn<5>(a, p.waves_m, tiles, (unsigned)p.splits, p.lds_bytes, st);
+  if (p.tn == 2) launch_filter_tn<2>(a, p.waves_m, p.tm, tiles, (unsigned)p.splits, p.lds_bytes, st);
+  else if (p.tn == 4) launch_filter_tn<4>(a, p.waves_m, p.tm, tiles, (unsigned)p.splits, p.lds_bytes, st);
+  else launch_filter_tn<5>(a, p.waves_m, p.tm, tiles, (unsigned)p.splits, p.lds_bytes, st);
   if (vcnn_status e = check_launch("filter_grad_bf16")) return e;
   if (p.splits == 1) return VCNN_OK;
   return launch_sum_slices(partial, nullptr, dw, VCNN_F32, g.M * g.K, p.splits, 1, 1, 0, st);

@@ -110,6 +110,7 @@ vcnn_status launch_flip_transpose(int dtype, const void* w, void* w2, int M, int
 // ---- bf16_conv.hip / bf16_mfma.hip -----------------------------------------------------------------
 struct HaloBf16Plan {
   int waves_m;       // waves of a block along the output maps (the other 4 / waves_m split the contraction)
+  int tm;            // 32-row tiles per wave (1 for at most 32 maps, else 2)
   int tn;            // 32-pixel column tiles per wave
   int cg, cgc;       // channel groups of 8: total, staged per chunk
   int nchunks;
@@ -131,7 +132,7 @@ vcnn_status launch_conv_halo_bf16(const HaloBf16Plan& p, int n, int c, int h, in
                                   const void* x, const void* wgt, int64_t w_so, int64_t w_si, int flip, const float* bias,
                                   void* y, int relu, void* workspace, hipStream_t st);
 struct FilterGradBf16Plan {
-  int waves_m, tn;
+  int waves_m, tm, tn;
   int ccs, nr, wp;   // channels, rows and row pitch of the halo tile
   int bh, bp, runs;  // output rows / pixels per run, runs per image
   int ngroups;       // image groups of 8

@@ -24,6 +24,8 @@ SHAPES = [
     (3, 19, 21, 22, 1, 8, 8, 0, 0),
     (2, 2, 33, 70, 21, 3, 9, 1, 4),
     (2, 16, 16, 16, 64, 5, 5, 2, 2),
+    (3, 9, 14, 15, 20, 3, 3, 1, 1),     # at most 32 maps: one 32-row tile per wave in every pass
+    (2, 64, 12, 12, 1, 4, 4, 0, 0),     # a single map over many channels goes to the matrix cores as well
 ]
 
 
