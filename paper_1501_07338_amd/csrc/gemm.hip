@@ -214,6 +214,116 @@ static void launch_cfg(const GemmArgs& a, bool a_kc, bool b_kc, bool av, bool bv
 }
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+// -------------------------------------------------------------------------------------------------
+// Small products (the fully connected layers at the experiments' batch sizes: a few MFLOP).  Their cost
+// is latency, not arithmetic: few tiles, and in the slab kernel above a chain of load -> barrier ->
+// MFMA rounds as long as the contraction.  Here a block owns one 32 x 32 tile of C and its four waves
+// split the contraction between them; every wave reads its operand fragments straight from global
+// memory, several groups of 8 contraction steps in flight at once (no LDS staging, no barrier in the
+// loop), and the four partial tiles are added in wave order through LDS.
+// -------------------------------------------------------------------------------------------------
+template <bool A_KC, bool B_KC, bool A_VEC, bool B_VEC, typename TI, typename TO>
+__global__ __launch_bounds__(kThreads) void gemm_small_kernel(GemmArgs a, int tiles_m, int kper) {
+  __shared__ float red[3][16][64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int i0 = (blockIdx.x % tiles_m) * 32, j0 = (blockIdx.x / tiles_m) * 32;
+  const int i = i0 + l32, j = j0 + l32;  // this lane's row of A and column of B
+  const bool i_ok = i < a.M, j_ok = j < a.N;
+  const TI* A = static_cast<const TI*>(a.A) + (int64_t)(i_ok ? i : 0) * a.a_si;
+  const TI* B = static_cast<const TI*>(a.B) + (int64_t)(j_ok ? j : 0) * a.b_sj;
+  const int ks = wave * kper, ke = min(a.K, ks + kper);  // kper is a multiple of 8
+
+  f32x16 acc;
+#pragma unroll
+  for (int q = 0; q < 16; ++q) acc[q] = 0.f;
+
+  // one group = 8 contraction indices = 4 MFMA steps; lanes 0-31 feed k0 + step, lanes 32-63 k0 + 4 + step
+  auto load4 = [&](const TI* base, int64_t sk, bool kc, bool vec, bool row_ok, int k0, float (&v)[4]) {
+    const int kb = k0 + 4 * half;
+    if (kc && vec) {
+      const bool ok = row_ok && kb < ke;  // K and the split are multiples of 4: a group of four is in or out as a whole
+      const float4 t = ld4(base + (ok ? kb : 0));
+      v[0] = ok ? t.x : 0.f, v[1] = ok ? t.y : 0.f, v[2] = ok ? t.z : 0.f, v[3] = ok ? t.w : 0.f;
+    } else {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const bool ok = row_ok && kb + u < ke;
+        const float t = ld(base + (ok ? (int64_t)(kb + u) * sk : 0));
+        v[u] = ok ? t : 0.f;
+      }
+    }
+  };
+  constexpr int U = 8;  // groups in flight
+  for (int k0 = ks; k0 < ke; k0 += 8 * U) {
+    float av[U][4], bv[U][4];
+#pragma unroll
+    for (int g = 0; g < U; ++g) {
+      load4(A, a.a_sk, A_KC, A_VEC, i_ok, k0 + 8 * g, av[g]);
+      load4(B, a.b_sk, B_KC, B_VEC, j_ok, k0 + 8 * g, bv[g]);
+    }
+#pragma unroll
+    for (int g = 0; g < U; ++g)
+#pragma unroll
+      for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[g][u], bv[g][u], acc, 0, 0, 0);
+  }
+
+  if (wave > 0) {
+#pragma unroll
+    for (int q = 0; q < 16; ++q) red[wave - 1][q][lane] = acc[q];
+  }
+  __syncthreads();
+  if (wave > 0) return;
+#pragma unroll
+  for (int w = 0; w < 3; ++w)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) acc[q] += red[w][q][lane];
+  if (!j_ok) return;
+  TO* C = static_cast<TO*>(a.C);
+#pragma unroll
+  for (int q = 0; q < 16; ++q) {
+    const int row = i0 + acc_row(q, lane);
+    if (row < a.M) {
+      float v = acc[q];
+      if (a.bias) v += a.bias[row];
+      if (a.relu) v = fmaxf(v, 0.f);
+      st(C + (int64_t)row * a.c_si + (int64_t)j * a.c_sj, v);
+    }
+  }
+}
+
+template <bool A_KC, bool B_KC, bool A_VEC, bool B_VEC>
+static void launch_small_t(const GemmArgs& a, hipStream_t st) {
+  const int tiles_m = (int)ceil_div(a.M, 32);
+  const int64_t tiles = (int64_t)tiles_m * ceil_div(a.N, 32);
+  const int kper = (int)ceil_div(ceil_div(a.K, 4), 8) * 8;
+  const dim3 grid((unsigned)tiles), block(kThreads);
+  const bool in16 = a.in_dtype == VCNN_BF16, out16 = a.out_dtype == VCNN_BF16;
+  if (in16 && out16)
+    hipLaunchKernelGGL((gemm_small_kernel<A_KC, B_KC, A_VEC, B_VEC, bf16, bf16>), grid, block, 0, st, a, tiles_m, kper);
+  else if (in16)
+    hipLaunchKernelGGL((gemm_small_kernel<A_KC, B_KC, A_VEC, B_VEC, bf16, float>), grid, block, 0, st, a, tiles_m, kper);
+  else
+    hipLaunchKernelGGL((gemm_small_kernel<A_KC, B_KC, A_VEC, B_VEC, float, float>), grid, block, 0, st, a, tiles_m, kper);
+}
+
+static void launch_small(const GemmArgs& a, bool a_kc, bool b_kc, bool av, bool bv, hipStream_t st) {
+  // 16-byte loads only matter (and are only defined here) for contraction-contiguous operands
+  av = av && a_kc, bv = bv && b_kc;
+  if (a_kc && b_kc) {
+    if (av && bv) launch_small_t<true, true, true, true>(a, st);
+    else launch_small_t<true, true, false, false>(a, st);
+  } else if (a_kc) {
+    if (av) launch_small_t<true, false, true, false>(a, st);
+    else launch_small_t<true, false, false, false>(a, st);
+  } else if (b_kc) {
+    if (bv) launch_small_t<false, true, false, true>(a, st);
+    else launch_small_t<false, true, false, false>(a, st);
+  } else {
+    launch_small_t<false, false, false, false>(a, st);
+  }
+}
+
 static bool in_aligned(const void* p, int dtype) { return dtype == VCNN_BF16 ? group_aligned<bf16>(p) : group_aligned<float>(p); }
 
 vcnn_status launch_gemm_f32(const GemmArgs& a, hipStream_t st) {
@@ -235,7 +345,10 @@ vcnn_status launch_gemm_f32(const GemmArgs& a, hipStream_t st) {
   // Small products (the fully connected layers at batch 128) would fill only a handful of large
   // tiles; 64x64 tiles spread them over more compute units.
   const int64_t big_tiles = ceil_div(a.M, 128) * ceil_div(a.N, 128);
-  if (a.M > 32 && a.N <= 4096 && big_tiles < 128)
+  const int64_t small_tiles = ceil_div(a.M, 32) * ceil_div(a.N, 32);
+  if (a.b_P == 0 && a.c_P == 0 && small_tiles <= 512 && (int64_t)a.M * a.N * a.K <= (int64_t)1 << 27)
+    launch_small(a, a_kc, b_kc, av, bv, st);
+  else if (a.M > 32 && a.N <= 4096 && big_tiles < 128)
     launch_cfg<64, 64, 32, 32, 32>(a, a_kc, b_kc, av, bv, st);
   else if (a.M <= 32)
     launch_cfg<32, 256, 32, 32, 64>(a, a_kc, b_kc, av, bv, st);
