@@ -203,6 +203,45 @@ def hbm_kernels(stream):
     return out
 
 
+def mfma_sustained(stream):
+    """Matrix-core rate with register operands only (no memory traffic): what the chip sustains under MFMA
+    load, reported beside the data-sheet peaks the roofline fractions are quoted against."""
+    import torch
+    from paper_1501_07338_amd import vcnn
+    blocks, out = 512, {}
+    sink = torch.empty(blocks * 256, device="cuda")
+    for name, dtype, iters, peak in (("f32", vcnn.F32, 20000, MFMA_F32_PEAK_TFLOPS), ("bf16", vcnn.BF16, 40000, 2500.0)):
+        flop = vcnn.probe_mfma(dtype, blocks, iters, sink)
+        ms = sorted(time_calls(lambda: vcnn.probe_mfma(dtype, blocks, iters, sink), 3, stream) for _ in range(3))[1]
+        out[name] = {"sustained_tflops": flop / (ms * 1e9), "data_sheet_tflops": peak, "ms": ms}
+    return out
+
+
+def batch_sweep(stream, steps=50):
+    """Training and forward-only images/s of the two recognition networks over the mini-batch sizes of the
+    paper's batch experiments (Tables 3 and 4: 1, 100, 200, 300, 400)."""
+    import torch
+    from paper_1501_07338_amd import workloads as wl
+    from paper_1501_07338_amd.net import TrainStep
+    rows = []
+    for name in ("cfg2", "cfg3"):
+        for b in (1, 100, 200, 300, 400):
+            net = wl.make_net(name, b)
+            ts = TrainStep(net, wl.make_params(net), wl.make_inputs(net), device="cuda:0")
+            for _ in range(5):
+                ts.step()
+            graph = ts.capture()
+            for _ in range(5):
+                graph.replay()
+            train_ms = timed_steps(graph.replay, steps, stream)
+            fwd_ms = timed_steps(ts.forward, steps, stream)
+            rows.append({"workload": name, "batch": b, "train_ms_per_step": train_ms, "train_images_per_s": b / (train_ms * 1e-3),
+                         "forward_ms": fwd_ms, "forward_images_per_s": b / (fwd_ms * 1e-3)})
+            del ts, graph
+    torch.cuda.empty_cache()
+    return rows
+
+
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/); filled in
 # from the committed summaries, None where no counter run covers the kernel.
 MEASURED_TRAFFIC: dict = {}
@@ -238,6 +277,7 @@ def main():
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--others", default="cfg1,cfg3,cfg4,cfg5,cfg5_bf16", help="comma list of further workloads to report ('' for none)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the mini-batch sweep of cfg2 / cfg3")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the layer path is single-GPU); use --gpus 1")
@@ -268,8 +308,11 @@ def main():
         "roofline": main_res["roofline"],
         "conv_layers": main_res.get("conv_layers"),
         "hbm_kernels": hbm_kernels(torch.cuda.current_stream()),
+        "mfma_sustained": mfma_sustained(torch.cuda.current_stream()),
         "other_workloads": others,
     }
+    if not args.no_sweep:
+        out["batch_sweep"] = batch_sweep(torch.cuda.current_stream())
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(args.workload)
     print(json.dumps(out))

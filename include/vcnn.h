@@ -152,6 +152,13 @@ vcnn_status vcnn_sgd_update_multi(int32_t tensors, const size_t* counts, float* 
 vcnn_status vcnn_f32_to_bf16(size_t count, const float* src, void* dst, void* stream);
 vcnn_status vcnn_bf16_to_f32(size_t count, const void* src, float* dst, void* stream);
 
+/* Measurement aid, not a layer operation: launches `blocks` blocks of 4 waves that each issue `iters` x 4
+ * independent matrix-core instructions (dtype VCNN_F32: v_mfma_f32_32x32x2_f32; VCNN_BF16:
+ * v_mfma_f32_32x32x16_bf16) on register operands, with no memory traffic except one float per thread
+ * written to `sink` (DEVICE, blocks*256 floats).  *flop (HOST, nullable) receives the flop count of the
+ * launch; timing it gives the matrix-core rate the chip sustains, to report beside the data-sheet peak. */
+vcnn_status vcnn_probe_mfma(int32_t dtype, int32_t blocks, int32_t iters, float* sink, double* flop, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

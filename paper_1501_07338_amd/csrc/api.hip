@@ -517,6 +517,15 @@ vcnn_status vcnn_sgd_update_multi(int32_t tensors, const size_t* counts, float* 
   return VCNN_OK;
 }
 
+vcnn_status vcnn_probe_mfma(int32_t dtype, int32_t blocks, int32_t iters, float* sink, double* flop, void* stream) {
+  if (vcnn_status s = check_dtype(dtype, "probe_mfma")) return s;
+  if (blocks <= 0 || iters <= 0) return fail(VCNN_ERR_SHAPE, "probe_mfma: non-positive size");
+  if (!sink) return fail(VCNN_ERR_NULL, "probe_mfma: NULL sink");
+  // waves x iterations x chains x flop per instruction (32x32x2 fp32: 4096; 32x32x16 bf16: 32768)
+  if (flop) *flop = (double)blocks * 4 * iters * 4 * (dtype == VCNN_BF16 ? 32768.0 : 4096.0);
+  return launch_mfma_probe(dtype, blocks, iters, sink, (hipStream_t)stream);
+}
+
 vcnn_status vcnn_f32_to_bf16(size_t count, const float* src, void* dst, void* stream) {
   if (count == 0) return VCNN_OK;
   if (!src || !dst) return fail(VCNN_ERR_NULL, "f32_to_bf16: NULL tensor");

@@ -153,6 +153,9 @@ vcnn_status launch_bwd_filter_bf16(const BwdFilterBf16Plan& p, const ConvGeom& g
 vcnn_status launch_sum_slices(const float* partial, const float* bias, void* out, int out_dtype, int64_t count,
                               int splits, int64_t plane, int maps, int relu, hipStream_t st);
 
+// ---- probe.hip ----------------------------------------------------------------------------------
+vcnn_status launch_mfma_probe(int dtype, int blocks, int iters, float* sink, hipStream_t st);
+
 // ---- pointwise.hip ------------------------------------------------------------------------------
 // dtype selects the element type (VCNN_F32 / VCNN_BF16) of the activation tensors passed as void*.
 size_t bias_grad_partial_bytes(const ConvGeom& g);

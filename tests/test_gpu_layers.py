@@ -289,6 +289,22 @@ def test_sgd_update_multi_matches_oracle_per_tensor():
         assert_close(to_np(many[k]), O.sgd_update(before[k], to_np(grads[k]), 0.5), 1e-6, f"sgd many {k}")
 
 
+@pytest.mark.parametrize("dtype,per_instr", [(vcnn.F32, 4096.0), (vcnn.BF16, 32768.0)])
+def test_probe_mfma_counts_its_flops_and_runs(dtype, per_instr):
+    blocks, iters = 8, 10
+    sink = torch.full((blocks * 256,), float("nan"), device=DEV)
+    flop = vcnn.probe_mfma(dtype, blocks, iters, sink)
+    assert flop == blocks * 4 * iters * 4 * per_instr
+    assert np.all(np.isfinite(to_np(sink)))
+    if dtype == vcnn.F32:
+        # thread 0 holds column 0, rows 8*(q/4) + q%4 of the 32x32 product; lane l supplies A[l%32][l/32] and B[l/32][l%32]
+        fa = lambda t: np.float32(1.0) + np.float32(0.001) * np.float32(t % 61)
+        fb = lambda t: np.float32(0.5) + np.float32(0.002) * np.float32(t % 53)
+        rows = [8 * (q // 4) + q % 4 for q in range(16)]
+        want = 4 * iters * sum(float(fa(r)) * float(fb(0)) + float(fa(r + 32)) * float(fb(32)) for r in rows)
+        assert abs(float(to_np(sink)[0]) - want) <= 1e-4 * want
+
+
 def test_gpu_launch_of_bad_arguments_is_rejected_cleanly():
     d = vcnn.conv_desc(2, 3, 8, 8, 4, 3, 3)
     x = torch.zeros((2, 3, 8, 8), device=DEV)
