@@ -250,6 +250,8 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
           cur[mi] = af[i][mi];
           af[i][mi] = nsrc[mi * mstride + i * 64];
         }
+        // keep the fragment loads of the next slab ahead of this step's MFMAs: a full slab of lead time
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
@@ -607,6 +609,8 @@ __global__ __launch_bounds__(kThreads, 2) void filter_grad_bf16_kernel(FilterBf1
           cur[mi] = af[i][mi];
           af[i][mi] = nsrc[mi * mstride + i * 64];
         }
+        // keep the fragment loads of the next slab ahead of this step's MFMAs: a full slab of lead time
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
