@@ -26,6 +26,7 @@ if str(ROOT) not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 MFMA_F32_PEAK_TFLOPS = 157.3
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 -> fp32 accumulate
 WORKLOAD_TEXT = {
     "cfg1": "cfg1: single conv block 8x1x28x28 -> conv5x5x6 -> ReLU -> maxpool2, fwd + bwd from an upstream gradient",
     "cfg2": "cfg2: small recognition CNN, batch 128x1x28x28, conv5x5x20-pool-conv5x5x50-pool-fc500-fc10, "
@@ -124,6 +125,8 @@ def run_workload(name, steps, warmup, layer_iters=10):
             layers.append({"layer": f"conv{li}", "pass": pname, "M": g["M"], "K": g["K"], "N": g["N"], "ms": t,
                            "gflops": flops / (t * 1e6),
                            "pct_mfma_f32_peak": 100.0 * flops / (t * 1e9) / MFMA_F32_PEAK_TFLOPS,
+                           # the bf16 variant contracts on the bf16 matrix-core instructions: price it against their peak
+                           "pct_mfma_peak": 100.0 * flops / (t * 1e9) / (MFMA_BF16_PEAK_TFLOPS if bf16 else MFMA_F32_PEAK_TFLOPS),
                            "algorithmic_bytes": in_b + out_b + w_b, "gbs": (in_b + out_b + w_b) / (t * 1e6),
                            "in_step": not (li == 0 and pname == "bwd_data")})
             if not (li == 0 and pname == "bwd_data"):
@@ -139,17 +142,19 @@ def run_workload(name, steps, warmup, layer_iters=10):
 def dominant_roofline(res):
     """Roofline record of the convolution pass that takes the most time inside the step.  A pass whose
     arithmetic intensity (flops over input + output + kernel bytes) is above the machine balance
-    (157.3 TFLOP/s over 8 TB/s) is priced against the fp32 matrix-core peak, else against HBM."""
+    (matrix-core peak over 8 TB/s) is priced against the matrix-core peak of the instructions it contracts
+    on (fp32: 157.3 TFLOP/s; bf16 variant: 2.5 PFLOP/s), else against HBM."""
     layers = [l for l in res.get("conv_layers") or [] if l["in_step"]]
     if not layers:
         return None
     top = max(layers, key=lambda r: r["ms"])
     flops = 2.0 * top["M"] * top["K"] * top["N"]
     name = f"{res['workload']}.{top['layer']}.{top['pass']}"
-    if flops / top["algorithmic_bytes"] >= MFMA_F32_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS:
+    peak = MFMA_BF16_PEAK_TFLOPS if res.get("storage_dtype") == "bf16" else MFMA_F32_PEAK_TFLOPS
+    if flops / top["algorithmic_bytes"] >= peak * 1e3 / HBM_PEAK_GBS:
         ach = flops / (top["ms"] * 1e9)
-        return {"kernel": name, "bound": "mfma", "achieved": ach, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / MFMA_F32_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC.get(name)}
+        return {"kernel": name, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
+                "frac": ach / peak, "traffic": MEASURED_TRAFFIC.get(name)}
     ach = top["algorithmic_bytes"] / (top["ms"] * 1e6)
     return {"kernel": name, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(name)}
@@ -244,7 +249,16 @@ def batch_sweep(stream, steps=50):
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/); filled in
 # from the committed summaries, None where no counter run covers the kernel.
-MEASURED_TRAFFIC: dict = {}
+MEASURED_TRAFFIC: dict = {
+    # (2 x FETCH_SIZE + WRITE_SIZE) x 1024 of the call's kernel, profiles/cfg5_cfg4_cfg2_hbm_traffic_pmc.txt
+    "cfg2.conv2.fwd": 4.08e6,        # conv_halo_kernel<64, 64, ...>: 1191.5 KiB fetched (x2), 1600 KiB written
+    "cfg5.conv2.fwd": 356.1e6,       # conv_halo_kernel<128, 128, ...>
+    "cfg5.conv2.bwd_filter": 451.7e6,  # conv_halo_filter_kernel<128, 128, ...> (without the slice sum)
+    "cfg5.conv2.bwd_data": 7926.0e6,   # gemm_f32_kernel<128, 128, ...> of the explicit route (without col2im)
+    "cfg5_bf16.conv2.fwd": 199.6e6,    # conv_halo_bf16_kernel<4, 1, 2, 5> (without the two re-layout passes)
+    "cfg5_bf16.conv2.bwd_filter": 409.5e6,  # filter_grad_bf16_kernel<4, 1, 2, 4>
+    "cfg5_bf16.conv2.bwd_data": 738.1e6,    # conv_halo_bf16_kernel<1, 4, 2, 4>: the kernel matrix is re-fetched past L2
+}
 
 
 def cpu_baseline(name, budget_s=20.0):

@@ -90,7 +90,7 @@ static bool halo_bwd_data_pays(const ConvGeom& g, const HaloPlan& hp) {
 
 // Which realisation a pass uses for a given shape.  The same decision drives the workspace query and
 // the launch, so the two always agree.
-enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER, PATH_HALO, PATH_HALO_FILTER, PATH_HALO_BF16, PATH_FILTER_BF16, PATH_HALO_FILTER_BF16 };
+enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER, PATH_HALO, PATH_HALO_FILTER, PATH_HALO_BF16, PATH_FILTER_BF16, PATH_HALO_FILTER_BF16, PATH_FEW_COLS_FILTER };
 struct Plan {
   Path path;
   DirectGeom dg;
@@ -99,6 +99,7 @@ struct Plan {
   HaloBf16Plan hb;
   BwdFilterBf16Plan fb;
   FilterGradBf16Plan hfb;
+  FewColsPlan fcp;
   int split;        // channel slices (few-out), output-map group size (few-in) or batch slices (filter gradient)
   size_t partial_bytes;
   size_t workspace_bytes;
@@ -176,6 +177,10 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
     if (allow_direct && g.k <= 4 && direct_filter_grad_plan(g, &p.dg, &p.split, &p.partial_bytes)) {
       p.path = PATH_DIRECT_FILTER;
       p.workspace_bytes = align256(p.partial_bytes);
+    } else if (algo == VCNN_ALGO_AUTO && g.k > 4 && filter_grad_few_cols_plan(g, &p.fcp)) {
+      // narrow kernel matrix (the networks' first layers): every block computes the whole result for its pixels
+      p.path = PATH_FEW_COLS_FILTER;
+      p.workspace_bytes = align256(p.fcp.partial_bytes);
     } else if (allow_direct && (g.c > 4 || g.k >= 32 || algo == VCNN_ALGO_IMPLICIT) && conv_halo_filter_plan(g, &p.hfp)) {
       p.path = PATH_HALO_FILTER;
       p.workspace_bytes = align256(p.hfp.partial_bytes);
@@ -305,6 +310,8 @@ vcnn_status vcnn_conv_bwd_filter(const vcnn_conv_desc* d, const void* x, const v
   float* bias_partial = (float*)((char*)workspace + plan.bias_offset);
   if (plan.path == PATH_DIRECT_FILTER) {
     if (vcnn_status s = launch_direct_filter_grad(plan.dg, dt, plan.split, x, dy, dw, (float*)workspace, st)) return s;
+  } else if (plan.path == PATH_FEW_COLS_FILTER) {
+    if (vcnn_status s = launch_filter_grad_few_cols(plan.fcp, dt, g, x, dy, dw, (float*)workspace, st)) return s;
   } else if (plan.path == PATH_HALO_FILTER_BF16) {
     if (vcnn_status s = launch_filter_grad_bf16(plan.hfb, g, x, dy, dw, workspace, st)) return s;
   } else if (plan.path == PATH_FILTER_BF16) {

@@ -105,6 +105,15 @@ struct HaloFilterPlan {
 bool conv_halo_filter_plan(const ConvGeom& g, HaloFilterPlan* p);
 vcnn_status launch_conv_halo_filter(const HaloFilterPlan& p, int dtype, const ConvGeom& g, const void* x, const void* dy,
                                     float* dw, float* partial, hipStream_t st);
+struct FewColsPlan {
+  int tm, tn;        // 32-row / 32-column tiles of the whole M x K result
+  int nr, wp;
+  int runs_per_img, total_runs, runs_per_block, blocks;
+  size_t lds_bytes, partial_bytes;
+};
+bool filter_grad_few_cols_plan(const ConvGeom& g, FewColsPlan* p);
+vcnn_status launch_filter_grad_few_cols(const FewColsPlan& p, int dtype, const ConvGeom& g, const void* x, const void* dy,
+                                        float* dw, float* partial, hipStream_t st);
 vcnn_status launch_flip_transpose(int dtype, const void* w, void* w2, int M, int C, int RS, hipStream_t st);
 
 // ---- bf16_conv.hip / bf16_mfma.hip -----------------------------------------------------------------

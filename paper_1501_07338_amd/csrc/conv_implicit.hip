@@ -591,4 +591,213 @@ vcnn_status launch_conv_halo_filter(const HaloFilterPlan& p, int dtype, const Co
   return launch_sum_slices(partial, nullptr, dw, VCNN_F32, g.M * g.K, p.splits, 1, 1, 0, st);
 }
 
+// =========================================================================================================
+// Filter gradient of layers with a narrow kernel matrix (K = C*R*S <= 128 columns, at most 64 maps): the first
+// layers of the networks, whose contraction over (sample, pixel) is very long while the result is tiny.
+// The kernel above would give such a layer one tile and leave most of its columns and waves idle.  Here
+// every block computes the whole M x K result for its share of the pixels: a run of 128 output pixels is
+// staged at once (dY rows and the input rows + halo, all loads in flight together), the four waves take
+// 32 pixels each, and their partial tiles are added in wave order through LDS.  Blocks write partial
+// results that a second kernel adds in a fixed order.
+// =========================================================================================================
+struct FewColsArgs {
+  const void* x;   // [n][c][h][w]
+  const void* dy;  // [n][m][oh][ow]
+  float* out;      // [blocks][m][K]
+  int n, c, h, w, m, r, s, ph, pw, oh, ow, P, K;
+  int runs_per_img, total_runs, runs_per_block;
+  int nr, wp;
+};
+
+static constexpr int kRunPixels = 128;
+
+template <int TM, int TN, typename T>
+__global__ __launch_bounds__(kThreads) void filter_grad_few_cols_kernel(FewColsArgs a) {
+  constexpr int BP = kRunPixels, PITCH = BP + 4, ROWS = 32 * TM;
+  extern __shared__ float4 smem4[];
+  float* const dyt = reinterpret_cast<float*>(smem4);             // [ROWS][PITCH]
+  int* const pixoff = reinterpret_cast<int*>(dyt + ROWS * PITCH);  // [BP]
+  float* const halo = dyt + ROWS * PITCH + BP;                     // [c][nr][wp]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int RS = a.r * a.s;
+  const int plane = a.nr * a.wp;
+
+  int tap_base[TN];
+#pragma unroll
+  for (int ni = 0; ni < TN; ++ni) {
+    const int col = min(ni * 32 + l32, a.K - 1);
+    const int c = col / RS;
+    const int q = col - c * RS;
+    const int r = q / a.s;
+    tap_base[ni] = c * plane + r * a.wp + (q - r * a.s);
+  }
+
+  f32x16 acc[TM][TN];
+  zero_acc<TM, TN>(acc);
+
+  const int run0 = blockIdx.x * a.runs_per_block;
+  const int run1 = min(a.total_runs, run0 + a.runs_per_block);
+  for (int run = run0; run < run1; ++run) {
+    const int n = run / a.runs_per_img;
+    const int p0 = (run - n * a.runs_per_img) * BP;
+    const int plen = min(BP, a.P - p0);
+    const int oh_first = p0 / a.ow;
+    __syncthreads();  // the previous run's MFMAs are done with the tiles
+    if (tid < BP) {
+      const int p = min(p0 + tid, a.P - 1);
+      const int oh = p / a.ow;
+      pixoff[tid] = (oh - oh_first) * a.wp + (p - oh * a.ow);
+    }
+    {  // dY rows of this run, zero beyond the maps / the sample's pixels; eight loads in flight per thread
+      const T* dyn = static_cast<const T*>(a.dy) + (int64_t)n * a.m * a.P + p0;
+      constexpr int PER = ROWS * BP / kThreads;
+      static_assert(PER % 8 == 0, "eight loads per round");
+#pragma unroll
+      for (int e0 = 0; e0 < PER; e0 += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int e = (e0 + u) * kThreads + tid;
+          const int m = e / BP, pk = e - m * BP;
+          const bool ok = m < a.m && pk < plen;
+          const float t = ld(dyn + (ok ? (int64_t)m * a.P + pk : 0));
+          v[u] = ok ? t : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int e = (e0 + u) * kThreads + tid;
+          const int m = e / BP, pk = e - m * BP;
+          dyt[m * PITCH + pk] = v[u];
+        }
+      }
+    }
+    stage_halo<8>(halo, static_cast<const T*>(a.x) + (int64_t)n * a.c * a.h * a.w, a.c, a.c, a.nr, a.wp, a.h, a.w,
+                  oh_first - a.ph, a.pw, tid);
+    __syncthreads();
+
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {  // this wave's 32 pixels in groups of 8 = four MFMA steps
+      const int pk0 = wave * 32 + g * 8 + 4 * half;
+      float4 af[TM];
+#pragma unroll
+      for (int mi = 0; mi < TM; ++mi) af[mi] = *reinterpret_cast<const float4*>(dyt + (mi * 32 + l32) * PITCH + pk0);
+      const int4 o4 = *reinterpret_cast<const int4*>(pixoff + pk0);
+      const int o[4] = {o4.x, o4.y, o4.z, o4.w};
+      float bf[TN][4];
+#pragma unroll
+      for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) bf[ni][i] = halo[tap_base[ni] + o[i]];
+      const float* afl = reinterpret_cast<const float*>(af);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < TN; ++ni)
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(afl[mi * 4 + i], bf[ni][i], acc[mi][ni], 0, 0, 0);
+    }
+  }
+
+  // add the four waves' tiles in wave order
+  float* red = reinterpret_cast<float*>(smem4);  // [TM*TN*16][64 lanes]
+#pragma unroll 1
+  for (int k = 1; k < 4; ++k) {
+    __syncthreads();
+    if (wave == k) {
+#pragma unroll
+      for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+          for (int q = 0; q < 16; ++q) red[((mi * TN + ni) * 16 + q) * 64 + lane] = acc[mi][ni][q];
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+      for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+          for (int q = 0; q < 16; ++q) acc[mi][ni][q] += red[((mi * TN + ni) * 16 + q) * 64 + lane];
+    }
+  }
+  if (wave != 0) return;
+  float* dst = a.out + (int64_t)blockIdx.x * a.m * a.K;
+#pragma unroll
+  for (int ni = 0; ni < TN; ++ni) {
+    const int col = ni * 32 + l32;
+    if (col >= a.K) continue;
+#pragma unroll
+    for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int m = mi * 32 + acc_row(q, lane);
+        if (m < a.m) dst[(int64_t)m * a.K + col] = acc[mi][ni][q];
+      }
+  }
+}
+
+bool filter_grad_few_cols_plan(const ConvGeom& g, FewColsPlan* p) {
+  if (g.K > 128 || g.M > 64 || (int64_t)g.c * g.h * g.w > 0x7fffffffLL || g.P > 0x7fffffffLL) return false;
+  p->tm = g.M <= 32 ? 1 : 2;
+  p->tn = (int)ceil_div(g.K, 32);
+  int rows = (kRunPixels + g.ow - 2) / g.ow + 1;  // rows a run of consecutive pixels can touch
+  if (rows > g.oh) rows = g.oh;
+  p->nr = rows + g.r - 1, p->wp = g.w + 2 * g.pw;
+  const size_t tile = (size_t)32 * p->tm * (kRunPixels + 4) * 4;
+  p->lds_bytes = tile + kRunPixels * 4 + (size_t)g.c * p->nr * p->wp * 4;
+  const size_t red = (size_t)p->tm * p->tn * 16 * 64 * 4;
+  if (red > tile || p->lds_bytes > 64 * 1024) return false;
+  p->runs_per_img = (int)ceil_div(g.P, kRunPixels);
+  const int64_t total = (int64_t)g.n * p->runs_per_img;
+  if (total > 0x7fffffffLL) return false;
+  p->total_runs = (int)total;
+  p->runs_per_block = (int)ceil_div(total, 1024);
+  p->blocks = (int)ceil_div(total, p->runs_per_block);
+  p->partial_bytes = p->blocks > 1 ? (size_t)p->blocks * g.M * g.K * sizeof(float) : 0;
+  return true;
+}
+
+template <int TM, int TN, typename T>
+static void launch_few_cols_one(const FewColsArgs& a, const FewColsPlan& p, hipStream_t st) {
+  auto kernel = filter_grad_few_cols_kernel<TM, TN, T>;
+  static bool opted = false;
+  if (!opted) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
+    opted = true;
+  }
+  hipLaunchKernelGGL(kernel, dim3((unsigned)p.blocks), dim3(kThreads), p.lds_bytes, st, a);
+}
+
+template <int TM, typename T>
+static void launch_few_cols_tn(const FewColsArgs& a, const FewColsPlan& p, hipStream_t st) {
+  if (p.tn == 1) launch_few_cols_one<TM, 1, T>(a, p, st);
+  else if (p.tn == 2) launch_few_cols_one<TM, 2, T>(a, p, st);
+  else if (p.tn == 3) launch_few_cols_one<TM, 3, T>(a, p, st);
+  else launch_few_cols_one<TM, 4, T>(a, p, st);
+}
+
+vcnn_status launch_filter_grad_few_cols(const FewColsPlan& p, int dtype, const ConvGeom& g, const void* x, const void* dy,
+                                        float* dw, float* partial, hipStream_t st) {
+  FewColsArgs a{};
+  a.x = x, a.dy = dy, a.out = p.blocks > 1 ? partial : dw;
+  a.n = g.n, a.c = g.c, a.h = g.h, a.w = g.w, a.m = g.k, a.r = g.r, a.s = g.s, a.ph = g.ph, a.pw = g.pw;
+  a.oh = g.oh, a.ow = g.ow, a.P = (int)g.P, a.K = (int)g.K;
+  a.runs_per_img = p.runs_per_img, a.total_runs = p.total_runs, a.runs_per_block = p.runs_per_block;
+  a.nr = p.nr, a.wp = p.wp;
+  if (dtype == VCNN_BF16) {
+    if (p.tm == 1) launch_few_cols_tn<1, bf16>(a, p, st);
+    else launch_few_cols_tn<2, bf16>(a, p, st);
+  } else {
+    if (p.tm == 1) launch_few_cols_tn<1, float>(a, p, st);
+    else launch_few_cols_tn<2, float>(a, p, st);
+  }
+  if (vcnn_status e = check_launch("filter_grad_few_cols")) return e;
+  if (p.blocks == 1) return VCNN_OK;
+  return launch_sum_slices(partial, nullptr, dw, VCNN_F32, g.M * g.K, p.blocks, 1, 1, 0, st);
+}
+
 }  // namespace vcnn

@@ -154,8 +154,50 @@ __global__ __launch_bounds__(kThreads) void sum_slices_kernel(const float* __res
   st(out + i, acc);
 }
 
+// The same sum for many slices of a short result: 16 lanes of a block share an output element, lane j adds
+// slices j, j + 16, ... (four loads in flight), and the 16 lane sums are added in lane order.  The order is
+// fixed by the shape alone, so results stay run-to-run identical.
+template <typename TO>
+__global__ __launch_bounds__(kThreads) void sum_slices_wide_kernel(const float* __restrict__ partial,
+                                                                   const float* __restrict__ bias,
+                                                                   TO* __restrict__ out, int64_t count, int splits,
+                                                                   int64_t plane, int maps, int relu) {
+  __shared__ float lanes[16][17];
+  const int e = threadIdx.x & 15, j = threadIdx.x >> 4;
+  const int64_t i = (int64_t)blockIdx.x * 16 + e;
+  float acc = 0.f;
+  if (i < count) {
+    int s = j;
+    for (; s + 48 < splits; s += 64) {
+      const float v0 = partial[(int64_t)s * count + i], v1 = partial[(int64_t)(s + 16) * count + i];
+      const float v2 = partial[(int64_t)(s + 32) * count + i], v3 = partial[(int64_t)(s + 48) * count + i];
+      acc = (((acc + v0) + v1) + v2) + v3;
+    }
+    for (; s < splits; s += 16) acc += partial[(int64_t)s * count + i];
+  }
+  lanes[j][e] = acc;
+  __syncthreads();
+  if (j != 0 || i >= count) return;
+  float total = 0.f;
+#pragma unroll
+  for (int l = 0; l < 16; ++l) total += lanes[l][e];
+  if (bias) total += bias[(i / plane) % maps];
+  if (relu) total = fmaxf(total, 0.f);
+  st(out + i, total);
+}
+
 vcnn_status launch_sum_slices(const float* partial, const float* bias, void* out, int out_dtype, int64_t count,
                               int splits, int64_t plane, int maps, int relu, hipStream_t st) {
+  if (splits >= 32 && count <= 65536) {  // few output elements, many slices: parallelise over the slices as well
+    const dim3 grid((unsigned)ceil_div(count, 16)), block(kThreads);
+    if (out_dtype == VCNN_BF16)
+      hipLaunchKernelGGL(sum_slices_wide_kernel<bf16>, grid, block, 0, st, partial, bias, (bf16*)out, count, splits, plane,
+                         maps, relu);
+    else
+      hipLaunchKernelGGL(sum_slices_wide_kernel<float>, grid, block, 0, st, partial, bias, (float*)out, count, splits,
+                         plane, maps, relu);
+    return check_launch("sum_slices_wide");
+  }
   const dim3 grid((unsigned)ceil_div(count, kThreads)), block(kThreads);
   if (out_dtype == VCNN_BF16)
     hipLaunchKernelGGL(sum_slices_kernel<bf16>, grid, block, 0, st, partial, bias, (bf16*)out, count, splits, plane, maps,
