@@ -311,7 +311,8 @@ vcnn_status vcnn_conv_bwd_filter(const vcnn_conv_desc* d, const void* x, const v
   if (plan.path == PATH_DIRECT_FILTER) {
     if (vcnn_status s = launch_direct_filter_grad(plan.dg, dt, plan.split, x, dy, dw, (float*)workspace, st)) return s;
   } else if (plan.path == PATH_FEW_COLS_FILTER) {
-    if (vcnn_status s = launch_filter_grad_few_cols(plan.fcp, dt, g, x, dy, dw, (float*)workspace, st)) return s;
+    if (vcnn_status s = launch_filter_grad_few_cols(plan.fcp, dt, g, x, dy, dw, dbias, (float*)workspace, st)) return s;
+    if (plan.fcp.bias_column) return VCNN_OK;  // the bias gradient came out of the same product
   } else if (plan.path == PATH_HALO_FILTER_BF16) {
     if (vcnn_status s = launch_filter_grad_bf16(plan.hfb, g, x, dy, dw, workspace, st)) return s;
   } else if (plan.path == PATH_FILTER_BF16) {

@@ -109,11 +109,13 @@ struct FewColsPlan {
   int tm, tn;        // 32-row / 32-column tiles of the whole M x K result
   int nr, wp;
   int runs_per_img, total_runs, runs_per_block, blocks;
+  bool bias_column;  // the kernel can produce the bias gradient in a spare column of its last tile
   size_t lds_bytes, partial_bytes;
 };
 bool filter_grad_few_cols_plan(const ConvGeom& g, FewColsPlan* p);
+// dbias nullable; when the plan has a bias column and dbias is given, dbias is produced here as well
 vcnn_status launch_filter_grad_few_cols(const FewColsPlan& p, int dtype, const ConvGeom& g, const void* x, const void* dy,
-                                        float* dw, float* partial, hipStream_t st);
+                                        float* dw, float* dbias, float* partial, hipStream_t st);
 vcnn_status launch_flip_transpose(int dtype, const void* w, void* w2, int M, int C, int RS, hipStream_t st);
 
 // ---- bf16_conv.hip / bf16_mfma.hip -----------------------------------------------------------------
@@ -161,6 +163,9 @@ vcnn_status launch_bwd_filter_bf16(const BwdFilterBf16Plan& p, const ConvGeom& g
 // out[i] = act(bias[(i / plane) % maps] + sum_s partial[s][i]), slices added in ascending order (bias nullable)
 vcnn_status launch_sum_slices(const float* partial, const float* bias, void* out, int out_dtype, int64_t count,
                               int splits, int64_t plane, int maps, int relu, hipStream_t st);
+// partial is [splits][rows][cols + 1]: main[r][c] = sum_s partial[s][r][c] for c < cols, last[r] = sum_s partial[s][r][cols]
+vcnn_status launch_sum_slices_split(const float* partial, float* main, float* last, int64_t rows, int cols, int splits,
+                                    hipStream_t st);
 
 // ---- probe.hip ----------------------------------------------------------------------------------
 vcnn_status launch_mfma_probe(int dtype, int blocks, int iters, float* sink, hipStream_t st);

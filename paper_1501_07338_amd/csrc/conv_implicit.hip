@@ -603,8 +603,9 @@ vcnn_status launch_conv_halo_filter(const HaloFilterPlan& p, int dtype, const Co
 struct FewColsArgs {
   const void* x;   // [n][c][h][w]
   const void* dy;  // [n][m][oh][ow]
-  float* out;      // [blocks][m][K]
+  float* out;      // [blocks][m][Kp]
   int n, c, h, w, m, r, s, ph, pw, oh, ow, P, K;
+  int Kp;          // K, or K + 1 when the spare column K carries the bias gradient (B operand = 1 there)
   int runs_per_img, total_runs, runs_per_block;
   int nr, wp;
 };
@@ -625,6 +626,7 @@ __global__ __launch_bounds__(kThreads) void filter_grad_few_cols_kernel(FewColsA
   const int plane = a.nr * a.wp;
 
   int tap_base[TN];
+  bool ones[TN];  // this lane's column is the bias column: db[m] = sum over pixels of dY[m][pixel] * 1
 #pragma unroll
   for (int ni = 0; ni < TN; ++ni) {
     const int col = min(ni * 32 + l32, a.K - 1);
@@ -632,6 +634,7 @@ __global__ __launch_bounds__(kThreads) void filter_grad_few_cols_kernel(FewColsA
     const int q = col - c * RS;
     const int r = q / a.s;
     tap_base[ni] = c * plane + r * a.wp + (q - r * a.s);
+    ones[ni] = a.Kp > a.K && ni * 32 + l32 == a.K;
   }
 
   f32x16 acc[TM][TN];
@@ -689,7 +692,10 @@ __global__ __launch_bounds__(kThreads) void filter_grad_few_cols_kernel(FewColsA
 #pragma unroll
       for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) bf[ni][i] = halo[tap_base[ni] + o[i]];
+        for (int i = 0; i < 4; ++i) {
+          const float t = halo[tap_base[ni] + o[i]];
+          bf[ni][i] = ones[ni] ? 1.f : t;
+        }
       const float* afl = reinterpret_cast<const float*>(af);
 #pragma unroll
       for (int i = 0; i < 4; ++i)
@@ -725,17 +731,17 @@ __global__ __launch_bounds__(kThreads) void filter_grad_few_cols_kernel(FewColsA
     }
   }
   if (wave != 0) return;
-  float* dst = a.out + (int64_t)blockIdx.x * a.m * a.K;
+  float* dst = a.out + (int64_t)blockIdx.x * a.m * a.Kp;
 #pragma unroll
   for (int ni = 0; ni < TN; ++ni) {
     const int col = ni * 32 + l32;
-    if (col >= a.K) continue;
+    if (col >= a.Kp) continue;
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
       for (int q = 0; q < 16; ++q) {
         const int m = mi * 32 + acc_row(q, lane);
-        if (m < a.m) dst[(int64_t)m * a.K + col] = acc[mi][ni][q];
+        if (m < a.m) dst[(int64_t)m * a.Kp + col] = acc[mi][ni][q];
       }
   }
 }
@@ -757,7 +763,9 @@ bool filter_grad_few_cols_plan(const ConvGeom& g, FewColsPlan* p) {
   p->total_runs = (int)total;
   p->runs_per_block = (int)ceil_div(total, 1024);
   p->blocks = (int)ceil_div(total, p->runs_per_block);
-  p->partial_bytes = p->blocks > 1 ? (size_t)p->blocks * g.M * g.K * sizeof(float) : 0;
+  // a spare column in the last 32-column tile carries the bias gradient along; partials are then always used
+  p->bias_column = g.K % 32 != 0;
+  p->partial_bytes = (size_t)p->blocks * g.M * (g.K + 1) * sizeof(float);
   return true;
 }
 
@@ -781,9 +789,11 @@ static void launch_few_cols_tn(const FewColsArgs& a, const FewColsPlan& p, hipSt
 }
 
 vcnn_status launch_filter_grad_few_cols(const FewColsPlan& p, int dtype, const ConvGeom& g, const void* x, const void* dy,
-                                        float* dw, float* partial, hipStream_t st) {
+                                        float* dw, float* dbias, float* partial, hipStream_t st) {
+  const bool with_bias = p.bias_column && dbias;
   FewColsArgs a{};
-  a.x = x, a.dy = dy, a.out = p.blocks > 1 ? partial : dw;
+  a.x = x, a.dy = dy, a.out = (p.blocks > 1 || with_bias) ? partial : dw;
+  a.Kp = (int)g.K + (with_bias ? 1 : 0);
   a.n = g.n, a.c = g.c, a.h = g.h, a.w = g.w, a.m = g.k, a.r = g.r, a.s = g.s, a.ph = g.ph, a.pw = g.pw;
   a.oh = g.oh, a.ow = g.ow, a.P = (int)g.P, a.K = (int)g.K;
   a.runs_per_img = p.runs_per_img, a.total_runs = p.total_runs, a.runs_per_block = p.runs_per_block;
@@ -796,6 +806,7 @@ vcnn_status launch_filter_grad_few_cols(const FewColsPlan& p, int dtype, const C
     else launch_few_cols_tn<2, float>(a, p, st);
   }
   if (vcnn_status e = check_launch("filter_grad_few_cols")) return e;
+  if (with_bias) return launch_sum_slices_split(partial, dw, dbias, g.M, (int)g.K, p.blocks, st);
   if (p.blocks == 1) return VCNN_OK;
   return launch_sum_slices(partial, nullptr, dw, VCNN_F32, g.M * g.K, p.blocks, 1, 1, 0, st);
 }

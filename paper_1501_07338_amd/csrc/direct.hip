@@ -186,6 +186,45 @@ __global__ __launch_bounds__(kThreads) void sum_slices_wide_kernel(const float* 
   st(out + i, total);
 }
 
+// Slice sum of a [rows][cols + 1] result whose last column goes to a vector of its own (a filter gradient with
+// the bias gradient riding along): same lane scheme and order as sum_slices_wide_kernel.
+__global__ __launch_bounds__(kThreads) void sum_slices_split_kernel(const float* __restrict__ partial,
+                                                                    float* __restrict__ main, float* __restrict__ last,
+                                                                    int64_t rows, int cols, int splits) {
+  __shared__ float lanes[16][17];
+  const int e = threadIdx.x & 15, j = threadIdx.x >> 4;
+  const int64_t count = rows * (cols + 1);
+  const int64_t i = (int64_t)blockIdx.x * 16 + e;
+  float acc = 0.f;
+  if (i < count) {
+    int s = j;
+    for (; s + 48 < splits; s += 64) {
+      const float v0 = partial[(int64_t)s * count + i], v1 = partial[(int64_t)(s + 16) * count + i];
+      const float v2 = partial[(int64_t)(s + 32) * count + i], v3 = partial[(int64_t)(s + 48) * count + i];
+      acc = (((acc + v0) + v1) + v2) + v3;
+    }
+    for (; s < splits; s += 16) acc += partial[(int64_t)s * count + i];
+  }
+  lanes[j][e] = acc;
+  __syncthreads();
+  if (j != 0 || i >= count) return;
+  float total = 0.f;
+#pragma unroll
+  for (int l = 0; l < 16; ++l) total += lanes[l][e];
+  const int64_t r = i / (cols + 1);
+  const int c = (int)(i - r * (cols + 1));
+  if (c < cols) main[r * cols + c] = total;
+  else last[r] = total;
+}
+
+vcnn_status launch_sum_slices_split(const float* partial, float* main, float* last, int64_t rows, int cols, int splits,
+                                    hipStream_t st) {
+  const int64_t count = rows * (cols + 1);
+  hipLaunchKernelGGL(sum_slices_split_kernel, dim3((unsigned)ceil_div(count, 16)), dim3(kThreads), 0, st, partial, main, last,
+                     rows, cols, splits);
+  return check_launch("sum_slices_split");
+}
+
 vcnn_status launch_sum_slices(const float* partial, const float* bias, void* out, int out_dtype, int64_t count,
                               int splits, int64_t plane, int maps, int relu, hipStream_t st) {
   if (splits >= 32 && count <= 65536) {  // few output elements, many slices: parallelise over the slices as well
