@@ -453,22 +453,20 @@ __global__ __launch_bounds__(kThreads) void interleave_images_kernel(const bf16*
 }
 
 // dyf[ng][mt][run][jl][lane][i8] = dy[8 ng + i8][32 mt + lane % 32][run*bp + 2 jl + lane / 32] for pixels inside
-// the run and the image, zero otherwise.
+// the run and the image, zero otherwise.  A thread owns one (map, pixel) and gathers its 8 images; consecutive
+// lanes take consecutive pixels, so the reads are coalesced; the 16-byte writes of neighbouring maps fill
+// whole cache lines between them.
 __global__ __launch_bounds__(kThreads) void dy_fragments_kernel(const bf16* __restrict__ dy, uint4* __restrict__ dyf, int N,
-                                                                int M, int P, int MT, int runs, int bp, int steps,
+                                                                int M, int P, int MT, int runs, int bp, int uch,
                                                                 int64_t total) {
   const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   if (i >= total) return;
-  const int lane = (int)(i & 63);
-  int64_t t = i >> 6;
-  const int jl = (int)(t % steps);
-  t /= steps;
+  const int u = (int)(i % uch);
+  int64_t t = i / uch;
   const int run = (int)(t % runs);
   t /= runs;
-  const int mt = (int)(t % MT);
-  const int ng = (int)(t / MT);
-  const int m = mt * 32 + (lane & 31);
-  const int u = 2 * jl + (lane >> 5);
+  const int m = (int)(t % (MT * 32));
+  const int ng = (int)(t / (MT * 32));
   const int p = run * bp + u;
   const bool inside = m < M && u < bp && p < P;
   uint32_t v[8];
@@ -479,7 +477,9 @@ __global__ __launch_bounds__(kThreads) void dy_fragments_kernel(const bf16* __re
     const uint16_t b = dy[ok ? ((int64_t)img * M + m) * P + p : 0].bits;
     v[i8] = ok ? b : 0u;
   }
-  dyf[i] = make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
+  const int64_t frag = (((int64_t)ng * MT + m / 32) * runs + run) * (uch / 2) + u / 2;
+  dyf[frag * 64 + (u & 1) * 32 + (m & 31)] =
+      make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
 }
 
 struct FilterBf16Args {
@@ -757,9 +757,9 @@ vcnn_status launch_filter_grad_bf16(const FilterGradBf16Plan& p, const ConvGeom&
     if (vcnn_status e = check_launch("interleave_images")) return e;
   }
   {
-    const int64_t total = (int64_t)p.ngroups * p.mt_total * p.runs * (p.uch / 2) * 64;
+    const int64_t total = (int64_t)p.ngroups * p.mt_total * 32 * p.runs * p.uch;
     hipLaunchKernelGGL(dy_fragments_kernel, dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, st,
-                       (const bf16*)dy, dyf, g.n, (int)g.M, (int)g.P, p.mt_total, p.runs, p.bp, p.uch / 2, total);
+                       (const bf16*)dy, dyf, g.n, (int)g.M, (int)g.P, p.mt_total, p.runs, p.bp, p.uch, total);
     if (vcnn_status e = check_launch("dy_fragments")) return e;
   }
   FilterBf16Args a{};
