@@ -165,6 +165,48 @@ def relu_bwd(x, dy):
     return dx
 
 
+def _elementwise(name, *arrays):
+    arrays = [_f64(a) for a in arrays]
+    out = np.empty_like(arrays[0])
+    getattr(_load(), name)(*[_p(a) for a in arrays], _p(out), ctypes.c_int64(out.size))
+    return out
+
+
+def tanh_fwd(x):
+    return _elementwise("oracle_tanh_fwd", x)
+
+
+def tanh_bwd(y, dy):
+    """dx from the forward OUTPUT y = tanh(x)."""
+    return _elementwise("oracle_tanh_bwd", y, dy)
+
+
+def sigmoid_fwd(x):
+    return _elementwise("oracle_sigmoid_fwd", x)
+
+
+def sigmoid_bwd(y, dy):
+    """dx from the forward OUTPUT y = sigmoid(x)."""
+    return _elementwise("oracle_sigmoid_bwd", y, dy)
+
+
+def avgpool_fwd(x, win, stride):
+    x = _f64(x)
+    n, c, h, wd = x.shape
+    oh, ow = (h - win[0]) // stride[0] + 1, (wd - win[1]) // stride[1] + 1
+    y = np.empty((n, c, oh, ow), dtype=np.float64)
+    _load().oracle_avgpool_fwd(_p(x), _p(y), n, c, h, wd, win[0], win[1], stride[0], stride[1])
+    return y
+
+
+def avgpool_bwd(dy, hw, win, stride):
+    dy = _f64(dy)
+    n, c, oh, ow = dy.shape
+    dx = np.empty((n, c, hw[0], hw[1]), dtype=np.float64)
+    _load().oracle_avgpool_bwd(_p(dy), _p(dx), n, c, hw[0], hw[1], win[0], win[1], stride[0], stride[1])
+    return dx
+
+
 def fc_fwd(x, w, b=None, relu=False):
     x, w = _f64(x), _f64(w)
     bsz, i = x.shape

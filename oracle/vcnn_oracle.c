@@ -199,6 +199,54 @@ void oracle_relu_bwd(const double *x, const double *dy, double *dx, i64 count) {
   for (i64 i = 0; i < count; ++i) dx[i] = x[i] > 0.0 ? dy[i] : 0.0;
 }
 
+/* The other nonlinear functions Eq. 1 names for sigma: hyperbolic tangent and the logistic sigmoid.  The
+ * derivatives are written in terms of the forward OUTPUT y: tanh' = 1 - y^2, sigmoid' = y (1 - y). */
+void oracle_tanh_fwd(const double *x, double *y, i64 count) {
+  for (i64 i = 0; i < count; ++i) y[i] = tanh(x[i]);
+}
+void oracle_tanh_bwd(const double *y, const double *dy, double *dx, i64 count) {
+  for (i64 i = 0; i < count; ++i) dx[i] = dy[i] * (1.0 - y[i] * y[i]);
+}
+void oracle_sigmoid_fwd(const double *x, double *y, i64 count) {
+  for (i64 i = 0; i < count; ++i) y[i] = 1.0 / (1.0 + exp(-x[i]));
+}
+void oracle_sigmoid_bwd(const double *y, const double *dy, double *dx, i64 count) {
+  for (i64 i = 0; i < count; ++i) dx[i] = dy[i] * y[i] * (1.0 - y[i]);
+}
+
+/* phi_p with the average operation ("Vectorizing Pooling"): mean of each window; same window geometry as
+ * max pooling (no padding, output floor((H-win)/stride)+1). */
+void oracle_avgpool_fwd(const double *x, double *y, int N, int C, int H, int W, int wh, int ww, int sh, int sw) {
+  const i64 OH = (H - wh) / sh + 1, OW = (W - ww) / sw + 1;
+#pragma omp parallel for schedule(static)
+  for (i64 nc = 0; nc < (i64)N * C; ++nc) {
+    const double *xp = x + nc * H * W;
+    for (i64 oh = 0; oh < OH; ++oh)
+      for (i64 ow = 0; ow < OW; ++ow) {
+        double sum = 0.0;
+        for (i64 i = 0; i < wh; ++i)
+          for (i64 j = 0; j < ww; ++j) sum += xp[(oh * sh + i) * W + ow * sw + j];
+        y[(nc * OH + oh) * OW + ow] = sum / (double)(wh * ww);
+      }
+  }
+}
+
+/* Exact gradient of average pooling (the transpose of the linear map above): every position of a window
+ * receives the window's gradient divided by the window size; overlapping windows add up.  For windows
+ * that tile the plane (stride = window) this is the nearest-neighbour upscaling of dy the paper uses,
+ * scaled by 1/(wh*ww). */
+void oracle_avgpool_bwd(const double *dy, double *dx, int N, int C, int H, int W, int wh, int ww, int sh, int sw) {
+  const i64 OH = (H - wh) / sh + 1, OW = (W - ww) / sw + 1;
+  for (i64 i = 0; i < (i64)N * C * H * W; ++i) dx[i] = 0.0;
+  for (i64 nc = 0; nc < (i64)N * C; ++nc)
+    for (i64 oh = 0; oh < OH; ++oh)
+      for (i64 ow = 0; ow < OW; ++ow) {
+        const double g = dy[(nc * OH + oh) * OW + ow] / (double)(wh * ww);
+        for (i64 i = 0; i < wh; ++i)
+          for (i64 j = 0; j < ww; ++j) dx[nc * H * W + (oh * sh + i) * W + ow * sw + j] += g;
+      }
+}
+
 /* Fully connected layer as a dense product ("Vectorizing Fully Connected Layers"):
  * y[b,o] = sigma(bias[o] + sum_i x[b,i] w[o,i]). */
 void oracle_fc_fwd(const double *x, const double *w, const double *bias, double *y, int B, int I, int O,

@@ -433,3 +433,83 @@ def test_chain_gradient_finite_differences_and_descent():
         np.testing.assert_allclose(res["grads"][li][1], central_diff(loss, params[li][1]), rtol=2e-5, atol=1e-8)
     np.testing.assert_allclose(res["dacts"][0], central_diff(loss, inputs["x"]), rtol=2e-5, atol=1e-8)
     assert train_step(net, inputs, res["new_params"])["loss"] < res["loss"]
+
+
+# ---- the other sigma functions Eq. 1 names, and average pooling ("Vectorizing Pooling") --------------------
+def test_tanh_and_sigmoid_closed_forms_and_symmetries():
+    # exact rational values: tanh(ln 2) = (2 - 1/2)/(2 + 1/2) = 3/5, sigmoid(ln 3) = 3/4, sigmoid(0) = 1/2, tanh(0) = 0
+    np.testing.assert_allclose(O.tanh_fwd(np.array([np.log(2.0), 0.0, -np.log(2.0)])), [0.6, 0.0, -0.6], atol=1e-15)
+    np.testing.assert_allclose(O.sigmoid_fwd(np.array([np.log(3.0), 0.0, -np.log(3.0)])), [0.75, 0.5, 0.25], atol=1e-15)
+    x = np.random.default_rng(40).normal(size=257) * 3.0
+    np.testing.assert_allclose(O.tanh_fwd(-x), -O.tanh_fwd(x), atol=1e-15)           # odd
+    np.testing.assert_allclose(O.sigmoid_fwd(x) + O.sigmoid_fwd(-x), 1.0, atol=1e-15)  # sigma(x) + sigma(-x) = 1
+    np.testing.assert_allclose(O.tanh_fwd(x), 2.0 * O.sigmoid_fwd(2.0 * x) - 1.0, atol=1e-14)  # ties the two together
+    # library third opinion
+    from scipy.special import expit
+    np.testing.assert_allclose(O.sigmoid_fwd(x), expit(x), atol=1e-15)
+    np.testing.assert_allclose(O.tanh_fwd(x), torch.tanh(torch.from_numpy(x)).numpy(), atol=1e-15)
+    # saturation keeps its sign and stays inside the open interval's closure
+    assert O.tanh_fwd(np.array([40.0]))[0] == 1.0 and O.sigmoid_fwd(np.array([-800.0]))[0] == 0.0
+
+
+@pytest.mark.parametrize("name", ["tanh", "sigmoid"])
+def test_tanh_sigmoid_backward_is_the_derivative(name):
+    fwd, bwd = (O.tanh_fwd, O.tanh_bwd) if name == "tanh" else (O.sigmoid_fwd, O.sigmoid_bwd)
+    rng = np.random.default_rng(41)
+    x, dy = rng.normal(size=64) * 2.0, rng.normal(size=64)
+    got = bwd(fwd(x), dy)  # the backward pass is written in terms of the forward output
+    eps = 1e-6
+    fd = (fwd(x + eps) - fwd(x - eps)) / (2 * eps) * dy
+    np.testing.assert_allclose(got, fd, rtol=1e-8, atol=1e-10)
+    # autograd as an independent derivative
+    xt = torch.from_numpy(x).requires_grad_(True)
+    (torch.tanh(xt) if name == "tanh" else torch.sigmoid(xt)).backward(torch.from_numpy(dy))
+    np.testing.assert_allclose(got, xt.grad.numpy(), atol=1e-14)
+
+
+def _avgpool_brute(x, win, stride):
+    n, c, h, w = x.shape
+    oh, ow = (h - win[0]) // stride[0] + 1, (w - win[1]) // stride[1] + 1
+    y = np.zeros((n, c, oh, ow))
+    for a in range(n):
+        for b in range(c):
+            for i in range(oh):
+                for j in range(ow):
+                    vals = [x[a, b, i * stride[0] + p, j * stride[1] + q] for p in range(win[0]) for q in range(win[1])]
+                    y[a, b, i, j] = sum(vals) / len(vals)
+    return y
+
+
+@pytest.mark.parametrize("shape,win,stride", [((2, 3, 4, 4), (2, 2), (2, 2)), ((1, 2, 7, 9), (3, 3), (2, 2)),
+                                              ((2, 1, 5, 6), (2, 3), (1, 2)), ((1, 1, 3, 3), (3, 3), (3, 3))])
+def test_avgpool_brute_force_library_and_adjoint(shape, win, stride):
+    rng = np.random.default_rng(42)
+    x = rng.normal(size=shape)
+    y = O.avgpool_fwd(x, win, stride)
+    np.testing.assert_allclose(y, _avgpool_brute(x, win, stride), atol=1e-14)
+    ref = torch.nn.functional.avg_pool2d(torch.from_numpy(x), win, stride).numpy()  # floor mode, no padding
+    assert y.shape == ref.shape
+    np.testing.assert_allclose(y, ref, atol=1e-14)
+    # the gradient is the transpose of a linear map: <avgpool(x), dy> = <x, avgpool_bwd(dy)> exactly
+    dy = rng.normal(size=y.shape)
+    dx = O.avgpool_bwd(dy, shape[2:], win, stride)
+    assert abs(np.sum(y * dy) - np.sum(x * dx)) <= 1e-12 * max(1.0, abs(np.sum(y * dy)))
+    # and autograd agrees element by element (also on the rows / columns no window covers: zero)
+    xt = torch.from_numpy(x).requires_grad_(True)
+    torch.nn.functional.avg_pool2d(xt, win, stride).backward(torch.from_numpy(dy))
+    np.testing.assert_allclose(dx, xt.grad.numpy(), atol=1e-14)
+
+
+def test_avgpool_tiling_windows_reduce_to_block_means_and_upscaling():
+    """stride = window: the forward pass is a reshape-mean and the backward pass is the nearest-neighbour
+    upscaling of dy (the paper's back-propagation through pooling) divided by the window size."""
+    rng = np.random.default_rng(43)
+    x = rng.normal(size=(2, 3, 6, 8))
+    y = O.avgpool_fwd(x, (2, 2), (2, 2))
+    np.testing.assert_allclose(y, x.reshape(2, 3, 3, 2, 4, 2).mean(axis=(3, 5)), atol=1e-15)
+    dy = rng.normal(size=y.shape)
+    up = np.repeat(np.repeat(dy, 2, axis=2), 2, axis=3) / 4.0
+    np.testing.assert_allclose(O.avgpool_bwd(dy, (6, 8), (2, 2), (2, 2)), up, atol=1e-15)
+    # constant input -> the same constant; mass conservation of the gradient
+    np.testing.assert_allclose(O.avgpool_fwd(np.full((1, 1, 5, 5), 2.5), (3, 3), (2, 2)), 2.5, atol=1e-15)
+    assert abs(O.avgpool_bwd(dy, (6, 8), (2, 2), (2, 2)).sum() - dy.sum()) < 1e-12
