@@ -47,7 +47,8 @@ enum {
 };
 
 enum { VCNN_F32 = 0, VCNN_BF16 = 1 };
-enum { VCNN_ACT_NONE = 0, VCNN_ACT_RELU = 1 };
+enum { VCNN_ACT_NONE = 0, VCNN_ACT_RELU = 1, VCNN_ACT_TANH = 2, VCNN_ACT_SIGMOID = 3 };  /* sigma of Eq. 1 */
+enum { VCNN_POOL_MAX = 0, VCNN_POOL_AVG = 1 };  /* the operation of phi_p ("Vectorizing Pooling") */
 enum { VCNN_PASS_FWD = 0, VCNN_PASS_BWD_FILTER = 1, VCNN_PASS_BWD_DATA = 2 };
 
 /* How the convolution calls realise the unroll.  EXPLICIT materialises the patch matrix in the
@@ -60,13 +61,15 @@ typedef struct {
   int32_t k, r, s;                            /* output maps, kernel height, kernel width */
   int32_t pad_h, pad_w, stride_h, stride_w;   /* zero padding per side; stride (must be 1) */
   int32_t dtype;                              /* VCNN_F32 | VCNN_BF16 */
-  int32_t act;                                /* VCNN_ACT_* fused into the forward epilogue */
+  int32_t act;                                /* VCNN_ACT_* applied by the forward pass (ReLU inside the product's
+                                                 epilogue, tanh / sigmoid by an element-wise pass over y) */
 } vcnn_conv_desc;
 
 typedef struct {
   int32_t n, c, h, w;                         /* input */
   int32_t win_h, win_w, stride_h, stride_w;   /* window and stride; no padding */
   int32_t dtype;
+  int32_t mode;                               /* VCNN_POOL_MAX (0) | VCNN_POOL_AVG */
 } vcnn_pool_desc;
 
 const char* vcnn_status_string(vcnn_status st);
@@ -109,12 +112,16 @@ vcnn_status vcnn_conv_bwd_data(const vcnn_conv_desc* d, const void* w, const voi
 vcnn_status vcnn_pool_out_shape(const vcnn_pool_desc* d, int32_t* oh, int32_t* ow);
 vcnn_status vcnn_pool_fwd(const vcnn_pool_desc* d, const void* x, void* y, int32_t* argmax, void* stream);
 /* Routes each output gradient to the recorded position; overlapping windows that recorded the same
- * position are summed in ascending window order.  Every element of dx is written. */
+ * position are summed in ascending window order.  Every element of dx is written.
+ * Average pooling (mode VCNN_POOL_AVG): y = mean of the window, argmax is not used and may be NULL in both
+ * calls; the backward pass is the exact transpose, dx[i] = sum over the windows covering i of dy / (win_h*win_w)
+ * (for windows that tile the plane: the nearest-neighbour upscaling of dy the paper back-propagates with). */
 vcnn_status vcnn_pool_bwd(const vcnn_pool_desc* d, const void* dy, const int32_t* argmax, void* dx, void* stream);
 
-/* Element-wise sigma of Eq. 1.  fwd: y = max(x, 0).  bwd: dx = ref > 0 ? dy : 0, where ref may be
- * either the forward input or the forward output (they are positive at the same places).  y == x
- * and dx == dy (in place) are allowed. */
+/* Element-wise sigma of Eq. 1.  ReLU: fwd y = max(x, 0); bwd dx = ref > 0 ? dy : 0, where ref may be
+ * either the forward input or the forward output (they are positive at the same places).
+ * tanh / sigmoid: fwd y = tanh(x) / 1/(1+exp(-x)); bwd takes ref = the forward OUTPUT y:
+ * dx = dy (1 - y^2) / dy y (1 - y).  y == x and dx == dy (in place) are allowed. */
 vcnn_status vcnn_act_fwd(int32_t act, int32_t dtype, size_t count, const void* x, void* y, void* stream);
 vcnn_status vcnn_act_bwd(int32_t act, int32_t dtype, size_t count, const void* ref, const void* dy, void* dx,
                          void* stream);

@@ -39,7 +39,7 @@ static vcnn_status make_geom(const vcnn_conv_desc* d, ConvGeom* g) {
     return fail(VCNN_ERR_SHAPE, "conv: kernel %dx%d larger than padded input %dx%d", d->r, d->s, d->h + 2 * d->pad_h,
                 d->w + 2 * d->pad_w);
   if (d->dtype != VCNN_F32 && d->dtype != VCNN_BF16) return fail(VCNN_ERR_UNSUPPORTED, "conv: unknown dtype %d", d->dtype);
-  if (d->act != VCNN_ACT_NONE && d->act != VCNN_ACT_RELU)
+  if (d->act < VCNN_ACT_NONE || d->act > VCNN_ACT_SIGMOID)
     return fail(VCNN_ERR_UNSUPPORTED, "conv: unknown activation %d", d->act);
   if (d->stride_h != 1 || d->stride_w != 1)
     return fail(VCNN_ERR_UNSUPPORTED, "conv: only stride 1 is built (got %dx%d)", d->stride_h, d->stride_w);
@@ -259,11 +259,23 @@ vcnn_status vcnn_col2im(const vcnn_conv_desc* d, const float* col, void* dx, voi
   return launch_col2im(g, d->dtype, col, dx, (hipStream_t)stream);
 }
 
+static vcnn_status conv_fwd_linear(const vcnn_conv_desc* d, const ConvGeom& g, const void* x, const void* w,
+                                   const float* bias, void* y, void* workspace, size_t workspace_bytes, void* stream);
+
 vcnn_status vcnn_conv_fwd(const vcnn_conv_desc* d, const void* x, const void* w, const float* bias, void* y,
                           void* workspace, size_t workspace_bytes, void* stream) {
   ConvGeom g;
   if (vcnn_status s = make_geom(d, &g)) return s;
   if (!x || !w || !y) return fail(VCNN_ERR_NULL, "conv_fwd: NULL tensor");
+  if (vcnn_status s = conv_fwd_linear(d, g, x, w, bias, y, workspace, workspace_bytes, stream)) return s;
+  // ReLU is applied inside the product's epilogue; the smooth sigma functions by one element-wise pass over y
+  if (d->act == VCNN_ACT_TANH || d->act == VCNN_ACT_SIGMOID)
+    return launch_smooth_act(d->act, d->dtype, (size_t)(g.M * g.N), y, nullptr, y, (hipStream_t)stream);
+  return VCNN_OK;
+}
+
+static vcnn_status conv_fwd_linear(const vcnn_conv_desc* d, const ConvGeom& g, const void* x, const void* w,
+                                   const float* bias, void* y, void* workspace, size_t workspace_bytes, void* stream) {
   const Plan plan = make_plan(g, VCNN_PASS_FWD, d->dtype);
   if (vcnn_status s = check_ws(workspace, workspace_bytes, plan.workspace_bytes, "conv_fwd")) return s;
   hipStream_t st = (hipStream_t)stream;
@@ -379,6 +391,7 @@ static vcnn_status check_pool(const vcnn_pool_desc* d, int* oh, int* ow) {
     return fail(VCNN_ERR_SHAPE, "pool: window %dx%d larger than input %dx%d", d->win_h, d->win_w, d->h, d->w);
   if ((int64_t)d->h * d->w > 0x7fffffffLL) return fail(VCNN_ERR_UNSUPPORTED, "pool: plane too large for int32 indices");
   if (vcnn_status s = check_dtype(d->dtype, "pool")) return s;
+  if (d->mode != VCNN_POOL_MAX && d->mode != VCNN_POOL_AVG) return fail(VCNN_ERR_UNSUPPORTED, "pool: unknown mode %d", d->mode);
   *oh = (d->h - d->win_h) / d->stride_h + 1;
   *ow = (d->w - d->win_w) / d->stride_w + 1;
   return VCNN_OK;
@@ -395,31 +408,37 @@ vcnn_status vcnn_pool_out_shape(const vcnn_pool_desc* d, int32_t* oh, int32_t* o
 vcnn_status vcnn_pool_fwd(const vcnn_pool_desc* d, const void* x, void* y, int32_t* argmax, void* stream) {
   int oh, ow;
   if (vcnn_status s = check_pool(d, &oh, &ow)) return s;
-  if (!x || !y || !argmax) return fail(VCNN_ERR_NULL, "pool_fwd: NULL tensor");
+  if (!x || !y || (!argmax && d->mode == VCNN_POOL_MAX)) return fail(VCNN_ERR_NULL, "pool_fwd: NULL tensor");
+  if (d->mode == VCNN_POOL_AVG) return launch_avgpool(*d, oh, ow, x, y, false, (hipStream_t)stream);
   return launch_pool_fwd(*d, oh, ow, x, y, argmax, (hipStream_t)stream);
 }
 
 vcnn_status vcnn_pool_bwd(const vcnn_pool_desc* d, const void* dy, const int32_t* argmax, void* dx, void* stream) {
   int oh, ow;
   if (vcnn_status s = check_pool(d, &oh, &ow)) return s;
-  if (!dy || !dx || !argmax) return fail(VCNN_ERR_NULL, "pool_bwd: NULL tensor");
+  if (!dy || !dx || (!argmax && d->mode == VCNN_POOL_MAX)) return fail(VCNN_ERR_NULL, "pool_bwd: NULL tensor");
+  if (d->mode == VCNN_POOL_AVG) return launch_avgpool(*d, oh, ow, dy, dx, true, (hipStream_t)stream);
   return launch_pool_bwd(*d, oh, ow, dy, argmax, dx, (hipStream_t)stream);
 }
 
 vcnn_status vcnn_act_fwd(int32_t act, int32_t dtype, size_t count, const void* x, void* y, void* stream) {
-  if (act != VCNN_ACT_RELU) return fail(VCNN_ERR_UNSUPPORTED, "act_fwd: activation %d is not built", act);
+  if (act != VCNN_ACT_RELU && act != VCNN_ACT_TANH && act != VCNN_ACT_SIGMOID)
+    return fail(VCNN_ERR_UNSUPPORTED, "act_fwd: activation %d is not built", act);
   if (vcnn_status s = check_dtype(dtype, "act_fwd")) return s;
   if (count == 0) return VCNN_OK;
   if (!x || !y) return fail(VCNN_ERR_NULL, "act_fwd: NULL tensor");
+  if (act != VCNN_ACT_RELU) return launch_smooth_act(act, dtype, count, x, nullptr, y, (hipStream_t)stream);
   return launch_relu_fwd(dtype, count, x, y, (hipStream_t)stream);
 }
 
 vcnn_status vcnn_act_bwd(int32_t act, int32_t dtype, size_t count, const void* ref, const void* dy, void* dx,
                          void* stream) {
-  if (act != VCNN_ACT_RELU) return fail(VCNN_ERR_UNSUPPORTED, "act_bwd: activation %d is not built", act);
+  if (act != VCNN_ACT_RELU && act != VCNN_ACT_TANH && act != VCNN_ACT_SIGMOID)
+    return fail(VCNN_ERR_UNSUPPORTED, "act_bwd: activation %d is not built", act);
   if (vcnn_status s = check_dtype(dtype, "act_bwd")) return s;
   if (count == 0) return VCNN_OK;
   if (!ref || !dy || !dx) return fail(VCNN_ERR_NULL, "act_bwd: NULL tensor");
+  if (act != VCNN_ACT_RELU) return launch_smooth_act(act, dtype, count, ref, dy, dx, (hipStream_t)stream);
   return launch_relu_bwd(dtype, count, ref, dy, dx, (hipStream_t)stream);
 }
 
@@ -432,7 +451,7 @@ static vcnn_status check_fc(int32_t batch, int32_t in_f, int32_t out_f) {
 vcnn_status vcnn_fc_fwd(int32_t dtype, int32_t batch, int32_t in_f, int32_t out_f, int32_t act, const void* x,
                         const void* w, const float* bias, void* y, void* stream) {
   if (vcnn_status s = check_fc(batch, in_f, out_f)) return s;
-  if (act != VCNN_ACT_NONE && act != VCNN_ACT_RELU) return fail(VCNN_ERR_UNSUPPORTED, "fc_fwd: unknown activation %d", act);
+  if (act < VCNN_ACT_NONE || act > VCNN_ACT_SIGMOID) return fail(VCNN_ERR_UNSUPPORTED, "fc_fwd: unknown activation %d", act);
   if (vcnn_status s = check_dtype(dtype, "fc_fwd")) return s;
   if (!x || !w || !y) return fail(VCNN_ERR_NULL, "fc_fwd: NULL tensor");
   // C(i = o, j = b) = sum_k W[o][k] * X[b][k], stored at y[b*O + o]
@@ -444,7 +463,10 @@ vcnn_status vcnn_fc_fwd(int32_t dtype, int32_t batch, int32_t in_f, int32_t out_
   a.b_sk = 1, a.b_sj = in_f, a.b_P = 0;
   a.c_si = 1, a.c_sj = out_f, a.c_P = 0;
   a.relu = act == VCNN_ACT_RELU;
-  return launch_gemm_f32(a, (hipStream_t)stream);
+  if (vcnn_status s = launch_gemm_f32(a, (hipStream_t)stream)) return s;
+  if (act == VCNN_ACT_TANH || act == VCNN_ACT_SIGMOID)
+    return launch_smooth_act(act, dtype, (size_t)batch * out_f, y, nullptr, y, (hipStream_t)stream);
+  return VCNN_OK;
 }
 
 vcnn_status vcnn_fc_bwd(int32_t dtype, int32_t batch, int32_t in_f, int32_t out_f, const void* x, const void* w,

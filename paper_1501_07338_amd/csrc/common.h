@@ -176,6 +176,10 @@ size_t bias_grad_partial_bytes(const ConvGeom& g);
 vcnn_status launch_bias_grad(const ConvGeom& g, int dtype, const void* dy, float* db, float* partial, hipStream_t st);
 vcnn_status launch_relu_fwd(int dtype, size_t count, const void* x, void* y, hipStream_t st);
 vcnn_status launch_relu_bwd(int dtype, size_t count, const void* ref, const void* dy, void* dx, hipStream_t st);
+// tanh / sigmoid: dy == nullptr -> forward from a = x; else backward from a = forward output
+vcnn_status launch_smooth_act(int act, int dtype, size_t count, const void* a, const void* dy, void* out, hipStream_t st);
+vcnn_status launch_avgpool(const vcnn_pool_desc& d, int oh, int ow, const void* src, void* dst, bool backward,
+                           hipStream_t st);
 vcnn_status launch_pool_fwd(const vcnn_pool_desc& d, int oh, int ow, const void* x, void* y, int32_t* argmax,
                             hipStream_t st);
 vcnn_status launch_pool_bwd(const vcnn_pool_desc& d, int oh, int ow, const void* dy, const int32_t* argmax, void* dx,

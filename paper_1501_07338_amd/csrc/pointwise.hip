@@ -74,6 +74,112 @@ vcnn_status launch_relu_bwd(int dtype, size_t count, const void* ref, const void
   return dtype == VCNN_BF16 ? relu_bwd_typed<bf16>(count, ref, dy, dx, st) : relu_bwd_typed<float>(count, ref, dy, dx, st);
 }
 
+// ---- tanh / sigmoid -------------------------------------------------------------------------------
+// The other sigma functions Eq. 1 names.  Forward from x; backward from the forward OUTPUT y
+// (tanh' = 1 - y^2, sigmoid' = y (1 - y)).  One element per thread; in place allowed.
+template <int ACT>
+__device__ __forceinline__ float smooth_fwd(float x) {
+  // tanhf / the logistic function in fp32; both saturate cleanly for large |x|
+  return ACT == VCNN_ACT_TANH ? tanhf(x) : 1.f / (1.f + __expf(-x));
+}
+template <int ACT>
+__device__ __forceinline__ float smooth_bwd(float y, float g) {
+  return ACT == VCNN_ACT_TANH ? g * (1.f - y * y) : g * y * (1.f - y);
+}
+
+template <int ACT, typename T>
+__global__ __launch_bounds__(kThreads) void smooth_fwd_kernel(size_t count, const T* x, T* y) {
+  const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i < count) st(y + i, smooth_fwd<ACT>(ld(x + i)));
+}
+
+template <int ACT, typename T>
+__global__ __launch_bounds__(kThreads) void smooth_bwd_kernel(size_t count, const T* y, const T* dy, T* dx) {
+  const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i < count) st(dx + i, smooth_bwd<ACT>(ld(y + i), ld(dy + i)));
+}
+
+template <int ACT, typename T>
+static vcnn_status smooth_typed(size_t count, const void* a, const void* dy, void* out, hipStream_t st) {
+  unsigned blocks;
+  if (vcnn_status s = grid_for(count, &blocks)) return s;
+  if (dy)
+    hipLaunchKernelGGL((smooth_bwd_kernel<ACT, T>), dim3(blocks), dim3(kThreads), 0, st, count, (const T*)a, (const T*)dy,
+                       (T*)out);
+  else
+    hipLaunchKernelGGL((smooth_fwd_kernel<ACT, T>), dim3(blocks), dim3(kThreads), 0, st, count, (const T*)a, (T*)out);
+  return check_launch("act");
+}
+
+// act = VCNN_ACT_TANH | VCNN_ACT_SIGMOID; dy == nullptr: forward (a = x), else backward (a = forward output)
+vcnn_status launch_smooth_act(int act, int dtype, size_t count, const void* a, const void* dy, void* out, hipStream_t st) {
+  if (act == VCNN_ACT_TANH)
+    return dtype == VCNN_BF16 ? smooth_typed<VCNN_ACT_TANH, bf16>(count, a, dy, out, st)
+                              : smooth_typed<VCNN_ACT_TANH, float>(count, a, dy, out, st);
+  return dtype == VCNN_BF16 ? smooth_typed<VCNN_ACT_SIGMOID, bf16>(count, a, dy, out, st)
+                            : smooth_typed<VCNN_ACT_SIGMOID, float>(count, a, dy, out, st);
+}
+
+// ---- average pooling ------------------------------------------------------------------------------
+// phi_p with the average operation.  Forward: one thread per output element, window summed in row-major
+// order.  Backward: exact transpose in gather form - one thread per input element adds dy / (window size)
+// of every window that covers it, in ascending window order (for windows that tile the plane this is the
+// paper's nearest-neighbour upscaling).  Plane (n, c) on blockIdx.y / z.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void avgpool_fwd_kernel(vcnn_pool_desc d, int oh_n, int ow_n,
+                                                               const T* __restrict__ x, T* __restrict__ y) {
+  const int o = blockIdx.x * kThreads + threadIdx.x;
+  const int64_t nc = (int64_t)blockIdx.z * gridDim.y + blockIdx.y;
+  if (o >= oh_n * ow_n || nc >= (int64_t)d.n * d.c) return;
+  const int oh = o / ow_n, ow = o - oh * ow_n;
+  const T* xp = x + nc * d.h * d.w + (int64_t)(oh * d.stride_h) * d.w + ow * d.stride_w;
+  float sum = 0.f;
+  for (int i = 0; i < d.win_h; ++i)
+    for (int j = 0; j < d.win_w; ++j) sum += ld(xp + i * d.w + j);
+  st(y + nc * oh_n * ow_n + o, sum / (float)(d.win_h * d.win_w));
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void avgpool_bwd_kernel(vcnn_pool_desc d, int oh_n, int ow_n,
+                                                               const T* __restrict__ dy, T* __restrict__ dx) {
+  const int pos = blockIdx.x * kThreads + threadIdx.x;
+  const int64_t nc = (int64_t)blockIdx.z * gridDim.y + blockIdx.y;
+  if (pos >= d.h * d.w || nc >= (int64_t)d.n * d.c) return;
+  const int hi = pos / d.w, wi = pos - hi * d.w;
+  int oh_lo = hi - d.win_h + 1;
+  oh_lo = oh_lo > 0 ? (oh_lo + d.stride_h - 1) / d.stride_h : 0;
+  const int oh_hi = min(oh_n - 1, hi / d.stride_h);
+  int ow_lo = wi - d.win_w + 1;
+  ow_lo = ow_lo > 0 ? (ow_lo + d.stride_w - 1) / d.stride_w : 0;
+  const int ow_hi = min(ow_n - 1, wi / d.stride_w);
+  const T* dp = dy + nc * oh_n * ow_n;
+  float acc = 0.f;
+  for (int oh = oh_lo; oh <= oh_hi; ++oh)
+    for (int ow = ow_lo; ow <= ow_hi; ++ow) acc += ld(dp + oh * ow_n + ow);
+  st(dx + nc * d.h * d.w + pos, acc / (float)(d.win_h * d.win_w));
+}
+
+template <typename T>
+static void avgpool_typed(const vcnn_pool_desc& d, int oh, int ow, const void* src, void* dst, bool backward,
+                          hipStream_t st) {
+  const int64_t planes = (int64_t)d.n * d.c;
+  const unsigned gy = (unsigned)std::min<int64_t>(planes, 32768);
+  const int64_t per_plane = backward ? (int64_t)d.h * d.w : (int64_t)oh * ow;
+  const dim3 grid((unsigned)ceil_div(per_plane, kThreads), gy, (unsigned)ceil_div(planes, gy)), block(kThreads);
+  if (backward)
+    hipLaunchKernelGGL(avgpool_bwd_kernel<T>, grid, block, 0, st, d, oh, ow, (const T*)src, (T*)dst);
+  else
+    hipLaunchKernelGGL(avgpool_fwd_kernel<T>, grid, block, 0, st, d, oh, ow, (const T*)src, (T*)dst);
+}
+
+vcnn_status launch_avgpool(const vcnn_pool_desc& d, int oh, int ow, const void* src, void* dst, bool backward,
+                           hipStream_t st) {
+  if ((int64_t)d.n * d.c > 32768LL * 65535) return fail(VCNN_ERR_UNSUPPORTED, "pool: too many planes for one launch");
+  if (d.dtype == VCNN_BF16) avgpool_typed<bf16>(d, oh, ow, src, dst, backward, st);
+  else avgpool_typed<float>(d, oh, ow, src, dst, backward, st);
+  return check_launch(backward ? "avgpool_bwd" : "avgpool_fwd");
+}
+
 // ---- max pooling --------------------------------------------------------------------------------
 // blockIdx.y = (n, c) plane, one thread per output element of the plane (ow fastest), 32-bit index
 // arithmetic.  WIN / STRIDE are compile-time for the common square cases (2/2, 3/2), 0 = run-time

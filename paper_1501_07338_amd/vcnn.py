@@ -15,7 +15,8 @@ LIB_PATH = Path(__file__).resolve().parent / "libvcnn.so"
 
 OK, ERR_NULL, ERR_SHAPE, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_HIP = 0, -1, -2, -3, -4, -5
 F32, BF16 = 0, 1
-ACT_NONE, ACT_RELU = 0, 1
+ACT_NONE, ACT_RELU, ACT_TANH, ACT_SIGMOID = 0, 1, 2, 3
+POOL_MAX, POOL_AVG = 0, 1
 PASS_FWD, PASS_BWD_FILTER, PASS_BWD_DATA = 0, 1, 2
 ALGO_AUTO, ALGO_EXPLICIT, ALGO_IMPLICIT = 0, 1, 2
 
@@ -26,7 +27,7 @@ class ConvDesc(Structure):
 
 
 class PoolDesc(Structure):
-    _fields_ = [(n, c_int32) for n in ("n", "c", "h", "w", "win_h", "win_w", "stride_h", "stride_w", "dtype")]
+    _fields_ = [(n, c_int32) for n in ("n", "c", "h", "w", "win_h", "win_w", "stride_h", "stride_w", "dtype", "mode")]
 
 
 class VcnnError(RuntimeError):
@@ -105,8 +106,8 @@ def conv_desc(n, c, h, w, k, r, s, pad_h=0, pad_w=0, stride_h=1, stride_w=1, dty
     return ConvDesc(n, c, h, w, k, r, s, pad_h, pad_w, stride_h, stride_w, dtype, act)
 
 
-def pool_desc(n, c, h, w, win_h, win_w, stride_h, stride_w, dtype=F32) -> PoolDesc:
-    return PoolDesc(n, c, h, w, win_h, win_w, stride_h, stride_w, dtype)
+def pool_desc(n, c, h, w, win_h, win_w, stride_h, stride_w, dtype=F32, mode=POOL_MAX) -> PoolDesc:
+    return PoolDesc(n, c, h, w, win_h, win_w, stride_h, stride_w, dtype, mode)
 
 
 def version() -> int:

@@ -76,6 +76,6 @@ def test_null_and_workspace_errors_need_no_gpu():
     assert lib.vcnn_fc_fwd(vcnn.F32, 0, 4, 4, 0, None, None, None, None, None) == vcnn.ERR_SHAPE
     assert lib.vcnn_fc_fwd(vcnn.F32, 2, 4, 4, 0, None, None, None, None, None) == vcnn.ERR_NULL
     assert lib.vcnn_softmax_loss(4, 10, None, None, None, None, None) == vcnn.ERR_NULL
-    assert lib.vcnn_act_fwd(3, vcnn.F32, 4, None, None, None) == vcnn.ERR_UNSUPPORTED
+    assert lib.vcnn_act_fwd(7, vcnn.F32, 4, None, None, None) == vcnn.ERR_UNSUPPORTED
     assert lib.vcnn_set_conv_algo(99) == vcnn.ERR_UNSUPPORTED
     assert lib.vcnn_set_conv_algo(vcnn.ALGO_AUTO) == vcnn.OK

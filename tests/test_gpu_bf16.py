@@ -250,3 +250,26 @@ def test_bf16_training_step(name, batch):
             assert l2_rel(moved, -net.lr * to_np(ts.grads[li][0]).astype(np.float64)) <= 1e-2
             # and the bf16 copy the next step reads is the rounding of the new master weights
             np.testing.assert_array_equal(f32_of(ts.params16[li]), wl.bf16_round(to_np(ts.params[li][0])))
+
+
+def test_smooth_sigma_and_avgpool_bf16():
+    """tanh / sigmoid and average pooling on bf16 tensors: fp32 arithmetic on the bf16-rounded inputs, result
+    rounded once."""
+    x, xd = b16(wl.random_tensor(2500, (3 * 4 * 15 * 15,), scale=2.0))
+    dy, dyd = b16(wl.random_tensor(2501, x.shape))
+    for act, fwd, bwd in ((vcnn.ACT_TANH, O.tanh_fwd, O.tanh_bwd), (vcnn.ACT_SIGMOID, O.sigmoid_fwd, O.sigmoid_bwd)):
+        y = torch.empty(x.shape, dtype=torch.bfloat16, device=DEV)
+        vcnn.act_fwd(act, vcnn.BF16, x.size, xd, y)
+        assert_close(f32_of(y), fwd(x), TOL_BF16, "bf16 sigma fwd")
+        dx = torch.empty(x.shape, dtype=torch.bfloat16, device=DEV)
+        vcnn.act_bwd(act, vcnn.BF16, x.size, y, dyd, dx)
+        assert_close(f32_of(dx), bwd(f32_of(y), dy), TOL_BF16, "bf16 sigma bwd")
+    xp, xpd = b16(wl.random_tensor(2502, (3, 4, 15, 15)))
+    d = vcnn.pool_desc(3, 4, 15, 15, 3, 3, 2, 2, dtype=vcnn.BF16, mode=vcnn.POOL_AVG)
+    yp = torch.empty((3, 4, 7, 7), dtype=torch.bfloat16, device=DEV)
+    vcnn.pool_fwd(d, xpd, yp, None)
+    assert_close(f32_of(yp), O.avgpool_fwd(xp, (3, 3), (2, 2)), TOL_BF16, "bf16 avgpool y")
+    g, gd = b16(wl.random_tensor(2503, (3, 4, 7, 7)))
+    dxp = torch.empty((3, 4, 15, 15), dtype=torch.bfloat16, device=DEV)
+    vcnn.pool_bwd(d, gd, None, dxp)
+    assert_close(f32_of(dxp), O.avgpool_bwd(g, (15, 15), (3, 3), (2, 2)), TOL_BF16, "bf16 avgpool dx")

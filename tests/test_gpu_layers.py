@@ -226,6 +226,60 @@ def test_fc(b, i, o, relu):
     assert torch.equal(dw, dw2) and torch.equal(db, db2) and torch.equal(dx, dx2)
 
 
+@pytest.mark.parametrize("act,fwd,bwd", [(vcnn.ACT_TANH, O.tanh_fwd, O.tanh_bwd), (vcnn.ACT_SIGMOID, O.sigmoid_fwd, O.sigmoid_bwd)])
+@pytest.mark.parametrize("count", [1, 255, 4099])
+def test_tanh_sigmoid_fwd_bwd(act, fwd, bwd, count):
+    x = random_tensor(1700, (count,), scale=3.0)
+    x[0] = 30.0  # saturation
+    dy = random_tensor(1701, (count,))
+    y = torch.full((count,), float("nan"), device=DEV)
+    vcnn.act_fwd(act, vcnn.F32, count, to_dev(x), y)
+    assert_close(to_np(y), fwd(x), 1e-6, "sigma fwd")
+    # backward from the forward output: feed both sides the same fp32 output
+    yh = to_np(y)
+    dx = torch.full((count,), float("nan"), device=DEV)
+    vcnn.act_bwd(act, vcnn.F32, count, y, to_dev(dy), dx)
+    assert_close(to_np(dx), bwd(yh, dy), 1e-6, "sigma bwd")
+    # in place
+    z = to_dev(x)
+    vcnn.act_fwd(act, vcnn.F32, count, z, z)
+    assert torch.equal(z, y)
+
+
+@pytest.mark.parametrize("act,fwd", [(vcnn.ACT_TANH, O.tanh_fwd), (vcnn.ACT_SIGMOID, O.sigmoid_fwd)])
+def test_conv_and_fc_forward_with_smooth_sigma(act, fwd):
+    n, c, h, w, k, r, s, ph, pw = 3, 5, 9, 11, 7, 3, 3, 1, 1
+    x, wt, b = random_tensor(1710, (n, c, h, w)), random_tensor(1711, (k, c, r, s), scale=0.3), random_tensor(1712, (k,))
+    d = vcnn.conv_desc(n, c, h, w, k, r, s, ph, pw, act=act)
+    y = torch.full((n, k, h, w), float("nan"), device=DEV)
+    vcnn.conv_fwd(d, to_dev(x), to_dev(wt), to_dev(b), y, ws_for(d, vcnn.PASS_FWD))
+    assert_close(to_np(y), fwd(O.conv_fwd(x, wt, b, pad=(ph, pw))), TOL_F32, "conv + sigma")
+    bsz, i, o = 9, 33, 12
+    xf, wf, bf = random_tensor(1713, (bsz, i)), random_tensor(1714, (o, i), scale=0.3), random_tensor(1715, (o,))
+    yf = torch.full((bsz, o), float("nan"), device=DEV)
+    vcnn.fc_fwd(vcnn.F32, bsz, i, o, act, to_dev(xf), to_dev(wf), to_dev(bf), yf)
+    assert_close(to_np(yf), fwd(O.fc_fwd(xf, wf, bf)), TOL_F32, "fc + sigma")
+
+
+AVG_SHAPES = [(2, 3, 4, 4, 2, 2), (3, 5, 24, 24, 2, 2), (2, 7, 32, 32, 3, 2), (3, 4, 15, 15, 3, 2), (1, 3, 9, 11, 2, 1),
+              (2, 2, 5, 6, 5, 1), (1, 1, 3, 3, 3, 3)]
+
+
+@pytest.mark.parametrize("shape", AVG_SHAPES)
+def test_avgpool_fwd_bwd(shape):
+    n, c, h, w, win, st = shape
+    x = random_tensor(1720, (n, c, h, w))
+    d = vcnn.pool_desc(n, c, h, w, win, win, st, st, mode=vcnn.POOL_AVG)
+    oh, ow = vcnn.pool_out_shape(d)
+    y = torch.full((n, c, oh, ow), float("nan"), device=DEV)
+    vcnn.pool_fwd(d, to_dev(x), y, None)  # no argmax record for the average
+    assert_close(to_np(y), O.avgpool_fwd(x, (win, win), (st, st)), 1e-6, "avgpool y")
+    dy = random_tensor(1721, (n, c, oh, ow))
+    dx = torch.full((n, c, h, w), float("nan"), device=DEV)
+    vcnn.pool_bwd(d, to_dev(dy), None, dx)
+    assert_close(to_np(dx), O.avgpool_bwd(dy, (h, w), (win, win), (st, st)), 1e-6, "avgpool dx")
+
+
 @pytest.mark.parametrize("b,c", [(128, 10), (1, 10), (300, 7), (5, 1)])
 def test_softmax_loss(b, c):
     z = random_tensor(1100, (b, c), scale=3.0)
