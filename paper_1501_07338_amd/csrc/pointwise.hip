@@ -546,16 +546,22 @@ template <typename T>
 __global__ __launch_bounds__(kL2Threads) void l2_loss_kernel(size_t count, float scale, const T* __restrict__ y,
                                                              const float* __restrict__ t, float* __restrict__ loss) {
   __shared__ float sm[kL2Threads];
-  float a0 = 0.f, a1 = 0.f;
+  // one block (the cost has no workspace to hold partial sums): eight independent loads in flight per thread,
+  // each with its own accumulator, combined in a fixed order
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   size_t i = threadIdx.x;
-  for (; i + kL2Threads < count; i += 2 * kL2Threads) {  // two independent loads in flight
-    const float d0 = ld(y + i) - t[i], d1 = ld(y + i + kL2Threads) - t[i + kL2Threads];
-    a0 += d0 * d0, a1 += d1 * d1;
+  for (; i + 7 * (size_t)kL2Threads < count; i += 8 * (size_t)kL2Threads) {
+    float d[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) d[u] = ld(y + i + u * (size_t)kL2Threads) - t[i + u * (size_t)kL2Threads];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc[u] += d[u] * d[u];
   }
   for (; i < count; i += kL2Threads) {
     const float d0 = ld(y + i) - t[i];
-    a0 += d0 * d0;
+    acc[0] += d0 * d0;
   }
+  const float a0 = ((acc[0] + acc[1]) + (acc[2] + acc[3])), a1 = ((acc[4] + acc[5]) + (acc[6] + acc[7]));
   const float total = block_sum<kL2Threads>(a0 + a1, sm);
   if (threadIdx.x == 0) *loss = total * scale;
 }
