@@ -19,7 +19,6 @@
 namespace vcnn {
 
 static constexpr int kThreads = 256;
-static constexpr int BK = 32;
 
 struct HaloArgs {
   const void* x;      // [n][c][h][w]       element type T (float or bf16)
@@ -379,7 +378,7 @@ struct HaloFilterArgs {
   int nr, wp;
 };
 
-template <int BM, int BNK, int WM, int WN, bool VEC, typename T>
+template <int BM, int BNK, int WM, int WN, int BK, bool VEC, typename T>
 __global__ __launch_bounds__(kThreads) void conv_halo_filter_kernel(HaloFilterArgs a) {
   static_assert((BM / WM) * (BNK / WN) * 64 == kThreads, "four waves per block");
   using LA = LdsTile<BM, BK, true>;
@@ -505,15 +504,20 @@ __global__ __launch_bounds__(kThreads) void conv_halo_filter_kernel(HaloFilterAr
   }
 }
 
+// Slab depth (pixels of dY staged per barrier): a narrow row tile does few MFMAs per pixel, so it takes deeper
+// slabs - the next slab's loads then have a few microseconds of MFMA work to hide behind.
+static int filter_bk(int64_t m) { return m <= 32 ? 128 : (m <= 64 ? 64 : 32); }
+
 bool conv_halo_filter_plan(const ConvGeom& g, HaloFilterPlan* p) {
   const int rs = g.r * g.s;
+  const int BK = filter_bk(g.M);
   if ((int64_t)g.c * g.h * g.w > 0x7fffffffLL) return false;  // 32-bit offsets inside a sample
   p->bm = g.M <= 32 ? 32 : (g.M <= 64 ? 64 : 128);
   p->bnk = g.M <= 64 ? 256 : 128;
   p->wp = g.w + 2 * g.pw;
   // channels a run of bnk consecutive kernel-matrix columns can touch
   p->ccs = (int)std::min<int64_t>(g.c, (p->bnk + rs - 2) / rs + 1);
-  const size_t a_bytes = 2 * (size_t)LdsTile<128, BK, true>::PITCH * p->bm * sizeof(float);
+  const size_t a_bytes = 2 * (size_t)(BK + 4) * p->bm * sizeof(float);
   // longest pixel run (multiple of BK, at most 1024 and at most one sample) whose halo fits the budget
   int best = 0;
   for (int bp = BK; bp <= 1024; bp += BK) {
@@ -544,10 +548,10 @@ bool conv_halo_filter_plan(const ConvGeom& g, HaloFilterPlan* p) {
   return tiles <= 0x7fffffffLL && p->splits <= 65535;
 }
 
-template <int BM, int BNK, int WM, int WN, bool VEC, typename T>
+template <int BM, int BNK, int WM, int WN, int BK, bool VEC, typename T>
 static void launch_halo_filter_one(const HaloFilterArgs& a, const HaloFilterPlan& p, int tiles, hipStream_t st) {
   const dim3 grid((unsigned)tiles, (unsigned)p.splits), block(kThreads);
-  auto kernel = conv_halo_filter_kernel<BM, BNK, WM, WN, VEC, T>;
+  auto kernel = conv_halo_filter_kernel<BM, BNK, WM, WN, BK, VEC, T>;
   static bool opted = false;
   if (!opted) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -557,15 +561,15 @@ static void launch_halo_filter_one(const HaloFilterArgs& a, const HaloFilterPlan
   hipLaunchKernelGGL(kernel, grid, block, p.lds_bytes, st, a);
 }
 
-template <int BM, int BNK, int WM, int WN>
+template <int BM, int BNK, int WM, int WN, int BK>
 static void launch_halo_filter(const HaloFilterArgs& a, const HaloFilterPlan& p, bool vec, int dtype, int tiles,
                                hipStream_t st) {
   if (dtype == VCNN_BF16) {
-    if (vec) launch_halo_filter_one<BM, BNK, WM, WN, true, bf16>(a, p, tiles, st);
-    else launch_halo_filter_one<BM, BNK, WM, WN, false, bf16>(a, p, tiles, st);
+    if (vec) launch_halo_filter_one<BM, BNK, WM, WN, BK, true, bf16>(a, p, tiles, st);
+    else launch_halo_filter_one<BM, BNK, WM, WN, BK, false, bf16>(a, p, tiles, st);
   } else {
-    if (vec) launch_halo_filter_one<BM, BNK, WM, WN, true, float>(a, p, tiles, st);
-    else launch_halo_filter_one<BM, BNK, WM, WN, false, float>(a, p, tiles, st);
+    if (vec) launch_halo_filter_one<BM, BNK, WM, WN, BK, true, float>(a, p, tiles, st);
+    else launch_halo_filter_one<BM, BNK, WM, WN, BK, false, float>(a, p, tiles, st);
   }
 }
 
@@ -581,11 +585,11 @@ vcnn_status launch_conv_halo_filter(const HaloFilterPlan& p, int dtype, const Co
   const int tiles = a.tiles_m * (int)ceil_div(g.K, p.bnk);
   const bool vec = p.vec && (dtype == VCNN_BF16 ? group_aligned<bf16>(dy) : group_aligned<float>(dy));
   if (p.bm == 32)
-    launch_halo_filter<32, 256, 32, 64>(a, p, vec, dtype, tiles, st);
+    launch_halo_filter<32, 256, 32, 64, 128>(a, p, vec, dtype, tiles, st);
   else if (p.bm == 64)
-    launch_halo_filter<64, 256, 64, 64>(a, p, vec, dtype, tiles, st);
+    launch_halo_filter<64, 256, 64, 64, 64>(a, p, vec, dtype, tiles, st);
   else
-    launch_halo_filter<128, 128, 64, 64>(a, p, vec, dtype, tiles, st);
+    launch_halo_filter<128, 128, 64, 64, 32>(a, p, vec, dtype, tiles, st);
   if (vcnn_status s = check_launch("conv_halo_filter")) return s;
   if (p.splits == 1) return VCNN_OK;
   return launch_sum_slices(partial, nullptr, dw, VCNN_F32, g.M * g.K, p.splits, 1, 1, 0, st);
