@@ -118,7 +118,7 @@ vcnn_status launch_filter_grad_few_cols(const FewColsPlan& p, int dtype, const C
                                         float* dw, float* dbias, float* partial, hipStream_t st);
 vcnn_status launch_flip_transpose(int dtype, const void* w, void* w2, int M, int C, int RS, hipStream_t st);
 
-// ---- bf16_conv.hip / bf16_mfma.hip -----------------------------------------------------------------
+// ---- bf16_conv.hip (implicit bf16 kernels) / bf16_mfma.hip (explicit-route bf16 product) ------------
 struct HaloBf16Plan {
   int waves_m;       // waves of a block along the output maps (the other 4 / waves_m split the contraction)
   int tm;            // 32-row tiles per wave (1 for at most 32 maps, else 2)

@@ -8,7 +8,6 @@
 // All of them run v_mfma_f32_32x32x2_f32 on LDS-staged, double-buffered slabs (see mma_core.h): the
 // global loads of slab t+1 are issued before the MFMAs of slab t and written to the other LDS buffer
 // afterwards, so a block synchronises once per slab.
-#include <cstdlib>
 
 #include "common.h"
 #include "elem.h"

@@ -1,5 +1,5 @@
-// Bandwidth-bound operators around the convolution: sigma (ReLU), max pooling with argmax record
-// (phi_p of Eq. 3 with the max operation), bias gradient, cost functions and the SGD update.
+// Bandwidth-bound operators around the convolution: sigma (ReLU, tanh, sigmoid), pooling (phi_p of Eq. 3 with the
+// max operation and its argmax record, or the average), bias gradient, cost functions and the SGD update.
 // Kernels are templates on the element type of the activation tensors (float or bf16); sums,
 // comparisons and costs are computed on float values.
 #include <algorithm>
