@@ -34,6 +34,20 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 static constexpr int kThreads = 256;
 static constexpr size_t kLdsBudget = 78 * 1024;  // two blocks per CU
 
+// Direct global -> LDS load of 16 bytes per lane: lane i of the wave deposits its bytes at lds_base + 16 i
+// (lds_base wave-uniform, held in M0).  Issued through inline assembly so that the compiler's wait-count
+// pass does not see it: seeing it, it drains every outstanding load before each later LDS read, and the
+// fragment prefetch loses its lead.  The kernels wait for these loads themselves (vmcnt(0) before the barrier
+// that publishes a tile); the hidden loads only make the compiler's own vmcnt waits more conservative,
+// never too short, because loads complete in order.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"  // M0 is reserved by the compiler; naming it as clobbered is still right
+__device__ __forceinline__ void load_to_lds16(const uint4* src, uint4* lds_base) {
+  const unsigned base = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)lds_base);  // low half = LDS offset
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(base), "v"(src) : "memory", "m0");
+}
+#pragma clang diagnostic pop
+
 __device__ __forceinline__ f32x16 mfma_bf16(uint4 a, uint4 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
@@ -209,7 +223,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
       const int ih = oh_first - a.ph + ry, iw = rx - a.pw;
       const bool ok = b0 + lane < npos && g0 + gl < a.cg && ih >= 0 && ih < a.h && iw >= 0 && iw < a.w;
       const uint4* src = ok ? x8n + ((g0 + gl) * a.h + ih) * a.w + iw : a.zero;
-      __builtin_amdgcn_global_load_lds(src, dst + b0, 16, 0, 0);
+      load_to_lds16(src, dst + b0);
       rx += dr;
       ry += dq;
       if (rx >= a.wp) rx -= a.wp, ++ry;
@@ -576,7 +590,7 @@ __global__ __launch_bounds__(kThreads, 2) void filter_grad_bf16_kernel(FilterBf1
       const int ih = ih0 + ry, iw = rx - a.pw, ch = c_first + cl;
       const bool ok = b0 + lane < npos && ch < a.c && ih >= 0 && ih < a.h && iw >= 0 && iw < a.w;
       const uint4* src = ok ? xg + (ch * a.h + ih) * a.w + iw : a.zero;
-      __builtin_amdgcn_global_load_lds(src, dst + b0, 16, 0, 0);
+      load_to_lds16(src, dst + b0);
       rx += dr;
       ry += dq;
       if (rx >= a.wp) rx -= a.wp, ++ry;
