@@ -13,15 +13,19 @@ static constexpr int kThreads = 256;
 static constexpr int kVec = 4;  // consecutive columns per thread
 
 // ---- phi_c --------------------------------------------------------------------------------------------
-// A block owns one input plane (n, c) and a band of output rows whose pixels form a run of up to
-// kThreads*kVec consecutive patch-matrix columns.  It stages the input rows of the band (plus halo,
-// zero padded) in LDS with coalesced loads and then, tap by tap, writes the R*S patch-matrix rows of
-// channel c for its column run: every store instruction of a wave covers 1 KB of one row.
+// A block owns one channel c and a chunk of up to kThreads*kVec consecutive patch-matrix columns.  Chunks
+// are cut at multiples of 32 columns of the whole matrix row - not at image or output-row boundaries - so
+// every 128-byte line of the patch matrix is written by exactly one block: lines shared between blocks
+// arrive at HBM as partial writes, which cost far more than their size.  A chunk therefore may start in
+// the middle of an output row and run across several images.  For every image it touches ("part") the
+// block stages the input rows under its pixels (plus halo, zero padded) in LDS with coalesced loads and
+// then, tap by tap, writes the R*S patch-matrix rows of channel c for its columns: every store
+// instruction of a wave covers 1 KB of one row.
 // ALIGNED: the patch-matrix row pitch and base allow 16-byte stores.
 template <bool ALIGNED, typename T>
 __global__ __launch_bounds__(kThreads) void im2col_f32_kernel(ConvGeom g, const T* __restrict__ x,
-                                                              T* __restrict__ col, int bh, int bands, int wp,
-                                                              int rsplit) {
+                                                              T* __restrict__ col, int chunk_cols, int chunks,
+                                                              int part_rows, int wp, int rsplit) {
   extern __shared__ float tile[];
   int b = blockIdx.x;
   // kernel rows [r_begin, r_end) of this block: tall kernels are split over blocks for parallelism
@@ -29,107 +33,116 @@ __global__ __launch_bounds__(kThreads) void im2col_f32_kernel(ConvGeom g, const 
   b /= rsplit;
   const int rper = (g.r + rsplit - 1) / rsplit;
   const int r_begin = rpart * rper, r_end = min(g.r, r_begin + rper);
-  const int band = b % bands;
-  b /= bands;
-  const int c = b % g.c;
-  const int n = b / g.c;
-  const int oh0 = band * bh;
-  const int bh_eff = min(bh, g.oh - oh0);
-  const int rows = bh_eff + (r_end - r_begin) - 1;  // tile row 0 = input row oh0 - ph + r_begin
+  const int chunk = b % chunks;
+  const int c = b / chunks;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
-  const T* plane = x + ((int64_t)n * g.c + c) * g.h * g.w;
-  for (int ry = wave; ry < rows; ry += kThreads / 64) {
-    const int ih = oh0 - g.ph + r_begin + ry;
+  // columns [j0, j1) = pixels from (n_first, oy_first, .) to (n_last, oy_last, .)
+  const int P = (int)g.P;
+  const int j0 = chunk * chunk_cols, j1 = (int)min((int64_t)j0 + chunk_cols, g.N);
+  const int n_first = j0 / P, n_last = (j1 - 1) / P;
+  const int oy_first = (j0 - n_first * P) / g.ow, oy_last = (j1 - 1 - n_last * P) / g.ow;
+  const int nparts = n_last - n_first + 1;
+
+  // Part i (image n_first+i) owns tile rows [i*part_rows, (i+1)*part_rows); its tile row 0 is input row
+  // lo - ph + r_begin, lo = its first output row in the chunk.
+  for (int idx = wave; idx < nparts * part_rows; idx += kThreads / 64) {
+    const int i = idx / part_rows, ry = idx - i * part_rows;
+    const int lo = i == 0 ? oy_first : 0, hi = i == nparts - 1 ? oy_last : g.oh - 1;
+    if (ry >= hi - lo + r_end - r_begin) continue;
+    const int ih = lo - g.ph + r_begin + ry;
     const bool row_ok = ih >= 0 && ih < g.h;
-    const T* src = plane + (int64_t)(row_ok ? ih : 0) * g.w;
+    const T* src = x + (((int64_t)(n_first + i) * g.c + c) * g.h + (row_ok ? ih : 0)) * g.w;
     for (int rx = lane; rx < wp; rx += 64) {
       const int iw = rx - g.pw;
       const bool ok = row_ok && iw >= 0 && iw < g.w;
       const float v = ld(src + (ok ? iw : 0));
-      tile[ry * wp + rx] = ok ? v : 0.f;
+      tile[idx * wp + rx] = ok ? v : 0.f;
     }
   }
   __syncthreads();
 
-  // This thread's runs of four consecutive columns.  Runs are aligned to multiples of four in the
-  // absolute column index (shift sh), so that all but a band's first and last run are 16-byte stores.
-  const int npix = bh_eff * g.ow;
-  const int64_t jband = (int64_t)n * g.P + (int64_t)oh0 * g.ow;
-  const int sh = ALIGNED ? (int)(jband & 3) : 0;
-  for (int q0 = threadIdx.x * kVec - sh; q0 < npix; q0 += kThreads * kVec) {
-    int base[kVec];
+  // This thread's run of four consecutive columns (it may straddle an output row or an image).
+  const int q0 = j0 + threadIdx.x * kVec;
+  if (q0 >= j1) return;
+  int base[kVec];
 #pragma unroll
-    for (int e = 0; e < kVec; ++e) {
-      const int q = min(max(q0 + e, 0), npix - 1);
-      const int oy = q / g.ow;
-      base[e] = oy * wp + (q - oy * g.ow);
-    }
-    T* dst = col + ((int64_t)(c * g.r + r_begin) * g.s) * g.N + jband + q0;
-    if (ALIGNED && q0 >= 0 && q0 + kVec <= npix) {
-      for (int r = 0; r < r_end - r_begin; ++r) {
-        const float* t0 = tile + r * wp;
+  for (int e = 0; e < kVec; ++e) {
+    const int j = min(q0 + e, j1 - 1);
+    const int n = j / P, p = j - n * P;
+    const int oy = p / g.ow, ox = p - oy * g.ow;
+    const int i = n - n_first;
+    base[e] = (i * part_rows + oy - (i == 0 ? oy_first : 0)) * wp + ox;
+  }
+  T* dst = col + ((int64_t)(c * g.r + r_begin) * g.s) * g.N + q0;
+  if (ALIGNED && q0 + kVec <= j1) {
+    for (int r = 0; r < r_end - r_begin; ++r) {
+      const float* t0 = tile + r * wp;
 #pragma unroll 4
-        for (int s = 0; s < g.s; ++s) {
-          st4(dst, make_float4(t0[base[0] + s], t0[base[1] + s], t0[base[2] + s], t0[base[3] + s]));
-          dst += g.N;
-        }
+      for (int s = 0; s < g.s; ++s) {
+        st4(dst, make_float4(t0[base[0] + s], t0[base[1] + s], t0[base[2] + s], t0[base[3] + s]));
+        dst += g.N;
       }
-    } else {
-      for (int r = 0; r < r_end - r_begin; ++r)
-        for (int s = 0; s < g.s; ++s) {
-          const int off = r * wp + s;
-          if (q0 >= 0) st(dst, tile[base[0] + off]);
-          if (q0 + 1 >= 0 && q0 + 1 < npix) st(dst + 1, tile[base[1] + off]);
-          if (q0 + 2 >= 0 && q0 + 2 < npix) st(dst + 2, tile[base[2] + off]);
-          if (q0 + 3 < npix) st(dst + 3, tile[base[3] + off]);
-          dst += g.N;
-        }
     }
+  } else {
+    for (int r = 0; r < r_end - r_begin; ++r)
+      for (int s = 0; s < g.s; ++s) {
+        const int off = r * wp + s;
+        st(dst, tile[base[0] + off]);
+        if (q0 + 1 < j1) st(dst + 1, tile[base[1] + off]);
+        if (q0 + 2 < j1) st(dst + 2, tile[base[2] + off]);
+        if (q0 + 3 < j1) st(dst + 3, tile[base[3] + off]);
+        dst += g.N;
+      }
   }
 }
 
 vcnn_status launch_im2col(const ConvGeom& g, int dtype, const void* x, void* col, hipStream_t st) {
   const int wp = g.w + 2 * g.pw;
-  // Rows per band: at most kThreads*kVec pixels.  Kernel rows per block: all of them if the staged
-  // tile (band + halo) fits 60 KB of LDS, else as many as fit; tall kernels are also split to get
-  // enough blocks in flight.
+  if (g.N > 0x7fffffffLL) return fail(VCNN_ERR_UNSUPPORTED, "im2col: more than 2^31-1 patch-matrix columns");
+  if (g.N == 0 || g.K == 0) return VCNN_OK;
+  // Chunk: as many columns as one pass of the block covers, fewer (in steps of 32) while the staged tile
+  // - per touched image the rows under the chunk plus the halo of the block's kernel rows - exceeds
+  // 60 KB of LDS.  Tall kernels are split over blocks (fewer halo rows, and enough blocks in flight).
   const size_t row_bytes = (size_t)wp * sizeof(float);
-  const int max_rows = (int)(60 * 1024 / row_bytes);  // tile rows that fit
-  if (max_rows < 1) return fail(VCNN_ERR_UNSUPPORTED, "im2col: one padded input row (%d floats) exceeds the LDS band", wp);
-  int bh = (kThreads * kVec) / g.ow;
-  if (bh < 1) bh = 1;  // rows wider than one pass of the block are covered by the thread loop
-  if (bh > g.oh) bh = g.oh;
-  if (bh > max_rows) bh = max_rows;
-  const int rper_max = max_rows - bh + 1;  // >= 1
-  const int bands = (int)ceil_div(g.oh, bh);
-  int64_t rsplit = ceil_div(8192, (int64_t)g.n * g.c * bands);
+  const int64_t max_rows = (int64_t)(60 * 1024 / row_bytes);  // tile rows that fit
+  auto parts_of = [&](int cols) { return (int)((cols - 1) / g.P + 2); };           // images a chunk can touch
+  auto rows_of = [&](int cols) { return (int)std::min<int64_t>(g.oh, (cols - 1) / g.ow + 2); };  // output rows of a part
+  int chunk_cols = kThreads * kVec;
+  while (chunk_cols > 32 && (int64_t)parts_of(chunk_cols) * rows_of(chunk_cols) > max_rows) chunk_cols -= 32;
+  if ((int64_t)parts_of(chunk_cols) * rows_of(chunk_cols) > max_rows)
+    return fail(VCNN_ERR_UNSUPPORTED, "im2col: padded input rows of %d floats do not fit the LDS tile", wp);
+  const int parts = parts_of(chunk_cols), out_rows = rows_of(chunk_cols);
+  const int rper_max = (int)(max_rows / parts) - out_rows + 1;  // >= 1
+  const int chunks = (int)ceil_div(g.N, chunk_cols);
+  int64_t rsplit = ceil_div(8192, (int64_t)g.c * chunks);
   if (rsplit < ceil_div(g.r, rper_max)) rsplit = ceil_div(g.r, rper_max);
   if (rsplit > g.r) rsplit = g.r;
   if (rsplit < 1) rsplit = 1;
   const int rper = (int)ceil_div(g.r, rsplit);
   rsplit = ceil_div(g.r, rper);  // no empty parts
-  const int64_t blocks = (int64_t)g.n * g.c * bands * rsplit;
+  const int64_t blocks = (int64_t)g.c * chunks * rsplit;
   if (blocks > 0x7fffffffLL) return fail(VCNN_ERR_UNSUPPORTED, "im2col: too many blocks for one launch");
-  const size_t lds = (size_t)(bh + rper - 1) * row_bytes;
+  const int part_rows = out_rows + rper - 1;
+  const size_t lds = (size_t)parts * part_rows * row_bytes;
   // 16-byte stores need the row pitch to be a multiple of four elements and an aligned matrix
   const dim3 grid((unsigned)blocks), block(kThreads);
   if (dtype == VCNN_BF16) {
     const bool aligned = g.N % kVec == 0 && group_aligned<bf16>(col);
     if (aligned)
-      hipLaunchKernelGGL((im2col_f32_kernel<true, bf16>), grid, block, lds, st, g, (const bf16*)x, (bf16*)col, bh, bands,
-                         wp, (int)rsplit);
+      hipLaunchKernelGGL((im2col_f32_kernel<true, bf16>), grid, block, lds, st, g, (const bf16*)x, (bf16*)col,
+                         chunk_cols, chunks, part_rows, wp, (int)rsplit);
     else
-      hipLaunchKernelGGL((im2col_f32_kernel<false, bf16>), grid, block, lds, st, g, (const bf16*)x, (bf16*)col, bh, bands,
-                         wp, (int)rsplit);
+      hipLaunchKernelGGL((im2col_f32_kernel<false, bf16>), grid, block, lds, st, g, (const bf16*)x, (bf16*)col,
+                         chunk_cols, chunks, part_rows, wp, (int)rsplit);
   } else {
     const bool aligned = g.N % kVec == 0 && group_aligned<float>(col);
     if (aligned)
-      hipLaunchKernelGGL((im2col_f32_kernel<true, float>), grid, block, lds, st, g, (const float*)x, (float*)col, bh,
-                         bands, wp, (int)rsplit);
+      hipLaunchKernelGGL((im2col_f32_kernel<true, float>), grid, block, lds, st, g, (const float*)x, (float*)col,
+                         chunk_cols, chunks, part_rows, wp, (int)rsplit);
     else
-      hipLaunchKernelGGL((im2col_f32_kernel<false, float>), grid, block, lds, st, g, (const float*)x, (float*)col, bh,
-                         bands, wp, (int)rsplit);
+      hipLaunchKernelGGL((im2col_f32_kernel<false, float>), grid, block, lds, st, g, (const float*)x, (float*)col,
+                         chunk_cols, chunks, part_rows, wp, (int)rsplit);
   }
   return check_launch("im2col");
 }
