@@ -181,21 +181,24 @@ vcnn_status launch_avgpool(const vcnn_pool_desc& d, int oh, int ow, const void* 
 }
 
 // ---- max pooling --------------------------------------------------------------------------------
-// blockIdx.y = (n, c) plane, one thread per output element of the plane (ow fastest), 32-bit index
-// arithmetic.  WIN / STRIDE are compile-time for the common square cases (2/2, 3/2), 0 = run-time
+// Forward: one thread per output element, indexed flat over the whole (n, c, oh, ow) tensor, so that a
+// block writes 1 KB-aligned runs of y and of the argmax record whatever the plane size (a block per
+// plane leaves the 128-byte lines at plane boundaries shared between blocks, and such partial lines are
+// expensive at HBM).  WIN / STRIDE are compile-time for the common square cases (2/2, 3/2), 0 = run-time
 // values from the descriptor.  Row-major scan with a strict '>' keeps the lowest flat index among
 // equal maxima.
 template <typename T, int WIN, int STRIDE>
-__global__ __launch_bounds__(kThreads) void pool_fwd_kernel(vcnn_pool_desc d, int oh_n, int ow_n,
+__global__ __launch_bounds__(kThreads) void pool_fwd_kernel(vcnn_pool_desc d, int oh_n, int ow_n, int64_t total,
                                                             const T* __restrict__ x, T* __restrict__ y,
                                                             int32_t* __restrict__ argmax) {
-  const int o = blockIdx.x * kThreads + threadIdx.x;
-  if (o >= oh_n * ow_n) return;
+  const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= total) return;
   const int win_h = WIN ? WIN : d.win_h, win_w = WIN ? WIN : d.win_w;
   const int sh = STRIDE ? STRIDE : d.stride_h, sw = STRIDE ? STRIDE : d.stride_w;
+  const int out_plane = oh_n * ow_n;
+  const int64_t nc = idx / out_plane;  // plane (n, c)
+  const int o = (int)(idx - nc * out_plane);
   const int oh = o / ow_n, ow = o - oh * ow_n;
-  const int64_t nc = (int64_t)blockIdx.z * gridDim.y + blockIdx.y;  // plane (n, c)
-  if (nc >= (int64_t)d.n * d.c) return;
   const T* xp = x + nc * d.h * d.w;
   const int h0 = oh * sh, w0 = ow * sw;
   float best = ld(xp + h0 * d.w + w0);
@@ -209,7 +212,6 @@ __global__ __launch_bounds__(kThreads) void pool_fwd_kernel(vcnn_pool_desc d, in
         bi = pos;
       }
     }
-  const int64_t idx = nc * oh_n * ow_n + o;
   st(y + idx, best);
   argmax[idx] = bi;
 }
@@ -262,18 +264,20 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_kernel(vcnn_pool_desc d, in
 }
 
 template <typename T>
-static void pool_fwd_typed(const vcnn_pool_desc& d, int oh, int ow, const void* x, void* y, int32_t* argmax,
-                           hipStream_t st) {
-  const int64_t planes = (int64_t)d.n * d.c;
-  const unsigned gy = (unsigned)std::min<int64_t>(planes, 32768);
-  const dim3 grid((unsigned)ceil_div((int64_t)oh * ow, kThreads), gy, (unsigned)ceil_div(planes, gy)), block(kThreads);
+static vcnn_status pool_fwd_typed(const vcnn_pool_desc& d, int oh, int ow, const void* x, void* y, int32_t* argmax,
+                                  hipStream_t st) {
+  const int64_t total = (int64_t)d.n * d.c * oh * ow;
+  const int64_t blocks = ceil_div(total, kThreads);
+  if (blocks > 0x7fffffffLL) return fail(VCNN_ERR_UNSUPPORTED, "pool_fwd: too many outputs for one launch");
+  const dim3 grid((unsigned)blocks), block(kThreads);
   const bool square = d.win_h == d.win_w && d.stride_h == d.stride_w;
   if (square && d.win_h == 2 && d.stride_h == 2)
-    hipLaunchKernelGGL((pool_fwd_kernel<T, 2, 2>), grid, block, 0, st, d, oh, ow, (const T*)x, (T*)y, argmax);
+    hipLaunchKernelGGL((pool_fwd_kernel<T, 2, 2>), grid, block, 0, st, d, oh, ow, total, (const T*)x, (T*)y, argmax);
   else if (square && d.win_h == 3 && d.stride_h == 2)
-    hipLaunchKernelGGL((pool_fwd_kernel<T, 3, 2>), grid, block, 0, st, d, oh, ow, (const T*)x, (T*)y, argmax);
+    hipLaunchKernelGGL((pool_fwd_kernel<T, 3, 2>), grid, block, 0, st, d, oh, ow, total, (const T*)x, (T*)y, argmax);
   else
-    hipLaunchKernelGGL((pool_fwd_kernel<T, 0, 0>), grid, block, 0, st, d, oh, ow, (const T*)x, (T*)y, argmax);
+    hipLaunchKernelGGL((pool_fwd_kernel<T, 0, 0>), grid, block, 0, st, d, oh, ow, total, (const T*)x, (T*)y, argmax);
+  return VCNN_OK;
 }
 
 // The same gather for small planes, staged: a block takes `pb` consecutive planes, copies their dy and
@@ -387,9 +391,9 @@ static void pool_bwd_typed(const vcnn_pool_desc& d, int oh, int ow, const void* 
 
 vcnn_status launch_pool_fwd(const vcnn_pool_desc& d, int oh, int ow, const void* x, void* y, int32_t* argmax,
                             hipStream_t st) {
-  if ((int64_t)d.n * d.c > 32768LL * 65535) return fail(VCNN_ERR_UNSUPPORTED, "pool: too many planes for one launch");
-  if (d.dtype == VCNN_BF16) pool_fwd_typed<bf16>(d, oh, ow, x, y, argmax, st);
-  else pool_fwd_typed<float>(d, oh, ow, x, y, argmax, st);
+  const vcnn_status rc = d.dtype == VCNN_BF16 ? pool_fwd_typed<bf16>(d, oh, ow, x, y, argmax, st)
+                                               : pool_fwd_typed<float>(d, oh, ow, x, y, argmax, st);
+  if (rc != VCNN_OK) return rc;
   return check_launch("pool_fwd");
 }
 
