@@ -216,14 +216,15 @@ static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 // -------------------------------------------------------------------------------------------------
 // Small products (the fully connected layers at the experiments' batch sizes: a few MFLOP).  Their cost
 // is latency, not arithmetic: few tiles, and in the slab kernel above a chain of load -> barrier ->
-// MFMA rounds as long as the contraction.  Here a block owns one 32 x 32 tile of C and its four waves
-// split the contraction between them; every wave reads its operand fragments straight from global
-// memory, several groups of 8 contraction steps in flight at once (no LDS staging, no barrier in the
-// loop), and the four partial tiles are added in wave order through LDS.
+// MFMA rounds as long as the contraction.  Here a block owns one 32 x 32 tile of C and its waves (4 to
+// 16, more for longer contractions) split the contraction between them; every wave reads its operand
+// fragments straight from global memory, several groups of 8 contraction steps in flight at once (no LDS
+// staging, no barrier in the loop), and the partial tiles are added in wave order through LDS.
 // -------------------------------------------------------------------------------------------------
 template <bool A_KC, bool B_KC, bool A_VEC, bool B_VEC, typename TI, typename TO>
-__global__ __launch_bounds__(kThreads) void gemm_small_kernel(GemmArgs a, int tiles_m, int kper) {
-  __shared__ float red[3][16][64];
+__global__ __launch_bounds__(1024) void gemm_small_kernel(GemmArgs a, int tiles_m, int kper) {
+  extern __shared__ float red[];  // [waves - 1][16][64]
+  const int waves = blockDim.x >> 6;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
   const int i0 = (blockIdx.x % tiles_m) * 32, j0 = (blockIdx.x / tiles_m) * 32;
@@ -269,14 +270,13 @@ __global__ __launch_bounds__(kThreads) void gemm_small_kernel(GemmArgs a, int ti
 
   if (wave > 0) {
 #pragma unroll
-    for (int q = 0; q < 16; ++q) red[wave - 1][q][lane] = acc[q];
+    for (int q = 0; q < 16; ++q) red[((wave - 1) * 16 + q) * 64 + lane] = acc[q];
   }
   __syncthreads();
   if (wave > 0) return;
+  for (int w = 0; w < waves - 1; ++w)
 #pragma unroll
-  for (int w = 0; w < 3; ++w)
-#pragma unroll
-    for (int q = 0; q < 16; ++q) acc[q] += red[w][q][lane];
+    for (int q = 0; q < 16; ++q) acc[q] += red[(w * 16 + q) * 64 + lane];
   if (!j_ok) return;
   TO* C = static_cast<TO*>(a.C);
 #pragma unroll
@@ -295,15 +295,18 @@ template <bool A_KC, bool B_KC, bool A_VEC, bool B_VEC>
 static void launch_small_t(const GemmArgs& a, hipStream_t st) {
   const int tiles_m = (int)ceil_div(a.M, 32);
   const int64_t tiles = (int64_t)tiles_m * ceil_div(a.N, 32);
-  const int kper = (int)ceil_div(ceil_div(a.K, 4), 8) * 8;
-  const dim3 grid((unsigned)tiles), block(kThreads);
+  // one wave per 64 contraction indices, 4 to 16 of them: a wave then has its whole share in flight at once
+  const int waves = (int)std::min<int64_t>(16, std::max<int64_t>(4, ceil_div(a.K, 64)));
+  const int kper = (int)ceil_div(ceil_div(a.K, waves), 8) * 8;
+  const dim3 grid((unsigned)tiles), block(64 * waves);
+  const size_t lds = (size_t)(waves - 1) * 16 * 64 * sizeof(float);
   const bool in16 = a.in_dtype == VCNN_BF16, out16 = a.out_dtype == VCNN_BF16;
   if (in16 && out16)
-    hipLaunchKernelGGL((gemm_small_kernel<A_KC, B_KC, A_VEC, B_VEC, bf16, bf16>), grid, block, 0, st, a, tiles_m, kper);
+    hipLaunchKernelGGL((gemm_small_kernel<A_KC, B_KC, A_VEC, B_VEC, bf16, bf16>), grid, block, lds, st, a, tiles_m, kper);
   else if (in16)
-    hipLaunchKernelGGL((gemm_small_kernel<A_KC, B_KC, A_VEC, B_VEC, bf16, float>), grid, block, 0, st, a, tiles_m, kper);
+    hipLaunchKernelGGL((gemm_small_kernel<A_KC, B_KC, A_VEC, B_VEC, bf16, float>), grid, block, lds, st, a, tiles_m, kper);
   else
-    hipLaunchKernelGGL((gemm_small_kernel<A_KC, B_KC, A_VEC, B_VEC, float, float>), grid, block, 0, st, a, tiles_m, kper);
+    hipLaunchKernelGGL((gemm_small_kernel<A_KC, B_KC, A_VEC, B_VEC, float, float>), grid, block, lds, st, a, tiles_m, kper);
 }
 
 static void launch_small(const GemmArgs& a, bool a_kc, bool b_kc, bool av, bool bv, hipStream_t st) {
