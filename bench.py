@@ -110,7 +110,8 @@ def run_workload(name, steps, warmup, layer_iters=10):
         d = ts.descs[li]
         w, b = ts.weights(li), ts.params[li][1]
         dw, db = ts.grads[li]
-        a_in, a_out, dy = ts.acts[li], ts.acts[li + 1], ts.dacts[li + 1]
+        a_in, a_out = ts.acts[li], ts.acts[li + 1]
+        dy = ts.dpre.get(li, ts.dacts[li + 1])  # the gradient w.r.t. the pre-activation, as the step passes it
         flops = 2.0 * g["M"] * g["K"] * g["N"]
         passes = {
             "fwd": lambda: vcnn.conv_fwd(d, a_in, w, b, a_out, ts.workspace),

@@ -117,6 +117,13 @@ vcnn_status vcnn_pool_fwd(const vcnn_pool_desc* d, const void* x, void* y, int32
  * calls; the backward pass is the exact transpose, dx[i] = sum over the windows covering i of dy / (win_h*win_w)
  * (for windows that tile the plane: the nearest-neighbour upscaling of dy the paper back-propagates with). */
 vcnn_status vcnn_pool_bwd(const vcnn_pool_desc* d, const void* dy, const int32_t* argmax, void* dx, void* stream);
+/* vcnn_pool_bwd with the next step of the delta recursion folded into its store: the pooling input x is the
+ * forward OUTPUT of the activation act_below (sigma of Eq. 1, applied by the layer below), and
+ * dx = pool_bwd(dy) * sigma'(.) evaluated from x (ReLU: x > 0; tanh: 1 - x^2; sigmoid: x (1 - x)), i.e. the
+ * gradient w.r.t. that layer's pre-activation; the separate vcnn_act_bwd call is then not needed.  x has the
+ * shape and dtype of dx.  act_below == VCNN_ACT_NONE is vcnn_pool_bwd (x is not read). */
+vcnn_status vcnn_pool_bwd_act(const vcnn_pool_desc* d, int32_t act_below, const void* x, const void* dy,
+                              const int32_t* argmax, void* dx, void* stream);
 
 /* Element-wise sigma of Eq. 1.  ReLU: fwd y = max(x, 0); bwd dx = ref > 0 ? dy : 0, where ref may be
  * either the forward input or the forward output (they are positive at the same places).
@@ -136,6 +143,14 @@ vcnn_status vcnn_fc_fwd(int32_t dtype, int32_t batch, int32_t in_f, int32_t out_
  * pre-activation.  Needs no workspace. */
 vcnn_status vcnn_fc_bwd(int32_t dtype, int32_t batch, int32_t in_f, int32_t out_f, const void* x, const void* w,
                         const void* dy, float* dw, float* dbias, void* dx, void* stream);
+/* vcnn_fc_bwd with the derivative of the activation below folded into the input gradient's store (same
+ * convention as vcnn_pool_bwd_act): x, the layer's input, is the forward output of act_below and
+ * dx[b][i] = (sum_o dy[b][o]*w[o][i]) * sigma'(.) from x[b][i]; dw and dbias as in vcnn_fc_bwd.  x is then read for
+ * dx as well.  When dw and dx are both requested and the products are small (the layers of the experiments at
+ * their batch sizes), both - and dbias - come out of one launch.  act_below == VCNN_ACT_NONE is vcnn_fc_bwd. */
+vcnn_status vcnn_fc_bwd_act(int32_t dtype, int32_t batch, int32_t in_f, int32_t out_f, int32_t act_below,
+                            const void* x, const void* w, const void* dy, float* dw, float* dbias, void* dx,
+                            void* stream);
 
 /* Softmax + cross-entropy cost, mean over the batch: loss = (1/B) sum_b (logsumexp(z_b) - z_b[label_b]),
  * dlogits[b][j] = (softmax(z_b)[j] - [j == label_b]) / B.  loss is a device scalar; dlogits may be NULL.

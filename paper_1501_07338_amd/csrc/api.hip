@@ -418,7 +418,22 @@ vcnn_status vcnn_pool_bwd(const vcnn_pool_desc* d, const void* dy, const int32_t
   if (vcnn_status s = check_pool(d, &oh, &ow)) return s;
   if (!dy || !dx || (!argmax && d->mode == VCNN_POOL_MAX)) return fail(VCNN_ERR_NULL, "pool_bwd: NULL tensor");
   if (d->mode == VCNN_POOL_AVG) return launch_avgpool(*d, oh, ow, dy, dx, true, (hipStream_t)stream);
-  return launch_pool_bwd(*d, oh, ow, dy, argmax, dx, (hipStream_t)stream);
+  return launch_pool_bwd(*d, oh, ow, dy, argmax, dx, VCNN_ACT_NONE, nullptr, (hipStream_t)stream);
+}
+
+vcnn_status vcnn_pool_bwd_act(const vcnn_pool_desc* d, int32_t act_below, const void* x, const void* dy,
+                              const int32_t* argmax, void* dx, void* stream) {
+  if (act_below == VCNN_ACT_NONE) return vcnn_pool_bwd(d, dy, argmax, dx, stream);
+  if (act_below != VCNN_ACT_RELU && act_below != VCNN_ACT_TANH && act_below != VCNN_ACT_SIGMOID)
+    return fail(VCNN_ERR_UNSUPPORTED, "pool_bwd_act: activation %d is not built", act_below);
+  int oh, ow;
+  if (vcnn_status s = check_pool(d, &oh, &ow)) return s;
+  if (!x || !dy || !dx || (!argmax && d->mode == VCNN_POOL_MAX)) return fail(VCNN_ERR_NULL, "pool_bwd_act: NULL tensor");
+  if (d->mode == VCNN_POOL_AVG) {  // the transpose of the mean, then the derivative in place
+    if (vcnn_status s = launch_avgpool(*d, oh, ow, dy, dx, true, (hipStream_t)stream)) return s;
+    return vcnn_act_bwd(act_below, d->dtype, (size_t)d->n * d->c * d->h * d->w, x, dx, dx, stream);
+  }
+  return launch_pool_bwd(*d, oh, ow, dy, argmax, dx, act_below, x, (hipStream_t)stream);
 }
 
 vcnn_status vcnn_act_fwd(int32_t act, int32_t dtype, size_t count, const void* x, void* y, void* stream) {
@@ -469,35 +484,58 @@ vcnn_status vcnn_fc_fwd(int32_t dtype, int32_t batch, int32_t in_f, int32_t out_
   return VCNN_OK;
 }
 
-vcnn_status vcnn_fc_bwd(int32_t dtype, int32_t batch, int32_t in_f, int32_t out_f, const void* x, const void* w,
-                        const void* dy, float* dw, float* dbias, void* dx, void* stream) {
+static vcnn_status fc_bwd_impl(int32_t dtype, int32_t batch, int32_t in_f, int32_t out_f, int32_t act_below,
+                               const void* x, const void* w, const void* dy, float* dw, float* dbias, void* dx,
+                               void* stream) {
   if (vcnn_status s = check_fc(batch, in_f, out_f)) return s;
   if (vcnn_status s = check_dtype(dtype, "fc_bwd")) return s;
-  if (!dy || (dw && !x) || (dx && !w)) return fail(VCNN_ERR_NULL, "fc_bwd: NULL tensor");
+  if (act_below != VCNN_ACT_NONE && act_below != VCNN_ACT_RELU && act_below != VCNN_ACT_TANH &&
+      act_below != VCNN_ACT_SIGMOID)
+    return fail(VCNN_ERR_UNSUPPORTED, "fc_bwd: activation %d is not built", act_below);
+  if (!dy || ((dw || (dx && act_below)) && !x) || (dx && !w)) return fail(VCNN_ERR_NULL, "fc_bwd: NULL tensor");
   hipStream_t st = (hipStream_t)stream;
-  if (dw) {  // dW(i = o, j = i_) = sum_b dY[b][o] * X[b][i_]
-    GemmArgs a{};
-    a.A = dy, a.B = x, a.C = dw;
-    a.in_dtype = dtype, a.out_dtype = VCNN_F32;
-    a.M = out_f, a.N = in_f, a.K = batch;
-    a.a_si = 1, a.a_sk = out_f;
-    a.b_sk = in_f, a.b_sj = 1, a.b_P = 0;
-    a.c_si = in_f, a.c_sj = 1, a.c_P = 0;
-    if (vcnn_status s = launch_gemm_f32(a, st)) return s;
+  GemmArgs gw{}, gx{};
+  // dW(i = o, j = i_) = sum_b dY[b][o] * X[b][i_]
+  gw.A = dy, gw.B = x, gw.C = dw;
+  gw.in_dtype = dtype, gw.out_dtype = VCNN_F32;
+  gw.M = out_f, gw.N = in_f, gw.K = batch;
+  gw.a_si = 1, gw.a_sk = out_f;
+  gw.b_sk = in_f, gw.b_sj = 1, gw.b_P = 0;
+  gw.c_si = in_f, gw.c_sj = 1, gw.c_P = 0;
+  // dX(i = b, j = i_) = sum_o dY[b][o] * W[o][i_]
+  gx.A = dy, gx.B = w, gx.C = dx;
+  gx.in_dtype = dtype, gx.out_dtype = dtype;
+  gx.M = batch, gx.N = in_f, gx.K = out_f;
+  gx.a_si = out_f, gx.a_sk = 1;
+  gx.b_sk = in_f, gx.b_sj = 1, gx.b_P = 0;
+  gx.c_si = in_f, gx.c_sj = 1, gx.c_P = 0;
+  gx.dact = act_below, gx.dact_ref = act_below ? x : nullptr;
+  // the small-product kernel takes the bias gradient along as the weight gradient's column of ones
+  gw.row_sums = dbias;
+  if (dw && gemm_is_small(gw)) dbias = nullptr;
+  else gw.row_sums = nullptr;
+  if (dw && dx && gemm_is_small(gw) && gemm_is_small(gx)) {
+    if (vcnn_status s = launch_fc_bwd_small(gw, gx, st)) return s;
+    dw = nullptr, dx = nullptr;
   }
+  if (dw)
+    if (vcnn_status s = launch_gemm_f32(gw, st)) return s;
   if (dbias)
     if (vcnn_status s = launch_col_sum(dtype, batch, out_f, dy, dbias, st)) return s;
-  if (dx) {  // dX(i = b, j = i_) = sum_o dY[b][o] * W[o][i_]
-    GemmArgs a{};
-    a.A = dy, a.B = w, a.C = dx;
-    a.in_dtype = dtype, a.out_dtype = dtype;
-    a.M = batch, a.N = in_f, a.K = out_f;
-    a.a_si = out_f, a.a_sk = 1;
-    a.b_sk = in_f, a.b_sj = 1, a.b_P = 0;
-    a.c_si = in_f, a.c_sj = 1, a.c_P = 0;
-    if (vcnn_status s = launch_gemm_f32(a, st)) return s;
-  }
+  if (dx)
+    if (vcnn_status s = launch_gemm_f32(gx, st)) return s;
   return VCNN_OK;
+}
+
+vcnn_status vcnn_fc_bwd(int32_t dtype, int32_t batch, int32_t in_f, int32_t out_f, const void* x, const void* w,
+                        const void* dy, float* dw, float* dbias, void* dx, void* stream) {
+  return fc_bwd_impl(dtype, batch, in_f, out_f, VCNN_ACT_NONE, x, w, dy, dw, dbias, dx, stream);
+}
+
+vcnn_status vcnn_fc_bwd_act(int32_t dtype, int32_t batch, int32_t in_f, int32_t out_f, int32_t act_below,
+                            const void* x, const void* w, const void* dy, float* dw, float* dbias, void* dx,
+                            void* stream) {
+  return fc_bwd_impl(dtype, batch, in_f, out_f, act_below, x, w, dy, dw, dbias, dx, stream);
 }
 
 vcnn_status vcnn_softmax_loss(int32_t batch, int32_t classes, const float* logits, const int32_t* labels, float* loss,

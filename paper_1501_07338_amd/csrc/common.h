@@ -48,8 +48,18 @@ struct GemmArgs {
   int64_t c_si, c_sj, c_simg;
   int c_P;
   int relu;
+  // optional: C(i,j) is multiplied by sigma'(.) of activation dact, evaluated from dact_ref (elements of
+  // out_dtype, indexed like C: the forward output of that activation)
+  int dact;
+  const void* dact_ref;
+  // optional, small products only: the row sums of A, sum_k A(i,k), written to row_sums[i]
+  float* row_sums;
 };
 vcnn_status launch_gemm_f32(const GemmArgs& a, hipStream_t st);
+// true if launch_gemm_f32 takes the small-product kernel (one 32 x 32 tile per block, contraction split over waves)
+bool gemm_is_small(const GemmArgs& a);
+// The weight-gradient (gw) and input-gradient (gx) products of a fully connected layer in one launch; both small.
+vcnn_status launch_fc_bwd_small(const GemmArgs& gw, const GemmArgs& gx, hipStream_t st);
 
 // Filter-gradient product: dW[m][k] = sum_j dY(m,j) * col[k][j] with dY in [N][M][P] layout, contraction
 // split over `splits` column ranges whose partial sums are combined in a fixed order.
@@ -182,7 +192,9 @@ vcnn_status launch_avgpool(const vcnn_pool_desc& d, int oh, int ow, const void* 
                            hipStream_t st);
 vcnn_status launch_pool_fwd(const vcnn_pool_desc& d, int oh, int ow, const void* x, void* y, int32_t* argmax,
                             hipStream_t st);
+// act / ref: optional activation derivative folded into the store (ref = the pooling input, indexed like dx)
 vcnn_status launch_pool_bwd(const vcnn_pool_desc& d, int oh, int ow, const void* dy, const int32_t* argmax, void* dx,
+                            int act, const void* ref,
                             hipStream_t st);
 vcnn_status launch_col_sum(int dtype, int rows, int cols, const void* a, float* out, hipStream_t st);  // out[c] = sum_r a[r][c]
 vcnn_status launch_softmax_loss_f32(int batch, int classes, const float* z, const int32_t* labels, float* loss,

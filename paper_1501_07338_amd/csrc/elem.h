@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "../../include/vcnn.h"
+
 namespace vcnn {
 
 struct bf16 {
@@ -38,6 +40,15 @@ __device__ __forceinline__ void st4(bf16* p, float4 v) {
   u.x = (uint32_t)f32_to_bf16_bits(v.x) | ((uint32_t)f32_to_bf16_bits(v.y) << 16);
   u.y = (uint32_t)f32_to_bf16_bits(v.z) | ((uint32_t)f32_to_bf16_bits(v.w) << 16);
   *reinterpret_cast<uint2*>(p) = u;
+}
+
+// Gradient g passed back through the activation `act` (VCNN_ACT_*) whose forward OUTPUT was y: the factor
+// sigma'(.) of the delta recursion, written in terms of y (ReLU: y > 0; tanh: 1 - y^2; sigmoid: y (1 - y)).
+__device__ __forceinline__ float act_grad(int act, float y, float g) {
+  if (act == VCNN_ACT_RELU) return y > 0.f ? g : 0.f;
+  if (act == VCNN_ACT_TANH) return g * (1.f - y * y);
+  if (act == VCNN_ACT_SIGMOID) return g * y * (1.f - y);
+  return g;
 }
 
 // Alignment (in bytes) a pointer needs for ld4 / st4 of its element type.

@@ -144,7 +144,9 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmArgs a, int tile
           float v = acc[mi][ni][q];
           if (a.bias) v += a.bias[i];
           if (a.relu) v = fmaxf(v, 0.f);
-          st(gC + (int64_t)i * a.c_si + cj, v);
+          const int64_t at = (int64_t)i * a.c_si + cj;
+          if (a.dact) v = act_grad(a.dact, ld(static_cast<const TO*>(a.dact_ref) + at), v);
+          st(gC + at, v);
         }
       }
   }
@@ -221,15 +223,17 @@ static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 // fragments straight from global memory, several groups of 8 contraction steps in flight at once (no LDS
 // staging, no barrier in the loop), and the partial tiles are added in wave order through LDS.
 // -------------------------------------------------------------------------------------------------
+// GemmArgs::row_sums: B gets a virtual column j = N of ones, whose products - the row sums of A - go to
+// row_sums[i] (a fully connected layer's bias gradient comes out of its weight-gradient product this way).
 template <bool A_KC, bool B_KC, bool A_VEC, bool B_VEC, typename TI, typename TO>
-__global__ __launch_bounds__(1024) void gemm_small_kernel(GemmArgs a, int tiles_m, int kper) {
-  extern __shared__ float red[];  // [waves - 1][16][64]
+__device__ __forceinline__ void small_tile(const GemmArgs& a, int tile, int tiles_m, int kper, float* red) {
   const int waves = blockDim.x >> 6;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
-  const int i0 = (blockIdx.x % tiles_m) * 32, j0 = (blockIdx.x / tiles_m) * 32;
+  const int i0 = (tile % tiles_m) * 32, j0 = (tile / tiles_m) * 32;
   const int i = i0 + l32, j = j0 + l32;  // this lane's row of A and column of B
   const bool i_ok = i < a.M, j_ok = j < a.N;
+  const bool j_ones = a.row_sums != nullptr && j == a.N;
   const TI* A = static_cast<const TI*>(a.A) + (int64_t)(i_ok ? i : 0) * a.a_si;
   const TI* B = static_cast<const TI*>(a.B) + (int64_t)(j_ok ? j : 0) * a.b_sj;
   const int ks = wave * kper, ke = min(a.K, ks + kper);  // kper is a multiple of 8
@@ -239,7 +243,7 @@ __global__ __launch_bounds__(1024) void gemm_small_kernel(GemmArgs a, int tiles_
   for (int q = 0; q < 16; ++q) acc[q] = 0.f;
 
   // one group = 8 contraction indices = 4 MFMA steps; lanes 0-31 feed k0 + step, lanes 32-63 k0 + 4 + step
-  auto load4 = [&](const TI* base, int64_t sk, bool kc, bool vec, bool row_ok, int k0, float (&v)[4]) {
+  auto load4 = [&](const TI* base, int64_t sk, bool kc, bool vec, bool row_ok, bool ones, int k0, float (&v)[4]) {
     const int kb = k0 + 4 * half;
     if (kc && vec) {
       const bool ok = row_ok && kb < ke;  // K and the split are multiples of 4: a group of four is in or out as a whole
@@ -253,14 +257,18 @@ __global__ __launch_bounds__(1024) void gemm_small_kernel(GemmArgs a, int tiles_
         v[u] = ok ? t : 0.f;
       }
     }
+    if (ones) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] = kb + u < ke ? 1.f : 0.f;
+    }
   };
   constexpr int U = 8;  // groups in flight
   for (int k0 = ks; k0 < ke; k0 += 8 * U) {
     float av[U][4], bv[U][4];
 #pragma unroll
     for (int g = 0; g < U; ++g) {
-      load4(A, a.a_sk, A_KC, A_VEC, i_ok, k0 + 8 * g, av[g]);
-      load4(B, a.b_sk, B_KC, B_VEC, j_ok, k0 + 8 * g, bv[g]);
+      load4(A, a.a_sk, A_KC, A_VEC, i_ok, false, k0 + 8 * g, av[g]);
+      load4(B, a.b_sk, B_KC, B_VEC, j_ok, j_ones, k0 + 8 * g, bv[g]);
     }
 #pragma unroll
     for (int g = 0; g < U; ++g)
@@ -277,27 +285,56 @@ __global__ __launch_bounds__(1024) void gemm_small_kernel(GemmArgs a, int tiles_
   for (int w = 0; w < waves - 1; ++w)
 #pragma unroll
     for (int q = 0; q < 16; ++q) acc[q] += red[(w * 16 + q) * 64 + lane];
-  if (!j_ok) return;
+  if (!j_ok && !j_ones) return;
   TO* C = static_cast<TO*>(a.C);
 #pragma unroll
   for (int q = 0; q < 16; ++q) {
     const int row = i0 + acc_row(q, lane);
     if (row < a.M) {
       float v = acc[q];
+      if (j_ones) {
+        a.row_sums[row] = v;
+        continue;
+      }
       if (a.bias) v += a.bias[row];
       if (a.relu) v = fmaxf(v, 0.f);
-      st(C + (int64_t)row * a.c_si + (int64_t)j * a.c_sj, v);
+      const int64_t at = (int64_t)row * a.c_si + (int64_t)j * a.c_sj;
+      if (a.dact) v = act_grad(a.dact, ld(static_cast<const TO*>(a.dact_ref) + at), v);
+      st(C + at, v);
     }
   }
 }
 
+template <bool A_KC, bool B_KC, bool A_VEC, bool B_VEC, typename TI, typename TO>
+__global__ __launch_bounds__(1024) void gemm_small_kernel(GemmArgs a, int tiles_m, int kper) {
+  extern __shared__ float red[];  // [waves - 1][16][64]
+  small_tile<A_KC, B_KC, A_VEC, B_VEC, TI, TO>(a, blockIdx.x, tiles_m, kper, red);
+}
+
+// Both products of a fully connected layer's backward pass in one launch: blocks [0, tiles_w) compute the
+// weight gradient dW = dY^T X (with the bias gradient as its column of ones), the rest the input gradient
+// dX = dY W.  The two are independent, and at these sizes neither fills the chip alone.
+template <bool A_VEC, typename TI>
+__global__ __launch_bounds__(1024) void fc_bwd_small_kernel(GemmArgs gw, GemmArgs gx, int tiles_w, int tiles_m_w,
+                                                            int kper_w, int tiles_m_x, int kper_x) {
+  extern __shared__ float red[];
+  if ((int)blockIdx.x < tiles_w)
+    small_tile<false, false, false, false, TI, float>(gw, blockIdx.x, tiles_m_w, kper_w, red);
+  else
+    small_tile<true, false, A_VEC, false, TI, TI>(gx, blockIdx.x - tiles_w, tiles_m_x, kper_x, red);
+}
+
+// one wave per 64 contraction indices, 4 to 16 of them: a wave then has its whole share in flight at once
+static int small_waves(int K) { return (int)std::min<int64_t>(16, std::max<int64_t>(4, ceil_div(K, 64))); }
+static int small_kper(int K, int waves) { return (int)ceil_div(ceil_div(K, waves), 8) * 8; }
+static int64_t small_tiles(const GemmArgs& a) { return ceil_div(a.M, 32) * ceil_div(a.N + (a.row_sums ? 1 : 0), 32); }
+
 template <bool A_KC, bool B_KC, bool A_VEC, bool B_VEC>
 static void launch_small_t(const GemmArgs& a, hipStream_t st) {
   const int tiles_m = (int)ceil_div(a.M, 32);
-  const int64_t tiles = (int64_t)tiles_m * ceil_div(a.N, 32);
-  // one wave per 64 contraction indices, 4 to 16 of them: a wave then has its whole share in flight at once
-  const int waves = (int)std::min<int64_t>(16, std::max<int64_t>(4, ceil_div(a.K, 64)));
-  const int kper = (int)ceil_div(ceil_div(a.K, waves), 8) * 8;
+  const int64_t tiles = small_tiles(a);
+  const int waves = small_waves(a.K);
+  const int kper = small_kper(a.K, waves);
   const dim3 grid((unsigned)tiles), block(64 * waves);
   const size_t lds = (size_t)(waves - 1) * 16 * 64 * sizeof(float);
   const bool in16 = a.in_dtype == VCNN_BF16, out16 = a.out_dtype == VCNN_BF16;
@@ -326,6 +363,10 @@ static void launch_small(const GemmArgs& a, bool a_kc, bool b_kc, bool av, bool 
   }
 }
 
+bool gemm_is_small(const GemmArgs& a) {
+  return a.b_P == 0 && a.c_P == 0 && small_tiles(a) <= 512 && (int64_t)a.M * a.N * a.K <= (int64_t)1 << 27;
+}
+
 static bool in_aligned(const void* p, int dtype) { return dtype == VCNN_BF16 ? group_aligned<bf16>(p) : group_aligned<float>(p); }
 
 vcnn_status launch_gemm_f32(const GemmArgs& a, hipStream_t st) {
@@ -347,10 +388,12 @@ vcnn_status launch_gemm_f32(const GemmArgs& a, hipStream_t st) {
   // Small products (the fully connected layers at batch 128) would fill only a handful of large
   // tiles; 64x64 tiles spread them over more compute units.
   const int64_t big_tiles = ceil_div(a.M, 128) * ceil_div(a.N, 128);
-  const int64_t small_tiles = ceil_div(a.M, 32) * ceil_div(a.N, 32);
-  if (a.b_P == 0 && a.c_P == 0 && small_tiles <= 512 && (int64_t)a.M * a.N * a.K <= (int64_t)1 << 27)
+  if (gemm_is_small(a)) {
     launch_small(a, a_kc, b_kc, av, bv, st);
-  else if (a.M > 32 && a.N <= 4096 && big_tiles < 128)
+    return check_launch("gemm_small");
+  }
+  if (a.row_sums) return fail(VCNN_ERR_UNSUPPORTED, "gemm: row sums are only built into the small-product kernel");
+  if (a.M > 32 && a.N <= 4096 && big_tiles < 128)
     launch_cfg<64, 64, 32, 32, 32>(a, a_kc, b_kc, av, bv, st);
   else if (a.M <= 32)
     launch_cfg<32, 256, 32, 32, 64>(a, a_kc, b_kc, av, bv, st);
@@ -542,6 +585,29 @@ vcnn_status launch_bwd_filter_gemm_f32(const ConvGeom& g, int dtype, const void*
   vcnn_status s = check_launch("bwd_filter_f32");
   if (s != VCNN_OK || splits == 1) return s;
   return launch_sum_slices(partial, nullptr, dw, VCNN_F32, g.M * g.K, splits, 1, 1, 0, st);
+}
+
+
+// gw: dW(o, i) = sum_b dY[b][o] X[b][i] (A = dY read across rows, B = X), gx: dX(b, i) = sum_o dY[b][o] W[o][i]
+// (A = dY contraction-contiguous, B = W); both must satisfy gemm_is_small.
+vcnn_status launch_fc_bwd_small(const GemmArgs& gw, const GemmArgs& gx, hipStream_t st) {
+  const int waves = std::max(small_waves(gw.K), small_waves(gx.K));
+  const int tiles_w = (int)small_tiles(gw), tiles_x = (int)small_tiles(gx);
+  const dim3 grid((unsigned)(tiles_w + tiles_x)), block(64 * waves);
+  const size_t lds = (size_t)(waves - 1) * 16 * 64 * sizeof(float);
+  const int tm_w = (int)ceil_div(gw.M, 32), tm_x = (int)ceil_div(gx.M, 32);
+  // each product keeps the split it has when launched alone (surplus waves get an empty share), so the fused
+  // launch returns the same bits as two separate ones
+  const int kp_w = small_kper(gw.K, small_waves(gw.K)), kp_x = small_kper(gx.K, small_waves(gx.K));
+  const bool av = in_aligned(gx.A, gx.in_dtype) && gx.a_si % 4 == 0 && gx.K % 4 == 0;
+  if (gw.in_dtype == VCNN_BF16) {
+    if (av) hipLaunchKernelGGL((fc_bwd_small_kernel<true, bf16>), grid, block, lds, st, gw, gx, tiles_w, tm_w, kp_w, tm_x, kp_x);
+    else hipLaunchKernelGGL((fc_bwd_small_kernel<false, bf16>), grid, block, lds, st, gw, gx, tiles_w, tm_w, kp_w, tm_x, kp_x);
+  } else {
+    if (av) hipLaunchKernelGGL((fc_bwd_small_kernel<true, float>), grid, block, lds, st, gw, gx, tiles_w, tm_w, kp_w, tm_x, kp_x);
+    else hipLaunchKernelGGL((fc_bwd_small_kernel<false, float>), grid, block, lds, st, gw, gx, tiles_w, tm_w, kp_w, tm_x, kp_x);
+  }
+  return check_launch("fc_bwd_small");
 }
 
 }  // namespace vcnn

@@ -221,7 +221,8 @@ __global__ __launch_bounds__(kThreads) void pool_fwd_kernel(vcnn_pool_desc d, in
 template <typename T, int WIN, int STRIDE>
 __global__ __launch_bounds__(kThreads) void pool_bwd_kernel(vcnn_pool_desc d, int oh_n, int ow_n,
                                                             const T* __restrict__ dy,
-                                                            const int32_t* __restrict__ argmax, T* __restrict__ dx) {
+                                                            const int32_t* __restrict__ argmax, T* __restrict__ dx,
+                                                            int act, const T* __restrict__ ref) {
   const int pos = blockIdx.x * kThreads + threadIdx.x;
   if (pos >= d.h * d.w) return;
   const int win_h = WIN ? WIN : d.win_h, win_w = WIN ? WIN : d.win_w;
@@ -260,6 +261,7 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_kernel(vcnn_pool_desc d, in
         if (argmax[o] == pos) acc += ld(dy + o);
       }
   }
+  if (act) acc = act_grad(act, ld(ref + nc * d.h * d.w + pos), acc);
   st(dx + nc * d.h * d.w + pos, acc);
 }
 
@@ -287,7 +289,8 @@ template <typename T, int WIN, int STRIDE>
 __global__ __launch_bounds__(kThreads) void pool_bwd_staged_kernel(vcnn_pool_desc d, int oh_n, int ow_n, int pb, int vec,
                                                                    const T* __restrict__ dy,
                                                                    const int32_t* __restrict__ argmax,
-                                                                   T* __restrict__ dx) {
+                                                                   T* __restrict__ dx, int act,
+                                                                   const T* __restrict__ ref) {
   extern __shared__ float pool_lds[];
   const int64_t planes = (int64_t)d.n * d.c;
   const int64_t nc0 = (int64_t)blockIdx.x * pb;
@@ -332,7 +335,13 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_staged_kernel(vcnn_pool_des
 #pragma unroll
           for (int t = 0; t < 4; ++t) acc[t] += j == t ? g : 0.f;
         }
-      st4(dx + nc0 * in_plane + (int64_t)pl * in_plane + pos0, make_float4(acc[0], acc[1], acc[2], acc[3]));
+      const int64_t at = nc0 * in_plane + (int64_t)pl * in_plane + pos0;
+      if (act) {
+        const float4 y = ld4(ref + at);
+        acc[0] = act_grad(act, y.x, acc[0]), acc[1] = act_grad(act, y.y, acc[1]);
+        acc[2] = act_grad(act, y.z, acc[2]), acc[3] = act_grad(act, y.w, acc[3]);
+      }
+      st4(dx + at, make_float4(acc[0], acc[1], acc[2], acc[3]));
     }
     return;
   }
@@ -352,13 +361,14 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_staged_kernel(vcnn_pool_des
         const int o = base + oh * ow_n + ow;
         if (am_s[o] == pos) acc += dy_s[o];
       }
+    if (act) acc = act_grad(act, ld(ref + nc0 * in_plane + e), acc);
     st(dx + nc0 * in_plane + e, acc);
   }
 }
 
 template <typename T>
 static void pool_bwd_typed(const vcnn_pool_desc& d, int oh, int ow, const void* dy, const int32_t* argmax, void* dx,
-                           hipStream_t st) {
+                           int act, const void* ref, hipStream_t st) {
   const int64_t planes = (int64_t)d.n * d.c;
   const bool square = d.win_h == d.win_w && d.stride_h == d.stride_w;
   const int which = square && d.win_h == 2 && d.stride_h == 2 ? 2 : (square && d.win_h == 3 && d.stride_h == 2 ? 3 : 0);
@@ -370,23 +380,23 @@ static void pool_bwd_typed(const vcnn_pool_desc& d, int oh, int ow, const void* 
   if (in_plane <= 16384 && out_plane * 8 <= 32 * 1024 && ceil_div(planes, pb) <= 0x7fffffffLL) {
     const dim3 grid((unsigned)ceil_div(planes, pb)), block(kThreads);
     const size_t lds = (size_t)pb * out_plane * 8;
-    const int vec = d.w % 4 == 0 && group_aligned<T>(dx);
+    const int vec = d.w % 4 == 0 && group_aligned<T>(dx) && (!act || group_aligned<T>(ref));
     if (which == 2)
-      hipLaunchKernelGGL((pool_bwd_staged_kernel<T, 2, 2>), grid, block, lds, st, d, oh, ow, (int)pb, vec, (const T*)dy, argmax, (T*)dx);
+      hipLaunchKernelGGL((pool_bwd_staged_kernel<T, 2, 2>), grid, block, lds, st, d, oh, ow, (int)pb, vec, (const T*)dy, argmax, (T*)dx, act, (const T*)ref);
     else if (which == 3)
-      hipLaunchKernelGGL((pool_bwd_staged_kernel<T, 3, 2>), grid, block, lds, st, d, oh, ow, (int)pb, vec, (const T*)dy, argmax, (T*)dx);
+      hipLaunchKernelGGL((pool_bwd_staged_kernel<T, 3, 2>), grid, block, lds, st, d, oh, ow, (int)pb, vec, (const T*)dy, argmax, (T*)dx, act, (const T*)ref);
     else
-      hipLaunchKernelGGL((pool_bwd_staged_kernel<T, 0, 0>), grid, block, lds, st, d, oh, ow, (int)pb, vec, (const T*)dy, argmax, (T*)dx);
+      hipLaunchKernelGGL((pool_bwd_staged_kernel<T, 0, 0>), grid, block, lds, st, d, oh, ow, (int)pb, vec, (const T*)dy, argmax, (T*)dx, act, (const T*)ref);
     return;
   }
   const unsigned gy = (unsigned)std::min<int64_t>(planes, 32768);
   const dim3 grid((unsigned)ceil_div((int64_t)d.h * d.w, kThreads), gy, (unsigned)ceil_div(planes, gy)), block(kThreads);
   if (which == 2)
-    hipLaunchKernelGGL((pool_bwd_kernel<T, 2, 2>), grid, block, 0, st, d, oh, ow, (const T*)dy, argmax, (T*)dx);
+    hipLaunchKernelGGL((pool_bwd_kernel<T, 2, 2>), grid, block, 0, st, d, oh, ow, (const T*)dy, argmax, (T*)dx, act, (const T*)ref);
   else if (which == 3)
-    hipLaunchKernelGGL((pool_bwd_kernel<T, 3, 2>), grid, block, 0, st, d, oh, ow, (const T*)dy, argmax, (T*)dx);
+    hipLaunchKernelGGL((pool_bwd_kernel<T, 3, 2>), grid, block, 0, st, d, oh, ow, (const T*)dy, argmax, (T*)dx, act, (const T*)ref);
   else
-    hipLaunchKernelGGL((pool_bwd_kernel<T, 0, 0>), grid, block, 0, st, d, oh, ow, (const T*)dy, argmax, (T*)dx);
+    hipLaunchKernelGGL((pool_bwd_kernel<T, 0, 0>), grid, block, 0, st, d, oh, ow, (const T*)dy, argmax, (T*)dx, act, (const T*)ref);
 }
 
 vcnn_status launch_pool_fwd(const vcnn_pool_desc& d, int oh, int ow, const void* x, void* y, int32_t* argmax,
@@ -398,10 +408,10 @@ vcnn_status launch_pool_fwd(const vcnn_pool_desc& d, int oh, int ow, const void*
 }
 
 vcnn_status launch_pool_bwd(const vcnn_pool_desc& d, int oh, int ow, const void* dy, const int32_t* argmax, void* dx,
-                            hipStream_t st) {
+                            int act, const void* ref, hipStream_t st) {
   if ((int64_t)d.n * d.c > 32768LL * 65535) return fail(VCNN_ERR_UNSUPPORTED, "pool: too many planes for one launch");
-  if (d.dtype == VCNN_BF16) pool_bwd_typed<bf16>(d, oh, ow, dy, argmax, dx, st);
-  else pool_bwd_typed<float>(d, oh, ow, dy, argmax, dx, st);
+  if (d.dtype == VCNN_BF16) pool_bwd_typed<bf16>(d, oh, ow, dy, argmax, dx, act, ref, st);
+  else pool_bwd_typed<float>(d, oh, ow, dy, argmax, dx, act, ref, st);
   return check_launch("pool_bwd");
 }
 

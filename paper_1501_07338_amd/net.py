@@ -58,7 +58,9 @@ class TrainStep:
                 d = vcnn.conv_desc(ishape[0], ishape[1], ishape[2], ishape[3], L.cout, L.kh, L.kw, L.pad_h, L.pad_w,
                                    dtype=dtype, act=vcnn.ACT_RELU if L.relu else vcnn.ACT_NONE)
                 self.descs[li] = d
-                ws_bytes = max(ws_bytes, *(vcnn.conv_workspace_bytes(d, p) for p in (vcnn.PASS_FWD, vcnn.PASS_BWD_DATA)))
+                # (a first layer's filter gradient has no input gradient to overlap with and runs on the main stream)
+                ws_bytes = max(ws_bytes, *(vcnn.conv_workspace_bytes(d, p)
+                                           for p in (vcnn.PASS_FWD, vcnn.PASS_BWD_DATA, vcnn.PASS_BWD_FILTER)))
                 ws_side_bytes = max(ws_side_bytes, vcnn.conv_workspace_bytes(d, vcnn.PASS_BWD_FILTER))
             elif isinstance(L, Pool):
                 self.descs[li] = vcnn.pool_desc(ishape[0], ishape[1], ishape[2], ishape[3], L.win, L.win, L.stride,
@@ -83,6 +85,12 @@ class TrainStep:
             for p, p16 in zip(self.params, self.params16):
                 if p is not None:
                     vcnn.f32_to_bf16(p[0].numel(), p[0], p16, stream)
+
+    def folds(self, li):
+        """True if layer li's input gradient is stored with the ReLU derivative of layer li-1 folded in,
+        i.e. it is written to dpre[li-1] (w.r.t. that layer's pre-activation) and dacts[li] stays unused."""
+        L = self.net.layers[li]
+        return li > 0 and getattr(self.net.layers[li - 1], "relu", False) and isinstance(L, (Pool, FC))
 
     # ---- one pass each ---------------------------------------------------------------------------
     def forward(self, stream=None):
@@ -122,31 +130,39 @@ class TrainStep:
         net = self.net
         main = stream if stream is not None else torch.cuda.current_stream()
         side = self.side if self.side is not None else main
+        folded = False  # the layer above already applied this layer's ReLU derivative and wrote dpre[li]
         for li in range(len(net.layers) - 1, -1, -1):
             L = net.layers[li]
             a_in, a_out, d = self.acts[li], self.acts[li + 1], self.dacts[li + 1]
             need_dx = li > 0 or self.first_layer_dx
             if getattr(L, "relu", False):
-                vcnn.act_bwd(vcnn.ACT_RELU, self.dtype, d.numel(), a_out, d, self.dpre[li], main)
+                if not folded:
+                    vcnn.act_bwd(vcnn.ACT_RELU, self.dtype, d.numel(), a_out, d, self.dpre[li], main)
                 d = self.dpre[li]
+            # pooling and fully connected layers fold the ReLU derivative of the layer below into their
+            # input-gradient store: it lands in that layer's dpre directly
+            folded = self.folds(li)
+            dx_out = self.dpre[li - 1] if folded else self.dacts[li]
+            act_below = vcnn.ACT_RELU if folded else vcnn.ACT_NONE
             if isinstance(L, Pool):
                 if need_dx:
-                    vcnn.pool_bwd(self.descs[li], d, self.argmax[li], self.dacts[li], main)
+                    vcnn.pool_bwd_act(self.descs[li], act_below, a_in, d, self.argmax[li], dx_out, main)
+                continue
+            w = self.weights(li)
+            dw, db = self.grads[li]
+            if isinstance(L, FC):  # one call: at these sizes both products and the bias gradient share a launch
+                bsz = a_in.shape[0]
+                vcnn.fc_bwd_act(self.dtype, bsz, a_in.numel() // bsz, L.out, act_below, a_in, w, d, dw, db,
+                                dx_out if need_dx else None, main)
+                continue
+            if not need_dx:  # nothing to overlap with
+                vcnn.conv_bwd_filter(self.descs[li], a_in, d, dw, db, self.workspace, main)
                 continue
             if side is not main:  # fork: the parameter-gradient strand starts once d is complete
                 self.forked[li].record(main)
                 side.wait_event(self.forked[li])
-            w = self.weights(li)
-            dw, db = self.grads[li]
-            if isinstance(L, Conv):
-                vcnn.conv_bwd_filter(self.descs[li], a_in, d, dw, db, self.workspace_side, side)
-                if need_dx:
-                    vcnn.conv_bwd_data(self.descs[li], w, d, self.dacts[li], self.workspace, main)
-            else:
-                bsz = a_in.shape[0]
-                vcnn.fc_bwd(self.dtype, bsz, a_in.numel() // bsz, L.out, a_in, w, d, dw, db, None, side)
-                if need_dx:
-                    vcnn.fc_bwd(self.dtype, bsz, a_in.numel() // bsz, L.out, a_in, w, d, None, None, self.dacts[li], main)
+            vcnn.conv_bwd_filter(self.descs[li], a_in, d, dw, db, self.workspace_side, side)
+            vcnn.conv_bwd_data(self.descs[li], w, d, self.dacts[li], self.workspace, main)
         if side is not main:  # join before anything reads the parameter gradients
             main.wait_stream(side)
 

@@ -52,6 +52,9 @@ _SIGNATURES = {
     "vcnn_pool_out_shape": (c_int32, [POINTER(PoolDesc), POINTER(c_int32), POINTER(c_int32)]),
     "vcnn_pool_fwd": (c_int32, [POINTER(PoolDesc), c_void_p, c_void_p, c_void_p, c_void_p]),
     "vcnn_pool_bwd": (c_int32, [POINTER(PoolDesc), c_void_p, c_void_p, c_void_p, c_void_p]),
+    "vcnn_pool_bwd_act": (c_int32, [POINTER(PoolDesc), c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
+    "vcnn_fc_bwd_act": (c_int32, [c_int32, c_int32, c_int32, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
+                                  c_void_p, c_void_p, c_void_p]),
     "vcnn_act_fwd": (c_int32, [c_int32, c_int32, c_size_t, c_void_p, c_void_p, c_void_p]),
     "vcnn_act_bwd": (c_int32, [c_int32, c_int32, c_size_t, c_void_p, c_void_p, c_void_p, c_void_p]),
     "vcnn_fc_fwd": (c_int32, [c_int32, c_int32, c_int32, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
@@ -78,6 +81,9 @@ def lib() -> ctypes.CDLL:
         if not LIB_PATH.exists():
             raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -m paper_1501_07338_amd.build); "
                                "there is no fallback path")
+        # torch first: the device pointers and streams passed in belong to the HIP runtime torch loads, and the
+        # library must resolve its HIP symbols against that same copy (a second runtime sees no device)
+        import torch  # noqa: F401
         handle = ctypes.CDLL(str(LIB_PATH))
         for name, (res, args) in _SIGNATURES.items():
             fn = getattr(handle, name)
@@ -179,6 +185,10 @@ def pool_bwd(d, dy, argmax, dx, stream=None):
     _check(lib().vcnn_pool_bwd(byref(d), _ptr(dy), _ptr(argmax), _ptr(dx), _stream(stream)))
 
 
+def pool_bwd_act(d, act_below, x, dy, argmax, dx, stream=None):
+    _check(lib().vcnn_pool_bwd_act(byref(d), act_below, _ptr(x), _ptr(dy), _ptr(argmax), _ptr(dx), _stream(stream)))
+
+
 def act_fwd(act, dtype, count, x, y, stream=None):
     _check(lib().vcnn_act_fwd(act, dtype, count, _ptr(x), _ptr(y), _stream(stream)))
 
@@ -194,6 +204,11 @@ def fc_fwd(dtype, batch, in_f, out_f, act, x, w, bias, y, stream=None):
 def fc_bwd(dtype, batch, in_f, out_f, x, w, dy, dw, dbias, dx, stream=None):
     _check(lib().vcnn_fc_bwd(dtype, batch, in_f, out_f, _ptr(x), _ptr(w), _ptr(dy), _ptr(dw), _ptr(dbias), _ptr(dx),
                              _stream(stream)))
+
+
+def fc_bwd_act(dtype, batch, in_f, out_f, act_below, x, w, dy, dw, dbias, dx, stream=None):
+    _check(lib().vcnn_fc_bwd_act(dtype, batch, in_f, out_f, act_below, _ptr(x), _ptr(w), _ptr(dy), _ptr(dw), _ptr(dbias),
+                                 _ptr(dx), _stream(stream)))
 
 
 def softmax_loss(batch, classes, logits, labels, loss, dlogits, stream=None):

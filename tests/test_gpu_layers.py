@@ -183,6 +183,61 @@ def test_pool_fwd_bwd(shape, ties):
     assert_close(to_np(dx), O.maxpool_bwd(dy, ram, (h, w)), 1e-6, "pool dx")
 
 
+def _sigma_bwd(act, y, g):
+    return {vcnn.ACT_RELU: O.relu_bwd, vcnn.ACT_TANH: O.tanh_bwd, vcnn.ACT_SIGMOID: O.sigmoid_bwd}[act](y, g)
+
+
+@pytest.mark.parametrize("act", [vcnn.ACT_RELU, vcnn.ACT_TANH, vcnn.ACT_SIGMOID])
+@pytest.mark.parametrize("shape", POOL_SHAPES)
+def test_pool_bwd_with_activation_derivative_folded(shape, act):
+    """pool_bwd_act = pool_bwd followed by act_bwd against the pooling input (an activation's output)."""
+    n, c, h, w, win, st = shape
+    x = random_tensor(810, (n, c, h, w))
+    x = np.maximum(x, 0).astype(np.float32) if act == vcnn.ACT_RELU else np.tanh(x).astype(np.float32) * 0.5 + 0.5
+    d = vcnn.pool_desc(n, c, h, w, win, win, st, st)
+    oh, ow = vcnn.pool_out_shape(d)
+    y = torch.empty((n, c, oh, ow), device=DEV)
+    am = torch.empty((n, c, oh, ow), dtype=torch.int32, device=DEV)
+    vcnn.pool_fwd(d, to_dev(x), y, am)
+    ram = O.maxpool_fwd(x, (win, win), (st, st))[1]
+    np.testing.assert_array_equal(to_np(am), ram)
+    dy = random_tensor(811, (n, c, oh, ow))
+    dx = torch.full((n, c, h, w), float("nan"), device=DEV)
+    vcnn.pool_bwd_act(d, act, to_dev(x), to_dev(dy), am, dx)
+    assert_close(to_np(dx), _sigma_bwd(act, x, O.maxpool_bwd(dy, ram, (h, w))), 1e-6, "pool dx * sigma'")
+    # no activation below: the plain call, x not read
+    vcnn.pool_bwd_act(d, vcnn.ACT_NONE, None, to_dev(dy), am, dx)
+    assert_close(to_np(dx), O.maxpool_bwd(dy, ram, (h, w)), 1e-6, "pool dx")
+    # average pooling takes the same call
+    da = vcnn.pool_desc(n, c, h, w, win, win, st, st, mode=vcnn.POOL_AVG)
+    vcnn.pool_bwd_act(da, act, to_dev(x), to_dev(dy), None, dx)
+    assert_close(to_np(dx), _sigma_bwd(act, x, O.avgpool_bwd(dy, (h, w), (win, win), (st, st))), 1e-6, "avgpool dx * sigma'")
+
+
+@pytest.mark.parametrize("act", [vcnn.ACT_RELU, vcnn.ACT_TANH, vcnn.ACT_SIGMOID])
+@pytest.mark.parametrize("b,i,o", [(128, 800, 500), (128, 500, 10), (7, 33, 5), (256, 2048, 1000)])
+def test_fc_bwd_with_activation_derivative_folded(b, i, o, act):
+    """fc_bwd_act = fc_bwd with act_bwd against the layer's input applied to dx (small and large product kernels)."""
+    x = random_tensor(1010, (b, i))
+    x = np.maximum(x, 0).astype(np.float32) if act == vcnn.ACT_RELU else np.tanh(x).astype(np.float32) * 0.5 + 0.5
+    w, dy = random_tensor(1011, (o, i), scale=(2.0 / i) ** 0.5), random_tensor(1012, (b, o))
+    dx = torch.full((b, i), float("nan"), device=DEV)
+    dw, db = torch.full((o, i), float("nan"), device=DEV), torch.full((o,), float("nan"), device=DEV)
+    vcnn.fc_bwd_act(vcnn.F32, b, i, o, act, to_dev(x), to_dev(w), to_dev(dy), dw, db, dx)
+    rdw, rdb, rdx = O.fc_bwd(x, w, dy)
+    assert_close(to_np(dx), _sigma_bwd(act, x, rdx), TOL_F32, "fc dx * sigma'")
+    assert_close(to_np(dw), rdw, TOL_F32, "fc dw")
+    assert_close(to_np(db), rdb, TOL_F32, "fc db")
+    # the input gradient alone gives the same bits; without an activation below it is the plain call
+    dx2 = torch.full((b, i), float("nan"), device=DEV)
+    vcnn.fc_bwd_act(vcnn.F32, b, i, o, act, to_dev(x), to_dev(w), to_dev(dy), None, None, dx2)
+    assert torch.equal(dx, dx2)
+    plain = torch.full((b, i), float("nan"), device=DEV)
+    vcnn.fc_bwd(vcnn.F32, b, i, o, None, to_dev(w), to_dev(dy), None, None, plain)
+    vcnn.fc_bwd_act(vcnn.F32, b, i, o, vcnn.ACT_NONE, None, to_dev(w), to_dev(dy), None, None, dx)
+    assert torch.equal(dx, plain)
+
+
 @pytest.mark.parametrize("count", [1, 3, 4, 1023, 4099])
 def test_act(count):
     x = random_tensor(900, (count,))
