@@ -207,6 +207,31 @@ def avgpool_bwd(dy, hw, win, stride):
     return dx
 
 
+_SIGMA = {"none": (lambda z: _f64(z).copy(), lambda y, g: _f64(g).copy()), "relu": (relu_fwd, relu_bwd),
+          "tanh": (tanh_fwd, tanh_bwd), "sigmoid": (sigmoid_fwd, sigmoid_bwd)}
+
+
+def pool_layer_fwd(x, bias, win, stride, mode="max", act="none"):
+    """The pooling layer of Eq. 3, "Vectorizing Pooling": y = sigma(phi_p(x) + b), one bias per feature map,
+    phi_p the max or the mean of each window.  Returns (y, argmax); argmax is None for average pooling."""
+    if mode == "max":
+        pooled, am = maxpool_fwd(x, win, stride)
+    else:
+        pooled, am = avgpool_fwd(x, win, stride), None
+    z = pooled + (0.0 if bias is None else _f64(bias)[None, :, None, None])
+    return _SIGMA[act][0](z), am
+
+
+def pool_layer_bwd(y, dy, argmax, hw, win, stride, mode="max", act="none"):
+    """Gradients of the layer above from its output y and dL/dy: through sigma (delta = dy * sigma'(.), from y),
+    then dbias[c] = sum of delta over samples and pixels, and dx = delta routed back through phi_p (to the
+    recorded maximum, or spread evenly over the window).  Returns (dx, dbias, delta)."""
+    delta = _SIGMA[act][1](y, dy)
+    dbias = delta.sum(axis=(0, 2, 3))
+    dx = maxpool_bwd(delta, argmax, hw) if mode == "max" else avgpool_bwd(delta, hw, win, stride)
+    return dx, dbias, delta
+
+
 def fc_fwd(x, w, b=None, relu=False):
     x, w = _f64(x), _f64(w)
     bsz, i = x.shape

@@ -513,3 +513,52 @@ def test_avgpool_tiling_windows_reduce_to_block_means_and_upscaling():
     # constant input -> the same constant; mass conservation of the gradient
     np.testing.assert_allclose(O.avgpool_fwd(np.full((1, 1, 5, 5), 2.5), (3, 3), (2, 2)), 2.5, atol=1e-15)
     assert abs(O.avgpool_bwd(dy, (6, 8), (2, 2), (2, 2)).sum() - dy.sum()) < 1e-12
+
+
+# ---- the pooling layer with bias and sigma (Eq. 3) -------------------------------------------------------
+@pytest.mark.parametrize("mode", ["max", "avg"])
+@pytest.mark.parametrize("act", ["none", "relu", "tanh", "sigmoid"])
+def test_pool_layer_matches_library_composition_and_finite_differences(mode, act):
+    """Eq. 3, y = sigma(phi_p(x) + b): forward against torch's CPU pooling + broadcast bias + activation in fp64;
+    backward (dx, dbias) against central differences of a random linear functional of y."""
+    torch = pytest.importorskip("torch")
+    F = torch.nn.functional
+    rng = np.random.default_rng(4100)
+    n, c, h, w, win, st = 2, 3, 7, 8, 3, 2
+    x = rng.standard_normal((n, c, h, w))
+    bias = rng.standard_normal(c)
+    g = rng.standard_normal((n, c, (h - win) // st + 1, (w - win) // st + 1))
+    y, am = O.pool_layer_fwd(x, bias, (win, win), (st, st), mode, act)
+    xt = torch.from_numpy(x)
+    pooled = F.max_pool2d(xt, win, st) if mode == "max" else F.avg_pool2d(xt, win, st)
+    z = pooled + torch.from_numpy(bias)[None, :, None, None]
+    want = {"none": z, "relu": torch.relu(z), "tanh": torch.tanh(z), "sigmoid": torch.sigmoid(z)}[act]
+    np.testing.assert_allclose(y, want.numpy(), rtol=1e-13, atol=1e-15)
+
+    dx, db, delta = O.pool_layer_bwd(y, g, am, (h, w), (win, win), (st, st), mode, act)
+    assert delta.shape == y.shape
+
+    def loss():  # central_diff perturbs x / bias in place
+        return float(np.sum(O.pool_layer_fwd(x, bias, (win, win), (st, st), mode, act)[0] * g))
+
+    # random x: no ties, and no pre-activation within the step of the ReLU kink
+    np.testing.assert_allclose(dx, central_diff(loss, x), rtol=2e-6, atol=1e-8)
+    np.testing.assert_allclose(db, central_diff(loss, bias), rtol=2e-6, atol=1e-8)
+
+
+def test_pool_layer_without_bias_and_sigma_is_plain_pooling():
+    rng = np.random.default_rng(4101)
+    x = rng.standard_normal((2, 2, 6, 6))
+    y, am = O.pool_layer_fwd(x, None, (2, 2), (2, 2))
+    ry, ram = O.maxpool_fwd(x, (2, 2), (2, 2))
+    np.testing.assert_array_equal(y, ry)
+    np.testing.assert_array_equal(am, ram)
+    g = rng.standard_normal(y.shape)
+    dx, db, delta = O.pool_layer_bwd(y, g, am, (6, 6), (2, 2), (2, 2))
+    np.testing.assert_array_equal(dx, O.maxpool_bwd(g, ram, (6, 6)))
+    np.testing.assert_array_equal(delta, g)
+    np.testing.assert_allclose(db, g.sum(axis=(0, 2, 3)))
+    # a constant shift of one map's bias shifts exactly that map's output (max and mean commute with it)
+    y2 = O.pool_layer_fwd(x, np.array([0.0, 1.5]), (2, 2), (2, 2))[0]
+    np.testing.assert_allclose(y2[:, 1], ry[:, 1] + 1.5)
+    np.testing.assert_array_equal(y2[:, 0], ry[:, 0])
