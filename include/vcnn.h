@@ -117,6 +117,20 @@ vcnn_status vcnn_pool_fwd(const vcnn_pool_desc* d, const void* x, void* y, int32
  * calls; the backward pass is the exact transpose, dx[i] = sum over the windows covering i of dy / (win_h*win_w)
  * (for windows that tile the plane: the nearest-neighbour upscaling of dy the paper back-propagates with). */
 vcnn_status vcnn_pool_bwd(const vcnn_pool_desc* d, const void* dy, const int32_t* argmax, void* dx, void* stream);
+/* The pooling layer of Eq. 3 ("Vectorizing Pooling"): y = sigma(phi_p(x) + b), phi_p the max or the mean of each
+ * window (d->mode), b one float per feature map (bias[c], NULL = zero), sigma = act (VCNN_ACT_*).  Shapes, argmax
+ * and tie rule as in vcnn_pool_fwd, which is this call with no bias and VCNN_ACT_NONE. */
+vcnn_status vcnn_pool_layer_fwd(const vcnn_pool_desc* d, int32_t act, const void* x, const float* bias, void* y,
+                                int32_t* argmax, void* stream);
+/* Gradients of that layer from its output y and dy = dL/dy: delta = dy * sigma'(.) evaluated from y (as in
+ * vcnn_act_bwd), dbias[c] = sum of delta over samples and pixels (NULL: not computed), dx = delta routed back
+ * through phi_p as in vcnn_pool_bwd.  workspace: device memory of at least vcnn_pool_layer_workspace_bytes (holds
+ * delta and partial sums; contents undefined afterwards; may be NULL when act is VCNN_ACT_NONE and dbias NULL).
+ * y is not read when act is VCNN_ACT_NONE.  VCNN_ERR_WORKSPACE if the workspace is too small. */
+vcnn_status vcnn_pool_layer_workspace_bytes(const vcnn_pool_desc* d, size_t* bytes);
+vcnn_status vcnn_pool_layer_bwd(const vcnn_pool_desc* d, int32_t act, const void* y, const void* dy,
+                                const int32_t* argmax, float* dbias, void* dx, void* workspace, size_t workspace_bytes,
+                                void* stream);
 /* vcnn_pool_bwd with the next step of the delta recursion folded into its store: the pooling input x is the
  * forward OUTPUT of the activation act_below (sigma of Eq. 1, applied by the layer below), and
  * dx = pool_bwd(dy) * sigma'(.) evaluated from x (ReLU: x > 0; tanh: 1 - x^2; sigmoid: x (1 - x)), i.e. the

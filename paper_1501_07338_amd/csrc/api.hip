@@ -405,19 +405,75 @@ vcnn_status vcnn_pool_out_shape(const vcnn_pool_desc* d, int32_t* oh, int32_t* o
   return VCNN_OK;
 }
 
-vcnn_status vcnn_pool_fwd(const vcnn_pool_desc* d, const void* x, void* y, int32_t* argmax, void* stream) {
+static bool known_act(int32_t act) {
+  return act == VCNN_ACT_NONE || act == VCNN_ACT_RELU || act == VCNN_ACT_TANH || act == VCNN_ACT_SIGMOID;
+}
+
+vcnn_status vcnn_pool_layer_fwd(const vcnn_pool_desc* d, int32_t act, const void* x, const float* bias, void* y,
+                                int32_t* argmax, void* stream) {
   int oh, ow;
   if (vcnn_status s = check_pool(d, &oh, &ow)) return s;
+  if (!known_act(act)) return fail(VCNN_ERR_UNSUPPORTED, "pool_layer_fwd: activation %d is not built", act);
   if (!x || !y || (!argmax && d->mode == VCNN_POOL_MAX)) return fail(VCNN_ERR_NULL, "pool_fwd: NULL tensor");
-  if (d->mode == VCNN_POOL_AVG) return launch_avgpool(*d, oh, ow, x, y, false, (hipStream_t)stream);
-  return launch_pool_fwd(*d, oh, ow, x, y, argmax, (hipStream_t)stream);
+  if (d->mode == VCNN_POOL_AVG) return launch_avgpool(*d, oh, ow, x, y, false, bias, act, (hipStream_t)stream);
+  return launch_pool_fwd(*d, oh, ow, x, y, argmax, bias, act, (hipStream_t)stream);
+}
+
+vcnn_status vcnn_pool_fwd(const vcnn_pool_desc* d, const void* x, void* y, int32_t* argmax, void* stream) {
+  return vcnn_pool_layer_fwd(d, VCNN_ACT_NONE, x, nullptr, y, argmax, stream);
+}
+
+// the pooled maps as the (n, M = maps, P = pixels per map) view the bias-gradient reduction takes
+static ConvGeom pooled_geom(const vcnn_pool_desc& d, int oh, int ow) {
+  ConvGeom g{};
+  g.n = d.n, g.M = d.c, g.P = (int64_t)oh * ow;
+  return g;
+}
+
+static size_t pool_delta_bytes(const vcnn_pool_desc& d, int oh, int ow) {
+  return align256((size_t)d.n * d.c * oh * ow * (d.dtype == VCNN_BF16 ? 2 : 4));
+}
+
+vcnn_status vcnn_pool_layer_workspace_bytes(const vcnn_pool_desc* d, size_t* bytes) {
+  if (!bytes) return fail(VCNN_ERR_NULL, "pool_layer_workspace_bytes: NULL out-parameter");
+  int oh, ow;
+  if (vcnn_status s = check_pool(d, &oh, &ow)) return s;
+  *bytes = pool_delta_bytes(*d, oh, ow) + align256(bias_grad_partial_bytes(pooled_geom(*d, oh, ow)));
+  return VCNN_OK;
+}
+
+vcnn_status vcnn_pool_layer_bwd(const vcnn_pool_desc* d, int32_t act, const void* y, const void* dy,
+                                const int32_t* argmax, float* dbias, void* dx, void* workspace, size_t workspace_bytes,
+                                void* stream) {
+  int oh, ow;
+  if (vcnn_status s = check_pool(d, &oh, &ow)) return s;
+  if (!known_act(act)) return fail(VCNN_ERR_UNSUPPORTED, "pool_layer_bwd: activation %d is not built", act);
+  if (!dy || !dx || (act != VCNN_ACT_NONE && !y) || (!argmax && d->mode == VCNN_POOL_MAX))
+    return fail(VCNN_ERR_NULL, "pool_layer_bwd: NULL tensor");
+  size_t need = 0;
+  (void)vcnn_pool_layer_workspace_bytes(d, &need);
+  if (act == VCNN_ACT_NONE && !dbias) need = 0;
+  if (need && (!workspace || workspace_bytes < need))
+    return fail(VCNN_ERR_WORKSPACE, "pool_layer_bwd: workspace has %zu bytes, needs %zu", workspace_bytes, need);
+  // delta = dy * sigma'(.) from y; then the two gradients read delta
+  const void* delta = dy;
+  if (act != VCNN_ACT_NONE) {
+    if (vcnn_status s = vcnn_act_bwd(act, d->dtype, (size_t)d->n * d->c * oh * ow, y, dy, workspace, stream)) return s;
+    delta = workspace;
+  }
+  if (dbias) {
+    float* partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + pool_delta_bytes(*d, oh, ow));
+    if (vcnn_status s = launch_bias_grad(pooled_geom(*d, oh, ow), d->dtype, delta, dbias, partial, (hipStream_t)stream))
+      return s;
+  }
+  return vcnn_pool_bwd(d, delta, argmax, dx, stream);
 }
 
 vcnn_status vcnn_pool_bwd(const vcnn_pool_desc* d, const void* dy, const int32_t* argmax, void* dx, void* stream) {
   int oh, ow;
   if (vcnn_status s = check_pool(d, &oh, &ow)) return s;
   if (!dy || !dx || (!argmax && d->mode == VCNN_POOL_MAX)) return fail(VCNN_ERR_NULL, "pool_bwd: NULL tensor");
-  if (d->mode == VCNN_POOL_AVG) return launch_avgpool(*d, oh, ow, dy, dx, true, (hipStream_t)stream);
+  if (d->mode == VCNN_POOL_AVG) return launch_avgpool(*d, oh, ow, dy, dx, true, nullptr, VCNN_ACT_NONE, (hipStream_t)stream);
   return launch_pool_bwd(*d, oh, ow, dy, argmax, dx, VCNN_ACT_NONE, nullptr, (hipStream_t)stream);
 }
 
@@ -430,7 +486,7 @@ vcnn_status vcnn_pool_bwd_act(const vcnn_pool_desc* d, int32_t act_below, const 
   if (vcnn_status s = check_pool(d, &oh, &ow)) return s;
   if (!x || !dy || !dx || (!argmax && d->mode == VCNN_POOL_MAX)) return fail(VCNN_ERR_NULL, "pool_bwd_act: NULL tensor");
   if (d->mode == VCNN_POOL_AVG) {  // the transpose of the mean, then the derivative in place
-    if (vcnn_status s = launch_avgpool(*d, oh, ow, dy, dx, true, (hipStream_t)stream)) return s;
+    if (vcnn_status s = launch_avgpool(*d, oh, ow, dy, dx, true, nullptr, VCNN_ACT_NONE, (hipStream_t)stream)) return s;
     return vcnn_act_bwd(act_below, d->dtype, (size_t)d->n * d->c * d->h * d->w, x, dx, dx, stream);
   }
   return launch_pool_bwd(*d, oh, ow, dy, argmax, dx, act_below, x, (hipStream_t)stream);

@@ -188,10 +188,11 @@ vcnn_status launch_relu_fwd(int dtype, size_t count, const void* x, void* y, hip
 vcnn_status launch_relu_bwd(int dtype, size_t count, const void* ref, const void* dy, void* dx, hipStream_t st);
 // tanh / sigmoid: dy == nullptr -> forward from a = x; else backward from a = forward output
 vcnn_status launch_smooth_act(int act, int dtype, size_t count, const void* a, const void* dy, void* out, hipStream_t st);
+// bias (per map, nullable) and act (VCNN_ACT_*): the epilogue of the pooling layer, forward only
 vcnn_status launch_avgpool(const vcnn_pool_desc& d, int oh, int ow, const void* src, void* dst, bool backward,
-                           hipStream_t st);
+                           const float* bias, int act, hipStream_t st);
 vcnn_status launch_pool_fwd(const vcnn_pool_desc& d, int oh, int ow, const void* x, void* y, int32_t* argmax,
-                            hipStream_t st);
+                            const float* bias, int act, hipStream_t st);
 // act / ref: optional activation derivative folded into the store (ref = the pooling input, indexed like dx)
 vcnn_status launch_pool_bwd(const vcnn_pool_desc& d, int oh, int ow, const void* dy, const int32_t* argmax, void* dx,
                             int act, const void* ref,

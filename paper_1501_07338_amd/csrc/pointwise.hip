@@ -87,6 +87,14 @@ __device__ __forceinline__ float smooth_bwd(float y, float g) {
   return ACT == VCNN_ACT_TANH ? g * (1.f - y * y) : g * y * (1.f - y);
 }
 
+// sigma by run-time id (VCNN_ACT_*), for epilogues
+__device__ __forceinline__ float act_apply(int act, float x) {
+  if (act == VCNN_ACT_RELU) return fmaxf(x, 0.f);
+  if (act == VCNN_ACT_TANH) return smooth_fwd<VCNN_ACT_TANH>(x);
+  if (act == VCNN_ACT_SIGMOID) return smooth_fwd<VCNN_ACT_SIGMOID>(x);
+  return x;
+}
+
 template <int ACT, typename T>
 __global__ __launch_bounds__(kThreads) void smooth_fwd_kernel(size_t count, const T* x, T* y) {
   const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
@@ -127,7 +135,8 @@ vcnn_status launch_smooth_act(int act, int dtype, size_t count, const void* a, c
 // paper's nearest-neighbour upscaling).  Plane (n, c) on blockIdx.y / z.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void avgpool_fwd_kernel(vcnn_pool_desc d, int oh_n, int ow_n,
-                                                               const T* __restrict__ x, T* __restrict__ y) {
+                                                               const T* __restrict__ x, T* __restrict__ y,
+                                                               const float* __restrict__ bias, int act) {
   const int o = blockIdx.x * kThreads + threadIdx.x;
   const int64_t nc = (int64_t)blockIdx.z * gridDim.y + blockIdx.y;
   if (o >= oh_n * ow_n || nc >= (int64_t)d.n * d.c) return;
@@ -136,7 +145,9 @@ __global__ __launch_bounds__(kThreads) void avgpool_fwd_kernel(vcnn_pool_desc d,
   float sum = 0.f;
   for (int i = 0; i < d.win_h; ++i)
     for (int j = 0; j < d.win_w; ++j) sum += ld(xp + i * d.w + j);
-  st(y + nc * oh_n * ow_n + o, sum / (float)(d.win_h * d.win_w));
+  float v = sum / (float)(d.win_h * d.win_w);
+  if (bias) v += bias[nc % d.c];
+  st(y + nc * oh_n * ow_n + o, act_apply(act, v));
 }
 
 template <typename T>
@@ -161,7 +172,7 @@ __global__ __launch_bounds__(kThreads) void avgpool_bwd_kernel(vcnn_pool_desc d,
 
 template <typename T>
 static void avgpool_typed(const vcnn_pool_desc& d, int oh, int ow, const void* src, void* dst, bool backward,
-                          hipStream_t st) {
+                          const float* bias, int act, hipStream_t st) {
   const int64_t planes = (int64_t)d.n * d.c;
   const unsigned gy = (unsigned)std::min<int64_t>(planes, 32768);
   const int64_t per_plane = backward ? (int64_t)d.h * d.w : (int64_t)oh * ow;
@@ -169,14 +180,14 @@ static void avgpool_typed(const vcnn_pool_desc& d, int oh, int ow, const void* s
   if (backward)
     hipLaunchKernelGGL(avgpool_bwd_kernel<T>, grid, block, 0, st, d, oh, ow, (const T*)src, (T*)dst);
   else
-    hipLaunchKernelGGL(avgpool_fwd_kernel<T>, grid, block, 0, st, d, oh, ow, (const T*)src, (T*)dst);
+    hipLaunchKernelGGL(avgpool_fwd_kernel<T>, grid, block, 0, st, d, oh, ow, (const T*)src, (T*)dst, bias, act);
 }
 
 vcnn_status launch_avgpool(const vcnn_pool_desc& d, int oh, int ow, const void* src, void* dst, bool backward,
-                           hipStream_t st) {
+                           const float* bias, int act, hipStream_t st) {
   if ((int64_t)d.n * d.c > 32768LL * 65535) return fail(VCNN_ERR_UNSUPPORTED, "pool: too many planes for one launch");
-  if (d.dtype == VCNN_BF16) avgpool_typed<bf16>(d, oh, ow, src, dst, backward, st);
-  else avgpool_typed<float>(d, oh, ow, src, dst, backward, st);
+  if (d.dtype == VCNN_BF16) avgpool_typed<bf16>(d, oh, ow, src, dst, backward, bias, act, st);
+  else avgpool_typed<float>(d, oh, ow, src, dst, backward, bias, act, st);
   return check_launch(backward ? "avgpool_bwd" : "avgpool_fwd");
 }
 
@@ -190,7 +201,8 @@ vcnn_status launch_avgpool(const vcnn_pool_desc& d, int oh, int ow, const void* 
 template <typename T, int WIN, int STRIDE>
 __global__ __launch_bounds__(kThreads) void pool_fwd_kernel(vcnn_pool_desc d, int oh_n, int ow_n, int64_t total,
                                                             const T* __restrict__ x, T* __restrict__ y,
-                                                            int32_t* __restrict__ argmax) {
+                                                            int32_t* __restrict__ argmax,
+                                                            const float* __restrict__ bias, int act) {
   const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   if (idx >= total) return;
   const int win_h = WIN ? WIN : d.win_h, win_w = WIN ? WIN : d.win_w;
@@ -212,7 +224,9 @@ __global__ __launch_bounds__(kThreads) void pool_fwd_kernel(vcnn_pool_desc d, in
         bi = pos;
       }
     }
-  st(y + idx, best);
+  // the per-map bias and sigma of the pooling layer (Eq. 3), when given
+  if (bias) best += bias[nc % d.c];
+  st(y + idx, act_apply(act, best));
   argmax[idx] = bi;
 }
 
@@ -267,18 +281,18 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_kernel(vcnn_pool_desc d, in
 
 template <typename T>
 static vcnn_status pool_fwd_typed(const vcnn_pool_desc& d, int oh, int ow, const void* x, void* y, int32_t* argmax,
-                                  hipStream_t st) {
+                                  const float* bias, int act, hipStream_t st) {
   const int64_t total = (int64_t)d.n * d.c * oh * ow;
   const int64_t blocks = ceil_div(total, kThreads);
   if (blocks > 0x7fffffffLL) return fail(VCNN_ERR_UNSUPPORTED, "pool_fwd: too many outputs for one launch");
   const dim3 grid((unsigned)blocks), block(kThreads);
   const bool square = d.win_h == d.win_w && d.stride_h == d.stride_w;
   if (square && d.win_h == 2 && d.stride_h == 2)
-    hipLaunchKernelGGL((pool_fwd_kernel<T, 2, 2>), grid, block, 0, st, d, oh, ow, total, (const T*)x, (T*)y, argmax);
+    hipLaunchKernelGGL((pool_fwd_kernel<T, 2, 2>), grid, block, 0, st, d, oh, ow, total, (const T*)x, (T*)y, argmax, bias, act);
   else if (square && d.win_h == 3 && d.stride_h == 2)
-    hipLaunchKernelGGL((pool_fwd_kernel<T, 3, 2>), grid, block, 0, st, d, oh, ow, total, (const T*)x, (T*)y, argmax);
+    hipLaunchKernelGGL((pool_fwd_kernel<T, 3, 2>), grid, block, 0, st, d, oh, ow, total, (const T*)x, (T*)y, argmax, bias, act);
   else
-    hipLaunchKernelGGL((pool_fwd_kernel<T, 0, 0>), grid, block, 0, st, d, oh, ow, total, (const T*)x, (T*)y, argmax);
+    hipLaunchKernelGGL((pool_fwd_kernel<T, 0, 0>), grid, block, 0, st, d, oh, ow, total, (const T*)x, (T*)y, argmax, bias, act);
   return VCNN_OK;
 }
 
@@ -400,9 +414,9 @@ static void pool_bwd_typed(const vcnn_pool_desc& d, int oh, int ow, const void* 
 }
 
 vcnn_status launch_pool_fwd(const vcnn_pool_desc& d, int oh, int ow, const void* x, void* y, int32_t* argmax,
-                            hipStream_t st) {
-  const vcnn_status rc = d.dtype == VCNN_BF16 ? pool_fwd_typed<bf16>(d, oh, ow, x, y, argmax, st)
-                                               : pool_fwd_typed<float>(d, oh, ow, x, y, argmax, st);
+                            const float* bias, int act, hipStream_t st) {
+  const vcnn_status rc = d.dtype == VCNN_BF16 ? pool_fwd_typed<bf16>(d, oh, ow, x, y, argmax, bias, act, st)
+                                               : pool_fwd_typed<float>(d, oh, ow, x, y, argmax, bias, act, st);
   if (rc != VCNN_OK) return rc;
   return check_launch("pool_fwd");
 }

@@ -52,6 +52,10 @@ _SIGNATURES = {
     "vcnn_pool_out_shape": (c_int32, [POINTER(PoolDesc), POINTER(c_int32), POINTER(c_int32)]),
     "vcnn_pool_fwd": (c_int32, [POINTER(PoolDesc), c_void_p, c_void_p, c_void_p, c_void_p]),
     "vcnn_pool_bwd": (c_int32, [POINTER(PoolDesc), c_void_p, c_void_p, c_void_p, c_void_p]),
+    "vcnn_pool_layer_fwd": (c_int32, [POINTER(PoolDesc), c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
+    "vcnn_pool_layer_workspace_bytes": (c_int32, [POINTER(PoolDesc), POINTER(c_size_t)]),
+    "vcnn_pool_layer_bwd": (c_int32, [POINTER(PoolDesc), c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                      c_void_p, c_size_t, c_void_p]),
     "vcnn_pool_bwd_act": (c_int32, [POINTER(PoolDesc), c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
     "vcnn_fc_bwd_act": (c_int32, [c_int32, c_int32, c_int32, c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p,
                                   c_void_p, c_void_p, c_void_p]),
@@ -183,6 +187,22 @@ def pool_fwd(d, x, y, argmax, stream=None):
 
 def pool_bwd(d, dy, argmax, dx, stream=None):
     _check(lib().vcnn_pool_bwd(byref(d), _ptr(dy), _ptr(argmax), _ptr(dx), _stream(stream)))
+
+
+def pool_layer_fwd(d, act, x, bias, y, argmax, stream=None):
+    _check(lib().vcnn_pool_layer_fwd(byref(d), act, _ptr(x), _ptr(bias), _ptr(y), _ptr(argmax), _stream(stream)))
+
+
+def pool_layer_workspace_bytes(d):
+    n = c_size_t(0)
+    _check(lib().vcnn_pool_layer_workspace_bytes(byref(d), byref(n)))
+    return n.value
+
+
+def pool_layer_bwd(d, act, y, dy, argmax, dbias, dx, workspace, stream=None):
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().vcnn_pool_layer_bwd(byref(d), act, _ptr(y), _ptr(dy), _ptr(argmax), _ptr(dbias), _ptr(dx),
+                                     _ptr(workspace), nbytes, _stream(stream)))
 
 
 def pool_bwd_act(d, act_below, x, dy, argmax, dx, stream=None):

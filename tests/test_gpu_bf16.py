@@ -10,7 +10,7 @@ from oracle.net import train_step as oracle_step
 from paper_1501_07338_amd import vcnn
 from paper_1501_07338_amd import workloads as wl
 from paper_1501_07338_amd.net import TrainStep
-from util import TOL_BF16, TOL_F32, assert_close, to_np
+from util import TOL_BF16, TOL_F32, assert_close, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -273,3 +273,44 @@ def test_smooth_sigma_and_avgpool_bf16():
     dxp = torch.empty((3, 4, 15, 15), dtype=torch.bfloat16, device=DEV)
     vcnn.pool_bwd(d, gd, None, dxp)
     assert_close(f32_of(dxp), O.avgpool_bwd(g, (15, 15), (3, 3), (2, 2)), TOL_BF16, "bf16 avgpool dx")
+
+
+@pytest.mark.parametrize("mode", ["max", "avg"])
+def test_pool_layer_bias_sigma_bf16(mode):
+    """Eq. 3's pooling layer on bf16 tensors (tanh); the fused input gradients of pool_bwd_act / fc_bwd_act on bf16."""
+    n, c, h, w = 4, 6, 14, 14
+    x, xd = b16(wl.random_tensor(2600, (n, c, h, w)))
+    bias = wl.random_tensor(2601, (c,))
+    d = vcnn.pool_desc(n, c, h, w, 2, 2, 2, 2, dtype=vcnn.BF16, mode=vcnn.POOL_MAX if mode == "max" else vcnn.POOL_AVG)
+    y = torch.empty((n, c, 7, 7), dtype=torch.bfloat16, device=DEV)
+    am = torch.empty((n, c, 7, 7), dtype=torch.int32, device=DEV) if mode == "max" else None
+    vcnn.pool_layer_fwd(d, vcnn.ACT_TANH, xd, to_dev(bias), y, am)
+    ry, ram = O.pool_layer_fwd(x, bias, (2, 2), (2, 2), mode, "tanh")
+    assert_close(f32_of(y), ry, TOL_BF16, "bf16 pool layer y")
+    if mode == "max":
+        np.testing.assert_array_equal(am.cpu().numpy(), ram)
+    dy, dyd = b16(wl.random_tensor(2602, (n, c, 7, 7)))
+    dx = torch.empty((n, c, h, w), dtype=torch.bfloat16, device=DEV)
+    db = torch.empty((c,), device=DEV)
+    ws = torch.empty(vcnn.pool_layer_workspace_bytes(d), dtype=torch.uint8, device=DEV)
+    vcnn.pool_layer_bwd(d, vcnn.ACT_TANH, y, dyd, am, db, dx, ws)
+    rdx, rdb, _ = O.pool_layer_bwd(f32_of(y), dy, ram, (h, w), (2, 2), (2, 2), mode, "tanh")
+    assert_close(f32_of(dx), rdx, TOL_BF16, "bf16 pool layer dx")
+    assert_close(db.cpu().numpy(), rdb, TOL_BF16, "bf16 pool layer dbias")
+    # ReLU derivative of the layer below folded into the pooling / fully connected input gradients
+    xr, xrd = b16(np.maximum(x, 0))
+    dx2 = torch.empty_like(dx)
+    vcnn.pool_bwd_act(d, vcnn.ACT_RELU, xrd, dyd, am, dx2)
+    plain = O.maxpool_bwd(dy, ram, (h, w)) if mode == "max" else O.avgpool_bwd(dy, (h, w), (2, 2), (2, 2))
+    assert_close(f32_of(dx2), O.relu_bwd(xr, plain), TOL_BF16, "bf16 pool dx * relu'")
+    b, i, o = 32, 96, 40
+    xf, xfd = b16(np.maximum(wl.random_tensor(2603, (b, i)), 0))
+    wf, wfd = b16(wl.random_tensor(2604, (o, i), scale=0.2))
+    gf, gfd = b16(wl.random_tensor(2605, (b, o)))
+    dxf = torch.empty((b, i), dtype=torch.bfloat16, device=DEV)
+    dwf, dbf = torch.empty((o, i), device=DEV), torch.empty((o,), device=DEV)
+    vcnn.fc_bwd_act(vcnn.BF16, b, i, o, vcnn.ACT_RELU, xfd, wfd, gfd, dwf, dbf, dxf)
+    rdw, rdbf, rdxf = O.fc_bwd(xf, wf, gf)
+    assert_close(f32_of(dxf), O.relu_bwd(xf, rdxf), TOL_BF16, "bf16 fc dx * relu'")
+    assert_close(dwf.cpu().numpy(), rdw, TOL_BF16, "bf16 fc dw")
+    assert_close(dbf.cpu().numpy(), rdbf, TOL_BF16, "bf16 fc db")

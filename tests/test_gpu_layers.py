@@ -214,6 +214,44 @@ def test_pool_bwd_with_activation_derivative_folded(shape, act):
     assert_close(to_np(dx), _sigma_bwd(act, x, O.avgpool_bwd(dy, (h, w), (win, win), (st, st))), 1e-6, "avgpool dx * sigma'")
 
 
+_ACT_NAME = {vcnn.ACT_NONE: "none", vcnn.ACT_RELU: "relu", vcnn.ACT_TANH: "tanh", vcnn.ACT_SIGMOID: "sigmoid"}
+
+
+@pytest.mark.parametrize("mode", ["max", "avg"])
+@pytest.mark.parametrize("act", [vcnn.ACT_NONE, vcnn.ACT_RELU, vcnn.ACT_TANH, vcnn.ACT_SIGMOID])
+@pytest.mark.parametrize("shape", [(3, 5, 24, 24, 2, 2), (2, 7, 32, 32, 3, 2), (130, 20, 9, 11, 2, 1), (1, 1, 3, 3, 3, 3)])
+def test_pool_layer_bias_sigma(shape, act, mode):
+    """The pooling layer of Eq. 3, y = sigma(pool(x) + b), and its gradients (dx, dbias) against the oracle."""
+    n, c, h, w, win, st = shape
+    x, bias = random_tensor(820, (n, c, h, w)), random_tensor(821, (c,))
+    d = vcnn.pool_desc(n, c, h, w, win, win, st, st, mode=vcnn.POOL_MAX if mode == "max" else vcnn.POOL_AVG)
+    oh, ow = vcnn.pool_out_shape(d)
+    y = torch.full((n, c, oh, ow), float("nan"), device=DEV)
+    am = torch.full((n, c, oh, ow), -7, dtype=torch.int32, device=DEV) if mode == "max" else None
+    vcnn.pool_layer_fwd(d, act, to_dev(x), to_dev(bias), y, am)
+    ry, ram = O.pool_layer_fwd(x, bias, (win, win), (st, st), mode, _ACT_NAME[act])
+    assert_close(to_np(y), ry, 1e-6, "pool layer y")
+    if mode == "max":
+        np.testing.assert_array_equal(to_np(am), ram)
+    # backward from the GPU's own fp32 output, so both sides evaluate sigma' at the same point
+    y32 = to_np(y)
+    dy = random_tensor(822, (n, c, oh, ow))
+    dx = torch.full((n, c, h, w), float("nan"), device=DEV)
+    db = torch.full((c,), float("nan"), device=DEV)
+    ws = torch.empty(max(vcnn.pool_layer_workspace_bytes(d), 16), dtype=torch.uint8, device=DEV)
+    vcnn.pool_layer_bwd(d, act, y, to_dev(dy), am, db, dx, ws)
+    rdx, rdb, _ = O.pool_layer_bwd(y32, dy, ram, (h, w), (win, win), (st, st), mode, _ACT_NAME[act])
+    assert_close(to_np(dx), rdx, 1e-6, "pool layer dx")
+    assert_close(to_np(db), rdb, TOL_F32, "pool layer dbias")
+    # without the bias gradient; a workspace that is too small is refused before any launch
+    dx2 = torch.full((n, c, h, w), float("nan"), device=DEV)
+    vcnn.pool_layer_bwd(d, act, y, to_dev(dy), am, None, dx2, ws)
+    assert torch.equal(dx, dx2)
+    if act != vcnn.ACT_NONE:
+        with pytest.raises(vcnn.VcnnError):
+            vcnn.pool_layer_bwd(d, act, y, to_dev(dy), am, db, dx2, ws[:8])
+
+
 @pytest.mark.parametrize("act", [vcnn.ACT_RELU, vcnn.ACT_TANH, vcnn.ACT_SIGMOID])
 @pytest.mark.parametrize("b,i,o", [(128, 800, 500), (128, 500, 10), (7, 33, 5), (256, 2048, 1000)])
 def test_fc_bwd_with_activation_derivative_folded(b, i, o, act):
