@@ -11,6 +11,7 @@
 // gather form): dx is the correlation of dy with the flipped, channel-transposed kernels, which a small
 // kernel writes to the workspace first.
 #include <algorithm>
+#include <type_traits>
 
 #include "common.h"
 #include "elem.h"
@@ -211,6 +212,159 @@ __global__ __launch_bounds__(kThreads) void conv_halo_kernel(HaloArgs a) {
   }
 }
 
+// The same kernel for 33..48 output maps (BM = 48), on the 16 x 16 x 4 form of the instruction: 32-row tiles
+// would run such a layer as 64 rows, a quarter of them padding.  Every wave holds all 48 rows (three 16-row
+// tiles) for WN of the block's pixels.  Lane l feeds row / pixel l % 16 and, of a group of 16 contraction
+// indices, the four 4*(l / 16) + [0, 4): step i of the group contracts index 4*(l / 16) + i on every lane,
+// the kernel-matrix slab and the tap table being read with the same permutation.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <int BM, int BN, int WN, int BK, bool VEC, typename T>
+__global__ __launch_bounds__(kThreads) void conv_halo16_kernel(HaloArgs a) {
+  static_assert((BN / WN) * 64 == kThreads, "four waves per block, side by side along the pixels");
+  static_assert(BM % 16 == 0 && WN % 16 == 0 && BK % 16 == 0, "16-wide tiles");
+  using LA = LdsTile<BM, BK, true>;
+  using SA = Stager<BM, BK, kThreads, true, VEC>;
+  constexpr int TM = BM / 16, TN = WN / 16;
+  extern __shared__ float4 smem4[];
+  float* const As0 = reinterpret_cast<float*>(smem4);              // 2 slabs of the kernel matrix
+  int* const tapoff = reinterpret_cast<int*>(As0 + 2 * LA::SIZE);  // [kch]
+  float* const halo = As0 + 2 * LA::SIZE + a.kch;                  // [cc][nr][wp]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l16 = lane & 15, kq = lane >> 4;
+  const int tm = blockIdx.x % a.tiles_m;
+  const int tj = blockIdx.x / a.tiles_m;
+  const int n = tj / a.tiles_per_img;
+  const int p0 = (tj - n * a.tiles_per_img) * BN;
+  const int i0 = tm * BM;
+  const int wn0 = wave * WN;
+  const int RS = a.r * a.s;
+  const int K = a.c * RS;
+  const int plane = a.nr * a.wp;
+  const int oh_first = p0 / a.ow;
+
+  for (int kk = tid; kk < a.kch; kk += kThreads) {  // tap table, as above
+    int off = 0;
+    if (kk < a.cc * RS) {
+      const int cl = kk / RS;
+      const int q = kk - cl * RS;
+      const int r = q / a.s;
+      off = cl * plane + r * a.wp + (q - r * a.s);
+    }
+    tapoff[kk] = off;
+  }
+
+  int lane_base[TN];
+#pragma unroll
+  for (int ni = 0; ni < TN; ++ni) {
+    const int p = min(p0 + wn0 + ni * 16 + l16, a.P - 1);
+    const int oh = p / a.ow;
+    lane_base[ni] = (oh - oh_first) * a.wp + (p - oh * a.ow);
+  }
+
+  SA sa;
+  sa.init(tid);
+  int64_t a_off[SA::SLOTS];
+  bool a_row_ok[SA::SLOTS];
+#pragma unroll
+  for (int e = 0; e < SA::SLOTS; ++e) {
+    const int i = i0 + sa.line(e);
+    a_row_ok[e] = i < a.m && sa.line(e) < BM;
+    a_off[e] = (int64_t)(a_row_ok[e] ? i : 0) * K;
+  }
+
+  f32x4 acc[TM][TN];
+#pragma unroll
+  for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) acc[mi][ni][q] = 0.f;
+
+  const T* xin = static_cast<const T*>(a.x) + (int64_t)n * a.c * a.h * a.w;
+  const T* wgt = static_cast<const T*>(a.wgt);
+  T* yout = static_cast<T*>(a.y);
+  const int slabs = a.kch / BK;
+
+  for (int c0 = 0; c0 < a.c; c0 += a.cc) {
+    const int cc = min(a.cc, a.c - c0);
+    const int kbase = c0 * RS;
+    const int klen = cc * RS;
+    auto fetch = [&](int sl) {
+#pragma unroll
+      for (int e = 0; e < SA::SLOTS; ++e) {
+        const int kk = sl * BK + sa.c;
+        sa.ok[e] = a_row_ok[e] && kk < klen;
+        const T* src = wgt + a_off[e] + kbase + min(kk, klen - (VEC ? 4 : 1));
+        if (VEC) {
+          const float4 t = ld4(src);
+          sa.v[e][0] = t.x, sa.v[e][1] = t.y, sa.v[e][2] = t.z, sa.v[e][3] = t.w;
+        } else {
+          sa.v[e][0] = ld(src);
+        }
+      }
+    };
+    fetch(0);
+    __syncthreads();  // previous chunk's MFMAs are done with the halo tile and the A slabs
+    stage_halo<8>(halo, xin + (int64_t)c0 * a.h * a.w, cc, cc, a.nr, a.wp, a.h, a.w, oh_first - a.ph, a.pw, tid);
+    sa.store(As0);
+    __syncthreads();
+
+    for (int sl = 0; sl < slabs; ++sl) {
+      const int cur = sl & 1;
+      if (sl * BK >= klen) break;
+      const bool more = (sl + 1) * BK < klen;
+      if (more) fetch(sl + 1);
+      const float* As = As0 + cur * LA::SIZE;
+      const int* toff = tapoff + sl * BK;
+#pragma unroll
+      for (int t = 0; t < BK / 16; ++t) {
+        float4 af[TM];
+#pragma unroll
+        for (int mi = 0; mi < TM; ++mi)
+          af[mi] = *reinterpret_cast<const float4*>(As + (mi * 16 + l16) * LA::PITCH + 16 * t + 4 * kq);
+        const int4 o4 = *reinterpret_cast<const int4*>(toff + 16 * t + 4 * kq);
+        const int o[4] = {o4.x, o4.y, o4.z, o4.w};
+        float bf[TN][4];
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) bf[ni][i] = halo[lane_base[ni] + o[i]];
+        const float* afl = reinterpret_cast<const float*>(af);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < TN; ++ni)
+              acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x4f32(afl[mi * 4 + i], bf[ni][i], acc[mi][ni], 0, 0, 0);
+      }
+      if (more) sa.store(As0 + (cur ^ 1) * LA::SIZE);
+      __syncthreads();
+    }
+  }
+
+  // 16 x 16 result: register q of lane l holds row 4*(l / 16) + q, column l % 16
+#pragma unroll
+  for (int ni = 0; ni < TN; ++ni) {
+    const int p = p0 + wn0 + ni * 16 + l16;
+    if (p >= a.P) continue;
+#pragma unroll
+    for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int i = i0 + mi * 16 + 4 * kq + q;
+        if (i < a.m) {
+          float v = acc[mi][ni][q];
+          if (a.bias) v += a.bias[i];
+          if (a.relu) v = fmaxf(v, 0.f);
+          st(yout + ((int64_t)n * a.m + i) * a.P + p, v);
+        }
+      }
+  }
+}
+
 // w2[c][m][r'][s'] = w[m][c][R-1-r'][S-1-s']: the kernel matrix of the input-gradient correlation.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void flip_transpose_kernel(const T* __restrict__ w, T* __restrict__ w2, int M,
@@ -237,7 +391,7 @@ vcnn_status launch_flip_transpose(int dtype, const void* w, void* w2, int M, int
 // ---- planning -------------------------------------------------------------------------------------------
 static constexpr size_t kLdsBudget = 76 * 1024;  // two blocks per CU out of 160 KB
 
-static int halo_bm(int m) { return m <= 32 ? 32 : (m <= 64 ? 64 : 128); }
+static int halo_bm(int m) { return m <= 32 ? 32 : (m <= 48 ? 48 : (m <= 64 ? 64 : 128)); }
 // Pixel tile: the widest tile unless a narrower one pads a small image less.  Narrow tiles do fewer MFMAs
 // per LDS read, so they carry a handicap - but only once the launch fills the chip; below that, more and
 // shorter blocks win.
@@ -323,6 +477,36 @@ static void launch_halo(const HaloArgs& a, const HaloPlan& p, bool vec, int dtyp
   }
 }
 
+template <int BN, bool VEC, typename T>
+static void launch_halo16_one(const HaloArgs& a, const HaloPlan& p, hipStream_t st) {
+  const dim3 grid((unsigned)((int64_t)a.tiles_m * a.n * a.tiles_per_img)), block(kThreads);
+  auto kernel = conv_halo16_kernel<48, BN, BN / 4, 64, VEC, T>;
+  static bool opted = false;
+  if (!opted) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)kLdsBudget);
+    opted = true;
+  }
+  hipLaunchKernelGGL(kernel, grid, block, p.lds_bytes, st, a);
+}
+
+// 48-row tiles: pixel tiles of 256, 128 or 64
+static void launch_halo16(const HaloArgs& a, const HaloPlan& p, bool vec, int dtype, hipStream_t st) {
+  auto go = [&](auto bn_tag) {
+    constexpr int BN = decltype(bn_tag)::value;
+    if (dtype == VCNN_BF16) {
+      if (vec) launch_halo16_one<BN, true, bf16>(a, p, st);
+      else launch_halo16_one<BN, false, bf16>(a, p, st);
+    } else {
+      if (vec) launch_halo16_one<BN, true, float>(a, p, st);
+      else launch_halo16_one<BN, false, float>(a, p, st);
+    }
+  };
+  if (p.bn == 256) go(std::integral_constant<int, 256>{});
+  else if (p.bn == 128) go(std::integral_constant<int, 128>{});
+  else go(std::integral_constant<int, 64>{});
+}
+
 vcnn_status launch_conv_halo(const HaloPlan& p, int dtype, int n, int c, int h, int w, int m, int r, int s, int ph,
                              int pw, const void* x, const void* wgt, const float* bias, void* y, int relu,
                              hipStream_t st) {
@@ -339,6 +523,8 @@ vcnn_status launch_conv_halo(const HaloPlan& p, int dtype, int n, int c, int h, 
     launch_halo<32, 256, 32, 64, 64>(a, p, vec, dtype, st);
   else if (p.bm == 32)
     launch_halo<32, 128, 32, 32, 64>(a, p, vec, dtype, st);
+  else if (p.bm == 48)
+    launch_halo16(a, p, vec, dtype, st);
   else if (p.bm == 64 && p.bn == 256)
     launch_halo<64, 256, 64, 64, 64>(a, p, vec, dtype, st);
   else if (p.bm == 64 && p.bn == 128)
