@@ -19,9 +19,12 @@
 //    maps; partial sums are added in a fixed order through LDS at the end).
 //
 // Contraction order: (channel group of 8, r, s, channel in group); a step contracts two (group, tap)
-// pairs, lanes 0-31 the even one and lanes 32-63 the odd one.  The input gradient is the same kernel
+// pairs, lanes 0-31 the even one and lanes 32-63 the odd one.  Layers with 33..48 output maps (M16) run on
+// v_mfma_f32_16x16x32_bf16 instead - three 16-row tiles per wave rather than 64 rows a quarter of which is
+// padding; there a step contracts four pairs, lanes 16 k .. 16 k + 15 the k-th of them.  The input gradient is the same kernel
 // run on dy with the flipped, transposed kernels (the re-ordering pass does the flip).
 #include <algorithm>
+#include <type_traits>
 
 #include "common.h"
 #include "elem.h"
@@ -29,6 +32,7 @@
 namespace vcnn {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 static constexpr int kThreads = 256;
@@ -50,6 +54,9 @@ __device__ __forceinline__ void load_to_lds16(const uint4* src, uint4* lds_base)
 
 __device__ __forceinline__ f32x16 mfma_bf16(uint4 a, uint4 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x4 mfma_bf16(uint4 a, uint4 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
 // x8[n][g][pos][c8] = x[n][8g + c8][pos], zero for channels >= C; x8[total] = 0 (the padding source)
@@ -74,12 +81,13 @@ __global__ __launch_bounds__(kThreads) void interleave_channels_kernel(const bf1
 }
 
 // wf[mt][ch][jl][lane][c8] = w(row = 32 mt + lane % 32, channel = 8 (ch*cgc + gl) + c8, tap q) where
-// (gl, q) = divmod(2 jl + lane / 32, RS); zero outside the matrix or the chunk.
+// (gl, q) = divmod(2 jl + lane / 32, RS); zero outside the matrix or the chunk.  With m16: row = 16 mt + lane % 16
+// and (gl, q) = divmod(4 jl + lane / 16, RS).
 // w(row, channel, q) = in[row*so + channel*si + (flip ? RS-1-q : q)].
 __global__ __launch_bounds__(kThreads) void reorder_weights_frag_kernel(const bf16* __restrict__ in, bf16* __restrict__ out,
                                                                         int CO, int CI, int RS, int64_t so, int64_t si,
                                                                         int flip, int cgc, int nchunks, int steps,
-                                                                        int64_t total) {
+                                                                        int m16, int64_t total) {
   const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   if (i >= total) return;
   const int c8 = (int)(i & 7);
@@ -89,8 +97,8 @@ __global__ __launch_bounds__(kThreads) void reorder_weights_frag_kernel(const bf
   t /= steps;
   const int ch = (int)(t % nchunks);
   const int mt = (int)(t / nchunks);
-  const int row = mt * 32 + (lane & 31);
-  const int u = 2 * jl + (lane >> 5);
+  const int row = m16 ? mt * 16 + (lane & 15) : mt * 32 + (lane & 31);
+  const int u = m16 ? 4 * jl + (lane >> 4) : 2 * jl + (lane >> 5);
   const int gl = u / RS, q = u - gl * RS;
   const int c = (ch * cgc + gl) * 8 + c8;
   bf16 v;
@@ -114,29 +122,35 @@ struct HaloBf16Args {
   int relu;
 };
 
-template <int WAVES_M, int WAVES_K, int TM, int TN>
+template <int WAVES_M, int WAVES_K, int TM, int TN, bool M16 = false>
 __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Args a) {
   static_assert(WAVES_M * WAVES_K * 64 == kThreads, "four waves per block");
-  constexpr int BM = 32 * TM * WAVES_M, BN = 32 * TN;
+  static_assert(!M16 || WAVES_M == 1, "16-row tiles: every wave holds all rows");
+  constexpr int TILE = M16 ? 16 : 32;     // rows and pixels of one accumulator tile
+  constexpr int AQ = M16 ? 4 : 16;        // accumulator registers per tile
+  constexpr int SPS = M16 ? 2 : 4;        // MFMA steps per slab of 8 (group, tap) pairs
+  using Acc = typename std::conditional<M16, f32x4, f32x16>::type;
+  constexpr int BM = TILE * TM * WAVES_M, BN = TILE * TN;
   extern __shared__ uint4 smem16[];
   int* const tbl = reinterpret_cast<int*>(smem16);  // [uch], per slab of 8 pairs: [half][4]
   int* const nxt = tbl + a.uch;                     // [uch/8 + 4]: next slab with work, first such slab per wave
   uint4* const hbuf = smem16 + a.uch / 4 + (a.uch / 8 + 7) / 4;  // 2 x [cgc][nr][wp], each padded to hpos positions
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int l32 = lane & 31, half = lane >> 5;
+  const int lcol = lane & (TILE - 1), half = lane / TILE;  // tile column / row of this lane, its pair of the step
   const int wave_m = wave % WAVES_M, wave_k = wave / WAVES_M;
   const int tm = blockIdx.x % a.tiles_m;
   const int tj = blockIdx.x / a.tiles_m;
   const int n = tj / a.tiles_per_img;
   const int p0 = (tj - n * a.tiles_per_img) * BN;
-  const int i0 = tm * BM + wave_m * 32 * TM;  // first output map of this wave
+  const int i0 = tm * BM + wave_m * TILE * TM;  // first output map of this wave
   const int RS = a.r * a.s;
   const int plane = a.nr * a.wp;
   const int oh_first = p0 / a.ow;
 
   // table: position offset of pair u = (group gl, tap q) inside the halo tile; padding pairs point at 0
-  // (their kernel-matrix entries are zero).  Entry u = 8*sl + 2*i + h is stored at 8*sl + 4*h + i.
+  // (their kernel-matrix entries are zero).  Entry u = 8*sl + 2*i + h is stored at 8*sl + 4*h + i (M16: entry
+  // 8*sl + 4*i + h at 8*sl + 2*h + i), so a lane reads the offsets of all its steps of a slab as one vector.
   for (int u = tid; u < a.uch; u += kThreads) {
     int off = 0;
     if (u < a.cgc * RS) {
@@ -146,13 +160,13 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
       off = gl * plane + r * a.wp + (q - r * a.s);
     }
     const int sl = u >> 3, w8 = u & 7;
-    tbl[sl * 8 + (w8 & 1) * 4 + (w8 >> 1)] = off;
+    tbl[sl * 8 + (M16 ? (w8 & 3) * 2 + (w8 >> 2) : (w8 & 1) * 4 + (w8 >> 1))] = off;
   }
 
   int lane_base[TN];
 #pragma unroll
   for (int ni = 0; ni < TN; ++ni) {
-    const int p = min(p0 + ni * 32 + l32, a.P - 1);
+    const int p = min(p0 + ni * TILE + lcol, a.P - 1);
     const int oh = p / a.ow;
     lane_base[ni] = (oh - oh_first) * a.wp + (p - oh * a.ow);
   }
@@ -180,26 +194,26 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
     }
   }
 
-  f32x16 acc[TM][TN];
+  Acc acc[TM][TN];
 #pragma unroll
   for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
     for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
-      for (int q = 0; q < 16; ++q) acc[mi][ni][q] = 0.f;
+      for (int q = 0; q < AQ; ++q) acc[mi][ni][q] = 0.f;
 
   const uint4* x8n = a.x8 + (int64_t)n * a.cg * a.h * a.w;
-  const int steps = a.uch / 2;                               // fragment steps per chunk
+  const int steps = a.uch / 8 * SPS;                         // fragment steps per chunk
   const int chunk_slabs = a.uch / 8;
   const int64_t mstride = (int64_t)a.nchunks * steps * 64;   // fragments per row tile
-  const uint4* wf0 = a.wf + (int64_t)(i0 / 32) * mstride + lane;
+  const uint4* wf0 = a.wf + (int64_t)(i0 / TILE) * mstride + lane;
 
   // A fragments of the slab this wave works on next: af[step in slab][row tile]
-  uint4 af[4][TM];
+  uint4 af[SPS][TM];
   auto load_a = [&](int ch, int sl) {
-    const uint4* src = wf0 + ((int64_t)ch * steps + sl * 4) * 64;
+    const uint4* src = wf0 + ((int64_t)ch * steps + sl * SPS) * 64;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < SPS; ++i)
 #pragma unroll
       for (int mi = 0; mi < TM; ++mi) af[i][mi] = src[mi * mstride + i * 64];
   };
@@ -251,11 +265,17 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
         if (ch + 1 < a.nchunks) nch = ch + 1, nsl = first_sl;
         else nsl = sl;
       }
-      const uint4* nsrc = wf0 + ((int64_t)nch * steps + nsl * 4) * 64;
-      const int4 o4 = *reinterpret_cast<const int4*>(tbl + sl * 8 + half * 4);
-      const int o[4] = {o4.x, o4.y, o4.z, o4.w};
+      const uint4* nsrc = wf0 + ((int64_t)nch * steps + nsl * SPS) * 64;
+      int o[4];
+      if (M16) {
+        const int2 o2 = *reinterpret_cast<const int2*>(tbl + sl * 8 + half * 2);
+        o[0] = o2.x, o[1] = o2.y;
+      } else {
+        const int4 o4 = *reinterpret_cast<const int4*>(tbl + sl * 8 + half * 4);
+        o[0] = o4.x, o[1] = o4.y, o[2] = o4.z, o[3] = o4.w;
+      }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < SPS; ++i) {
         uint4 bfr[TN], cur[TM];
 #pragma unroll
         for (int ni = 0; ni < TN; ++ni) bfr[ni] = halo[lane_base[ni] + o[i]];
@@ -277,7 +297,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
 
   // contraction split between waves: add the partial sums in wave order through LDS
   if (WAVES_K > 1) {
-    float* red = reinterpret_cast<float*>(smem16);  // [TM*TN*16][64 lanes]
+    float* red = reinterpret_cast<float*>(smem16);  // [TM*TN*AQ][64 lanes]
 #pragma unroll 1
     for (int k = 1; k < WAVES_K; ++k) {
       __syncthreads();
@@ -287,7 +307,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
 #pragma unroll
           for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
-            for (int q = 0; q < 16; ++q) red[(((wave_m * TM + mi) * TN + ni) * 16 + q) * 64 + lane] = acc[mi][ni][q];
+            for (int q = 0; q < AQ; ++q) red[(((wave_m * TM + mi) * TN + ni) * AQ + q) * 64 + lane] = acc[mi][ni][q];
       }
       __syncthreads();
       if (wave_k == 0) {
@@ -296,7 +316,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
 #pragma unroll
           for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
-            for (int q = 0; q < 16; ++q) acc[mi][ni][q] += red[(((wave_m * TM + mi) * TN + ni) * 16 + q) * 64 + lane];
+            for (int q = 0; q < AQ; ++q) acc[mi][ni][q] += red[(((wave_m * TM + mi) * TN + ni) * AQ + q) * 64 + lane];
       }
     }
     if (wave_k != 0) return;
@@ -304,13 +324,14 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
 
 #pragma unroll
   for (int ni = 0; ni < TN; ++ni) {
-    const int p = p0 + ni * 32 + l32;
+    const int p = p0 + ni * TILE + lcol;
     if (p >= a.P) continue;
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
-      for (int q = 0; q < 16; ++q) {
-        const int i = i0 + mi * 32 + 8 * (q >> 2) + 4 * half + (q & 3);
+      for (int q = 0; q < AQ; ++q) {
+        // result tile: 32 x 32 -> row 8*(q/4) + 4*(lane/32) + q%4; 16 x 16 -> row 4*(lane/16) + q; column = lcol
+        const int i = i0 + mi * TILE + (M16 ? 4 * half + q : 8 * (q >> 2) + 4 * half + (q & 3));
         if (i < a.m) {
           float v = acc[mi][ni][q];
           if (a.bias) v += a.bias[i];
@@ -322,7 +343,8 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
 }
 
 // ---- planning ---------------------------------------------------------------------------------------------
-static constexpr int kTnChoices[] = {2, 4, 5};
+static constexpr int kTnChoices[] = {2, 4, 5};     // 32-pixel tiles per wave
+static constexpr int kTn16Choices[] = {4, 8, 10};  // 16-pixel tiles per wave (the same pixel counts)
 
 bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int pw, HaloBf16Plan* p) {
   const int oh = h + 2 * ph - r + 1, ow = w + 2 * pw - s + 1;
@@ -330,22 +352,25 @@ bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph
   const int rs = r * s;
   const int cg = (c + 7) / 8;
   if ((int64_t)cg * h * w > 0x7fffffffLL) return false;  // 32-bit position offsets inside a sample
+  p->m16 = m > 32 && m <= 48;  // three 16-row tiles instead of two 32-row ones
   p->waves_m = m > 128 ? 4 : (m > 64 ? 2 : 1);
-  p->tm = m <= 32 ? 1 : 2;  // 32-row tiles per wave
+  p->tm = p->m16 ? 3 : (m <= 32 ? 1 : 2);  // row tiles per wave
+  const int tile = p->m16 ? 16 : 32, aq = p->m16 ? 4 : 16, sps = p->m16 ? 2 : 4;
   const int waves_k = 4 / p->waves_m;
-  const int bm = 32 * p->tm * p->waves_m;
+  const int bm = tile * p->tm * p->waves_m;
   const int tiles_m = (int)ceil_div(m, bm);
   const int wp = w + 2 * pw;
   // pixel tile: fewest rounds of 512 resident blocks, weighted by the tile width (time per tile)
   const int64_t P = (int64_t)oh * ow;
   int best_tn = 0, best_cgc = 0, best_nr = 0;
   double best_cost = 0;
-  for (int tn : kTnChoices) {
-    const int bn = 32 * tn;
+  for (int k = 0; k < 3; ++k) {
+    const int tn = p->m16 ? kTn16Choices[k] : kTnChoices[k];
+    const int bn = tile * tn;
     int rows = (bn + ow - 2) / ow + 1;
     if (rows > oh) rows = oh;
     const int nr = rows + r - 1;
-    const size_t red_bytes = waves_k > 1 ? (size_t)p->waves_m * p->tm * tn * 16 * 64 * sizeof(float) : 0;
+    const size_t red_bytes = waves_k > 1 ? (size_t)p->waves_m * p->tm * tn * aq * 64 * sizeof(float) : 0;
     if (red_bytes > kLdsBudget) continue;
     int cgc = 0;
     for (int t = 1; t <= cg; ++t) {
@@ -357,7 +382,8 @@ bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph
     if (cgc == 0) continue;
     const int64_t tiles = (int64_t)tiles_m * n * ceil_div(P, bn);
     if (tiles > 0x7fffffffLL) continue;
-    const double cost = (double)ceil_div(tiles, 512) * tn * (1.0 + 0.5 / tn);  // wider tiles reuse A fragments better
+    const double wide = bn / 32.0;
+    const double cost = (double)ceil_div(tiles, 512) * wide * (1.0 + 0.5 / wide);  // wider tiles reuse A fragments better
     if (best_tn == 0 || cost < best_cost - 1e-9) best_tn = tn, best_cgc = cgc, best_nr = nr, best_cost = cost;
   }
   if (best_tn == 0) return false;
@@ -373,18 +399,18 @@ bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph
   }
   p->tn = best_tn, p->cg = cg, p->cgc = pick, p->nchunks = (int)ceil_div(cg, pick), p->nr = best_nr, p->wp = wp;
   p->uch = (int)ceil_div((int64_t)pick * rs, 8) * 8;
-  const size_t red_bytes = waves_k > 1 ? (size_t)p->waves_m * p->tm * best_tn * 16 * 64 * sizeof(float) : 0;
+  const size_t red_bytes = waves_k > 1 ? (size_t)p->waves_m * p->tm * best_tn * aq * 64 * sizeof(float) : 0;
   p->hpos = (int)(((size_t)pick * best_nr * wp + 63) & ~(size_t)63);
   p->lds_bytes = std::max((size_t)p->uch * 4 + ((size_t)p->uch / 8 + 7) / 4 * 16 + 2 * (size_t)p->hpos * 16, red_bytes);
   p->x8_bytes = (((size_t)n * cg * h * w + 1) * 16 + 255) & ~(size_t)255;  // + the block of zeros
-  p->wf_bytes = ((size_t)tiles_m * (bm / 32) * p->nchunks * (p->uch / 2) * 64 * 16 + 255) & ~(size_t)255;
+  p->wf_bytes = ((size_t)tiles_m * (bm / tile) * p->nchunks * (p->uch / 8 * sps) * 64 * 16 + 255) & ~(size_t)255;
   return true;
 }
 
-template <int WAVES_M, int WAVES_K, int TM, int TN>
+template <int WAVES_M, int WAVES_K, int TM, int TN, bool M16 = false>
 static void launch_one(const HaloBf16Args& a, size_t lds, hipStream_t st) {
   const dim3 grid((unsigned)((int64_t)a.tiles_m * a.n * a.tiles_per_img)), block(kThreads);
-  auto kernel = conv_halo_bf16_kernel<WAVES_M, WAVES_K, TM, TN>;
+  auto kernel = conv_halo_bf16_kernel<WAVES_M, WAVES_K, TM, TN, M16>;
   static bool opted = false;  // one flag per instantiation, i.e. per kernel
   if (!opted) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -414,12 +440,14 @@ vcnn_status launch_conv_halo_bf16(const HaloBf16Plan& p, int n, int c, int h, in
                        (const bf16*)x, x8, c, p.cg, h * w, total);
     if (vcnn_status e = check_launch("interleave_channels")) return e;
   }
-  const int bm = 32 * p.tm * p.waves_m;
+  const int tile = p.m16 ? 16 : 32;
+  const int bm = tile * p.tm * p.waves_m;
   const int tiles_m = (int)ceil_div(m, bm);
   {
-    const int64_t total = (int64_t)tiles_m * (bm / 32) * p.nchunks * (p.uch / 2) * 512;
+    const int steps = p.uch / 8 * (p.m16 ? 2 : 4);
+    const int64_t total = (int64_t)tiles_m * (bm / tile) * p.nchunks * steps * 512;
     hipLaunchKernelGGL(reorder_weights_frag_kernel, dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, st,
-                       (const bf16*)wgt, wf, m, c, rs, w_so, w_si, flip, p.cgc, p.nchunks, p.uch / 2, total);
+                       (const bf16*)wgt, wf, m, c, rs, w_so, w_si, flip, p.cgc, p.nchunks, steps, p.m16, total);
     if (vcnn_status e = check_launch("reorder_weights_frag")) return e;
   }
   HaloBf16Args a{};
@@ -428,9 +456,13 @@ vcnn_status launch_conv_halo_bf16(const HaloBf16Plan& p, int n, int c, int h, in
   a.oh = h + 2 * ph - r + 1, a.ow = w + 2 * pw - s + 1;
   a.P = a.oh * a.ow;
   a.tiles_m = tiles_m;
-  a.tiles_per_img = (int)ceil_div(a.P, 32 * p.tn);
+  a.tiles_per_img = (int)ceil_div(a.P, tile * p.tn);
   a.cg = p.cg, a.cgc = p.cgc, a.nchunks = p.nchunks, a.nr = p.nr, a.wp = p.wp, a.uch = p.uch, a.hpos = p.hpos, a.relu = relu;
-  if (p.tn == 2) launch_tn<2>(a, p.waves_m, p.tm, p.lds_bytes, st);
+  if (p.m16) {
+    if (p.tn == 4) launch_one<1, 4, 3, 4, true>(a, p.lds_bytes, st);
+    else if (p.tn == 8) launch_one<1, 4, 3, 8, true>(a, p.lds_bytes, st);
+    else launch_one<1, 4, 3, 10, true>(a, p.lds_bytes, st);
+  } else if (p.tn == 2) launch_tn<2>(a, p.waves_m, p.tm, p.lds_bytes, st);
   else if (p.tn == 4) launch_tn<4>(a, p.waves_m, p.tm, p.lds_bytes, st);
   else launch_tn<5>(a, p.waves_m, p.tm, p.lds_bytes, st);
   return check_launch("conv_halo_bf16");
