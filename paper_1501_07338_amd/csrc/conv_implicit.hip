@@ -396,7 +396,7 @@ static int halo_bm(int m) { return m <= 32 ? 32 : (m <= 48 ? 48 : (m <= 64 ? 64 
 // per LDS read, so they carry a handicap - but only once the launch fills the chip; below that, more and
 // shorter blocks win.
 static int halo_bn(int m, int64_t P, int n) {
-  const int widest = m <= 64 ? 256 : 128;
+  const int widest = m <= 32 ? 512 : (m <= 64 ? 256 : 128);
   const int64_t row_tiles = ceil_div(m, halo_bm(m));
   int best = 0;
   double best_cost = 0;
@@ -519,7 +519,9 @@ vcnn_status launch_conv_halo(const HaloPlan& p, int dtype, int n, int c, int h, 
   a.tiles_per_img = (int)ceil_div(a.P, p.bn);
   a.cc = p.cc, a.nr = p.nr, a.wp = p.wp, a.kch = p.kch, a.relu = relu;
   const bool vec = p.vec && (dtype == VCNN_BF16 ? group_aligned<bf16>(wgt) : group_aligned<float>(wgt));
-  if (p.bm == 32 && p.bn == 256)
+  if (p.bm == 32 && p.bn == 512)
+    launch_halo<32, 512, 32, 128, 64>(a, p, vec, dtype, st);
+  else if (p.bm == 32 && p.bn == 256)
     launch_halo<32, 256, 32, 64, 64>(a, p, vec, dtype, st);
   else if (p.bm == 32)
     launch_halo<32, 128, 32, 32, 64>(a, p, vec, dtype, st);

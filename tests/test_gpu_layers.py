@@ -33,6 +33,7 @@ CONV_SHAPES = [
     (2, 2, 33, 70, 21, 3, 9, 1, 4),     # two input channels, wide rows
     (5, 4, 12, 12, 9, 16, 16, 8, 8),    # kernel larger than the image interior
     (2, 1, 70, 70, 7, 21, 1, 0, 0),     # tall single-column kernel
+    (65, 3, 63, 65, 8, 3, 3, 1, 1),     # at most 32 maps on many large images: the 512-pixel tile
     (2, 6, 40, 40, 48, 5, 5, 2, 2),     # 33..48 output maps: 16-row matrix-core tiles, wide pixel tile
     (3, 38, 14, 14, 38, 3, 3, 1, 1),    # ... in both directions (the input gradient has 38 maps too), small image
     (2, 40, 9, 30, 44, 2, 3, 0, 1),     # ... ragged everything
