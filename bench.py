@@ -251,14 +251,16 @@ def batch_sweep(stream, steps=50):
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/); filled in
 # from the committed summaries, None where no counter run covers the kernel.
 MEASURED_TRAFFIC: dict = {
-    # (2 x FETCH_SIZE + WRITE_SIZE) x 1024 of the call's kernel, profiles/cfg5_cfg4_cfg2_hbm_traffic_pmc.txt
+    # (2 x FETCH_SIZE + WRITE_SIZE) x 1024 of the call's main kernel, profiles/cfg5_cfg4_cfg2_hbm_traffic_pmc.txt
     "cfg2.conv2.fwd": 4.08e6,        # conv_halo_kernel<64, 64, ...>: 1191.5 KiB fetched (x2), 1600 KiB written
-    "cfg5.conv2.fwd": 356.1e6,       # conv_halo_kernel<128, 128, ...>
-    "cfg5.conv2.bwd_filter": 451.7e6,  # conv_halo_filter_kernel<128, 128, ...> (without the slice sum)
-    "cfg5.conv2.bwd_data": 7926.0e6,   # gemm_f32_kernel<128, 128, ...> of the explicit route (without col2im)
+    "cfg2.conv2.bwd_filter": 19.0e6,   # conv_halo_filter_kernel<64, 256, ...> on 256 blocks: 2493 KiB fetched (x2),
+                                       # 13558 KiB of partial products written (then added by sum_slices_wide)
+    "cfg5.conv2.fwd": 356.3e6,       # conv_halo_kernel<128, 128, ...>
+    "cfg5.conv2.bwd_filter": 451.8e6,  # conv_halo_filter_kernel<128, 128, ...> (without the slice sum)
+    "cfg5.conv2.bwd_data": 8007.5e6,   # gemm_f32_kernel<128, 128, ...> of the explicit route (without col2im)
     "cfg5_bf16.conv2.fwd": 199.6e6,    # conv_halo_bf16_kernel<4, 1, 2, 5> (without the two re-layout passes)
-    "cfg5_bf16.conv2.bwd_filter": 422.7e6,  # filter_grad_bf16_kernel<4, 1, 2, 4>
-    "cfg5_bf16.conv2.bwd_data": 738.1e6,    # conv_halo_bf16_kernel<1, 4, 2, 4>: the kernel matrix is re-fetched past L2
+    "cfg5_bf16.conv2.bwd_filter": 426.5e6,  # filter_grad_bf16_kernel<4, 1, 2, 4>
+    "cfg5_bf16.conv2.bwd_data": 632.5e6,    # conv_halo_bf16_kernel<1, 4, 3, 8, true>: the kernel matrix is re-fetched past L2
 }
 
 
