@@ -390,6 +390,10 @@ vcnn_status launch_flip_transpose(int dtype, const void* w, void* w2, int M, int
 
 // ---- planning -------------------------------------------------------------------------------------------
 static constexpr size_t kLdsBudget = 76 * 1024;  // two blocks per CU out of 160 KB
+// 128-row tiles (64 accumulator + about 75 other registers per lane) fit three waves per SIMD and measure
+// faster with three smaller blocks per CU than with two (cfg5 c3 forward 3.29 -> 3.17 ms); the narrower tiles
+// stage their halo tile more often with a smaller budget and lose more than they gain.
+static constexpr size_t kLdsBudget3 = 52 * 1024;
 
 static int halo_bm(int m) { return m <= 32 ? 32 : (m <= 48 ? 48 : (m <= 64 ? 64 : 128)); }
 // Pixel tile: the widest tile unless a narrower one pads a small image less.  Narrow tiles do fewer MFMAs
@@ -426,7 +430,7 @@ bool conv_halo_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int
   for (int cc = 1; cc <= c; ++cc) {
     const int kch = (int)ceil_div((int64_t)cc * rs, BK) * BK;
     const size_t bytes = a_bytes + (size_t)kch * 4 + (size_t)cc * nr * wp * 4;
-    if (bytes > kLdsBudget || kch > 2048) break;
+    if (bytes > (bm == 128 ? kLdsBudget3 : kLdsBudget) || kch > 2048) break;
     best = cc;
   }
   if (best == 0) return false;
@@ -713,7 +717,7 @@ bool conv_halo_filter_plan(const ConvGeom& g, HaloFilterPlan* p) {
     if (rows > g.oh) rows = g.oh;
     const int nr = rows + g.r - 1;
     const size_t bytes = a_bytes + (size_t)bp * 4 + (size_t)p->ccs * nr * p->wp * 4;
-    if (bytes > kLdsBudget) break;
+    if (bytes > (p->bm >= 64 ? kLdsBudget3 : kLdsBudget)) break;
     best = bp;
     if (bp >= g.P) break;
   }

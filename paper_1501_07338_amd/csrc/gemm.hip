@@ -37,7 +37,7 @@ __device__ __forceinline__ int xcd_remap(int bid, int total) {
 
 // TI: element type of A and B in memory (float or bf16); TO: element type of C.  All arithmetic is fp32.
 template <int BM, int BN, int BK, int WM, int WN, bool A_KC, bool B_KC, bool A_VEC, bool B_VEC, typename TI, typename TO>
-__global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmArgs a, int tiles_m, int tiles_total) {
+__global__ __launch_bounds__(kThreads, BK == 16 ? 4 : 1) void gemm_f32_kernel(GemmArgs a, int tiles_m, int tiles_total) {
   static_assert((BM / WM) * (BN / WN) * 64 == kThreads, "four waves per block");
   using LA = LdsTile<BM, BK, A_KC>;
   using LB = LdsTile<BN, BK, B_KC>;
@@ -400,7 +400,7 @@ vcnn_status launch_gemm_f32(const GemmArgs& a, hipStream_t st) {
   else if (a.M <= 64)
     launch_cfg<64, 256, 32, 64, 64>(a, a_kc, b_kc, av, bv, st);
   else
-    launch_cfg<128, 128, 32, 64, 64>(a, a_kc, b_kc, av, bv, st);
+    launch_cfg<128, 128, 16, 64, 64>(a, a_kc, b_kc, av, bv, st);
   return check_launch("gemm_f32");
 }
 
