@@ -326,9 +326,16 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_staged_kernel(vcnn_pool_des
     constexpr int ROWS = WIN && STRIDE ? (WIN + STRIDE - 1) / STRIDE : 1;
     constexpr int COLS = WIN && STRIDE ? (WIN + 2) / STRIDE + 1 : 1;
     const int wq = d.w / 4, items = d.h * wq;
-    for (int e = threadIdx.x; e < np * items; e += kThreads) {
-      const int pl = e / items, rem = e - pl * items;
-      const int hi = rem / wq, w0 = (rem - hi * wq) * 4;
+    // (plane, row, group of four) of item e, advanced by kThreads per pass without divisions
+    const int d_pl = kThreads / items, d_rem = kThreads - d_pl * items;
+    const int d_hi = d_rem / wq, d_wg = d_rem - d_hi * wq;
+    int pl = threadIdx.x / items;
+    int hi = (threadIdx.x - pl * items) / wq;
+    int wg = threadIdx.x - pl * items - hi * wq;
+    for (int e = threadIdx.x; e < np * items; e += kThreads, pl += d_pl, hi += d_hi, wg += d_wg) {
+      if (wg >= wq) wg -= wq, ++hi;
+      if (hi >= d.h) hi -= d.h, ++pl;
+      const int w0 = wg * 4;
       int oh_lo = hi - WIN + 1;
       oh_lo = oh_lo > 0 ? (oh_lo + STRIDE - 1) / STRIDE : 0;
       const int oh_hi = min(oh_n - 1, hi / STRIDE);
@@ -359,9 +366,16 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_staged_kernel(vcnn_pool_des
     }
     return;
   }
-  for (int e = threadIdx.x; e < np * in_plane; e += kThreads) {
-    const int pl = e / in_plane, pos = e - pl * in_plane;
-    const int hi = pos / d.w, wi = pos - hi * d.w;
+  // one pixel per thread; (plane, row, column) advanced by kThreads per pass without divisions
+  const int d_pl = kThreads / in_plane, d_rem = kThreads - d_pl * in_plane;
+  const int d_hi = d_rem / d.w, d_wi = d_rem - d_hi * d.w;
+  int pl = threadIdx.x / in_plane;
+  int hi = (threadIdx.x - pl * in_plane) / d.w;
+  int wi = threadIdx.x - pl * in_plane - hi * d.w;
+  for (int e = threadIdx.x; e < np * in_plane; e += kThreads, pl += d_pl, hi += d_hi, wi += d_wi) {
+    if (wi >= d.w) wi -= d.w, ++hi;
+    if (hi >= d.h) hi -= d.h, ++pl;
+    const int pos = hi * d.w + wi;
     int oh_lo = hi - win_h + 1;
     oh_lo = oh_lo > 0 ? (oh_lo + sh - 1) / sh : 0;
     const int oh_hi = min(oh_n - 1, hi / sh);
@@ -370,11 +384,25 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_staged_kernel(vcnn_pool_des
     const int ow_hi = min(ow_n - 1, wi / sw);
     const int base = pl * out_plane;
     float acc = 0.f;
-    for (int oh = oh_lo; oh <= oh_hi; ++oh)
-      for (int ow = ow_lo; ow <= ow_hi; ++ow) {
-        const int o = base + oh * ow_n + ow;
-        if (am_s[o] == pos) acc += dy_s[o];
-      }
+    if (WIN && STRIDE) {
+      // at most ceil(WIN/STRIDE) windows per axis cover a pixel: a fixed set, visited with a predicate
+      constexpr int CAND = WIN && STRIDE ? (WIN + STRIDE - 1) / STRIDE : 1;
+#pragma unroll
+      for (int a = 0; a < CAND; ++a)
+#pragma unroll
+        for (int b = 0; b < CAND; ++b) {
+          const int oh = oh_lo + a, ow = ow_lo + b;
+          const bool ok = oh <= oh_hi && ow <= ow_hi;
+          const int o = base + (ok ? oh * ow_n + ow : 0);
+          acc += (ok && am_s[o] == pos) ? dy_s[o] : 0.f;
+        }
+    } else {
+      for (int oh = oh_lo; oh <= oh_hi; ++oh)
+        for (int ow = ow_lo; ow <= ow_hi; ++ow) {
+          const int o = base + oh * ow_n + ow;
+          if (am_s[o] == pos) acc += dy_s[o];
+        }
+    }
     if (act) acc = act_grad(act, ld(ref + nc0 * in_plane + e), acc);
     st(dx + nc0 * in_plane + e, acc);
   }
