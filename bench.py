@@ -5,9 +5,9 @@ A "step" is one full training step (forward, cost, backward, SGD update) of a sy
 inputs and weights are already resident in HBM; every arithmetic step runs in libvcnn's HIP kernels.
 The headline line reports images/s on the small recognition CNN (workload cfg2: every operator of
 the path - unrolled convolutions, ReLU, max pooling, fully connected layers, softmax cost - is in
-it).  The step is recorded once into a HIP graph and replayed, so that the launch-bound small layers
-are not dominated by host launch overhead; the eager (one C call per layer pass) rate is reported
-next to it.  Per-layer GFLOP/s of every convolution pass, the roofline figure of the dominant call,
+it).  The step is timed twice - issued eagerly (one C call per layer pass) and replayed from a HIP graph
+recorded once - and the faster of the two is the figure, the other one riding along (`config.launch` says
+which was used).  Per-layer GFLOP/s of every convolution pass, the roofline figure of the dominant call,
 the other four workloads and the CPU-oracle baseline ride along in the same JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--others cfg1,cfg3,cfg4,cfg5]
@@ -97,8 +97,15 @@ def run_workload(name, steps, warmup, layer_iters=10):
     for _ in range(warmup):
         graph.replay()
     graph_ms = timed_steps(graph.replay, steps, stream)
-    res = {"workload": name, "batch": net.batch, "storage_dtype": "bf16" if bf16 else "f32", "ms_per_step": graph_ms, "ms_per_step_eager": eager_ms,
-           "images_per_s": net.batch / (graph_ms * 1e-3), "images_per_s_eager": net.batch / (eager_ms * 1e-3),
+    # The same step, issued two ways: the faster one is the workload's figure (a replayed graph saves host launch
+    # time on the launch-bound small networks; on the large ones it can schedule the two streams' branches worse
+    # than the eager launch order does).
+    best_ms = min(graph_ms, eager_ms)
+    res = {"workload": name, "batch": net.batch, "storage_dtype": "bf16" if bf16 else "f32", "ms_per_step": best_ms,
+           "launch": "one HIP-graph replay per step" if graph_ms <= eager_ms else "eager: one C call per layer pass",
+           "ms_per_step_graph": graph_ms, "ms_per_step_eager": eager_ms,
+           "images_per_s": net.batch / (best_ms * 1e-3), "images_per_s_graph": net.batch / (graph_ms * 1e-3),
+           "images_per_s_eager": net.batch / (eager_ms * 1e-3),
            "loss_after_timed_steps": float(ts.loss.item())}
 
     layers = []
@@ -318,8 +325,8 @@ def main():
         "value": main_res["images_per_s"], "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": WORKLOAD_TEXT.get(args.workload, args.workload), "launch": "one HIP-graph replay per step",
-                   "eager_ms_per_step": main_res["ms_per_step_eager"], "eager_images_per_s": main_res["images_per_s_eager"]},
+        "config": {"workload": WORKLOAD_TEXT.get(args.workload, args.workload), "launch": main_res["launch"],
+                   "graph_ms_per_step": main_res["ms_per_step_graph"], "eager_ms_per_step": main_res["ms_per_step_eager"]},
         "conv_gflops_fwd_bwd": main_res.get("conv_gflops_fwd_bwd"),
         "conv_pct_mfma_f32_peak": main_res.get("conv_pct_mfma_f32_peak"),
         "roofline": main_res["roofline"],
