@@ -330,7 +330,8 @@ vcnn_status vcnn_conv_bwd_filter(const vcnn_conv_desc* d, const void* x, const v
   } else if (plan.path == PATH_FILTER_BF16) {
     if (vcnn_status s = launch_bwd_filter_bf16(plan.fb, g, x, dy, dw, workspace, st)) return s;
   } else if (plan.path == PATH_HALO_FILTER) {
-    if (vcnn_status s = launch_conv_halo_filter(plan.hfp, dt, g, x, dy, dw, (float*)workspace, st)) return s;
+    if (vcnn_status s = launch_conv_halo_filter(plan.hfp, dt, g, x, dy, dw, dbias, (float*)workspace, st)) return s;
+    if (plan.hfp.bias_column) return VCNN_OK;  // the bias gradient came out of the same product
   } else {
     float* partial = (float*)((char*)workspace + col_bytes(g));
     if (vcnn_status s = launch_im2col(g, dt, x, workspace, st)) return s;

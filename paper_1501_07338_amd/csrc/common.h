@@ -111,10 +111,12 @@ struct HaloFilterPlan {
   int runs_per_img, runs_per_split, splits;
   size_t lds_bytes, partial_bytes;
   bool vec;
+  bool bias_column;  // the last column tile has a spare column: it carries the bias gradient (B operand = 1)
 };
 bool conv_halo_filter_plan(const ConvGeom& g, HaloFilterPlan* p);
+// dbias may be null; with p.bias_column it is produced by the same launches, otherwise the caller computes it
 vcnn_status launch_conv_halo_filter(const HaloFilterPlan& p, int dtype, const ConvGeom& g, const void* x, const void* dy,
-                                    float* dw, float* partial, hipStream_t st);
+                                    float* dw, float* dbias, float* partial, hipStream_t st);
 struct FewColsPlan {
   int tm, tn;        // 32-row / 32-column tiles of the whole M x K result
   int nr, wp;

@@ -560,8 +560,9 @@ namespace vcnn {
 struct HaloFilterArgs {
   const void* x;     // [n][c][h][w]     element type T (float or bf16)
   const void* dy;    // [n][m][oh][ow]   element type T
-  float* out;        // [splits][m][c*r*s]
+  float* out;        // [splits][m][Kp]
   int n, c, h, w, m, r, s, ph, pw, oh, ow, P;
+  int Kp;            // row pitch of out: c*r*s, or c*r*s + 1 when column c*r*s carries the bias gradient
   int tiles_m;
   int bp;            // pixels per run (multiple of BK)
   int runs_per_img;
@@ -593,7 +594,9 @@ __global__ __launch_bounds__(kThreads) void conv_halo_filter_kernel(HaloFilterAr
   const int plane = a.nr * a.wp;
   const int c_first = k0 / RS;
 
-  // this lane's kernel-matrix columns: offset of tap (c, r, s) inside the halo tile
+  // this lane's kernel-matrix columns: offset of tap (c, r, s) inside the halo tile.  Column K, when the
+  // output has room for it, is the bias gradient, the sum over pixels of dY times one: its lane reads a plane
+  // of ones kept behind the staged channels (dY is zero beyond a run's last pixel, so the ones need no mask).
   int tap_base[TN];
 #pragma unroll
   for (int ni = 0; ni < TN; ++ni) {
@@ -602,7 +605,10 @@ __global__ __launch_bounds__(kThreads) void conv_halo_filter_kernel(HaloFilterAr
     const int q = col - c * RS;
     const int r = q / a.s;
     tap_base[ni] = (c - c_first) * plane + r * a.wp + (q - r * a.s);
+    if (a.Kp > K && k0 + wn0 + ni * 32 + l32 == K) tap_base[ni] = a.ccs * plane;
   }
+  if (a.Kp > K)
+    for (int e = tid; e < plane; e += kThreads) halo[a.ccs * plane + e] = 1.f;  // published by the first run's barrier
 
   SA sa;
   sa.init(tid);
@@ -681,17 +687,17 @@ __global__ __launch_bounds__(kThreads) void conv_halo_filter_kernel(HaloFilterAr
     }
   }
 
-  float* dst = a.out + (int64_t)blockIdx.y * a.m * K;
+  float* dst = a.out + (int64_t)blockIdx.y * a.m * a.Kp;
 #pragma unroll
   for (int ni = 0; ni < TN; ++ni) {
     const int col = k0 + wn0 + ni * 32 + l32;
-    if (col >= K) continue;
+    if (col >= a.Kp) continue;
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
       for (int q = 0; q < 16; ++q) {
         const int m = i0 + wm0 + mi * 32 + acc_row(q, lane);
-        if (m < a.m) dst[(int64_t)m * K + col] = acc[mi][ni][q];
+        if (m < a.m) dst[(int64_t)m * a.Kp + col] = acc[mi][ni][q];
       }
   }
 }
@@ -735,7 +741,16 @@ bool conv_halo_filter_plan(const ConvGeom& g, HaloFilterPlan* p) {
   if (want < 1) want = 1;
   p->runs_per_split = (int)ceil_div(total_runs, want);
   p->splits = (int)ceil_div(total_runs, p->runs_per_split);
-  p->partial_bytes = p->splits > 1 ? (size_t)p->splits * g.M * g.K * sizeof(float) : 0;
+  // a spare column in the last column tile takes the bias gradient along; its partials then have K + 1 columns and
+  // are split into dW and db by the slice sum even when there is a single slice
+  p->bias_column = g.K % p->bnk != 0;
+  if (p->bias_column) {  // room for the plane of ones, if the budget still holds
+    const size_t with_ones = p->lds_bytes + (size_t)p->nr * p->wp * 4;
+    if (with_ones <= kLdsBudget) p->lds_bytes = with_ones;
+    else p->bias_column = false;
+  }
+  p->partial_bytes = p->bias_column ? (size_t)p->splits * g.M * (g.K + 1) * sizeof(float)
+                                    : (p->splits > 1 ? (size_t)p->splits * g.M * g.K * sizeof(float) : 0);
   p->vec = g.P % 4 == 0;
   return tiles <= 0x7fffffffLL && p->splits <= 65535;
 }
@@ -766,9 +781,11 @@ static void launch_halo_filter(const HaloFilterArgs& a, const HaloFilterPlan& p,
 }
 
 vcnn_status launch_conv_halo_filter(const HaloFilterPlan& p, int dtype, const ConvGeom& g, const void* x, const void* dy,
-                                    float* dw, float* partial, hipStream_t st) {
+                                    float* dw, float* dbias, float* partial, hipStream_t st) {
+  const bool with_bias = p.bias_column && dbias;
   HaloFilterArgs a{};
-  a.x = x, a.dy = dy, a.out = p.splits > 1 ? partial : dw;
+  a.x = x, a.dy = dy, a.out = (p.splits > 1 || with_bias) ? partial : dw;
+  a.Kp = (int)g.K + (with_bias ? 1 : 0);
   a.n = g.n, a.c = g.c, a.h = g.h, a.w = g.w, a.m = g.k, a.r = g.r, a.s = g.s, a.ph = g.ph, a.pw = g.pw;
   a.oh = g.oh, a.ow = g.ow, a.P = (int)g.P;
   a.tiles_m = (int)ceil_div(g.M, p.bm);
@@ -783,6 +800,7 @@ vcnn_status launch_conv_halo_filter(const HaloFilterPlan& p, int dtype, const Co
   else
     launch_halo_filter<128, 128, 64, 64, 32>(a, p, vec, dtype, tiles, st);
   if (vcnn_status s = check_launch("conv_halo_filter")) return s;
+  if (with_bias) return launch_sum_slices_split(partial, dw, dbias, g.M, (int)g.K, p.splits, st);
   if (p.splits == 1) return VCNN_OK;
   return launch_sum_slices(partial, nullptr, dw, VCNN_F32, g.M * g.K, p.splits, 1, 1, 0, st);
 }

@@ -217,9 +217,37 @@ __global__ __launch_bounds__(kThreads) void sum_slices_split_kernel(const float*
   else last[r] = total;
 }
 
+// The same split sum for large results or few slices: one thread per element, slices in ascending order, loads of
+// consecutive threads coalesced.
+__global__ __launch_bounds__(kThreads) void sum_slices_split_plain_kernel(const float* __restrict__ partial,
+                                                                          float* __restrict__ main,
+                                                                          float* __restrict__ last, int64_t rows, int cols,
+                                                                          int splits) {
+  const int64_t count = rows * (cols + 1);
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= count) return;
+  float acc = 0.f;
+  int s = 0;
+  for (; s + 4 <= splits; s += 4) {  // four independent loads in flight, added in ascending order
+    const float v0 = partial[(int64_t)s * count + i], v1 = partial[(int64_t)(s + 1) * count + i];
+    const float v2 = partial[(int64_t)(s + 2) * count + i], v3 = partial[(int64_t)(s + 3) * count + i];
+    acc = (((acc + v0) + v1) + v2) + v3;
+  }
+  for (; s < splits; ++s) acc += partial[(int64_t)s * count + i];
+  const int64_t r = i / (cols + 1);
+  const int c = (int)(i - r * (cols + 1));
+  if (c < cols) main[r * cols + c] = acc;
+  else last[r] = acc;
+}
+
 vcnn_status launch_sum_slices_split(const float* partial, float* main, float* last, int64_t rows, int cols, int splits,
                                     hipStream_t st) {
   const int64_t count = rows * (cols + 1);
+  if (splits < 32 || count > 65536) {
+    hipLaunchKernelGGL(sum_slices_split_plain_kernel, dim3((unsigned)ceil_div(count, kThreads)), dim3(kThreads), 0, st,
+                       partial, main, last, rows, cols, splits);
+    return check_launch("sum_slices_split");
+  }
   hipLaunchKernelGGL(sum_slices_split_kernel, dim3((unsigned)ceil_div(count, 16)), dim3(kThreads), 0, st, partial, main, last,
                      rows, cols, splits);
   return check_launch("sum_slices_split");
