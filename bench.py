@@ -260,14 +260,16 @@ def batch_sweep(stream, steps=50):
 MEASURED_TRAFFIC: dict = {
     # (2 x FETCH_SIZE + WRITE_SIZE) x 1024 of the call's main kernel, profiles/cfg5_cfg4_cfg2_hbm_traffic_pmc.txt
     "cfg2.conv2.fwd": 4.08e6,        # conv_halo_kernel<64, 64, ...>: 1191.5 KiB fetched (x2), 1600 KiB written
-    "cfg2.conv2.bwd_filter": 19.0e6,   # conv_halo_filter_kernel<64, 256, ...> on 256 blocks: 2493 KiB fetched (x2),
-                                       # 13558 KiB of partial products written (then added by sum_slices_wide)
-    "cfg5.conv2.fwd": 356.3e6,       # conv_halo_kernel<128, 128, ...>
-    "cfg5.conv2.bwd_filter": 451.8e6,  # conv_halo_filter_kernel<128, 128, ...> (without the slice sum)
-    "cfg5.conv2.bwd_data": 8007.5e6,   # gemm_f32_kernel<128, 128, ...> of the explicit route (without col2im)
-    "cfg5_bf16.conv2.fwd": 199.6e6,    # conv_halo_bf16_kernel<4, 1, 2, 5> (without the two re-layout passes)
-    "cfg5_bf16.conv2.bwd_filter": 426.5e6,  # filter_grad_bf16_kernel<4, 1, 2, 4>
-    "cfg5_bf16.conv2.bwd_data": 632.5e6,    # conv_halo_bf16_kernel<1, 4, 3, 8, true>: the kernel matrix is re-fetched past L2
+    "cfg2.conv2.bwd_filter": 19.6e6,   # conv_halo_filter_kernel<64, 256, ...> on 256 blocks: 2494 KiB fetched (x2),
+                                       # 14146 KiB of partial products written (then added by sum_slices_split)
+    "cfg2.conv2.bwd_data": 19.2e6,     # gemm_f32_kernel<128, 128, 16, ...> writing the 16 MB patch-matrix gradient
+                                       # (1360 KiB fetched x2, 16000 KiB written; col2im then reads it back)
+    "cfg5.conv2.fwd": 356.1e6,       # conv_halo_kernel<128, 128, ...>
+    "cfg5.conv2.bwd_filter": 479.9e6,  # conv_halo_filter_kernel<128, 128, ...> (without the slice sum)
+    "cfg5.conv2.bwd_data": 7937.3e6,   # gemm_f32_kernel<128, 128, 16, ...> of the explicit route (without col2im)
+    "cfg5_bf16.conv2.fwd": 199.9e6,    # conv_halo_bf16_kernel<4, 1, 2, 5> (without the two re-layout passes)
+    "cfg5_bf16.conv2.bwd_filter": 425.8e6,  # filter_grad_bf16_kernel<4, 1, 2, 4>
+    "cfg5_bf16.conv2.bwd_data": 635.2e6,    # conv_halo_bf16_kernel<1, 4, 3, 8, true>: the kernel matrix is re-fetched past L2
 }
 
 
