@@ -90,7 +90,7 @@ static bool halo_bwd_data_pays(const ConvGeom& g, const HaloPlan& hp) {
 
 // Which realisation a pass uses for a given shape.  The same decision drives the workspace query and
 // the launch, so the two always agree.
-enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER, PATH_HALO, PATH_HALO_FILTER, PATH_HALO_BF16, PATH_FILTER_BF16, PATH_HALO_FILTER_BF16, PATH_FEW_COLS_FILTER };
+enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER, PATH_HALO, PATH_HALO_FILTER, PATH_HALO_BF16, PATH_FILTER_BF16, PATH_HALO_FILTER_BF16, PATH_FEW_COLS_FILTER, PATH_SMALL };
 struct Plan {
   Path path;
   DirectGeom dg;
@@ -146,6 +146,8 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
       p.workspace_bytes = align256(p.partial_bytes);
     } else if (is_pointwise(g)) {
       p.path = PATH_POINTWISE;
+    } else if (algo == VCNN_ALGO_AUTO && g.k > 4 && conv_small_applies(g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw)) {
+      p.path = PATH_SMALL;  // a few hundred MFLOP: latency-bound, one tile per block and the contraction over its waves
     } else if (allow_direct && (g.c > 4 || g.k >= 32 || algo == VCNN_ALGO_IMPLICIT) &&
                conv_halo_plan(g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, &p.hp)) {
       p.path = PATH_HALO;
@@ -164,6 +166,10 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
       p.path = PATH_POINTWISE;
     } else if (allow_direct && g.k <= 4 && direct_bwd_data_geom(g, &p.dg) && direct_few_in_plan(&p.dg, &p.split)) {
       p.path = PATH_FEW_IN;
+    } else if (algo == VCNN_ALGO_AUTO && g.c > 4 && g.r - 1 - g.ph >= 0 && g.s - 1 - g.pw >= 0 &&
+               conv_small_applies(g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw)) {
+      p.path = PATH_SMALL;  // the same latency-bound kernel on dy with the flipped matrix (kept in the workspace)
+      p.workspace_bytes = align256((size_t)g.M * g.K * sizeof(float));
     } else if (allow_direct && g.r - 1 - g.ph >= 0 && g.s - 1 - g.pw >= 0 &&
                conv_halo_plan(g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, &p.hp) &&
                (algo == VCNN_ALGO_IMPLICIT || halo_bwd_data_pays(g, p.hp))) {
@@ -284,6 +290,8 @@ static vcnn_status conv_fwd_linear(const vcnn_conv_desc* d, const ConvGeom& g, c
   if (plan.path == PATH_FEW_OUT)
     return launch_direct_few_out(plan.dg, dt, plan.split, x, w, bias, y, (float*)workspace, relu, st);
   if (plan.path == PATH_FEW_IN) return launch_direct_few_in(plan.dg, dt, plan.split, x, w, bias, y, relu, st);
+  if (plan.path == PATH_SMALL)
+    return launch_conv_small(dt, g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, x, w, bias, y, relu, st);
   if (plan.path == PATH_HALO)
     return launch_conv_halo(plan.hp, dt, g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, x, w, bias, y, relu, st);
   if (plan.path == PATH_HALO_BF16) {
@@ -357,6 +365,11 @@ vcnn_status vcnn_conv_bwd_data(const vcnn_conv_desc* d, const void* w, const voi
     // correlation of dy (k channels) with the flipped kernels into c maps: the re-ordering pass flips and transposes
     return launch_conv_halo_bf16(plan.hb, g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, dy, w,
                                  (int64_t)g.r * g.s, g.K, 1, nullptr, dx, 0, workspace, st);
+  }
+  if (plan.path == PATH_SMALL) {
+    if (vcnn_status s = launch_flip_transpose(dt, w, workspace, g.k, g.c, g.r * g.s, st)) return s;
+    return launch_conv_small(dt, g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, dy, workspace,
+                             nullptr, dx, 0, st);
   }
   if (plan.path == PATH_HALO) {
     if (vcnn_status s = launch_flip_transpose(dt, w, workspace, g.k, g.c, g.r * g.s, st)) return s;

@@ -29,6 +29,13 @@ struct ConvGeom {
 vcnn_status launch_im2col(const ConvGeom& g, int dtype, const void* x, void* col, hipStream_t st);
 vcnn_status launch_col2im(const ConvGeom& g, int dtype, const float* col, void* dx, hipStream_t st);
 
+// ---- conv_small.hip -----------------------------------------------------------------------------
+// Correlation of x [n][c][h][w] with the kernel matrix wgt [m][c*r*s] for small layers: one 32 x 32 tile per block,
+// the contraction split over its waves, the input rows staged in LDS once.
+bool conv_small_applies(int n, int c, int h, int w, int m, int r, int s, int ph, int pw);
+vcnn_status launch_conv_small(int dtype, int n, int c, int h, int w, int m, int r, int s, int ph, int pw, const void* x,
+                              const void* wgt, const float* bias, void* y, int relu, hipStream_t st);
+
 // ---- gemm.hip -----------------------------------------------------------------------------------
 // Generic strided product C(i,j) = act(bias[i] + sum_k A(i,k) B(k,j)), fp32 MFMA.
 //   A(i,k) = A[i*a_si + k*a_sk]

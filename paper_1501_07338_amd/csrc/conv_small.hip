@@ -1,0 +1,213 @@
+// Implicit-unroll convolution for small layers (a few hundred MFLOP: the second layer of the small
+// recognition network at batch 128).  Their cost is latency, not arithmetic: in the slab kernel a block walks
+// the whole contraction K = C*R*S through a chain of fetch -> barrier -> MFMA rounds, and there are too few
+// blocks to fill the chip.  Here a block owns 32 output maps x 32 consecutive output pixels of one sample and
+// its 4 to 8 waves split the contraction (one wave per 64 indices).  The input rows under the pixels (all
+// channels, with halo, zero padded) are staged in LDS once; every wave requests its share of the kernel-matrix
+// rows from global memory before it waits for that tile, so all global latencies overlap; the B operand of
+// each MFMA is then read from the tile at lane_base(pixel) + tap_offset(c, r, s) - the patch-matrix entry of
+// Eq. 2 formed by address arithmetic - and the waves' partial tiles are added in wave order through LDS.
+// Three barriers in all.  The input gradient runs the same kernel on dy with the flipped, channel-transposed
+// kernel matrix (back-propagation paragraph of "Vectorizing Convolution"), which a small pass writes first.
+#include <algorithm>
+
+#include "common.h"
+#include "elem.h"
+#include "mma_core.h"
+
+namespace vcnn {
+
+struct SmallConvArgs {
+  const void* x;      // [n][c][h][w] input of the correlation (forward: x; input gradient: dy)
+  const void* wgt;    // kernel matrix [m][K], K = c*r*s, row-major
+  const float* bias;  // [m] or null
+  void* y;            // [n][m][oh][ow]
+  int n, c, h, w, m, r, s, ph, pw, oh, ow, P;
+  int K, Kp;          // c*r*s, and rounded up to a multiple of 4 (tap-table length)
+  int nr, wp;         // rows and row pitch of the staged tile, per channel
+  int vec_a;          // 16-byte kernel-matrix loads (K % 4 == 0, aligned)
+  int relu;
+  int tiles_m, tiles_per_img, kper;
+};
+
+template <typename T>
+__global__ __launch_bounds__(512) void conv_small_kernel(SmallConvArgs a) {
+  extern __shared__ int small_lds[];
+  int* const tapoff = small_lds;                                         // [Kp]
+  float* const halo = reinterpret_cast<float*>(small_lds + a.Kp);        // [c][nr][wp]
+  const int plane = a.nr * a.wp;
+  float* const red = reinterpret_cast<float*>(small_lds);                // [waves - 1][16][64], reuses table + tile
+  const int waves = blockDim.x >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int RS = a.r * a.s;
+
+  int b = blockIdx.x;
+  const int i0 = (b % a.tiles_m) * 32;
+  b /= a.tiles_m;
+  const int n = b / a.tiles_per_img;
+  const int p0 = (b - n * a.tiles_per_img) * 32;
+  const int oh_first = p0 / a.ow;
+
+  // tap table: offset of tap k = (cc, r, s) inside the tile; padding entries point at 0 (their columns are masked)
+  for (int k = tid; k < a.Kp; k += blockDim.x) {
+    int off = 0;
+    if (k < a.K) {
+      const int cc = k / RS, q = k - cc * RS;
+      const int r = q / a.s;
+      off = cc * plane + r * a.wp + (q - r * a.s);
+    }
+    tapoff[k] = off;
+  }
+  // the tile: input rows oh_first - ph + [0, nr), columns -pw + [0, wp) of every channel, zero outside the image
+  const T* xin = static_cast<const T*>(a.x) + (int64_t)n * a.c * a.h * a.w;
+  for (int e = tid; e < a.c * plane; e += blockDim.x) {
+    const int cl = e / plane, rem = e - cl * plane;
+    const int ry = rem / a.wp, rx = rem - ry * a.wp;
+    const int ih = oh_first - a.ph + ry, iw = rx - a.pw;
+    const bool ok = ih >= 0 && ih < a.h && iw >= 0 && iw < a.w;
+    const float v = ld(xin + (ok ? (cl * a.h + ih) * a.w + iw : 0));
+    halo[e] = ok ? v : 0.f;
+  }
+
+  // this wave's share of the contraction, and the kernel-matrix row of this lane: requested now, used after the barrier
+  const int i = i0 + l32;
+  const bool i_ok = i < a.m;
+  const T* wrow = static_cast<const T*>(a.wgt) + (int64_t)(i_ok ? i : 0) * a.K;
+  const int ks = wave * a.kper, ke = min(a.K, ks + a.kper);  // kper is a multiple of 8
+  constexpr int U = 8;  // groups of 8 contraction indices in flight
+  float av[U][4];
+  auto load_a = [&](int k0) {
+#pragma unroll
+    for (int g = 0; g < U; ++g) {
+      const int kb = k0 + 8 * g + 4 * half;
+      if (a.vec_a) {
+        const bool ok = i_ok && kb < ke;  // K and the split are multiples of 4: a group of four is in or out as a whole
+        const float4 t = ld4(wrow + (ok ? kb : 0));
+        av[g][0] = ok ? t.x : 0.f, av[g][1] = ok ? t.y : 0.f, av[g][2] = ok ? t.z : 0.f, av[g][3] = ok ? t.w : 0.f;
+      } else {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const bool ok = i_ok && kb + u < ke;
+          const float t = ld(wrow + (ok ? kb + u : 0));
+          av[g][u] = ok ? t : 0.f;
+        }
+      }
+    }
+  };
+  load_a(ks);
+  __syncthreads();  // table and tile are complete
+
+  const int p = min(p0 + l32, a.P - 1);  // this lane's pixel (lanes beyond the sample's last pixel repeat it, unused)
+  const int oy = p / a.ow;
+  const int lane_base = (oy - oh_first) * a.wp + (p - oy * a.ow);
+
+  f32x16 acc;
+#pragma unroll
+  for (int q = 0; q < 16; ++q) acc[q] = 0.f;
+  for (int k0 = ks; k0 < ke; k0 += 8 * U) {
+    if (k0 != ks) load_a(k0);
+    float bv[U][4];
+#pragma unroll
+    for (int g = 0; g < U; ++g) {
+      const int kb = min(k0 + 8 * g + 4 * half, a.Kp - 4);  // beyond the share: any valid entry, A is zero there
+      const int4 to = *reinterpret_cast<const int4*>(tapoff + kb);
+      bv[g][0] = halo[lane_base + to.x], bv[g][1] = halo[lane_base + to.y];
+      bv[g][2] = halo[lane_base + to.z], bv[g][3] = halo[lane_base + to.w];
+    }
+#pragma unroll
+    for (int g = 0; g < U; ++g)
+#pragma unroll
+      for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[g][u], bv[g][u], acc, 0, 0, 0);
+  }
+
+  __syncthreads();  // every wave is done with the table and the tile: their memory now takes the partial tiles
+  if (wave > 0) {
+#pragma unroll
+    for (int q = 0; q < 16; ++q) red[((wave - 1) * 16 + q) * 64 + lane] = acc[q];
+  }
+  __syncthreads();
+  if (wave > 0) return;
+  for (int w = 0; w < waves - 1; ++w)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) acc[q] += red[(w * 16 + q) * 64 + lane];
+  if (p0 + l32 >= a.P) return;
+  T* y = static_cast<T*>(a.y);
+#pragma unroll
+  for (int q = 0; q < 16; ++q) {
+    const int row = i0 + acc_row(q, lane);
+    if (row < a.m) {
+      float v = acc[q];
+      if (a.bias) v += a.bias[row];
+      if (a.relu) v = fmaxf(v, 0.f);
+      st(y + ((int64_t)n * a.m + row) * a.P + p, v);
+    }
+  }
+}
+
+static constexpr size_t kSmallLds = 112 * 1024;
+
+// one wave per 64 contraction indices, 4 to 8 of them (more waves cost more LDS for the partial tiles than
+// their shorter shares save)
+static int small_waves(int64_t K) { return (int)std::min<int64_t>(8, std::max<int64_t>(4, ceil_div(K, 64))); }
+
+static size_t small_lds_bytes(int c, int w, int r, int s, int ph, int pw, int64_t K, int* nr_out, int* wp_out) {
+  const int ow = w + 2 * pw - s + 1;
+  const int nr = (32 + ow - 2) / ow + 1 + r - 1, wp = w + 2 * pw;  // rows a run of 32 pixels can touch, plus halo
+  *nr_out = nr, *wp_out = wp;
+  const int64_t Kp = (K + 3) & ~(int64_t)3;
+  const int64_t tile = ((int64_t)c * nr * wp + 3) & ~(int64_t)3;
+  return std::max((size_t)(Kp + tile) * 4, (size_t)(small_waves(K) - 1) * 16 * 64 * sizeof(float));
+}
+
+// Small enough that latency, not arithmetic, is the cost: at most 768 tiles and 2^29 multiply-adds; the
+// contraction between 64 and 4096; tap table, tile and partial sums within the LDS of one block.
+bool conv_small_applies(int n, int c, int h, int w, int m, int r, int s, int ph, int pw) {
+  const int oh = h + 2 * ph - r + 1, ow = w + 2 * pw - s + 1;
+  if (oh <= 0 || ow <= 0) return false;
+  const int64_t K = (int64_t)c * r * s, P = (int64_t)oh * ow;
+  if (K < 64 || K > 4096) return false;
+  if ((int64_t)c * h * w > 0x7fffffffLL || (int64_t)m * P > 0x7fffffffLL) return false;
+  int nr, wp;
+  if (small_lds_bytes(c, w, r, s, ph, pw, K, &nr, &wp) > kSmallLds) return false;
+  if ((int64_t)c * nr * wp > 16384) return false;  // the tile is staged in one round: keep it small
+  const int64_t tiles = ceil_div(m, 32) * n * ceil_div(P, 32);
+  return tiles <= 768 && tiles * 32 * 32 * K <= ((int64_t)1 << 29);  // multiply-adds as executed, tile padding included
+}
+
+vcnn_status launch_conv_small(int dtype, int n, int c, int h, int w, int m, int r, int s, int ph, int pw, const void* x,
+                              const void* wgt, const float* bias, void* y, int relu, hipStream_t st) {
+  SmallConvArgs a{};
+  a.x = x, a.wgt = wgt, a.bias = bias, a.y = y;
+  a.n = n, a.c = c, a.h = h, a.w = w, a.m = m, a.r = r, a.s = s, a.ph = ph, a.pw = pw;
+  a.oh = h + 2 * ph - r + 1, a.ow = w + 2 * pw - s + 1, a.P = a.oh * a.ow;
+  a.K = c * r * s, a.Kp = (a.K + 3) & ~3;
+  a.relu = relu;
+  const size_t lds = small_lds_bytes(c, w, r, s, ph, pw, a.K, &a.nr, &a.wp);
+  a.vec_a = a.K % 4 == 0 && (dtype == VCNN_BF16 ? group_aligned<bf16>(wgt) : group_aligned<float>(wgt));
+  const int waves = small_waves(a.K);
+  a.kper = (int)ceil_div(ceil_div(a.K, waves), 8) * 8;
+  a.tiles_m = (int)ceil_div(m, 32);
+  a.tiles_per_img = (int)ceil_div(a.P, 32);
+  const int64_t tiles = (int64_t)a.tiles_m * n * a.tiles_per_img;
+  const dim3 grid((unsigned)tiles), block(64 * waves);
+  static bool opted[2] = {false, false};
+  if (dtype == VCNN_BF16) {
+    if (!opted[1]) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(conv_small_kernel<bf16>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmallLds);
+      opted[1] = true;
+    }
+    hipLaunchKernelGGL(conv_small_kernel<bf16>, grid, block, lds, st, a);
+  } else {
+    if (!opted[0]) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(conv_small_kernel<float>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmallLds);
+      opted[0] = true;
+    }
+    hipLaunchKernelGGL(conv_small_kernel<float>, grid, block, lds, st, a);
+  }
+  return check_launch("conv_small");
+}
+
+}  // namespace vcnn
