@@ -79,3 +79,27 @@ def test_null_and_workspace_errors_need_no_gpu():
     assert lib.vcnn_act_fwd(7, vcnn.F32, 4, None, None, None) == vcnn.ERR_UNSUPPORTED
     assert lib.vcnn_set_conv_algo(99) == vcnn.ERR_UNSUPPORTED
     assert lib.vcnn_set_conv_algo(vcnn.ALGO_AUTO) == vcnn.OK
+
+
+def test_fused_and_layer_entry_points_validate_before_launch():
+    """The calls that fold an activation derivative, and the pooling layer of Eq. 3: unknown activation ids,
+    NULL tensors and a workspace that is too small are refused on the host."""
+    lib = vcnn.lib()
+    p = vcnn.pool_desc(2, 3, 8, 8, 2, 2, 2, 2)
+    fake = 0x1000  # never dereferenced: validation fails first
+    assert lib.vcnn_pool_bwd_act(ctypes.byref(p), 9, fake, fake, fake, fake, None) == vcnn.ERR_UNSUPPORTED
+    assert lib.vcnn_pool_bwd_act(ctypes.byref(p), vcnn.ACT_RELU, None, fake, fake, fake, None) == vcnn.ERR_NULL
+    assert lib.vcnn_pool_layer_fwd(ctypes.byref(p), 9, fake, None, fake, fake, None) == vcnn.ERR_UNSUPPORTED
+    assert lib.vcnn_pool_layer_fwd(ctypes.byref(p), vcnn.ACT_TANH, None, None, fake, fake, None) == vcnn.ERR_NULL
+    assert lib.vcnn_pool_layer_workspace_bytes(ctypes.byref(p), None) == vcnn.ERR_NULL
+    need = vcnn.pool_layer_workspace_bytes(p)
+    assert need >= 2 * 3 * 4 * 4 * 4  # at least the delta tensor
+    assert lib.vcnn_pool_layer_bwd(ctypes.byref(p), vcnn.ACT_TANH, fake, fake, fake, fake, fake, fake, need - 1,
+                                   None) == vcnn.ERR_WORKSPACE
+    assert lib.vcnn_pool_layer_bwd(ctypes.byref(p), vcnn.ACT_TANH, None, fake, fake, None, fake, fake, need,
+                                   None) == vcnn.ERR_NULL  # y is needed for sigma'
+    assert lib.vcnn_pool_layer_bwd(ctypes.byref(p), 9, fake, fake, fake, None, fake, fake, need, None) == vcnn.ERR_UNSUPPORTED
+    assert lib.vcnn_fc_bwd_act(vcnn.F32, 4, 8, 2, 9, fake, fake, fake, None, None, fake, None) == vcnn.ERR_UNSUPPORTED
+    # with an activation below, x is read for dx as well
+    assert lib.vcnn_fc_bwd_act(vcnn.F32, 4, 8, 2, vcnn.ACT_RELU, None, fake, fake, None, None, fake, None) == vcnn.ERR_NULL
+    assert lib.vcnn_fc_bwd_act(vcnn.F32, 0, 8, 2, vcnn.ACT_NONE, fake, fake, fake, None, None, fake, None) == vcnn.ERR_SHAPE
