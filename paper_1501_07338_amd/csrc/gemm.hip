@@ -527,7 +527,7 @@ static int bwd_filter_bn(const ConvGeom&) { return 128; }
 
 static int bwd_filter_chunk(const ConvGeom& g) {
   const int64_t tiles = ceil_div(g.M, bwd_filter_bm(g)) * ceil_div(g.K, bwd_filter_bn(g));
-  int64_t want = 1024 / tiles;
+  int64_t want = 512 / tiles;
   const int64_t max_splits = g.N / 512 > 0 ? g.N / 512 : 1;
   if (want < 1) want = 1;
   if (want > max_splits) want = max_splits;
