@@ -259,7 +259,7 @@ def batch_sweep(stream, steps=50):
 # from the committed summaries, None where no counter run covers the kernel.
 MEASURED_TRAFFIC: dict = {
     # (2 x FETCH_SIZE + WRITE_SIZE) x 1024 of the call's main kernel, profiles/cfg5_cfg4_cfg2_hbm_traffic_pmc.txt
-    "cfg2.conv2.fwd": 4.08e6,        # conv_halo_kernel<64, 64, ...>: 1191.5 KiB fetched (x2), 1600 KiB written
+    "cfg2.conv2.fwd": 7.2e6,         # conv_small_kernel: 2699 KiB fetched (x2), 1600 KiB written
     "cfg2.conv2.bwd_filter": 19.6e6,   # conv_halo_filter_kernel<64, 256, ...> on 256 blocks: 2494 KiB fetched (x2),
                                        # 14146 KiB of partial products written (then added by sum_slices_split)
     "cfg2.conv2.bwd_data": 19.2e6,     # gemm_f32_kernel<128, 128, 16, ...> writing the 16 MB patch-matrix gradient
