@@ -219,7 +219,7 @@ static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 // Small products (the fully connected layers at the experiments' batch sizes: a few MFLOP).  Their cost
 // is latency, not arithmetic: few tiles, and in the slab kernel above a chain of load -> barrier ->
 // MFMA rounds as long as the contraction.  Here a block owns one 32 x 32 tile of C and its waves (4 to
-// 16, more for longer contractions) split the contraction between them; every wave reads its operand
+// 8, more for longer contractions) split the contraction between them; every wave reads its operand
 // fragments straight from global memory, several groups of 8 contraction steps in flight at once (no LDS
 // staging, no barrier in the loop), and the partial tiles are added in wave order through LDS.
 // -------------------------------------------------------------------------------------------------
@@ -265,15 +265,19 @@ __device__ __forceinline__ void small_tile(const GemmArgs& a, int tile, int tile
   constexpr int U = 8;  // groups in flight
   for (int k0 = ks; k0 < ke; k0 += 8 * U) {
     float av[U][4], bv[U][4];
-#pragma unroll
-    for (int g = 0; g < U; ++g) {
-      load4(A, a.a_sk, A_KC, A_VEC, i_ok, false, k0 + 8 * g, av[g]);
-      load4(B, a.b_sk, B_KC, B_VEC, j_ok, j_ones, k0 + 8 * g, bv[g]);
-    }
+    const int ng = min(U, (ke - k0 + 7) >> 3);  // groups with work (wave-uniform): short shares skip the rest
 #pragma unroll
     for (int g = 0; g < U; ++g)
+      if (g < ng) {
+        load4(A, a.a_sk, A_KC, A_VEC, i_ok, false, k0 + 8 * g, av[g]);
+        load4(B, a.b_sk, B_KC, B_VEC, j_ok, j_ones, k0 + 8 * g, bv[g]);
+      }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[g][u], bv[g][u], acc, 0, 0, 0);
+    for (int g = 0; g < U; ++g)
+      if (g < ng) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[g][u], bv[g][u], acc, 0, 0, 0);
+      }
   }
 
   if (wave > 0) {
@@ -324,8 +328,8 @@ __global__ __launch_bounds__(1024) void fc_bwd_small_kernel(GemmArgs gw, GemmArg
     small_tile<true, false, A_VEC, false, TI, TI>(gx, blockIdx.x - tiles_w, tiles_m_x, kper_x, red);
 }
 
-// one wave per 64 contraction indices, 4 to 16 of them: a wave then has its whole share in flight at once
-static int small_waves(int K) { return (int)std::min<int64_t>(16, std::max<int64_t>(4, ceil_div(K, 64))); }
+// one wave per 64 contraction indices, 4 to 8 of them (16 measured no faster and need 61 KB of LDS for the partial tiles)
+static int small_waves(int K) { return (int)std::min<int64_t>(8, std::max<int64_t>(4, ceil_div(K, 64))); }
 static int small_kper(int K, int waves) { return (int)ceil_div(ceil_div(K, waves), 8) * 8; }
 static int64_t small_tiles(const GemmArgs& a) { return ceil_div(a.M, 32) * ceil_div(a.N + (a.row_sums ? 1 : 0), 32); }
 
