@@ -22,19 +22,31 @@ __device__ __forceinline__ int tap_index(const DirectGeom& g, int r, int s) {
 }
 
 // Stages rows [y0 - py, y0 - py + rows) of one input plane into LDS, columns shifted by px, zero filled.
+// Elements are taken in flat tile order and every thread issues up to eight loads before it stores any of
+// them, so a plane costs one or two memory round trips rather than one per row.
 template <typename T>
 __device__ __forceinline__ void stage_plane(const DirectGeom& g, const T* __restrict__ plane, int y0, int rows,
                                             float* tile) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (int ry = wave; ry < rows; ry += kThreads / 64) {
-    const int iy = y0 + ry - g.py;
-    const bool row_ok = iy >= 0 && iy < g.ih;
-    for (int rx = lane; rx < g.twp; rx += 64) {
-      const int ix = rx - g.px;
-      float v = 0.f;
-      if (row_ok && ix >= 0 && ix < g.iw) v = ld(plane + (int64_t)iy * g.iw + ix);
-      tile[ry * g.twp + rx] = v;
+  constexpr int U = 8;
+  const int total = rows * g.twp;
+  const int dq = kThreads / g.twp, dr = kThreads - dq * g.twp;
+  int ry = threadIdx.x / g.twp;
+  int rx = threadIdx.x - ry * g.twp;
+  for (int e0 = threadIdx.x; e0 < total; e0 += U * kThreads) {
+    float v[U];
+    bool ok[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int iy = y0 + ry - g.py, ix = rx - g.px;
+      ok[u] = e0 + u * kThreads < total && iy >= 0 && iy < g.ih && ix >= 0 && ix < g.iw;
+      v[u] = ld(plane + (ok[u] ? (int64_t)iy * g.iw + ix : 0));
+      rx += dr;
+      ry += dq;
+      if (rx >= g.twp) rx -= g.twp, ++ry;
     }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (e0 + u * kThreads < total) tile[e0 + u * kThreads] = ok[u] ? v[u] : 0.f;
   }
 }
 
