@@ -16,25 +16,25 @@ namespace vcnn {
 static constexpr int kThreads = 256;
 static constexpr int kPx = 4;                 // consecutive output pixels per thread
 static constexpr size_t kMaxLds = 64 * 1024;  // static launch limit without opting in to more
+static constexpr int kFewOutWeightsPerThread = 2;  // kernels of one channel kept in LDS: up to 512 padded taps
 
 __device__ __forceinline__ int tap_index(const DirectGeom& g, int r, int s) {
   return g.flip ? (g.r - 1 - r) * g.s + (g.s - 1 - s) : r * g.s + s;
 }
 
-// Stages rows [y0 - py, y0 - py + rows) of one input plane into LDS, columns shifted by px, zero filled.
-// Elements are taken in flat tile order and every thread issues up to eight loads before it stores any of
-// them, so a plane costs one or two memory round trips rather than one per row.
-template <typename T>
-__device__ __forceinline__ void stage_plane(const DirectGeom& g, const T* __restrict__ plane, int y0, int rows,
-                                            float* tile) {
-  constexpr int U = 8;
-  const int total = rows * g.twp;
-  const int dq = kThreads / g.twp, dr = kThreads - dq * g.twp;
-  int ry = threadIdx.x / g.twp;
-  int rx = threadIdx.x - ry * g.twp;
-  for (int e0 = threadIdx.x; e0 < total; e0 += U * kThreads) {
-    float v[U];
-    bool ok[U];
+// One input plane's rows [y0 - py, y0 - py + rows), columns shifted by px, on their way into an LDS tile (zero
+// filled outside the image).  Elements are taken in flat tile order; load() issues all of this thread's loads
+// (up to U per pass) before anything waits for them, store() writes them to the tile - so a plane costs one
+// memory round trip rather than one per row, and a caller can put other work between the two halves.
+template <int U>
+struct PlaneRegs {
+  float v[U];
+  bool ok[U];
+  template <typename T>
+  __device__ __forceinline__ void load(const DirectGeom& g, const T* __restrict__ plane, int y0, int total, int e0) {
+    const int dq = kThreads / g.twp, dr = kThreads - dq * g.twp;
+    int ry = e0 / g.twp;
+    int rx = e0 - ry * g.twp;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int iy = y0 + ry - g.py, ix = rx - g.px;
@@ -44,9 +44,23 @@ __device__ __forceinline__ void stage_plane(const DirectGeom& g, const T* __rest
       ry += dq;
       if (rx >= g.twp) rx -= g.twp, ++ry;
     }
+  }
+  __device__ __forceinline__ void store(float* tile, int total, int e0) const {
 #pragma unroll
     for (int u = 0; u < U; ++u)
       if (e0 + u * kThreads < total) tile[e0 + u * kThreads] = ok[u] ? v[u] : 0.f;
+  }
+};
+
+template <typename T>
+__device__ __forceinline__ void stage_plane(const DirectGeom& g, const T* __restrict__ plane, int y0, int rows,
+                                            float* tile) {
+  constexpr int U = 8;
+  const int total = rows * g.twp;
+  for (int e0 = threadIdx.x; e0 < total; e0 += U * kThreads) {
+    PlaneRegs<U> regs;
+    regs.load(g, plane, y0, total, e0);
+    regs.store(tile, total, e0);
   }
 }
 
@@ -82,6 +96,40 @@ __device__ __forceinline__ void row_taps(const DirectGeom& g, const float* row, 
 #undef VCNN_TAP
 }
 
+// The same with the kernel rows already in LDS in walking order (flipped when staged), padded to a multiple of
+// four: one 16-byte read brings four taps, instead of one scalar load - and one wait - per tap.
+template <int CO>
+__device__ __forceinline__ void row_taps_lds(int S, const float* row, const float* const (&wrow)[CO],
+                                             float (&acc)[CO][kPx]) {
+  float x0 = row[0], x1 = row[1], x2 = row[2];
+  int s = 0;
+#define VCNN_TAP(XA, XB, XC, XD, WV)                 \
+  _Pragma("unroll") for (int o = 0; o < CO; ++o) {   \
+    const float wv = WV;                             \
+    acc[o][0] = fmaf(wv, XA, acc[o][0]);             \
+    acc[o][1] = fmaf(wv, XB, acc[o][1]);             \
+    acc[o][2] = fmaf(wv, XC, acc[o][2]);             \
+    acc[o][3] = fmaf(wv, XD, acc[o][3]);             \
+  }
+  for (; s + 4 <= S; s += 4) {
+    const float x3 = row[s + 3], x4 = row[s + 4], x5 = row[s + 5], x6 = row[s + 6];
+    float4 w4[CO];
+#pragma unroll
+    for (int o = 0; o < CO; ++o) w4[o] = *reinterpret_cast<const float4*>(wrow[o] + s);
+    VCNN_TAP(x0, x1, x2, x3, w4[o].x)
+    VCNN_TAP(x1, x2, x3, x4, w4[o].y)
+    VCNN_TAP(x2, x3, x4, x5, w4[o].z)
+    VCNN_TAP(x3, x4, x5, x6, w4[o].w)
+    x0 = x4, x1 = x5, x2 = x6;
+  }
+  for (; s < S; ++s) {
+    const float x3 = row[s + 3];
+    VCNN_TAP(x0, x1, x2, x3, wrow[o][s])
+    x0 = x1, x1 = x2, x2 = x3;
+  }
+#undef VCNN_TAP
+}
+
 // ---- few output maps (CO <= 4), any number of input channels -----------------------------------------
 // Block = (sample, band of output rows, slice of the input channels).  Partial sums over channel
 // slices go to `out` as [slice][n][co][oh][ow] when isplit > 1 and are combined by sum_slices_kernel.
@@ -111,17 +159,84 @@ __global__ __launch_bounds__(kThreads) void direct_few_out_kernel(DirectGeom g, 
 #pragma unroll
     for (int j = 0; j < kPx; ++j) acc[o][j] = 0.f;
 
-  for (int i = i0; i < i1; ++i) {
-    __syncthreads();
-    stage_plane(g, in + ((int64_t)n * g.ci + i) * g.ih * g.iw, y0, rows, tile);
-    __syncthreads();
-    if (active) {
-      for (int r = 0; r < g.r; ++r) {
+  // The kernels of a channel, [CO][r][sp] with rows padded to sp = a multiple of four taps and already in walking
+  // order, sit in LDS behind the two tiles (two copies as well).
+  const int sp = (g.s + 3) & ~3, wfloats = CO * g.r * sp;
+  const bool w_in_lds = wfloats <= kFewOutWeightsPerThread * kThreads;  // else (very tall kernels) read from global
+  const int tile_floats = ((g.bh + g.r - 1) * g.twp + 3) & ~3;
+  float* const wl0 = tile + 2 * tile_floats;
+  struct WRegs {
+    float v[kFewOutWeightsPerThread];
+  };
+  auto load_w = [&](int i) {  // this thread's kernel elements of channel i
+    WRegs wr;
+#pragma unroll
+    for (int u = 0; u < kFewOutWeightsPerThread; ++u) {
+      const int t = threadIdx.x + u * kThreads;
+      wr.v[u] = 0.f;
+      if (w_in_lds && t < wfloats) {
+        const int o = t / (g.r * sp), q = t - o * g.r * sp;
+        const int r = q / sp, sx = q - r * sp;
+        if (sx < g.s) wr.v[u] = ld(w + (int64_t)o * g.w_so + (int64_t)i * g.w_si + tap_index(g, r, sx));
+      }
+    }
+    return wr;
+  };
+  auto store_w = [&](const WRegs& wr, float* wl) {
+#pragma unroll
+    for (int u = 0; u < kFewOutWeightsPerThread; ++u) {
+      const int t = threadIdx.x + u * kThreads;
+      if (w_in_lds && t < wfloats) wl[t] = wr.v[u];
+    }
+  };
+  auto taps_of = [&](int i, const float* t, const float* wl) {
+    if (!active) return;
+    for (int r = 0; r < g.r; ++r) {
+      if (w_in_lds) {
+        const float* wrow[CO];
+#pragma unroll
+        for (int o = 0; o < CO; ++o) wrow[o] = wl + (o * g.r + r) * sp;
+        row_taps_lds<CO>(g.s, t + (ty + r) * g.twp + gx * kPx, wrow, acc);
+      } else {
         const T* wrow[CO];
 #pragma unroll
         for (int o = 0; o < CO; ++o) wrow[o] = w + (int64_t)o * g.w_so + (int64_t)i * g.w_si + tap_index(g, r, 0);
-        row_taps<CO, T>(g, tile + (ty + r) * g.twp + gx * kPx, wrow, acc);
+        row_taps<CO, T>(g, t + (ty + r) * g.twp + gx * kPx, wrow, acc);
       }
+    }
+  };
+  const int total = rows * g.twp;
+  const T* planes = in + (int64_t)n * g.ci * g.ih * g.iw;
+  constexpr int U = 12;
+  if (total <= U * kThreads) {
+    // Two tiles: while the block multiplies channel i out of one, the loads of channel i + 1 are in flight and
+    // land in the other.  One barrier per channel: it separates the reads of a tile from its next refill and
+    // publishes the tile just filled.
+    PlaneRegs<U> regs;
+    regs.load(g, planes + (int64_t)i0 * g.ih * g.iw, y0, total, threadIdx.x);
+    WRegs wreg = load_w(i0);
+    regs.store(tile, total, threadIdx.x);
+    store_w(wreg, wl0);
+    for (int i = i0; i < i1; ++i) {
+      const int cur = (i - i0) & 1;
+      __syncthreads();
+      if (i + 1 < i1) {
+        regs.load(g, planes + (int64_t)(i + 1) * g.ih * g.iw, y0, total, threadIdx.x);
+        wreg = load_w(i + 1);
+      }
+      taps_of(i, tile + cur * tile_floats, wl0 + cur * wfloats);
+      if (i + 1 < i1) {
+        regs.store(tile + (cur ^ 1) * tile_floats, total, threadIdx.x);
+        store_w(wreg, wl0 + (cur ^ 1) * wfloats);
+      }
+    }
+  } else {
+    for (int i = i0; i < i1; ++i) {
+      __syncthreads();
+      stage_plane(g, planes + (int64_t)i * g.ih * g.iw, y0, rows, tile);
+      store_w(load_w(i), wl0);
+      __syncthreads();
+      taps_of(i, tile, wl0);
     }
   }
   if (!active) return;
@@ -350,14 +465,14 @@ __global__ __launch_bounds__(kThreads) void direct_few_in_kernel(DirectGeom g, c
 }
 
 // ---- planning ------------------------------------------------------------------------------------------
-static bool plan_bands(DirectGeom* g, int planes_in_lds, int min_pitch) {
+static bool plan_bands(DirectGeom* g, int planes_in_lds, int min_pitch, size_t extra_bytes = 0) {
   g->groups = (g->ow + kPx - 1) / kPx;
   if (g->groups > kThreads) return false;
   g->twp = g->groups * kPx + g->s - 1;
   if (g->twp < min_pitch) g->twp = min_pitch;
   int bh = kThreads / g->groups;
   if (bh > g->oh) bh = g->oh;
-  while (bh >= 1 && (size_t)planes_in_lds * (bh + g->r - 1) * g->twp * sizeof(float) > kMaxLds - 4096) --bh;
+  while (bh >= 1 && (size_t)planes_in_lds * ((bh + g->r - 1) * g->twp + 4) * sizeof(float) + extra_bytes > kMaxLds - 4096) --bh;
   if (bh < 1) return false;
   g->bh = bh;
   g->bands = (g->oh + bh - 1) / bh;
@@ -380,6 +495,11 @@ bool direct_bwd_data_geom(const ConvGeom& c, DirectGeom* g) {
   return true;
 }
 
+static size_t few_out_weight_bytes(const DirectGeom& g) {
+  const size_t wfloats = (size_t)g.co * g.r * ((g.s + 3) & ~3);
+  return wfloats <= (size_t)kFewOutWeightsPerThread * kThreads ? 2 * wfloats * sizeof(float) : 0;
+}
+
 // Channel slices for the few-output kernel: enough blocks to fill the chip, at least 8 channels each.
 static int few_out_split(const DirectGeom& g) {
   const int64_t base = (int64_t)g.n * g.bands;
@@ -392,7 +512,8 @@ static int few_out_split(const DirectGeom& g) {
 
 bool direct_few_out_plan(DirectGeom* g, int* isplit, size_t* partial_bytes) {
   if (g->co < 1 || g->co > 4) return false;
-  if (!plan_bands(g, 1, 0)) return false;
+  // two tiles (the next channel is staged while one is multiplied out) and two copies of a channel's kernels
+  if (!plan_bands(g, 2, 0, few_out_weight_bytes(*g))) return false;
   *isplit = few_out_split(*g);
   *partial_bytes = *isplit > 1 ? (size_t)*isplit * g->n * g->co * g->oh * g->ow * sizeof(float) : 0;
   return true;
@@ -401,7 +522,7 @@ bool direct_few_out_plan(DirectGeom* g, int* isplit, size_t* partial_bytes) {
 template <typename T, typename TO>
 static void launch_few_out_typed(const DirectGeom& g, int isplit, const void* in, const void* w, const float* bias,
                                  void* dst, int relu, hipStream_t st) {
-  const size_t lds = (size_t)(g.bh + g.r - 1) * g.twp * sizeof(float);
+  const size_t lds = 2 * (size_t)(((g.bh + g.r - 1) * g.twp + 3) & ~3) * sizeof(float) + few_out_weight_bytes(g);
   const dim3 grid((unsigned)((int64_t)g.n * g.bands * isplit)), block(kThreads);
   const T* i = (const T*)in;
   const T* k = (const T*)w;
