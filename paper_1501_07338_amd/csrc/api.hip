@@ -164,6 +164,12 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
       p.workspace_bytes = align256(p.partial_bytes);
     } else if (is_pointwise(g)) {
       p.path = PATH_POINTWISE;
+    } else if (allow_direct && g.k <= 4 && g.c >= 64 && g.r - 1 - g.ph >= 0 && g.s - 1 - g.pw >= 0 &&
+               conv_halo_plan(g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, &p.hp)) {
+      // few maps into many channels: the correlation's contraction is short (k*r*s) but it has many output maps,
+      // which is matrix-core work; the flipped matrix lives in the workspace
+      p.path = PATH_HALO;
+      p.workspace_bytes = align256((size_t)g.M * g.K * sizeof(float));
     } else if (allow_direct && g.k <= 4 && direct_bwd_data_geom(g, &p.dg) && direct_few_in_plan(&p.dg, &p.split)) {
       p.path = PATH_FEW_IN;
     } else if (algo == VCNN_ALGO_AUTO && g.c > 4 && g.r - 1 - g.ph >= 0 && g.s - 1 - g.pw >= 0 &&
