@@ -616,6 +616,8 @@ __global__ __launch_bounds__(kThreads) void direct_filter_grad_kernel(DirectGeom
   const int dyp = g.groups * kPx;  // dy band pitch
   float* xt = lds;
   float* dt = lds + (g.bh + g.r - 1) * g.twp;
+  DirectGeom gd = g;  // the dy plane seen as an unpadded input plane of pitch dyp
+  gd.twp = dyp, gd.py = 0, gd.px = 0, gd.ih = g.oh, gd.iw = g.ow;
 
   float acc[kTapChunk];
 #pragma unroll
@@ -630,9 +632,7 @@ __global__ __launch_bounds__(kThreads) void direct_filter_grad_kernel(DirectGeom
       const int bh_eff = min(g.bh, g.oh - y0);
       __syncthreads();
       stage_plane(g, xp, y0, bh_eff + g.r - 1, xt);
-      for (int ry = wave; ry < bh_eff; ry += kThreads / 64)
-        for (int rx = lane; rx < dyp; rx += 64)
-          dt[ry * dyp + rx] = rx < g.ow ? ld(dp + (int64_t)(y0 + ry) * g.ow + rx) : 0.f;
+      stage_plane(gd, dp, y0, bh_eff, dt);  // the dy band: rows y0 + [0, bh_eff), pitch dyp, zero beyond ow
       __syncthreads();
       if (valid) {
         const int npg = bh_eff * g.groups;
