@@ -480,18 +480,42 @@ __global__ __launch_bounds__(kThreads) void bias_grad_kernel(int n, int M, int64
   __shared__ float sm[kThreads];
   const int m = blockIdx.x, slice = blockIdx.y;
   const int n0 = slice * per_slice, n1 = min(n, n0 + per_slice);
-  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-  for (int i = n0; i < n1; ++i) {
-    const T* row = dy + ((int64_t)i * M + m) * P;
-    int64_t p = threadIdx.x;
-    for (; p + 3 * kThreads < P; p += 4 * kThreads) {
-      const float v0 = ld(row + p), v1 = ld(row + p + kThreads), v2 = ld(row + p + 2 * kThreads),
-                  v3 = ld(row + p + 3 * kThreads);
-      a0 += v0, a1 += v1, a2 += v2, a3 += v3;
+  // four samples x two positions per thread and pass: eight independent (masked) loads in flight, so a slice
+  // costs a few memory round trips whatever P is
+  float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (per_slice < 4) {  // few samples per slice: eight positions of one sample per pass instead
+    for (int i = n0; i < n1; ++i) {
+      const T* row = dy + ((int64_t)i * M + m) * P;
+      for (int64_t p = threadIdx.x; p < P; p += 8 * kThreads) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = ld(row + (p + u * kThreads < P ? p + u * kThreads : p));
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a[u] += p + u * kThreads < P ? v[u] : 0.f;
+      }
     }
-    for (; p < P; p += kThreads) a0 += ld(row + p);
+  } else
+  for (int i = n0; i < n1; i += 4) {
+    const T* rows[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) rows[u] = dy + ((int64_t)min(i + u, n1 - 1) * M + m) * P;
+    for (int64_t p = threadIdx.x; p < P; p += 2 * kThreads) {
+      const bool second = p + kThreads < P;
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        v[u] = ld(rows[u] + p);
+        v[4 + u] = ld(rows[u] + (second ? p + kThreads : p));
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const bool in = i + u < n1;
+        a[u] += in ? v[u] : 0.f;
+        a[4 + u] += in && second ? v[4 + u] : 0.f;
+      }
+    }
   }
-  const float total = block_sum<kThreads>((a0 + a1) + (a2 + a3), sm);
+  const float total = block_sum<kThreads>(((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7])), sm);
   if (threadIdx.x == 0) out[(int64_t)slice * M + m] = total;
 }
 
@@ -505,7 +529,7 @@ __global__ __launch_bounds__(kThreads) void bias_grad_finish_kernel(int M, int s
 }
 
 int bias_grad_slices(const ConvGeom& g) {
-  int64_t s = ceil_div(512, g.M);
+  int64_t s = ceil_div(2048, g.M);
   if (s > g.n) s = g.n;
   return (int)(s < 1 ? 1 : s);
 }
