@@ -90,7 +90,7 @@ static bool halo_bwd_data_pays(const ConvGeom& g, const HaloPlan& hp) {
 
 // Which realisation a pass uses for a given shape.  The same decision drives the workspace query and
 // the launch, so the two always agree.
-enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER, PATH_HALO, PATH_HALO_FILTER, PATH_HALO_BF16, PATH_FILTER_BF16, PATH_HALO_FILTER_BF16, PATH_FEW_COLS_FILTER, PATH_SMALL };
+enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER, PATH_HALO, PATH_HALO_FILTER, PATH_HALO_BF16, PATH_FILTER_BF16, PATH_HALO_FILTER_BF16, PATH_FEW_COLS_FILTER, PATH_SMALL, PATH_SMALL_BWD };
 struct Plan {
   Path path;
   DirectGeom dg;
@@ -172,6 +172,8 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
       p.workspace_bytes = align256((size_t)g.M * g.K * sizeof(float));
     } else if (allow_direct && g.k <= 4 && direct_bwd_data_geom(g, &p.dg) && direct_few_in_plan(&p.dg, &p.split)) {
       p.path = PATH_FEW_IN;
+    } else if (algo == VCNN_ALGO_AUTO && conv_small_bwd_applies(dtype, g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw)) {
+      p.path = PATH_SMALL_BWD;  // transposed product and phi_c^{-1} fused on chip, no workspace
     } else if (algo == VCNN_ALGO_AUTO && g.c > 4 && g.r - 1 - g.ph >= 0 && g.s - 1 - g.pw >= 0 &&
                conv_small_applies(g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw)) {
       p.path = PATH_SMALL;  // the same latency-bound kernel on dy with the flipped matrix (kept in the workspace)
@@ -372,6 +374,8 @@ vcnn_status vcnn_conv_bwd_data(const vcnn_conv_desc* d, const void* w, const voi
     return launch_conv_halo_bf16(plan.hb, g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, dy, w,
                                  (int64_t)g.r * g.s, g.K, 1, nullptr, dx, 0, workspace, st);
   }
+  if (plan.path == PATH_SMALL_BWD)
+    return launch_conv_small_bwd(g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, dy, w, dx, st);
   if (plan.path == PATH_SMALL) {
     if (vcnn_status s = launch_flip_transpose(dt, w, workspace, g.k, g.c, g.r * g.s, st)) return s;
     return launch_conv_small(dt, g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, dy, workspace,

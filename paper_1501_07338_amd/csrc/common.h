@@ -35,6 +35,11 @@ vcnn_status launch_col2im(const ConvGeom& g, int dtype, const float* col, void* 
 bool conv_small_applies(int n, int c, int h, int w, int m, int r, int s, int ph, int pw);
 vcnn_status launch_conv_small(int dtype, int n, int c, int h, int w, int m, int r, int s, int ph, int pw, const void* x,
                               const void* wgt, const float* bias, void* y, int relu, hipStream_t st);
+// Input gradient dx [n][c][h][w] of a small layer from dy [n][m][oh][ow] and the kernels wgt [m][c][r][s]: the
+// transposed product and phi_c^{-1} on chip, one sample and four channels per block (fp32 only).
+bool conv_small_bwd_applies(int dtype, int n, int c, int h, int w, int m, int r, int s, int ph, int pw);
+vcnn_status launch_conv_small_bwd(int n, int c, int h, int w, int m, int r, int s, int ph, int pw,
+                                  const void* dy, const void* wgt, void* dx, hipStream_t st);
 
 // ---- gemm.hip -----------------------------------------------------------------------------------
 // Generic strided product C(i,j) = act(bias[i] + sum_k A(i,k) B(k,j)), fp32 MFMA.

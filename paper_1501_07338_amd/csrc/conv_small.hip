@@ -210,4 +210,196 @@ vcnn_status launch_conv_small(int dtype, int n, int c, int h, int w, int m, int 
   return check_launch("conv_small");
 }
 
+// ---- input gradient of small layers: transposed product and phi_c^{-1} in one kernel ---------------------------
+// The back-propagation paragraph of "Vectorizing Convolution" forms the patch-matrix gradient
+// dcol[(c, r, s)][p] = sum_m W[m][c][r][s] dy[m][p] and folds it back with phi_c^{-1}.  For a small layer both steps
+// fit on chip: a block owns one sample and four input channels (one per wave) and stages the sample's dy [m][P] in
+// LDS.  The r*s rows of dcol that belong to a wave's channel are one 32-row MFMA tile (taps on the row axis, the
+// sample's pixels on the column axis, maps as the contraction).  phi_c^{-1} is applied straight from the
+// accumulator registers (lane = output pixel, register = tap): tap by tap, every lane adds its entry to the input
+// pixel it belongs to in an h x w plane in LDS.  One such step touches distinct pixels (one tap, different output
+// pixels); the two half-waves, which hold different taps, use a plane each, and the two are added at the end.  A
+// wave's LDS instructions execute in program order, so every input pixel sums its taps in a fixed order and the
+// result is bit-identical run to run.  Neither the patch-matrix gradient nor a flipped kernel matrix goes through
+// HBM, and nothing is multiplied with the zero border of a 'valid' layer.  What such a layer costs is latency, so
+// a thread requests everything it needs from global memory (its share of dy, the kernel-matrix entries of up to
+// 64 maps) before it waits for any of it, and the loops over maps and taps are free of branches.
+struct SmallBwdArgs {
+  const void* dy;   // [n][m][oh][ow]
+  const void* wgt;  // [m][c][r][s]
+  void* dx;         // [n][c][h][w]
+  int n, c, h, w, m, r, s, ph, pw, oh, ow, P;
+  int RS;          // taps per channel (at most 32)
+  int dy_floats;   // staged dy incl. its zero tail
+  int chunks;      // channel groups of four
+};
+
+static constexpr int kSmallBwdWaves = 4;
+
+template <int NT>  // 32-pixel tiles per sample
+__global__ __launch_bounds__(64 * kSmallBwdWaves, NT <= 2 ? 3 : 2) void conv_small_bwd_kernel(SmallBwdArgs a) {
+  using T = float;  // the bf16 variant has its own matrix-core route for these layers
+  constexpr int kThreads = 64 * kSmallBwdWaves;
+  extern __shared__ int small_lds[];
+  int* const taprs = small_lds;                                 // [32]: (r << 16) | s of tap t, -1 beyond the last tap
+  float* const dyl = reinterpret_cast<float*>(small_lds + 32);  // [m][P] as in memory, then 32 zeros
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int hw = a.h * a.w;
+  float* const planes = dyl + a.dy_floats + wave * 2 * hw;  // [2][h][w]: this wave's channel, one plane per half-wave
+  const int n = blockIdx.x / a.chunks;
+  const int c = (blockIdx.x - n * a.chunks) * kSmallBwdWaves + wave;
+  const bool c_ok = c < a.c;  // a wave without a channel runs along on channel 0 and stores nothing
+
+  // A operand: row = tap t of this wave's channel, contraction index = map
+  const bool t_ok = l32 < a.RS;
+  const T* const wgt = static_cast<const T*>(a.wgt);
+  const int wstride = a.c * a.RS;  // between maps; the whole kernel tensor is below 2^31 elements
+  const int woff = (c_ok ? c : 0) * a.RS + (t_ok ? l32 : 0) + half * wstride;
+  constexpr int U = 32;  // MFMA steps (two maps each) per batch of loads
+  float av[U];
+  auto load_a = [&](int k0) {
+#pragma unroll
+    for (int g = 0; g < U; ++g) {
+      const int k = k0 + 2 * g + half;
+      const float t = ld(wgt + woff + min(k0 + 2 * g, a.m - 1 - half) * wstride);  // beyond the last map: a valid address
+      av[g] = t_ok && k < a.m ? t : 0.f;
+    }
+  };
+  load_a(0);
+
+  // the sample's dy, a straight copy, sixteen loads in flight per thread
+  const T* dyn = static_cast<const T*>(a.dy) + (int64_t)n * a.m * a.P;
+  const int total = a.m * a.P;
+  constexpr int V = 16;
+  for (int e0 = tid; e0 < a.dy_floats; e0 += V * kThreads) {
+    float v[V];
+#pragma unroll
+    for (int u = 0; u < V; ++u) {
+      const int e = e0 + u * kThreads;
+      v[u] = e < total ? ld(dyn + e) : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < V; ++u) {
+      const int e = e0 + u * kThreads;
+      if (e < a.dy_floats) dyl[e] = v[u];
+    }
+  }
+  if (tid < 32) {
+    const int r = tid / a.s;
+    taprs[tid] = tid < a.RS ? (r << 16) | (tid - r * a.s) : -1;
+  }
+  for (int j = lane; j < 2 * hw; j += 64) planes[j] = 0.f;
+  __syncthreads();
+
+  f32x16 acc[NT];
+#pragma unroll
+  for (int j = 0; j < NT; ++j)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) acc[j][q] = 0.f;
+  // In groups of four steps (one branch per group); steps beyond the last map multiply a zero A.  Columns beyond P
+  // of the last tile read into the next map's row (or the zeros): finite, and never used.
+  for (int k0 = 0; k0 < a.m; k0 += 2 * U) {
+    if (k0) load_a(k0);
+#pragma unroll
+    for (int g0 = 0; g0 < U; g0 += 4) {
+      if (k0 + 2 * g0 < a.m) {
+        float bv[4][NT];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int k = min(k0 + 2 * (g0 + g) + half, a.m - 1);
+#pragma unroll
+          for (int j = 0; j < NT; ++j) bv[g][j] = dyl[k * a.P + l32 + 32 * j];
+        }
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+          for (int j = 0; j < NT; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[g0 + g], bv[g][j], acc[j], 0, 0, 0);
+      }
+    }
+  }
+
+  // phi_c^{-1}: tap (r, s) of output pixel (oy, ox) belongs to input pixel (oy - ph + r, ox - pw + s)
+  float* const plane = planes + half * hw;
+  int y0[NT], x0[NT];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    const int p = 32 * j + l32;
+    const int oy = p / a.ow;
+    y0[j] = p < a.P ? oy - a.ph : -(1 << 20);  // a pixel beyond the sample's last one lands outside the plane
+    x0[j] = p - oy * a.ow - a.pw;
+  }
+#pragma unroll
+  for (int q = 0; q < 16; ++q) {
+    const int rs = taprs[acc_row(q, lane)];
+    int idx[NT];
+    bool ok[NT];
+    float old[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      const int y = y0[j] + (rs >> 16), x = x0[j] + (rs & 0xffff);
+      ok[j] = rs >= 0 && (unsigned)y < (unsigned)a.h && (unsigned)x < (unsigned)a.w;
+      idx[j] = ok[j] ? y * a.w + x : 0;
+    }
+#pragma unroll
+    for (int j = 0; j < NT; ++j) old[j] = plane[idx[j]];
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+      if (ok[j]) plane[idx[j]] = old[j] + acc[j][q];
+  }
+  if (!c_ok) return;
+  T* dxp = static_cast<T*>(a.dx) + ((int64_t)n * a.c + c) * hw;
+  for (int j = lane; j < hw; j += 64) st(dxp + j, planes[j] + planes[hw + j]);
+}
+
+static constexpr size_t kSmallBwdLds = 96 * 1024;
+
+static size_t small_bwd_layout(int m, int P, int hw, int* dy_floats) {
+  *dy_floats = m * P + 32;  // the last tile's columns beyond P read on into the next row, at most 31 past the end
+  return (32 + (size_t)*dy_floats + (size_t)kSmallBwdWaves * 2 * hw) * sizeof(float);
+}
+
+// At most 32 taps and 128 output pixels per sample, a few hundred MFLOP as executed, more than four input channels.
+bool conv_small_bwd_applies(int dtype, int n, int c, int h, int w, int m, int r, int s, int ph, int pw) {
+  const int oh = h + 2 * ph - r + 1, ow = w + 2 * pw - s + 1;
+  if (dtype != VCNN_F32 || oh <= 0 || ow <= 0 || r * s > 32 || (int64_t)oh * ow > 128 || (int64_t)h * w > 1024 || c <= 4 ||
+      m <= 4 || m > 4096 || (int64_t)m * c * r * s > 0x7fffffffLL)
+    return false;
+  int dy_floats;
+  if (small_bwd_layout(m, oh * ow, h * w, &dy_floats) > kSmallBwdLds) return false;
+  const int64_t blocks = (int64_t)n * ceil_div(c, kSmallBwdWaves);
+  return blocks <= (1 << 16) && blocks * kSmallBwdWaves * 32 * ceil_div(oh * ow, 32) * 32 * m <= ((int64_t)1 << 29);
+}
+
+template <int NT>
+static void launch_small_bwd_nt(const SmallBwdArgs& a, dim3 grid, dim3 block, size_t lds, hipStream_t st) {
+  static bool opted = false;
+  if (!opted) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(conv_small_bwd_kernel<NT>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmallBwdLds);
+    opted = true;
+  }
+  hipLaunchKernelGGL(conv_small_bwd_kernel<NT>, grid, block, lds, st, a);
+}
+
+vcnn_status launch_conv_small_bwd(int n, int c, int h, int w, int m, int r, int s, int ph, int pw,
+                                  const void* dy, const void* wgt, void* dx, hipStream_t st) {
+  SmallBwdArgs a{};
+  a.dy = dy, a.wgt = wgt, a.dx = dx;
+  a.n = n, a.c = c, a.h = h, a.w = w, a.m = m, a.r = r, a.s = s, a.ph = ph, a.pw = pw;
+  a.oh = h + 2 * ph - r + 1, a.ow = w + 2 * pw - s + 1, a.P = a.oh * a.ow;
+  a.RS = r * s;
+  const size_t lds = small_bwd_layout(m, a.P, h * w, &a.dy_floats);
+  a.chunks = (int)ceil_div(c, kSmallBwdWaves);
+  const dim3 grid((unsigned)(n * a.chunks)), block(64 * kSmallBwdWaves);
+  switch ((int)ceil_div(a.P, 32)) {
+    case 1: launch_small_bwd_nt<1>(a, grid, block, lds, st); break;
+    case 2: launch_small_bwd_nt<2>(a, grid, block, lds, st); break;
+    case 3: launch_small_bwd_nt<3>(a, grid, block, lds, st); break;
+    case 4: launch_small_bwd_nt<4>(a, grid, block, lds, st); break;
+    default: return fail(VCNN_ERR_UNSUPPORTED, "conv_small_bwd: more than 128 output pixels per sample");
+  }
+  return check_launch("conv_small_bwd");
+}
+
 }  // namespace vcnn

@@ -37,6 +37,9 @@ CONV_SHAPES = [
     (2, 6, 40, 40, 48, 5, 5, 2, 2),     # 33..48 output maps: 16-row matrix-core tiles, wide pixel tile
     (3, 38, 14, 14, 38, 3, 3, 1, 1),    # ... in both directions (the input gradient has 38 maps too), small image
     (2, 40, 9, 30, 44, 2, 3, 0, 1),     # ... ragged everything
+    (3, 6, 9, 11, 7, 4, 3, 2, 0),       # small layer (fused input gradient): ragged channel group, odd map count, 3 pixel tiles
+    (2, 9, 6, 14, 33, 1, 1, 1, 0),      # ... one tap with padding, 4 pixel tiles, two batches of maps
+    (2, 8, 6, 6, 40, 5, 6, 4, 5),       # ... 'full' padding, 30 taps, large LDS tile
 ]
 
 
