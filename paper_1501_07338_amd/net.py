@@ -161,8 +161,10 @@ class TrainStep:
             if side is not main:  # fork: the parameter-gradient strand starts once d is complete
                 self.forked[li].record(main)
                 side.wait_event(self.forked[li])
-            vcnn.conv_bwd_filter(self.descs[li], a_in, d, dw, db, self.workspace_side, side)
+            # the input gradient first: the chain below waits for it, and a kernel-gradient block that is already
+            # resident can leave no LDS for it
             vcnn.conv_bwd_data(self.descs[li], w, d, self.dacts[li], self.workspace, main)
+            vcnn.conv_bwd_filter(self.descs[li], a_in, d, dw, db, self.workspace_side, side)
         if side is not main:  # join before anything reads the parameter gradients
             main.wait_stream(side)
 

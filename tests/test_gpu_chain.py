@@ -206,3 +206,22 @@ def test_hip_graph_replay_matches_eager(name, batch):
                 np.testing.assert_array_equal(to_np(graphed.params[li][0]), to_np(eager.params[li][0]),
                                               err_msg=f"replay {replay} w {li}")
         assert float(to_np(graphed.loss)) == float(to_np(eager.loss))
+
+
+@pytest.mark.parametrize("name,batch", [("cfg2", 32), ("cfg3", 16)])
+def test_one_stream_step_matches_two_stream_step(name, batch):
+    """The benchmark also times the step with every kernel on one stream; the schedule must not change a bit."""
+    net = wl.make_net(name, batch)
+    inputs, params = wl.make_inputs(net), wl.make_params(net)
+    two = TrainStep(net, params, inputs, device=DEV)
+    one = TrainStep(net, params, inputs, device=DEV, overlap=False)
+    assert one.side is None and two.side is not None
+    for _ in range(3):
+        two.step()
+        one.step()
+    torch.cuda.synchronize()
+    for li in range(len(net.layers)):
+        if two.grads[li] is not None:
+            np.testing.assert_array_equal(to_np(one.grads[li][0]), to_np(two.grads[li][0]), err_msg=f"dw {li}")
+            np.testing.assert_array_equal(to_np(one.params[li][0]), to_np(two.params[li][0]), err_msg=f"w {li}")
+    assert float(to_np(one.loss)) == float(to_np(two.loss))
