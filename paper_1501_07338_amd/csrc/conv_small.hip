@@ -25,6 +25,7 @@ struct SmallConvArgs {
   int n, c, h, w, m, r, s, ph, pw, oh, ow, P;
   int K, Kp;          // c*r*s, and rounded up to a multiple of 4 (tap-table length)
   int nr, wp;         // rows and row pitch of the staged tile, per channel
+  unsigned magic_plane, magic_wp;  // ceil(2^32 / (nr * wp)), ceil(2^32 / wp): division by multiply-high
   int vec_a;          // 16-byte kernel-matrix loads (K % 4 == 0, aligned)
   int relu;
   int tiles_m, tiles_per_img, kper;
@@ -59,15 +60,28 @@ __global__ __launch_bounds__(512) void conv_small_kernel(SmallConvArgs a) {
     }
     tapoff[k] = off;
   }
-  // the tile: input rows oh_first - ph + [0, nr), columns -pw + [0, wp) of every channel, zero outside the image
+  // the tile: input rows oh_first - ph + [0, nr), columns -pw + [0, wp) of every channel, zero outside the image;
+  // eight loads in flight per thread, the index split with multiply-high (exact: tile size * divisor < 2^32)
   const T* xin = static_cast<const T*>(a.x) + (int64_t)n * a.c * a.h * a.w;
-  for (int e = tid; e < a.c * plane; e += blockDim.x) {
-    const int cl = e / plane, rem = e - cl * plane;
-    const int ry = rem / a.wp, rx = rem - ry * a.wp;
-    const int ih = oh_first - a.ph + ry, iw = rx - a.pw;
-    const bool ok = ih >= 0 && ih < a.h && iw >= 0 && iw < a.w;
-    const float v = ld(xin + (ok ? (cl * a.h + ih) * a.w + iw : 0));
-    halo[e] = ok ? v : 0.f;
+  const int tile_elems = a.c * plane;
+  constexpr int SV = 8;
+  for (int e0 = tid; e0 < tile_elems; e0 += SV * blockDim.x) {
+    float v[SV];
+#pragma unroll
+    for (int u = 0; u < SV; ++u) {
+      const int e = min(e0 + u * (int)blockDim.x, tile_elems - 1);
+      const int cl = (int)__umulhi((unsigned)e, a.magic_plane), rem = e - cl * plane;
+      const int ry = (int)__umulhi((unsigned)rem, a.magic_wp), rx = rem - ry * a.wp;
+      const int ih = oh_first - a.ph + ry, iw = rx - a.pw;
+      const bool ok = ih >= 0 && ih < a.h && iw >= 0 && iw < a.w;
+      const float t = ld(xin + (ok ? (cl * a.h + ih) * a.w + iw : 0));
+      v[u] = ok ? t : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < SV; ++u) {
+      const int e = e0 + u * (int)blockDim.x;
+      if (e < tile_elems) halo[e] = v[u];
+    }
   }
 
   // this wave's share of the contraction, and the kernel-matrix row of this lane: requested now, used after the barrier
@@ -164,7 +178,7 @@ static size_t small_lds_bytes(int c, int w, int r, int s, int ph, int pw, int64_
 // contraction between 64 and 4096; tap table, tile and partial sums within the LDS of one block.
 bool conv_small_applies(int n, int c, int h, int w, int m, int r, int s, int ph, int pw) {
   const int oh = h + 2 * ph - r + 1, ow = w + 2 * pw - s + 1;
-  if (oh <= 0 || ow <= 0) return false;
+  if (oh <= 0 || ow <= 0 || w + 2 * pw < 2) return false;  // (a one-column tile has no 32-bit reciprocal)
   const int64_t K = (int64_t)c * r * s, P = (int64_t)oh * ow;
   if (K < 64 || K > 4096) return false;
   if ((int64_t)c * h * w > 0x7fffffffLL || (int64_t)m * P > 0x7fffffffLL) return false;
@@ -184,6 +198,8 @@ vcnn_status launch_conv_small(int dtype, int n, int c, int h, int w, int m, int 
   a.K = c * r * s, a.Kp = (a.K + 3) & ~3;
   a.relu = relu;
   const size_t lds = small_lds_bytes(c, w, r, s, ph, pw, a.K, &a.nr, &a.wp);
+  a.magic_plane = (unsigned)((((uint64_t)1 << 32) + (uint64_t)(a.nr * a.wp) - 1) / (uint64_t)(a.nr * a.wp));
+  a.magic_wp = (unsigned)((((uint64_t)1 << 32) + (uint64_t)a.wp - 1) / (uint64_t)a.wp);
   a.vec_a = a.K % 4 == 0 && (dtype == VCNN_BF16 ? group_aligned<bf16>(wgt) : group_aligned<float>(wgt));
   const int waves = small_waves(a.K);
   a.kper = (int)ceil_div(ceil_div(a.K, waves), 8) * 8;
