@@ -5,9 +5,9 @@ A "step" is one full training step (forward, cost, backward, SGD update) of a sy
 inputs and weights are already resident in HBM; every arithmetic step runs in libvcnn's HIP kernels.
 The headline line reports images/s on the small recognition CNN (workload cfg2: every operator of
 the path - unrolled convolutions, ReLU, max pooling, fully connected layers, softmax cost - is in
-it).  The step is timed twice - issued eagerly (one C call per layer pass) and replayed from a HIP graph
-recorded once - and the faster of the two is the figure, the other one riding along (`config.launch` says
-which was used).  Per-layer GFLOP/s of every convolution pass, the roofline figure of the dominant call,
+it).  The step is timed three ways - issued eagerly (one C call per layer pass) on one stream, eagerly with the
+parameter gradients on a second stream, and replayed from a HIP graph recorded once - and the fastest is the
+figure, the others riding along (`config.launch` says which was used).  Per-layer GFLOP/s of every convolution pass, the roofline figure of the dominant call,
 the other four workloads and the CPU-oracle baseline ride along in the same JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--others cfg1,cfg3,cfg4,cfg5]
@@ -273,8 +273,8 @@ MEASURED_TRAFFIC: dict = {
     "cfg2.conv2.fwd": 7.2e6,         # conv_small_kernel: 2699 KiB fetched (x2), 1600 KiB written
     "cfg2.conv2.bwd_filter": 19.6e6,   # conv_halo_filter_kernel<64, 256, ...> on 256 blocks: 2494 KiB fetched (x2),
                                        # 14146 KiB of partial products written (then added by sum_slices_split)
-    "cfg2.conv2.bwd_data": 19.2e6,     # gemm_f32_kernel<128, 128, 16, ...> writing the 16 MB patch-matrix gradient
-                                       # (1360 KiB fetched x2, 16000 KiB written; col2im then reads it back)
+    "cfg2.conv2.bwd_data": 4.1e6,      # conv_small_bwd_kernel<2>: 1294 KiB fetched (x2), 1440 KiB written (the
+                                       # patch-matrix gradient stays on chip)
     "cfg5.conv2.fwd": 356.1e6,       # conv_halo_kernel<128, 128, ...>
     "cfg5.conv2.bwd_filter": 479.9e6,  # conv_halo_filter_kernel<128, 128, ...> (without the slice sum)
     "cfg5.conv2.bwd_data": 7937.3e6,   # gemm_f32_kernel<128, 128, 16, ...> of the explicit route (without col2im)

@@ -251,6 +251,7 @@ struct SmallBwdArgs {
 };
 
 static constexpr int kSmallBwdWaves = 4;
+static constexpr int kXcds = 8;  // block ids are dealt round-robin to the chip's 8 accelerator dies
 
 template <int NT>  // 32-pixel tiles per sample
 __global__ __launch_bounds__(64 * kSmallBwdWaves, NT <= 2 ? 3 : 2) void conv_small_bwd_kernel(SmallBwdArgs a) {
@@ -263,8 +264,12 @@ __global__ __launch_bounds__(64 * kSmallBwdWaves, NT <= 2 ? 3 : 2) void conv_sma
   const int l32 = lane & 31, half = lane >> 5;
   const int hw = a.h * a.w;
   float* const planes = dyl + a.dy_floats + wave * 2 * hw;  // [2][h][w]: this wave's channel, one plane per half-wave
-  const int n = blockIdx.x / a.chunks;
-  const int c = (blockIdx.x - n * a.chunks) * kSmallBwdWaves + wave;
+  // Consecutive block ids go to different XCDs (each with its own L2): give every XCD a contiguous range of
+  // (sample, channel group) pairs, so that the groups of one sample fetch its dy through the same L2.
+  const int blocks = gridDim.x, xcd = blockIdx.x % kXcds;
+  const int b = xcd * (blocks / kXcds) + min(xcd, blocks % kXcds) + blockIdx.x / kXcds;
+  const int n = b / a.chunks;
+  const int c = (b - n * a.chunks) * kSmallBwdWaves + wave;
   const bool c_ok = c < a.c;  // a wave without a channel runs along on channel 0 and stores nothing
 
   // A operand: row = tap t of this wave's channel, contraction index = map

@@ -147,8 +147,14 @@ def test_conv_bwd_data(shape, algo):
     _, wt, _, dy = conv_case(shape, 600)
     d = vcnn.conv_desc(n, c, h, w, k, r, s, ph, pw)
     dx = torch.full((n, c, h, w), float("nan"), device=DEV)
-    vcnn.conv_bwd_data(d, to_dev(wt), to_dev(dy), dx, ws_for(d, vcnn.PASS_BWD_DATA))
+    ws = ws_for(d, vcnn.PASS_BWD_DATA)
+    vcnn.conv_bwd_data(d, to_dev(wt), to_dev(dy), dx, ws)
     assert_close(to_np(dx), O.conv_bwd_data(wt, dy, (h, w), pad=(ph, pw)), TOL_F32, "dx")
+    # run-to-run bit identity (fixed summation order on every route)
+    first = to_np(dx).copy()
+    dx.fill_(float("nan"))
+    vcnn.conv_bwd_data(d, to_dev(wt), to_dev(dy), dx, ws)
+    np.testing.assert_array_equal(to_np(dx), first)
 
 
 def test_bwd_filter_split_contraction_many_columns():
