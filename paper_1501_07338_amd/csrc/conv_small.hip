@@ -254,7 +254,7 @@ static constexpr int kSmallBwdWaves = 4;
 static constexpr int kXcds = 8;  // block ids are dealt round-robin to the chip's 8 accelerator dies
 
 template <int NT>  // 32-pixel tiles per sample
-__global__ __launch_bounds__(64 * kSmallBwdWaves, NT <= 2 ? 3 : 2) void conv_small_bwd_kernel(SmallBwdArgs a) {
+__global__ __launch_bounds__(64 * kSmallBwdWaves, NT <= 2 ? 4 : 2) void conv_small_bwd_kernel(SmallBwdArgs a) {
   using T = float;  // the bf16 variant has its own matrix-core route for these layers
   constexpr int kThreads = 64 * kSmallBwdWaves;
   extern __shared__ int small_lds[];

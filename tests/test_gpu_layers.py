@@ -40,6 +40,7 @@ CONV_SHAPES = [
     (3, 6, 9, 11, 7, 4, 3, 2, 0),       # small layer (fused input gradient): ragged channel group, odd map count, 3 pixel tiles
     (2, 9, 6, 14, 33, 1, 1, 1, 0),      # ... one tap with padding, 4 pixel tiles, two batches of maps
     (2, 8, 6, 6, 40, 5, 6, 4, 5),       # ... 'full' padding, 30 taps, large LDS tile
+    (2, 6, 8, 8, 70, 3, 3, 1, 1),       # ... more than 64 maps: the kernel-matrix entries come in two batches
 ]
 
 
