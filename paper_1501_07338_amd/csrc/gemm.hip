@@ -315,17 +315,22 @@ __global__ __launch_bounds__(1024) void gemm_small_kernel(GemmArgs a, int tiles_
   small_tile<A_KC, B_KC, A_VEC, B_VEC, TI, TO>(a, blockIdx.x, tiles_m, kper, red);
 }
 
-// Both products of a fully connected layer's backward pass in one launch: blocks [0, tiles_w) compute the
-// weight gradient dW = dY^T X (with the bias gradient as its column of ones), the rest the input gradient
-// dX = dY W.  The two are independent, and at these sizes neither fills the chip alone.
+// Both products of a fully connected layer's backward pass in one launch: tiles_w blocks compute the weight
+// gradient dW = dY^T X (with the bias gradient as its column of ones), tiles_x blocks the input gradient
+// dX = dY W.  The two are independent, and at these sizes neither fills the chip alone.  The product with the
+// longer contraction takes the low block ids: when the grid is a little larger than what is resident at once,
+// the blocks that start late are then the short ones.
 template <bool A_VEC, typename TI>
 __global__ __launch_bounds__(1024) void fc_bwd_small_kernel(GemmArgs gw, GemmArgs gx, int tiles_w, int tiles_m_w,
-                                                            int kper_w, int tiles_m_x, int kper_x) {
+                                                            int kper_w, int tiles_x, int tiles_m_x, int kper_x,
+                                                            int x_first) {
   extern __shared__ float red[];
-  if ((int)blockIdx.x < tiles_w)
-    small_tile<false, false, false, false, TI, float>(gw, blockIdx.x, tiles_m_w, kper_w, red);
+  const int b = blockIdx.x;
+  const bool is_w = x_first ? b >= tiles_x : b < tiles_w;
+  if (is_w)
+    small_tile<false, false, false, false, TI, float>(gw, x_first ? b - tiles_x : b, tiles_m_w, kper_w, red);
   else
-    small_tile<true, false, A_VEC, false, TI, TI>(gx, blockIdx.x - tiles_w, tiles_m_x, kper_x, red);
+    small_tile<true, false, A_VEC, false, TI, TI>(gx, x_first ? b : b - tiles_w, tiles_m_x, kper_x, red);
 }
 
 // one wave per 64 contraction indices, 4 to 8 of them (16 measured no faster and need 61 KB of LDS for the partial tiles)
@@ -604,12 +609,13 @@ vcnn_status launch_fc_bwd_small(const GemmArgs& gw, const GemmArgs& gx, hipStrea
   // launch returns the same bits as two separate ones
   const int kp_w = small_kper(gw.K, small_waves(gw.K)), kp_x = small_kper(gx.K, small_waves(gx.K));
   const bool av = in_aligned(gx.A, gx.in_dtype) && gx.a_si % 4 == 0 && gx.K % 4 == 0;
+  const int x_first = gx.K >= gw.K;
   if (gw.in_dtype == VCNN_BF16) {
-    if (av) hipLaunchKernelGGL((fc_bwd_small_kernel<true, bf16>), grid, block, lds, st, gw, gx, tiles_w, tm_w, kp_w, tm_x, kp_x);
-    else hipLaunchKernelGGL((fc_bwd_small_kernel<false, bf16>), grid, block, lds, st, gw, gx, tiles_w, tm_w, kp_w, tm_x, kp_x);
+    if (av) hipLaunchKernelGGL((fc_bwd_small_kernel<true, bf16>), grid, block, lds, st, gw, gx, tiles_w, tm_w, kp_w, tiles_x, tm_x, kp_x, x_first);
+    else hipLaunchKernelGGL((fc_bwd_small_kernel<false, bf16>), grid, block, lds, st, gw, gx, tiles_w, tm_w, kp_w, tiles_x, tm_x, kp_x, x_first);
   } else {
-    if (av) hipLaunchKernelGGL((fc_bwd_small_kernel<true, float>), grid, block, lds, st, gw, gx, tiles_w, tm_w, kp_w, tm_x, kp_x);
-    else hipLaunchKernelGGL((fc_bwd_small_kernel<false, float>), grid, block, lds, st, gw, gx, tiles_w, tm_w, kp_w, tm_x, kp_x);
+    if (av) hipLaunchKernelGGL((fc_bwd_small_kernel<true, float>), grid, block, lds, st, gw, gx, tiles_w, tm_w, kp_w, tiles_x, tm_x, kp_x, x_first);
+    else hipLaunchKernelGGL((fc_bwd_small_kernel<false, float>), grid, block, lds, st, gw, gx, tiles_w, tm_w, kp_w, tiles_x, tm_x, kp_x, x_first);
   }
   return check_launch("fc_bwd_small");
 }
