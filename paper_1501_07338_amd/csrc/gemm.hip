@@ -9,6 +9,8 @@
 // global loads of slab t+1 are issued before the MFMAs of slab t and written to the other LDS buffer
 // afterwards, so a block synchronises once per slab.
 
+#include <type_traits>
+
 #include "common.h"
 #include "elem.h"
 #include "mma_core.h"
@@ -225,26 +227,33 @@ static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 // -------------------------------------------------------------------------------------------------
 // GemmArgs::row_sums: B gets a virtual column j = N of ones, whose products - the row sums of A - go to
 // row_sums[i] (a fully connected layer's bias gradient comes out of its weight-gradient product this way).
-template <bool A_KC, bool B_KC, bool A_VEC, bool B_VEC, typename TI, typename TO>
+// T16: 16 x 16 tiles on v_mfma_f32_16x16x4_f32 instead of 32 x 32 on v_mfma_f32_32x32x2_f32, for products with so
+// few 32 x 32 tiles that most compute units would stay idle (four times the blocks, a quarter of the rows each).
+typedef float f32x4s __attribute__((ext_vector_type(4)));
+template <bool T16, bool A_KC, bool B_KC, bool A_VEC, bool B_VEC, typename TI, typename TO>
 __device__ __forceinline__ void small_tile(const GemmArgs& a, int tile, int tiles_m, int kper, float* red) {
+  constexpr int TS = T16 ? 16 : 32;    // tile side
+  constexpr int KL = T16 ? 4 : 2;      // lanes that share a row (each takes every KL-th group of four indices)
+  constexpr int GK = 4 * KL;           // contraction indices per group = 4 MFMA steps
+  constexpr int NQ = T16 ? 4 : 16;     // accumulator registers per lane
   const int waves = blockDim.x >> 6;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int l32 = lane & 31, half = lane >> 5;
-  const int i0 = (tile % tiles_m) * 32, j0 = (tile / tiles_m) * 32;
-  const int i = i0 + l32, j = j0 + l32;  // this lane's row of A and column of B
+  const int lr = lane & (TS - 1), kq = lane / TS;
+  const int i0 = (tile % tiles_m) * TS, j0 = (tile / tiles_m) * TS;
+  const int i = i0 + lr, j = j0 + lr;  // this lane's row of A and column of B
   const bool i_ok = i < a.M, j_ok = j < a.N;
   const bool j_ones = a.row_sums != nullptr && j == a.N;
   const TI* A = static_cast<const TI*>(a.A) + (int64_t)(i_ok ? i : 0) * a.a_si;
   const TI* B = static_cast<const TI*>(a.B) + (int64_t)(j_ok ? j : 0) * a.b_sj;
-  const int ks = wave * kper, ke = min(a.K, ks + kper);  // kper is a multiple of 8
+  const int ks = wave * kper, ke = min(a.K, ks + kper);  // kper is a multiple of GK
 
-  f32x16 acc;
+  typename std::conditional<T16, f32x4s, f32x16>::type acc;
 #pragma unroll
-  for (int q = 0; q < 16; ++q) acc[q] = 0.f;
+  for (int q = 0; q < NQ; ++q) acc[q] = 0.f;
 
-  // one group = 8 contraction indices = 4 MFMA steps; lanes 0-31 feed k0 + step, lanes 32-63 k0 + 4 + step
+  // one group = GK contraction indices = 4 MFMA steps; the lanes of a row feed k0 + 4 * kq + step
   auto load4 = [&](const TI* base, int64_t sk, bool kc, bool vec, bool row_ok, bool ones, int k0, float (&v)[4]) {
-    const int kb = k0 + 4 * half;
+    const int kb = k0 + 4 * kq;
     if (kc && vec) {
       const bool ok = row_ok && kb < ke;  // K and the split are multiples of 4: a group of four is in or out as a whole
       const float4 t = ld4(base + (ok ? kb : 0));
@@ -263,37 +272,40 @@ __device__ __forceinline__ void small_tile(const GemmArgs& a, int tile, int tile
     }
   };
   constexpr int U = 8;  // groups in flight
-  for (int k0 = ks; k0 < ke; k0 += 8 * U) {
+  for (int k0 = ks; k0 < ke; k0 += GK * U) {
     float av[U][4], bv[U][4];
-    const int ng = min(U, (ke - k0 + 7) >> 3);  // groups with work (wave-uniform): short shares skip the rest
+    const int ng = min(U, (ke - k0 + GK - 1) / GK);  // groups with work (wave-uniform): short shares skip the rest
 #pragma unroll
     for (int g = 0; g < U; ++g)
       if (g < ng) {
-        load4(A, a.a_sk, A_KC, A_VEC, i_ok, false, k0 + 8 * g, av[g]);
-        load4(B, a.b_sk, B_KC, B_VEC, j_ok, j_ones, k0 + 8 * g, bv[g]);
+        load4(A, a.a_sk, A_KC, A_VEC, i_ok, false, k0 + GK * g, av[g]);
+        load4(B, a.b_sk, B_KC, B_VEC, j_ok, j_ones, k0 + GK * g, bv[g]);
       }
 #pragma unroll
     for (int g = 0; g < U; ++g)
       if (g < ng) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[g][u], bv[g][u], acc, 0, 0, 0);
+        for (int u = 0; u < 4; ++u) {
+          if constexpr (T16) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[g][u], bv[g][u], acc, 0, 0, 0);
+          else acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av[g][u], bv[g][u], acc, 0, 0, 0);
+        }
       }
   }
 
   if (wave > 0) {
 #pragma unroll
-    for (int q = 0; q < 16; ++q) red[((wave - 1) * 16 + q) * 64 + lane] = acc[q];
+    for (int q = 0; q < NQ; ++q) red[((wave - 1) * NQ + q) * 64 + lane] = acc[q];
   }
   __syncthreads();
   if (wave > 0) return;
   for (int w = 0; w < waves - 1; ++w)
 #pragma unroll
-    for (int q = 0; q < 16; ++q) acc[q] += red[(w * 16 + q) * 64 + lane];
+    for (int q = 0; q < NQ; ++q) acc[q] += red[(w * NQ + q) * 64 + lane];
   if (!j_ok && !j_ones) return;
   TO* C = static_cast<TO*>(a.C);
 #pragma unroll
-  for (int q = 0; q < 16; ++q) {
-    const int row = i0 + acc_row(q, lane);
+  for (int q = 0; q < NQ; ++q) {
+    const int row = i0 + (T16 ? 4 * kq + q : acc_row(q, lane));
     if (row < a.M) {
       float v = acc[q];
       if (j_ones) {
@@ -310,9 +322,10 @@ __device__ __forceinline__ void small_tile(const GemmArgs& a, int tile, int tile
 }
 
 template <bool A_KC, bool B_KC, bool A_VEC, bool B_VEC, typename TI, typename TO>
-__global__ __launch_bounds__(1024) void gemm_small_kernel(GemmArgs a, int tiles_m, int kper) {
+__global__ __launch_bounds__(1024) void gemm_small_kernel(GemmArgs a, int tiles_m, int kper, int t16) {
   extern __shared__ float red[];  // [waves - 1][16][64]
-  small_tile<A_KC, B_KC, A_VEC, B_VEC, TI, TO>(a, blockIdx.x, tiles_m, kper, red);
+  if (t16) small_tile<true, A_KC, B_KC, A_VEC, B_VEC, TI, TO>(a, blockIdx.x, tiles_m, kper, red);
+  else small_tile<false, A_KC, B_KC, A_VEC, B_VEC, TI, TO>(a, blockIdx.x, tiles_m, kper, red);
 }
 
 // Both products of a fully connected layer's backward pass in one launch: tiles_w blocks compute the weight
@@ -323,36 +336,54 @@ __global__ __launch_bounds__(1024) void gemm_small_kernel(GemmArgs a, int tiles_
 template <bool A_VEC, typename TI>
 __global__ __launch_bounds__(1024) void fc_bwd_small_kernel(GemmArgs gw, GemmArgs gx, int tiles_w, int tiles_m_w,
                                                             int kper_w, int tiles_x, int tiles_m_x, int kper_x,
-                                                            int x_first) {
+                                                            int x_first, int w16, int x16) {
   extern __shared__ float red[];
   const int b = blockIdx.x;
   const bool is_w = x_first ? b >= tiles_x : b < tiles_w;
-  if (is_w)
-    small_tile<false, false, false, false, TI, float>(gw, x_first ? b - tiles_x : b, tiles_m_w, kper_w, red);
-  else
-    small_tile<true, false, A_VEC, false, TI, TI>(gx, x_first ? b : b - tiles_w, tiles_m_x, kper_x, red);
+  if (is_w) {
+    const int t = x_first ? b - tiles_x : b;
+    if (w16) small_tile<true, false, false, false, false, TI, float>(gw, t, tiles_m_w, kper_w, red);
+    else small_tile<false, false, false, false, false, TI, float>(gw, t, tiles_m_w, kper_w, red);
+  } else {
+    const int t = x_first ? b : b - tiles_w;
+    if (x16) small_tile<true, true, false, A_VEC, false, TI, TI>(gx, t, tiles_m_x, kper_x, red);
+    else small_tile<false, true, false, A_VEC, false, TI, TI>(gx, t, tiles_m_x, kper_x, red);
+  }
 }
 
 // one wave per 64 contraction indices, 4 to 8 of them (16 measured no faster and need 61 KB of LDS for the partial tiles)
 static int small_waves(int K) { return (int)std::min<int64_t>(8, std::max<int64_t>(4, ceil_div(K, 64))); }
-static int small_kper(int K, int waves) { return (int)ceil_div(ceil_div(K, waves), 8) * 8; }
 static int64_t small_tiles(const GemmArgs& a) { return ceil_div(a.M, 32) * ceil_div(a.N + (a.row_sums ? 1 : 0), 32); }
+// At most 64 tiles of 32 x 32 leave three quarters of the chip idle: 16 x 16 tiles then.  The choice depends on the
+// product alone, so a product returns the same bits whichever launch carries it.
+static bool small_use16(const GemmArgs& a) { return small_tiles(a) <= 64; }
+static int small_side(const GemmArgs& a) { return small_use16(a) ? 16 : 32; }
+static int64_t small_blocks(const GemmArgs& a) {
+  const int ts = small_side(a);
+  return ceil_div(a.M, ts) * ceil_div(a.N + (a.row_sums ? 1 : 0), ts);
+}
+// a wave's share of the contraction: a multiple of the indices one group of four MFMA steps covers (8 or 16)
+static int small_kper(const GemmArgs& a, int waves) {
+  const int gk = small_use16(a) ? 16 : 8;
+  return (int)ceil_div(ceil_div(a.K, waves), gk) * gk;
+}
 
 template <bool A_KC, bool B_KC, bool A_VEC, bool B_VEC>
 static void launch_small_t(const GemmArgs& a, hipStream_t st) {
-  const int tiles_m = (int)ceil_div(a.M, 32);
-  const int64_t tiles = small_tiles(a);
+  const int tiles_m = (int)ceil_div(a.M, small_side(a));
+  const int64_t tiles = small_blocks(a);
   const int waves = small_waves(a.K);
-  const int kper = small_kper(a.K, waves);
+  const int kper = small_kper(a, waves);
+  const int t16 = small_use16(a);
   const dim3 grid((unsigned)tiles), block(64 * waves);
   const size_t lds = (size_t)(waves - 1) * 16 * 64 * sizeof(float);
   const bool in16 = a.in_dtype == VCNN_BF16, out16 = a.out_dtype == VCNN_BF16;
   if (in16 && out16)
-    hipLaunchKernelGGL((gemm_small_kernel<A_KC, B_KC, A_VEC, B_VEC, bf16, bf16>), grid, block, lds, st, a, tiles_m, kper);
+    hipLaunchKernelGGL((gemm_small_kernel<A_KC, B_KC, A_VEC, B_VEC, bf16, bf16>), grid, block, lds, st, a, tiles_m, kper, t16);
   else if (in16)
-    hipLaunchKernelGGL((gemm_small_kernel<A_KC, B_KC, A_VEC, B_VEC, bf16, float>), grid, block, lds, st, a, tiles_m, kper);
+    hipLaunchKernelGGL((gemm_small_kernel<A_KC, B_KC, A_VEC, B_VEC, bf16, float>), grid, block, lds, st, a, tiles_m, kper, t16);
   else
-    hipLaunchKernelGGL((gemm_small_kernel<A_KC, B_KC, A_VEC, B_VEC, float, float>), grid, block, lds, st, a, tiles_m, kper);
+    hipLaunchKernelGGL((gemm_small_kernel<A_KC, B_KC, A_VEC, B_VEC, float, float>), grid, block, lds, st, a, tiles_m, kper, t16);
 }
 
 static void launch_small(const GemmArgs& a, bool a_kc, bool b_kc, bool av, bool bv, hipStream_t st) {
@@ -601,21 +632,22 @@ vcnn_status launch_bwd_filter_gemm_f32(const ConvGeom& g, int dtype, const void*
 // (A = dY contraction-contiguous, B = W); both must satisfy gemm_is_small.
 vcnn_status launch_fc_bwd_small(const GemmArgs& gw, const GemmArgs& gx, hipStream_t st) {
   const int waves = std::max(small_waves(gw.K), small_waves(gx.K));
-  const int tiles_w = (int)small_tiles(gw), tiles_x = (int)small_tiles(gx);
+  const int tiles_w = (int)small_blocks(gw), tiles_x = (int)small_blocks(gx);
   const dim3 grid((unsigned)(tiles_w + tiles_x)), block(64 * waves);
   const size_t lds = (size_t)(waves - 1) * 16 * 64 * sizeof(float);
-  const int tm_w = (int)ceil_div(gw.M, 32), tm_x = (int)ceil_div(gx.M, 32);
+  const int tm_w = (int)ceil_div(gw.M, small_side(gw)), tm_x = (int)ceil_div(gx.M, small_side(gx));
+  const int w16 = small_use16(gw), x16 = small_use16(gx);
   // each product keeps the split it has when launched alone (surplus waves get an empty share), so the fused
   // launch returns the same bits as two separate ones
-  const int kp_w = small_kper(gw.K, small_waves(gw.K)), kp_x = small_kper(gx.K, small_waves(gx.K));
+  const int kp_w = small_kper(gw, small_waves(gw.K)), kp_x = small_kper(gx, small_waves(gx.K));
   const bool av = in_aligned(gx.A, gx.in_dtype) && gx.a_si % 4 == 0 && gx.K % 4 == 0;
   const int x_first = gx.K >= gw.K;
   if (gw.in_dtype == VCNN_BF16) {
-    if (av) hipLaunchKernelGGL((fc_bwd_small_kernel<true, bf16>), grid, block, lds, st, gw, gx, tiles_w, tm_w, kp_w, tiles_x, tm_x, kp_x, x_first);
-    else hipLaunchKernelGGL((fc_bwd_small_kernel<false, bf16>), grid, block, lds, st, gw, gx, tiles_w, tm_w, kp_w, tiles_x, tm_x, kp_x, x_first);
+    if (av) hipLaunchKernelGGL((fc_bwd_small_kernel<true, bf16>), grid, block, lds, st, gw, gx, tiles_w, tm_w, kp_w, tiles_x, tm_x, kp_x, x_first, w16, x16);
+    else hipLaunchKernelGGL((fc_bwd_small_kernel<false, bf16>), grid, block, lds, st, gw, gx, tiles_w, tm_w, kp_w, tiles_x, tm_x, kp_x, x_first, w16, x16);
   } else {
-    if (av) hipLaunchKernelGGL((fc_bwd_small_kernel<true, float>), grid, block, lds, st, gw, gx, tiles_w, tm_w, kp_w, tiles_x, tm_x, kp_x, x_first);
-    else hipLaunchKernelGGL((fc_bwd_small_kernel<false, float>), grid, block, lds, st, gw, gx, tiles_w, tm_w, kp_w, tiles_x, tm_x, kp_x, x_first);
+    if (av) hipLaunchKernelGGL((fc_bwd_small_kernel<true, float>), grid, block, lds, st, gw, gx, tiles_w, tm_w, kp_w, tiles_x, tm_x, kp_x, x_first, w16, x16);
+    else hipLaunchKernelGGL((fc_bwd_small_kernel<false, float>), grid, block, lds, st, gw, gx, tiles_w, tm_w, kp_w, tiles_x, tm_x, kp_x, x_first, w16, x16);
   }
   return check_launch("fc_bwd_small");
 }
