@@ -273,7 +273,7 @@ MEASURED_TRAFFIC: dict = {
     "cfg2.conv2.fwd": 7.2e6,         # conv_small_kernel: 2699 KiB fetched (x2), 1600 KiB written
     "cfg2.conv2.bwd_filter": 19.6e6,   # conv_halo_filter_kernel<64, 256, ...> on 256 blocks: 2494 KiB fetched (x2),
                                        # 14146 KiB of partial products written (then added by sum_slices_split)
-    "cfg2.conv2.bwd_data": 4.1e6,      # conv_small_bwd_kernel<2>: 1294 KiB fetched (x2), 1440 KiB written (the
+    "cfg2.conv2.bwd_data": 4.1e6,      # conv_small_bwd_kernel<2, 3>: 1294 KiB fetched (x2), 1440 KiB written (the
                                        # patch-matrix gradient stays on chip)
     "cfg5.conv2.fwd": 356.1e6,       # conv_halo_kernel<128, 128, ...>
     "cfg5.conv2.bwd_filter": 479.9e6,  # conv_halo_filter_kernel<128, 128, ...> (without the slice sum)

@@ -253,8 +253,10 @@ struct SmallBwdArgs {
 static constexpr int kSmallBwdWaves = 4;
 static constexpr int kXcds = 8;  // block ids are dealt round-robin to the chip's 8 accelerator dies
 
-template <int NT>  // 32-pixel tiles per sample
-__global__ __launch_bounds__(64 * kSmallBwdWaves, NT <= 2 ? 4 : 2) void conv_small_bwd_kernel(SmallBwdArgs a) {
+// NT: 32-pixel tiles per sample.  WPS: waves per SIMD the registers are held to; 4 (a few values then live in
+// scratch memory) only pays when the grid would otherwise not be resident at once.
+template <int NT, int WPS>
+__global__ __launch_bounds__(64 * kSmallBwdWaves, WPS) void conv_small_bwd_kernel(SmallBwdArgs a) {
   using T = float;  // the bf16 variant has its own matrix-core route for these layers
   constexpr int kThreads = 64 * kSmallBwdWaves;
   extern __shared__ int small_lds[];
@@ -392,15 +394,23 @@ bool conv_small_bwd_applies(int dtype, int n, int c, int h, int w, int m, int r,
   return blocks <= (1 << 16) && blocks * kSmallBwdWaves * 32 * ceil_div(oh * ow, 32) * 32 * m <= ((int64_t)1 << 29);
 }
 
-template <int NT>
-static void launch_small_bwd_nt(const SmallBwdArgs& a, dim3 grid, dim3 block, size_t lds, hipStream_t st) {
+template <int NT, int WPS>
+static void launch_small_bwd_one(const SmallBwdArgs& a, dim3 grid, dim3 block, size_t lds, hipStream_t st) {
   static bool opted = false;
   if (!opted) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(conv_small_bwd_kernel<NT>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(conv_small_bwd_kernel<NT, WPS>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmallBwdLds);
     opted = true;
   }
-  hipLaunchKernelGGL(conv_small_bwd_kernel<NT>, grid, block, lds, st, a);
+  hipLaunchKernelGGL((conv_small_bwd_kernel<NT, WPS>), grid, block, lds, st, a);
+}
+
+template <int NT>
+static void launch_small_bwd_nt(const SmallBwdArgs& a, dim3 grid, dim3 block, size_t lds, hipStream_t st) {
+  // 256 compute units x 3 blocks are resident with 3 waves per SIMD; a larger grid (up to two pixel tiles) fits
+  // better with 4
+  if (NT <= 2 && grid.x > 768) launch_small_bwd_one<NT, NT <= 2 ? 4 : 2>(a, grid, block, lds, st);
+  else launch_small_bwd_one<NT, NT <= 2 ? 3 : 2>(a, grid, block, lds, st);
 }
 
 vcnn_status launch_conv_small_bwd(int n, int c, int h, int w, int m, int r, int s, int ph, int pw,

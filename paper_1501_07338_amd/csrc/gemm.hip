@@ -220,8 +220,8 @@ static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 // -------------------------------------------------------------------------------------------------
 // Small products (the fully connected layers at the experiments' batch sizes: a few MFLOP).  Their cost
 // is latency, not arithmetic: few tiles, and in the slab kernel above a chain of load -> barrier ->
-// MFMA rounds as long as the contraction.  Here a block owns one 32 x 32 tile of C and its waves (4 to
-// 8, more for longer contractions) split the contraction between them; every wave reads its operand
+// MFMA rounds as long as the contraction.  Here a block owns one 32 x 32 (or 16 x 16) tile of C and its waves
+// (4 to 8, more for longer contractions) split the contraction between them; every wave reads its operand
 // fragments straight from global memory, several groups of 8 contraction steps in flight at once (no LDS
 // staging, no barrier in the loop), and the partial tiles are added in wave order through LDS.
 // -------------------------------------------------------------------------------------------------
@@ -351,8 +351,9 @@ __global__ __launch_bounds__(1024) void fc_bwd_small_kernel(GemmArgs gw, GemmArg
   }
 }
 
-// one wave per 64 contraction indices, 4 to 8 of them (16 measured no faster and need 61 KB of LDS for the partial tiles)
-static int small_waves(int K) { return (int)std::min<int64_t>(8, std::max<int64_t>(4, ceil_div(K, 64))); }
+// 4 to 8 waves split the contraction, 8 from 128 indices on (16 measured no faster and need 61 KB of LDS for the
+// partial tiles)
+static int small_waves(int K) { return (int)std::min<int64_t>(8, std::max<int64_t>(4, ceil_div(K, 16))); }
 static int64_t small_tiles(const GemmArgs& a) { return ceil_div(a.M, 32) * ceil_div(a.N + (a.row_sums ? 1 : 0), 32); }
 // At most 64 tiles of 32 x 32 leave three quarters of the chip idle: 16 x 16 tiles then.  The choice depends on the
 // product alone, so a product returns the same bits whichever launch carries it.

@@ -310,7 +310,7 @@ def test_act(count):
     np.testing.assert_array_equal(to_np(xin), O.relu_fwd(x).astype(np.float32))
 
 
-@pytest.mark.parametrize("b,i,o", [(128, 800, 500), (128, 500, 10), (7, 33, 5), (1, 1, 1), (130, 70, 131), (128, 576, 64)])
+@pytest.mark.parametrize("b,i,o", [(128, 800, 500), (128, 500, 10), (7, 33, 5), (1, 1, 1), (130, 70, 131), (128, 576, 64), (40, 100, 48)])
 @pytest.mark.parametrize("relu", [False, True])
 def test_fc(b, i, o, relu):
     x, w, bias = random_tensor(1000, (b, i)), random_tensor(1001, (o, i), scale=(2.0 / i) ** 0.5), random_tensor(1002, (o,))
