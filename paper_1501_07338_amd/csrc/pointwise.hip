@@ -584,7 +584,9 @@ vcnn_status launch_col_sum(int dtype, int rows, int cols, const void* a, float* 
 
 // ---- costs --------------------------------------------------------------------------------------
 // Single block: thread t handles rows t, t+256, ...; the per-row losses are combined with the fixed
-// tree of block_sum.
+// tree of block_sum.  SMALL (at most 16 classes): a row is read into registers with all its loads in flight at
+// once - the kernel is one memory latency long instead of one per class - and the arithmetic is the same.
+template <bool SMALL>
 __global__ __launch_bounds__(kThreads) void softmax_loss_f32_kernel(int batch, int classes, const float* __restrict__ z,
                                                                     const int32_t* __restrict__ labels,
                                                                     float* __restrict__ loss, float* __restrict__ dz) {
@@ -593,16 +595,40 @@ __global__ __launch_bounds__(kThreads) void softmax_loss_f32_kernel(int batch, i
   const float inv_b = 1.f / (float)batch;
   for (int b = threadIdx.x; b < batch; b += kThreads) {
     const float* zb = z + (int64_t)b * classes;
-    float m = zb[0];
-    for (int j = 1; j < classes; ++j) m = fmaxf(m, zb[j]);
-    float se = 0.f;
-    for (int j = 0; j < classes; ++j) se += expf(zb[j] - m);
-    const float lse = m + logf(se);
-    const int lab = labels[b];
-    acc += lse - zb[lab];
-    if (dz)
-      for (int j = 0; j < classes; ++j)
-        dz[(int64_t)b * classes + j] = (expf(zb[j] - lse) - (j == lab ? 1.f : 0.f)) * inv_b;
+    if constexpr (SMALL) {
+      constexpr int C = 16;
+      float zr[C];
+#pragma unroll
+      for (int j = 0; j < C; ++j) zr[j] = zb[min(j, classes - 1)];
+      const int lab = labels[b];
+      float m = zr[0];
+#pragma unroll
+      for (int j = 1; j < C; ++j) m = j < classes ? fmaxf(m, zr[j]) : m;
+      float se = 0.f;
+#pragma unroll
+      for (int j = 0; j < C; ++j) se += j < classes ? expf(zr[j] - m) : 0.f;
+      const float lse = m + logf(se);
+      float zl = zr[0];
+#pragma unroll
+      for (int j = 1; j < C; ++j) zl = j == lab ? zr[j] : zl;
+      acc += lse - zl;
+      if (dz) {
+#pragma unroll
+        for (int j = 0; j < C; ++j)
+          if (j < classes) dz[(int64_t)b * classes + j] = (expf(zr[j] - lse) - (j == lab ? 1.f : 0.f)) * inv_b;
+      }
+    } else {
+      float m = zb[0];
+      for (int j = 1; j < classes; ++j) m = fmaxf(m, zb[j]);
+      float se = 0.f;
+      for (int j = 0; j < classes; ++j) se += expf(zb[j] - m);
+      const float lse = m + logf(se);
+      const int lab = labels[b];
+      acc += lse - zb[lab];
+      if (dz)
+        for (int j = 0; j < classes; ++j)
+          dz[(int64_t)b * classes + j] = (expf(zb[j] - lse) - (j == lab ? 1.f : 0.f)) * inv_b;
+    }
   }
   const float total = block_sum<kThreads>(acc, sm);
   if (threadIdx.x == 0 && loss) *loss = total * inv_b;
@@ -610,7 +636,10 @@ __global__ __launch_bounds__(kThreads) void softmax_loss_f32_kernel(int batch, i
 
 vcnn_status launch_softmax_loss_f32(int batch, int classes, const float* z, const int32_t* labels, float* loss,
                                     float* dz, hipStream_t st) {
-  hipLaunchKernelGGL(softmax_loss_f32_kernel, dim3(1), dim3(kThreads), 0, st, batch, classes, z, labels, loss, dz);
+  if (classes <= 16)
+    hipLaunchKernelGGL(softmax_loss_f32_kernel<true>, dim3(1), dim3(kThreads), 0, st, batch, classes, z, labels, loss, dz);
+  else
+    hipLaunchKernelGGL(softmax_loss_f32_kernel<false>, dim3(1), dim3(kThreads), 0, st, batch, classes, z, labels, loss, dz);
   return check_launch("softmax_loss_f32");
 }
 

@@ -387,7 +387,7 @@ def test_avgpool_fwd_bwd(shape):
     assert_close(to_np(dx), O.avgpool_bwd(dy, (h, w), (win, win), (st, st)), 1e-6, "avgpool dx")
 
 
-@pytest.mark.parametrize("b,c", [(128, 10), (1, 10), (300, 7), (5, 1)])
+@pytest.mark.parametrize("b,c", [(128, 10), (1, 10), (300, 7), (5, 1), (70, 16), (33, 17), (9, 100)])
 def test_softmax_loss(b, c):
     z = random_tensor(1100, (b, c), scale=3.0)
     labels = (np.arange(b) * 7 % c).astype(np.int32)
