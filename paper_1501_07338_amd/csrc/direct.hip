@@ -281,33 +281,45 @@ __global__ __launch_bounds__(kThreads) void sum_slices_kernel(const float* __res
   st(out + i, acc);
 }
 
-// The same sum for many slices of a short result: 16 lanes of a block share an output element, lane j adds
-// slices j, j + 16, ... (four loads in flight), and the 16 lane sums are added in lane order.  The order is
-// fixed by the shape alone, so results stay run-to-run identical.
+// The same sum for many slices of a short result: a block takes 16 consecutive output elements and 16 lanes share
+// an element; lane j adds slices j, j + 16, ... in ascending order, eight loads in flight, and the 16 lane sums are
+// added in lane order (32 elements x 8 lanes measured slower: the results are short, the slices many).  The order is fixed by the shape alone, so results stay
+// run-to-run identical.  Returns the element's sum in the threads of lane 0.
+static constexpr int kSumEl = 16, kSumLanes = kThreads / kSumEl;
+__device__ __forceinline__ float sum_slices_lanes(const float* __restrict__ partial, int64_t count, int64_t i, int splits,
+                                                  float (*lanes)[kSumEl + 1]) {
+  const int e = threadIdx.x & (kSumEl - 1), j = threadIdx.x / kSumEl;
+  float acc = 0.f;
+  if (i < count) {
+    int s = j;
+    for (; s + 7 * kSumLanes < splits; s += 8 * kSumLanes) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = partial[(int64_t)(s + kSumLanes * u) * count + i];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc += v[u];
+    }
+    for (; s < splits; s += kSumLanes) acc += partial[(int64_t)s * count + i];
+  }
+  lanes[j][e] = acc;
+  __syncthreads();
+  float total = 0.f;
+  if (j == 0) {
+#pragma unroll
+    for (int l = 0; l < kSumLanes; ++l) total += lanes[l][e];
+  }
+  return total;
+}
+
 template <typename TO>
 __global__ __launch_bounds__(kThreads) void sum_slices_wide_kernel(const float* __restrict__ partial,
                                                                    const float* __restrict__ bias,
                                                                    TO* __restrict__ out, int64_t count, int splits,
                                                                    int64_t plane, int maps, int relu) {
-  __shared__ float lanes[16][17];
-  const int e = threadIdx.x & 15, j = threadIdx.x >> 4;
-  const int64_t i = (int64_t)blockIdx.x * 16 + e;
-  float acc = 0.f;
-  if (i < count) {
-    int s = j;
-    for (; s + 48 < splits; s += 64) {
-      const float v0 = partial[(int64_t)s * count + i], v1 = partial[(int64_t)(s + 16) * count + i];
-      const float v2 = partial[(int64_t)(s + 32) * count + i], v3 = partial[(int64_t)(s + 48) * count + i];
-      acc = (((acc + v0) + v1) + v2) + v3;
-    }
-    for (; s < splits; s += 16) acc += partial[(int64_t)s * count + i];
-  }
-  lanes[j][e] = acc;
-  __syncthreads();
-  if (j != 0 || i >= count) return;
-  float total = 0.f;
-#pragma unroll
-  for (int l = 0; l < 16; ++l) total += lanes[l][e];
+  __shared__ float lanes[kSumLanes][kSumEl + 1];
+  const int64_t i = (int64_t)blockIdx.x * kSumEl + (threadIdx.x & (kSumEl - 1));
+  float total = sum_slices_lanes(partial, count, i, splits, lanes);
+  if (threadIdx.x >= kSumEl || i >= count) return;
   if (bias) total += bias[(i / plane) % maps];
   if (relu) total = fmaxf(total, 0.f);
   st(out + i, total);
@@ -318,26 +330,11 @@ __global__ __launch_bounds__(kThreads) void sum_slices_wide_kernel(const float* 
 __global__ __launch_bounds__(kThreads) void sum_slices_split_kernel(const float* __restrict__ partial,
                                                                     float* __restrict__ main, float* __restrict__ last,
                                                                     int64_t rows, int cols, int splits) {
-  __shared__ float lanes[16][17];
-  const int e = threadIdx.x & 15, j = threadIdx.x >> 4;
+  __shared__ float lanes[kSumLanes][kSumEl + 1];
   const int64_t count = rows * (cols + 1);
-  const int64_t i = (int64_t)blockIdx.x * 16 + e;
-  float acc = 0.f;
-  if (i < count) {
-    int s = j;
-    for (; s + 48 < splits; s += 64) {
-      const float v0 = partial[(int64_t)s * count + i], v1 = partial[(int64_t)(s + 16) * count + i];
-      const float v2 = partial[(int64_t)(s + 32) * count + i], v3 = partial[(int64_t)(s + 48) * count + i];
-      acc = (((acc + v0) + v1) + v2) + v3;
-    }
-    for (; s < splits; s += 16) acc += partial[(int64_t)s * count + i];
-  }
-  lanes[j][e] = acc;
-  __syncthreads();
-  if (j != 0 || i >= count) return;
-  float total = 0.f;
-#pragma unroll
-  for (int l = 0; l < 16; ++l) total += lanes[l][e];
+  const int64_t i = (int64_t)blockIdx.x * kSumEl + (threadIdx.x & (kSumEl - 1));
+  const float total = sum_slices_lanes(partial, count, i, splits, lanes);
+  if (threadIdx.x >= kSumEl || i >= count) return;
   const int64_t r = i / (cols + 1);
   const int c = (int)(i - r * (cols + 1));
   if (c < cols) main[r * cols + c] = total;
@@ -375,7 +372,7 @@ vcnn_status launch_sum_slices_split(const float* partial, float* main, float* la
                        partial, main, last, rows, cols, splits);
     return check_launch("sum_slices_split");
   }
-  hipLaunchKernelGGL(sum_slices_split_kernel, dim3((unsigned)ceil_div(count, 16)), dim3(kThreads), 0, st, partial, main, last,
+  hipLaunchKernelGGL(sum_slices_split_kernel, dim3((unsigned)ceil_div(count, kSumEl)), dim3(kThreads), 0, st, partial, main, last,
                      rows, cols, splits);
   return check_launch("sum_slices_split");
 }
@@ -383,7 +380,7 @@ vcnn_status launch_sum_slices_split(const float* partial, float* main, float* la
 vcnn_status launch_sum_slices(const float* partial, const float* bias, void* out, int out_dtype, int64_t count,
                               int splits, int64_t plane, int maps, int relu, hipStream_t st) {
   if (splits >= 32 && count <= 65536) {  // few output elements, many slices: parallelise over the slices as well
-    const dim3 grid((unsigned)ceil_div(count, 16)), block(kThreads);
+    const dim3 grid((unsigned)ceil_div(count, kSumEl)), block(kThreads);
     if (out_dtype == VCNN_BF16)
       hipLaunchKernelGGL(sum_slices_wide_kernel<bf16>, grid, block, 0, st, partial, bias, (bf16*)out, count, splits, plane,
                          maps, relu);
