@@ -147,12 +147,18 @@ __global__ __launch_bounds__(512) void conv_small_kernel(SmallConvArgs a) {
     for (int q = 0; q < 16; ++q) acc[q] += red[(w * 16 + q) * 64 + lane];
   if (p0 + l32 >= a.P) return;
   T* y = static_cast<T*>(a.y);
+  float bq[16];  // the bias of all 16 rows requested at once (clamped rows), not one wait per row
+#pragma unroll
+  for (int q = 0; q < 16; ++q) bq[q] = 0.f;
+  if (a.bias) {
+#pragma unroll
+    for (int q = 0; q < 16; ++q) bq[q] = a.bias[min(i0 + acc_row(q, lane), a.m - 1)];
+  }
 #pragma unroll
   for (int q = 0; q < 16; ++q) {
     const int row = i0 + acc_row(q, lane);
     if (row < a.m) {
-      float v = acc[q];
-      if (a.bias) v += a.bias[row];
+      float v = acc[q] + bq[q];
       if (a.relu) v = fmaxf(v, 0.f);
       st(y + ((int64_t)n * a.m + row) * a.P + p, v);
     }

@@ -303,6 +303,22 @@ __device__ __forceinline__ void small_tile(const GemmArgs& a, int tile, int tile
     for (int q = 0; q < NQ; ++q) acc[q] += red[(w * NQ + q) * 64 + lane];
   if (!j_ok && !j_ones) return;
   TO* C = static_cast<TO*>(a.C);
+  // what the epilogue reads (bias, the activation below) is requested for all rows at once, at clamped addresses,
+  // before any of it is used: one memory latency instead of one per accumulator register
+  float bq[NQ], rq[NQ];
+#pragma unroll
+  for (int q = 0; q < NQ; ++q) bq[q] = 0.f, rq[q] = 0.f;
+  if (a.bias) {
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) bq[q] = a.bias[min(i0 + (T16 ? 4 * kq + q : acc_row(q, lane)), a.M - 1)];
+  }
+  if (a.dact && !j_ones) {
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+      const int row = min(i0 + (T16 ? 4 * kq + q : acc_row(q, lane)), a.M - 1);
+      rq[q] = ld(static_cast<const TO*>(a.dact_ref) + (int64_t)row * a.c_si + (int64_t)j * a.c_sj);
+    }
+  }
 #pragma unroll
   for (int q = 0; q < NQ; ++q) {
     const int row = i0 + (T16 ? 4 * kq + q : acc_row(q, lane));
@@ -312,10 +328,10 @@ __device__ __forceinline__ void small_tile(const GemmArgs& a, int tile, int tile
         a.row_sums[row] = v;
         continue;
       }
-      if (a.bias) v += a.bias[row];
+      v += bq[q];
       if (a.relu) v = fmaxf(v, 0.f);
       const int64_t at = (int64_t)row * a.c_si + (int64_t)j * a.c_sj;
-      if (a.dact) v = act_grad(a.dact, ld(static_cast<const TO*>(a.dact_ref) + at), v);
+      if (a.dact) v = act_grad(a.dact, rq[q], v);
       st(C + at, v);
     }
   }
