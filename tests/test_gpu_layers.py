@@ -41,6 +41,7 @@ CONV_SHAPES = [
     (2, 9, 6, 14, 33, 1, 1, 1, 0),      # ... one tap with padding, 4 pixel tiles, two batches of maps
     (2, 8, 6, 6, 40, 5, 6, 4, 5),       # ... 'full' padding, 30 taps, large LDS tile
     (2, 6, 8, 8, 70, 3, 3, 1, 1),       # ... more than 64 maps: the kernel-matrix entries come in two batches
+    (200, 16, 7, 7, 8, 3, 3, 1, 1),     # ... more blocks than are resident at once (the tighter register budget)
 ]
 
 
