@@ -312,9 +312,23 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_staged_kernel(vcnn_pool_des
   const int out_plane = oh_n * ow_n, in_plane = d.h * d.w;
   float* dy_s = pool_lds;
   int* am_s = reinterpret_cast<int*>(pool_lds + pb * out_plane);
-  for (int i = threadIdx.x; i < np * out_plane; i += kThreads) {
-    dy_s[i] = ld(dy + nc0 * out_plane + i);
-    am_s[i] = argmax[nc0 * out_plane + i];
+  // Small planes make this kernel one of memory latency: everything a thread reads from global memory (records
+  // here, the activation reference below) is requested several elements ahead of its use.
+  const int recs = np * out_plane;
+  for (int i0 = threadIdx.x; i0 < recs; i0 += 4 * kThreads) {
+    float dv[4];
+    int av[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = min(i0 + u * kThreads, recs - 1);
+      dv[u] = ld(dy + nc0 * out_plane + i);
+      av[u] = argmax[nc0 * out_plane + i];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = i0 + u * kThreads;
+      if (i < recs) dy_s[i] = dv[u], am_s[i] = av[u];
+    }
   }
   __syncthreads();
   const int win_h = WIN ? WIN : d.win_h, win_w = WIN ? WIN : d.win_w;
@@ -332,9 +346,19 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_staged_kernel(vcnn_pool_des
     int pl = threadIdx.x / items;
     int hi = (threadIdx.x - pl * items) / wq;
     int wg = threadIdx.x - pl * items - hi * wq;
-    for (int e = threadIdx.x; e < np * items; e += kThreads, pl += d_pl, hi += d_hi, wg += d_wg) {
+    constexpr int U = 4;
+    const int total4 = np * items;
+    for (int e0 = threadIdx.x; e0 < total4; e0 += U * kThreads) {
+      float4 yv[U];  // item e is the e-th group of four pixels of the block's planes
+      if (act) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) yv[u] = ld4(ref + nc0 * in_plane + 4 * (int64_t)min(e0 + u * kThreads, total4 - 1));
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u, pl += d_pl, hi += d_hi, wg += d_wg) {
       if (wg >= wq) wg -= wq, ++hi;
       if (hi >= d.h) hi -= d.h, ++pl;
+      if (e0 + u * kThreads >= total4) continue;
       const int w0 = wg * 4;
       int oh_lo = hi - WIN + 1;
       oh_lo = oh_lo > 0 ? (oh_lo + STRIDE - 1) / STRIDE : 0;
@@ -358,11 +382,12 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_staged_kernel(vcnn_pool_des
         }
       const int64_t at = nc0 * in_plane + (int64_t)pl * in_plane + pos0;
       if (act) {
-        const float4 y = ld4(ref + at);
+        const float4 y = yv[u];
         acc[0] = act_grad(act, y.x, acc[0]), acc[1] = act_grad(act, y.y, acc[1]);
         acc[2] = act_grad(act, y.z, acc[2]), acc[3] = act_grad(act, y.w, acc[3]);
       }
       st4(dx + at, make_float4(acc[0], acc[1], acc[2], acc[3]));
+      }
     }
     return;
   }
@@ -372,9 +397,20 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_staged_kernel(vcnn_pool_des
   int pl = threadIdx.x / in_plane;
   int hi = (threadIdx.x - pl * in_plane) / d.w;
   int wi = threadIdx.x - pl * in_plane - hi * d.w;
-  for (int e = threadIdx.x; e < np * in_plane; e += kThreads, pl += d_pl, hi += d_hi, wi += d_wi) {
+  constexpr int U = 8;
+  const int total = np * in_plane;
+  for (int e0 = threadIdx.x; e0 < total; e0 += U * kThreads) {
+    float rv[U];
+    if (act) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) rv[u] = ld(ref + nc0 * in_plane + min(e0 + u * kThreads, total - 1));
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u, pl += d_pl, hi += d_hi, wi += d_wi) {
+    const int e = e0 + u * kThreads;
     if (wi >= d.w) wi -= d.w, ++hi;
     if (hi >= d.h) hi -= d.h, ++pl;
+    if (e >= total) continue;
     const int pos = hi * d.w + wi;
     int oh_lo = hi - win_h + 1;
     oh_lo = oh_lo > 0 ? (oh_lo + sh - 1) / sh : 0;
@@ -403,8 +439,9 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_staged_kernel(vcnn_pool_des
           if (am_s[o] == pos) acc += dy_s[o];
         }
     }
-    if (act) acc = act_grad(act, ld(ref + nc0 * in_plane + e), acc);
+    if (act) acc = act_grad(act, rv[u], acc);
     st(dx + nc0 * in_plane + e, acc);
+    }
   }
 }
 
