@@ -356,37 +356,37 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_staged_kernel(vcnn_pool_des
       }
 #pragma unroll
       for (int u = 0; u < U; ++u, pl += d_pl, hi += d_hi, wg += d_wg) {
-      if (wg >= wq) wg -= wq, ++hi;
-      if (hi >= d.h) hi -= d.h, ++pl;
-      if (e0 + u * kThreads >= total4) continue;
-      const int w0 = wg * 4;
-      int oh_lo = hi - WIN + 1;
-      oh_lo = oh_lo > 0 ? (oh_lo + STRIDE - 1) / STRIDE : 0;
-      const int oh_hi = min(oh_n - 1, hi / STRIDE);
-      int ow_lo = w0 - WIN + 1;
-      ow_lo = ow_lo > 0 ? (ow_lo + STRIDE - 1) / STRIDE : 0;
-      const int ow_hi = min(ow_n - 1, (w0 + 3) / STRIDE);
-      const int base = pl * out_plane, pos0 = hi * d.w + w0;
-      float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        if (wg >= wq) wg -= wq, ++hi;
+        if (hi >= d.h) hi -= d.h, ++pl;
+        if (e0 + u * kThreads >= total4) continue;
+        const int w0 = wg * 4;
+        int oh_lo = hi - WIN + 1;
+        oh_lo = oh_lo > 0 ? (oh_lo + STRIDE - 1) / STRIDE : 0;
+        const int oh_hi = min(oh_n - 1, hi / STRIDE);
+        int ow_lo = w0 - WIN + 1;
+        ow_lo = ow_lo > 0 ? (ow_lo + STRIDE - 1) / STRIDE : 0;
+        const int ow_hi = min(ow_n - 1, (w0 + 3) / STRIDE);
+        const int base = pl * out_plane, pos0 = hi * d.w + w0;
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int a = 0; a < ROWS; ++a)
+        for (int a = 0; a < ROWS; ++a)
 #pragma unroll
-        for (int b = 0; b < COLS; ++b) {
-          const int oh = oh_lo + a, ow = ow_lo + b;
-          const bool ok = oh <= oh_hi && ow <= ow_hi;
-          const int o = base + (ok ? oh * ow_n + ow : 0);
-          const int j = am_s[o] - pos0;
-          const float g = ok ? dy_s[o] : 0.f;
+          for (int b = 0; b < COLS; ++b) {
+            const int oh = oh_lo + a, ow = ow_lo + b;
+            const bool ok = oh <= oh_hi && ow <= ow_hi;
+            const int o = base + (ok ? oh * ow_n + ow : 0);
+            const int j = am_s[o] - pos0;
+            const float g = ok ? dy_s[o] : 0.f;
 #pragma unroll
-          for (int t = 0; t < 4; ++t) acc[t] += j == t ? g : 0.f;
+            for (int t = 0; t < 4; ++t) acc[t] += j == t ? g : 0.f;
+          }
+        const int64_t at = nc0 * in_plane + (int64_t)pl * in_plane + pos0;
+        if (act) {
+          const float4 y = yv[u];
+          acc[0] = act_grad(act, y.x, acc[0]), acc[1] = act_grad(act, y.y, acc[1]);
+          acc[2] = act_grad(act, y.z, acc[2]), acc[3] = act_grad(act, y.w, acc[3]);
         }
-      const int64_t at = nc0 * in_plane + (int64_t)pl * in_plane + pos0;
-      if (act) {
-        const float4 y = yv[u];
-        acc[0] = act_grad(act, y.x, acc[0]), acc[1] = act_grad(act, y.y, acc[1]);
-        acc[2] = act_grad(act, y.z, acc[2]), acc[3] = act_grad(act, y.w, acc[3]);
-      }
-      st4(dx + at, make_float4(acc[0], acc[1], acc[2], acc[3]));
+        st4(dx + at, make_float4(acc[0], acc[1], acc[2], acc[3]));
       }
     }
     return;
@@ -407,40 +407,40 @@ __global__ __launch_bounds__(kThreads) void pool_bwd_staged_kernel(vcnn_pool_des
     }
 #pragma unroll
     for (int u = 0; u < U; ++u, pl += d_pl, hi += d_hi, wi += d_wi) {
-    const int e = e0 + u * kThreads;
-    if (wi >= d.w) wi -= d.w, ++hi;
-    if (hi >= d.h) hi -= d.h, ++pl;
-    if (e >= total) continue;
-    const int pos = hi * d.w + wi;
-    int oh_lo = hi - win_h + 1;
-    oh_lo = oh_lo > 0 ? (oh_lo + sh - 1) / sh : 0;
-    const int oh_hi = min(oh_n - 1, hi / sh);
-    int ow_lo = wi - win_w + 1;
-    ow_lo = ow_lo > 0 ? (ow_lo + sw - 1) / sw : 0;
-    const int ow_hi = min(ow_n - 1, wi / sw);
-    const int base = pl * out_plane;
-    float acc = 0.f;
-    if (WIN && STRIDE) {
-      // at most ceil(WIN/STRIDE) windows per axis cover a pixel: a fixed set, visited with a predicate
-      constexpr int CAND = WIN && STRIDE ? (WIN + STRIDE - 1) / STRIDE : 1;
+      const int e = e0 + u * kThreads;
+      if (wi >= d.w) wi -= d.w, ++hi;
+      if (hi >= d.h) hi -= d.h, ++pl;
+      if (e >= total) continue;
+      const int pos = hi * d.w + wi;
+      int oh_lo = hi - win_h + 1;
+      oh_lo = oh_lo > 0 ? (oh_lo + sh - 1) / sh : 0;
+      const int oh_hi = min(oh_n - 1, hi / sh);
+      int ow_lo = wi - win_w + 1;
+      ow_lo = ow_lo > 0 ? (ow_lo + sw - 1) / sw : 0;
+      const int ow_hi = min(ow_n - 1, wi / sw);
+      const int base = pl * out_plane;
+      float acc = 0.f;
+      if (WIN && STRIDE) {
+        // at most ceil(WIN/STRIDE) windows per axis cover a pixel: a fixed set, visited with a predicate
+        constexpr int CAND = WIN && STRIDE ? (WIN + STRIDE - 1) / STRIDE : 1;
 #pragma unroll
-      for (int a = 0; a < CAND; ++a)
+        for (int a = 0; a < CAND; ++a)
 #pragma unroll
-        for (int b = 0; b < CAND; ++b) {
-          const int oh = oh_lo + a, ow = ow_lo + b;
-          const bool ok = oh <= oh_hi && ow <= ow_hi;
-          const int o = base + (ok ? oh * ow_n + ow : 0);
-          acc += (ok && am_s[o] == pos) ? dy_s[o] : 0.f;
-        }
-    } else {
-      for (int oh = oh_lo; oh <= oh_hi; ++oh)
-        for (int ow = ow_lo; ow <= ow_hi; ++ow) {
-          const int o = base + oh * ow_n + ow;
-          if (am_s[o] == pos) acc += dy_s[o];
-        }
-    }
-    if (act) acc = act_grad(act, rv[u], acc);
-    st(dx + nc0 * in_plane + e, acc);
+          for (int b = 0; b < CAND; ++b) {
+            const int oh = oh_lo + a, ow = ow_lo + b;
+            const bool ok = oh <= oh_hi && ow <= ow_hi;
+            const int o = base + (ok ? oh * ow_n + ow : 0);
+            acc += (ok && am_s[o] == pos) ? dy_s[o] : 0.f;
+          }
+      } else {
+        for (int oh = oh_lo; oh <= oh_hi; ++oh)
+          for (int ow = ow_lo; ow <= ow_hi; ++ow) {
+            const int o = base + oh * ow_n + ow;
+            if (am_s[o] == pos) acc += dy_s[o];
+          }
+      }
+      if (act) acc = act_grad(act, rv[u], acc);
+      st(dx + nc0 * in_plane + e, acc);
     }
   }
 }
