@@ -3,19 +3,27 @@
 
 A "step" is one full training step (forward, cost, backward, SGD update) of a synthetic network whose
 inputs and weights are already resident in HBM; every arithmetic step runs in libvcnn's HIP kernels.
-The headline line reports images/s on the small recognition CNN (workload cfg2: every operator of
-the path - unrolled convolutions, ReLU, max pooling, fully connected layers, softmax cost - is in
-it).  The step is timed three ways - issued eagerly (one C call per layer pass) on one stream, eagerly with the
-parameter gradients on a second stream, and replayed from a HIP graph recorded once - and the fastest is the
-figure, the others riding along (`config.launch` says which was used).  Per-layer GFLOP/s of every convolution pass, the roofline figure of the dominant call,
-the other four workloads and the CPU-oracle baseline ride along in the same JSON line.
+The headline is the largest of the five workloads, the deconvolution CNN cfg5 in fp32 (1.29 TFLOP per
+step): images/s of the training step, GFLOP/s of its convolution passes against the fp32 matrix-core
+peak, and the roofline record of the pass that takes the most time.  cfg5 with bf16 storage and
+cfg1-cfg4 ride along as compact summaries; the long per-layer tables, the bandwidth-bound kernels and
+the mini-batch sweep go to gpurun_out/bench_detail.json.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--others cfg1,cfg3,cfg4,cfg5]
+Every timed step starts from the same seeded parameters: the squared-error networks (cfg4, cfg5) leave
+the range of finite floats within three plain-SGD steps at the stated learning rate, so the initial
+parameters are restored before each step, outside the step's event pair, and the per-layer timings run
+on the tensors of exactly one step.  Each step is bracketed by its own pair of events on the stream it
+is issued on; ms_per_step is the mean over the K timed steps.  A non-finite loss aborts the run.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5] [--others cfg5_bf16,cfg1,...]
 """
 from __future__ import annotations
 
 import argparse
 import json
+import math
+import os
+import statistics
 import sys
 import time
 from pathlib import Path
@@ -24,6 +32,7 @@ ROOT = Path(__file__).resolve().parent
 if str(ROOT) not in sys.path:
     sys.path.insert(0, str(ROOT))
 
+METRIC = "conv fwd+bwd GFLOP/s (% MFMA peak) and images/sec per training step, 1 GPU"  # the benchmark's
 HBM_PEAK_GBS = 8000.0
 MFMA_F32_PEAK_TFLOPS = 157.3
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 -> fp32 accumulate
@@ -35,8 +44,11 @@ WORKLOAD_TEXT = {
             "full training step",
     "cfg4": "cfg4: denoising CNN, batch 64x1x64x64, conv9x9x64-conv5x5x32-conv5x5x1 'same', L2 loss, full training step",
     "cfg5": "cfg5: deconvolution CNN, batch 16x1x184x184, conv121x1x38-conv1x121x38-conv16x16x512-conv1x1x512-conv8x8x1 "
-            "valid, L2 loss, full training step",
+            "valid, L2 loss, full training step (fwd + cost + bwd + SGD)",
 }
+LAUNCH_TEXT = {"graph": "one HIP-graph replay per step (parameter gradients on a second branch)",
+               "two_streams": "eager: one C call per layer pass, parameter gradients on a second stream",
+               "one_stream": "eager: one C call per layer pass, one stream"}
 
 
 def conv_geom(net, li):
@@ -50,7 +62,7 @@ def conv_geom(net, li):
 
 def time_calls(fn, iters, stream):
     """Average duration in ms of `fn` over `iters` back-to-back enqueues, measured with events on
-    the stream the kernels are launched on."""
+    the stream the kernels are launched on (one untimed call first)."""
     import torch
     start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     fn()
@@ -63,19 +75,30 @@ def time_calls(fn, iters, stream):
     return start.elapsed_time(stop) / iters
 
 
-def timed_steps(fn, steps, stream):
-    """Wall-clock and GPU-event time per step of `steps` calls of fn, synchronised on both sides."""
+def timed_steps(fn, steps, stream, before=None):
+    """Times exactly `steps` calls of fn, each between its own pair of events on `stream`, synchronised on
+    both sides of the whole region; `before` (the parameter restore) runs ahead of each step outside its
+    event pair.  Returns (mean ms per step, median ms per step, wall ms per step including `before`)."""
     import torch
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
     torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
-    ev0.record(stream)
-    for _ in range(steps):
+    for a, b in pairs:
+        if before is not None:
+            before()
+        a.record(stream)
         fn()
-    ev1.record(stream)
+        b.record(stream)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / steps
-    return max(wall_ms, ev0.elapsed_time(ev1) / steps)
+    ms = [a.elapsed_time(b) for a, b in pairs]
+    return sum(ms) / steps, statistics.median(ms), wall_ms
+
+
+def finite_or_die(name, loss):
+    if not math.isfinite(loss):
+        sys.exit(f"bench.py: {name}: the loss is not finite ({loss}); refusing to report timings of non-finite tensors")
+    return loss
 
 
 def run_workload(name, steps, warmup, layer_iters=10):
@@ -88,37 +111,49 @@ def run_workload(name, steps, warmup, layer_iters=10):
     net = wl.make_net(name[:-5] if bf16 else name)
     inputs, params = wl.make_inputs(net), wl.make_params(net)
     ts = TrainStep(net, params, inputs, device="cuda:0", first_layer_dx=False, dtype=vcnn.BF16 if bf16 else vcnn.F32)
+    ts.snapshot()
     esize = 2.0 if bf16 else 4.0
     stream = torch.cuda.current_stream()
-    for _ in range(warmup):
-        ts.step()
-    eager_ms = timed_steps(ts.step, steps, stream)
-    side, ts.side = ts.side, None  # the same step with every kernel on one stream (no fork / join events)
-    for _ in range(warmup):
-        ts.step()
-    single_ms = timed_steps(ts.step, steps, stream)
-    ts.side = side
-    graph = ts.capture()
-    for _ in range(warmup):
-        graph.replay()
-    graph_ms = timed_steps(graph.replay, steps, stream)
+    losses = []
+
+    def timed(fn):
+        for _ in range(warmup):
+            ts.restore()
+            fn()
+        res = timed_steps(fn, steps, stream, before=ts.restore)
+        losses.append(finite_or_die(name, float(ts.loss.item())))  # the loss of a first step, every time
+        return res
+
     # The same step, issued three ways; the fastest is the workload's figure.  On the small networks every kernel
     # is a few microseconds, the fork / join between the two streams costs more than the overlap returns and a
     # plain in-order launch wins; on the large ones the parameter-gradient strand on a second stream pays, eagerly
     # or as a replayed graph.
-    modes = {"one HIP-graph replay per step (parameter gradients on a second branch)": graph_ms,
-             "eager: one C call per layer pass, parameter gradients on a second stream": eager_ms,
-             "eager: one C call per layer pass, one stream": single_ms}
-    launch = min(modes, key=modes.get)
-    best_ms = modes[launch]
+    modes = {}
+    modes["two_streams"] = timed(ts.step)
+    side, ts.side = ts.side, None  # the same step with every kernel on one stream (no fork / join events)
+    modes["one_stream"] = timed(ts.step)
+    ts.side = side
+    ts.restore()
+    graph = ts.capture()
+    modes["graph"] = timed(graph.replay)
+    assert max(losses) - min(losses) <= 1e-6 * abs(losses[0]), f"{name}: the three launch modes disagree on the loss {losses}"
+    launch = min(modes, key=lambda m: modes[m][0])
+    best_ms = modes[launch][0]
     res = {"workload": name, "batch": net.batch, "storage_dtype": "bf16" if bf16 else "f32", "ms_per_step": best_ms,
-           "launch": launch,
-           "ms_per_step_graph": graph_ms, "ms_per_step_eager": eager_ms, "ms_per_step_eager_one_stream": single_ms,
-           "images_per_s": net.batch / (best_ms * 1e-3), "images_per_s_graph": net.batch / (graph_ms * 1e-3),
-           "images_per_s_eager": net.batch / (eager_ms * 1e-3),
-           "images_per_s_eager_one_stream": net.batch / (single_ms * 1e-3),
-           "loss_after_timed_steps": float(ts.loss.item())}
+           "ms_per_step_median": modes[launch][1], "wall_ms_per_step_with_restore": modes[launch][2],
+           "launch": launch, "ms_per_step_by_launch": {m: v[0] for m, v in modes.items()},
+           "images_per_s": net.batch / (best_ms * 1e-3), "loss_first_step": losses[0]}
 
+    # Per-layer passes on the tensors of exactly one step from the seeded parameters (no update applied)
+    ts.restore()
+    ts.forward()
+    ts.cost()
+    ts.backward()
+    torch.cuda.synchronize()
+    finite_or_die(name, float(ts.loss.item()))
+    for t in ts.acts + [g for pair in ts.grads if pair is not None for g in pair]:
+        if not bool(torch.isfinite(t.float()).all()):
+            sys.exit(f"bench.py: {name}: non-finite tensor ahead of the per-layer timings")
     layers = []
     conv_flops = conv_ms = 0.0
     for li, L in enumerate(net.layers):
@@ -131,31 +166,52 @@ def run_workload(name, steps, warmup, layer_iters=10):
         a_in, a_out = ts.acts[li], ts.acts[li + 1]
         dy = ts.dpre.get(li, ts.dacts[li + 1])  # the gradient w.r.t. the pre-activation, as the step passes it
         flops = 2.0 * g["M"] * g["K"] * g["N"]
+        dx_buf = ts.dacts[li] if li > 0 else torch.empty_like(a_in)
+        y_buf = torch.empty_like(a_out)  # the forward pass is re-run into a spare buffer: the step's tensors stay as they are
         passes = {
-            "fwd": lambda: vcnn.conv_fwd(d, a_in, w, b, a_out, ts.workspace),
+            "fwd": lambda: vcnn.conv_fwd(d, a_in, w, b, y_buf, ts.workspace),
             "bwd_filter": lambda: vcnn.conv_bwd_filter(d, a_in, dy, dw, db, ts.workspace_side),
-            "bwd_data": lambda: vcnn.conv_bwd_data(d, w, dy, ts.dacts[li], ts.workspace),
+            "bwd_data": lambda: vcnn.conv_bwd_data(d, w, dy, dx_buf, ts.workspace),
         }
         in_b = esize * g["n"] * g["c"] * g["h"] * g["w"]
         out_b = esize * g["M"] * g["N"]
         w_b = esize * g["M"] * g["K"]
+        ws_need = max(vcnn.conv_workspace_bytes(d, p) for p in (vcnn.PASS_FWD, vcnn.PASS_BWD_DATA))
+        assert ts.workspace.numel() >= ws_need
         for pname, fn in passes.items():
             t = time_calls(fn, layer_iters, stream)
+            peak = MFMA_BF16_PEAK_TFLOPS if bf16 else MFMA_F32_PEAK_TFLOPS
             layers.append({"layer": f"conv{li}", "pass": pname, "M": g["M"], "K": g["K"], "N": g["N"], "ms": t,
                            "gflops": flops / (t * 1e6),
-                           "pct_mfma_f32_peak": 100.0 * flops / (t * 1e9) / MFMA_F32_PEAK_TFLOPS,
-                           # the bf16 variant contracts on the bf16 matrix-core instructions: price it against their peak
-                           "pct_mfma_peak": 100.0 * flops / (t * 1e9) / (MFMA_BF16_PEAK_TFLOPS if bf16 else MFMA_F32_PEAK_TFLOPS),
+                           # the bf16 variant contracts on the bf16 matrix-core instructions: priced against their peak
+                           "pct_mfma_peak": 100.0 * flops / (t * 1e9) / peak,
                            "algorithmic_bytes": in_b + out_b + w_b, "gbs": (in_b + out_b + w_b) / (t * 1e6),
                            "in_step": not (li == 0 and pname == "bwd_data")})
             if not (li == 0 and pname == "bwd_data"):
                 conv_flops += flops
                 conv_ms += t
+        del y_buf, dx_buf
     res["conv_layers"] = layers
     res["conv_gflops_fwd_bwd"] = conv_flops / (conv_ms * 1e6) if conv_ms else None
-    res["conv_pct_mfma_f32_peak"] = 100.0 * res["conv_gflops_fwd_bwd"] / (MFMA_F32_PEAK_TFLOPS * 1e3) if conv_ms else None
+    peak = MFMA_BF16_PEAK_TFLOPS if bf16 else MFMA_F32_PEAK_TFLOPS
+    res["conv_pct_mfma_peak"] = 100.0 * res["conv_gflops_fwd_bwd"] / (peak * 1e3) if conv_ms else None
     res["roofline"] = dominant_roofline(res)
+    del graph, ts
+    torch.cuda.empty_cache()
     return res
+
+
+def measured_traffic(name):
+    """HBM bytes per launch of the named pass from the tracked counter summary (profiles/traffic.json, written by
+    `python -m paper_1501_07338_amd.benchaid.profile_summary` from two rocprofv3 --pmc runs); None if not covered."""
+    path = ROOT / "profiles" / "traffic.json"
+    if not path.exists():
+        return None
+    try:
+        rec = json.loads(path.read_text()).get("passes", {}).get(name)
+    except (ValueError, OSError):
+        return None
+    return None if rec is None else rec.get("hbm_bytes")
 
 
 def dominant_roofline(res):
@@ -173,16 +229,19 @@ def dominant_roofline(res):
     if flops / top["algorithmic_bytes"] >= peak * 1e3 / HBM_PEAK_GBS:
         ach = flops / (top["ms"] * 1e9)
         return {"kernel": name, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s",
-                "frac": ach / peak, "traffic": MEASURED_TRAFFIC.get(name)}
+                "frac": ach / peak, "traffic": measured_traffic(name), "ms": top["ms"], "flops": flops}
     ach = top["algorithmic_bytes"] / (top["ms"] * 1e6)
     return {"kernel": name, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": ach / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC.get(name)}
+            "frac": ach / HBM_PEAK_GBS, "traffic": measured_traffic(name), "ms": top["ms"],
+            "bytes": top["algorithmic_bytes"]}
 
 
 def hbm_kernels(stream):
     """Achieved GB/s of the bandwidth-bound kernels at the largest shapes of the workloads: the explicit
-    unroll phi_c / phi_c^{-1} (cfg4 c2: 1.68 GB patch matrix; cfg5 c5: 3.7 GB), max pooling (cfg3 p1)
-    and ReLU (cfg4 c1 output).  Algorithmic bytes over the median of three timing loops."""
+    unroll phi_c / phi_c^{-1} (cfg4 c2: 1.68 GB patch matrix; cfg5 c5: 3.7 GB), max pooling (cfg3 p1 at the
+    workload's batch 128, and at batch 2048, which is NOT a workload of the benchmark: it only shows the
+    kernel's bandwidth once the tensor is no longer launch-latency sized) and ReLU (cfg4 c1 output).
+    Algorithmic bytes over the median of three timing loops."""
     import torch
     from paper_1501_07338_amd import vcnn
     out = []
@@ -191,9 +250,12 @@ def hbm_kernels(stream):
         ts = sorted(time_calls(fn, 10, stream) for _ in range(3))
         return ts[1]
 
-    def rec(kernel, shape, nbytes, ms):
-        out.append({"kernel": kernel, "shape": shape, "algorithmic_bytes": nbytes, "ms": ms, "gbs": nbytes / (ms * 1e6),
-                    "frac_hbm_peak": nbytes / (ms * 1e6) / HBM_PEAK_GBS})
+    def rec(kernel, shape, nbytes, ms, note=None):
+        r = {"kernel": kernel, "shape": shape, "algorithmic_bytes": nbytes, "ms": ms, "gbs": nbytes / (ms * 1e6),
+             "frac_hbm_peak": nbytes / (ms * 1e6) / HBM_PEAK_GBS}
+        if note:
+            r["note"] = note
+        out.append(r)
 
     for name, (n, c, h, w, k, r, s, ph, pw) in {"cfg4.c2": (64, 64, 64, 64, 32, 5, 5, 2, 2),
                                                  "cfg5.c5": (16, 512, 49, 49, 1, 8, 8, 0, 0)}.items():
@@ -207,9 +269,8 @@ def hbm_kernels(stream):
         rec("im2col", name, nbytes, timed(lambda: vcnn.im2col(d, x, col)))
         rec("col2im", name, nbytes, timed(lambda: vcnn.col2im(d, col, dx)))
         del x, col, dx
-    # cfg3 p1 (3x3 stride 2, 24 MB: launch-latency sized) and the same layer at 16x the batch, where the
-    # tensor is large enough for the bandwidth to show
-    for name, n in {"cfg3.p1": 128, "cfg3.p1 at batch 2048": 2048}.items():
+    for name, n, note in (("cfg3.p1", 128, None),
+                          ("cfg3.p1 at batch 2048", 2048, "not a BASELINE config: the layer at 16x the workload's batch")):
         c, h, w = 32, 32, 32
         d = vcnn.pool_desc(n, c, h, w, 3, 3, 2, 2)
         oh, ow = vcnn.pool_out_shape(d)
@@ -217,33 +278,43 @@ def hbm_kernels(stream):
         y = torch.empty(n, c, oh, ow, device="cuda")
         am = torch.empty(n, c, oh, ow, dtype=torch.int32, device="cuda")
         dy, dx = torch.randn_like(y), torch.empty_like(x)
-        rec("pool_fwd", name, 4.0 * (x.numel() + 2 * y.numel()), timed(lambda: vcnn.pool_fwd(d, x, y, am)))
-        rec("pool_bwd", name, 4.0 * (x.numel() + 2 * y.numel()), timed(lambda: vcnn.pool_bwd(d, dy, am, dx)))
+        rec("pool_fwd", name, 4.0 * (x.numel() + 2 * y.numel()), timed(lambda: vcnn.pool_fwd(d, x, y, am)), note)
+        rec("pool_bwd", name, 4.0 * (x.numel() + 2 * y.numel()), timed(lambda: vcnn.pool_bwd(d, dy, am, dx)), note)
         del x, y, am, dy, dx
     t = torch.randn(64, 64, 64, 64, device="cuda")  # cfg4 c1 output
     g, o = torch.randn_like(t), torch.empty_like(t)
     rec("relu_bwd", "cfg4.c1 output", 12.0 * t.numel(), timed(lambda: vcnn.act_bwd(vcnn.ACT_RELU, vcnn.F32, t.numel(), t, g, o)))
+    del t, g, o
     torch.cuda.empty_cache()
     return out
 
 
-def mfma_sustained(stream):
-    """Matrix-core rate with register operands only (no memory traffic): what the chip sustains under MFMA
-    load, reported beside the data-sheet peaks the roofline fractions are quoted against."""
+def aids(stream):
+    """The benchmark's own yardsticks (outside the layer library): the matrix-core rate with register operands
+    only - what the chip sustains under MFMA load, beside the data-sheet peaks the roofline fractions are quoted
+    against - and a plain streaming copy of 1 GiB, the kernel of known size that the HBM traffic counters of a
+    profiler run are scaled by."""
     import torch
-    from paper_1501_07338_amd import vcnn
+    from paper_1501_07338_amd import benchaid
     blocks, out = 512, {}
     sink = torch.empty(blocks * 256, device="cuda")
-    for name, dtype, iters, peak in (("f32", vcnn.F32, 20000, MFMA_F32_PEAK_TFLOPS), ("bf16", vcnn.BF16, 40000, 2500.0)):
-        flop = vcnn.probe_mfma(dtype, blocks, iters, sink)
-        ms = sorted(time_calls(lambda: vcnn.probe_mfma(dtype, blocks, iters, sink), 3, stream) for _ in range(3))[1]
-        out[name] = {"sustained_tflops": flop / (ms * 1e9), "data_sheet_tflops": peak, "ms": ms}
+    for name, bf16, iters, peak in (("f32", False, 20000, MFMA_F32_PEAK_TFLOPS), ("bf16", True, 40000, MFMA_BF16_PEAK_TFLOPS)):
+        flop = benchaid.mfma(bf16, blocks, iters, sink)
+        ms = sorted(time_calls(lambda: benchaid.mfma(bf16, blocks, iters, sink), 3, stream) for _ in range(3))[1]
+        out["mfma_" + name] = {"sustained_tflops": flop / (ms * 1e9), "data_sheet_tflops": peak, "ms": ms}
+    src = torch.empty(1 << 28, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    ms = sorted(time_calls(lambda: benchaid.copy(src, dst), 5, stream) for _ in range(3))[1]
+    out["copy_1GiB"] = {"bytes_moved": 2.0 * src.numel() * 4, "ms": ms, "gbs": 2.0 * src.numel() * 4 / (ms * 1e6)}
+    del src, dst, sink
+    torch.cuda.empty_cache()
     return out
 
 
 def batch_sweep(stream, steps=50):
     """Training and forward-only images/s of the two recognition networks over the mini-batch sizes of the
-    paper's batch experiments (Tables 3 and 4: 1, 100, 200, 300, 400)."""
+    paper's batch experiments (Tables 3 and 4: 1, 100, 200, 300, 400).  These softmax networks stay finite
+    under repeated updates (checked), so their steps run back to back."""
     import torch
     from paper_1501_07338_amd import workloads as wl
     from paper_1501_07338_amd.net import TrainStep
@@ -252,13 +323,15 @@ def batch_sweep(stream, steps=50):
         for b in (1, 100, 200, 300, 400):
             net = wl.make_net(name, b)
             ts = TrainStep(net, wl.make_params(net), wl.make_inputs(net), device="cuda:0")
+            ts.snapshot()
             for _ in range(5):
                 ts.step()
             graph = ts.capture()
             for _ in range(5):
                 graph.replay()
-            train_ms = timed_steps(graph.replay, steps, stream)
-            fwd_ms = timed_steps(ts.forward, steps, stream)
+            train_ms = timed_steps(graph.replay, steps, stream, before=ts.restore)[0]
+            finite_or_die(f"{name} batch {b}", float(ts.loss.item()))
+            fwd_ms = timed_steps(ts.forward, steps, stream)[0]
             rows.append({"workload": name, "batch": b, "train_ms_per_step": train_ms, "train_images_per_s": b / (train_ms * 1e-3),
                          "forward_ms": fwd_ms, "forward_images_per_s": b / (fwd_ms * 1e-3)})
             del ts, graph
@@ -266,55 +339,73 @@ def batch_sweep(stream, steps=50):
     return rows
 
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/); filled in
-# from the committed summaries, None where no counter run covers the kernel.
-MEASURED_TRAFFIC: dict = {
-    # (2 x FETCH_SIZE + WRITE_SIZE) x 1024 of the call's main kernel, profiles/cfg5_cfg4_cfg2_hbm_traffic_pmc.txt
-    "cfg2.conv2.fwd": 7.2e6,         # conv_small_kernel: 2699 KiB fetched (x2), 1600 KiB written
-    "cfg2.conv2.bwd_filter": 19.6e6,   # conv_halo_filter_kernel<64, 256, ...> on 256 blocks: 2494 KiB fetched (x2),
-                                       # 14146 KiB of partial products written (then added by sum_slices_split)
-    "cfg2.conv2.bwd_data": 4.1e6,      # conv_small_bwd_kernel<2, 3>: 1294 KiB fetched (x2), 1440 KiB written (the
-                                       # patch-matrix gradient stays on chip)
-    "cfg5.conv2.fwd": 356.1e6,       # conv_halo_kernel<128, 128, ...>
-    "cfg5.conv2.bwd_filter": 479.9e6,  # conv_halo_filter_kernel<128, 128, ...> (without the slice sum)
-    "cfg5.conv2.bwd_data": 7937.3e6,   # gemm_f32_kernel<128, 128, 16, ...> of the explicit route (without col2im)
-    "cfg5_bf16.conv2.fwd": 199.9e6,    # conv_halo_bf16_kernel<4, 1, 2, 5> (without the two re-layout passes)
-    "cfg5_bf16.conv2.bwd_filter": 425.8e6,  # filter_grad_bf16_kernel<4, 1, 2, 4>
-    "cfg5_bf16.conv2.bwd_data": 635.2e6,    # conv_halo_bf16_kernel<1, 4, 3, 8, true>: the kernel matrix is re-fetched past L2
-}
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
-def cpu_baseline(name, budget_s=20.0):
-    """The fp64 oracle, as it stands, timed on this host's cores on the same workload."""
+def cpu_baseline(name, budget_s=30.0):
+    """The fp64 oracle, as it stands, timed on this host's cores on a bounded sample of the same workload: whole
+    training steps of the network at a mini-batch small enough for about 10-30 s of CPU work (cfg5: one sample of
+    the 16, every layer at its full spatial size; the oracle's loops are per sample, so images/s carries over)."""
     import oracle
     from oracle.net import train_step
     from paper_1501_07338_amd import workloads as wl
-    net = wl.make_net(name)
+    base = name[:-5] if name.endswith("_bf16") else name
+    full = wl.make_net(base)
+    batch = {"cfg5": 1, "cfg4": 8}.get(base, full.batch)
+    net = wl.make_net(base, batch)
     inputs, params = wl.make_inputs(net), wl.make_params(net)
-    train_step(net, inputs, params)  # warm-up (loads the library, touches memory)
     times = []
     t_all = time.perf_counter()
-    while len(times) < 3 or (time.perf_counter() - t_all < 0.5 * budget_s and len(times) < 15):
+    while not times or (time.perf_counter() - t_all < 0.5 * budget_s and len(times) < 15):
         t0 = time.perf_counter()
         train_step(net, inputs, params)
         times.append(time.perf_counter() - t0)
-        if time.perf_counter() - t_all > budget_s:
-            break
-    times.sort()
-    med = times[len(times) // 2]
-    return {"value": net.batch / med, "unit": "images/s", "cores": oracle.threads(), "kind": "oracle",
-            "sample": f"{len(times)} full training steps of {name} (batch {net.batch}), median", "s_per_step": med}
+    med = statistics.median(times)
+    return {"value": batch / med, "unit": "images/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"{len(times)} full training step(s) of {base} at batch {batch} of {full.batch} "
+                      f"(all layers at full spatial size), median; fp64 nested loops",
+            "s_per_step": med, "cpu_model": cpu_model()}
+
+
+def summary(r):
+    """The compact per-workload record of the JSON line."""
+    out = {k: r[k] for k in ("batch", "storage_dtype", "ms_per_step", "images_per_s", "launch", "loss_first_step")}
+    out["conv_tflops_fwd_bwd"] = None if r["conv_gflops_fwd_bwd"] is None else r["conv_gflops_fwd_bwd"] / 1e3
+    out["conv_pct_mfma_peak"] = r["conv_pct_mfma_peak"]
+    rf = r.get("roofline")
+    if rf:
+        out["roofline"] = {k: rf[k] for k in ("kernel", "bound", "achieved", "peak", "unit", "frac", "traffic")}
+    return out
+
+
+def rounded(o, digits=5):
+    if isinstance(o, float):
+        return float(f"{o:.{digits}g}")
+    if isinstance(o, dict):
+        return {k: rounded(v, digits) for k, v in o.items()}
+    if isinstance(o, (list, tuple)):
+        return [rounded(v, digits) for v in o]
+    return o
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2")
-    ap.add_argument("--others", default="cfg1,cfg3,cfg4,cfg5,cfg5_bf16", help="comma list of further workloads to report ('' for none)")
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg5")
+    ap.add_argument("--others", default="cfg5_bf16,cfg4,cfg3,cfg2,cfg1", help="comma list of further workloads to report ('' for none)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--no-sweep", action="store_true", help="skip the mini-batch sweep of cfg2 / cfg3")
+    ap.add_argument("--no-hbm", action="store_true", help="skip the bandwidth-bound kernels and the benchmark's yardsticks")
+    ap.add_argument("--detail", default=str(ROOT / "gpurun_out" / "bench_detail.json"), help="where the long tables go")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the layer path is single-GPU); use --gpus 1")
@@ -328,32 +419,56 @@ def main():
     main_res = run_workload(args.workload, args.steps, args.warmup)
     others = {}
     for name in [s for s in args.others.split(",") if s and s != args.workload]:
-        big = name.startswith(("cfg4", "cfg5"))
-        others[name] = run_workload(name, max(3, min(args.steps, 20)) if big else args.steps,
-                                    max(2, min(args.warmup, 3)) if big else args.warmup, layer_iters=5 if big else 10)
-        torch.cuda.empty_cache()
+        small = name in ("cfg1", "cfg2", "cfg3")
+        others[name] = run_workload(name, max(args.steps, 100) if small else args.steps, args.warmup,
+                                    layer_iters=10 if small else 5)
 
+    detail = {"main": main_res, "other_workloads": others}
+    stream = torch.cuda.current_stream()
+    if not args.no_hbm:
+        detail["hbm_kernels"] = hbm_kernels(stream)
+        detail["yardsticks"] = aids(stream)
+    if not args.no_sweep:
+        detail["batch_sweep"] = batch_sweep(stream)
+
+    base = args.workload[:-5] if args.workload.endswith("_bf16") else args.workload
     out = {
-        "metric": "images/sec per training step (conv fwd+bwd GFLOP/s and % of fp32 MFMA peak alongside)",
+        "metric": METRIC,
         "value": main_res["images_per_s"], "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": WORKLOAD_TEXT.get(args.workload, args.workload), "launch": main_res["launch"],
-                   "graph_ms_per_step": main_res["ms_per_step_graph"], "eager_ms_per_step": main_res["ms_per_step_eager"],
-                   "eager_one_stream_ms_per_step": main_res["ms_per_step_eager_one_stream"]},
-        "conv_gflops_fwd_bwd": main_res.get("conv_gflops_fwd_bwd"),
-        "conv_pct_mfma_f32_peak": main_res.get("conv_pct_mfma_f32_peak"),
-        "roofline": main_res["roofline"],
-        "conv_layers": main_res.get("conv_layers"),
-        "hbm_kernels": hbm_kernels(torch.cuda.current_stream()),
-        "mfma_sustained": mfma_sustained(torch.cuda.current_stream()),
-        "other_workloads": others,
+        "dtype": main_res["storage_dtype"], "data": "synthetic",
+        "config": {"workload": WORKLOAD_TEXT.get(base, base) + (" [bf16 storage, fp32 accumulation]" if base != args.workload else ""),
+                   "launch": LAUNCH_TEXT[main_res["launch"]], "ms_per_step_by_launch": main_res["ms_per_step_by_launch"],
+                   "ms_per_step_median": main_res["ms_per_step_median"],
+                   "timing": "each step between its own event pair on the launch stream, mean of the K steps; the seeded "
+                             "parameters are restored before every step outside the pair",
+                   "loss_first_step": main_res["loss_first_step"]},
+        "conv_gflops_fwd_bwd": main_res["conv_gflops_fwd_bwd"],
+        "conv_pct_mfma_peak": main_res["conv_pct_mfma_peak"],
+        "roofline": {k: main_res["roofline"][k] for k in ("kernel", "bound", "achieved", "peak", "unit", "frac", "traffic")},
+        # [layer, pass, ms, TFLOP/s, % of the matrix-core peak]
+        "conv_layers": [[l["layer"], l["pass"], l["ms"], l["gflops"] / 1e3, l["pct_mfma_peak"]] for l in main_res["conv_layers"]],
+        "other_workloads": {k: summary(v) for k, v in others.items()},
     }
-    if not args.no_sweep:
-        out["batch_sweep"] = batch_sweep(torch.cuda.current_stream())
+    if "hbm_kernels" in detail:
+        out["hbm_kernels"] = [[h["kernel"], h["shape"], h["gbs"], h["frac_hbm_peak"]] for h in detail["hbm_kernels"]]
+        out["yardsticks"] = {"mfma_f32_sustained_tflops": detail["yardsticks"]["mfma_f32"]["sustained_tflops"],
+                             "mfma_bf16_sustained_tflops": detail["yardsticks"]["mfma_bf16"]["sustained_tflops"],
+                             "copy_1GiB_gbs": detail["yardsticks"]["copy_1GiB"]["gbs"]}
+    if "batch_sweep" in detail:  # [workload, batch, training images/s, forward-only images/s]
+        out["batch_sweep"] = [[r["workload"], r["batch"], r["train_images_per_s"], r["forward_images_per_s"]]
+                              for r in detail["batch_sweep"]]
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(args.workload)
-    print(json.dumps(out))
+        detail["cpu_baseline"] = out["cpu_baseline"]
+    try:
+        os.makedirs(os.path.dirname(args.detail), exist_ok=True)
+        with open(args.detail, "w") as f:
+            json.dump(detail, f, allow_nan=False, indent=1)
+        out["detail_file"] = os.path.relpath(args.detail, ROOT)
+    except (OSError, ValueError) as e:
+        out["detail_file"] = f"not written: {e}"
+    print(json.dumps(rounded(out), allow_nan=False))
 
 
 if __name__ == "__main__":

@@ -168,7 +168,8 @@ vcnn_status vcnn_fc_bwd_act(int32_t dtype, int32_t batch, int32_t in_f, int32_t 
 
 /* Softmax + cross-entropy cost, mean over the batch: loss = (1/B) sum_b (logsumexp(z_b) - z_b[label_b]),
  * dlogits[b][j] = (softmax(z_b)[j] - [j == label_b]) / B.  loss is a device scalar; dlogits may be NULL.
- * Labels outside [0, classes) are not detected. */
+ * Precondition: 0 <= labels[b] < classes.  A label outside that range is never used as an index: the loss and
+ * that sample's row of dlogits come out as NaN, and the call still returns VCNN_OK (the labels live on the device). */
 vcnn_status vcnn_softmax_loss(int32_t batch, int32_t classes, const float* logits, const int32_t* labels,
                               float* loss, float* dlogits, void* stream);
 /* Squared-error cost for the image-to-image networks: loss = 1/(2*batch) * sum (y-t)^2, dy = (y-t)/batch.
@@ -187,13 +188,6 @@ vcnn_status vcnn_sgd_update_multi(int32_t tensors, const size_t* counts, float* 
 /* Rounds a float tensor to bfloat16 (nearest even) and back: dst_bf16[i] = bf16(src[i]);  src_f32[i] = float(bf16). */
 vcnn_status vcnn_f32_to_bf16(size_t count, const float* src, void* dst, void* stream);
 vcnn_status vcnn_bf16_to_f32(size_t count, const void* src, float* dst, void* stream);
-
-/* Measurement aid, not a layer operation: launches `blocks` blocks of 4 waves that each issue `iters` x 4
- * independent matrix-core instructions (dtype VCNN_F32: v_mfma_f32_32x32x2_f32; VCNN_BF16:
- * v_mfma_f32_32x32x16_bf16) on register operands, with no memory traffic except one float per thread
- * written to `sink` (DEVICE, blocks*256 floats).  *flop (HOST, nullable) receives the flop count of the
- * launch; timing it gives the matrix-core rate the chip sustains, to report beside the data-sheet peak. */
-vcnn_status vcnn_probe_mfma(int32_t dtype, int32_t blocks, int32_t iters, float* sink, double* flop, void* stream);
 
 #ifdef __cplusplus
 }

@@ -307,21 +307,21 @@ def conv_bwd_filter_at(x, dy, rs, pad, idx):
 
 def conv_bwd_data_at(w, dy, pad, idx):
     """dx at positions idx = [(n,c,h,w), ...], stride 1: sum over kernels and taps of
-    w[k,c,r,s] * dy[n,k,h+ph-r,w+pw-s] for the taps whose output position exists."""
+    w[k,c,r,s] * dy[n,k,h+ph-r,w+pw-s] for the taps whose output position exists (the terms phi_c^{-1} adds up
+    for that pixel).  The existing taps of a pixel form one rectangle r0..r1 x s0..s1; the sum runs over it at once."""
     w, dy = _f64(w), _f64(dy)
-    kk, _, r, s = w.shape
+    _, _, r, s = w.shape
     oh, ow = dy.shape[2:]
     out = np.empty(len(idx))
     for t, (n, c, h, wi) in enumerate(idx):
-        acc = 0.0
-        for rr in range(r):
-            o_h = h + pad[0] - rr
-            if o_h < 0 or o_h >= oh:
-                continue
-            for ss in range(s):
-                o_w = wi + pad[1] - ss
-                if o_w < 0 or o_w >= ow:
-                    continue
-                acc += float(np.dot(w[:, c, rr, ss], dy[n, :, o_h, o_w]))
-        out[t] = acc
+        # tap rr exists iff 0 <= h + ph - rr < oh
+        r0, r1 = max(0, h + pad[0] - oh + 1), min(r - 1, h + pad[0])
+        s0, s1 = max(0, wi + pad[1] - ow + 1), min(s - 1, wi + pad[1])
+        if r0 > r1 or s0 > s1:
+            out[t] = 0.0
+            continue
+        taps = w[:, c, r0:r1 + 1, s0:s1 + 1]
+        # output rows h+ph-rr for rr = r0..r1, i.e. descending: reverse the window to line it up with the taps
+        win = dy[n, :, h + pad[0] - r1:h + pad[0] - r0 + 1, wi + pad[1] - s1:wi + pad[1] - s0 + 1][:, ::-1, ::-1]
+        out[t] = float(np.sum(taps * win))
     return out

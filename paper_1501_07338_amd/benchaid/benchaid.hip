@@ -1,0 +1,80 @@
+// Measurement aids for the benchmark; NOT part of the layer library and not linked into it.  Built as a
+// shared object of its own (libvcnn_benchaid.so) that only the benchmark loads.
+//   benchaid_mfma: the matrix-core rate this chip sustains with no memory traffic at all, to put beside the
+//     data-sheet peak when a kernel's matrix-core fraction is reported (the clock under sustained MFMA load
+//     is below the nominal 2.4 GHz).  Every wave issues independent MFMAs back to back on register operands.
+//   benchaid_copy: a plain streaming copy of a known size, the yardstick the HBM traffic counters of a
+//     profiler run are scaled by.
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+static constexpr int kThreads = 256;
+static constexpr int kChains = 4;  // independent accumulators per wave
+
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void benchaid_mfma_kernel(float* __restrict__ sink, int iters) {
+  f32x16 acc[kChains];
+#pragma unroll
+  for (int c = 0; c < kChains; ++c)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) acc[c][q] = 0.f;
+  // operands with varied mantissas (power depends on the data; all-zero operands would flatter the clock)
+  const float fa = 1.0f + 0.001f * (float)(threadIdx.x % 61), fb = 0.5f + 0.002f * (float)(threadIdx.x % 53);
+  if (BF16) {
+    bf16x8 a, b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) a[e] = (__bf16)(fa + 0.01f * e), b[e] = (__bf16)(fb - 0.01f * e);
+    for (int i = 0; i < iters; ++i)
+#pragma unroll
+      for (int c = 0; c < kChains; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[c], 0, 0, 0);
+  } else {
+    for (int i = 0; i < iters; ++i)
+#pragma unroll
+      for (int c = 0; c < kChains; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa, fb, acc[c], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < kChains; ++c)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) s += acc[c][q];
+  sink[(size_t)blockIdx.x * kThreads + threadIdx.x] = s;
+}
+
+// dst[i] = src[i], 16 bytes per thread, grid-stride
+__global__ __launch_bounds__(kThreads) void benchaid_copy_kernel(const float4* __restrict__ src, float4* __restrict__ dst,
+                                                                 size_t count4) {
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < count4; i += (size_t)gridDim.x * kThreads)
+    dst[i] = src[i];
+}
+
+extern "C" {
+
+// Launches `blocks` blocks of 4 waves that each issue iters x 4 independent matrix-core instructions (bf16 == 0:
+// v_mfma_f32_32x32x2_f32, else v_mfma_f32_32x32x16_bf16); one float per thread is written to sink (DEVICE,
+// blocks*256 floats).  *flop (HOST, nullable) receives the flop count of the launch.  Returns 0 or a hipError_t.
+int benchaid_mfma(int bf16, int blocks, int iters, float* sink, double* flop, void* stream) {
+  if (blocks <= 0 || iters <= 0 || !sink) return (int)hipErrorInvalidValue;
+  if (flop) *flop = (double)blocks * 4 * iters * kChains * (bf16 ? 32768.0 : 4096.0);
+  if (bf16)
+    hipLaunchKernelGGL(benchaid_mfma_kernel<true>, dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream, sink, iters);
+  else
+    hipLaunchKernelGGL(benchaid_mfma_kernel<false>, dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream, sink, iters);
+  return (int)hipGetLastError();
+}
+
+// Copies `bytes` (a multiple of 16; src and dst DEVICE, 16-byte aligned) with one streaming kernel.
+int benchaid_copy(const void* src, void* dst, size_t bytes, void* stream) {
+  if (!src || !dst || bytes == 0 || (bytes & 15)) return (int)hipErrorInvalidValue;
+  const size_t count4 = bytes / 16;
+  size_t blocks = (count4 + kThreads - 1) / kThreads;
+  if (blocks > 256 * 64) blocks = 256 * 64;
+  hipLaunchKernelGGL(benchaid_copy_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream,
+                     (const float4*)src, (float4*)dst, count4);
+  return (int)hipGetLastError();
+}
+
+}  // extern "C"

@@ -646,11 +646,12 @@ vcnn_status vcnn_sgd_update_multi(int32_t tensors, const size_t* counts, float* 
   if (!counts || !w || !dw) return fail(VCNN_ERR_NULL, "sgd_update_multi: NULL argument array");
   for (int t = 0; t < tensors; ++t)
     if (counts[t] > 0 && (!w[t] || !dw[t])) return fail(VCNN_ERR_NULL, "sgd_update_multi: NULL tensor %d", t);
-  for (int t0 = 0; t0 < tensors; t0 += kSgdBatch) {
+  // batches of up to kSgdBatch non-empty tensors; t carries on where the previous batch stopped
+  for (int t = 0; t < tensors;) {
     SgdBatch a{};
     a.lr = lr;
     uint64_t blocks = 0;
-    for (int t = t0; t < tensors && a.tensors < kSgdBatch; ++t) {
+    for (; t < tensors && a.tensors < kSgdBatch; ++t) {
       if (counts[t] == 0) continue;
       const int k = a.tensors++;
       a.w[k] = w[t], a.dw[k] = dw[t], a.w16[k] = w_bf16 ? w_bf16[t] : nullptr, a.count[k] = counts[t];
@@ -658,20 +659,11 @@ vcnn_status vcnn_sgd_update_multi(int32_t tensors, const size_t* counts, float* 
       blocks += (counts[t] + 255) / 256;
       if (blocks > 0x7fffffffULL) return fail(VCNN_ERR_SHAPE, "sgd_update_multi: too many elements for one launch");
     }
-    if (a.tensors == 0) continue;
+    if (a.tensors == 0) break;
     a.first[a.tensors] = (unsigned)blocks;
     if (vcnn_status s = launch_sgd_multi(a, (hipStream_t)stream)) return s;
   }
   return VCNN_OK;
-}
-
-vcnn_status vcnn_probe_mfma(int32_t dtype, int32_t blocks, int32_t iters, float* sink, double* flop, void* stream) {
-  if (vcnn_status s = check_dtype(dtype, "probe_mfma")) return s;
-  if (blocks <= 0 || iters <= 0) return fail(VCNN_ERR_SHAPE, "probe_mfma: non-positive size");
-  if (!sink) return fail(VCNN_ERR_NULL, "probe_mfma: NULL sink");
-  // waves x iterations x chains x flop per instruction (32x32x2 fp32: 4096; 32x32x16 bf16: 32768)
-  if (flop) *flop = (double)blocks * 4 * iters * 4 * (dtype == VCNN_BF16 ? 32768.0 : 4096.0);
-  return launch_mfma_probe(dtype, blocks, iters, sink, (hipStream_t)stream);
 }
 
 vcnn_status vcnn_f32_to_bf16(size_t count, const float* src, void* dst, void* stream) {

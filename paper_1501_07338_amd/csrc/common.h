@@ -192,9 +192,6 @@ vcnn_status launch_sum_slices(const float* partial, const float* bias, void* out
 vcnn_status launch_sum_slices_split(const float* partial, float* main, float* last, int64_t rows, int cols, int splits,
                                     hipStream_t st);
 
-// ---- probe.hip ----------------------------------------------------------------------------------
-vcnn_status launch_mfma_probe(int dtype, int blocks, int iters, float* sink, hipStream_t st);
-
 // ---- pointwise.hip ------------------------------------------------------------------------------
 // dtype selects the element type (VCNN_F32 / VCNN_BF16) of the activation tensors passed as void*.
 size_t bias_grad_partial_bytes(const ConvGeom& g);

@@ -630,6 +630,7 @@ __global__ __launch_bounds__(kThreads) void softmax_loss_f32_kernel(int batch, i
   __shared__ float sm[kThreads];
   float acc = 0.f;
   const float inv_b = 1.f / (float)batch;
+  const float kNaN = __builtin_nanf("");
   for (int b = threadIdx.x; b < batch; b += kThreads) {
     const float* zb = z + (int64_t)b * classes;
     if constexpr (SMALL) {
@@ -638,6 +639,7 @@ __global__ __launch_bounds__(kThreads) void softmax_loss_f32_kernel(int batch, i
 #pragma unroll
       for (int j = 0; j < C; ++j) zr[j] = zb[min(j, classes - 1)];
       const int lab = labels[b];
+      const bool lab_ok = lab >= 0 && lab < classes;
       float m = zr[0];
 #pragma unroll
       for (int j = 1; j < C; ++j) m = j < classes ? fmaxf(m, zr[j]) : m;
@@ -648,11 +650,12 @@ __global__ __launch_bounds__(kThreads) void softmax_loss_f32_kernel(int batch, i
       float zl = zr[0];
 #pragma unroll
       for (int j = 1; j < C; ++j) zl = j == lab ? zr[j] : zl;
-      acc += lse - zl;
+      acc += lab_ok ? lse - zl : kNaN;  // a label outside [0, classes) has no cost: the result says so
       if (dz) {
 #pragma unroll
         for (int j = 0; j < C; ++j)
-          if (j < classes) dz[(int64_t)b * classes + j] = (expf(zr[j] - lse) - (j == lab ? 1.f : 0.f)) * inv_b;
+          if (j < classes)
+            dz[(int64_t)b * classes + j] = lab_ok ? (expf(zr[j] - lse) - (j == lab ? 1.f : 0.f)) * inv_b : kNaN;
       }
     } else {
       float m = zb[0];
@@ -661,10 +664,11 @@ __global__ __launch_bounds__(kThreads) void softmax_loss_f32_kernel(int batch, i
       for (int j = 0; j < classes; ++j) se += expf(zb[j] - m);
       const float lse = m + logf(se);
       const int lab = labels[b];
-      acc += lse - zb[lab];
+      const bool lab_ok = lab >= 0 && lab < classes;  // never index the row with a label outside it
+      acc += lab_ok ? lse - zb[lab_ok ? lab : 0] : kNaN;
       if (dz)
         for (int j = 0; j < classes; ++j)
-          dz[(int64_t)b * classes + j] = (expf(zb[j] - lse) - (j == lab ? 1.f : 0.f)) * inv_b;
+          dz[(int64_t)b * classes + j] = lab_ok ? (expf(zb[j] - lse) - (j == lab ? 1.f : 0.f)) * inv_b : kNaN;
     }
   }
   const float total = block_sum<kThreads>(acc, sm);

@@ -86,6 +86,19 @@ class TrainStep:
                 if p is not None:
                     vcnn.f32_to_bf16(p[0].numel(), p[0], p16, stream)
 
+    def snapshot(self):
+        """Keeps a device copy of the current parameters for restore()."""
+        self._saved = [None if p is None else (p[0].clone(), p[1].clone()) for p in self.params]
+
+    def restore(self, stream=None):
+        """Puts the parameters of the last snapshot() back (device-to-device copies, no arithmetic) and refreshes the
+        bf16 working copies, so that the next step starts from the same state again."""
+        for p, q in zip(self.params, self._saved):
+            if p is not None:
+                p[0].copy_(q[0], non_blocking=True)
+                p[1].copy_(q[1], non_blocking=True)
+        self.refresh_weights(stream)
+
     def folds(self, li):
         """True if layer li's input gradient is stored with the ReLU derivative of layer li-1 folded in,
         i.e. it is written to dpre[li-1] (w.r.t. that layer's pre-activation) and dacts[li] stays unused."""

@@ -68,7 +68,6 @@ _SIGNATURES = {
     "vcnn_softmax_loss": (c_int32, [c_int32, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
     "vcnn_l2_loss": (c_int32, [c_int32, c_size_t, c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
     "vcnn_sgd_update": (c_int32, [c_size_t, c_float, c_void_p, c_void_p, c_void_p]),
-    "vcnn_probe_mfma": (c_int32, [c_int32, c_int32, c_int32, c_void_p, c_void_p, c_void_p]),
     "vcnn_sgd_update_multi": (c_int32, [c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_float, c_void_p]),
     "vcnn_f32_to_bf16": (c_int32, [c_size_t, c_void_p, c_void_p, c_void_p]),
     "vcnn_bf16_to_f32": (c_int32, [c_size_t, c_void_p, c_void_p, c_void_p]),
@@ -242,14 +241,6 @@ def l2_loss(dtype, count, batch, y, target, loss, dy, stream=None):
 
 def sgd_update(count, lr, w, dw, stream=None):
     _check(lib().vcnn_sgd_update(count, lr, _ptr(w), _ptr(dw), _stream(stream)))
-
-
-def probe_mfma(dtype, blocks, iters, sink, stream=None) -> float:
-    """Launches the register-only matrix-core loop; returns the flop count of the launch."""
-    from ctypes import c_double
-    flop = c_double()
-    _check(lib().vcnn_probe_mfma(dtype, blocks, iters, _ptr(sink), byref(flop), _stream(stream)))
-    return flop.value
 
 
 def sgd_update_multi(lr, ws, dws, w16s=None, stream=None):

@@ -1,6 +1,7 @@
 """The bfloat16 variant: x, w, y, dy, dx stored as bf16, accumulation / bias / dW / db / loss in fp32.
-The oracle stays fp64 on the bf16-rounded initial tensors and never rounds intermediates; tolerance is
-2e-2 max-norm relative for bf16 tensors and the fp32 bar for tensors the path keeps in fp32."""
+Per pass the oracle is fp64 arithmetic on the same bf16-rounded operands; tolerance is 2e-2 max-norm relative for
+bf16 tensors and the fp32 bar for tensors the path keeps in fp32.  In the whole-chain test the oracle additionally
+rounds each stored activation to bf16, so that both sides take the ReLU / pooling decisions in the storage type."""
 import numpy as np
 import pytest
 import torch
@@ -182,12 +183,12 @@ def test_fc_bf16():
     assert_close(f32_of(dx), rdx, TOL_BF16, "bf16 fc dx")
 
 
-def reference(name, batch):
+def reference(name, batch, chain=True):
     net = wl.make_net(name, batch)
     inputs, params = wl.make_inputs(net), wl.make_params(net)
     inputs = dict(inputs, x=wl.bf16_round(inputs["x"]))
     params = [None if p is None else (wl.bf16_round(p[0]), p[1]) for p in params]
-    return net, inputs, params, oracle_step(net, inputs, params)
+    return net, inputs, params, oracle_step(net, inputs, params) if chain else None
 
 
 @pytest.mark.parametrize("name,batch", [("cfg5", 1), ("cfg4", 2)])
@@ -225,32 +226,64 @@ def test_bf16_layerwise_parity(name, batch):
         assert_close(f32_of(dx), O.conv_bwd_data(w, dpre, (h, wdt), pad=pad), TOL_BF16, f"{name} bf16 layer {li} dx")
 
 
-@pytest.mark.parametrize("name,batch", [("cfg5", 1), ("cfg4", 2), ("cfg2", 16)])
+def stored_bf16(a):
+    """What a layer of the bf16 variant leaves in memory: the value rounded to bfloat16 (nearest even)."""
+    return wl.bf16_round(np.asarray(a, dtype=np.float32)).astype(np.float64)
+
+
+@pytest.mark.parametrize("name,batch", [("cfg5", 1), ("cfg4", 2), ("cfg2", 16), ("cfg3", 8)])
 def test_bf16_training_step(name, batch):
-    """Whole step in the bf16 variant against the fp64 oracle started from the same bf16-rounded input
-    and weights.  The oracle does not emulate the rounding of intermediate activations: forward tensors
-    and the loss meet the 2e-2 bar; a ReLU decision taken on a rounded value flips for a fraction f of
-    the elements, which alone puts a relative L2 error of about sqrt(f) on the gradients behind it, so
-    those are only checked coarsely here (the layer-wise test holds every pass to the bar)."""
-    net, inputs, params, ref = reference(name, batch)
+    """Whole step in the bf16 variant, every tensor of the chain element-wise against the fp64 oracle started from
+    the same bf16-rounded input and weights.  Both sides take the chain's discrete decisions (ReLU side, pooling
+    maximum) in the same precision, the storage type's: the oracle rounds every activation to bfloat16 as it is
+    stored and computes each layer in fp64 from the stored values.  Decisions that still differ must be ties within
+    one bf16 step of the oracle's own values (the two sides' fp32 / fp64 sums can round to neighbouring bf16
+    values); the oracle's backward pass then takes those validated choices, and activations, input gradients and
+    parameter gradients all meet the 2e-2 bar."""
+    net, inputs, params, _ = reference(name, batch, chain=False)
+    ref = oracle_step(net, inputs, params, store=stored_bf16)
     ts = TrainStep(net, params, inputs, device=DEV, first_layer_dx=True, dtype=vcnn.BF16)
     ts.step()
-    for li in range(len(net.layers)):
-        assert_close(f32_of(ts.acts[li + 1]), ref["acts"][li + 1], TOL_BF16, f"{name} bf16 act {li}")
+    flips = 0
+    step16 = 2.0 ** -7  # two neighbouring bfloat16 values differ by at most 2^-7 relative
+    for li, L in enumerate(net.layers):
+        got, want = f32_of(ts.acts[li + 1]).astype(np.float64), ref["acts"][li + 1]
+        assert_close(got, want, TOL_BF16, f"{name} bf16 act {li}")
+        if isinstance(L, wl.Pool):
+            gam, ram, x_ref = ts.argmax[li].cpu().numpy(), ref["argmax"][li], ref["acts"][li]
+            for n, c, oh, ow in np.argwhere(gam != ram):
+                plane = x_ref[n, c].reshape(-1)
+                a, b = plane[ram[n, c, oh, ow]], plane[gam[n, c, oh, ow]]
+                assert abs(a - b) <= 2 * step16 * max(abs(a), abs(b)), f"{name} bf16 argmax {(li, n, c, oh, ow)} is not a near-tie"
+                flips += 1
+        elif L.relu:
+            differ = (got > 0) != (want > 0)
+            assert np.all(np.maximum(np.abs(got), np.abs(want))[differ] <= 1e-3 * np.max(np.abs(want))), \
+                f"{name} bf16 layer {li}: a ReLU decision differs away from zero"
+            flips += int(np.count_nonzero(differ))
+    print(f"{name} bf16 batch {batch}: {flips} near-tie decisions differ")
+    relu_side = {li: ref["acts"][li + 1] > 0 for li, L in enumerate(net.layers) if getattr(L, "relu", False)}
+    if flips:
+        relu_side = {li: f32_of(ts.acts[li + 1]) > 0 for li in relu_side}
+        ref = oracle_step(net, inputs, params, store=stored_bf16, decisions={
+            "argmax": {li: am.cpu().numpy() for li, am in ts.argmax.items()}, "relu": relu_side})
     if net.loss != "upstream":
         assert abs(float(to_np(ts.loss)) - ref["loss"]) <= TOL_BF16 * abs(ref["loss"])
-
-    def l2_rel(got, want):
-        want = np.asarray(want, dtype=np.float64)
-        return float(np.linalg.norm(np.asarray(got, dtype=np.float64) - want) / max(np.linalg.norm(want), 1e-300))
-
     for li in range(len(net.layers) - 1, -1, -1):
+        if ts.folds(li):  # stored with the ReLU derivative of the layer below already applied
+            assert_close(f32_of(ts.dpre[li - 1]), O.relu_bwd(relu_side[li - 1].astype(np.float64), ref["dacts"][li]),
+                         TOL_BF16, f"{name} bf16 dpre {li - 1}")
+        else:
+            assert_close(f32_of(ts.dacts[li]), ref["dacts"][li], TOL_BF16, f"{name} bf16 dact {li}")
         if ts.grads[li] is not None:
-            e_w = l2_rel(to_np(ts.grads[li][0]), ref["grads"][li][0])
-            assert e_w <= 0.15, f"{name} bf16 dw {li}: relative L2 error {e_w:.3e}"
+            # products of bf16-stored tensors that carry their own rounding: the chain's bar, not the 1e-4 that holds
+            # for a single pass on identical operands (test_bf16_layerwise_parity)
+            assert_close(to_np(ts.grads[li][0]), ref["grads"][li][0], TOL_BF16, f"{name} bf16 dw {li}")
+            assert_close(to_np(ts.grads[li][1]), ref["grads"][li][1], TOL_BF16, f"{name} bf16 db {li}")
             # the update moved the master weights by -lr * dw
             moved = to_np(ts.params[li][0]).astype(np.float64) - params[li][0]
-            assert l2_rel(moved, -net.lr * to_np(ts.grads[li][0]).astype(np.float64)) <= 1e-2
+            want = -net.lr * to_np(ts.grads[li][0]).astype(np.float64)
+            assert np.max(np.abs(moved - want)) <= 1e-2 * np.max(np.abs(want)) + 2.0 ** -23 * np.max(np.abs(params[li][0]))
             # and the bf16 copy the next step reads is the rounding of the new master weights
             np.testing.assert_array_equal(f32_of(ts.params16[li]), wl.bf16_round(to_np(ts.params[li][0])))
 

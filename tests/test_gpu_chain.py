@@ -5,8 +5,10 @@ Two protocols:
     pooling sees bit-identical inputs and its argmax indices must match exactly;
   * end-to-end: the HIP chain runs on its own intermediates; tensors must match within tolerance and
     any argmax mismatch must be a near-tie in the oracle's own values.
-cfg1-cfg3 run at their stated sizes; cfg4 and cfg5 run the same layer stack on a smaller batch so
-the nested-loop oracle finishes in seconds (their full-size layers are covered by sampled checks).
+cfg1-cfg3 run at their stated sizes, the two recognition networks also at the mini-batch sizes of the paper's
+batch experiments (Tables 3 and 4: 1, 100, 300, 400; 200 lies between tested sizes on the same routes), where the
+library picks other kernels; cfg4 and cfg5 run the same layer stack on a smaller batch so the nested-loop oracle
+finishes in seconds (their layers at the stated batch are covered layer by layer in test_gpu_fullsize.py).
 """
 import functools
 
@@ -23,7 +25,8 @@ from util import TOL_F32, assert_close, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
-CASES = [("cfg1", None), ("cfg2", None), ("cfg3", None), ("cfg4", 4), ("cfg5", 1)]
+CASES = [("cfg1", None), ("cfg2", None), ("cfg3", None), ("cfg4", 4), ("cfg5", 1),
+         ("cfg2", 1), ("cfg2", 100), ("cfg2", 300), ("cfg2", 400), ("cfg3", 1), ("cfg3", 100), ("cfg3", 300), ("cfg3", 400)]
 
 
 @functools.lru_cache(maxsize=None)
@@ -138,24 +141,24 @@ def test_end_to_end_training_step(name, batch):
             differ = (got > 0) != (want > 0)
             assert np.all(np.maximum(np.abs(got), np.abs(want))[differ] <= 1e-5 * np.max(np.abs(want)))
             flips += int(np.count_nonzero(differ))
-    # A flipped near-tie (pool argmax or ReLU sign) legitimately moves one gradient element, which the
-    # max-norm measure sees at full size and which spreads over a receptive field further down.  The
-    # strict bar applies when all discrete decisions agree; otherwise all but a small fraction of the
-    # elements must still meet it (the layer-wise test covers every layer strictly).
-    print(f"{name}: {flips} near-tie decisions differ")
+    # A flipped near-tie (pool argmax or ReLU sign) legitimately moves one gradient element, which the max-norm
+    # measure sees at full size and which spreads over a receptive field further down.  Each differing decision has
+    # just been checked to be a tie within rounding of the oracle's own values, i.e. an equally valid choice; the
+    # oracle's backward pass is then evaluated with those choices, and the gradients are held to the strict bar.
+    print(f"{name} batch {net.batch}: {flips} near-tie decisions differ")
+    relu_side = {li: ref["acts"][li + 1] > 0 for li, L in enumerate(net.layers) if getattr(L, "relu", False)}
+    if flips:
+        relu_side = {li: to_np(ts.acts[li + 1]) > 0 for li in relu_side}
+        ref = oracle_step(net, inputs, params, decisions={
+            "argmax": {li: to_np(am) for li, am in ts.argmax.items()}, "relu": relu_side})
 
     def check(got, want, what):
-        if flips == 0:
-            assert_close(got, want, TOL_F32, what)
-        else:
-            # one rerouted element shifts every filter-gradient entry a little (each is a sum over all
-            # pixels) and a receptive field of the input gradients a lot: only a coarse check is meaningful
-            bad = np.abs(np.asarray(got, dtype=np.float64) - want) > 0.05 * np.max(np.abs(want))
-            assert bad.mean() <= 0.01, f"{what}: {bad.mean():.2%} of the elements are off after {flips} flips"
+        assert_close(got, want, TOL_F32, what)
 
     for li in range(len(net.layers)):
         if ts.folds(li):  # stored with the ReLU derivative of the layer below already applied
-            check(to_np(ts.dpre[li - 1]), O.relu_bwd(ref["acts"][li], ref["dacts"][li]), f"{name} dpre {li - 1}")
+            check(to_np(ts.dpre[li - 1]), O.relu_bwd(relu_side[li - 1].astype(np.float64), ref["dacts"][li]),
+                  f"{name} dpre {li - 1}")
         else:
             check(to_np(ts.dacts[li]), ref["dacts"][li], f"{name} dact {li}")
         if ts.grads[li] is not None:
@@ -163,11 +166,11 @@ def test_end_to_end_training_step(name, batch):
             check(to_np(ts.grads[li][1]), ref["grads"][li][1], f"{name} db {li}")
             check(to_np(ts.params[li][0]), ref["new_params"][li][0], f"{name} w' {li}")
             check(to_np(ts.params[li][1]), ref["new_params"][li][1], f"{name} b' {li}")
-            if flips == 0:  # the update changed the weights by -lr*dw (to fp32 rounding of w)
-                step_gpu = to_np(ts.params[li][0]).astype(np.float64) - before[li][0]
-                step_ref = -net.lr * ref["grads"][li][0]
-                slack = 1e-3 * np.max(np.abs(step_ref)) + 2.0 ** -23 * np.max(np.abs(before[li][0]))
-                assert np.max(np.abs(step_gpu - step_ref)) <= slack, f"{name} sgd step {li}"
+            # the update changed the weights by -lr*dw (to fp32 rounding of w)
+            step_gpu = to_np(ts.params[li][0]).astype(np.float64) - before[li][0]
+            step_ref = -net.lr * ref["grads"][li][0]
+            slack = 1e-3 * np.max(np.abs(step_ref)) + 2.0 ** -23 * np.max(np.abs(before[li][0]))
+            assert np.max(np.abs(step_gpu - step_ref)) <= slack, f"{name} sgd step {li}"
     if net.loss != "upstream":
         assert abs(float(to_np(ts.loss)) - ref["loss"]) <= TOL_F32 * abs(ref["loss"])
     # run-to-run bit identity of a full step from the same state
@@ -225,3 +228,64 @@ def test_one_stream_step_matches_two_stream_step(name, batch):
             np.testing.assert_array_equal(to_np(one.grads[li][0]), to_np(two.grads[li][0]), err_msg=f"dw {li}")
             np.testing.assert_array_equal(to_np(one.params[li][0]), to_np(two.params[li][0]), err_msg=f"w {li}")
     assert float(to_np(one.loss)) == float(to_np(two.loss))
+
+
+@pytest.mark.parametrize("name,batch", [("cfg2", 1), ("cfg2", 100), ("cfg2", 200), ("cfg2", 400), ("cfg2", 600),
+                                        ("cfg3", 1), ("cfg3", 200), ("cfg3", 400)])
+def test_forward_only_pass(name, batch):
+    """The test-time path the mini-batch sweep times (the paper's Table 4): TrainStep.forward alone, on a state
+    whose gradient buffers were never written, against the oracle's forward tensors and pooling choices."""
+    net = wl.make_net(name, batch)
+    inputs, params = wl.make_inputs(net), wl.make_params(net)
+    ts = TrainStep(net, params, inputs, device=DEV)
+    for t in ts.acts[1:]:
+        t.fill_(float("nan"))
+    ts.forward()
+    a = np.asarray(inputs["x"], dtype=np.float64)
+    for li, L in enumerate(net.layers):
+        if isinstance(L, wl.Conv):
+            a = O.conv_fwd(a, params[li][0], params[li][1], pad=(L.pad_h, L.pad_w), relu=L.relu)
+        elif isinstance(L, wl.Pool):
+            ref_in = a
+            a, am = O.maxpool_fwd(a, (L.win, L.win), (L.stride, L.stride))
+            argmax_mismatches_are_near_ties(to_np(ts.argmax[li]), am, ref_in)
+        else:
+            a = O.fc_fwd(a.reshape(a.shape[0], -1), params[li][0], params[li][1], relu=L.relu)
+        assert_close(to_np(ts.acts[li + 1]), a, TOL_F32, f"{name} batch {batch} forward-only act {li}")
+
+
+@pytest.mark.parametrize("name,bf16", [("cfg4", False), ("cfg5", False), ("cfg5", True)])
+def test_launch_schedules_agree_bit_for_bit_at_full_size(name, bf16):
+    """The three ways the benchmark issues a step (two streams, one stream, HIP-graph replay) at the workloads'
+    stated batch: one step each from the same seeded parameters must leave identical bits, the replay repeatedly
+    (parameters restored in between, with other work and synchronisations between the replays)."""
+    net = wl.make_net(name)
+    inputs, params = wl.make_inputs(net), wl.make_params(net)
+    dt = vcnn.BF16 if bf16 else vcnn.F32
+    two = TrainStep(net, params, inputs, device=DEV, dtype=dt)
+    one = TrainStep(net, params, inputs, device=DEV, dtype=dt, overlap=False)
+    rep = TrainStep(net, params, inputs, device=DEV, dtype=dt)
+    two.step()
+    one.step()
+    rep.snapshot()
+    graph = rep.capture()  # one eager step, then the recording
+    torch.cuda.synchronize()
+    assert np.isfinite(float(to_np(two.loss)))
+
+    def same(a, b, what):
+        for li in range(len(net.layers)):
+            if a.grads[li] is not None:
+                assert torch.equal(a.grads[li][0], b.grads[li][0]), f"{what}: dw {li}"
+                assert torch.equal(a.grads[li][1], b.grads[li][1]), f"{what}: db {li}"
+                assert torch.equal(a.params[li][0], b.params[li][0]), f"{what}: w {li}"
+            assert torch.equal(a.acts[li + 1], b.acts[li + 1]), f"{what}: act {li}"
+        assert float(to_np(a.loss)) == float(to_np(b.loss)), what
+
+    same(one, two, "one stream vs two streams")
+    same(rep, two, "eager step of the recorded state vs two streams")
+    for replay in range(3):
+        rep.restore()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.isfinite(torch.randn(1 << 16, device=DEV).sum().item())  # unrelated eager work between replays
+        same(rep, two, f"replay {replay} vs two streams")

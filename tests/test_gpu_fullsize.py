@@ -1,7 +1,14 @@
 """Full-size parity of the big layers (workloads cfg4 and cfg5 at their stated batch), in the launch
-configuration the benchmark times.  The nested-loop oracle would need minutes for these, so each pass
-is checked at sampled output positions that the oracle's single-output probes evaluate straight from
-the definition, plus size-independent properties (bias-gradient sum, determinism)."""
+configuration the benchmark times.
+
+Every layer the nested-loop oracle finishes in seconds (all of cfg4; cfg5's c1, c2, c4, c5) is compared as a
+WHOLE tensor, every pass.  cfg5's c3 (383 GFLOP per pass: minutes of fp64 loops) is checked
+  * at a stratified set of positions that the oracle's single-output probes evaluate straight from the
+    definition: one position in every cell of a grid finer than any block tile of the kernels (every sample,
+    every group of 16 output maps / 8 input channels, every run of 32 pixels or 32 kernel-matrix columns), plus
+    the first and last row and column of every sample; and
+  * as a whole tensor against the library's other, independent realisation (patch matrix + plain product).
+The bf16 variant of cfg5 runs the same protocol at its own tolerance."""
 import numpy as np
 import pytest
 import torch
@@ -9,11 +16,11 @@ import torch
 import oracle as O
 from paper_1501_07338_amd import vcnn
 from paper_1501_07338_amd import workloads as wl
-from util import TOL_F32, to_dev, to_np
+from util import TOL_BF16, TOL_F32, assert_close, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
-SAMPLES = 40
+PROBED = {("cfg5", 2)}  # layers too large for the whole-tensor oracle
 
 
 def conv_layers(name):
@@ -24,63 +31,156 @@ def conv_layers(name):
 CASES = [(name, li) for name in ("cfg4", "cfg5") for li, _, _ in conv_layers(name)]
 
 
-def sample_idx(rng, shape, extra=()):
-    idx = [tuple(int(rng.integers(0, d)) for d in shape) for _ in range(SAMPLES)]
-    corners = [tuple(0 for _ in shape), tuple(d - 1 for d in shape)]
-    return idx + corners + list(extra)
+def stratified(rng, shape, cells):
+    """One random index in every cell of the grid that cuts axis a of `shape` into runs of cells[a] (the last axes
+    may be given flattened).  Returns an int array [count, len(shape)]."""
+    axes = []
+    for d, c in zip(shape, cells):
+        starts = np.arange(0, d, c)
+        axes.append((starts, np.minimum(starts + c, d)))
+    grids = np.meshgrid(*[np.arange(len(s)) for s, _ in axes], indexing="ij")
+    out = []
+    for a, g in enumerate(grids):
+        lo, hi = axes[a][0][g.reshape(-1)], axes[a][1][g.reshape(-1)]
+        out.append(lo + (rng.random(lo.shape) * (hi - lo)).astype(np.int64))
+    return np.stack(out, axis=1)
 
 
-def check_samples(got, want, what):
+def pixel_probes(rng, n, ch, ch_cell, h, w, px_cell):
+    """Positions (n, channel, y, x) of an [n][ch][h][w] tensor: every sample x every run of ch_cell channels x every
+    run of px_cell consecutive pixels of the flattened plane, then rows 0 / h-1 and columns 0 / w-1 of every sample."""
+    s = stratified(rng, (n, ch, h * w), (1, ch_cell, px_cell))
+    idx = [(int(a), int(b), int(p) // w, int(p) % w) for a, b, p in s]
+    for a in range(n):
+        for y, x in ((0, int(rng.integers(w))), (h - 1, int(rng.integers(w))), (int(rng.integers(h)), 0),
+                     (int(rng.integers(h)), w - 1), (0, 0), (0, w - 1), (h - 1, 0), (h - 1, w - 1)):
+            idx.append((a, int(rng.integers(ch)), y, x))
+    return idx
+
+
+def filter_probes(rng, k, c, r, s, col_cell=32):
+    """Positions (k, c, r, s) of the kernel gradient: every run of 16 maps x every run of col_cell columns of the
+    kernel matrix (c, r, s flattened), plus its four corners."""
+    st = stratified(rng, (k, c * r * s), (16, col_cell))
+    idx = [(int(a),) + tuple(int(v) for v in np.unravel_index(int(q), (c, r, s))) for a, q in st]
+    return idx + [(0, 0, 0, 0), (k - 1, c - 1, r - 1, s - 1), (0, c - 1, r - 1, s - 1), (k - 1, 0, 0, 0)]
+
+
+def check_points(got, want, tol, what):
     want = np.asarray(want, dtype=np.float64)
-    err = np.max(np.abs(np.asarray(got, dtype=np.float64) - want)) / max(np.max(np.abs(want)), 1e-30)
-    assert err <= TOL_F32, f"{what}: sampled max-norm relative error {err:.3e}"
+    got = np.asarray(got, dtype=np.float64)
+    assert np.all(np.isfinite(got)), f"{what}: non-finite values"
+    err = np.max(np.abs(got - want)) / max(np.max(np.abs(want)), 1e-30)
+    assert err <= tol, f"{what}: max-norm relative error {err:.3e} over {want.size} probes (worst at probe {int(np.argmax(np.abs(got - want)))})"
 
 
-@pytest.mark.parametrize("name,li", CASES)
-def test_conv_layer_full_size_sampled(name, li):
+def take(a, idx):
+    ii = np.asarray(idx, dtype=np.int64)
+    return a[tuple(ii[:, d] for d in range(ii.shape[1]))]
+
+
+def layer_tensors(name, li, seed0, bf16):
     net = wl.make_net(name)
     L = net.layers[li]
     n, c, h, w = net.in_shape(li)
     _, k, oh, ow = net.shapes[li]
-    pad = (L.pad_h, L.pad_w)
-    seed = 5000 + 100 * net.index + li
+    seed = seed0 + 100 * net.index + li
     x = np.abs(wl.random_tensor(seed, (n, c, h, w))) if li > 0 else wl.random_tensor(seed, (n, c, h, w))
     wt = wl.random_tensor(seed + 1, (k, c, L.kh, L.kw), scale=(2.0 / (c * L.kh * L.kw)) ** 0.5)
     b = wl.random_tensor(seed + 2, (k,), scale=0.1)
     dy = wl.random_tensor(seed + 3, (n, k, oh, ow))
-    rng = np.random.default_rng(seed)
+    if bf16:
+        x, wt, dy = wl.bf16_round(x), wl.bf16_round(wt), wl.bf16_round(dy)
+    return net, L, (n, c, h, w), (k, oh, ow), x, wt, b, dy, np.random.default_rng(seed)
 
-    d = vcnn.conv_desc(n, c, h, w, k, L.kh, L.kw, L.pad_h, L.pad_w, act=vcnn.ACT_RELU if L.relu else vcnn.ACT_NONE)
+
+def run_layer(name, li, bf16):
+    net, L, (n, c, h, w), (k, oh, ow), x, wt, b, dy, rng = layer_tensors(name, li, 6000 if bf16 else 5000, bf16)
+    pad = (L.pad_h, L.pad_w)
+    tol = TOL_BF16 if bf16 else TOL_F32
+    tag = f"{name}{' bf16' if bf16 else ''} conv{li}"
+    act_t = torch.bfloat16 if bf16 else torch.float32
+    dev = (lambda a: torch.from_numpy(a).to(DEV).to(torch.bfloat16)) if bf16 else to_dev
+    host = lambda t: (torch.cuda.synchronize(), t.float().cpu().numpy())[1]
+    d = vcnn.conv_desc(n, c, h, w, k, L.kh, L.kw, L.pad_h, L.pad_w, dtype=vcnn.BF16 if bf16 else vcnn.F32,
+                       act=vcnn.ACT_RELU if L.relu else vcnn.ACT_NONE)
     ws = torch.empty(max(256, *(vcnn.conv_workspace_bytes(d, p) for p in range(3))), dtype=torch.uint8, device=DEV)
-    xd, wd, bd, dyd = to_dev(x), to_dev(wt), to_dev(b), to_dev(dy)
+    xd, wd, bd, dyd = dev(x), dev(wt), to_dev(b), dev(dy)
+    whole = (name, li) not in PROBED
 
-    y = torch.full((n, k, oh, ow), float("nan"), device=DEV)
+    y = torch.full((n, k, oh, ow), float("nan"), dtype=act_t, device=DEV)
     vcnn.conv_fwd(d, xd, wd, bd, y, ws)
-    yh = to_np(y)
-    assert np.all(np.isfinite(yh))
-    idx = sample_idx(rng, yh.shape)
-    check_samples([yh[i] for i in idx], O.conv_fwd_at(x, wt, b, pad, idx, relu=L.relu), f"{name} conv{li} fwd")
-
+    yh = host(y)
     dw = torch.full(wt.shape, float("nan"), device=DEV)
     db = torch.full((k,), float("nan"), device=DEV)
     vcnn.conv_bwd_filter(d, xd, dyd, dw, db, ws)
-    dwh = to_np(dw)
-    assert np.all(np.isfinite(dwh))
-    idx = sample_idx(rng, dwh.shape)
-    check_samples([dwh[i] for i in idx], O.conv_bwd_filter_at(x, dy, (L.kh, L.kw), pad, idx), f"{name} conv{li} dw")
-    check_samples(to_np(db), dy.astype(np.float64).sum(axis=(0, 2, 3)), f"{name} conv{li} db")
-    # run-to-run bit identity at full size
-    dw2 = torch.empty_like(dw)
+    dwh, dbh = to_np(dw), to_np(db)
+    dw2 = torch.empty_like(dw)  # run-to-run bit identity at full size
     vcnn.conv_bwd_filter(d, xd, dyd, dw2, None, ws)
-    assert torch.equal(dw, dw2)
-
-    dx = torch.full((n, c, h, w), float("nan"), device=DEV)
+    assert torch.equal(dw, dw2), f"{tag}: the kernel gradient is not bit-identical from run to run"
+    dx = torch.full((n, c, h, w), float("nan"), dtype=act_t, device=DEV)
     vcnn.conv_bwd_data(d, wd, dyd, dx, ws)
-    dxh = to_np(dx)
-    assert np.all(np.isfinite(dxh))
-    border = [(0, 0, 0, w - 1), (n - 1, c - 1, h - 1, 0), (n // 2, c // 2, h // 2, w // 2)]
-    idx = sample_idx(rng, dxh.shape, border)
-    check_samples([dxh[i] for i in idx], O.conv_bwd_data_at(wt, dy, pad, idx), f"{name} conv{li} dx")
+    dxh = host(dx)
+    del ws, y, dx
+    torch.cuda.empty_cache()
+
+    if whole:
+        assert_close(yh, O.conv_fwd(x, wt, b, pad=pad, relu=L.relu), tol, f"{tag} fwd (whole tensor)")
+        rdw, rdb = O.conv_bwd_filter(x, dy, (L.kh, L.kw), pad=pad)
+        assert_close(dwh, rdw, TOL_F32, f"{tag} dw (whole tensor)")
+        assert_close(dbh, rdb, TOL_F32, f"{tag} db")
+        assert_close(dxh, O.conv_bwd_data(wt, dy, (h, w), pad=pad), tol, f"{tag} dx (whole tensor)")
+        return
+    idx = pixel_probes(rng, n, k, 16, oh, ow, 32)
+    check_points(take(yh, idx), O.conv_fwd_at(x, wt, b, pad, idx, relu=L.relu), tol, f"{tag} fwd")
+    idx = filter_probes(rng, k, c, L.kh, L.kw)
+    check_points(take(dwh, idx), O.conv_bwd_filter_at(x, dy, (L.kh, L.kw), pad, idx), TOL_F32, f"{tag} dw")
+    check_points(dbh, dy.astype(np.float64).sum(axis=(0, 2, 3)), TOL_F32, f"{tag} db")
+    idx = pixel_probes(rng, n, c, 8, h, w, 32)
+    check_points(take(dxh, idx), O.conv_bwd_data_at(wt, dy, pad, idx), tol, f"{tag} dx")
+
+
+@pytest.mark.parametrize("name,li", CASES)
+def test_conv_layer_full_size(name, li):
+    run_layer(name, li, bf16=False)
+
+
+@pytest.mark.parametrize("li", [li for li, _, _ in conv_layers("cfg5")])
+def test_cfg5_layer_full_size_bf16(li):
+    """The bf16 variant at cfg5's full batch (the configuration the benchmark times): bf16 matrix-core
+    kernels for the forward pass and both gradients, against the oracle evaluated on the same bf16-rounded tensors."""
+    run_layer("cfg5", li, bf16=True)
+
+
+@pytest.mark.parametrize("name,li", [("cfg5", 2), ("cfg5", 1), ("cfg4", 1)])
+def test_two_realisations_agree_on_the_whole_tensor(name, li):
+    """The default route of each pass against the explicit route (patch matrix written out by phi_c, plain product,
+    phi_c^{-1}): two independent sets of kernels, every element of every result at the fp32 bar.  For cfg5 c3, which
+    the oracle only probes, this covers the elements between the probes."""
+    net, L, (n, c, h, w), (k, oh, ow), x, wt, b, dy, _ = layer_tensors(name, li, 5000, False)
+    d = vcnn.conv_desc(n, c, h, w, k, L.kh, L.kw, L.pad_h, L.pad_w, act=vcnn.ACT_RELU if L.relu else vcnn.ACT_NONE)
+    xd, wd, bd, dyd = to_dev(x), to_dev(wt), to_dev(b), to_dev(dy)
+    res = {}
+    try:
+        for algo in (vcnn.ALGO_AUTO, vcnn.ALGO_EXPLICIT):
+            vcnn.set_conv_algo(algo)
+            ws = torch.empty(max(256, *(vcnn.conv_workspace_bytes(d, p) for p in range(3))), dtype=torch.uint8, device=DEV)
+            y = torch.full((n, k, oh, ow), float("nan"), device=DEV)
+            dw = torch.full(wt.shape, float("nan"), device=DEV)
+            db = torch.full((k,), float("nan"), device=DEV)
+            dx = torch.full((n, c, h, w), float("nan"), device=DEV)
+            vcnn.conv_fwd(d, xd, wd, bd, y, ws)
+            vcnn.conv_bwd_filter(d, xd, dyd, dw, db, ws)
+            vcnn.conv_bwd_data(d, wd, dyd, dx, ws)
+            torch.cuda.synchronize()
+            res[algo] = (y, dw, db, dx)
+            del ws
+    finally:
+        vcnn.set_conv_algo(vcnn.ALGO_AUTO)
+    for what, a, e in zip(("y", "dw", "db", "dx"), res[vcnn.ALGO_AUTO], res[vcnn.ALGO_EXPLICIT]):
+        assert bool(torch.isfinite(a).all()) and bool(torch.isfinite(e).all())
+        err = float((a.double() - e.double()).abs().max() / e.double().abs().max())
+        assert err <= TOL_F32, f"{name} conv{li} {what}: the two realisations differ by {err:.3e} (max-norm relative)"
 
 
 def test_unroll_full_size_properties():
@@ -93,8 +193,8 @@ def test_unroll_full_size_properties():
     col = torch.empty((c * r * s, n * h * w), device=DEV)
     vcnn.im2col(d, xd, col)
     rng = np.random.default_rng(7)
-    rows = rng.integers(0, c * r * s, size=200)
-    cols = rng.integers(0, n * h * w, size=200)
+    rows = rng.integers(0, c * r * s, size=2000)
+    cols = rng.integers(0, n * h * w, size=2000)
     got = col[torch.from_numpy(rows).to(DEV), torch.from_numpy(cols).to(DEV)].cpu().numpy()
     for g, rr, cc in zip(got, rows, cols):
         ci, q = divmod(int(rr), r * s)
@@ -110,57 +210,3 @@ def test_unroll_full_size_properties():
     lhs = float(torch.sum(col.double() * col.double()))
     rhs = float(torch.sum(xd.double() * back.double()))
     assert abs(lhs - rhs) <= 1e-6 * abs(lhs)
-
-
-@pytest.mark.parametrize("li", [li for li, _, _ in conv_layers("cfg5")])
-def test_cfg5_layer_full_size_bf16_sampled(li):
-    """The bf16 variant at cfg5's full batch (the configuration the benchmark times): bf16 matrix-core
-    kernels for the forward pass and both gradients, sampled against the oracle's probes evaluated on
-    the same bf16-rounded tensors."""
-    from util import TOL_BF16
-    net = wl.make_net("cfg5")
-    L = net.layers[li]
-    n, c, h, w = net.in_shape(li)
-    _, k, oh, ow = net.shapes[li]
-    pad = (L.pad_h, L.pad_w)
-    seed = 6000 + li
-    x = wl.bf16_round(np.abs(wl.random_tensor(seed, (n, c, h, w))) if li > 0 else wl.random_tensor(seed, (n, c, h, w)))
-    wt = wl.bf16_round(wl.random_tensor(seed + 1, (k, c, L.kh, L.kw), scale=(2.0 / (c * L.kh * L.kw)) ** 0.5))
-    b = wl.random_tensor(seed + 2, (k,), scale=0.1)
-    dy = wl.bf16_round(wl.random_tensor(seed + 3, (n, k, oh, ow)))
-    rng = np.random.default_rng(seed)
-    dev16 = lambda a: torch.from_numpy(a).to(DEV).to(torch.bfloat16)
-    host = lambda t: (torch.cuda.synchronize(), t.float().cpu().numpy())[1]
-
-    d = vcnn.conv_desc(n, c, h, w, k, L.kh, L.kw, L.pad_h, L.pad_w, dtype=vcnn.BF16,
-                       act=vcnn.ACT_RELU if L.relu else vcnn.ACT_NONE)
-    ws = torch.empty(max(256, *(vcnn.conv_workspace_bytes(d, p) for p in range(3))), dtype=torch.uint8, device=DEV)
-    xd, wd, bd, dyd = dev16(x), dev16(wt), to_dev(b), dev16(dy)
-
-    def check(got, want, tol, what):
-        want = np.asarray(want, dtype=np.float64)
-        err = np.max(np.abs(np.asarray(got, dtype=np.float64) - want)) / max(np.max(np.abs(want)), 1e-30)
-        assert err <= tol, f"{what}: sampled max-norm relative error {err:.3e}"
-
-    y = torch.full((n, k, oh, ow), float("nan"), dtype=torch.bfloat16, device=DEV)
-    vcnn.conv_fwd(d, xd, wd, bd, y, ws)
-    yh = host(y)
-    assert np.all(np.isfinite(yh))
-    idx = sample_idx(rng, yh.shape)
-    check([yh[i] for i in idx], O.conv_fwd_at(x, wt, b, pad, idx, relu=L.relu), TOL_BF16, f"cfg5 bf16 conv{li} fwd")
-
-    dw = torch.full(wt.shape, float("nan"), device=DEV)
-    db = torch.full((k,), float("nan"), device=DEV)
-    vcnn.conv_bwd_filter(d, xd, dyd, dw, db, ws)
-    dwh = to_np(dw)
-    assert np.all(np.isfinite(dwh))
-    idx = sample_idx(rng, dwh.shape)
-    check([dwh[i] for i in idx], O.conv_bwd_filter_at(x, dy, (L.kh, L.kw), pad, idx), TOL_F32, f"cfg5 bf16 conv{li} dw")
-    check(to_np(db), dy.astype(np.float64).sum(axis=(0, 2, 3)), TOL_F32, f"cfg5 bf16 conv{li} db")
-
-    dx = torch.full((n, c, h, w), float("nan"), dtype=torch.bfloat16, device=DEV)
-    vcnn.conv_bwd_data(d, wd, dyd, dx, ws)
-    dxh = host(dx)
-    assert np.all(np.isfinite(dxh))
-    idx = sample_idx(rng, dxh.shape, [(0, 0, 0, w - 1), (n - 1, c - 1, h - 1, 0)])
-    check([dxh[i] for i in idx], O.conv_bwd_data_at(wt, dy, pad, idx), TOL_BF16, f"cfg5 bf16 conv{li} dx")

@@ -198,6 +198,66 @@ def test_pool_fwd_bwd(shape, ties):
     assert_close(to_np(dx), O.maxpool_bwd(dy, ram, (h, w)), 1e-6, "pool dx")
 
 
+# (n, c, h, w, (win_h, win_w), (stride_h, stride_w)): windows and strides that differ between the two axes
+RECT_POOL_SHAPES = [(2, 3, 9, 11, (2, 3), (1, 2)), (3, 4, 16, 12, (3, 2), (2, 1)), (2, 5, 32, 32, (3, 2), (2, 2)),
+                    (1, 2, 7, 20, (1, 4), (1, 3)), (2, 2, 13, 6, (5, 1), (2, 1)), (130, 6, 12, 10, (2, 3), (2, 3)),
+                    (1, 1, 4, 9, (4, 2), (3, 5))]
+
+
+@pytest.mark.parametrize("ties", [False, True])
+@pytest.mark.parametrize("shape", RECT_POOL_SHAPES)
+def test_pool_rectangular_windows_and_strides(shape, ties):
+    """win_h != win_w and stride_h != stride_w through every pooling call: max forward (values, argmax), its
+    routing gradient alone and with an activation derivative folded in, the mean and its transpose, and the
+    pooling layer of Eq. 3 with bias and sigma."""
+    n, c, h, w, win, st = shape
+    x = random_tensor(830, (n, c, h, w))
+    if ties:
+        x = np.maximum(np.round(x * 2) / 2, 0).astype(np.float32)
+    d = vcnn.pool_desc(n, c, h, w, win[0], win[1], st[0], st[1])
+    oh, ow = vcnn.pool_out_shape(d)
+    assert (oh, ow) == ((h - win[0]) // st[0] + 1, (w - win[1]) // st[1] + 1)
+    y = torch.full((n, c, oh, ow), float("nan"), device=DEV)
+    am = torch.full((n, c, oh, ow), -7, dtype=torch.int32, device=DEV)
+    vcnn.pool_fwd(d, to_dev(x), y, am)
+    ry, ram = O.maxpool_fwd(x, win, st)
+    np.testing.assert_array_equal(to_np(am), ram)
+    np.testing.assert_array_equal(to_np(y), ry.astype(np.float32))
+    dy = random_tensor(831, (n, c, oh, ow))
+    dx = torch.full((n, c, h, w), float("nan"), device=DEV)
+    vcnn.pool_bwd(d, to_dev(dy), am, dx)
+    rdx = O.maxpool_bwd(dy, ram, (h, w))
+    assert_close(to_np(dx), rdx, 1e-6, "pool dx")
+    xr = np.maximum(x, 0).astype(np.float32)  # as the output of a ReLU below
+    vcnn.pool_fwd(d, to_dev(xr), y, am)
+    ram_r = O.maxpool_fwd(xr, win, st)[1]
+    np.testing.assert_array_equal(to_np(am), ram_r)
+    vcnn.pool_bwd_act(d, vcnn.ACT_RELU, to_dev(xr), to_dev(dy), am, dx)
+    assert_close(to_np(dx), O.relu_bwd(xr, O.maxpool_bwd(dy, ram_r, (h, w))), 1e-6, "pool dx * relu'")
+    # the mean and its transpose
+    da = vcnn.pool_desc(n, c, h, w, win[0], win[1], st[0], st[1], mode=vcnn.POOL_AVG)
+    vcnn.pool_fwd(da, to_dev(x), y, None)
+    assert_close(to_np(y), O.avgpool_fwd(x, win, st), 1e-6, "avgpool y")
+    vcnn.pool_bwd(da, to_dev(dy), None, dx)
+    assert_close(to_np(dx), O.avgpool_bwd(dy, (h, w), win, st), 1e-6, "avgpool dx")
+    # Eq. 3: sigma(pool + b), and its gradients
+    bias = random_tensor(832, (c,))
+    for mode, desc in (("max", d), ("avg", da)):
+        amx = am if mode == "max" else None
+        vcnn.pool_layer_fwd(desc, vcnn.ACT_TANH, to_dev(x), to_dev(bias), y, amx)
+        ly, lam = O.pool_layer_fwd(x, bias, win, st, mode, "tanh")
+        assert_close(to_np(y), ly, 1e-6, f"{mode} pool layer y")
+        if mode == "max":
+            np.testing.assert_array_equal(to_np(am), lam)
+        y32 = to_np(y)
+        db = torch.full((c,), float("nan"), device=DEV)
+        ws = torch.empty(max(vcnn.pool_layer_workspace_bytes(desc), 16), dtype=torch.uint8, device=DEV)
+        vcnn.pool_layer_bwd(desc, vcnn.ACT_TANH, y, to_dev(dy), amx, db, dx, ws)
+        ldx, ldb, _ = O.pool_layer_bwd(y32, dy, lam, (h, w), win, st, mode, "tanh")
+        assert_close(to_np(dx), ldx, 1e-6, f"{mode} pool layer dx")
+        assert_close(to_np(db), ldb, TOL_F32, f"{mode} pool layer dbias")
+
+
 def _sigma_bwd(act, y, g):
     return {vcnn.ACT_RELU: O.relu_bwd, vcnn.ACT_TANH: O.tanh_bwd, vcnn.ACT_SIGMOID: O.sigmoid_bwd}[act](y, g)
 
@@ -403,6 +463,27 @@ def test_softmax_loss(b, c):
         assert np.max(np.abs(to_np(dz))) < 1e-7
 
 
+@pytest.mark.parametrize("c", [10, 16, 40])
+@pytest.mark.parametrize("bad", [-1, -2147483648, 2147483647, None])
+def test_softmax_loss_label_out_of_range_is_flagged_not_dereferenced(c, bad):
+    """A label outside [0, classes) must not be used as an index: the call completes, the loss is NaN and so is
+    that sample's gradient row; every other row is the ordinary result."""
+    b = 37
+    bad = c if bad is None else bad
+    z = random_tensor(1110, (b, c), scale=2.0)
+    labels = (np.arange(b) * 3 % c).astype(np.int32)
+    good = labels.copy()
+    labels[[4, 20]] = bad
+    loss = torch.zeros((), device=DEV)
+    dz = torch.zeros((b, c), device=DEV)
+    vcnn.softmax_loss(b, c, to_dev(z), to_dev(labels), loss, dz)
+    got = to_np(dz)
+    assert np.isnan(float(to_np(loss)))
+    assert np.all(np.isnan(got[[4, 20]]))
+    rows = np.setdiff1d(np.arange(b), [4, 20])
+    assert_close(got[rows], O.softmax_loss(z, good)[1][rows], TOL_F32, "dlogits of the rows with valid labels")
+
+
 def test_softmax_loss_uniform_logits_is_log_classes():
     z = np.full((64, 10), 1.5, dtype=np.float32)
     loss = torch.empty((), device=DEV)
@@ -451,20 +532,46 @@ def test_sgd_update_multi_matches_oracle_per_tensor():
         assert_close(to_np(many[k]), O.sgd_update(before[k], to_np(grads[k]), 0.5), 1e-6, f"sgd many {k}")
 
 
-@pytest.mark.parametrize("dtype,per_instr", [(vcnn.F32, 4096.0), (vcnn.BF16, 32768.0)])
-def test_probe_mfma_counts_its_flops_and_runs(dtype, per_instr):
+@pytest.mark.parametrize("empty", [(0,), (0, 5, 17), (15, 16, 31, 32), tuple(range(0, 40, 2)), tuple(range(39))])
+def test_sgd_update_multi_with_empty_tensors_among_many(empty):
+    """More tensors than one launch holds, some of them empty: every non-empty tensor is updated exactly once
+    (an empty tensor takes no slot of a launch, so the launches' tensor ranges must follow the slots, not the
+    positions)."""
+    sizes = [0 if k in empty else 33 + 7 * k for k in range(40)]
+    many = [to_dev(random_tensor(1500 + k, (sizes[k],))) for k in range(40)]
+    grads = [to_dev(random_tensor(1600 + k, (sizes[k],))) for k in range(40)]
+    before = [to_np(t).copy() for t in many]
+    vcnn.sgd_update_multi(0.5, many, grads)
+    for k in range(40):
+        if sizes[k]:
+            assert_close(to_np(many[k]), O.sgd_update(before[k], to_np(grads[k]), 0.5), 1e-6, f"sgd tensor {k} of 40")
+
+
+@pytest.mark.parametrize("bf16,per_instr", [(False, 4096.0), (True, 32768.0)])
+def test_benchaid_mfma_counts_its_flops_and_runs(bf16, per_instr):
+    """The benchmark's register-only matrix-core loop (a measurement aid outside the layer library)."""
+    from paper_1501_07338_amd import benchaid
     blocks, iters = 8, 10
     sink = torch.full((blocks * 256,), float("nan"), device=DEV)
-    flop = vcnn.probe_mfma(dtype, blocks, iters, sink)
+    flop = benchaid.mfma(bf16, blocks, iters, sink)
     assert flop == blocks * 4 * iters * 4 * per_instr
     assert np.all(np.isfinite(to_np(sink)))
-    if dtype == vcnn.F32:
+    if not bf16:
         # thread 0 holds column 0, rows 8*(q/4) + q%4 of the 32x32 product; lane l supplies A[l%32][l/32] and B[l/32][l%32]
         fa = lambda t: np.float32(1.0) + np.float32(0.001) * np.float32(t % 61)
         fb = lambda t: np.float32(0.5) + np.float32(0.002) * np.float32(t % 53)
         rows = [8 * (q // 4) + q % 4 for q in range(16)]
         want = 4 * iters * sum(float(fa(r)) * float(fb(0)) + float(fa(r + 32)) * float(fb(32)) for r in rows)
         assert abs(float(to_np(sink)[0]) - want) <= 1e-4 * want
+
+
+def test_benchaid_copy_copies():
+    from paper_1501_07338_amd import benchaid
+    src = torch.arange(1 << 20, dtype=torch.float32, device=DEV)
+    dst = torch.zeros_like(src)
+    assert benchaid.copy(src, dst) == 4 << 20
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
 
 
 def test_gpu_launch_of_bad_arguments_is_rejected_cleanly():

@@ -267,6 +267,19 @@ def test_probes_match_full():
     np.testing.assert_allclose(O.conv_bwd_data_at(w, dy, pad, ix), [dx[i] for i in ix], atol=1e-12)
 
 
+@pytest.mark.parametrize("hw,rs,pad", [((7, 8), (3, 2), (1, 1)), ((6, 6), (4, 4), (0, 0)), ((5, 9), (5, 3), (2, 1)),
+                                       ((9, 4), (1, 4), (0, 3)), ((8, 8), (8, 8), (0, 0)), ((4, 5), (3, 3), (2, 2))])
+def test_input_gradient_probe_matches_full_at_every_pixel(hw, rs, pad):
+    """The single-pixel input-gradient probe sums a rectangle of existing taps at once; every pixel of small
+    layers - interior, borders, corners, 'valid' and padded, taps wider than the output - against the C loops."""
+    w = rnd(3, 2, *rs)
+    oh, ow = O.conv_out_hw(hw[0], hw[1], rs[0], rs[1], pad[0], pad[1])
+    dy = rnd(2, 3, oh, ow)
+    dx = O.conv_bwd_data(w, dy, hw, pad=pad)
+    ix = list(np.ndindex(*dx.shape))
+    np.testing.assert_allclose(O.conv_bwd_data_at(w, dy, pad, ix), dx.reshape(-1), atol=1e-12)
+
+
 # ---------------------------------------------------------------------------------------------
 # pooling
 # ---------------------------------------------------------------------------------------------
@@ -562,3 +575,41 @@ def test_pool_layer_without_bias_and_sigma_is_plain_pooling():
     y2 = O.pool_layer_fwd(x, np.array([0.0, 1.5]), (2, 2), (2, 2))[0]
     np.testing.assert_allclose(y2[:, 1], ry[:, 1] + 1.5)
     np.testing.assert_array_equal(y2[:, 0], ry[:, 0])
+
+
+# ---- the chain's handling of discrete decisions ------------------------------------------------------------
+def test_chain_store_hook_and_decision_overrides():
+    """`store` = identity and `decisions` = the chain's own decisions change nothing; a stored activation is what
+    the next layer reads; an overridden pooling choice or ReLU side moves the gradient by exactly the routed
+    amount (checked on a two-layer chain by hand)."""
+    from oracle.net import train_step
+    from paper_1501_07338_amd import workloads as wl
+    net = wl.make_net("cfg2", 3)
+    inputs, params = wl.make_inputs(net), wl.make_params(net)
+    ref = train_step(net, inputs, params)
+    same = train_step(net, inputs, params, store=lambda a: a)
+    relu_own = {li: ref["acts"][li + 1] > 0 for li, L in enumerate(net.layers) if getattr(L, "relu", False)}
+    own = train_step(net, inputs, params, decisions={"argmax": ref["argmax"], "relu": relu_own})
+    for a, b, c in zip(ref["dacts"], same["dacts"], own["dacts"]):
+        np.testing.assert_array_equal(a, b)
+        np.testing.assert_array_equal(a, c)
+    # a coarser storage type: every stored activation is on its grid, and layer li+1 is computed from it
+    grid = lambda a: np.round(np.asarray(a) * 64.0) / 64.0
+    q = train_step(net, inputs, params, store=grid)
+    for a in q["acts"][1:]:
+        np.testing.assert_array_equal(a, grid(a))
+    L0 = net.layers[0]
+    np.testing.assert_array_equal(q["acts"][1], grid(O.conv_fwd(q["acts"][0], params[0][0], params[0][1], relu=L0.relu)))
+    np.testing.assert_array_equal(q["acts"][2], grid(O.maxpool_fwd(q["acts"][1], (2, 2), (2, 2))[0]))
+    # by hand: conv (1x1 kernel, weight 1) -> ReLU -> 2x2 pool, upstream gradient g
+    tiny = wl.Net("tiny", 9, 1, (1, 2, 2), [wl.Conv(1, 1, 1, relu=True), wl.Pool(2, 2)], "upstream")
+    x = np.array([[[[1.0, 3.0], [2.0, -1.0]]]])
+    g = np.array([[[[5.0]]]])
+    p = [(np.ones((1, 1, 1, 1)), np.zeros(1)), None]
+    r0 = train_step(tiny, {"x": x, "upstream": g}, p)
+    np.testing.assert_array_equal(r0["dacts"][0], [[[[0.0, 5.0], [0.0, 0.0]]]])       # the maximum is the 3
+    r1 = train_step(tiny, {"x": x, "upstream": g}, p, decisions={"argmax": {1: np.array([[[[2]]]], dtype=np.int32)}})
+    np.testing.assert_array_equal(r1["dacts"][0], [[[[0.0, 0.0], [5.0, 0.0]]]])       # routed to flat index 2 instead
+    r2 = train_step(tiny, {"x": x, "upstream": g}, p, decisions={"relu": {0: np.zeros((1, 1, 2, 2), dtype=bool)}})
+    np.testing.assert_array_equal(r2["dacts"][0], np.zeros((1, 1, 2, 2)))             # every ReLU input taken as <= 0
+    np.testing.assert_array_equal(r2["acts"][1], r0["acts"][1])                       # forward tensors untouched
