@@ -101,6 +101,18 @@ vcnn_status vcnn_conv_fwd(const vcnn_conv_desc* d, const void* x, const void* w,
  * applies vcnn_act_bwd to dy first. */
 vcnn_status vcnn_conv_bwd_filter(const vcnn_conv_desc* d, const void* x, const void* dy, float* dw, float* dbias,
                                  void* workspace, size_t workspace_bytes, void* stream);
+/* vcnn_conv_bwd_filter for callers that cannot allocate device memory or size a workspace: code under HIP graph
+ * capture, tight serving or fine-tuning loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * kernels, bit for bit; the partial sums live in a fixed array inside the library's code object
+ * (vcnn_conv_bwd_filter_noalloc_limit() bytes, 32 MiB, held by every GPU the library runs on until the process
+ * ends) instead of a caller workspace.  The call allocates and frees nothing.  A layer whose pass needs more
+ * (vcnn_conv_workspace_bytes(d, VCNN_PASS_BWD_FILTER) > limit) is rejected with VCNN_ERR_WORKSPACE before anything
+ * is enqueued.  All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ * streams or host threads) race; calls ordered on one stream do not.  The first call on each device looks the
+ * array's address up and should be made outside a stream capture. */
+size_t vcnn_conv_bwd_filter_noalloc_limit(void);
+vcnn_status vcnn_conv_bwd_filter_noalloc(const vcnn_conv_desc* d, const void* x, const void* dy, float* dw,
+                                         float* dbias, void* stream);
 /* Input gradient: dx = phi_c^{-1}(W^T * dy_matrix).  Same convention for dy as above. */
 vcnn_status vcnn_conv_bwd_data(const vcnn_conv_desc* d, const void* w, const void* dy, void* dx, void* workspace,
                                size_t workspace_bytes, void* stream);

@@ -406,6 +406,50 @@ vcnn_status vcnn_conv_bwd_data(const vcnn_conv_desc* d, const void* w, const voi
   return launch_col2im(g, dt, (const float*)workspace, dx, st);
 }
 
+// ---- the kernel-gradient pass for callers that cannot allocate ----------------------------------------
+// The partial sums of the split contraction (and of the bias gradient) live in a fixed array of the code object
+// instead of a caller workspace.  Every GPU the library runs on holds its own copy of the array, at its own address,
+// until the process ends; host code never uses the array's name as an address, only what hipGetSymbolAddress
+// returned for the device that is current.
+static constexpr size_t kScratchBytes = (size_t)32 << 20;
+static constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+static vcnn_status scratch_of_current_device(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(VCNN_ERR_HIP, "conv_bwd_filter_noalloc: hipGetDevice: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(VCNN_ERR_UNSUPPORTED, "conv_bwd_filter_noalloc: device index %d", dev);
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {  // once per device (a second thread racing here looks the same address up again)
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p)
+      return fail(VCNN_ERR_HIP, "conv_bwd_filter_noalloc: hipGetSymbolAddress: %s", hipGetErrorString(e));
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return VCNN_OK;
+}
+
+size_t vcnn_conv_bwd_filter_noalloc_limit(void) { return kScratchBytes; }
+
+vcnn_status vcnn_conv_bwd_filter_noalloc(const vcnn_conv_desc* d, const void* x, const void* dy, float* dw,
+                                         float* dbias, void* stream) {
+  ConvGeom g;
+  if (vcnn_status s = make_geom(d, &g)) return s;
+  if (!x || !dy || !dw) return fail(VCNN_ERR_NULL, "conv_bwd_filter_noalloc: NULL tensor");
+  const size_t need = workspace_need(g, VCNN_PASS_BWD_FILTER, d->dtype);
+  if (need > kScratchBytes)
+    return fail(VCNN_ERR_WORKSPACE,
+                "conv_bwd_filter_noalloc: this layer needs %zu bytes of scratch memory, the built-in array holds %zu; "
+                "use vcnn_conv_bwd_filter with a workspace", need, kScratchBytes);
+  void* ws = nullptr;
+  if (vcnn_status s = scratch_of_current_device(&ws)) return s;
+  // nothing in the pass reads scratch memory it has not written in the same call, so nothing needs clearing
+  return vcnn_conv_bwd_filter(d, x, dy, dw, dbias, ws, kScratchBytes, stream);
+}
+
 static vcnn_status check_pool(const vcnn_pool_desc* d, int* oh, int* ow) {
   if (!d) return fail(VCNN_ERR_NULL, "pool descriptor is NULL");
   if (d->n <= 0 || d->c <= 0 || d->h <= 0 || d->w <= 0 || d->win_h <= 0 || d->win_w <= 0 || d->stride_h <= 0 ||

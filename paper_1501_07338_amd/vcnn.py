@@ -48,6 +48,8 @@ _SIGNATURES = {
     "vcnn_conv_fwd": (c_int32, [POINTER(ConvDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     "vcnn_conv_bwd_filter": (c_int32, [POINTER(ConvDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t,
                                        c_void_p]),
+    "vcnn_conv_bwd_filter_noalloc_limit": (c_size_t, []),
+    "vcnn_conv_bwd_filter_noalloc": (c_int32, [POINTER(ConvDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
     "vcnn_conv_bwd_data": (c_int32, [POINTER(ConvDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     "vcnn_pool_out_shape": (c_int32, [POINTER(PoolDesc), POINTER(c_int32), POINTER(c_int32)]),
     "vcnn_pool_fwd": (c_int32, [POINTER(PoolDesc), c_void_p, c_void_p, c_void_p, c_void_p]),
@@ -167,6 +169,14 @@ def conv_fwd(d, x, w, bias, y, workspace=None, stream=None):
 def conv_bwd_filter(d, x, dy, dw, dbias, workspace=None, stream=None):
     p, nbytes = _ws(workspace)
     _check(lib().vcnn_conv_bwd_filter(byref(d), _ptr(x), _ptr(dy), _ptr(dw), _ptr(dbias), p, nbytes, _stream(stream)))
+
+
+def conv_bwd_filter_noalloc_limit() -> int:
+    return lib().vcnn_conv_bwd_filter_noalloc_limit()
+
+
+def conv_bwd_filter_noalloc(d, x, dy, dw, dbias, stream=None):
+    _check(lib().vcnn_conv_bwd_filter_noalloc(byref(d), _ptr(x), _ptr(dy), _ptr(dw), _ptr(dbias), _stream(stream)))
 
 
 def conv_bwd_data(d, w, dy, dx, workspace=None, stream=None):
