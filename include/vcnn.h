@@ -53,8 +53,10 @@ enum { VCNN_PASS_FWD = 0, VCNN_PASS_BWD_FILTER = 1, VCNN_PASS_BWD_DATA = 2 };
 
 /* How the convolution calls realise the unroll.  EXPLICIT materialises the patch matrix in the
  * workspace (phi_c as a kernel of its own, then a matrix product); IMPLICIT forms the patch-matrix
- * tiles on the fly inside the product.  AUTO picks per shape. */
-enum { VCNN_ALGO_AUTO = 0, VCNN_ALGO_EXPLICIT = 1, VCNN_ALGO_IMPLICIT = 2 };
+ * tiles on the fly inside the product.  AUTO picks per shape.  FOLD is AUTO except that the input gradient
+ * takes, wherever the layer allows it, the transposed product with phi_c^{-1} applied to every tile of the
+ * patch-matrix gradient on chip (AUTO uses that route only where it is the fastest). */
+enum { VCNN_ALGO_AUTO = 0, VCNN_ALGO_EXPLICIT = 1, VCNN_ALGO_IMPLICIT = 2, VCNN_ALGO_FOLD = 3 };
 
 typedef struct {
   int32_t n, c, h, w;                         /* input: batch, channels, height, width */

@@ -90,7 +90,7 @@ static bool halo_bwd_data_pays(const ConvGeom& g, const HaloPlan& hp) {
 
 // Which realisation a pass uses for a given shape.  The same decision drives the workspace query and
 // the launch, so the two always agree.
-enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER, PATH_HALO, PATH_HALO_FILTER, PATH_HALO_BF16, PATH_FILTER_BF16, PATH_HALO_FILTER_BF16, PATH_FEW_COLS_FILTER, PATH_SMALL, PATH_SMALL_BWD };
+enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER, PATH_HALO, PATH_HALO_FILTER, PATH_HALO_BF16, PATH_FILTER_BF16, PATH_HALO_FILTER_BF16, PATH_FEW_COLS_FILTER, PATH_SMALL, PATH_SMALL_BWD, PATH_FOLD };
 struct Plan {
   Path path;
   DirectGeom dg;
@@ -100,6 +100,7 @@ struct Plan {
   BwdFilterBf16Plan fb;
   FilterGradBf16Plan hfb;
   FewColsPlan fcp;
+  FoldPlan fold;
   int split;        // channel slices (few-out), output-map group size (few-in) or batch slices (filter gradient)
   size_t partial_bytes;
   size_t workspace_bytes;
@@ -111,8 +112,9 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
   p.path = PATH_EXPLICIT;
   const int algo = g_conv_algo.load();
   const bool allow_direct = algo != VCNN_ALGO_EXPLICIT;
+  const bool automatic = algo == VCNN_ALGO_AUTO || algo == VCNN_ALGO_FOLD;  // FOLD only re-routes the input gradient
   // bf16 variant, default route: the bf16 matrix-core kernels wherever the layer has enough maps / channels
-  const bool bf16_mfma = dtype == VCNN_BF16 && algo == VCNN_ALGO_AUTO;
+  const bool bf16_mfma = dtype == VCNN_BF16 && automatic;
   // (1x1 layers included: with asynchronous staging they are a plain bf16 product through the same kernel)
   if (bf16_mfma && pass == VCNN_PASS_FWD && (g.k > 4 || g.c >= 64) &&
       conv_halo_bf16_plan(g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, &p.hb)) {
@@ -120,7 +122,8 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
     p.workspace_bytes = p.hb.x8_bytes + p.hb.wf_bytes;
     return p;
   }
-  if (bf16_mfma && pass == VCNN_PASS_BWD_DATA && g.c > 4 && g.r - 1 - g.ph >= 0 && g.s - 1 - g.pw >= 0 &&
+  if (bf16_mfma && pass == VCNN_PASS_BWD_DATA && !(algo == VCNN_ALGO_FOLD && bwd_data_fold_plan(g, &p.fold)) && g.c > 4 &&
+      g.r - 1 - g.ph >= 0 && g.s - 1 - g.pw >= 0 &&
       conv_halo_bf16_plan(g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, &p.hb)) {
     p.path = PATH_HALO_BF16;
     p.workspace_bytes = p.hb.x8_bytes + p.hb.wf_bytes;
@@ -146,7 +149,7 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
       p.workspace_bytes = align256(p.partial_bytes);
     } else if (is_pointwise(g)) {
       p.path = PATH_POINTWISE;
-    } else if (algo == VCNN_ALGO_AUTO && g.k > 4 && conv_small_applies(g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw)) {
+    } else if (automatic && g.k > 4 && conv_small_applies(g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw)) {
       p.path = PATH_SMALL;  // a few hundred MFLOP: latency-bound, one tile per block and the contraction over its waves
     } else if (allow_direct && (g.c > 4 || g.k >= 32 || algo == VCNN_ALGO_IMPLICIT) &&
                conv_halo_plan(g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, &p.hp)) {
@@ -158,8 +161,11 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
     }
   } else if (pass == VCNN_PASS_BWD_DATA) {
     // the input gradient is a correlation of dy (k channels) with the flipped kernels into c maps
-    if (allow_direct && g.c <= 4 && direct_bwd_data_geom(g, &p.dg) &&
-        direct_few_out_plan(&p.dg, &p.split, &p.partial_bytes)) {
+    if (algo == VCNN_ALGO_FOLD && !is_pointwise(g) && bwd_data_fold_plan(g, &p.fold)) {
+      p.path = PATH_FOLD;
+      p.workspace_bytes = align256(p.fold.partial_bytes);
+    } else if (allow_direct && g.c <= 4 && direct_bwd_data_geom(g, &p.dg) &&
+               direct_few_out_plan(&p.dg, &p.split, &p.partial_bytes)) {
       p.path = PATH_FEW_OUT;
       p.workspace_bytes = align256(p.partial_bytes);
     } else if (is_pointwise(g)) {
@@ -172,9 +178,9 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
       p.workspace_bytes = align256((size_t)g.M * g.K * sizeof(float));
     } else if (allow_direct && g.k <= 4 && direct_bwd_data_geom(g, &p.dg) && direct_few_in_plan(&p.dg, &p.split)) {
       p.path = PATH_FEW_IN;
-    } else if (algo == VCNN_ALGO_AUTO && conv_small_bwd_applies(dtype, g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw)) {
+    } else if (automatic && conv_small_bwd_applies(dtype, g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw)) {
       p.path = PATH_SMALL_BWD;  // transposed product and phi_c^{-1} fused on chip, no workspace
-    } else if (algo == VCNN_ALGO_AUTO && g.c > 4 && g.r - 1 - g.ph >= 0 && g.s - 1 - g.pw >= 0 &&
+    } else if (automatic && g.c > 4 && g.r - 1 - g.ph >= 0 && g.s - 1 - g.pw >= 0 &&
                conv_small_applies(g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw)) {
       p.path = PATH_SMALL;  // the same latency-bound kernel on dy with the flipped matrix (kept in the workspace)
       p.workspace_bytes = align256((size_t)g.M * g.K * sizeof(float));
@@ -184,6 +190,10 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
       // correlation of dy (k channels) with the flipped kernels; the flipped matrix lives in the workspace
       p.path = PATH_HALO;
       p.workspace_bytes = align256((size_t)g.M * g.K * sizeof(float));
+    } else if (automatic && bwd_data_fold_plan(g, &p.fold)) {
+      // the paper's route (transposed product, then phi_c^{-1}) with the fold done per tile on chip
+      p.path = PATH_FOLD;
+      p.workspace_bytes = align256(p.fold.partial_bytes);
     } else {
       p.workspace_bytes = col_bytes(g);
     }
@@ -191,7 +201,7 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
     if (allow_direct && g.k <= 4 && direct_filter_grad_plan(g, &p.dg, &p.split, &p.partial_bytes)) {
       p.path = PATH_DIRECT_FILTER;
       p.workspace_bytes = align256(p.partial_bytes);
-    } else if (algo == VCNN_ALGO_AUTO && g.k > 4 && filter_grad_few_cols_plan(g, &p.fcp)) {
+    } else if (automatic && g.k > 4 && filter_grad_few_cols_plan(g, &p.fcp)) {
       // narrow kernel matrix (the networks' first layers): every block computes the whole result for its pixels
       p.path = PATH_FEW_COLS_FILTER;
       p.workspace_bytes = align256(p.fcp.partial_bytes);
@@ -236,7 +246,7 @@ const char* vcnn_last_error(void) { return g_err; }
 int32_t vcnn_version(void) { return 100; }
 
 vcnn_status vcnn_set_conv_algo(int32_t algo) {
-  if (algo != VCNN_ALGO_AUTO && algo != VCNN_ALGO_EXPLICIT && algo != VCNN_ALGO_IMPLICIT)
+  if (algo != VCNN_ALGO_AUTO && algo != VCNN_ALGO_EXPLICIT && algo != VCNN_ALGO_IMPLICIT && algo != VCNN_ALGO_FOLD)
     return fail(VCNN_ERR_UNSUPPORTED, "unknown conv algorithm %d", algo);
   g_conv_algo.store(algo);
   return VCNN_OK;
@@ -386,6 +396,7 @@ vcnn_status vcnn_conv_bwd_data(const vcnn_conv_desc* d, const void* w, const voi
     return launch_conv_halo(plan.hp, dt, g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, dy,
                             workspace, nullptr, dx, 0, st);
   }
+  if (plan.path == PATH_FOLD) return launch_bwd_data_fold(plan.fold, dt, g, w, dy, dx, (float*)workspace, st);
   // dcol[k][j] = sum_m W[m][k] * dY(m, j)
   GemmArgs a{};
   a.A = w, a.B = dy, a.bias = nullptr;

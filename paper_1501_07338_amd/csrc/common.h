@@ -185,6 +185,17 @@ bool bwd_filter_bf16_plan(const ConvGeom& g, BwdFilterBf16Plan* p);
 vcnn_status launch_bwd_filter_bf16(const BwdFilterBf16Plan& p, const ConvGeom& g, const void* x, const void* dy, float* dw,
                                    void* workspace, hipStream_t st);
 
+// ---- conv_fold.hip ------------------------------------------------------------------------------------
+// Input gradient as the transposed product with phi_c^{-1} applied to each tile on chip (layers with many output
+// maps and large kernels, whose patch-matrix gradient would be gigabytes).  workspace: partial_bytes.
+struct FoldPlan {
+  int tiles_i, tiles_j, rsz, wreg;
+  size_t lds_bytes, partial_bytes;
+};
+bool bwd_data_fold_plan(const ConvGeom& g, FoldPlan* p);
+vcnn_status launch_bwd_data_fold(const FoldPlan& p, int dtype, const ConvGeom& g, const void* w, const void* dy, void* dx,
+                                 float* partial, hipStream_t st);
+
 // out[i] = act(bias[(i / plane) % maps] + sum_s partial[s][i]), slices added in ascending order (bias nullable)
 vcnn_status launch_sum_slices(const float* partial, const float* bias, void* out, int out_dtype, int64_t count,
                               int splits, int64_t plane, int maps, int relu, hipStream_t st);

@@ -173,6 +173,55 @@ def test_bwd_filter_split_contraction_many_columns():
     assert_close(to_np(db), rdb, TOL_F32, "db")
 
 
+# layers the fused route of the input gradient (transposed product + phi_c^{-1} per tile on chip) accepts: at least
+# 64 output maps, and the input pixels one 128 x 128 tile of the patch-matrix gradient touches fit a small LDS region
+FOLD_SHAPES = [
+    (2, 2, 70, 70, 130, 16, 16, 0, 0),   # one channel per row tile (256 taps), 24 column tiles, contraction tail (130 maps)
+    (3, 5, 14, 18, 64, 16, 16, 8, 8),    # padded: region rows and columns outside the image are dropped
+    (2, 3, 20, 20, 70, 8, 8, 0, 0),      # 64 taps per channel: a row tile spans two channels, the last one is short
+    (1, 7, 9, 9, 64, 3, 3, 1, 1),        # K = 63: one ragged row tile over all channels, scalar kernel-matrix loads
+    (2, 1, 40, 33, 96, 11, 12, 3, 0),    # one channel, 132 taps: the second row tile holds 4 rows
+    (4, 38, 20, 20, 72, 16, 16, 0, 0),   # the shape family of the deconvolution network's third layer (5 x 5 outputs)
+]
+
+
+@pytest.mark.parametrize("dtype", [vcnn.F32, vcnn.BF16])
+@pytest.mark.parametrize("shape", FOLD_SHAPES)
+def test_conv_bwd_data_fused_fold_route(shape, dtype):
+    n, c, h, w, k, r, s, ph, pw = shape
+    x, wt, b, dy = conv_case(shape, 1900)
+    tol = TOL_F32
+    cast = lambda t: t
+    if dtype == vcnn.BF16:
+        from paper_1501_07338_amd.workloads import bf16_round
+        from util import TOL_BF16
+        wt, dy, tol = bf16_round(wt), bf16_round(dy), TOL_BF16
+        cast = lambda t: t.to(torch.bfloat16)
+    d = vcnn.conv_desc(n, c, h, w, k, r, s, ph, pw, dtype=dtype)
+    want = O.conv_bwd_data(wt, dy, (h, w), pad=(ph, pw))
+    wd, dyd = cast(to_dev(wt)), cast(to_dev(dy))
+    try:
+        other = []
+        for a in (vcnn.ALGO_EXPLICIT, vcnn.ALGO_IMPLICIT):
+            vcnn.set_conv_algo(a)
+            other.append(vcnn.conv_workspace_bytes(d, vcnn.PASS_BWD_DATA))
+        vcnn.set_conv_algo(vcnn.ALGO_FOLD)
+        need = vcnn.conv_workspace_bytes(d, vcnn.PASS_BWD_DATA)
+        # its workspace holds the folded regions only: not the patch-matrix gradient, not a flipped kernel matrix
+        assert 0 < need < other[0] and need != other[1], "the fused route was not taken"
+        ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+        ws.fill_(0xFF)  # NaN patterns: nothing may be read before it is written
+        dx = cast(torch.full((n, c, h, w), float("nan"), device=DEV))
+        vcnn.conv_bwd_data(d, wd, dyd, dx, ws)
+        assert_close(to_np(dx.float()), want, tol, "fused fold dx")
+        dx2 = cast(torch.full((n, c, h, w), float("nan"), device=DEV))
+        vcnn.conv_bwd_data(d, wd, dyd, dx2, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(dx, dx2), "not bit-identical from run to run"
+    finally:
+        vcnn.set_conv_algo(vcnn.ALGO_AUTO)
+
+
 POOL_SHAPES = [(2, 3, 4, 4, 2, 2), (3, 5, 24, 24, 2, 2), (2, 7, 32, 32, 3, 2), (3, 4, 15, 15, 3, 2), (2, 2, 7, 7, 3, 2),
                (1, 3, 9, 11, 2, 1), (2, 2, 5, 6, 5, 1), (1, 1, 3, 3, 3, 3)]
 
