@@ -289,6 +289,35 @@ def hbm_kernels(stream):
     return out
 
 
+def fourier_comparison(stream):
+    """Forward pass of the deconvolution network's two layers with one-dimensional kernels (121 x 1 and 1 x 121) on
+    the unroll + matrix-core route and through the Fourier domain - the alternative the paper's related-work
+    paragraph names.  A comparison only: the default route never takes the transform."""
+    import torch
+    from paper_1501_07338_amd import vcnn
+    rows = []
+    for name, (n, c, h, w, k, r, s) in {"cfg5.c1 (121x1, 1->38 maps)": (16, 1, 184, 184, 38, 121, 1),
+                                        "cfg5.c2 (1x121, 38->38 maps)": (16, 38, 64, 184, 38, 1, 121)}.items():
+        x = torch.rand(n, c, h, w, device="cuda")
+        wt = torch.randn(k, c, r, s, device="cuda") * (2.0 / (c * r * s)) ** 0.5
+        b = torch.zeros(k, device="cuda")
+        d = vcnn.conv_desc(n, c, h, w, k, r, s)
+        oh, ow = vcnn.conv_out_shape(d)
+        y = torch.empty(n, k, oh, ow, device="cuda")
+        row = {"layer": name, "gflop": 2.0 * k * c * r * s * n * oh * ow / 1e9}
+        try:
+            for key, algo in (("unroll_ms", vcnn.ALGO_AUTO), ("fourier_ms", vcnn.ALGO_FFT)):
+                vcnn.set_conv_algo(algo)
+                ws = torch.empty(max(256, vcnn.conv_workspace_bytes(d, vcnn.PASS_FWD)), dtype=torch.uint8, device="cuda")
+                row[key] = sorted(time_calls(lambda: vcnn.conv_fwd(d, x, wt, b, y, ws), 10, stream) for _ in range(3))[1]
+                del ws
+        finally:
+            vcnn.set_conv_algo(vcnn.ALGO_AUTO)
+        rows.append(row)
+    torch.cuda.empty_cache()
+    return rows
+
+
 def aids(stream):
     """The benchmark's own yardsticks (outside the layer library): the matrix-core rate with register operands
     only - what the chip sustains under MFMA load, beside the data-sheet peaks the roofline fractions are quoted
@@ -428,6 +457,7 @@ def main():
     if not args.no_hbm:
         detail["hbm_kernels"] = hbm_kernels(stream)
         detail["yardsticks"] = aids(stream)
+        detail["fourier_comparison"] = fourier_comparison(stream)
     if not args.no_sweep:
         detail["batch_sweep"] = batch_sweep(stream)
 
@@ -455,6 +485,7 @@ def main():
         out["yardsticks"] = {"mfma_f32_sustained_tflops": detail["yardsticks"]["mfma_f32"]["sustained_tflops"],
                              "mfma_bf16_sustained_tflops": detail["yardsticks"]["mfma_bf16"]["sustained_tflops"],
                              "copy_1GiB_gbs": detail["yardsticks"]["copy_1GiB"]["gbs"]}
+        out["fourier_comparison"] = [[r["layer"], r["unroll_ms"], r["fourier_ms"]] for r in detail["fourier_comparison"]]
     if "batch_sweep" in detail:  # [workload, batch, training images/s, forward-only images/s]
         out["batch_sweep"] = [[r["workload"], r["batch"], r["train_images_per_s"], r["forward_images_per_s"]]
                               for r in detail["batch_sweep"]]

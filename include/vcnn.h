@@ -55,8 +55,11 @@ enum { VCNN_PASS_FWD = 0, VCNN_PASS_BWD_FILTER = 1, VCNN_PASS_BWD_DATA = 2 };
  * workspace (phi_c as a kernel of its own, then a matrix product); IMPLICIT forms the patch-matrix
  * tiles on the fly inside the product.  AUTO picks per shape.  FOLD is AUTO except that the input gradient
  * takes, wherever the layer allows it, the transposed product with phi_c^{-1} applied to every tile of the
- * patch-matrix gradient on chip (AUTO uses that route only where it is the fastest). */
-enum { VCNN_ALGO_AUTO = 0, VCNN_ALGO_EXPLICIT = 1, VCNN_ALGO_IMPLICIT = 2, VCNN_ALGO_FOLD = 3 };
+ * patch-matrix gradient on chip (AUTO uses that route only where it is the fastest).  FFT is AUTO except that the
+ * forward pass of layers with one-dimensional kernels (r x 1 or 1 x s, at least 8 taps, no padding across the
+ * kernel) goes through the Fourier domain - the alternative the paper's related-work paragraph names ("FFT
+ * speedup"), kept as a comparison: AUTO never takes it. */
+enum { VCNN_ALGO_AUTO = 0, VCNN_ALGO_EXPLICIT = 1, VCNN_ALGO_IMPLICIT = 2, VCNN_ALGO_FOLD = 3, VCNN_ALGO_FFT = 4 };
 
 typedef struct {
   int32_t n, c, h, w;                         /* input: batch, channels, height, width */

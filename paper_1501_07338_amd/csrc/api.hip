@@ -90,7 +90,7 @@ static bool halo_bwd_data_pays(const ConvGeom& g, const HaloPlan& hp) {
 
 // Which realisation a pass uses for a given shape.  The same decision drives the workspace query and
 // the launch, so the two always agree.
-enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER, PATH_HALO, PATH_HALO_FILTER, PATH_HALO_BF16, PATH_FILTER_BF16, PATH_HALO_FILTER_BF16, PATH_FEW_COLS_FILTER, PATH_SMALL, PATH_SMALL_BWD, PATH_FOLD };
+enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER, PATH_HALO, PATH_HALO_FILTER, PATH_HALO_BF16, PATH_FILTER_BF16, PATH_HALO_FILTER_BF16, PATH_FEW_COLS_FILTER, PATH_SMALL, PATH_SMALL_BWD, PATH_FOLD, PATH_FFT };
 struct Plan {
   Path path;
   DirectGeom dg;
@@ -101,6 +101,7 @@ struct Plan {
   FilterGradBf16Plan hfb;
   FewColsPlan fcp;
   FoldPlan fold;
+  FftPlan fft;
   int split;        // channel slices (few-out), output-map group size (few-in) or batch slices (filter gradient)
   size_t partial_bytes;
   size_t workspace_bytes;
@@ -112,7 +113,13 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
   p.path = PATH_EXPLICIT;
   const int algo = g_conv_algo.load();
   const bool allow_direct = algo != VCNN_ALGO_EXPLICIT;
-  const bool automatic = algo == VCNN_ALGO_AUTO || algo == VCNN_ALGO_FOLD;  // FOLD only re-routes the input gradient
+  // FOLD only re-routes the input gradient, FFT only the forward pass of layers with one-dimensional kernels
+  const bool automatic = algo == VCNN_ALGO_AUTO || algo == VCNN_ALGO_FOLD || algo == VCNN_ALGO_FFT;
+  if (algo == VCNN_ALGO_FFT && pass == VCNN_PASS_FWD && conv_fft_plan(g, &p.fft)) {
+    p.path = PATH_FFT;
+    p.workspace_bytes = p.fft.xf_bytes + p.fft.wf_bytes + p.fft.yf_bytes;
+    return p;
+  }
   // bf16 variant, default route: the bf16 matrix-core kernels wherever the layer has enough maps / channels
   const bool bf16_mfma = dtype == VCNN_BF16 && automatic;
   // (1x1 layers included: with asynchronous staging they are a plain bf16 product through the same kernel)
@@ -246,7 +253,8 @@ const char* vcnn_last_error(void) { return g_err; }
 int32_t vcnn_version(void) { return 100; }
 
 vcnn_status vcnn_set_conv_algo(int32_t algo) {
-  if (algo != VCNN_ALGO_AUTO && algo != VCNN_ALGO_EXPLICIT && algo != VCNN_ALGO_IMPLICIT && algo != VCNN_ALGO_FOLD)
+  if (algo != VCNN_ALGO_AUTO && algo != VCNN_ALGO_EXPLICIT && algo != VCNN_ALGO_IMPLICIT && algo != VCNN_ALGO_FOLD &&
+      algo != VCNN_ALGO_FFT)
     return fail(VCNN_ERR_UNSUPPORTED, "unknown conv algorithm %d", algo);
   g_conv_algo.store(algo);
   return VCNN_OK;
@@ -316,6 +324,7 @@ static vcnn_status conv_fwd_linear(const vcnn_conv_desc* d, const ConvGeom& g, c
     return launch_conv_halo_bf16(plan.hb, g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, x, w, g.K, (int64_t)g.r * g.s, 0,
                                  bias, y, relu, workspace, st);
   }
+  if (plan.path == PATH_FFT) return launch_conv_fft(plan.fft, dt, g, x, w, bias, y, relu, workspace, st);
 
   GemmArgs a{};
   a.A = w, a.C = y, a.bias = bias;

@@ -196,6 +196,17 @@ bool bwd_data_fold_plan(const ConvGeom& g, FoldPlan* p);
 vcnn_status launch_bwd_data_fold(const FoldPlan& p, int dtype, const ConvGeom& g, const void* w, const void* dy, void* dx,
                                  float* partial, hipStream_t st);
 
+// ---- fft_conv.hip -------------------------------------------------------------------------------------
+// Forward pass of layers with r x 1 or 1 x s kernels through the Fourier domain (comparison route).
+// workspace: xf_bytes + wf_bytes + yf_bytes.
+struct FftPlan {
+  int along_w, len, taps, pad, out_len, other, Q, L, logL, LP, sb;
+  size_t xf_bytes, wf_bytes, yf_bytes;
+};
+bool conv_fft_plan(const ConvGeom& g, FftPlan* p);
+vcnn_status launch_conv_fft(const FftPlan& p, int dtype, const ConvGeom& g, const void* x, const void* w, const float* bias,
+                            void* y, int relu, void* workspace, hipStream_t st);
+
 // out[i] = act(bias[(i / plane) % maps] + sum_s partial[s][i]), slices added in ascending order (bias nullable)
 vcnn_status launch_sum_slices(const float* partial, const float* bias, void* out, int out_dtype, int64_t count,
                               int splits, int64_t plane, int maps, int relu, hipStream_t st);

@@ -18,7 +18,7 @@ F32, BF16 = 0, 1
 ACT_NONE, ACT_RELU, ACT_TANH, ACT_SIGMOID = 0, 1, 2, 3
 POOL_MAX, POOL_AVG = 0, 1
 PASS_FWD, PASS_BWD_FILTER, PASS_BWD_DATA = 0, 1, 2
-ALGO_AUTO, ALGO_EXPLICIT, ALGO_IMPLICIT, ALGO_FOLD = 0, 1, 2, 3
+ALGO_AUTO, ALGO_EXPLICIT, ALGO_IMPLICIT, ALGO_FOLD, ALGO_FFT = 0, 1, 2, 3, 4
 
 
 class ConvDesc(Structure):

@@ -222,6 +222,52 @@ def test_conv_bwd_data_fused_fold_route(shape, dtype):
         vcnn.set_conv_algo(vcnn.ALGO_AUTO)
 
 
+# layers with one-dimensional kernels, for the Fourier-domain forward pass (the paper's related-work comparison)
+FFT_SHAPES = [
+    (2, 3, 9, 40, 5, 1, 21, 0, 0),       # 1 x 21 on rows of 40: transform length 64
+    (1, 2, 40, 9, 5, 21, 1, 0, 0),       # 21 x 1 on columns
+    (3, 5, 7, 33, 20, 1, 9, 0, 4),       # padded along the kernel: 'same' rows
+    (2, 4, 33, 7, 3, 9, 1, 4, 0),        # ... columns
+    (2, 1, 70, 70, 7, 21, 1, 0, 0),      # one channel, transform length 128
+    (2, 38, 6, 184, 38, 1, 121, 0, 0),   # the deconvolution network's second layer on a few rows (length 256)
+    (1, 1, 184, 20, 38, 121, 1, 0, 0),   # ... its first layer on a few columns
+    (1, 2, 3, 600, 2, 1, 100, 0, 0),     # transform length 1024
+    (2, 3, 5, 16, 4, 1, 16, 0, 0),       # kernel as long as the line: one output per line
+    (1, 17, 4, 50, 33, 1, 8, 0, 7),      # 'full' padding, more maps than one batch of the contraction
+]
+
+
+@pytest.mark.parametrize("dtype", [vcnn.F32, vcnn.BF16])
+@pytest.mark.parametrize("relu", [False, True])
+@pytest.mark.parametrize("shape", FFT_SHAPES)
+def test_conv_fwd_fourier_route(shape, relu, dtype):
+    n, c, h, w, k, r, s, ph, pw = shape
+    x, wt, b, _ = conv_case(shape, 2900)
+    tol = TOL_F32
+    cast = lambda t: t
+    if dtype == vcnn.BF16:
+        from paper_1501_07338_amd.workloads import bf16_round
+        from util import TOL_BF16
+        x, wt, tol = bf16_round(x), bf16_round(wt), TOL_BF16
+        cast = lambda t: t.to(torch.bfloat16)
+    d = vcnn.conv_desc(n, c, h, w, k, r, s, ph, pw, dtype=dtype, act=vcnn.ACT_RELU if relu else vcnn.ACT_NONE)
+    oh, ow = vcnn.conv_out_shape(d)
+    want = O.conv_fwd(x, wt, b, pad=(ph, pw), relu=relu)
+    try:
+        vcnn.set_conv_algo(vcnn.ALGO_AUTO)
+        plain = vcnn.conv_workspace_bytes(d, vcnn.PASS_FWD)
+        vcnn.set_conv_algo(vcnn.ALGO_FFT)
+        need = vcnn.conv_workspace_bytes(d, vcnn.PASS_FWD)
+        assert need > plain and need >= 8 * (c + k) * n * (h if r == 1 else w) * 17, "the Fourier route was not taken"
+        ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+        ws.fill_(0xFF)  # NaN patterns: nothing may be read before it is written
+        y = cast(torch.full((n, k, oh, ow), float("nan"), device=DEV))
+        vcnn.conv_fwd(d, cast(to_dev(x)), cast(to_dev(wt)), to_dev(b), y, ws)
+        assert_close(to_np(y.float()), want, tol, "Fourier-domain forward")
+    finally:
+        vcnn.set_conv_algo(vcnn.ALGO_AUTO)
+
+
 POOL_SHAPES = [(2, 3, 4, 4, 2, 2), (3, 5, 24, 24, 2, 2), (2, 7, 32, 32, 3, 2), (3, 4, 15, 15, 3, 2), (2, 2, 7, 7, 3, 2),
                (1, 3, 9, 11, 2, 1), (2, 2, 5, 6, 5, 1), (1, 1, 3, 3, 3, 3)]
 
