@@ -123,6 +123,7 @@ struct HaloFilterPlan {
   int runs_per_img, runs_per_split, splits;
   size_t lds_bytes, partial_bytes;
   bool vec;
+  bool vec4_any;     // float dY can be fetched 16 bytes at a time from any dword boundary (every run has >= 4 pixels)
   bool bias_column;  // the last column tile has a spare column: it carries the bias gradient (B operand = 1)
 };
 bool conv_halo_filter_plan(const ConvGeom& g, HaloFilterPlan* p);

@@ -14,6 +14,7 @@
 // small kernel adds, for every input pixel, the regions that cover it in ascending tile order.
 #include <algorithm>
 #include <cstdlib>
+#include <type_traits>
 
 #include "common.h"
 #include "elem.h"
@@ -58,13 +59,13 @@ __host__ __device__ inline FoldRegion fold_region(int it, int jt, int K, int P, 
   return g;
 }
 
-template <bool A_VEC, bool MI_INDEP, typename T>
+template <bool A_VEC, bool B_VEC, bool MI_INDEP, typename T>
 __global__ __launch_bounds__(kThreads, 4) void bwd_data_fold_kernel(FoldArgs a) {
   constexpr int BM = kFoldBM, BN = kFoldBN, BK = kFoldBK, WM = 64, WN = 64, TM = 2, TN = 2;
   using LA = LdsTile<BM, BK, false>;
   using LB = LdsTile<BN, BK, false>;
   using SA = Stager<BM, BK, kThreads, false, A_VEC>;
-  using SB = Stager<BN, BK, kThreads, false, false>;
+  using SB = Stager<BN, BK, kThreads, false, B_VEC>;
   extern __shared__ float4 smem4[];
   float* smem = reinterpret_cast<float*>(smem4);
   float* const As0 = smem;
@@ -107,7 +108,10 @@ __global__ __launch_bounds__(kThreads, 4) void bwd_data_fold_kernel(FoldArgs a) 
   const bool a_ok = i0 + sa.c < a.K;  // A_VEC: K is a multiple of 4, so a group of four rows is in or out as a whole
   const int a_i = a_ok ? i0 + sa.c : 0;
   const bool b_ok = j0 + sb.c < a.P;
-  const int b_j = b_ok ? j0 + sb.c : 0;
+  // B_VEC (float only): four pixels per 16-byte load at dword alignment; the sample's last group may end early - its
+  // load is moved back to the last four pixels (P >= 4) and the wanted ones are shifted down, zeros behind them
+  const int b_j = b_ok ? (B_VEC ? min(j0 + sb.c, a.P - 4) : j0 + sb.c) : 0;
+  const int b_d = b_ok ? j0 + sb.c - b_j : 0;
   auto fetch = [&](int k0) {
 #pragma unroll
     for (int e = 0; e < SA::SLOTS; ++e) {
@@ -125,7 +129,19 @@ __global__ __launch_bounds__(kThreads, 4) void bwd_data_fold_kernel(FoldArgs a) 
     for (int e = 0; e < SB::SLOTS; ++e) {
       const int k = k0 + sb.line(e);
       sb.ok[e] = b_ok && k < a.m;
-      sb.v[e][0] = ld(gB + (int64_t)min(k, a.m - 1) * a.P + b_j);
+      const T* src = gB + (int64_t)min(k, a.m - 1) * a.P + b_j;
+      if constexpr (B_VEC && std::is_same<T, float>::value) {
+        const float4 t = ld4_dword_aligned(src);
+        sb.v[e][0] = t.x, sb.v[e][1] = t.y, sb.v[e][2] = t.z, sb.v[e][3] = t.w;
+        if (b_d > 0) {
+          sb.v[e][0] = b_d == 1 ? t.y : (b_d == 2 ? t.z : t.w);
+          sb.v[e][1] = b_d == 1 ? t.z : (b_d == 2 ? t.w : 0.f);
+          sb.v[e][2] = b_d == 1 ? t.w : 0.f;
+          sb.v[e][3] = 0.f;
+        }
+      } else {
+        sb.v[e][0] = ld(src);
+      }
     }
   };
 
@@ -318,14 +334,19 @@ vcnn_status launch_bwd_data_fold(const FoldPlan& p, int dtype, const ConvGeom& g
     if (ds > -g.s && ds < g.s && dr < g.r && std::abs(dr * g.ow + ds) < 64) mi_indep = false;
   }
   auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, block, p.lds_bytes, st, a); };
+  const bool bvec = !bf && g.P >= 4 && (reinterpret_cast<uintptr_t>(dy) & 3) == 0;
   if (bf) {
-    if (vec && mi_indep) go(bwd_data_fold_kernel<true, true, bf16>);
-    else if (vec) go(bwd_data_fold_kernel<true, false, bf16>);
-    else go(bwd_data_fold_kernel<false, false, bf16>);
+    if (vec && mi_indep) go(bwd_data_fold_kernel<true, false, true, bf16>);
+    else if (vec) go(bwd_data_fold_kernel<true, false, false, bf16>);
+    else go(bwd_data_fold_kernel<false, false, false, bf16>);
+  } else if (bvec) {
+    if (vec && mi_indep) go(bwd_data_fold_kernel<true, true, true, float>);
+    else if (vec) go(bwd_data_fold_kernel<true, true, false, float>);
+    else go(bwd_data_fold_kernel<false, true, false, float>);
   } else {
-    if (vec && mi_indep) go(bwd_data_fold_kernel<true, true, float>);
-    else if (vec) go(bwd_data_fold_kernel<true, false, float>);
-    else go(bwd_data_fold_kernel<false, false, float>);
+    if (vec && mi_indep) go(bwd_data_fold_kernel<true, false, true, float>);
+    else if (vec) go(bwd_data_fold_kernel<true, false, false, float>);
+    else go(bwd_data_fold_kernel<false, false, false, float>);
   }
   if (vcnn_status s = check_launch("bwd_data_fold")) return s;
   const int64_t total = (int64_t)g.n * g.c * g.h * g.w;

@@ -634,7 +634,20 @@ __global__ __launch_bounds__(kThreads) void conv_halo_filter_kernel(HaloFilterAr
         const int m = i0 + sa.line(e);
         sa.ok[e] = m < a.m && pk < plen;
         const T* src = dyn + (int64_t)min(m, a.m - 1) * a.P + min(pk, plen - (VEC ? 4 : 1));
-        if (VEC) {
+        if constexpr (VEC && std::is_same<T, float>::value) {
+          // rows of dY start at any dword (odd pixel counts): a 16-byte load at dword alignment.  A run's last group
+          // of four may end before its fourth pixel: the load is moved back to the last four pixels (plen >= 4 by
+          // the plan) and the wanted ones are shifted down, zeros behind them.
+          const float4 t = ld4_dword_aligned(src);
+          const int d = pk - min(pk, plen - 4);
+          sa.v[e][0] = t.x, sa.v[e][1] = t.y, sa.v[e][2] = t.z, sa.v[e][3] = t.w;
+          if (d > 0 && d < 4) {
+            sa.v[e][0] = d == 1 ? t.y : (d == 2 ? t.z : t.w);
+            sa.v[e][1] = d == 1 ? t.z : (d == 2 ? t.w : 0.f);
+            sa.v[e][2] = d == 1 ? t.w : 0.f;
+            sa.v[e][3] = 0.f;
+          }
+        } else if constexpr (VEC) {
           const float4 t = ld4(src);
           sa.v[e][0] = t.x, sa.v[e][1] = t.y, sa.v[e][2] = t.z, sa.v[e][3] = t.w;
         } else {
@@ -751,7 +764,10 @@ bool conv_halo_filter_plan(const ConvGeom& g, HaloFilterPlan* p) {
   }
   p->partial_bytes = p->bias_column ? (size_t)p->splits * g.M * (g.K + 1) * sizeof(float)
                                     : (p->splits > 1 ? (size_t)p->splits * g.M * g.K * sizeof(float) : 0);
+  // 16-byte loads of dY: when the pixel count is a multiple of 4 (rows then keep the tensor's alignment); float rows
+  // may also start at any dword, as long as every run holds at least four pixels (vec4_any)
   p->vec = g.P % 4 == 0;
+  p->vec4_any = g.P >= 4 && (g.P % best == 0 || g.P % best >= 4);
   return tiles <= 0x7fffffffLL && p->splits <= 65535;
 }
 
@@ -792,7 +808,8 @@ vcnn_status launch_conv_halo_filter(const HaloFilterPlan& p, int dtype, const Co
   a.bp = p.bp, a.runs_per_img = p.runs_per_img, a.runs_per_split = p.runs_per_split;
   a.ccs = p.ccs, a.nr = p.nr, a.wp = p.wp;
   const int tiles = a.tiles_m * (int)ceil_div(g.K, p.bnk);
-  const bool vec = p.vec && (dtype == VCNN_BF16 ? group_aligned<bf16>(dy) : group_aligned<float>(dy));
+  const bool vec = dtype == VCNN_BF16 ? p.vec && group_aligned<bf16>(dy)
+                                      : (p.vec && group_aligned<float>(dy)) || (p.vec4_any && (reinterpret_cast<uintptr_t>(dy) & 3) == 0);
   if (p.bm == 32)
     launch_halo_filter<32, 256, 32, 64, 128>(a, p, vec, dtype, tiles, st);
   else if (p.bm == 64)

@@ -42,6 +42,16 @@ __device__ __forceinline__ void st4(bf16* p, float4 v) {
   *reinterpret_cast<uint2*>(p) = u;
 }
 
+// Four consecutive floats from an address that is only 4-byte aligned: one 16-byte load (the target's unaligned
+// access mode serves wide loads at any dword boundary; the compiler emits global_load_dwordx4 for this type).
+struct __attribute__((aligned(4))) float4_dword_aligned {
+  float x, y, z, w;
+};
+__device__ __forceinline__ float4 ld4_dword_aligned(const float* p) {
+  const float4_dword_aligned t = *reinterpret_cast<const float4_dword_aligned*>(p);
+  return make_float4(t.x, t.y, t.z, t.w);
+}
+
 // Gradient g passed back through the activation `act` (VCNN_ACT_*) whose forward OUTPUT was y: the factor
 // sigma'(.) of the delta recursion, written in terms of y (ReLU: y > 0; tanh: 1 - y^2; sigmoid: y (1 - y)).
 __device__ __forceinline__ float act_grad(int act, float y, float g) {
