@@ -101,6 +101,21 @@ def finite_or_die(name, loss):
     return loss
 
 
+MARKERS: dict = {}  # marker id -> name of the phase it precedes (filled only with --markers)
+
+
+def mark(name):
+    """With --markers: launches an empty kernel whose grid size numbers the phase `name` in a kernel trace."""
+    if MARKERS is not None and mark.enabled:
+        from paper_1501_07338_amd import benchaid
+        ident = len(MARKERS) + 1
+        MARKERS[ident] = name
+        benchaid.marker(ident)
+
+
+mark.enabled = False
+
+
 def run_workload(name, steps, warmup, layer_iters=10):
     """`name` is a workload, optionally suffixed `_bf16` for the bfloat16-storage variant."""
     import torch
@@ -179,7 +194,9 @@ def run_workload(name, steps, warmup, layer_iters=10):
         ws_need = max(vcnn.conv_workspace_bytes(d, p) for p in (vcnn.PASS_FWD, vcnn.PASS_BWD_DATA))
         assert ts.workspace.numel() >= ws_need
         for pname, fn in passes.items():
+            mark(f"{name}.conv{li}.{pname}")
             t = time_calls(fn, layer_iters, stream)
+            mark("-")
             peak = MFMA_BF16_PEAK_TFLOPS if bf16 else MFMA_F32_PEAK_TFLOPS
             layers.append({"layer": f"conv{li}", "pass": pname, "M": g["M"], "K": g["K"], "N": g["N"], "ms": t,
                            "gflops": flops / (t * 1e6),
@@ -283,7 +300,9 @@ def hbm_kernels(stream):
         del x, y, am, dy, dx
     t = torch.randn(64, 64, 64, 64, device="cuda")  # cfg4 c1 output
     g, o = torch.randn_like(t), torch.empty_like(t)
+    mark("relu_bwd on 3 x 67 MB")
     rec("relu_bwd", "cfg4.c1 output", 12.0 * t.numel(), timed(lambda: vcnn.act_bwd(vcnn.ACT_RELU, vcnn.F32, t.numel(), t, g, o)))
+    mark("-")
     del t, g, o
     torch.cuda.empty_cache()
     return out
@@ -333,7 +352,9 @@ def aids(stream):
         out["mfma_" + name] = {"sustained_tflops": flop / (ms * 1e9), "data_sheet_tflops": peak, "ms": ms}
     src = torch.empty(1 << 28, device="cuda").normal_()
     dst = torch.empty_like(src)
+    mark("copy of 1 GiB")
     ms = sorted(time_calls(lambda: benchaid.copy(src, dst), 5, stream) for _ in range(3))[1]
+    mark("-")
     out["copy_1GiB"] = {"bytes_moved": 2.0 * src.numel() * 4, "ms": ms, "gbs": 2.0 * src.numel() * 4 / (ms * 1e6)}
     del src, dst, sink
     torch.cuda.empty_cache()
@@ -434,6 +455,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--no-sweep", action="store_true", help="skip the mini-batch sweep of cfg2 / cfg3")
     ap.add_argument("--no-hbm", action="store_true", help="skip the bandwidth-bound kernels and the benchmark's yardsticks")
+    ap.add_argument("--markers", action="store_true", help="number the per-layer timing phases with empty marker kernels "
+                    "(for rocprofv3 traces; the map goes to the detail file)")
     ap.add_argument("--detail", default=str(ROOT / "gpurun_out" / "bench_detail.json"), help="where the long tables go")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -445,6 +468,7 @@ def main():
         sys.exit("bench.py: no GPU visible")
     vcnn.lib()  # raises if the HIP library has not been built: there is no fallback path
 
+    mark.enabled = args.markers
     main_res = run_workload(args.workload, args.steps, args.warmup)
     others = {}
     for name in [s for s in args.others.split(",") if s and s != args.workload]:
@@ -452,7 +476,7 @@ def main():
         others[name] = run_workload(name, max(args.steps, 100) if small else args.steps, args.warmup,
                                     layer_iters=10 if small else 5)
 
-    detail = {"main": main_res, "other_workloads": others}
+    detail = {"main": main_res, "other_workloads": others, "markers": MARKERS}
     stream = torch.cuda.current_stream()
     if not args.no_hbm:
         detail["hbm_kernels"] = hbm_kernels(stream)

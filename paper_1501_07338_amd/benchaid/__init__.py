@@ -19,6 +19,7 @@ def lib() -> ctypes.CDLL:
         h = ctypes.CDLL(str(LIB_PATH))
         h.benchaid_mfma.restype, h.benchaid_mfma.argtypes = c_int, [c_int, c_int, c_int, c_void_p, c_void_p, c_void_p]
         h.benchaid_copy.restype, h.benchaid_copy.argtypes = c_int, [c_void_p, c_void_p, c_size_t, c_void_p]
+        h.benchaid_marker.restype, h.benchaid_marker.argtypes = c_int, [c_int, c_void_p]
         _lib = h
     return _lib
 
@@ -46,3 +47,10 @@ def copy(src, dst, stream=None) -> int:
     if err:
         raise RuntimeError(f"benchaid_copy: HIP error {err}")
     return nbytes
+
+
+def marker(ident: int, stream=None) -> None:
+    """An empty kernel of `ident` blocks: marks the start of a phase in a kernel trace."""
+    err = lib().benchaid_marker(ident, _stream(stream))
+    if err:
+        raise RuntimeError(f"benchaid_marker: HIP error {err}")

@@ -5,6 +5,7 @@
 //     is below the nominal 2.4 GHz).  Every wave issues independent MFMAs back to back on register operands.
 //   benchaid_copy: a plain streaming copy of a known size, the yardstick the HBM traffic counters of a
 //     profiler run are scaled by.
+//   benchaid_marker: an empty kernel whose grid size numbers the phase that follows it in a kernel trace.
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
@@ -51,7 +52,17 @@ __global__ __launch_bounds__(kThreads) void benchaid_copy_kernel(const float4* _
     dst[i] = src[i];
 }
 
+// does nothing; its grid size is what a kernel trace shows
+__global__ void benchaid_marker_kernel() {}
+
 extern "C" {
+
+// A phase marker for kernel traces: an empty kernel of `id` blocks of 64 threads (grid size 64 * id in the trace).
+int benchaid_marker(int id, void* stream) {
+  if (id <= 0 || id > 65535) return (int)hipErrorInvalidValue;
+  hipLaunchKernelGGL(benchaid_marker_kernel, dim3((unsigned)id), dim3(64), 0, (hipStream_t)stream);
+  return (int)hipGetLastError();
+}
 
 // Launches `blocks` blocks of 4 waves that each issue iters x 4 independent matrix-core instructions (bf16 == 0:
 // v_mfma_f32_32x32x2_f32, else v_mfma_f32_32x32x16_bf16); one float per thread is written to sink (DEVICE,
