@@ -215,6 +215,10 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
     } else if (allow_direct && (g.c > 4 || g.k >= 32 || algo == VCNN_ALGO_IMPLICIT) && conv_halo_filter_plan(g, &p.hfp)) {
       p.path = PATH_HALO_FILTER;
       p.workspace_bytes = align256(p.hfp.partial_bytes);
+    } else if (automatic && is_pointwise(g) && g.k >= 32) {
+      // the patch matrix of an unpadded 1 x 1 layer is the input itself: the product reads it in place
+      p.path = PATH_POINTWISE;
+      p.workspace_bytes = align256(bwd_filter_partial_bytes(g));
     } else if (allow_direct && direct_filter_grad_plan(g, &p.dg, &p.split, &p.partial_bytes)) {
       p.path = PATH_DIRECT_FILTER;
       p.workspace_bytes = align256(p.partial_bytes);
@@ -367,10 +371,12 @@ vcnn_status vcnn_conv_bwd_filter(const vcnn_conv_desc* d, const void* x, const v
   } else if (plan.path == PATH_HALO_FILTER) {
     if (vcnn_status s = launch_conv_halo_filter(plan.hfp, dt, g, x, dy, dw, dbias, (float*)workspace, st)) return s;
     if (plan.hfp.bias_column) return VCNN_OK;  // the bias gradient came out of the same product
+  } else if (plan.path == PATH_POINTWISE) {
+    if (vcnn_status s = launch_bwd_filter_gemm_f32(g, dt, dy, nullptr, x, dw, (float*)workspace, st)) return s;
   } else {
     float* partial = (float*)((char*)workspace + col_bytes(g));
     if (vcnn_status s = launch_im2col(g, dt, x, workspace, st)) return s;
-    if (vcnn_status s = launch_bwd_filter_gemm_f32(g, dt, dy, workspace, dw, partial, st)) return s;
+    if (vcnn_status s = launch_bwd_filter_gemm_f32(g, dt, dy, workspace, nullptr, dw, partial, st)) return s;
   }
   if (dbias) return launch_bias_grad(g, dt, dy, dbias, bias_partial, st);
   return VCNN_OK;

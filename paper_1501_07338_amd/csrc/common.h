@@ -77,8 +77,9 @@ vcnn_status launch_fc_bwd_small(const GemmArgs& gw, const GemmArgs& gx, hipStrea
 // split over `splits` column ranges whose partial sums are combined in a fixed order.
 int bwd_filter_splits(const ConvGeom& g);
 size_t bwd_filter_partial_bytes(const ConvGeom& g);
-vcnn_status launch_bwd_filter_gemm_f32(const ConvGeom& g, int dtype, const void* dy, const void* col, float* dw,
-                                       float* partial, hipStream_t st);
+// xin != nullptr (unpadded 1 x 1 layers only): the patch matrix is the input itself, read in place; col is unused
+vcnn_status launch_bwd_filter_gemm_f32(const ConvGeom& g, int dtype, const void* dy, const void* col, const void* xin,
+                                       float* dw, float* partial, hipStream_t st);
 
 // ---- direct.hip ---------------------------------------------------------------------------------
 // Generic correlation out[n][o][y][x] = sum_{i,r,s} wgt(o,i,r,s) * in[n][i][y+r-py][x+s-px] used by the

@@ -84,6 +84,21 @@ __global__ __launch_bounds__(kThreads, BK == 16 ? 4 : 1) void gemm_f32_kernel(Ge
     b_row_ok[e] = j < a.N;
     b_off[e] = jmap(b_row_ok[e] ? j : 0, a.b_P, a.b_simg, a.b_sj);
   }
+  // B contiguous along j and fetched four columns at a time (B_VEC, !B_KC; float: at any dword boundary): every slot
+  // of a thread holds the same four columns j .. j+3.  If they run over the end of the matrix or of a sample (per-sample
+  // [k][P] maps with P not a multiple of 4) they are fetched one by one from their own offsets.
+  bool b_whole = true;
+  int64_t b_off1[4] = {0, 0, 0, 0};
+  bool b_ok1[4] = {false, false, false, false};
+  if constexpr (B_VEC && !B_KC && std::is_same<TI, float>::value) {
+    const int j = j0 + sb.c;
+    b_whole = j + 3 < a.N && (a.b_P == 0 || j % a.b_P + 3 < a.b_P);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      b_ok1[u] = j + u < a.N;
+      b_off1[u] = jmap(b_ok1[u] ? j + u : 0, a.b_P, a.b_simg, a.b_sj);
+    }
+  }
 
   auto fetch = [&](int k0) {
 #pragma unroll
@@ -103,7 +118,19 @@ __global__ __launch_bounds__(kThreads, BK == 16 ? 4 : 1) void gemm_f32_kernel(Ge
       const int k = k0 + sb.k_of(e, 0);
       sb.ok[e] = b_row_ok[e] && k < a.K;
       const TI* src = gB + b_off[e] + (int64_t)min(k, (B_VEC && B_KC) ? a.K - 4 : a.K - 1) * a.b_sk;
-      if (B_VEC) {
+      if constexpr (B_VEC && !B_KC && std::is_same<TI, float>::value) {
+        if (b_whole) {
+          const float4 t = ld4_dword_aligned(src);
+          sb.v[e][0] = t.x, sb.v[e][1] = t.y, sb.v[e][2] = t.z, sb.v[e][3] = t.w;
+        } else {
+          const int64_t ko = (int64_t)min(k, a.K - 1) * a.b_sk;
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const float t = ld(gB + b_off1[u] + ko);
+            sb.v[e][u] = b_ok1[u] ? t : 0.f;
+          }
+        }
+      } else if constexpr (B_VEC) {
         const float4 t = ld4(src);
         sb.v[e][0] = t.x, sb.v[e][1] = t.y, sb.v[e][2] = t.z, sb.v[e][3] = t.w;
       } else {
@@ -439,6 +466,8 @@ vcnn_status launch_gemm_f32(const GemmArgs& a, hipStream_t st) {
     av = in_aligned(a.A, a.in_dtype) && a.a_si == 1 && a.a_sk % 4 == 0 && a.M % 4 == 0;
   if (b_kc)
     bv = in_aligned(a.B, a.in_dtype) && a.b_P == 0 && a.b_sj % 4 == 0 && a.K % 4 == 0;
+  else if (a.in_dtype == VCNN_F32)  // 16-byte loads at any dword boundary; groups that straddle are split in the kernel
+    bv = (reinterpret_cast<uintptr_t>(a.B) & 3) == 0 && a.b_sj == 1 && a.N >= 4;
   else
     bv = in_aligned(a.B, a.in_dtype) && a.b_sj == 1 && a.b_sk % 4 == 0 && a.N % 4 == 0 &&
          (a.b_P == 0 || (a.b_P % 4 == 0 && a.b_simg % 4 == 0));
@@ -469,7 +498,7 @@ vcnn_status launch_gemm_f32(const GemmArgs& a, hipStream_t st) {
 // -------------------------------------------------------------------------------------------------
 template <int BM, int BN, int BK, int WM, int WN, bool VEC, typename T>
 __global__ __launch_bounds__(kThreads) void bwd_filter_f32_kernel(ConvGeom g, const T* __restrict__ dy,
-                                                                  const T* __restrict__ col,
+                                                                  const T* __restrict__ col, const T* __restrict__ xin,
                                                                   float* __restrict__ out, int tiles_m, int chunk) {
   static_assert((BM / WM) * (BN / WN) * 64 == kThreads, "four waves per block");
   using LA = LdsTile<BM, BK, true>;
@@ -503,34 +532,70 @@ __global__ __launch_bounds__(kThreads) void bwd_filter_f32_kernel(ConvGeom g, co
   int n = (int)(j / P);
   int p = (int)(j - (int64_t)n * P);
 
+  // B operand: the patch matrix col[k][j], or - for an unpadded 1 x 1 layer, whose patch matrix is the input itself
+  // sample by sample - x[(n*K + k)*P + p] read in place (xin != nullptr).
+  auto b_src = [&](int k, int nn, int pp, int64_t jj) {
+    return xin ? xin + ((int64_t)nn * K + k) * P + pp : col + (int64_t)k * g.N + jj;
+  };
   auto fetch = [&]() {
-    // With VEC, je - js and P are multiples of 4, so a group of four is inside or outside as a whole.
-    // Out-of-range slots load from a clamped, valid address and are zeroed when written to LDS.
+    // Out-of-range slots load from a clamped, valid address and are zeroed when written to LDS.  VEC: a group of
+    // four consecutive contraction indices is one 16-byte load when it lies inside one sample and inside the range
+    // (float: at any dword boundary; bf16: P and the range are multiples of 4, so groups never straddle); a group
+    // that runs over the end of a sample or of the range is fetched element by element.
     const bool jin = j < je;
     const int nn = jin ? n : 0, pp = jin ? p : 0;
     const int64_t jj = jin ? j : 0;
+    const bool whole = !VEC || (j + 3 < je && p + 3 < P);
+    if (whole || !jin) {
 #pragma unroll
-    for (int e = 0; e < SA::SLOTS; ++e) {
-      const int m = i0 + sa.line(e);
-      sa.ok[e] = jin && m < M;
-      const T* src = dy + ((int64_t)nn * M + min(m, M - 1)) * P + pp;
-      if (VEC) {
-        const float4 t = ld4(src);
-        sa.v[e][0] = t.x, sa.v[e][1] = t.y, sa.v[e][2] = t.z, sa.v[e][3] = t.w;
-      } else {
-        sa.v[e][0] = ld(src);
+      for (int e = 0; e < SA::SLOTS; ++e) {
+        const int m = i0 + sa.line(e);
+        sa.ok[e] = jin && m < M;
+        const T* src = dy + ((int64_t)nn * M + min(m, M - 1)) * P + pp;
+        if constexpr (VEC) {
+          float4 t;
+          if constexpr (std::is_same<T, float>::value) t = ld4_dword_aligned(src);
+          else t = ld4(src);
+          sa.v[e][0] = t.x, sa.v[e][1] = t.y, sa.v[e][2] = t.z, sa.v[e][3] = t.w;
+        } else {
+          sa.v[e][0] = ld(src);
+        }
       }
-    }
 #pragma unroll
-    for (int e = 0; e < SB::SLOTS; ++e) {
-      const int k = k0 + sb.line(e);
-      sb.ok[e] = jin && k < K;
-      const T* src = col + (int64_t)min(k, K - 1) * g.N + jj;
-      if (VEC) {
-        const float4 t = ld4(src);
-        sb.v[e][0] = t.x, sb.v[e][1] = t.y, sb.v[e][2] = t.z, sb.v[e][3] = t.w;
-      } else {
-        sb.v[e][0] = ld(src);
+      for (int e = 0; e < SB::SLOTS; ++e) {
+        const int k = k0 + sb.line(e);
+        sb.ok[e] = jin && k < K;
+        const T* src = b_src(min(k, K - 1), nn, pp, jj);
+        if constexpr (VEC) {
+          float4 t;
+          if constexpr (std::is_same<T, float>::value) t = ld4_dword_aligned(src);
+          else t = ld4(src);
+          sb.v[e][0] = t.x, sb.v[e][1] = t.y, sb.v[e][2] = t.z, sb.v[e][3] = t.w;
+        } else {
+          sb.v[e][0] = ld(src);
+        }
+      }
+    } else if constexpr (VEC) {
+      int nu = n, pu = p;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const bool in = j + u < je;
+        const int nq = in ? nu : 0, pq = in ? pu : 0;
+#pragma unroll
+        for (int e = 0; e < SA::SLOTS; ++e) {
+          const int m = i0 + sa.line(e);
+          sa.ok[e] = m < M;
+          const float t = ld(dy + ((int64_t)nq * M + min(m, M - 1)) * P + pq);
+          sa.v[e][u] = in ? t : 0.f;
+        }
+#pragma unroll
+        for (int e = 0; e < SB::SLOTS; ++e) {
+          const int k = k0 + sb.line(e);
+          sb.ok[e] = k < K;
+          const float t = ld(b_src(min(k, K - 1), nq, pq, in ? j + u : 0));
+          sb.v[e][u] = in ? t : 0.f;
+        }
+        if (++pu >= P) pu = 0, ++nu;
       }
     }
     j += BK;
@@ -601,29 +666,30 @@ size_t bwd_filter_partial_bytes(const ConvGeom& g) {
 }
 
 template <int BM, int BN, int WM, int WN, bool VEC, typename T>
-static void launch_bf_one(const ConvGeom& g, const void* dy, const void* col, float* out, int tiles_m, int chunk,
-                          dim3 grid, hipStream_t st) {
+static void launch_bf_one(const ConvGeom& g, const void* dy, const void* col, const void* xin, float* out, int tiles_m,
+                          int chunk, dim3 grid, hipStream_t st) {
   const size_t lds = gemm_lds_bytes<BM, BN, kBfBK, true, true>();
   auto kernel = bwd_filter_f32_kernel<BM, BN, kBfBK, WM, WN, VEC, T>;
   static bool opted_in = false;
   allow_lds(kernel, lds, opted_in);
-  hipLaunchKernelGGL(kernel, grid, dim3(kThreads), lds, st, g, (const T*)dy, (const T*)col, out, tiles_m, chunk);
+  hipLaunchKernelGGL(kernel, grid, dim3(kThreads), lds, st, g, (const T*)dy, (const T*)col, (const T*)xin, out, tiles_m,
+                     chunk);
 }
 
 template <int BM, int BN, int WM, int WN>
-static void launch_bf(const ConvGeom& g, int dtype, const void* dy, const void* col, float* out, int tiles_m, int chunk,
-                      dim3 grid, bool vec, hipStream_t st) {
+static void launch_bf(const ConvGeom& g, int dtype, const void* dy, const void* col, const void* xin, float* out,
+                      int tiles_m, int chunk, dim3 grid, bool vec, hipStream_t st) {
   if (dtype == VCNN_BF16) {
-    if (vec) launch_bf_one<BM, BN, WM, WN, true, bf16>(g, dy, col, out, tiles_m, chunk, grid, st);
-    else launch_bf_one<BM, BN, WM, WN, false, bf16>(g, dy, col, out, tiles_m, chunk, grid, st);
+    if (vec) launch_bf_one<BM, BN, WM, WN, true, bf16>(g, dy, col, xin, out, tiles_m, chunk, grid, st);
+    else launch_bf_one<BM, BN, WM, WN, false, bf16>(g, dy, col, xin, out, tiles_m, chunk, grid, st);
   } else {
-    if (vec) launch_bf_one<BM, BN, WM, WN, true, float>(g, dy, col, out, tiles_m, chunk, grid, st);
-    else launch_bf_one<BM, BN, WM, WN, false, float>(g, dy, col, out, tiles_m, chunk, grid, st);
+    if (vec) launch_bf_one<BM, BN, WM, WN, true, float>(g, dy, col, xin, out, tiles_m, chunk, grid, st);
+    else launch_bf_one<BM, BN, WM, WN, false, float>(g, dy, col, xin, out, tiles_m, chunk, grid, st);
   }
 }
 
-vcnn_status launch_bwd_filter_gemm_f32(const ConvGeom& g, int dtype, const void* dy, const void* col, float* dw,
-                                       float* partial, hipStream_t st) {
+vcnn_status launch_bwd_filter_gemm_f32(const ConvGeom& g, int dtype, const void* dy, const void* col, const void* xin,
+                                       float* dw, float* partial, hipStream_t st) {
   const int chunk = bwd_filter_chunk(g);
   const int splits = bwd_filter_splits(g);
   float* out = splits > 1 ? partial : dw;
@@ -632,13 +698,16 @@ vcnn_status launch_bwd_filter_gemm_f32(const ConvGeom& g, int dtype, const void*
   const int64_t tiles = (int64_t)tiles_m * ceil_div(g.K, bwd_filter_bn(g));
   const dim3 grid((unsigned)tiles, (unsigned)splits);
   if (splits > 65535) return fail(VCNN_ERR_UNSUPPORTED, "bwd_filter: too many contraction splits");
-  const bool vec = g.P % 4 == 0 && in_aligned(dy, dtype) && in_aligned(col, dtype);
+  const void* b = xin ? xin : col;
+  // bf16: 8-byte loads need groups of four that keep the tensors' alignment; float: 16-byte loads at any dword
+  const bool vec = dtype == VCNN_BF16 ? g.P % 4 == 0 && g.N % 4 == 0 && in_aligned(dy, dtype) && in_aligned(b, dtype)
+                                      : g.P >= 4 && ((reinterpret_cast<uintptr_t>(dy) | reinterpret_cast<uintptr_t>(b)) & 3) == 0;
   if (bm == 32)
-    launch_bf<32, 128, 32, 32>(g, dtype, dy, col, out, tiles_m, chunk, grid, vec, st);
+    launch_bf<32, 128, 32, 32>(g, dtype, dy, col, xin, out, tiles_m, chunk, grid, vec, st);
   else if (bm == 64)
-    launch_bf<64, 128, 32, 64>(g, dtype, dy, col, out, tiles_m, chunk, grid, vec, st);
+    launch_bf<64, 128, 32, 64>(g, dtype, dy, col, xin, out, tiles_m, chunk, grid, vec, st);
   else
-    launch_bf<128, 128, 64, 64>(g, dtype, dy, col, out, tiles_m, chunk, grid, vec, st);
+    launch_bf<128, 128, 64, 64>(g, dtype, dy, col, xin, out, tiles_m, chunk, grid, vec, st);
   vcnn_status s = check_launch("bwd_filter_f32");
   if (s != VCNN_OK || splits == 1) return s;
   return launch_sum_slices(partial, nullptr, dw, VCNN_F32, g.M * g.K, splits, 1, 1, 0, st);

@@ -42,6 +42,9 @@ CONV_SHAPES = [
     (2, 8, 6, 6, 40, 5, 6, 4, 5),       # ... 'full' padding, 30 taps, large LDS tile
     (2, 6, 8, 8, 70, 3, 3, 1, 1),       # ... more than 64 maps: the kernel-matrix entries come in two batches
     (200, 16, 7, 7, 8, 3, 3, 1, 1),     # ... more blocks than are resident at once (the tighter register budget)
+    (3, 20, 7, 7, 40, 1, 1, 0, 0),      # 1 x 1 with an odd pixel count: groups of four run over the end of a sample
+    (5, 130, 5, 5, 70, 1, 1, 0, 0),     # ... two column tiles of the kernel matrix, three row tiles, 125 columns in all
+    (2, 33, 3, 1, 64, 1, 1, 0, 0),      # ... fewer pixels per sample than one group of four
 ]
 
 
