@@ -88,6 +88,18 @@ static bool halo_bwd_data_pays(const ConvGeom& g, const HaloPlan& hp) {
   return halo_flops / mfma_rate < exp_flops / mfma_rate + 1.3 * col_traffic / hbm_rate;
 }
 
+// The same correlation against the fused route (transposed product with phi_c^{-1} per tile on chip), which executes
+// exactly the nominal flops but pays a fixed fold per 128 x 128 tile: per tile about 4.1 us per 16 output maps of
+// contraction plus 8 us, 1024 tiles resident at once (measured on cfg5 c2 and c3).
+static bool fold_beats_halo(const ConvGeom& g, const HaloPlan& hp, const FoldPlan& fp) {
+  const double halo_flops = 2.0 * (double)ceil_div(g.c, hp.bm) * hp.bm * ((double)g.k * g.r * g.s) *
+                            ((double)g.n * ceil_div((int64_t)g.h * g.w, hp.bn) * hp.bn);
+  const double halo_s = halo_flops / 100e12;
+  const double tiles = (double)g.n * fp.tiles_i * fp.tiles_j;
+  const double fold_s = tiles * (4.1e-6 * (double)ceil_div(g.M, 16) + 8e-6) / 1024.0;
+  return fold_s < halo_s;
+}
+
 // Which realisation a pass uses for a given shape.  The same decision drives the workspace query and
 // the launch, so the two always agree.
 enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER, PATH_HALO, PATH_HALO_FILTER, PATH_HALO_BF16, PATH_FILTER_BF16, PATH_HALO_FILTER_BF16, PATH_FEW_COLS_FILTER, PATH_SMALL, PATH_SMALL_BWD, PATH_FOLD, PATH_FFT };
@@ -193,7 +205,8 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
       p.workspace_bytes = align256((size_t)g.M * g.K * sizeof(float));
     } else if (allow_direct && g.r - 1 - g.ph >= 0 && g.s - 1 - g.pw >= 0 &&
                conv_halo_plan(g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, &p.hp) &&
-               (algo == VCNN_ALGO_IMPLICIT || halo_bwd_data_pays(g, p.hp))) {
+               (algo == VCNN_ALGO_IMPLICIT ||
+                (halo_bwd_data_pays(g, p.hp) && !(automatic && bwd_data_fold_plan(g, &p.fold) && fold_beats_halo(g, p.hp, p.fold))))) {
       // correlation of dy (k channels) with the flipped kernels; the flipped matrix lives in the workspace
       p.path = PATH_HALO;
       p.workspace_bytes = align256((size_t)g.M * g.K * sizeof(float));

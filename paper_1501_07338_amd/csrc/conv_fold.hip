@@ -105,8 +105,12 @@ __global__ __launch_bounds__(kThreads, 4) void bwd_data_fold_kernel(FoldArgs a) 
   sb.init(tid);
   // A(i, k) = w[k][i] (contiguous along i), B(k, j) = dy[n][k][j] (contiguous along j); slots outside the matrix
   // read a valid address and are zeroed when the slab is written to LDS
-  const bool a_ok = i0 + sa.c < a.K;  // A_VEC: K is a multiple of 4, so a group of four rows is in or out as a whole
-  const int a_i = a_ok ? i0 + sa.c : 0;
+  // A_VEC: four rows per 16-byte load at dword alignment (float) or 8-byte load (bf16: K a multiple of 4).  The
+  // matrix's last group may hold fewer than four rows: the load is moved back to the last four (K >= 4) and the
+  // wanted ones are shifted down, zeros behind them.
+  const bool a_ok = i0 + sa.c < a.K;
+  const int a_i = a_ok ? (A_VEC ? min(i0 + sa.c, a.K - 4) : i0 + sa.c) : 0;
+  const int a_d = a_ok ? i0 + sa.c - a_i : 0;
   const bool b_ok = j0 + sb.c < a.P;
   // B_VEC (float only): four pixels per 16-byte load at dword alignment; the sample's last group may end early - its
   // load is moved back to the last four pixels (P >= 4) and the wanted ones are shifted down, zeros behind them
@@ -118,9 +122,17 @@ __global__ __launch_bounds__(kThreads, 4) void bwd_data_fold_kernel(FoldArgs a) 
       const int k = k0 + sa.line(e);
       sa.ok[e] = a_ok && k < a.m;
       const T* src = gA + (int64_t)min(k, a.m - 1) * a.K + a_i;
-      if (A_VEC) {
-        const float4 t = ld4(src);
+      if constexpr (A_VEC) {
+        float4 t;
+        if constexpr (std::is_same<T, float>::value) t = ld4_dword_aligned(src);
+        else t = ld4(src);
         sa.v[e][0] = t.x, sa.v[e][1] = t.y, sa.v[e][2] = t.z, sa.v[e][3] = t.w;
+        if (a_d > 0) {
+          sa.v[e][0] = a_d == 1 ? t.y : (a_d == 2 ? t.z : t.w);
+          sa.v[e][1] = a_d == 1 ? t.z : (a_d == 2 ? t.w : 0.f);
+          sa.v[e][2] = a_d == 1 ? t.w : 0.f;
+          sa.v[e][3] = 0.f;
+        }
       } else {
         sa.v[e][0] = ld(src);
       }
@@ -287,7 +299,7 @@ __global__ __launch_bounds__(kThreads) void fold_gather_kernel(FoldArgs a, float
 }
 
 bool bwd_data_fold_plan(const ConvGeom& g, FoldPlan* p) {
-  if (g.M < 64) return false;  // short contractions leave the fold, not the product, as the bulk of the work
+  if (g.M < 32) return false;  // short contractions leave the fold, not the product, as the bulk of the work
   if (g.P >= (1 << 23)) return false;  // pixel indices stay exact in float (div_small)
   const int RS = g.r * g.s;
   const int tiles_i = (int)ceil_div(g.K, kFoldBM), tiles_j = (int)ceil_div(g.P, kFoldBN);
@@ -305,9 +317,9 @@ bool bwd_data_fold_plan(const ConvGeom& g, FoldPlan* p) {
   }
   if (rows * wreg > (1 << 20)) return false;
   const int rsz = (int)(rows * wreg);
-  if ((size_t)rsz * kCopies * sizeof(float) > 40 * 1024) return false;
+  if ((size_t)rsz * kCopies * sizeof(float) > 60 * 1024) return false;
   // the regions must stay a small fraction of the patch-matrix gradient they replace
-  if ((int64_t)rsz * 8 > (int64_t)kFoldBM * kFoldBN) return false;
+  if ((int64_t)rsz * 4 > (int64_t)kFoldBM * kFoldBN) return false;
   p->tiles_i = tiles_i, p->tiles_j = tiles_j, p->rsz = rsz, p->wreg = wreg;
   p->partial_bytes = (size_t)g.n * tiles_i * tiles_j * rsz * sizeof(float);
   const size_t slabs = 2 * (size_t)(LdsTile<kFoldBM, kFoldBK, false>::SIZE + LdsTile<kFoldBN, kFoldBK, false>::SIZE) * sizeof(float);
@@ -324,7 +336,7 @@ vcnn_status launch_bwd_data_fold(const FoldPlan& p, int dtype, const ConvGeom& g
   a.tiles_i = p.tiles_i, a.tiles_j = p.tiles_j, a.rsz = p.rsz, a.wreg = p.wreg;
   const dim3 grid((unsigned)((int64_t)g.n * p.tiles_i * p.tiles_j)), block(kThreads);
   const bool bf = dtype == VCNN_BF16;
-  const bool vec = g.K % 4 == 0 && (bf ? group_aligned<bf16>(w) : group_aligned<float>(w));
+  const bool vec = bf ? g.K % 4 == 0 && group_aligned<bf16>(w) : g.K >= 4 && (reinterpret_cast<uintptr_t>(w) & 3) == 0;
   // Rows i and i + 32 of one channel are taps (r1, s1), (r2, s2) with (r2 - r1) * s + (s2 - s1) = 32; their entries
   // for pixels p, p' land on one input pixel iff p' - p = (r2 - r1) * ow + (s2 - s1).  A wave's pixels span 64
   // consecutive ones, so beyond that distance the two rows' adds of one step cannot meet.
@@ -333,7 +345,11 @@ vcnn_status launch_bwd_data_fold(const FoldPlan& p, int dtype, const ConvGeom& g
     const int ds = 32 - dr * g.s;
     if (ds > -g.s && ds < g.s && dr < g.r && std::abs(dr * g.ow + ds) < 64) mi_indep = false;
   }
-  auto go = [&](auto kernel) { hipLaunchKernelGGL(kernel, grid, block, p.lds_bytes, st, a); };
+  auto go = [&](auto kernel) {
+    if (p.lds_bytes > 48 * 1024)  // opt in to more than the default dynamic LDS limit (idempotent, host-side only)
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
+    hipLaunchKernelGGL(kernel, grid, block, p.lds_bytes, st, a);
+  };
   const bool bvec = !bf && g.P >= 4 && (reinterpret_cast<uintptr_t>(dy) & 3) == 0;
   if (bf) {
     if (vec && mi_indep) go(bwd_data_fold_kernel<true, false, true, bf16>);

@@ -407,7 +407,10 @@ static int halo_bn(int m, int64_t P, int n) {
   for (int bn = widest; bn >= 64; bn /= 2) {
     if (m <= 32 && bn < 128) break;  // 32-row tiles keep their four waves side by side
     const int64_t tiles = row_tiles * n * ceil_div(P, bn);
-    const double handicap = tiles >= 512 ? (bn == widest ? 1.0 : (2 * bn == widest ? 1.1 : 1.25)) : 1.0;
+    // the handicap applies once the next wider tile already fills the chip (512 resident blocks): narrowing a launch
+    // that leaves compute units idle, or with one block each, costs nothing
+    const int64_t wider_tiles = bn == widest ? tiles : row_tiles * n * ceil_div(P, 2 * bn);
+    const double handicap = wider_tiles >= 512 ? (bn == widest ? 1.0 : (2 * bn == widest ? 1.1 : 1.25)) : 1.0;
     const double cost = (double)ceil_div(P, bn) * bn * handicap;
     if (best == 0 || cost < best_cost - 1e-9 || (cost < best_cost + 1e-9 && tiles <= 1024)) best = bn, best_cost = cost;
   }
