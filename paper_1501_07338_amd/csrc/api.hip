@@ -102,7 +102,7 @@ static bool fold_beats_halo(const ConvGeom& g, const HaloPlan& hp, const FoldPla
 
 // Which realisation a pass uses for a given shape.  The same decision drives the workspace query and
 // the launch, so the two always agree.
-enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER, PATH_HALO, PATH_HALO_FILTER, PATH_HALO_BF16, PATH_FILTER_BF16, PATH_HALO_FILTER_BF16, PATH_FEW_COLS_FILTER, PATH_SMALL, PATH_SMALL_BWD, PATH_FOLD, PATH_FFT };
+enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER, PATH_HALO, PATH_HALO_FILTER, PATH_HALO_BF16, PATH_FILTER_BF16, PATH_HALO_FILTER_BF16, PATH_FEW_COLS_FILTER, PATH_SMALL, PATH_SMALL_BWD, PATH_FOLD, PATH_FFT, PATH_TAPS };
 struct Plan {
   Path path;
   DirectGeom dg;
@@ -163,7 +163,10 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
     return p;
   }
   if (pass == VCNN_PASS_FWD) {
-    if (allow_direct && g.k <= 4 && direct_fwd_geom(g, &p.dg) && direct_few_out_plan(&p.dg, &p.split, &p.partial_bytes)) {
+    if (automatic && conv_taps_applies(g)) {
+      p.path = PATH_TAPS;  // one map over many channels: the taps as rows of a 1 x 1 product, then a gather
+      p.workspace_bytes = align256(conv_taps_fwd_bytes(g));
+    } else if (allow_direct && g.k <= 4 && direct_fwd_geom(g, &p.dg) && direct_few_out_plan(&p.dg, &p.split, &p.partial_bytes)) {
       p.path = PATH_FEW_OUT;
       p.workspace_bytes = align256(p.partial_bytes);
     } else if (is_pointwise(g)) {
@@ -218,7 +221,10 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
       p.workspace_bytes = col_bytes(g);
     }
   } else {
-    if (allow_direct && g.k <= 4 && direct_filter_grad_plan(g, &p.dg, &p.split, &p.partial_bytes)) {
+    if (automatic && conv_taps_applies(g)) {
+      p.path = PATH_TAPS;  // phi_c of the one-map gradient times the input, on the matrix cores
+      p.workspace_bytes = conv_taps_filter_bytes(g, dtype);
+    } else if (allow_direct && g.k <= 4 && direct_filter_grad_plan(g, &p.dg, &p.split, &p.partial_bytes)) {
       p.path = PATH_DIRECT_FILTER;
       p.workspace_bytes = align256(p.partial_bytes);
     } else if (automatic && g.k > 4 && filter_grad_few_cols_plan(g, &p.fcp)) {
@@ -330,6 +336,7 @@ static vcnn_status conv_fwd_linear(const vcnn_conv_desc* d, const ConvGeom& g, c
   hipStream_t st = (hipStream_t)stream;
   const int relu = d->act == VCNN_ACT_RELU;
   const int dt = d->dtype;
+  if (plan.path == PATH_TAPS) return launch_conv_taps_fwd(g, dt, x, w, bias, y, relu, (float*)workspace, st);
   if (plan.path == PATH_FEW_OUT)
     return launch_direct_few_out(plan.dg, dt, plan.split, x, w, bias, y, (float*)workspace, relu, st);
   if (plan.path == PATH_FEW_IN) return launch_direct_few_in(plan.dg, dt, plan.split, x, w, bias, y, relu, st);
@@ -372,7 +379,9 @@ vcnn_status vcnn_conv_bwd_filter(const vcnn_conv_desc* d, const void* x, const v
   hipStream_t st = (hipStream_t)stream;
   const int dt = d->dtype;
   float* bias_partial = (float*)((char*)workspace + plan.bias_offset);
-  if (plan.path == PATH_DIRECT_FILTER) {
+  if (plan.path == PATH_TAPS) {
+    if (vcnn_status s = launch_conv_taps_filter(g, dt, x, dy, dw, workspace, st)) return s;
+  } else if (plan.path == PATH_DIRECT_FILTER) {
     if (vcnn_status s = launch_direct_filter_grad(plan.dg, dt, plan.split, x, dy, dw, (float*)workspace, st)) return s;
   } else if (plan.path == PATH_FEW_COLS_FILTER) {
     if (vcnn_status s = launch_filter_grad_few_cols(plan.fcp, dt, g, x, dy, dw, dbias, (float*)workspace, st)) return s;

@@ -198,6 +198,16 @@ bool bwd_data_fold_plan(const ConvGeom& g, FoldPlan* p);
 vcnn_status launch_bwd_data_fold(const FoldPlan& p, int dtype, const ConvGeom& g, const void* w, const void* dy, void* dx,
                                  float* partial, hipStream_t st);
 
+// ---- conv_taps.hip --------------------------------------------------------------------------------------
+// One-map layers over many channels with the kernel's taps as the rows of the product (see the file header).
+bool conv_taps_applies(const ConvGeom& g);
+size_t conv_taps_fwd_bytes(const ConvGeom& g);             // workspace of the forward pass (Z)
+size_t conv_taps_filter_bytes(const ConvGeom& g, int dtype);  // workspace of the kernel gradient
+vcnn_status launch_conv_taps_fwd(const ConvGeom& g, int dtype, const void* x, const void* w, const float* bias, void* y,
+                                 int relu, float* z, hipStream_t st);
+vcnn_status launch_conv_taps_filter(const ConvGeom& g, int dtype, const void* x, const void* dy, float* dw, void* workspace,
+                                    hipStream_t st);
+
 // ---- fft_conv.hip -------------------------------------------------------------------------------------
 // Forward pass of layers with r x 1 or 1 x s kernels through the Fourier domain (comparison route).
 // workspace: xf_bytes + wf_bytes + yf_bytes.

@@ -483,6 +483,8 @@ vcnn_status launch_gemm_f32(const GemmArgs& a, hipStream_t st) {
     launch_cfg<64, 64, 32, 32, 32>(a, a_kc, b_kc, av, bv, st);
   else if (a.M <= 32)
     launch_cfg<32, 256, 32, 32, 64>(a, a_kc, b_kc, av, bv, st);
+  else if (a.M <= 64 && ceil_div(a.N, 256) < 256)  // too few 256-wide tiles to occupy the compute units: halve them
+    launch_cfg<64, 128, 32, 32, 64>(a, a_kc, b_kc, av, bv, st);
   else if (a.M <= 64)
     launch_cfg<64, 256, 32, 64, 64>(a, a_kc, b_kc, av, bv, st);
   else

@@ -45,6 +45,9 @@ CONV_SHAPES = [
     (3, 20, 7, 7, 40, 1, 1, 0, 0),      # 1 x 1 with an odd pixel count: groups of four run over the end of a sample
     (5, 130, 5, 5, 70, 1, 1, 0, 0),     # ... two column tiles of the kernel matrix, three row tiles, 125 columns in all
     (2, 33, 3, 1, 64, 1, 1, 0, 0),      # ... fewer pixels per sample than one group of four
+    (2, 64, 12, 12, 1, 4, 4, 0, 0),     # one map over 64 and more channels: the taps as rows of a matrix-core product
+    (3, 70, 9, 11, 1, 5, 5, 2, 2),      # ... padded ('same'), odd pixel counts
+    (2, 130, 14, 9, 1, 8, 3, 0, 1),     # ... rectangular kernel, padded along one axis only
 ]
 
 
@@ -185,6 +188,9 @@ FOLD_SHAPES = [
     (1, 7, 9, 9, 64, 3, 3, 1, 1),        # K = 63: one ragged row tile over all channels, scalar kernel-matrix loads
     (2, 1, 40, 33, 96, 11, 12, 3, 0),    # one channel, 132 taps: the second row tile holds 4 rows
     (4, 38, 20, 20, 72, 16, 16, 0, 0),   # the shape family of the deconvolution network's third layer (5 x 5 outputs)
+    (1, 3, 20, 20, 256, 8, 8, 0, 0),     # 128 maps and more: the bf16 variant contracts on the bf16 matrix cores
+    (2, 5, 14, 18, 136, 16, 16, 8, 8),   # ... padded, contraction tail (136 = 17 words of 8)
+    (3, 2, 40, 40, 200, 16, 16, 0, 0),   # ... 625 pixels per sample: five column tiles of 128, the last one short
 ]
 
 
