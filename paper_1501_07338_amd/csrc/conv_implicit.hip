@@ -752,7 +752,21 @@ bool conv_halo_filter_plan(const ConvGeom& g, HaloFilterPlan* p) {
   p->runs_per_img = (int)ceil_div(g.P, best);
   const int64_t tiles = ceil_div(g.M, p->bm) * ceil_div(g.K, p->bnk);
   const int64_t total_runs = (int64_t)g.n * p->runs_per_img;
+  // contraction slices: at least enough for about 1024 blocks; among up to twice as many, the count whose blocks
+  // fill whole rounds of the resident set best (long blocks: a last round that is half empty costs half a round)
   int64_t want = ceil_div(1024, tiles);
+  if (want <= 8) {  // (many slices mean short blocks, whose rounds do not matter - and more partial sums to add)
+    const int64_t slots = 256 * (p->bm >= 64 ? 3 : 2);
+    double best_fill = 0;
+    int64_t best_want = want;
+    for (int64_t w = want; w <= 2 * want; ++w) {
+      const int64_t per = ceil_div(total_runs, std::min<int64_t>(w, total_runs));
+      const int64_t blocks = tiles * ceil_div(total_runs, per);
+      const double fill = (double)blocks / (double)(ceil_div(blocks, slots) * slots);
+      if (fill > best_fill + 0.02) best_fill = fill, best_want = w;
+    }
+    want = best_want;
+  }
   if (want > total_runs) want = total_runs;
   if (want < 1) want = 1;
   p->runs_per_split = (int)ceil_div(total_runs, want);
