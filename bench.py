@@ -350,6 +350,10 @@ def aids(stream):
         flop = benchaid.mfma(bf16, blocks, iters, sink)
         ms = sorted(time_calls(lambda: benchaid.mfma(bf16, blocks, iters, sink), 3, stream) for _ in range(3))[1]
         out["mfma_" + name] = {"sustained_tflops": flop / (ms * 1e9), "data_sheet_tflops": peak, "ms": ms}
+        # the same loop with operands whose bits change from instruction to instruction, as a layer's do: the
+        # clock the chip holds depends on the power the matrix cores draw
+        ms = sorted(time_calls(lambda: benchaid.mfma(bf16, blocks, iters, sink, toggle=True), 3, stream) for _ in range(3))[1]
+        out["mfma_" + name]["sustained_tflops_changing_operands"] = flop / (ms * 1e9)
     src = torch.empty(1 << 28, device="cuda").normal_()
     dst = torch.empty_like(src)
     mark("copy of 1 GiB")
@@ -508,6 +512,8 @@ def main():
         out["hbm_kernels"] = [[h["kernel"], h["shape"], h["gbs"], h["frac_hbm_peak"]] for h in detail["hbm_kernels"]]
         out["yardsticks"] = {"mfma_f32_sustained_tflops": detail["yardsticks"]["mfma_f32"]["sustained_tflops"],
                              "mfma_bf16_sustained_tflops": detail["yardsticks"]["mfma_bf16"]["sustained_tflops"],
+                             "mfma_f32_changing_operands_tflops": detail["yardsticks"]["mfma_f32"]["sustained_tflops_changing_operands"],
+                             "mfma_bf16_changing_operands_tflops": detail["yardsticks"]["mfma_bf16"]["sustained_tflops_changing_operands"],
                              "copy_1GiB_gbs": detail["yardsticks"]["copy_1GiB"]["gbs"]}
         out["fourier_comparison"] = [[r["layer"], r["unroll_ms"], r["fourier_ms"]] for r in detail["fourier_comparison"]]
     if "batch_sweep" in detail:  # [workload, batch, training images/s, forward-only images/s]

@@ -17,7 +17,7 @@ def lib() -> ctypes.CDLL:
             raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -m paper_1501_07338_amd.build)")
         import torch  # noqa: F401  (one HIP runtime per process: torch's)
         h = ctypes.CDLL(str(LIB_PATH))
-        h.benchaid_mfma.restype, h.benchaid_mfma.argtypes = c_int, [c_int, c_int, c_int, c_void_p, c_void_p, c_void_p]
+        h.benchaid_mfma.restype, h.benchaid_mfma.argtypes = c_int, [c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p]
         h.benchaid_copy.restype, h.benchaid_copy.argtypes = c_int, [c_void_p, c_void_p, c_size_t, c_void_p]
         h.benchaid_marker.restype, h.benchaid_marker.argtypes = c_int, [c_int, c_void_p]
         _lib = h
@@ -31,10 +31,11 @@ def _stream(stream):
     return getattr(stream, "cuda_stream", stream)
 
 
-def mfma(bf16: bool, blocks: int, iters: int, sink, stream=None) -> float:
-    """Launches the register-only matrix-core loop; returns the flop count of the launch."""
+def mfma(bf16: bool, blocks: int, iters: int, sink, stream=None, toggle: bool = False) -> float:
+    """Launches the register-only matrix-core loop (toggle: operands that change from instruction to instruction);
+    returns the flop count of the launch."""
     flop = c_double()
-    err = lib().benchaid_mfma(int(bf16), blocks, iters, sink.data_ptr(), byref(flop), _stream(stream))
+    err = lib().benchaid_mfma(int(bf16), int(toggle), blocks, iters, sink.data_ptr(), byref(flop), _stream(stream))
     if err:
         raise RuntimeError(f"benchaid_mfma: HIP error {err}")
     return flop.value

@@ -16,6 +16,61 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 static constexpr int kThreads = 256;
 static constexpr int kChains = 4;  // independent accumulators per wave
 
+// Pseudo-random bits (a multiplicative hash): operands whose bits differ from lane to lane and from step to step.
+__device__ __forceinline__ uint32_t mix(uint32_t v) {
+  v ^= v >> 16, v *= 0x7feb352du, v ^= v >> 15, v *= 0x846ca68bu, v ^= v >> 16;
+  return v;
+}
+// a float in [1, 2) (or its negative) with random mantissa bits
+__device__ __forceinline__ float unit_float(uint32_t bits) {
+  return __uint_as_float(0x3f800000u | (bits & 0x807fffffu));
+}
+
+// The same loop with operands that CHANGE from one instruction to the next (eight register operand pairs with
+// random mantissas, taken in turn): the power the matrix cores draw, and with it the clock the chip holds,
+// depends on how many operand bits toggle, and a layer's operands do toggle.
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void benchaid_mfma_toggle_kernel(float* __restrict__ sink, int iters) {
+  f32x16 acc[kChains];
+#pragma unroll
+  for (int c = 0; c < kChains; ++c)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) acc[c][q] = 0.f;
+  const uint32_t seed = mix(blockIdx.x * kThreads + threadIdx.x + 1u);
+  if (BF16) {
+    bf16x8 a[8], b[8];
+#pragma unroll
+    for (int v = 0; v < 8; ++v)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        a[v][e] = (__bf16)unit_float(mix(seed + 16u * v + e));
+        b[v][e] = (__bf16)(unit_float(mix(seed + 16u * v + e + 8u)) * 0.001f);
+      }
+    for (int i = 0; i < iters; i += 8)
+#pragma unroll
+      for (int v = 0; v < 8; ++v)
+#pragma unroll
+        for (int c = 0; c < kChains; ++c)
+          acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[(v + c) & 7], b[(v + 3 * c) & 7], acc[c], 0, 0, 0);
+  } else {
+    float a[8], b[8];
+#pragma unroll
+    for (int v = 0; v < 8; ++v) a[v] = unit_float(mix(seed + 2u * v)), b[v] = unit_float(mix(seed + 2u * v + 1u)) * 0.001f;
+    for (int i = 0; i < iters; i += 8)
+#pragma unroll
+      for (int v = 0; v < 8; ++v)
+#pragma unroll
+        for (int c = 0; c < kChains; ++c)
+          acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[(v + c) & 7], b[(v + 3 * c) & 7], acc[c], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < kChains; ++c)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) s += acc[c][q];
+  sink[(size_t)blockIdx.x * kThreads + threadIdx.x] = s;
+}
+
 template <bool BF16>
 __global__ __launch_bounds__(kThreads) void benchaid_mfma_kernel(float* __restrict__ sink, int iters) {
   f32x16 acc[kChains];
@@ -67,10 +122,15 @@ int benchaid_marker(int id, void* stream) {
 // Launches `blocks` blocks of 4 waves that each issue iters x 4 independent matrix-core instructions (bf16 == 0:
 // v_mfma_f32_32x32x2_f32, else v_mfma_f32_32x32x16_bf16); one float per thread is written to sink (DEVICE,
 // blocks*256 floats).  *flop (HOST, nullable) receives the flop count of the launch.  Returns 0 or a hipError_t.
-int benchaid_mfma(int bf16, int blocks, int iters, float* sink, double* flop, void* stream) {
-  if (blocks <= 0 || iters <= 0 || !sink) return (int)hipErrorInvalidValue;
+// toggle != 0: the operands change from instruction to instruction (iters must then be a multiple of 8).
+int benchaid_mfma(int bf16, int toggle, int blocks, int iters, float* sink, double* flop, void* stream) {
+  if (blocks <= 0 || iters <= 0 || !sink || (toggle && iters % 8)) return (int)hipErrorInvalidValue;
   if (flop) *flop = (double)blocks * 4 * iters * kChains * (bf16 ? 32768.0 : 4096.0);
-  if (bf16)
+  if (toggle && bf16)
+    hipLaunchKernelGGL(benchaid_mfma_toggle_kernel<true>, dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream, sink, iters);
+  else if (toggle)
+    hipLaunchKernelGGL(benchaid_mfma_toggle_kernel<false>, dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream, sink, iters);
+  else if (bf16)
     hipLaunchKernelGGL(benchaid_mfma_kernel<true>, dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream, sink, iters);
   else
     hipLaunchKernelGGL(benchaid_mfma_kernel<false>, dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream, sink, iters);

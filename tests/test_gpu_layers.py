@@ -667,6 +667,12 @@ def test_benchaid_mfma_counts_its_flops_and_runs(bf16, per_instr):
         rows = [8 * (q // 4) + q % 4 for q in range(16)]
         want = 4 * iters * sum(float(fa(r)) * float(fb(0)) + float(fa(r + 32)) * float(fb(32)) for r in rows)
         assert abs(float(to_np(sink)[0]) - want) <= 1e-4 * want
+    # the variant with operands that change from instruction to instruction: same count, finite sums
+    sink.fill_(float("nan"))
+    assert benchaid.mfma(bf16, blocks, 16, sink, toggle=True) == blocks * 4 * 16 * 4 * per_instr
+    assert np.all(np.isfinite(to_np(sink)))
+    with pytest.raises(RuntimeError):
+        benchaid.mfma(bf16, blocks, 10, sink, toggle=True)  # not a multiple of eight
 
 
 def test_benchaid_copy_copies():
