@@ -102,7 +102,7 @@ static bool fold_beats_halo(const ConvGeom& g, const HaloPlan& hp, const FoldPla
 
 // Which realisation a pass uses for a given shape.  The same decision drives the workspace query and
 // the launch, so the two always agree.
-enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER, PATH_HALO, PATH_HALO_FILTER, PATH_HALO_BF16, PATH_FILTER_BF16, PATH_HALO_FILTER_BF16, PATH_FEW_COLS_FILTER, PATH_SMALL, PATH_SMALL_BWD, PATH_FOLD, PATH_FFT, PATH_TAPS };
+enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER, PATH_HALO, PATH_HALO_FILTER, PATH_HALO_BF16, PATH_FILTER_BF16, PATH_HALO_FILTER_BF16, PATH_FEW_COLS_FILTER, PATH_SMALL, PATH_SMALL_BWD, PATH_FOLD, PATH_FFT, PATH_TAPS, PATH_POINTWISE_BF16 };
 struct Plan {
   Path path;
   DirectGeom dg;
@@ -114,6 +114,8 @@ struct Plan {
   FewColsPlan fcp;
   FoldPlan fold;
   FftPlan fft;
+  PointwiseBf16Plan pwb;
+  PointwiseFilterBf16Plan pwf;
   int split;        // channel slices (few-out), output-map group size (few-in) or batch slices (filter gradient)
   size_t partial_bytes;
   size_t workspace_bytes;
@@ -134,7 +136,26 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
   }
   // bf16 variant, default route: the bf16 matrix-core kernels wherever the layer has enough maps / channels
   const bool bf16_mfma = dtype == VCNN_BF16 && automatic;
-  // (1x1 layers included: with asynchronous staging they are a plain bf16 product through the same kernel)
+  // unpadded 1 x 1 layers: three plain bf16 products on the tensors as they are stored
+  if (bf16_mfma && is_pointwise(g)) {
+    if (pass == VCNN_PASS_FWD && pointwise_bf16_plan(g.n, g.k, g.c, g.P, &p.pwb)) {
+      p.path = PATH_POINTWISE_BF16;
+      return p;
+    }
+    if (pass == VCNN_PASS_BWD_DATA && pointwise_bf16_plan(g.n, g.c, g.k, g.P, &p.pwb)) {
+      p.path = PATH_POINTWISE_BF16;
+      p.workspace_bytes = align256((size_t)g.k * g.c * 2);  // the transposed kernel matrix
+      return p;
+    }
+    if (pass == VCNN_PASS_BWD_FILTER && pointwise_filter_bf16_plan(g, &p.pwf)) {
+      p.path = PATH_POINTWISE_BF16;
+      p.workspace_bytes = align256(p.pwf.partial_bytes);
+      p.bias_offset = p.workspace_bytes;
+      p.workspace_bytes += align256(bias_grad_partial_bytes(g));
+      return p;
+    }
+  }
+  // (other 1x1 layers included: they are a plain bf16 product through the same kernel)
   if (bf16_mfma && pass == VCNN_PASS_FWD && (g.k > 4 || g.c >= 64) &&
       conv_halo_bf16_plan(g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, &p.hb)) {
     p.path = PATH_HALO_BF16;
@@ -349,6 +370,8 @@ static vcnn_status conv_fwd_linear(const vcnn_conv_desc* d, const ConvGeom& g, c
                                  bias, y, relu, workspace, st);
   }
   if (plan.path == PATH_FFT) return launch_conv_fft(plan.fft, dt, g, x, w, bias, y, relu, workspace, st);
+  if (plan.path == PATH_POINTWISE_BF16)
+    return launch_pointwise_bf16(plan.pwb, g.n, g.k, g.c, (int)g.P, w, x, bias, y, relu, st);
 
   GemmArgs a{};
   a.A = w, a.C = y, a.bias = bias;
@@ -386,6 +409,8 @@ vcnn_status vcnn_conv_bwd_filter(const vcnn_conv_desc* d, const void* x, const v
   } else if (plan.path == PATH_FEW_COLS_FILTER) {
     if (vcnn_status s = launch_filter_grad_few_cols(plan.fcp, dt, g, x, dy, dw, dbias, (float*)workspace, st)) return s;
     if (plan.fcp.bias_column) return VCNN_OK;  // the bias gradient came out of the same product
+  } else if (plan.path == PATH_POINTWISE_BF16) {
+    if (vcnn_status s = launch_pointwise_filter_bf16(plan.pwf, g, x, dy, dw, (float*)workspace, st)) return s;
   } else if (plan.path == PATH_HALO_FILTER_BF16) {
     if (vcnn_status s = launch_filter_grad_bf16(plan.hfb, g, x, dy, dw, workspace, st)) return s;
   } else if (plan.path == PATH_FILTER_BF16) {
@@ -420,6 +445,11 @@ vcnn_status vcnn_conv_bwd_data(const vcnn_conv_desc* d, const void* w, const voi
     // correlation of dy (k channels) with the flipped kernels into c maps: the re-ordering pass flips and transposes
     return launch_conv_halo_bf16(plan.hb, g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, dy, w,
                                  (int64_t)g.r * g.s, g.K, 1, nullptr, dx, 0, workspace, st);
+  }
+  if (plan.path == PATH_POINTWISE_BF16) {
+    // dx[n][c][p] = sum_m w[m][c] * dy[n][m][p]: the forward product on the transposed kernel matrix
+    if (vcnn_status s = launch_flip_transpose(dt, w, workspace, g.k, g.c, 1, st)) return s;
+    return launch_pointwise_bf16(plan.pwb, g.n, g.c, g.k, (int)g.P, workspace, dy, nullptr, dx, 0, st);
   }
   if (plan.path == PATH_SMALL_BWD)
     return launch_conv_small_bwd(g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, dy, w, dx, st);

@@ -163,6 +163,21 @@ struct BwdFilterBf16Plan {
   int64_t chunk;
   size_t dyt_bytes, col_bytes, partial_bytes;
 };
+// Unpadded 1 x 1 layers of the bf16 variant as plain bf16 products on the NCHW tensors (bf16_pointwise.hip).
+struct PointwiseBf16Plan {
+  int bm, tiles_m, tiles_p;
+};
+struct PointwiseFilterBf16Plan {
+  int bm, slabs_per_img, units_per_split, splits;
+  size_t partial_bytes;
+};
+// Y[n][rows][P] = act(bias + A[rows][depth] * X[n][depth][P]); A contraction-contiguous and 16-byte aligned
+bool pointwise_bf16_plan(int64_t n, int64_t rows, int64_t depth, int64_t P, PointwiseBf16Plan* p);
+vcnn_status launch_pointwise_bf16(const PointwiseBf16Plan& p, int n, int rows, int depth, int P, const void* A, const void* X,
+                                  const float* bias, void* Y, int relu, hipStream_t st);
+bool pointwise_filter_bf16_plan(const ConvGeom& g, PointwiseFilterBf16Plan* p);
+vcnn_status launch_pointwise_filter_bf16(const PointwiseFilterBf16Plan& p, const ConvGeom& g, const void* x, const void* dy,
+                                         float* dw, float* partial, hipStream_t st);
 bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int pw, HaloBf16Plan* p);
 // y = act(bias + W (*) x) with W(o, i, q) = wgt[o*w_so + i*w_si + (flip ? r*s-1-q : q)]; the workspace holds
 // x8_bytes + wf_bytes

@@ -102,6 +102,68 @@ def _check_bf16_layer(n, c, h, w, k, r, s, ph, pw, seed):
     assert_close(f32_of(dx), O.conv_bwd_data(wt, dy, (h, w), pad=(ph, pw)), TOL_BF16, "bf16 dx")
 
 
+POINTWISE_SHAPES = [
+    (3, 64, 7, 7, 96),      # odd plane size (rows start on odd elements), one ragged 128-row tile
+    (2, 72, 13, 11, 40),    # contraction not a multiple of the 64-deep slab, 64-row tile
+    (5, 136, 9, 15, 200),   # two row tiles, two pixel tiles, three slabs
+    (2, 32, 20, 20, 32),    # even plane size, the smallest row count
+    (3, 40, 5, 3, 64),      # 15 pixels: a last pixel group of three
+    (4, 48, 2, 3, 56),      # 6 pixels: below one group of eight (the kernel gradient falls back)
+    (2, 512, 17, 9, 512),   # the shape class of the deconvolution network's 1 x 1 layer: whole slabs, a second pixel
+                            # tile that overlaps the first
+    (3, 128, 13, 11, 192),  # odd plane of 143 pixels, two and three whole slabs
+    (2, 64, 16, 9, 64),     # even plane of 144 pixels, a single slab
+    (1, 64, 16, 16, 320),   # exactly two pixel tiles, three row tiles
+]
+
+
+# (the element offset is only used where all three passes take the products of this test: their loads are written
+# for rows at any 2-byte boundary; other realisations are given tensors as an allocator returns them)
+@pytest.mark.parametrize("shape,offset", [(sh, off) for sh in POINTWISE_SHAPES for off in (0, 1) if off == 0 or sh[2] * sh[3] >= 8])
+def test_conv_bf16_pointwise(shape, offset):
+    """Unpadded 1 x 1 layers of the bf16 variant: the three plain bf16 products on the tensors as stored.  offset = 1
+    places x, dy, y and dx one element into their buffers, so that every row parity occurs also for even planes."""
+    n, c, h, w, k = shape
+
+    def placed(a):
+        r = wl.bf16_round(a)
+        buf = torch.zeros(r.size + 8, dtype=torch.bfloat16, device=DEV)
+        view = buf[offset:offset + r.size].view(r.shape)
+        view.copy_(torch.from_numpy(r).to(DEV))
+        return r, view
+
+    def blank(shape_):
+        buf = torch.full((int(np.prod(shape_)) + 8,), float("nan"), dtype=torch.bfloat16, device=DEV)
+        return buf, buf[offset:offset + int(np.prod(shape_))].view(shape_)
+
+    x, xd = placed(wl.random_tensor(2500, (n, c, h, w)))
+    wt, wd = b16(wl.random_tensor(2501, (k, c, 1, 1), scale=(2.0 / c) ** 0.5))
+    b = wl.random_tensor(2502, (k,), scale=0.1)
+    dy, dyd = placed(wl.random_tensor(2503, (n, k, h, w)))
+    for act, relu in ((vcnn.ACT_NONE, False), (vcnn.ACT_RELU, True)):
+        d = vcnn.conv_desc(n, c, h, w, k, 1, 1, 0, 0, dtype=vcnn.BF16, act=act)
+        ws = torch.empty(max(256, *(vcnn.conv_workspace_bytes(d, p) for p in range(3))), dtype=torch.uint8, device=DEV)
+        ybuf, y = blank((n, k, h, w))
+        vcnn.conv_fwd(d, xd, wd, torch.from_numpy(b).to(DEV), y, ws)
+        assert_close(f32_of(y), O.conv_fwd(x, wt, b, pad=(0, 0), relu=relu), TOL_BF16, "bf16 1x1 conv_fwd")
+        # nothing is written outside the tensor
+        assert torch.isnan(ybuf[:offset]).all() and torch.isnan(ybuf[offset + y.numel():]).all()
+    dw = torch.full((k, c, 1, 1), float("nan"), device=DEV)
+    db = torch.full((k,), float("nan"), device=DEV)
+    vcnn.conv_bwd_filter(d, xd, dyd, dw, db, ws)
+    rdw, rdb = O.conv_bwd_filter(x, dy, (1, 1), pad=(0, 0))
+    assert_close(to_np(dw), rdw, TOL_F32, "bf16 1x1 dw (fp32 result)")
+    assert_close(to_np(db), rdb, TOL_F32, "bf16 1x1 db (fp32 result)")
+    dxbuf, dx = blank((n, c, h, w))
+    vcnn.conv_bwd_data(d, wd, dyd, dx, ws)
+    assert_close(f32_of(dx), O.conv_bwd_data(wt, dy, (h, w), pad=(0, 0)), TOL_BF16, "bf16 1x1 dx")
+    assert torch.isnan(dxbuf[:offset]).all() and torch.isnan(dxbuf[offset + dx.numel():]).all()
+    # run to run the kernel gradient's ordered partial sums give the same bits
+    dw2 = torch.empty_like(dw)
+    vcnn.conv_bwd_filter(d, xd, dyd, dw2, db, ws)
+    assert torch.equal(dw, dw2)
+
+
 @pytest.mark.parametrize("k", [40, 100, 200])           # waves of a block: all on the contraction, 2 x 2, all on the maps
 @pytest.mark.parametrize("hw", [(40, 64), (64, 80)])    # pixel tiles of 128 and of 160 win the tile choice
 def test_conv_bf16_wide_pixel_tiles(k, hw):
