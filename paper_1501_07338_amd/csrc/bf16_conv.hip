@@ -122,15 +122,15 @@ struct HaloBf16Args {
   int relu;
 };
 
-template <int WAVES_M, int WAVES_K, int TM, int TN, bool M16 = false>
+template <int WAVES_M, int WAVES_K, int TM, int TN, bool M16 = false, int WAVES_N = 1>
 __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Args a) {
-  static_assert(WAVES_M * WAVES_K * 64 == kThreads, "four waves per block");
+  static_assert(WAVES_M * WAVES_K * WAVES_N * 64 == kThreads, "four waves per block");
   static_assert(!M16 || WAVES_M == 1, "16-row tiles: every wave holds all rows");
   constexpr int TILE = M16 ? 16 : 32;     // rows and pixels of one accumulator tile
   constexpr int AQ = M16 ? 4 : 16;        // accumulator registers per tile
   constexpr int SPS = M16 ? 2 : 4;        // MFMA steps per slab of 8 (group, tap) pairs
   using Acc = typename std::conditional<M16, f32x4, f32x16>::type;
-  constexpr int BM = TILE * TM * WAVES_M, BN = TILE * TN;
+  constexpr int BM = TILE * TM * WAVES_M, WN = TILE * TN, BN = WN * WAVES_N;  // block rows, wave pixels, block pixels
   extern __shared__ uint4 smem16[];
   int* const tbl = reinterpret_cast<int*>(smem16);  // [uch], per slab of 8 pairs: [half][4]
   int* const nxt = tbl + a.uch;                     // [uch/8 + 4]: next slab with work, first such slab per wave
@@ -138,7 +138,8 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lcol = lane & (TILE - 1), half = lane / TILE;  // tile column / row of this lane, its pair of the step
-  const int wave_m = wave % WAVES_M, wave_k = wave / WAVES_M;
+  const int wave_m = wave % WAVES_M, wave_k = (wave / WAVES_M) % WAVES_K, wave_n = wave / (WAVES_M * WAVES_K);
+  const int pw0 = wave_n * WN;  // first pixel of this wave inside the block's tile
   const int tm = blockIdx.x % a.tiles_m;
   const int tj = blockIdx.x / a.tiles_m;
   const int n = tj / a.tiles_per_img;
@@ -166,7 +167,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
   int lane_base[TN];
 #pragma unroll
   for (int ni = 0; ni < TN; ++ni) {
-    const int p = min(p0 + ni * TILE + lcol, a.P - 1);
+    const int p = min(p0 + pw0 + ni * TILE + lcol, a.P - 1);
     const int oh = p / a.ow;
     lane_base[ni] = (oh - oh_first) * a.wp + (p - oh * a.ow);
   }
@@ -324,7 +325,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
 
 #pragma unroll
   for (int ni = 0; ni < TN; ++ni) {
-    const int p = p0 + ni * TILE + lcol;
+    const int p = p0 + pw0 + ni * TILE + lcol;
     if (p >= a.P) continue;
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi)
@@ -346,17 +347,20 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
 static constexpr int kTnChoices[] = {2, 4, 5};     // 32-pixel tiles per wave
 static constexpr int kTn16Choices[] = {4, 8, 10};  // 16-pixel tiles per wave (the same pixel counts)
 
-bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int pw, HaloBf16Plan* p) {
+// One arrangement of the four waves (waves_m along the maps, waves_n along the pixels, the rest along the contraction);
+// *cost_out is the estimated time in units of one 32-pixel wave tile.
+static bool plan_arrangement(int waves_m, int waves_n, int n, int c, int h, int w, int m, int r, int s, int ph, int pw,
+                             HaloBf16Plan* p, double* cost_out) {
   const int oh = h + 2 * ph - r + 1, ow = w + 2 * pw - s + 1;
   if (oh <= 0 || ow <= 0) return false;
   const int rs = r * s;
   const int cg = (c + 7) / 8;
   if ((int64_t)cg * h * w > 0x7fffffffLL) return false;  // 32-bit position offsets inside a sample
   p->m16 = m > 32 && m <= 48;  // three 16-row tiles instead of two 32-row ones
-  p->waves_m = m > 128 ? 4 : (m > 64 ? 2 : 1);
+  p->waves_m = waves_m, p->waves_n = waves_n;
   p->tm = p->m16 ? 3 : (m <= 32 ? 1 : 2);  // row tiles per wave
   const int tile = p->m16 ? 16 : 32, aq = p->m16 ? 4 : 16, sps = p->m16 ? 2 : 4;
-  const int waves_k = 4 / p->waves_m;
+  const int waves_k = 4 / (p->waves_m * p->waves_n);
   const int bm = tile * p->tm * p->waves_m;
   const int tiles_m = (int)ceil_div(m, bm);
   const int wp = w + 2 * pw;
@@ -366,7 +370,7 @@ bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph
   double best_cost = 0;
   for (int k = 0; k < 3; ++k) {
     const int tn = p->m16 ? kTn16Choices[k] : kTnChoices[k];
-    const int bn = tile * tn;
+    const int bn = tile * tn * p->waves_n;
     int rows = (bn + ow - 2) / ow + 1;
     if (rows > oh) rows = oh;
     const int nr = rows + r - 1;
@@ -382,7 +386,7 @@ bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph
     if (cgc == 0) continue;
     const int64_t tiles = (int64_t)tiles_m * n * ceil_div(P, bn);
     if (tiles > 0x7fffffffLL) continue;
-    const double wide = bn / 32.0;
+    const double wide = tile * tn / 32.0;
     const double cost = (double)ceil_div(tiles, 512) * wide * (1.0 + 0.5 / wide);  // wider tiles reuse A fragments better
     if (best_tn == 0 || cost < best_cost - 1e-9) best_tn = tn, best_cgc = cgc, best_nr = nr, best_cost = cost;
   }
@@ -404,13 +408,29 @@ bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph
   p->lds_bytes = std::max((size_t)p->uch * 4 + ((size_t)p->uch / 8 + 7) / 4 * 16 + 2 * (size_t)p->hpos * 16, red_bytes);
   p->x8_bytes = (((size_t)n * cg * h * w + 1) * 16 + 255) & ~(size_t)255;  // + the block of zeros
   p->wf_bytes = ((size_t)tiles_m * (bm / tile) * p->nchunks * (p->uch / 8 * sps) * 64 * 16 + 255) & ~(size_t)255;
+  *cost_out = best_cost;
   return true;
 }
 
-template <int WAVES_M, int WAVES_K, int TM, int TN, bool M16 = false>
+bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int pw, HaloBf16Plan* p) {
+  double cost = 0;
+  if (m <= 128) return plan_arrangement(m > 64 ? 2 : 1, 1, n, c, h, w, m, r, s, ph, pw, p, &cost);
+  // many maps: the four waves take different maps of the same pixels, or - when the image is large enough for
+  // four times as many pixels per block - different pixels of the same maps; these read the same kernel-matrix
+  // fragments at about the same time, three of four from the first-level cache (cfg5 c3 forward: 0.8 instead
+  // of 2.7 GB from the second level)
+  HaloBf16Plan wide{};
+  double wide_cost = 0;
+  const bool maps_ok = plan_arrangement(4, 1, n, c, h, w, m, r, s, ph, pw, p, &cost);
+  const bool wide_ok = plan_arrangement(1, 4, n, c, h, w, m, r, s, ph, pw, &wide, &wide_cost);
+  if (wide_ok && (!maps_ok || wide_cost <= cost + 1e-9)) *p = wide;
+  return maps_ok || wide_ok;
+}
+
+template <int WAVES_M, int WAVES_K, int TM, int TN, bool M16 = false, int WAVES_N = 1>
 static void launch_one(const HaloBf16Args& a, size_t lds, hipStream_t st) {
   const dim3 grid((unsigned)((int64_t)a.tiles_m * a.n * a.tiles_per_img)), block(kThreads);
-  auto kernel = conv_halo_bf16_kernel<WAVES_M, WAVES_K, TM, TN, M16>;
+  auto kernel = conv_halo_bf16_kernel<WAVES_M, WAVES_K, TM, TN, M16, WAVES_N>;
   static bool opted = false;  // one flag per instantiation, i.e. per kernel
   if (!opted) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -421,8 +441,9 @@ static void launch_one(const HaloBf16Args& a, size_t lds, hipStream_t st) {
 }
 
 template <int TN>
-static void launch_tn(const HaloBf16Args& a, int waves_m, int tm, size_t lds, hipStream_t st) {
-  if (waves_m == 4) launch_one<4, 1, 2, TN>(a, lds, st);
+static void launch_tn(const HaloBf16Args& a, int waves_m, int waves_n, int tm, size_t lds, hipStream_t st) {
+  if (waves_n == 4) launch_one<1, 1, 2, TN, false, 4>(a, lds, st);
+  else if (waves_m == 4) launch_one<4, 1, 2, TN>(a, lds, st);
   else if (waves_m == 2) launch_one<2, 2, 2, TN>(a, lds, st);
   else if (tm == 2) launch_one<1, 4, 2, TN>(a, lds, st);
   else launch_one<1, 4, 1, TN>(a, lds, st);
@@ -456,15 +477,15 @@ vcnn_status launch_conv_halo_bf16(const HaloBf16Plan& p, int n, int c, int h, in
   a.oh = h + 2 * ph - r + 1, a.ow = w + 2 * pw - s + 1;
   a.P = a.oh * a.ow;
   a.tiles_m = tiles_m;
-  a.tiles_per_img = (int)ceil_div(a.P, tile * p.tn);
+  a.tiles_per_img = (int)ceil_div(a.P, tile * p.tn * p.waves_n);
   a.cg = p.cg, a.cgc = p.cgc, a.nchunks = p.nchunks, a.nr = p.nr, a.wp = p.wp, a.uch = p.uch, a.hpos = p.hpos, a.relu = relu;
   if (p.m16) {
     if (p.tn == 4) launch_one<1, 4, 3, 4, true>(a, p.lds_bytes, st);
     else if (p.tn == 8) launch_one<1, 4, 3, 8, true>(a, p.lds_bytes, st);
     else launch_one<1, 4, 3, 10, true>(a, p.lds_bytes, st);
-  } else if (p.tn == 2) launch_tn<2>(a, p.waves_m, p.tm, p.lds_bytes, st);
-  else if (p.tn == 4) launch_tn<4>(a, p.waves_m, p.tm, p.lds_bytes, st);
-  else launch_tn<5>(a, p.waves_m, p.tm, p.lds_bytes, st);
+  } else if (p.tn == 2) launch_tn<2>(a, p.waves_m, p.waves_n, p.tm, p.lds_bytes, st);
+  else if (p.tn == 4) launch_tn<4>(a, p.waves_m, p.waves_n, p.tm, p.lds_bytes, st);
+  else launch_tn<5>(a, p.waves_m, p.waves_n, p.tm, p.lds_bytes, st);
   return check_launch("conv_halo_bf16");
 }
 

@@ -146,7 +146,9 @@ vcnn_status launch_flip_transpose(int dtype, const void* w, void* w2, int M, int
 
 // ---- bf16_conv.hip (implicit bf16 kernels) / bf16_mfma.hip (explicit-route bf16 product) ------------
 struct HaloBf16Plan {
-  int waves_m;       // waves of a block along the output maps (the other 4 / waves_m split the contraction)
+  int waves_m;       // waves of a block along the output maps
+  int waves_n;       // waves of a block along the pixels (same maps: they read the same kernel-matrix fragments);
+                     // the remaining 4 / (waves_m * waves_n) split the contraction
   int m16;           // 1: 33..48 maps on 16 x 16 tiles (tm = 3 row tiles, tn in 16-pixel tiles), else 32 x 32 tiles
   int tm;            // row tiles per wave (32-row tiles: 1 for at most 32 maps, else 2)
   int tn;            // column tiles per wave (of 32 pixels, or of 16 with m16)

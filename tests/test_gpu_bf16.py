@@ -30,6 +30,8 @@ SHAPES = [
     (2, 16, 40, 40, 48, 5, 5, 2, 2),    # 33..48 maps: three 16-row tiles per wave, wide pixel tile
     (3, 38, 14, 14, 38, 3, 3, 1, 1),    # ... forward and input gradient alike, small image
     (2, 40, 9, 30, 44, 2, 3, 0, 1),     # ... ragged
+    (600, 8, 10, 10, 200, 3, 3, 1, 1),  # many maps, many small images: the four waves of a block take different maps
+                                        # (large images: different pixels, test_conv_bf16_wide_pixel_tiles with 200 maps)
 ]
 
 
