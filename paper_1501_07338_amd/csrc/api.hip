@@ -156,7 +156,8 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
     }
   }
   // (other 1x1 layers included: they are a plain bf16 product through the same kernel)
-  if (bf16_mfma && pass == VCNN_PASS_FWD && (g.k > 4 || g.c >= 64) &&
+  // (a single map over many channels is faster as the taps-as-rows product below, in bf16 storage as well)
+  if (bf16_mfma && pass == VCNN_PASS_FWD && (g.k > 4 || g.c >= 64) && !conv_taps_applies(g) &&
       conv_halo_bf16_plan(g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, &p.hb)) {
     p.path = PATH_HALO_BF16;
     p.workspace_bytes = p.hb.x8_bytes + p.hb.wf_bytes;
