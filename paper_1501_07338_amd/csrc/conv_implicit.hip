@@ -718,6 +718,155 @@ __global__ __launch_bounds__(kThreads) void conv_halo_filter_kernel(HaloFilterAr
   }
 }
 
+// The same kernel for 33..48 output maps (BM = 48) on the 16 x 16 x 4 form of the instruction (as the forward kernel
+// above: 32-row tiles would run such a layer as 64 rows, a quarter of them padding).  Every wave holds all 48 rows
+// for WN of the block's kernel-matrix columns.  Lane l feeds row / column l % 16 and, of a group of 16 pixels, the
+// four 4*(l / 16) + [0, 4); the dY slab and the pixel-offset table are read with the same permutation.
+template <int BM, int BNK, int WN, int BK, bool VEC, typename T>
+__global__ __launch_bounds__(kThreads) void conv_halo_filter16_kernel(HaloFilterArgs a) {
+  static_assert((BNK / WN) * 64 == kThreads, "four waves per block, side by side along the columns");
+  static_assert(BM % 16 == 0 && WN % 16 == 0 && BK % 16 == 0, "16-wide tiles");
+  using LA = LdsTile<BM, BK, true>;
+  using SA = Stager<BM, BK, kThreads, true, VEC>;
+  constexpr int TM = BM / 16, TN = WN / 16;
+  extern __shared__ float4 smem4[];
+  float* const As0 = reinterpret_cast<float*>(smem4);
+  int* const pixoff = reinterpret_cast<int*>(As0 + 2 * LA::SIZE);  // [bp]
+  float* const halo = As0 + 2 * LA::SIZE + a.bp;                   // [ccs][nr][wp]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l16 = lane & 15, kq = lane >> 4;
+  const int tm = blockIdx.x % a.tiles_m;
+  const int tk = blockIdx.x / a.tiles_m;
+  const int i0 = tm * BM, k0 = tk * BNK;
+  const int wn0 = wave * WN;
+  const int RS = a.r * a.s;
+  const int K = a.c * RS;
+  const int plane = a.nr * a.wp;
+  const int c_first = k0 / RS;
+
+  int tap_base[TN];  // as above; column K, when there is room for it, reads the plane of ones (bias gradient)
+#pragma unroll
+  for (int ni = 0; ni < TN; ++ni) {
+    const int col = min(k0 + wn0 + ni * 16 + l16, K - 1);
+    const int c = col / RS;
+    const int q = col - c * RS;
+    const int r = q / a.s;
+    tap_base[ni] = (c - c_first) * plane + r * a.wp + (q - r * a.s);
+    if (a.Kp > K && k0 + wn0 + ni * 16 + l16 == K) tap_base[ni] = a.ccs * plane;
+  }
+  if (a.Kp > K)
+    for (int e = tid; e < plane; e += kThreads) halo[a.ccs * plane + e] = 1.f;  // published by the first run's barrier
+
+  SA sa;
+  sa.init(tid);
+
+  f32x4 acc[TM][TN];
+#pragma unroll
+  for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) acc[mi][ni][q] = 0.f;
+
+  const int total_runs = a.n * a.runs_per_img;
+  const int run0 = blockIdx.y * a.runs_per_split;
+  const int run1 = min(total_runs, run0 + a.runs_per_split);
+  const int slabs_per_run = a.bp / BK;
+
+  for (int run = run0; run < run1; ++run) {
+    const int n = run / a.runs_per_img;
+    const int p0 = (run - n * a.runs_per_img) * a.bp;
+    const int plen = min(a.bp, a.P - p0);
+    const int oh_first = p0 / a.ow;
+    const T* dyn = static_cast<const T*>(a.dy) + (int64_t)n * a.m * a.P + p0;
+    auto fetch = [&](int sl) {
+      const int pk = sl * BK + sa.c;
+#pragma unroll
+      for (int e = 0; e < SA::SLOTS; ++e) {
+        const int m = i0 + sa.line(e);
+        sa.ok[e] = m < a.m && pk < plen;
+        const T* src = dyn + (int64_t)min(m, a.m - 1) * a.P + min(pk, plen - (VEC ? 4 : 1));
+        if constexpr (VEC && std::is_same<T, float>::value) {
+          const float4 t = ld4_dword_aligned(src);  // as above: the run's last group is moved back and shifted down
+          const int d = pk - min(pk, plen - 4);
+          sa.v[e][0] = t.x, sa.v[e][1] = t.y, sa.v[e][2] = t.z, sa.v[e][3] = t.w;
+          if (d > 0 && d < 4) {
+            sa.v[e][0] = d == 1 ? t.y : (d == 2 ? t.z : t.w);
+            sa.v[e][1] = d == 1 ? t.z : (d == 2 ? t.w : 0.f);
+            sa.v[e][2] = d == 1 ? t.w : 0.f;
+            sa.v[e][3] = 0.f;
+          }
+        } else if constexpr (VEC) {
+          const float4 t = ld4(src);
+          sa.v[e][0] = t.x, sa.v[e][1] = t.y, sa.v[e][2] = t.z, sa.v[e][3] = t.w;
+        } else {
+          sa.v[e][0] = ld(src);
+        }
+      }
+    };
+    fetch(0);
+    __syncthreads();  // the previous run's MFMAs are done with the halo tile, the table and the slabs
+    for (int pk = tid; pk < a.bp; pk += kThreads) {
+      const int p = min(p0 + pk, a.P - 1);
+      const int oh = p / a.ow;
+      pixoff[pk] = (oh - oh_first) * a.wp + (p - oh * a.ow);
+    }
+    stage_halo<8>(halo, static_cast<const T*>(a.x) + ((int64_t)n * a.c + c_first) * a.h * a.w, a.ccs, a.c - c_first,
+                  a.nr, a.wp, a.h, a.w, oh_first - a.ph, a.pw, tid);
+    sa.store(As0);
+    __syncthreads();
+
+    for (int sl = 0; sl < slabs_per_run; ++sl) {
+      const int cur = sl & 1;
+      if (sl * BK >= plen) break;
+      const bool more = (sl + 1) * BK < plen;
+      if (more) fetch(sl + 1);
+      const float* As = As0 + cur * LA::SIZE;
+      const int* poff = pixoff + sl * BK;
+#pragma unroll
+      for (int t = 0; t < BK / 16; ++t) {
+        float4 af[TM];
+#pragma unroll
+        for (int mi = 0; mi < TM; ++mi)
+          af[mi] = *reinterpret_cast<const float4*>(As + (mi * 16 + l16) * LA::PITCH + 16 * t + 4 * kq);
+        const int4 o4 = *reinterpret_cast<const int4*>(poff + 16 * t + 4 * kq);
+        const int o[4] = {o4.x, o4.y, o4.z, o4.w};
+        float bf[TN][4];
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) bf[ni][i] = halo[tap_base[ni] + o[i]];
+        const float* afl = reinterpret_cast<const float*>(af);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < TN; ++ni)
+              acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x4f32(afl[mi * 4 + i], bf[ni][i], acc[mi][ni], 0, 0, 0);
+      }
+      if (more) sa.store(As0 + (cur ^ 1) * LA::SIZE);
+      __syncthreads();
+    }
+  }
+
+  // 16 x 16 result: register q of lane l holds row 4*(l / 16) + q, column l % 16
+  float* dst = a.out + (int64_t)blockIdx.y * a.m * a.Kp;
+#pragma unroll
+  for (int ni = 0; ni < TN; ++ni) {
+    const int col = k0 + wn0 + ni * 16 + l16;
+    if (col >= a.Kp) continue;
+#pragma unroll
+    for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int m = i0 + mi * 16 + 4 * kq + q;
+        if (m < a.m) dst[(int64_t)m * a.Kp + col] = acc[mi][ni][q];
+      }
+  }
+}
+
 // Slab depth (pixels of dY staged per barrier): a narrow row tile does few MFMAs per pixel, so it takes deeper
 // slabs - the next slab's loads then have a few microseconds of MFMA work to hide behind.
 static int filter_bk(int64_t m) { return m <= 32 ? 128 : (m <= 64 ? 64 : 32); }
@@ -726,7 +875,7 @@ bool conv_halo_filter_plan(const ConvGeom& g, HaloFilterPlan* p) {
   const int rs = g.r * g.s;
   const int BK = filter_bk(g.M);
   if ((int64_t)g.c * g.h * g.w > 0x7fffffffLL) return false;  // 32-bit offsets inside a sample
-  p->bm = g.M <= 32 ? 32 : (g.M <= 64 ? 64 : 128);
+  p->bm = g.M <= 32 ? 32 : (g.M <= 48 ? 48 : (g.M <= 64 ? 64 : 128));
   p->bnk = g.M <= 64 ? 256 : 128;
   p->wp = g.w + 2 * g.pw;
   // channels a run of bnk consecutive kernel-matrix columns can touch
@@ -739,7 +888,7 @@ bool conv_halo_filter_plan(const ConvGeom& g, HaloFilterPlan* p) {
     if (rows > g.oh) rows = g.oh;
     const int nr = rows + g.r - 1;
     const size_t bytes = a_bytes + (size_t)bp * 4 + (size_t)p->ccs * nr * p->wp * 4;
-    if (bytes > (p->bm >= 64 ? kLdsBudget3 : kLdsBudget)) break;
+    if (bytes > (p->bm >= 48 ? kLdsBudget3 : kLdsBudget)) break;
     best = bp;
     if (bp >= g.P) break;
   }
@@ -756,7 +905,7 @@ bool conv_halo_filter_plan(const ConvGeom& g, HaloFilterPlan* p) {
   // fill whole rounds of the resident set best (long blocks: a last round that is half empty costs half a round)
   int64_t want = ceil_div(1024, tiles);
   if (want <= 8) {  // (many slices mean short blocks, whose rounds do not matter - and more partial sums to add)
-    const int64_t slots = 256 * (p->bm >= 64 ? 3 : 2);
+    const int64_t slots = 256 * (p->bm >= 48 ? 3 : 2);
     double best_fill = 0;
     int64_t best_want = want;
     for (int64_t w = want; w <= 2 * want; ++w) {
@@ -813,6 +962,31 @@ static void launch_halo_filter(const HaloFilterArgs& a, const HaloFilterPlan& p,
   }
 }
 
+template <bool VEC, typename T>
+static void launch_halo_filter16_one(const HaloFilterArgs& a, const HaloFilterPlan& p, int tiles, hipStream_t st) {
+  const dim3 grid((unsigned)tiles, (unsigned)p.splits), block(kThreads);
+  auto kernel = conv_halo_filter16_kernel<48, 256, 64, 64, VEC, T>;
+  static bool opted = false;
+  if (!opted) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)kLdsBudget);
+    opted = true;
+  }
+  hipLaunchKernelGGL(kernel, grid, block, p.lds_bytes, st, a);
+}
+
+// 48-row tiles (33..48 output maps)
+static void launch_halo_filter16(const HaloFilterArgs& a, const HaloFilterPlan& p, bool vec, int dtype, int tiles,
+                                 hipStream_t st) {
+  if (dtype == VCNN_BF16) {
+    if (vec) launch_halo_filter16_one<true, bf16>(a, p, tiles, st);
+    else launch_halo_filter16_one<false, bf16>(a, p, tiles, st);
+  } else {
+    if (vec) launch_halo_filter16_one<true, float>(a, p, tiles, st);
+    else launch_halo_filter16_one<false, float>(a, p, tiles, st);
+  }
+}
+
 vcnn_status launch_conv_halo_filter(const HaloFilterPlan& p, int dtype, const ConvGeom& g, const void* x, const void* dy,
                                     float* dw, float* dbias, float* partial, hipStream_t st) {
   const bool with_bias = p.bias_column && dbias;
@@ -827,7 +1001,9 @@ vcnn_status launch_conv_halo_filter(const HaloFilterPlan& p, int dtype, const Co
   const int tiles = a.tiles_m * (int)ceil_div(g.K, p.bnk);
   const bool vec = dtype == VCNN_BF16 ? p.vec && group_aligned<bf16>(dy)
                                       : (p.vec && group_aligned<float>(dy)) || (p.vec4_any && (reinterpret_cast<uintptr_t>(dy) & 3) == 0);
-  if (p.bm == 32)
+  if (p.bm == 48)
+    launch_halo_filter16(a, p, vec, dtype, tiles, st);
+  else if (p.bm == 32)
     launch_halo_filter<32, 256, 32, 64, 128>(a, p, vec, dtype, tiles, st);
   else if (p.bm == 64)
     launch_halo_filter<64, 256, 64, 64, 64>(a, p, vec, dtype, tiles, st);
