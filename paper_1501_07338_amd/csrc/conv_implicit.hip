@@ -1077,31 +1077,27 @@ __global__ __launch_bounds__(kThreads) void filter_grad_few_cols_kernel(FewColsA
       const int oh = p / a.ow;
       pixoff[tid] = (oh - oh_first) * a.wp + (p - oh * a.ow);
     }
-    {  // dY rows of this run, zero beyond the maps / the sample's pixels; eight loads in flight per thread
-      const T* dyn = static_cast<const T*>(a.dy) + (int64_t)n * a.m * a.P + p0;
-      constexpr int PER = ROWS * BP / kThreads;
-      static_assert(PER % 8 == 0, "eight loads per round");
+    // dY rows of this run, zero beyond the maps / the sample's pixels.  All of a thread's loads are issued before the
+    // halo tile is staged and stored only after it: the run costs one memory round trip, not one per eight loads
+    const T* dyn = static_cast<const T*>(a.dy) + (int64_t)n * a.m * a.P + p0;
+    constexpr int PER = ROWS * BP / kThreads;
+    float dyv[PER];
 #pragma unroll
-      for (int e0 = 0; e0 < PER; e0 += 8) {
-        float v[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int e = (e0 + u) * kThreads + tid;
-          const int m = e / BP, pk = e - m * BP;
-          const bool ok = m < a.m && pk < plen;
-          const float t = ld(dyn + (ok ? (int64_t)m * a.P + pk : 0));
-          v[u] = ok ? t : 0.f;
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const int e = (e0 + u) * kThreads + tid;
-          const int m = e / BP, pk = e - m * BP;
-          dyt[m * PITCH + pk] = v[u];
-        }
-      }
+    for (int u = 0; u < PER; ++u) {
+      const int e = u * kThreads + tid;
+      const int m = e / BP, pk = e - m * BP;
+      const bool ok = m < a.m && pk < plen;
+      const float t = ld(dyn + (ok ? (int64_t)m * a.P + pk : 0));
+      dyv[u] = ok ? t : 0.f;
     }
     stage_halo<8>(halo, static_cast<const T*>(a.x) + (int64_t)n * a.c * a.h * a.w, a.c, a.c, a.nr, a.wp, a.h, a.w,
                   oh_first - a.ph, a.pw, tid);
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      const int e = u * kThreads + tid;
+      const int m = e / BP, pk = e - m * BP;
+      dyt[m * PITCH + pk] = dyv[u];
+    }
     __syncthreads();
 
 #pragma unroll
