@@ -54,7 +54,7 @@ __global__ __launch_bounds__(kThreads) void taps_gather_kernel(const float* __re
 
 bool conv_taps_applies(const ConvGeom& g) {
   // one map, enough channels for the contraction of the forward product, enough taps for its rows
-  return g.k == 1 && g.c >= 64 && g.r * g.s >= 16 && g.r * g.s <= 1024 && g.r - 1 - g.ph >= 0 && g.s - 1 - g.pw >= 0 &&
+  return g.k == 1 && g.c >= 32 && g.r * g.s >= 16 && g.r * g.s <= 1024 && g.r - 1 - g.ph >= 0 && g.s - 1 - g.pw >= 0 &&
          (int64_t)g.n * g.h * g.w <= 0x7fffffffLL;
 }
 

@@ -27,6 +27,7 @@ SHAPES = [
     (2, 16, 16, 16, 64, 5, 5, 2, 2),
     (3, 9, 14, 15, 20, 3, 3, 1, 1),     # at most 32 maps: one 32-row tile per wave in every pass
     (2, 64, 12, 12, 1, 4, 4, 0, 0),     # a single map over many channels goes to the matrix cores as well
+    (2, 40, 9, 11, 1, 4, 4, 1, 1),      # ... 32 to 63 channels: forward and kernel gradient as taps-as-rows products
     (2, 16, 40, 40, 48, 5, 5, 2, 2),    # 33..48 maps: three 16-row tiles per wave, wide pixel tile
     (3, 38, 14, 14, 38, 3, 3, 1, 1),    # ... forward and input gradient alike, small image
     (2, 40, 9, 30, 44, 2, 3, 0, 1),     # ... ragged

@@ -45,7 +45,8 @@ CONV_SHAPES = [
     (3, 20, 7, 7, 40, 1, 1, 0, 0),      # 1 x 1 with an odd pixel count: groups of four run over the end of a sample
     (5, 130, 5, 5, 70, 1, 1, 0, 0),     # ... two column tiles of the kernel matrix, three row tiles, 125 columns in all
     (2, 33, 3, 1, 64, 1, 1, 0, 0),      # ... fewer pixels per sample than one group of four
-    (2, 64, 12, 12, 1, 4, 4, 0, 0),     # one map over 64 and more channels: the taps as rows of a matrix-core product
+    (2, 64, 12, 12, 1, 4, 4, 0, 0),     # one map over 32 and more channels: the taps as rows of a matrix-core product
+    (3, 32, 13, 10, 1, 5, 5, 2, 2),     # ... the fewest channels that take this route (the denoising network's last layer)
     (3, 70, 9, 11, 1, 5, 5, 2, 2),      # ... padded ('same'), odd pixel counts
     (2, 130, 14, 9, 1, 8, 3, 0, 1),     # ... rectangular kernel, padded along one axis only
 ]
