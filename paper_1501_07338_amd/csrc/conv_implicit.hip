@@ -417,12 +417,17 @@ static int halo_bn(int m, int64_t P, int n) {
   return best;
 }
 // Slab depth: narrow row tiles do few MFMAs per slab, so they take deeper slabs (fewer barriers per MFMA).
-static int halo_bk(int m) { return m <= 64 ? 64 : 32; }
+static int halo_bk(int m, int64_t K) {
+  if (m <= 64 && m > 48 && K <= 128 && ceil_div(K, 32) * 32 < ceil_div(K, 64) * 64) return 32;  // a short contraction pads less
+  return m <= 64 ? 64 : 32;
+}
 
 bool conv_halo_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int pw, HaloPlan* p) {
   const int oh = h + 2 * ph - r + 1, ow = w + 2 * pw - s + 1;
   if (oh <= 0 || ow <= 0 || (int64_t)c * h * w > 0x7fffffffLL) return false;  // 32-bit offsets inside a sample
-  const int bm = halo_bm(m), bn = halo_bn(m, (int64_t)oh * ow, n), BK = halo_bk(m);
+  const int bm = halo_bm(m), bn = halo_bn(m, (int64_t)oh * ow, n);
+  int BK = halo_bk(m, (int64_t)c * r * s);
+  if (bm == 64 && bn != 256) BK = 64;  // the 32-deep variant exists for the widest pixel tile only
   const int rs = r * s;
   int rows = (bn + ow - 2) / ow + 1;  // rows a run of bn consecutive pixels can touch
   if (rows > oh) rows = oh;
@@ -534,6 +539,8 @@ vcnn_status launch_conv_halo(const HaloPlan& p, int dtype, int n, int c, int h, 
     launch_halo<32, 128, 32, 32, 64>(a, p, vec, dtype, st);
   else if (p.bm == 48)
     launch_halo16(a, p, vec, dtype, st);
+  else if (p.bm == 64 && p.bn == 256 && p.bk == 32)
+    launch_halo<64, 256, 64, 64, 32>(a, p, vec, dtype, st);
   else if (p.bm == 64 && p.bn == 256)
     launch_halo<64, 256, 64, 64, 64>(a, p, vec, dtype, st);
   else if (p.bm == 64 && p.bn == 128)
