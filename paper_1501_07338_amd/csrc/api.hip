@@ -371,8 +371,9 @@ static vcnn_status conv_fwd_linear(const vcnn_conv_desc* d, const ConvGeom& g, c
                                  bias, y, relu, workspace, st);
   }
   if (plan.path == PATH_FFT) return launch_conv_fft(plan.fft, dt, g, x, w, bias, y, relu, workspace, st);
-  if (plan.path == PATH_POINTWISE_BF16)
-    return launch_pointwise_bf16(plan.pwb, g.n, g.k, g.c, (int)g.P, w, x, bias, y, relu, st);
+  // (its 16-byte reads of the kernel matrix need that alignment; a matrix placed otherwise takes the generic product)
+  const bool pointwise_bf16 = plan.path == PATH_POINTWISE_BF16 && (reinterpret_cast<uintptr_t>(w) & 15) == 0;
+  if (pointwise_bf16) return launch_pointwise_bf16(plan.pwb, g.n, g.k, g.c, (int)g.P, w, x, bias, y, relu, st);
 
   GemmArgs a{};
   a.A = w, a.C = y, a.bias = bias;
@@ -381,7 +382,7 @@ static vcnn_status conv_fwd_linear(const vcnn_conv_desc* d, const ConvGeom& g, c
   a.a_si = g.K, a.a_sk = 1;
   a.c_si = g.P, a.c_sj = 1, a.c_P = (int)g.P, a.c_simg = g.M * g.P;
   a.relu = relu;
-  if (plan.path == PATH_POINTWISE) {
+  if (plan.path == PATH_POINTWISE || plan.path == PATH_POINTWISE_BF16) {
     // patch matrix == input: B(k, j) = x[n][k][p]
     a.B = x;
     a.b_sk = g.P, a.b_sj = 1, a.b_P = (int)g.P, a.b_simg = g.K * g.P;

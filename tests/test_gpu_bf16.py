@@ -161,6 +161,11 @@ def test_conv_bf16_pointwise(shape, offset):
     vcnn.conv_bwd_data(d, wd, dyd, dx, ws)
     assert_close(f32_of(dx), O.conv_bwd_data(wt, dy, (h, w), pad=(0, 0)), TOL_BF16, "bf16 1x1 dx")
     assert torch.isnan(dxbuf[:offset]).all() and torch.isnan(dxbuf[offset + dx.numel():]).all()
+    if offset:  # a kernel matrix that is not 16-byte aligned takes the generic product: same result within the bar
+        _, wd_off = placed(wt)
+        ybuf, y = blank((n, k, h, w))
+        vcnn.conv_fwd(d, xd, wd_off, torch.from_numpy(b).to(DEV), y, ws)
+        assert_close(f32_of(y), O.conv_fwd(x, wt, b, pad=(0, 0), relu=True), TOL_BF16, "bf16 1x1 conv_fwd, offset kernel matrix")
     # run to run the kernel gradient's ordered partial sums give the same bits
     dw2 = torch.empty_like(dw)
     vcnn.conv_bwd_filter(d, xd, dyd, dw2, db, ws)
