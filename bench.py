@@ -7,7 +7,7 @@ The headline is the largest of the five workloads, the deconvolution CNN cfg5 in
 step): images/s of the training step, GFLOP/s of its convolution passes against the fp32 matrix-core
 peak, and the roofline record of the pass that takes the most time.  cfg5 with bf16 storage and
 cfg1-cfg4 ride along as compact summaries; the long per-layer tables, the bandwidth-bound kernels and
-the mini-batch sweep go to gpurun_out/bench_detail.json.
+the mini-batch sweep go to a side file (--detail).
 
 Every timed step starts from the same seeded parameters: the squared-error networks (cfg4, cfg5) leave
 the range of finite floats within three plain-SGD steps at the stated learning rate, so the initial

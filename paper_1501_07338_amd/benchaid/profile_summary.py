@@ -6,9 +6,9 @@ size = 64 x phase number; the numbering is in the detail file it writes).  Walki
 everything between a marker and the next one belongs to that phase, so each convolution pass gets rows of its
 own even where one kernel name serves several layers.
 
-    python -m paper_1501_07338_amd.benchaid.profile_summary --name cfg5_f32_bf16 --detail gpurun_out/prof/detail.json \\
-        --trace gpurun_out/prof/trace --fetch gpurun_out/prof/fetch --write gpurun_out/prof/write \\
-        --mfma gpurun_out/prof/mfma --cmd "<the bench.py arguments of the runs>" [--out profiles]
+    python -m paper_1501_07338_amd.benchaid.profile_summary --name cfg5_f32_bf16 --detail <dir>/detail.json \\
+        --trace <dir>/trace --fetch <dir>/fetch --write <dir>/write \\
+        --mfma <dir>/mfma --cmd "<the bench.py arguments of the runs>" [--out profiles]
 
 Counter calibration: the phase "copy of 1 GiB" is a plain streaming copy (2^30 bytes read, 2^30 written); the
 factor bytes / (counter KiB x 1024) it gives for FETCH_SIZE and for WRITE_SIZE scales every other reading.
