@@ -181,7 +181,22 @@ def main():
                 traffic["passes"][phase] = {"kernel": top[0][0], "grid": top[0][1], "fetch_kib": top[3], "write_kib": top[4],
                                             "hbm_bytes": top[2], "pass_hbm_bytes": pass_bytes}
         open(os.path.join(args.out, f"{args.name}_hbm_traffic_pmc.txt"), "w").write("\n".join(out) + "\n")
-        json.dump(traffic, open(os.path.join(args.out, "traffic.json"), "w"), indent=1)
+        # one table for every summarised set of runs: passes of other sets stay, those of this set are replaced
+        path = os.path.join(args.out, "traffic.json")
+        table = {"runs": {}, "passes": {}}
+        if os.path.exists(path):
+            try:
+                kept = json.load(open(path))
+                if "runs" in kept:
+                    table = kept
+            except ValueError:
+                pass
+        table["passes"] = {k: v for k, v in table["passes"].items() if v.get("run") != args.name}
+        for k, v in traffic["passes"].items():
+            table["passes"][k] = dict(v, run=args.name)
+        table["runs"][args.name] = {"commit": traffic["commit"], "command": traffic["command"],
+                                    "calibration": traffic.get("calibration")}
+        json.dump(table, open(path, "w"), indent=1, sort_keys=True)
 
     if args.mfma:
         m_ph = phases_of(load_counters(args.mfma), markers, "Kernel_Name", "Grid_Size")
