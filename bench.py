@@ -354,6 +354,15 @@ def aids(stream):
         # clock the chip holds depends on the power the matrix cores draw
         ms = sorted(time_calls(lambda: benchaid.mfma(bf16, blocks, iters, sink, toggle=True), 3, stream) for _ in range(3))[1]
         out["mfma_" + name]["sustained_tflops_changing_operands"] = flop / (ms * 1e9)
+    # the matrix-core loop of a 128 x 128 fp32 tile fed from LDS as the layer kernels feed it, three blocks per compute
+    # unit: alone, and with the fetch of new operand words from the L2 into LDS between the barriers
+    words = torch.empty(8 << 20 >> 2, device="cuda").normal_()  # 8 MB
+    sink3 = torch.empty(768 * 256, device="cuda")
+    for key, staged in (("lds_fed_tflops", False), ("lds_fed_with_staging_tflops", True)):
+        flop = benchaid.mfma_lds(staged, 768, 4000, sink3, words)
+        ms = sorted(time_calls(lambda: benchaid.mfma_lds(staged, 768, 4000, sink3, words), 3, stream) for _ in range(3))[1]
+        out["mfma_f32"][key] = flop / (ms * 1e9)
+    del words, sink3
     src = torch.empty(1 << 28, device="cuda").normal_()
     dst = torch.empty_like(src)
     mark("copy of 1 GiB")
@@ -513,6 +522,8 @@ def main():
         out["yardsticks"] = {"mfma_f32_sustained_tflops": detail["yardsticks"]["mfma_f32"]["sustained_tflops"],
                              "mfma_bf16_sustained_tflops": detail["yardsticks"]["mfma_bf16"]["sustained_tflops"],
                              "mfma_f32_changing_operands_tflops": detail["yardsticks"]["mfma_f32"]["sustained_tflops_changing_operands"],
+                             "mfma_f32_lds_fed_tflops": detail["yardsticks"]["mfma_f32"]["lds_fed_tflops"],
+                             "mfma_f32_lds_fed_with_staging_tflops": detail["yardsticks"]["mfma_f32"]["lds_fed_with_staging_tflops"],
                              "mfma_bf16_changing_operands_tflops": detail["yardsticks"]["mfma_bf16"]["sustained_tflops_changing_operands"],
                              "copy_1GiB_gbs": detail["yardsticks"]["copy_1GiB"]["gbs"]}
         out["fourier_comparison"] = [[r["layer"], r["unroll_ms"], r["fourier_ms"]] for r in detail["fourier_comparison"]]

@@ -18,6 +18,7 @@ def lib() -> ctypes.CDLL:
         import torch  # noqa: F401  (one HIP runtime per process: torch's)
         h = ctypes.CDLL(str(LIB_PATH))
         h.benchaid_mfma.restype, h.benchaid_mfma.argtypes = c_int, [c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_void_p]
+        h.benchaid_mfma_lds.restype, h.benchaid_mfma_lds.argtypes = c_int, [c_int, c_int, c_int, c_void_p, c_void_p, c_int, c_void_p, c_void_p]
         h.benchaid_copy.restype, h.benchaid_copy.argtypes = c_int, [c_void_p, c_void_p, c_size_t, c_void_p]
         h.benchaid_marker.restype, h.benchaid_marker.argtypes = c_int, [c_int, c_void_p]
         _lib = h
@@ -38,6 +39,18 @@ def mfma(bf16: bool, blocks: int, iters: int, sink, stream=None, toggle: bool = 
     err = lib().benchaid_mfma(int(bf16), int(toggle), blocks, iters, sink.data_ptr(), byref(flop), _stream(stream))
     if err:
         raise RuntimeError(f"benchaid_mfma: HIP error {err}")
+    return flop.value
+
+
+def mfma_lds(staged: bool, blocks: int, iters: int, sink, src=None, stream=None) -> float:
+    """Launches the fp32 matrix-core loop of a 128 x 128 tile fed from LDS (staged: with the fetch of new operand
+    words from the device tensor src into LDS every 64 instructions); returns the flop count of the launch."""
+    flop = c_double()
+    count4 = 0 if src is None else src.numel() * src.element_size() // 16
+    err = lib().benchaid_mfma_lds(int(staged), blocks, iters, sink.data_ptr(), None if src is None else src.data_ptr(),
+                                  count4, byref(flop), _stream(stream))
+    if err:
+        raise RuntimeError(f"benchaid_mfma_lds: HIP error {err}")
     return flop.value
 
 

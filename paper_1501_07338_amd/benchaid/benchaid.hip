@@ -100,6 +100,73 @@ __global__ __launch_bounds__(kThreads) void benchaid_mfma_kernel(float* __restri
   sink[(size_t)blockIdx.x * kThreads + threadIdx.x] = s;
 }
 
+// The fp32 matrix-core loop of a 128 x 128 tile with its operands read from LDS, as the layer kernels read them: per
+// 16 instructions a wave reads two 16-byte A fragments and eight 4-byte B words at lane-dependent addresses, and
+// the block meets at a barrier every 64 instructions.  STAGED adds what feeds such a loop from memory: per barrier
+// interval every thread fetches four 16-byte words of a global array (a few MB: it stays in the L2) and writes them
+// to LDS before the barrier.  Three blocks per compute unit (52 KB of LDS each), like the layer kernels.  The rate
+// of this loop, not the data-sheet peak, is what a kernel of that structure can approach.
+static constexpr int kLdsFedFloats = 52 * 1024 / 4;
+template <bool STAGED>
+__global__ __launch_bounds__(kThreads) void benchaid_mfma_lds_kernel(float* __restrict__ sink, int iters,
+                                                                       const float4* __restrict__ src, int src_count4) {
+  extern __shared__ float lds[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  for (int i = tid; i < kLdsFedFloats; i += kThreads) lds[i] = 1.0f + 0.001f * (float)((i * 2654435761u) >> 20);
+  __syncthreads();
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[a][b][q] = 0.f;
+  const int abase = (lane & 31) * 36 + (lane >> 5) * 4;   // A fragments: rows of 32 + 4 floats
+  const int bbase = 4096 + (lane & 31) + (lane >> 5);     // B words: 32 neighbouring words, the upper half one further
+  float* const stage = lds + 8448;                        // 4 x 1152 floats, behind everything the loop reads
+  float4 sv[4];
+  size_t pos = ((size_t)blockIdx.x * 977 + tid) % (size_t)(src_count4 - 4096);
+  for (int it = 0; it < iters; ++it) {
+    const int off = (it & 7) * 8;
+    if (STAGED && (it & 3) == 0) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) sv[e] = src[pos + e * kThreads];
+    }
+    float4 af[2];
+    af[0] = *reinterpret_cast<const float4*>(lds + abase + off);
+    af[1] = *reinterpret_cast<const float4*>(lds + abase + 1152 + off);
+    float bf[2][4];
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) bf[ni][i] = lds[bbase + ni * 64 + (off + i) * 67];
+    const float* afl = reinterpret_cast<const float*>(af);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni)
+          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(afl[mi * 4 + i], bf[ni][i], acc[mi][ni], 0, 0, 0);
+    if ((it & 3) == 3) {
+      if (STAGED) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) *reinterpret_cast<float4*>(stage + (tid >> 3) * 36 + (tid & 7) * 4 + e * 1152) = sv[e];
+        pos = (pos + 4 * kThreads) % (size_t)(src_count4 - 4096);
+      }
+      __syncthreads();
+    }
+  }
+  float s = STAGED ? stage[tid] : 0.f;
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) s += acc[a][b][q];
+  sink[(size_t)blockIdx.x * kThreads + tid] = s;
+}
+
 // dst[i] = src[i], 16 bytes per thread, grid-stride
 __global__ __launch_bounds__(kThreads) void benchaid_copy_kernel(const float4* __restrict__ src, float4* __restrict__ dst,
                                                                  size_t count4) {
@@ -134,6 +201,34 @@ int benchaid_mfma(int bf16, int toggle, int blocks, int iters, float* sink, doub
     hipLaunchKernelGGL(benchaid_mfma_kernel<true>, dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream, sink, iters);
   else
     hipLaunchKernelGGL(benchaid_mfma_kernel<false>, dim3((unsigned)blocks), dim3(kThreads), 0, (hipStream_t)stream, sink, iters);
+  return (int)hipGetLastError();
+}
+
+// Launches `blocks` blocks of the LDS-fed loop (iters x 16 instructions per wave, iters a multiple of 8).  staged != 0:
+// with the fetch of new operand words from src (DEVICE, src_count4 >= 8192 16-byte words, readable) into LDS every 64
+// instructions; src may be null otherwise.  sink: DEVICE, blocks*256 floats.  *flop (HOST, nullable) receives the
+// flop count.  Returns 0 or a hipError_t.
+int benchaid_mfma_lds(int staged, int blocks, int iters, float* sink, const void* src, int src_count4, double* flop,
+                      void* stream) {
+  if (blocks <= 0 || iters <= 0 || iters % 8 || !sink || (staged && (!src || src_count4 < 8192))) return (int)hipErrorInvalidValue;
+  if (flop) *flop = (double)blocks * 4 * iters * 16 * 4096.0;
+  const size_t lds = (size_t)kLdsFedFloats * sizeof(float);
+  static bool opted = false;
+  if (!opted) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(benchaid_mfma_lds_kernel<false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(benchaid_mfma_lds_kernel<true>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return (int)e;
+    opted = true;
+  }
+  if (staged)
+    hipLaunchKernelGGL(benchaid_mfma_lds_kernel<true>, dim3((unsigned)blocks), dim3(kThreads), lds, (hipStream_t)stream, sink,
+                       iters, (const float4*)src, src_count4);
+  else
+    hipLaunchKernelGGL(benchaid_mfma_lds_kernel<false>, dim3((unsigned)blocks), dim3(kThreads), lds, (hipStream_t)stream, sink,
+                       iters, (const float4*)nullptr, 8192);
   return (int)hipGetLastError();
 }
 

@@ -676,6 +676,22 @@ def test_benchaid_mfma_counts_its_flops_and_runs(bf16, per_instr):
         benchaid.mfma(bf16, blocks, 10, sink, toggle=True)  # not a multiple of eight
 
 
+@pytest.mark.parametrize("staged", [False, True])
+def test_benchaid_mfma_lds_counts_its_flops_and_runs(staged):
+    """The LDS-fed matrix-core loop of the benchmark's yardsticks: its flop count, a finite result, bad arguments."""
+    from paper_1501_07338_amd import benchaid
+    blocks, iters = 16, 24
+    sink = torch.full((blocks * 256,), float("nan"), device=DEV)
+    words = torch.ones(8192 * 4, device=DEV)
+    assert benchaid.mfma_lds(staged, blocks, iters, sink, words) == blocks * 4 * iters * 16 * 4096.0
+    assert np.all(np.isfinite(to_np(sink)))
+    with pytest.raises(RuntimeError):
+        benchaid.mfma_lds(staged, blocks, 10, sink, words)  # not a multiple of eight
+    if staged:
+        with pytest.raises(RuntimeError):
+            benchaid.mfma_lds(True, blocks, iters, sink, torch.ones(64, device=DEV))  # too few words to fetch from
+
+
 def test_benchaid_copy_copies():
     from paper_1501_07338_amd import benchaid
     src = torch.arange(1 << 20, dtype=torch.float32, device=DEV)
