@@ -613,3 +613,31 @@ def test_chain_store_hook_and_decision_overrides():
     r2 = train_step(tiny, {"x": x, "upstream": g}, p, decisions={"relu": {0: np.zeros((1, 1, 2, 2), dtype=bool)}})
     np.testing.assert_array_equal(r2["dacts"][0], np.zeros((1, 1, 2, 2)))             # every ReLU input taken as <= 0
     np.testing.assert_array_equal(r2["acts"][1], r0["acts"][1])                       # forward tensors untouched
+
+
+def _golden_shape_cases():
+    from pathlib import Path
+    cases = []
+    for line in (Path(__file__).parent / "golden" / "paper_shapes.txt").read_text().splitlines():
+        if line.strip() and not line.startswith("#"):
+            kind, cite, args, want = (f.strip() for f in line.split("|"))
+            cases.append(pytest.param(kind, args.split(), tuple(int(v) for v in want.split("x")), id=f"{kind}: {cite[:50]}"))
+    return cases
+
+
+@pytest.mark.parametrize("kind,args,want", _golden_shape_cases())
+def test_paper_shapes_fixture(kind, args, want):
+    """The shapes the paper states (tests/golden/paper_shapes.txt, each with its passage) come out of the oracle."""
+    dims = lambda t: tuple(int(v) for v in t.split("x"))
+    if kind == "conv":
+        (c, h, w), (k, r, s), ph, pw = dims(args[0]), dims(args[1]), int(args[2]), int(args[3])
+        if c * r * s * k * h * w > 2e8:  # the large layers: the output-shape rule alone (no arithmetic)
+            assert (k, h + 2 * ph - r + 1, w + 2 * pw - s + 1) == want
+        else:
+            assert O.conv_fwd(np.zeros((1, c, h, w)), np.zeros((k, c, r, s)), pad=(ph, pw)).shape[1:] == want
+    elif kind == "unroll":
+        (c, h, w), (r, s), batch = dims(args[0]), dims(args[1]), int(args[2])
+        assert O.im2col(np.zeros((batch, c, h, w)), (r, s)).shape == want
+    else:
+        (h, w), win, stride = dims(args[0]), int(args[1]), int(args[2])
+        assert O.maxpool_fwd(np.zeros((1, 1, h, w)), (win, win), (stride, stride))[0].shape[2:] == want
