@@ -103,3 +103,29 @@ def test_fused_and_layer_entry_points_validate_before_launch():
     # with an activation below, x is read for dx as well
     assert lib.vcnn_fc_bwd_act(vcnn.F32, 4, 8, 2, vcnn.ACT_RELU, None, fake, fake, None, None, fake, None) == vcnn.ERR_NULL
     assert lib.vcnn_fc_bwd_act(vcnn.F32, 0, 8, 2, vcnn.ACT_NONE, fake, fake, fake, None, None, fake, None) == vcnn.ERR_SHAPE
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+def test_workspace_queries_of_every_workload_layer(name):
+    """Route planning runs on the host: for every convolution of the five workloads, every pass, both storage types
+    and every forced route the query succeeds, agrees with itself, and stays below the explicit patch matrix plus its
+    partial sums (the largest realisation there is)."""
+    from paper_1501_07338_amd import workloads as wl
+    net = wl.make_net(name)
+    try:
+        for li, L in enumerate(net.layers):
+            if not isinstance(L, wl.Conv):
+                continue
+            n, c, h, w = net.in_shape(li)
+            _, k, oh, ow = net.shapes[li]
+            for dtype in (vcnn.F32, vcnn.BF16):
+                d = vcnn.conv_desc(n, c, h, w, k, L.kh, L.kw, L.pad_h, L.pad_w, dtype=dtype)
+                patch_matrix = 4 * c * L.kh * L.kw * n * oh * ow
+                for algo in (vcnn.ALGO_AUTO, vcnn.ALGO_EXPLICIT, vcnn.ALGO_IMPLICIT, vcnn.ALGO_FOLD, vcnn.ALGO_FFT):
+                    vcnn.set_conv_algo(algo)
+                    for p in (vcnn.PASS_FWD, vcnn.PASS_BWD_FILTER, vcnn.PASS_BWD_DATA):
+                        need = vcnn.conv_workspace_bytes(d, p)
+                        assert need == vcnn.conv_workspace_bytes(d, p)
+                        assert 0 <= need <= 3 * patch_matrix + (1 << 28), (name, li, dtype, algo, p, need)
+    finally:
+        vcnn.set_conv_algo(vcnn.ALGO_AUTO)
