@@ -116,8 +116,9 @@ def mark(name):
 mark.enabled = False
 
 
-def run_workload(name, steps, warmup, layer_iters=10):
-    """`name` is a workload, optionally suffixed `_bf16` for the bfloat16-storage variant."""
+def run_workload(name, steps, warmup, layer_iters=10, algos=None):
+    """`name` is a workload, optionally suffixed `_bf16` for the bfloat16-storage variant; algos: per-layer route
+    choices ({layer index: vcnn.ALGO_*}) for the step and the per-layer timings."""
     import torch
     from paper_1501_07338_amd import vcnn, workloads as wl
     from paper_1501_07338_amd.net import TrainStep
@@ -125,7 +126,8 @@ def run_workload(name, steps, warmup, layer_iters=10):
     bf16 = name.endswith("_bf16")
     net = wl.make_net(name[:-5] if bf16 else name)
     inputs, params = wl.make_inputs(net), wl.make_params(net)
-    ts = TrainStep(net, params, inputs, device="cuda:0", first_layer_dx=False, dtype=vcnn.BF16 if bf16 else vcnn.F32)
+    ts = TrainStep(net, params, inputs, device="cuda:0", first_layer_dx=False, dtype=vcnn.BF16 if bf16 else vcnn.F32,
+                   algos=algos)
     ts.snapshot()
     esize = 2.0 if bf16 else 4.0
     stream = torch.cuda.current_stream()
@@ -183,15 +185,16 @@ def run_workload(name, steps, warmup, layer_iters=10):
         flops = 2.0 * g["M"] * g["K"] * g["N"]
         dx_buf = ts.dacts[li] if li > 0 else torch.empty_like(a_in)
         y_buf = torch.empty_like(a_out)  # the forward pass is re-run into a spare buffer: the step's tensors stay as they are
+        routed = lambda call, li=li: ts._routed(li, call)  # the layer's own route choice, if it has one
         passes = {
-            "fwd": lambda: vcnn.conv_fwd(d, a_in, w, b, y_buf, ts.workspace),
-            "bwd_filter": lambda: vcnn.conv_bwd_filter(d, a_in, dy, dw, db, ts.workspace_side),
-            "bwd_data": lambda: vcnn.conv_bwd_data(d, w, dy, dx_buf, ts.workspace),
+            "fwd": lambda: routed(lambda: vcnn.conv_fwd(d, a_in, w, b, y_buf, ts.workspace)),
+            "bwd_filter": lambda: routed(lambda: vcnn.conv_bwd_filter(d, a_in, dy, dw, db, ts.workspace_side)),
+            "bwd_data": lambda: routed(lambda: vcnn.conv_bwd_data(d, w, dy, dx_buf, ts.workspace)),
         }
         in_b = esize * g["n"] * g["c"] * g["h"] * g["w"]
         out_b = esize * g["M"] * g["N"]
         w_b = esize * g["M"] * g["K"]
-        ws_need = max(vcnn.conv_workspace_bytes(d, p) for p in (vcnn.PASS_FWD, vcnn.PASS_BWD_DATA))
+        ws_need = routed(lambda: max(vcnn.conv_workspace_bytes(d, p) for p in (vcnn.PASS_FWD, vcnn.PASS_BWD_DATA)))
         assert ts.workspace.numel() >= ws_need
         for pname, fn in passes.items():
             mark(f"{name}.conv{li}.{pname}")
@@ -335,6 +338,26 @@ def fourier_comparison(stream):
         rows.append(row)
     torch.cuda.empty_cache()
     return rows
+
+
+def split_products_comparison(steps, warmup, default_res):
+    """The same cfg5 training step with VCNN_ALGO_SPLIT: the float products of the forward pass and of the kernel
+    gradient as sums of six bfloat16 products each (every float operand is exactly a sum of three bfloat16 terms; the
+    three smallest term products lie below float rounding).  On request only - the headline is the float
+    matrix-core path; this row shows what the chip's bfloat16 rate buys at float accuracy."""
+    from paper_1501_07338_amd import vcnn
+    # the large layer only (c3: 383 GFLOP per pass, contraction 9728): on the smaller layers six passes of the bf16
+    # kernels cost more than one of the float kernel
+    res = run_workload("cfg5", steps, warmup, layer_iters=5, algos={2: vcnn.ALGO_SPLIT})
+    passes = {(l["layer"], l["pass"]): l["ms"] for l in res["conv_layers"]}
+    base = {(l["layer"], l["pass"]): l["ms"] for l in default_res["conv_layers"]}
+    return {"what": "cfg5 step with VCNN_ALGO_SPLIT on the 16x16x512 layer (opt-in): its fp32 forward and kernel-gradient "
+                    "products as six bf16 matrix-core products each, fp32 accumulate; everything else as in the headline",
+            "ms_per_step": res["ms_per_step"], "images_per_s": res["images_per_s"], "launch": res["launch"],
+            "loss_first_step": res["loss_first_step"],
+            "loss_rel_diff_to_default": abs(res["loss_first_step"] - default_res["loss_first_step"]) / abs(default_res["loss_first_step"]),
+            "conv_ms_split_vs_default": {f"{k[0]}.{k[1]}": [passes[k], base[k]] for k in passes
+                                         if k in base and abs(passes[k] - base[k]) > 0.1 * base[k]}}
 
 
 def aids(stream):
@@ -495,6 +518,8 @@ def main():
         detail["hbm_kernels"] = hbm_kernels(stream)
         detail["yardsticks"] = aids(stream)
         detail["fourier_comparison"] = fourier_comparison(stream)
+        if args.workload == "cfg5":
+            detail["split_products"] = split_products_comparison(args.steps, args.warmup, main_res)
     if not args.no_sweep:
         detail["batch_sweep"] = batch_sweep(stream)
 
@@ -527,6 +552,8 @@ def main():
                              "mfma_bf16_changing_operands_tflops": detail["yardsticks"]["mfma_bf16"]["sustained_tflops_changing_operands"],
                              "copy_1GiB_gbs": detail["yardsticks"]["copy_1GiB"]["gbs"]}
         out["fourier_comparison"] = [[r["layer"], r["unroll_ms"], r["fourier_ms"]] for r in detail["fourier_comparison"]]
+    if "split_products" in detail:
+        out["split_products"] = detail["split_products"]
     if "batch_sweep" in detail:  # [workload, batch, training images/s, forward-only images/s]
         out["batch_sweep"] = [[r["workload"], r["batch"], r["train_images_per_s"], r["forward_images_per_s"]]
                               for r in detail["batch_sweep"]]

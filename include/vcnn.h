@@ -58,8 +58,13 @@ enum { VCNN_PASS_FWD = 0, VCNN_PASS_BWD_FILTER = 1, VCNN_PASS_BWD_DATA = 2 };
  * patch-matrix gradient on chip (AUTO uses that route only where it is the fastest).  FFT is AUTO except that the
  * forward pass of layers with one-dimensional kernels (r x 1 or 1 x s, at least 8 taps, no padding across the
  * kernel) goes through the Fourier domain - the alternative the paper's related-work paragraph names ("FFT
- * speedup"), kept as a comparison: AUTO never takes it. */
-enum { VCNN_ALGO_AUTO = 0, VCNN_ALGO_EXPLICIT = 1, VCNN_ALGO_IMPLICIT = 2, VCNN_ALGO_FOLD = 3, VCNN_ALGO_FFT = 4 };
+ * speedup"), kept as a comparison: AUTO never takes it.  SPLIT is AUTO except that the forward pass and the kernel
+ * gradient of fp32 layers with more than 4 maps and channels compute their products (Eq. 1 / Eq. 2) as sums of
+ * bfloat16 products: every float operand is, exactly, a sum of three bfloat16 terms, and the six largest of the nine
+ * term products, accumulated in float, carry the product to within float rounding.  The result stays within the
+ * float tolerance; the matrix cores multiply bfloat16 sixteen times as fast as float.  AUTO never takes it. */
+enum { VCNN_ALGO_AUTO = 0, VCNN_ALGO_EXPLICIT = 1, VCNN_ALGO_IMPLICIT = 2, VCNN_ALGO_FOLD = 3, VCNN_ALGO_FFT = 4,
+       VCNN_ALGO_SPLIT = 5 };
 
 typedef struct {
   int32_t n, c, h, w;                         /* input: batch, channels, height, width */
@@ -82,7 +87,7 @@ const char* vcnn_last_error(void);
 /* Library version as major*10000 + minor*100 + patch. */
 int32_t vcnn_version(void);
 /* Process-wide choice of VCNN_ALGO_* for the convolution calls (default AUTO).  Returns VCNN_ERR_UNSUPPORTED
- * for an unknown value.  Meant for A/B measurements; both choices compute the same function. */
+ * for an unknown value.  Meant for A/B measurements; every choice computes the same function. */
 vcnn_status vcnn_set_conv_algo(int32_t algo);
 
 /* Output size of the layer of Eq. 1: oh = (h + 2*pad_h - r)/stride_h + 1, likewise ow. */

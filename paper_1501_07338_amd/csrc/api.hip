@@ -102,7 +102,7 @@ static bool fold_beats_halo(const ConvGeom& g, const HaloPlan& hp, const FoldPla
 
 // Which realisation a pass uses for a given shape.  The same decision drives the workspace query and
 // the launch, so the two always agree.
-enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER, PATH_HALO, PATH_HALO_FILTER, PATH_HALO_BF16, PATH_FILTER_BF16, PATH_HALO_FILTER_BF16, PATH_FEW_COLS_FILTER, PATH_SMALL, PATH_SMALL_BWD, PATH_FOLD, PATH_FFT, PATH_TAPS, PATH_POINTWISE_BF16 };
+enum Path { PATH_EXPLICIT, PATH_POINTWISE, PATH_FEW_OUT, PATH_FEW_IN, PATH_DIRECT_FILTER, PATH_HALO, PATH_HALO_FILTER, PATH_HALO_BF16, PATH_FILTER_BF16, PATH_HALO_FILTER_BF16, PATH_FEW_COLS_FILTER, PATH_SMALL, PATH_SMALL_BWD, PATH_FOLD, PATH_FFT, PATH_TAPS, PATH_POINTWISE_BF16, PATH_SPLIT };
 struct Plan {
   Path path;
   DirectGeom dg;
@@ -116,6 +116,7 @@ struct Plan {
   FftPlan fft;
   PointwiseBf16Plan pwb;
   PointwiseFilterBf16Plan pwf;
+  SplitPlan sp;
   int split;        // channel slices (few-out), output-map group size (few-in) or batch slices (filter gradient)
   size_t partial_bytes;
   size_t workspace_bytes;
@@ -128,7 +129,16 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
   const int algo = g_conv_algo.load();
   const bool allow_direct = algo != VCNN_ALGO_EXPLICIT;
   // FOLD only re-routes the input gradient, FFT only the forward pass of layers with one-dimensional kernels
-  const bool automatic = algo == VCNN_ALGO_AUTO || algo == VCNN_ALGO_FOLD || algo == VCNN_ALGO_FFT;
+  const bool automatic = algo == VCNN_ALGO_AUTO || algo == VCNN_ALGO_FOLD || algo == VCNN_ALGO_FFT || algo == VCNN_ALGO_SPLIT;
+  if (algo == VCNN_ALGO_SPLIT && dtype == VCNN_F32 && pass != VCNN_PASS_BWD_DATA && conv_split_plan(g, pass, &p.sp)) {
+    p.path = PATH_SPLIT;  // float products as sums of bfloat16 products
+    p.workspace_bytes = align256(p.sp.workspace_bytes);
+    if (pass == VCNN_PASS_BWD_FILTER) {
+      p.bias_offset = p.workspace_bytes;
+      p.workspace_bytes += align256(bias_grad_partial_bytes(g));
+    }
+    return p;
+  }
   if (algo == VCNN_ALGO_FFT && pass == VCNN_PASS_FWD && conv_fft_plan(g, &p.fft)) {
     p.path = PATH_FFT;
     p.workspace_bytes = p.fft.xf_bytes + p.fft.wf_bytes + p.fft.yf_bytes;
@@ -299,7 +309,7 @@ int32_t vcnn_version(void) { return 100; }
 
 vcnn_status vcnn_set_conv_algo(int32_t algo) {
   if (algo != VCNN_ALGO_AUTO && algo != VCNN_ALGO_EXPLICIT && algo != VCNN_ALGO_IMPLICIT && algo != VCNN_ALGO_FOLD &&
-      algo != VCNN_ALGO_FFT)
+      algo != VCNN_ALGO_FFT && algo != VCNN_ALGO_SPLIT)
     return fail(VCNN_ERR_UNSUPPORTED, "unknown conv algorithm %d", algo);
   g_conv_algo.store(algo);
   return VCNN_OK;
@@ -371,6 +381,8 @@ static vcnn_status conv_fwd_linear(const vcnn_conv_desc* d, const ConvGeom& g, c
                                  bias, y, relu, workspace, st);
   }
   if (plan.path == PATH_FFT) return launch_conv_fft(plan.fft, dt, g, x, w, bias, y, relu, workspace, st);
+  if (plan.path == PATH_SPLIT)
+    return launch_conv_split_fwd(plan.sp, g, (const float*)x, (const float*)w, bias, (float*)y, relu, workspace, st);
   // (its 16-byte reads of the kernel matrix need that alignment; a matrix placed otherwise takes the generic product)
   const bool pointwise_bf16 = plan.path == PATH_POINTWISE_BF16 && (reinterpret_cast<uintptr_t>(w) & 15) == 0;
   if (pointwise_bf16) return launch_pointwise_bf16(plan.pwb, g.n, g.k, g.c, (int)g.P, w, x, bias, y, relu, st);
@@ -411,6 +423,8 @@ vcnn_status vcnn_conv_bwd_filter(const vcnn_conv_desc* d, const void* x, const v
   } else if (plan.path == PATH_FEW_COLS_FILTER) {
     if (vcnn_status s = launch_filter_grad_few_cols(plan.fcp, dt, g, x, dy, dw, dbias, (float*)workspace, st)) return s;
     if (plan.fcp.bias_column) return VCNN_OK;  // the bias gradient came out of the same product
+  } else if (plan.path == PATH_SPLIT) {
+    if (vcnn_status s = launch_conv_split_filter(plan.sp, g, (const float*)x, (const float*)dy, dw, workspace, st)) return s;
   } else if (plan.path == PATH_POINTWISE_BF16) {
     if (vcnn_status s = launch_pointwise_filter_bf16(plan.pwf, g, x, dy, dw, (float*)workspace, st)) return s;
   } else if (plan.path == PATH_HALO_FILTER_BF16) {

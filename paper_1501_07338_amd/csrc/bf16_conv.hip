@@ -113,6 +113,8 @@ struct HaloBf16Args {
   const uint4* wf;    // [mt][chunk][step][64 lanes] fragments
   const float* bias;  // [m] or null
   bf16* y;            // [n][m][oh][ow]
+  float* y32;         // not null: the result goes here instead, in float, added to what is there when `accumulate`
+  int accumulate;
   int n, h, w, m, r, s, ph, pw, oh, ow, P;
   int tiles_m, tiles_per_img;
   int cg, cgc, nchunks;
@@ -335,9 +337,12 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
         const int i = i0 + mi * TILE + (M16 ? 4 * half + q : 8 * (q >> 2) + 4 * half + (q & 3));
         if (i < a.m) {
           float v = acc[mi][ni][q];
+          const int64_t at = ((int64_t)n * a.m + i) * a.P + p;
+          if (a.y32 && a.accumulate) v += a.y32[at];
           if (a.bias) v += a.bias[i];
           if (a.relu) v = fmaxf(v, 0.f);
-          st(a.y + ((int64_t)n * a.m + i) * a.P + p, v);
+          if (a.y32) a.y32[at] = v;
+          else st(a.y + at, v);
         }
       }
   }
@@ -451,11 +456,19 @@ static void launch_tn(const HaloBf16Args& a, int waves_m, int waves_n, int tm, s
 
 vcnn_status launch_conv_halo_bf16(const HaloBf16Plan& p, int n, int c, int h, int w, int m, int r, int s, int ph, int pw,
                                   const void* x, const void* wgt, int64_t w_so, int64_t w_si, int flip, const float* bias,
-                                  void* y, int relu, void* workspace, hipStream_t st) {
-  uint4* x8 = (uint4*)workspace;
-  bf16* wf = (bf16*)((char*)workspace + p.x8_bytes);
+                                  void* y, int relu, void* workspace, hipStream_t st, float* y32, int accumulate) {
+  return launch_conv_halo_bf16_prepared(p, n, c, h, w, m, r, s, ph, pw, x, wgt, w_so, w_si, flip, bias, y, relu, workspace,
+                                        (char*)workspace + p.x8_bytes, st, y32, accumulate);
+}
+
+vcnn_status launch_conv_halo_bf16_prepared(const HaloBf16Plan& p, int n, int c, int h, int w, int m, int r, int s, int ph,
+                                           int pw, const void* x, const void* wgt, int64_t w_so, int64_t w_si, int flip,
+                                           const float* bias, void* y, int relu, void* x8_buf, void* wf_buf, hipStream_t st,
+                                           float* y32, int accumulate) {
+  uint4* x8 = (uint4*)x8_buf;
+  bf16* wf = (bf16*)wf_buf;
   const int rs = r * s;
-  {
+  if (x) {
     const int64_t total = (int64_t)n * p.cg * h * w;
     hipLaunchKernelGGL(interleave_channels_kernel, dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, st,
                        (const bf16*)x, x8, c, p.cg, h * w, total);
@@ -464,7 +477,7 @@ vcnn_status launch_conv_halo_bf16(const HaloBf16Plan& p, int n, int c, int h, in
   const int tile = p.m16 ? 16 : 32;
   const int bm = tile * p.tm * p.waves_m;
   const int tiles_m = (int)ceil_div(m, bm);
-  {
+  if (wgt) {
     const int steps = p.uch / 8 * (p.m16 ? 2 : 4);
     const int64_t total = (int64_t)tiles_m * (bm / tile) * p.nchunks * steps * 512;
     hipLaunchKernelGGL(reorder_weights_frag_kernel, dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, st,
@@ -473,6 +486,7 @@ vcnn_status launch_conv_halo_bf16(const HaloBf16Plan& p, int n, int c, int h, in
   }
   HaloBf16Args a{};
   a.x8 = x8, a.zero = x8 + (int64_t)n * p.cg * h * w, a.wf = (const uint4*)wf, a.bias = bias, a.y = (bf16*)y;
+  a.y32 = y32, a.accumulate = accumulate;
   a.n = n, a.h = h, a.w = w, a.m = m, a.r = r, a.s = s, a.ph = ph, a.pw = pw;
   a.oh = h + 2 * ph - r + 1, a.ow = w + 2 * pw - s + 1;
   a.P = a.oh * a.ow;
@@ -811,26 +825,33 @@ static void launch_filter_tn(const FilterBf16Args& a, int waves_m, int tm, unsig
 }
 
 vcnn_status launch_filter_grad_bf16(const FilterGradBf16Plan& p, const ConvGeom& g0, const void* x, const void* dy,
-                                    float* dw, void* workspace, hipStream_t st) {
+                                    float* dw, void* workspace, hipStream_t st, int accumulate) {
+  return launch_filter_grad_bf16_prepared(p, g0, x, dy, dw, workspace, (char*)workspace + p.x8n_bytes,
+                                          (float*)((char*)workspace + p.x8n_bytes + p.dyf_bytes), st, accumulate);
+}
+
+vcnn_status launch_filter_grad_bf16_prepared(const FilterGradBf16Plan& p, const ConvGeom& g0, const void* x, const void* dy,
+                                             float* dw, void* x8n_buf, void* dyf_buf, float* partial, hipStream_t st,
+                                             int accumulate) {
   const ConvGeom g = flatten_pointwise(g0);
-  uint4* x8n = (uint4*)workspace;
-  uint4* dyf = (uint4*)((char*)workspace + p.x8n_bytes);
-  float* partial = (float*)((char*)workspace + p.x8n_bytes + p.dyf_bytes);
+  uint4* x8n = (uint4*)x8n_buf;
+  uint4* dyf = (uint4*)dyf_buf;
   const int64_t chw = (int64_t)g.c * g.h * g.w;
-  {
+  if (x) {
     const int64_t total = (int64_t)p.ngroups * chw;
     hipLaunchKernelGGL(interleave_images_kernel, dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, st,
                        (const bf16*)x, x8n, g.n, chw, total);
     if (vcnn_status e = check_launch("interleave_images")) return e;
   }
-  {
+  if (dy) {
     const int64_t total = (int64_t)p.ngroups * p.mt_total * 32 * p.runs * p.uch;
     hipLaunchKernelGGL(dy_fragments_kernel, dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, st,
                        (const bf16*)dy, dyf, g.n, (int)g.M, (int)g.P, p.mt_total, p.runs, p.bp, p.uch, total);
     if (vcnn_status e = check_launch("dy_fragments")) return e;
   }
   FilterBf16Args a{};
-  a.x8n = x8n, a.zero = x8n + (int64_t)p.ngroups * chw, a.dyf = dyf, a.out = p.splits > 1 ? partial : dw;
+  // accumulate: dw += the product (the slice sum takes dw as its addend); the workspace then holds at least one slice
+  a.x8n = x8n, a.zero = x8n + (int64_t)p.ngroups * chw, a.dyf = dyf, a.out = (p.splits > 1 || accumulate) ? partial : dw;
   a.c = g.c, a.h = g.h, a.w = g.w, a.m = g.k, a.r = g.r, a.s = g.s, a.ph = g.ph, a.pw = g.pw, a.oh = g.oh, a.ow = g.ow;
   a.K = (int)g.K;
   a.tiles_m = (int)ceil_div(g.M, 32 * p.tm * p.waves_m), a.mt_total = p.mt_total;
@@ -842,7 +863,9 @@ vcnn_status launch_filter_grad_bf16(const FilterGradBf16Plan& p, const ConvGeom&
   else if (p.tn == 4) launch_filter_tn<4>(a, p.waves_m, p.tm, tiles, (unsigned)p.splits, p.lds_bytes, st);
   else launch_filter_tn<5>(a, p.waves_m, p.tm, tiles, (unsigned)p.splits, p.lds_bytes, st);
   if (vcnn_status e = check_launch("filter_grad_bf16")) return e;
-  if (p.splits == 1) return VCNN_OK;
+  if (p.splits == 1 && !accumulate) return VCNN_OK;
+  if (accumulate)  // "bias" of element i = dw[i]
+    return launch_sum_slices(partial, dw, dw, VCNN_F32, g.M * g.K, p.splits, 1, (int)(g.M * g.K), 0, st);
   return launch_sum_slices(partial, nullptr, dw, VCNN_F32, g.M * g.K, p.splits, 1, 1, 0, st);
 }
 

@@ -185,7 +185,14 @@ bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph
 // x8_bytes + wf_bytes
 vcnn_status launch_conv_halo_bf16(const HaloBf16Plan& p, int n, int c, int h, int w, int m, int r, int s, int ph, int pw,
                                   const void* x, const void* wgt, int64_t w_so, int64_t w_si, int flip, const float* bias,
-                                  void* y, int relu, void* workspace, hipStream_t st);
+                                  void* y, int relu, void* workspace, hipStream_t st, float* y32 = nullptr,
+                                  int accumulate = 0);  // y32: float result (added to its contents when accumulate) instead of y
+// The same with the two re-laid operands in buffers of the caller (x8_bytes, wf_bytes); a null x or wgt means that its
+// buffer already holds that operand from an earlier call.
+vcnn_status launch_conv_halo_bf16_prepared(const HaloBf16Plan& p, int n, int c, int h, int w, int m, int r, int s, int ph,
+                                           int pw, const void* x, const void* wgt, int64_t w_so, int64_t w_si, int flip,
+                                           const float* bias, void* y, int relu, void* x8_buf, void* wf_buf, hipStream_t st,
+                                           float* y32, int accumulate);
 struct FilterGradBf16Plan {
   int waves_m, tm, tn;
   int ccs, nr, wp;   // channels, rows and row pitch of the halo tile
@@ -198,8 +205,28 @@ struct FilterGradBf16Plan {
 };
 bool filter_grad_bf16_plan(const ConvGeom& g, FilterGradBf16Plan* p);
 // workspace: x8n_bytes + dyf_bytes + partial_bytes
+// accumulate: dw += the product; the workspace then needs max(partial_bytes, one slice of M*K floats) behind dyf
 vcnn_status launch_filter_grad_bf16(const FilterGradBf16Plan& p, const ConvGeom& g, const void* x, const void* dy,
-                                    float* dw, void* workspace, hipStream_t st);
+                                    float* dw, void* workspace, hipStream_t st, int accumulate = 0);
+// The same with the re-laid operands in buffers of the caller (x8n_bytes, dyf_bytes; null x or dy: already there) and
+// the slices in `partial`.
+vcnn_status launch_filter_grad_bf16_prepared(const FilterGradBf16Plan& p, const ConvGeom& g, const void* x, const void* dy,
+                                             float* dw, void* x8n_buf, void* dyf_buf, float* partial, hipStream_t st,
+                                             int accumulate);
+
+// ---- split_bf16.hip: fp32 products of large layers as sums of bf16 products (on request only) ------------------------
+struct SplitPlan {
+  HaloBf16Plan fwd;
+  FilterGradBf16Plan filter;
+  size_t part_x_bytes, part_w_bytes, part_dy_bytes;  // one bf16 term of x, of w, of dy
+  size_t inner_bytes;                                // workspace of the bf16 kernel
+  size_t workspace_bytes;
+};
+bool conv_split_plan(const ConvGeom& g, int pass, SplitPlan* p);
+vcnn_status launch_conv_split_fwd(const SplitPlan& p, const ConvGeom& g, const float* x, const float* w, const float* bias,
+                                  float* y, int relu, void* workspace, hipStream_t st);
+vcnn_status launch_conv_split_filter(const SplitPlan& p, const ConvGeom& g, const float* x, const float* dy, float* dw,
+                                     void* workspace, hipStream_t st);
 bool bwd_filter_bf16_plan(const ConvGeom& g, BwdFilterBf16Plan* p);
 vcnn_status launch_bwd_filter_bf16(const BwdFilterBf16Plan& p, const ConvGeom& g, const void* x, const void* dy, float* dw,
                                    void* workspace, hipStream_t st);

@@ -23,8 +23,11 @@ class TrainStep:
     """Device-resident state of one network: parameters, activations, gradients, workspace."""
 
     def __init__(self, net: Net, params: list, inputs: dict, device: str = "cuda:0", first_layer_dx: bool = False,
-                 dtype: int = vcnn.F32, overlap: bool = True):
+                 dtype: int = vcnn.F32, overlap: bool = True, algos: Optional[dict] = None):
+        """algos: {layer index: vcnn.ALGO_*} - convolutions named there are planned and launched under that route
+        choice, the others under the process-wide one."""
         self.net, self.dev, self.dtype = net, torch.device(device), dtype
+        self.algos = dict(algos or {})
         self.first_layer_dx = first_layer_dx
         self.side = torch.cuda.Stream(self.dev) if overlap else None  # default priority
         f32 = dict(dtype=torch.float32, device=self.dev)
@@ -59,9 +62,10 @@ class TrainStep:
                                    dtype=dtype, act=vcnn.ACT_RELU if L.relu else vcnn.ACT_NONE)
                 self.descs[li] = d
                 # (a first layer's filter gradient has no input gradient to overlap with and runs on the main stream)
-                ws_bytes = max(ws_bytes, *(vcnn.conv_workspace_bytes(d, p)
-                                           for p in (vcnn.PASS_FWD, vcnn.PASS_BWD_DATA, vcnn.PASS_BWD_FILTER)))
-                ws_side_bytes = max(ws_side_bytes, vcnn.conv_workspace_bytes(d, vcnn.PASS_BWD_FILTER))
+                need = self._routed(li, lambda: [vcnn.conv_workspace_bytes(d, p)
+                                                 for p in (vcnn.PASS_FWD, vcnn.PASS_BWD_DATA, vcnn.PASS_BWD_FILTER)])
+                ws_bytes = max(ws_bytes, *need)
+                ws_side_bytes = max(ws_side_bytes, need[2])
             elif isinstance(L, Pool):
                 self.descs[li] = vcnn.pool_desc(ishape[0], ishape[1], ishape[2], ishape[3], L.win, L.win, L.stride,
                                                 L.stride, dtype=dtype)
@@ -105,6 +109,18 @@ class TrainStep:
         L = self.net.layers[li]
         return li > 0 and getattr(self.net.layers[li - 1], "relu", False) and isinstance(L, (Pool, FC))
 
+    def _routed(self, li, call):
+        """call() under the route choice given for layer li (the process-wide choice is put back afterwards)."""
+        algo = self.algos.get(li)
+        if algo is None:
+            return call()
+        before = vcnn.conv_algo()
+        vcnn.set_conv_algo(algo)
+        try:
+            return call()
+        finally:
+            vcnn.set_conv_algo(before)
+
     # ---- one pass each ---------------------------------------------------------------------------
     def forward(self, stream=None):
         net = self.net
@@ -112,7 +128,7 @@ class TrainStep:
             a_in, a_out = self.acts[li], self.acts[li + 1]
             if isinstance(L, Conv):
                 w, b = self.weights(li), self.params[li][1]
-                vcnn.conv_fwd(self.descs[li], a_in, w, b, a_out, self.workspace, stream)
+                self._routed(li, lambda: vcnn.conv_fwd(self.descs[li], a_in, w, b, a_out, self.workspace, stream))
             elif isinstance(L, Pool):
                 vcnn.pool_fwd(self.descs[li], a_in, a_out, self.argmax[li], stream)
             else:
@@ -169,15 +185,15 @@ class TrainStep:
                                 dx_out if need_dx else None, main)
                 continue
             if not need_dx:  # nothing to overlap with
-                vcnn.conv_bwd_filter(self.descs[li], a_in, d, dw, db, self.workspace, main)
+                self._routed(li, lambda: vcnn.conv_bwd_filter(self.descs[li], a_in, d, dw, db, self.workspace, main))
                 continue
             if side is not main:  # fork: the parameter-gradient strand starts once d is complete
                 self.forked[li].record(main)
                 side.wait_event(self.forked[li])
             # the input gradient first: the chain below waits for it, and a kernel-gradient block that is already
             # resident can leave no LDS for it
-            vcnn.conv_bwd_data(self.descs[li], w, d, self.dacts[li], self.workspace, main)
-            vcnn.conv_bwd_filter(self.descs[li], a_in, d, dw, db, self.workspace_side, side)
+            self._routed(li, lambda: vcnn.conv_bwd_data(self.descs[li], w, d, self.dacts[li], self.workspace, main))
+            self._routed(li, lambda: vcnn.conv_bwd_filter(self.descs[li], a_in, d, dw, db, self.workspace_side, side))
         if side is not main:  # join before anything reads the parameter gradients
             main.wait_stream(side)
 

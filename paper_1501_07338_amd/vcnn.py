@@ -18,7 +18,7 @@ F32, BF16 = 0, 1
 ACT_NONE, ACT_RELU, ACT_TANH, ACT_SIGMOID = 0, 1, 2, 3
 POOL_MAX, POOL_AVG = 0, 1
 PASS_FWD, PASS_BWD_FILTER, PASS_BWD_DATA = 0, 1, 2
-ALGO_AUTO, ALGO_EXPLICIT, ALGO_IMPLICIT, ALGO_FOLD, ALGO_FFT = 0, 1, 2, 3, 4
+ALGO_AUTO, ALGO_EXPLICIT, ALGO_IMPLICIT, ALGO_FOLD, ALGO_FFT, ALGO_SPLIT = 0, 1, 2, 3, 4, 5
 
 
 class ConvDesc(Structure):
@@ -133,8 +133,18 @@ def last_error() -> str:
     return lib().vcnn_last_error().decode()
 
 
+_conv_algo = ALGO_AUTO  # what this binding last set (the library keeps the choice process-wide and has no getter)
+
+
 def set_conv_algo(algo: int) -> None:
+    global _conv_algo
     _check(lib().vcnn_set_conv_algo(algo))
+    _conv_algo = algo
+
+
+def conv_algo() -> int:
+    """The route choice last made through set_conv_algo (AUTO at start)."""
+    return _conv_algo
 
 
 def conv_out_shape(d: ConvDesc):

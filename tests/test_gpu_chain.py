@@ -122,10 +122,17 @@ def argmax_mismatches_are_near_ties(gpu_am, ref_am, x_ref):
     return len(bad)
 
 
-@pytest.mark.parametrize("name,batch", CASES)
-def test_end_to_end_training_step(name, batch):
+# cfg5's 16 x 16 x 512 layer and cfg4's 512-map layer as six bfloat16 products per float product (VCNN_ALGO_SPLIT)
+SPLIT_CASES = [("cfg5", 1, {2: vcnn.ALGO_SPLIT}), ("cfg4", 4, {1: vcnn.ALGO_SPLIT})]
+
+
+@pytest.mark.parametrize("name,batch,algos", [(n, b, None) for n, b in CASES] + SPLIT_CASES)
+def test_end_to_end_training_step(name, batch, algos):
     net, inputs, params, ref = reference(name, batch)
-    ts = TrainStep(net, params, inputs, device=DEV, first_layer_dx=True)
+    ts = TrainStep(net, params, inputs, device=DEV, first_layer_dx=True, algos=algos)
+    for li in algos or {}:  # the named layers really are planned under that route: its workspace need is another
+        query = lambda: vcnn.conv_workspace_bytes(ts.descs[li], vcnn.PASS_FWD)
+        assert ts._routed(li, query) != query()
     before = [None if p is None else (to_np(p[0]).copy(), to_np(p[1]).copy()) for p in ts.params]
     ts.step()
     torch.cuda.synchronize()
@@ -174,8 +181,9 @@ def test_end_to_end_training_step(name, batch):
     if net.loss != "upstream":
         assert abs(float(to_np(ts.loss)) - ref["loss"]) <= TOL_F32 * abs(ref["loss"])
     # run-to-run bit identity of a full step from the same state
-    ts2 = TrainStep(net, params, inputs, device=DEV, first_layer_dx=True)
+    ts2 = TrainStep(net, params, inputs, device=DEV, first_layer_dx=True, algos=algos)
     ts2.step()
+    assert vcnn.conv_algo() == vcnn.ALGO_AUTO  # a per-layer route choice leaves the process-wide one alone
     for li in range(len(net.layers)):
         if ts.grads[li] is not None:
             np.testing.assert_array_equal(to_np(ts.grads[li][0]), to_np(ts2.grads[li][0]))
@@ -289,3 +297,31 @@ def test_launch_schedules_agree_bit_for_bit_at_full_size(name, bf16):
         torch.cuda.synchronize()
         assert np.isfinite(torch.randn(1 << 16, device=DEV).sum().item())  # unrelated eager work between replays
         same(rep, two, f"replay {replay} vs two streams")
+
+
+def test_step_with_split_products_on_the_large_layer():
+    """cfg5 at its stated batch with VCNN_ALGO_SPLIT on the 16 x 16 x 512 layer only (the per-layer route choice of
+    TrainStep) beside the step on the float kernels: every activation and the loss within a tenth of the fp32 bar, the
+    HIP-graph replay bit-identical to the eager step, and the process-wide route choice untouched.  (Gradients are
+    held to the oracle's at batch 1 by the end-to-end test: at this size each passes through ReLU and max-pooling
+    decisions that a last-bit change of an activation may flip, so two valid steps need not agree element by element.)"""
+    net = wl.make_net("cfg5")
+    inputs, params = wl.make_inputs(net), wl.make_params(net)
+    base = TrainStep(net, params, inputs, device=DEV)
+    split = TrainStep(net, params, inputs, device=DEV, algos={2: vcnn.ALGO_SPLIT})
+    assert split.workspace.numel() > base.workspace.numel()  # the route is planned for that layer
+    base.step()
+    split.snapshot()
+    graph = split.capture()  # one eager step, then the recording
+    torch.cuda.synchronize()
+    assert vcnn.conv_algo() == vcnn.ALGO_AUTO
+    for li in range(len(net.layers)):
+        a, b = split.acts[li + 1].double(), base.acts[li + 1].double()
+        assert float((a - b).abs().max() / b.abs().max()) <= 0.1 * TOL_F32, f"act {li}"
+    assert abs(float(split.loss) - float(base.loss)) <= 0.1 * TOL_F32 * abs(float(base.loss))
+    eager = [t.clone() for pair in split.grads if pair is not None for t in pair] + [split.loss.clone()]
+    split.restore()
+    graph.replay()
+    torch.cuda.synchronize()
+    again = [t for pair in split.grads if pair is not None for t in pair] + [split.loss]
+    assert all(torch.equal(a, b) for a, b in zip(eager, again))

@@ -183,6 +183,34 @@ def test_two_realisations_agree_on_the_whole_tensor(name, li):
         assert err <= TOL_F32, f"{name} conv{li} {what}: the two realisations differ by {err:.3e} (max-norm relative)"
 
 
+@pytest.mark.parametrize("name,li", [("cfg5", 2), ("cfg4", 1)])
+def test_split_products_agree_with_the_float_kernels_at_full_size(name, li):
+    """VCNN_ALGO_SPLIT (float products as six bfloat16 products) against the default float kernels, every element of
+    the forward result and of the kernel gradient at the stated size: a tenth of the fp32 bar."""
+    net, L, (n, c, h, w), (k, oh, ow), x, wt, b, dy, _ = layer_tensors(name, li, 5000, False)
+    d = vcnn.conv_desc(n, c, h, w, k, L.kh, L.kw, L.pad_h, L.pad_w, act=vcnn.ACT_RELU if L.relu else vcnn.ACT_NONE)
+    xd, wd, bd, dyd = to_dev(x), to_dev(wt), to_dev(b), to_dev(dy)
+    res = {}
+    try:
+        for algo in (vcnn.ALGO_AUTO, vcnn.ALGO_SPLIT):
+            vcnn.set_conv_algo(algo)
+            ws = torch.empty(max(256, *(vcnn.conv_workspace_bytes(d, p) for p in range(2))), dtype=torch.uint8, device=DEV)
+            y = torch.full((n, k, oh, ow), float("nan"), device=DEV)
+            dw = torch.full(wt.shape, float("nan"), device=DEV)
+            db = torch.full((k,), float("nan"), device=DEV)
+            vcnn.conv_fwd(d, xd, wd, bd, y, ws)
+            vcnn.conv_bwd_filter(d, xd, dyd, dw, db, ws)
+            torch.cuda.synchronize()
+            res[algo] = (y, dw, db)
+            del ws
+    finally:
+        vcnn.set_conv_algo(vcnn.ALGO_AUTO)
+    for what, a, e in zip(("y", "dw", "db"), res[vcnn.ALGO_SPLIT], res[vcnn.ALGO_AUTO]):
+        assert bool(torch.isfinite(a).all()) and bool(torch.isfinite(e).all())
+        err = float((a.double() - e.double()).abs().max() / e.double().abs().max())
+        assert err <= 0.1 * TOL_F32, f"{name} conv{li} {what}: split products differ from the float kernels by {err:.3e}"
+
+
 def test_unroll_full_size_properties():
     """phi_c and phi_c^{-1} at a large layer (cfg4 c2: 1600 x 262144 patch matrix): sampled entries
     are exact copies, and the adjoint identity holds."""

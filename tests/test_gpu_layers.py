@@ -652,6 +652,55 @@ def test_sgd_update_multi_with_empty_tensors_among_many(empty):
             assert_close(to_np(many[k]), O.sgd_update(before[k], to_np(grads[k]), 0.5), 1e-6, f"sgd tensor {k} of 40")
 
 
+SPLIT_SHAPES = [
+    (3, 12, 19, 23, 37, 3, 5, 1, 2),    # ragged everything, 33..48 maps
+    (2, 20, 12, 12, 50, 5, 5, 0, 0),
+    (4, 33, 10, 10, 40, 1, 1, 0, 0),    # 1 x 1
+    (3, 7, 13, 11, 130, 3, 3, 1, 1),    # many maps
+    (9, 16, 16, 16, 64, 5, 5, 2, 2),    # a batch that is not a multiple of the 8-image groups of the kernel gradient
+    (2, 38, 30, 30, 96, 16, 16, 0, 0),  # the shape class of the deconvolution network's large layer
+]
+
+
+@pytest.mark.parametrize("shape", SPLIT_SHAPES)
+def test_conv_split_products_route(shape):
+    """VCNN_ALGO_SPLIT: the float products of the forward pass and of the kernel gradient as six bfloat16 products each.
+    The result must hold the float tolerance - and by a wide margin, the dropped terms lying below float rounding."""
+    n, c, h, w, k, r, s, ph, pw = shape
+    x = random_tensor(2600, (n, c, h, w))
+    wt = random_tensor(2601, (k, c, r, s), scale=(2.0 / (c * r * s)) ** 0.5)
+    b = random_tensor(2602, (k,), scale=0.1)
+    oh, ow = h + 2 * ph - r + 1, w + 2 * pw - s + 1
+    dy = random_tensor(2603, (n, k, oh, ow))
+    xd, wd, bd, dyd = (torch.from_numpy(a).to(DEV) for a in (x, wt, b, dy))
+    d = vcnn.conv_desc(n, c, h, w, k, r, s, ph, pw, act=vcnn.ACT_RELU)
+    sizes = {}
+    try:
+        for name, algo in (("auto", vcnn.ALGO_AUTO), ("split", vcnn.ALGO_SPLIT)):
+            vcnn.set_conv_algo(algo)
+            sizes[name] = [vcnn.conv_workspace_bytes(d, p) for p in range(3)]
+        assert sizes["split"][0] != sizes["auto"][0] and sizes["split"][1] != sizes["auto"][1]  # the route is taken
+        assert sizes["split"][2] == sizes["auto"][2]  # the input gradient is not re-routed
+        ws = torch.empty(max(256, *sizes["split"]), dtype=torch.uint8, device=DEV)
+        y = torch.full((n, k, oh, ow), float("nan"), device=DEV)
+        vcnn.conv_fwd(d, xd, wd, bd, y, ws)
+        want = O.conv_fwd(x, wt, b, pad=(ph, pw), relu=True)
+        assert_close(to_np(y), want, 2e-6, "split-product conv_fwd")
+        dw = torch.full((k, c, r, s), float("nan"), device=DEV)
+        db = torch.full((k,), float("nan"), device=DEV)
+        vcnn.conv_bwd_filter(d, xd, dyd, dw, db, ws)
+        rdw, rdb = O.conv_bwd_filter(x, dy, (r, s), pad=(ph, pw))
+        assert_close(to_np(dw), rdw, 2e-6, "split-product dw")
+        assert_close(to_np(db), rdb, TOL_F32, "split-product db")
+        dw2 = torch.empty_like(dw)  # fixed order of the six products and of their slices: the same bits again
+        vcnn.conv_bwd_filter(d, xd, dyd, dw2, db, ws)
+        y2 = torch.empty_like(y)
+        vcnn.conv_fwd(d, xd, wd, bd, y2, ws)
+        assert torch.equal(dw, dw2) and torch.equal(y, y2)
+    finally:
+        vcnn.set_conv_algo(vcnn.ALGO_AUTO)
+
+
 @pytest.mark.parametrize("bf16,per_instr", [(False, 4096.0), (True, 32768.0)])
 def test_benchaid_mfma_counts_its_flops_and_runs(bf16, per_instr):
     """The benchmark's register-only matrix-core loop (a measurement aid outside the layer library)."""
