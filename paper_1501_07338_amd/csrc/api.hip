@@ -782,20 +782,24 @@ vcnn_status vcnn_sgd_update_multi(int32_t tensors, const size_t* counts, float* 
   if (tensors < 0) return fail(VCNN_ERR_SHAPE, "sgd_update_multi: negative tensor count");
   if (tensors == 0) return VCNN_OK;
   if (!counts || !w || !dw) return fail(VCNN_ERR_NULL, "sgd_update_multi: NULL argument array");
-  for (int t = 0; t < tensors; ++t)
+  const uint64_t max_blocks = 0x7fffffffULL;  // of one launch
+  for (int t = 0; t < tensors; ++t) {  // all checks before the first launch: an error leaves every tensor as it was
     if (counts[t] > 0 && (!w[t] || !dw[t])) return fail(VCNN_ERR_NULL, "sgd_update_multi: NULL tensor %d", t);
-  // batches of up to kSgdBatch non-empty tensors; t carries on where the previous batch stopped
+    if ((counts[t] + 255) / 256 > max_blocks) return fail(VCNN_ERR_SHAPE, "sgd_update_multi: tensor %d has too many elements", t);
+  }
+  // batches of up to kSgdBatch non-empty tensors and max_blocks blocks; t carries on where the previous batch stopped
   for (int t = 0; t < tensors;) {
     SgdBatch a{};
     a.lr = lr;
     uint64_t blocks = 0;
     for (; t < tensors && a.tensors < kSgdBatch; ++t) {
       if (counts[t] == 0) continue;
+      const uint64_t more = (counts[t] + 255) / 256;
+      if (blocks + more > max_blocks) break;  // this tensor opens the next batch
       const int k = a.tensors++;
       a.w[k] = w[t], a.dw[k] = dw[t], a.w16[k] = w_bf16 ? w_bf16[t] : nullptr, a.count[k] = counts[t];
       a.first[k] = (unsigned)blocks;
-      blocks += (counts[t] + 255) / 256;
-      if (blocks > 0x7fffffffULL) return fail(VCNN_ERR_SHAPE, "sgd_update_multi: too many elements for one launch");
+      blocks += more;
     }
     if (a.tensors == 0) break;
     a.first[a.tensors] = (unsigned)blocks;

@@ -109,6 +109,8 @@ __global__ __launch_bounds__(kThreads) void reorder_weights_frag_kernel(const bf
 
 struct HaloBf16Args {
   const uint4* x8;    // [n][cg][h][w] positions of 8 channels
+  int64_t x8_term;    // TERMS > 1: distance between the terms of x8, and of wf, in 16-byte words
+  int64_t wf_term;
   const uint4* zero;  // 16 zero bytes
   const uint4* wf;    // [mt][chunk][step][64 lanes] fragments
   const float* bias;  // [m] or null
@@ -121,11 +123,18 @@ struct HaloBf16Args {
   int nr, wp;         // halo rows and row pitch (positions) per group
   int uch;            // (group, tap) pairs per chunk, padded to a multiple of 8
   int hpos;           // positions per halo buffer (cgc*nr*wp rounded up to a multiple of 64)
+  int nbuf;           // halo buffers: 2 = the next chunk is staged during the products of this one, 1 = between chunks
   int relu;
 };
 
-template <int WAVES_M, int WAVES_K, int TM, int TN, bool M16 = false, int WAVES_N = 1>
+// TERMS = 3: both operands are given as three bfloat16 terms each (a float split exactly into three), and a step
+// multiplies the six largest of the nine term pairs - smallest first - into the same accumulators: the float product
+// to within float rounding, with every staged word and every fragment used for two or three MFMAs instead of one.
+template <int WAVES_M, int WAVES_K, int TM, int TN, bool M16 = false, int WAVES_N = 1, int TERMS = 1>
 __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Args a) {
+  static_assert(TERMS == 1 || TERMS == 3, "plain bfloat16 operands, or floats as three terms");
+  constexpr int PAIRS = TERMS == 1 ? 1 : 6;
+  constexpr int kTermA[6] = {2, 0, 1, 1, 0, 0}, kTermB[6] = {0, 2, 1, 0, 1, 0};  // kernel-matrix term, input term
   static_assert(WAVES_M * WAVES_K * WAVES_N * 64 == kThreads, "four waves per block");
   static_assert(!M16 || WAVES_M == 1, "16-row tiles: every wave holds all rows");
   constexpr int TILE = M16 ? 16 : 32;     // rows and pixels of one accumulator tile
@@ -136,7 +145,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
   extern __shared__ uint4 smem16[];
   int* const tbl = reinterpret_cast<int*>(smem16);  // [uch], per slab of 8 pairs: [half][4]
   int* const nxt = tbl + a.uch;                     // [uch/8 + 4]: next slab with work, first such slab per wave
-  uint4* const hbuf = smem16 + a.uch / 4 + (a.uch / 8 + 7) / 4;  // 2 x [cgc][nr][wp], each padded to hpos positions
+  uint4* const hbuf = smem16 + a.uch / 4 + (a.uch / 8 + 7) / 4;  // nbuf x TERMS x [cgc][nr][wp], each padded to hpos positions
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lcol = lane & (TILE - 1), half = lane / TILE;  // tile column / row of this lane, its pair of the step
@@ -212,13 +221,15 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
   const uint4* wf0 = a.wf + (int64_t)(i0 / TILE) * mstride + lane;
 
   // A fragments of the slab this wave works on next: af[step in slab][row tile]
-  uint4 af[SPS][TM];
+  uint4 af[TERMS][SPS][TM];
   auto load_a = [&](int ch, int sl) {
     const uint4* src = wf0 + ((int64_t)ch * steps + sl * SPS) * 64;
 #pragma unroll
-    for (int i = 0; i < SPS; ++i)
+    for (int t = 0; t < TERMS; ++t)
 #pragma unroll
-      for (int mi = 0; mi < TM; ++mi) af[i][mi] = src[mi * mstride + i * 64];
+      for (int i = 0; i < SPS; ++i)
+#pragma unroll
+        for (int mi = 0; mi < TM; ++mi) af[t][i][mi] = src[t * a.wf_term + mi * mstride + i * 64];
   };
   __syncthreads();  // nxt is complete
   const int first_work = nxt[chunk_slabs + wave_k];  // this wave's first slab with work in any chunk
@@ -240,7 +251,8 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
       const int ih = oh_first - a.ph + ry, iw = rx - a.pw;
       const bool ok = b0 + lane < npos && g0 + gl < a.cg && ih >= 0 && ih < a.h && iw >= 0 && iw < a.w;
       const uint4* src = ok ? x8n + ((g0 + gl) * a.h + ih) * a.w + iw : a.zero;
-      load_to_lds16(src, dst + b0);
+#pragma unroll
+      for (int t = 0; t < TERMS; ++t) load_to_lds16(ok ? src + t * a.x8_term : src, dst + t * a.hpos + b0);
       rx += dr;
       ry += dq;
       if (rx >= a.wp) rx -= a.wp, ++ry;
@@ -248,16 +260,17 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
     }
   };
   stage(0, hbuf);
+  constexpr int kBuf = TERMS;  // planes per halo buffer
 
   for (int ch = 0; ch < a.nchunks; ++ch) {
     const int ulen = min(a.cgc, a.cg - ch * a.cgc) * RS;  // valid (group, tap) pairs in this chunk
     const int slabs = (ulen + 7) >> 3;
-    const uint4* halo = hbuf + (ch & 1) * a.hpos;
+    const uint4* halo = hbuf + (ch & (a.nbuf - 1)) * kBuf * a.hpos;
     // this chunk's tile has landed (every wave waits for its own loads, the barrier publishes them) and
     // every wave is done with the other buffer (first pass: the table is complete)
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     __syncthreads();
-    if (ch + 1 < a.nchunks) stage(ch + 1, hbuf + ((ch + 1) & 1) * a.hpos);
+    if (a.nbuf == 2 && ch + 1 < a.nchunks) stage(ch + 1, hbuf + ((ch + 1) & 1) * kBuf * a.hpos);
 
     for (int sl = first_work; sl < slabs;) {
       // where this wave continues: its next slab with work in this chunk, else its first one in the next
@@ -279,22 +292,34 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
       }
 #pragma unroll
       for (int i = 0; i < SPS; ++i) {
-        uint4 bfr[TN], cur[TM];
+        uint4 bfr[TERMS][TN], cur[TERMS][TM];
 #pragma unroll
-        for (int ni = 0; ni < TN; ++ni) bfr[ni] = halo[lane_base[ni] + o[i]];
+        for (int t = 0; t < TERMS; ++t)
 #pragma unroll
-        for (int mi = 0; mi < TM; ++mi) {
-          cur[mi] = af[i][mi];
-          af[i][mi] = nsrc[mi * mstride + i * 64];
-        }
+          for (int ni = 0; ni < TN; ++ni) bfr[t][ni] = halo[t * a.hpos + lane_base[ni] + o[i]];
+#pragma unroll
+        for (int t = 0; t < TERMS; ++t)
+#pragma unroll
+          for (int mi = 0; mi < TM; ++mi) {
+            cur[t][mi] = af[t][i][mi];
+            af[t][i][mi] = nsrc[t * a.wf_term + mi * mstride + i * 64];
+          }
         // keep the fragment loads of the next slab ahead of this step's MFMAs: a full slab of lead time
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int mi = 0; mi < TM; ++mi)
+        for (int pr = 0; pr < PAIRS; ++pr) {
+          const int ta = TERMS == 1 ? 0 : kTermA[pr], tb = TERMS == 1 ? 0 : kTermB[pr];
 #pragma unroll
-          for (int ni = 0; ni < TN; ++ni) acc[mi][ni] = mfma_bf16(cur[mi], bfr[ni], acc[mi][ni]);
+          for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < TN; ++ni) acc[mi][ni] = mfma_bf16(cur[ta][mi], bfr[tb][ni], acc[mi][ni]);
+        }
       }
       sl = after;
+    }
+    if (a.nbuf == 1 && ch + 1 < a.nchunks) {  // one buffer: every wave is done reading it, then it is refilled
+      __syncthreads();
+      stage(ch + 1, hbuf);
     }
   }
 
@@ -355,14 +380,14 @@ static constexpr int kTn16Choices[] = {4, 8, 10};  // 16-pixel tiles per wave (t
 // One arrangement of the four waves (waves_m along the maps, waves_n along the pixels, the rest along the contraction);
 // *cost_out is the estimated time in units of one 32-pixel wave tile.
 static bool plan_arrangement(int waves_m, int waves_n, int n, int c, int h, int w, int m, int r, int s, int ph, int pw,
-                             HaloBf16Plan* p, double* cost_out) {
+                             HaloBf16Plan* p, double* cost_out, int terms, int nbuf = 2) {
   const int oh = h + 2 * ph - r + 1, ow = w + 2 * pw - s + 1;
   if (oh <= 0 || ow <= 0) return false;
   const int rs = r * s;
   const int cg = (c + 7) / 8;
   if ((int64_t)cg * h * w > 0x7fffffffLL) return false;  // 32-bit position offsets inside a sample
   p->m16 = m > 32 && m <= 48;  // three 16-row tiles instead of two 32-row ones
-  p->waves_m = waves_m, p->waves_n = waves_n;
+  p->waves_m = waves_m, p->waves_n = waves_n, p->terms = terms, p->nbuf = nbuf;
   p->tm = p->m16 ? 3 : (m <= 32 ? 1 : 2);  // row tiles per wave
   const int tile = p->m16 ? 16 : 32, aq = p->m16 ? 4 : 16, sps = p->m16 ? 2 : 4;
   const int waves_k = 4 / (p->waves_m * p->waves_n);
@@ -373,7 +398,9 @@ static bool plan_arrangement(int waves_m, int waves_n, int n, int c, int h, int 
   const int64_t P = (int64_t)oh * ow;
   int best_tn = 0, best_cgc = 0, best_nr = 0;
   double best_cost = 0;
-  for (int k = 0; k < 3; ++k) {
+  // (three terms: the fragments and halo words of a step take three times the registers, which leaves room for the
+  // accumulators of 64-pixel wave tiles only; their six products per step give those the reuse of wider tiles)
+  for (int k = 0; k < (terms == 3 ? 1 : 3); ++k) {
     const int tn = p->m16 ? kTn16Choices[k] : kTnChoices[k];
     const int bn = tile * tn * p->waves_n;
     int rows = (bn + ow - 2) / ow + 1;
@@ -385,7 +412,7 @@ static bool plan_arrangement(int waves_m, int waves_n, int n, int c, int h, int 
     for (int t = 1; t <= cg; ++t) {
       const int uch = (int)ceil_div((int64_t)t * rs, 8) * 8;
       const size_t hpos = ((size_t)t * nr * wp + 63) & ~(size_t)63;
-      if ((size_t)uch * 4 + ((size_t)uch / 8 + 7) / 4 * 16 + 2 * hpos * 16 > kLdsBudget || uch > 4096) break;
+      if ((size_t)uch * 4 + ((size_t)uch / 8 + 7) / 4 * 16 + nbuf * terms * hpos * 16 > kLdsBudget || uch > 4096) break;
       cgc = t;
     }
     if (cgc == 0) continue;
@@ -410,32 +437,39 @@ static bool plan_arrangement(int waves_m, int waves_n, int n, int c, int h, int 
   p->uch = (int)ceil_div((int64_t)pick * rs, 8) * 8;
   const size_t red_bytes = waves_k > 1 ? (size_t)p->waves_m * p->tm * best_tn * aq * 64 * sizeof(float) : 0;
   p->hpos = (int)(((size_t)pick * best_nr * wp + 63) & ~(size_t)63);
-  p->lds_bytes = std::max((size_t)p->uch * 4 + ((size_t)p->uch / 8 + 7) / 4 * 16 + 2 * (size_t)p->hpos * 16, red_bytes);
+  p->lds_bytes = std::max((size_t)p->uch * 4 + ((size_t)p->uch / 8 + 7) / 4 * 16 + nbuf * terms * (size_t)p->hpos * 16, red_bytes);
   p->x8_bytes = (((size_t)n * cg * h * w + 1) * 16 + 255) & ~(size_t)255;  // + the block of zeros
   p->wf_bytes = ((size_t)tiles_m * (bm / tile) * p->nchunks * (p->uch / 8 * sps) * 64 * 16 + 255) & ~(size_t)255;
   *cost_out = best_cost;
   return true;
 }
 
-bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int pw, HaloBf16Plan* p) {
+bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int pw, HaloBf16Plan* p, int terms) {
   double cost = 0;
-  if (m <= 128) return plan_arrangement(m > 64 ? 2 : 1, 1, n, c, h, w, m, r, s, ph, pw, p, &cost);
+  if (terms != 1 && m <= 128) return false;  // the three-term form is built for the arrangements of many maps only
+  if (m <= 128) return plan_arrangement(m > 64 ? 2 : 1, 1, n, c, h, w, m, r, s, ph, pw, p, &cost, terms);
   // many maps: the four waves take different maps of the same pixels, or - when the image is large enough for
   // four times as many pixels per block - different pixels of the same maps; these read the same kernel-matrix
   // fragments at about the same time, three of four from the first-level cache (cfg5 c3 forward: 0.8 instead
   // of 2.7 GB from the second level)
   HaloBf16Plan wide{};
   double wide_cost = 0;
-  const bool maps_ok = plan_arrangement(4, 1, n, c, h, w, m, r, s, ph, pw, p, &cost);
-  const bool wide_ok = plan_arrangement(1, 4, n, c, h, w, m, r, s, ph, pw, &wide, &wide_cost);
+  // (three halo planes of a large kernel may only fit LDS once: then a chunk is staged between the products of two
+  // chunks, not during them, and the other resident block covers the gap)
+  bool maps_ok = plan_arrangement(4, 1, n, c, h, w, m, r, s, ph, pw, p, &cost, terms);
+  bool wide_ok = plan_arrangement(1, 4, n, c, h, w, m, r, s, ph, pw, &wide, &wide_cost, terms);
+  if (terms == 3 && !maps_ok && !wide_ok) {
+    maps_ok = plan_arrangement(4, 1, n, c, h, w, m, r, s, ph, pw, p, &cost, terms, 1);
+    wide_ok = plan_arrangement(1, 4, n, c, h, w, m, r, s, ph, pw, &wide, &wide_cost, terms, 1);
+  }
   if (wide_ok && (!maps_ok || wide_cost <= cost + 1e-9)) *p = wide;
   return maps_ok || wide_ok;
 }
 
-template <int WAVES_M, int WAVES_K, int TM, int TN, bool M16 = false, int WAVES_N = 1>
+template <int WAVES_M, int WAVES_K, int TM, int TN, bool M16 = false, int WAVES_N = 1, int TERMS = 1>
 static void launch_one(const HaloBf16Args& a, size_t lds, hipStream_t st) {
   const dim3 grid((unsigned)((int64_t)a.tiles_m * a.n * a.tiles_per_img)), block(kThreads);
-  auto kernel = conv_halo_bf16_kernel<WAVES_M, WAVES_K, TM, TN, M16, WAVES_N>;
+  auto kernel = conv_halo_bf16_kernel<WAVES_M, WAVES_K, TM, TN, M16, WAVES_N, TERMS>;
   static bool opted = false;  // one flag per instantiation, i.e. per kernel
   if (!opted) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -446,8 +480,13 @@ static void launch_one(const HaloBf16Args& a, size_t lds, hipStream_t st) {
 }
 
 template <int TN>
-static void launch_tn(const HaloBf16Args& a, int waves_m, int waves_n, int tm, size_t lds, hipStream_t st) {
-  if (waves_n == 4) launch_one<1, 1, 2, TN, false, 4>(a, lds, st);
+static void launch_tn(const HaloBf16Args& a, int waves_m, int waves_n, int tm, int terms, size_t lds, hipStream_t st) {
+  if (terms == 3) {  // (planned for the two arrangements of many maps and 64-pixel wave tiles only)
+    if constexpr (TN == 2) {
+      if (waves_n == 4) launch_one<1, 1, 2, TN, false, 4, 3>(a, lds, st);
+      else launch_one<4, 1, 2, TN, false, 1, 3>(a, lds, st);
+    }
+  } else if (waves_n == 4) launch_one<1, 1, 2, TN, false, 4>(a, lds, st);
   else if (waves_m == 4) launch_one<4, 1, 2, TN>(a, lds, st);
   else if (waves_m == 2) launch_one<2, 2, 2, TN>(a, lds, st);
   else if (tm == 2) launch_one<1, 4, 2, TN>(a, lds, st);
@@ -461,46 +500,79 @@ vcnn_status launch_conv_halo_bf16(const HaloBf16Plan& p, int n, int c, int h, in
                                         (char*)workspace + p.x8_bytes, st, y32, accumulate);
 }
 
-vcnn_status launch_conv_halo_bf16_prepared(const HaloBf16Plan& p, int n, int c, int h, int w, int m, int r, int s, int ph,
-                                           int pw, const void* x, const void* wgt, int64_t w_so, int64_t w_si, int flip,
-                                           const float* bias, void* y, int relu, void* x8_buf, void* wf_buf, hipStream_t st,
-                                           float* y32, int accumulate) {
-  uint4* x8 = (uint4*)x8_buf;
-  bf16* wf = (bf16*)wf_buf;
-  const int rs = r * s;
-  if (x) {
-    const int64_t total = (int64_t)n * p.cg * h * w;
-    hipLaunchKernelGGL(interleave_channels_kernel, dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, st,
-                       (const bf16*)x, x8, c, p.cg, h * w, total);
-    if (vcnn_status e = check_launch("interleave_channels")) return e;
-  }
+// the two re-laying passes of one operand each, and the product on re-laid operands
+static vcnn_status relay_input(const HaloBf16Plan& p, int n, int c, int h, int w, const void* x, void* x8_buf, hipStream_t st) {
+  const int64_t total = (int64_t)n * p.cg * h * w;
+  hipLaunchKernelGGL(interleave_channels_kernel, dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, st,
+                     (const bf16*)x, (uint4*)x8_buf, c, p.cg, h * w, total);
+  return check_launch("interleave_channels");
+}
+
+static vcnn_status relay_kernels(const HaloBf16Plan& p, int c, int m, int rs, const void* wgt, int64_t w_so, int64_t w_si,
+                                 int flip, void* wf_buf, hipStream_t st) {
   const int tile = p.m16 ? 16 : 32;
   const int bm = tile * p.tm * p.waves_m;
   const int tiles_m = (int)ceil_div(m, bm);
-  if (wgt) {
-    const int steps = p.uch / 8 * (p.m16 ? 2 : 4);
-    const int64_t total = (int64_t)tiles_m * (bm / tile) * p.nchunks * steps * 512;
-    hipLaunchKernelGGL(reorder_weights_frag_kernel, dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, st,
-                       (const bf16*)wgt, wf, m, c, rs, w_so, w_si, flip, p.cgc, p.nchunks, steps, p.m16, total);
-    if (vcnn_status e = check_launch("reorder_weights_frag")) return e;
-  }
+  const int steps = p.uch / 8 * (p.m16 ? 2 : 4);
+  const int64_t total = (int64_t)tiles_m * (bm / tile) * p.nchunks * steps * 512;
+  hipLaunchKernelGGL(reorder_weights_frag_kernel, dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, st,
+                     (const bf16*)wgt, (bf16*)wf_buf, m, c, rs, w_so, w_si, flip, p.cgc, p.nchunks, steps, p.m16, total);
+  return check_launch("reorder_weights_frag");
+}
+
+static vcnn_status launch_product(const HaloBf16Plan& p, int n, int h, int w, int m, int r, int s, int ph, int pw,
+                                  const float* bias, void* y, int relu, const void* x8_buf, const void* wf_buf,
+                                  hipStream_t st, float* y32, int accumulate) {
+  const uint4* x8 = (const uint4*)x8_buf;
+  const int tile = p.m16 ? 16 : 32;
+  const int bm = tile * p.tm * p.waves_m;
   HaloBf16Args a{};
-  a.x8 = x8, a.zero = x8 + (int64_t)n * p.cg * h * w, a.wf = (const uint4*)wf, a.bias = bias, a.y = (bf16*)y;
+  a.x8 = x8, a.zero = x8 + (int64_t)n * p.cg * h * w, a.wf = (const uint4*)wf_buf, a.bias = bias, a.y = (bf16*)y;
+  a.x8_term = (int64_t)(p.x8_bytes / 16), a.wf_term = (int64_t)(p.wf_bytes / 16);  // (read by the three-term form only)
   a.y32 = y32, a.accumulate = accumulate;
   a.n = n, a.h = h, a.w = w, a.m = m, a.r = r, a.s = s, a.ph = ph, a.pw = pw;
   a.oh = h + 2 * ph - r + 1, a.ow = w + 2 * pw - s + 1;
   a.P = a.oh * a.ow;
-  a.tiles_m = tiles_m;
+  a.tiles_m = (int)ceil_div(m, bm);
   a.tiles_per_img = (int)ceil_div(a.P, tile * p.tn * p.waves_n);
   a.cg = p.cg, a.cgc = p.cgc, a.nchunks = p.nchunks, a.nr = p.nr, a.wp = p.wp, a.uch = p.uch, a.hpos = p.hpos, a.relu = relu;
+  a.nbuf = p.nbuf;
   if (p.m16) {
     if (p.tn == 4) launch_one<1, 4, 3, 4, true>(a, p.lds_bytes, st);
     else if (p.tn == 8) launch_one<1, 4, 3, 8, true>(a, p.lds_bytes, st);
     else launch_one<1, 4, 3, 10, true>(a, p.lds_bytes, st);
-  } else if (p.tn == 2) launch_tn<2>(a, p.waves_m, p.waves_n, p.tm, p.lds_bytes, st);
-  else if (p.tn == 4) launch_tn<4>(a, p.waves_m, p.waves_n, p.tm, p.lds_bytes, st);
-  else launch_tn<5>(a, p.waves_m, p.waves_n, p.tm, p.lds_bytes, st);
+  } else if (p.tn == 2) launch_tn<2>(a, p.waves_m, p.waves_n, p.tm, p.terms, p.lds_bytes, st);
+  else if (p.tn == 4) launch_tn<4>(a, p.waves_m, p.waves_n, p.tm, p.terms, p.lds_bytes, st);
+  else launch_tn<5>(a, p.waves_m, p.waves_n, p.tm, p.terms, p.lds_bytes, st);
   return check_launch("conv_halo_bf16");
+}
+
+vcnn_status launch_conv_halo_bf16_prepared(const HaloBf16Plan& p, int n, int c, int h, int w, int m, int r, int s, int ph,
+                                           int pw, const void* x, const void* wgt, int64_t w_so, int64_t w_si, int flip,
+                                           const float* bias, void* y, int relu, void* x8_buf, void* wf_buf, hipStream_t st,
+                                           float* y32, int accumulate) {
+  if (x)
+    if (vcnn_status e = relay_input(p, n, c, h, w, x, x8_buf, st)) return e;
+  if (wgt)
+    if (vcnn_status e = relay_kernels(p, c, m, r * s, wgt, w_so, w_si, flip, wf_buf, st)) return e;
+  return launch_product(p, n, h, w, m, r, s, ph, pw, bias, y, relu, x8_buf, wf_buf, st, y32, accumulate);
+}
+
+// Three-term form (p planned with terms = 3): x_terms / w_terms hold the three bfloat16 terms of the float input and
+// kernels, each term `x_term_bytes` / `w_term_bytes` after the one before; x8_bufs / wf_bufs take the three re-laid
+// copies (3 x p.x8_bytes, 3 x p.wf_bytes).  One product kernel multiplies the six term pairs; the result is float.
+vcnn_status launch_conv_halo_bf16_terms(const HaloBf16Plan& p, int n, int c, int h, int w, int m, int r, int s, int ph,
+                                        int pw, const void* x_terms, size_t x_term_bytes, const void* w_terms,
+                                        size_t w_term_bytes, int64_t w_so, int64_t w_si, const float* bias, float* y32,
+                                        int relu, void* x8_bufs, void* wf_bufs, hipStream_t st) {
+  for (int t = 0; t < 3; ++t) {
+    if (vcnn_status e = relay_input(p, n, c, h, w, (const char*)x_terms + t * x_term_bytes, (char*)x8_bufs + t * p.x8_bytes, st))
+      return e;
+    if (vcnn_status e = relay_kernels(p, c, m, r * s, (const char*)w_terms + t * w_term_bytes, w_so, w_si, 0,
+                                      (char*)wf_bufs + t * p.wf_bytes, st))
+      return e;
+  }
+  return launch_product(p, n, h, w, m, r, s, ph, pw, bias, nullptr, relu, x8_bufs, wf_bufs, st, y32, 0);
 }
 
 // =========================================================================================================

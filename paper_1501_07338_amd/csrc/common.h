@@ -156,7 +156,9 @@ struct HaloBf16Plan {
   int nchunks;
   int nr, wp;        // halo rows and row pitch (positions of 8 channels) per group
   int uch;           // (group, tap) pairs per chunk, padded to a multiple of 8
-  int hpos;          // positions per halo buffer
+  int hpos;          // positions per halo buffer (per term)
+  int nbuf;          // halo buffers in LDS (2, or 1 when three planes only fit once)
+  int terms;         // 1: bfloat16 operands; 3: float operands as three bfloat16 terms each, six products per step
   size_t lds_bytes;
   size_t x8_bytes, wf_bytes;  // workspace: channel-interleaved input, fragment-ordered kernel matrix
 };
@@ -180,7 +182,7 @@ vcnn_status launch_pointwise_bf16(const PointwiseBf16Plan& p, int n, int rows, i
 bool pointwise_filter_bf16_plan(const ConvGeom& g, PointwiseFilterBf16Plan* p);
 vcnn_status launch_pointwise_filter_bf16(const PointwiseFilterBf16Plan& p, const ConvGeom& g, const void* x, const void* dy,
                                          float* dw, float* partial, hipStream_t st);
-bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int pw, HaloBf16Plan* p);
+bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int pw, HaloBf16Plan* p, int terms = 1);
 // y = act(bias + W (*) x) with W(o, i, q) = wgt[o*w_so + i*w_si + (flip ? r*s-1-q : q)]; the workspace holds
 // x8_bytes + wf_bytes
 vcnn_status launch_conv_halo_bf16(const HaloBf16Plan& p, int n, int c, int h, int w, int m, int r, int s, int ph, int pw,
@@ -193,6 +195,10 @@ vcnn_status launch_conv_halo_bf16_prepared(const HaloBf16Plan& p, int n, int c, 
                                            int pw, const void* x, const void* wgt, int64_t w_so, int64_t w_si, int flip,
                                            const float* bias, void* y, int relu, void* x8_buf, void* wf_buf, hipStream_t st,
                                            float* y32, int accumulate);
+vcnn_status launch_conv_halo_bf16_terms(const HaloBf16Plan& p, int n, int c, int h, int w, int m, int r, int s, int ph,
+                                        int pw, const void* x_terms, size_t x_term_bytes, const void* w_terms,
+                                        size_t w_term_bytes, int64_t w_so, int64_t w_si, const float* bias, float* y32,
+                                        int relu, void* x8_bufs, void* wf_bufs, hipStream_t st);
 struct FilterGradBf16Plan {
   int waves_m, tm, tn;
   int ccs, nr, wp;   // channels, rows and row pitch of the halo tile

@@ -51,7 +51,10 @@ bool conv_split_plan(const ConvGeom& g, int pass, SplitPlan* p) {
   p->part_w_bytes = align256((size_t)g.M * g.K * 2);
   p->part_dy_bytes = align256((size_t)g.M * g.N * 2);
   if (pass == VCNN_PASS_FWD) {
-    if (g.k <= 4 || !conv_halo_bf16_plan(g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, &p->fwd)) return false;
+    // many maps: the six term products inside one kernel; else six passes of the bfloat16 kernel
+    if (g.k <= 4 || !(conv_halo_bf16_plan(g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, &p->fwd, 3) ||
+                      conv_halo_bf16_plan(g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, &p->fwd)))
+      return false;
     p->inner_bytes = 3 * (p->fwd.x8_bytes + p->fwd.wf_bytes);  // every term of both operands re-laid once
     p->workspace_bytes = 3 * p->part_x_bytes + 3 * p->part_w_bytes + p->inner_bytes;
     return true;
@@ -74,6 +77,9 @@ vcnn_status launch_conv_split_fwd(const SplitPlan& p, const ConvGeom& g, const f
   char* wfs = x8s + 3 * p.fwd.x8_bytes;      // three fragment-ordered terms of w
   if (vcnn_status e = split3(x, xs, p.part_x_bytes, (int64_t)g.n * g.c * g.h * g.w, st)) return e;
   if (vcnn_status e = split3(w, ws, p.part_w_bytes, g.M * g.K, st)) return e;
+  if (p.fwd.terms == 3)
+    return launch_conv_halo_bf16_terms(p.fwd, g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, xs, p.part_x_bytes, ws,
+                                       p.part_w_bytes, g.K, (int64_t)g.r * g.s, bias, y, relu, x8s, wfs, st);
   bool x_done[3] = {false, false, false}, w_done[3] = {false, false, false};
   for (int t = 0; t < 6; ++t) {
     const int i = kPairs[t][0], j = kPairs[t][1];
