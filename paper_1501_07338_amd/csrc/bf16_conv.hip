@@ -221,13 +221,16 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
   const uint4* wf0 = a.wf + (int64_t)(i0 / TILE) * mstride + lane;
 
   // A fragments of the slab this wave works on next: af[step in slab][row tile]
-  uint4 af[TERMS][SPS][TM];
+  // (three terms: one step ahead instead of one slab - a step is 6 * TM * TN MFMAs long - which leaves the registers
+  // for reading the halo words a step ahead as well)
+  constexpr int AHEAD = TERMS == 3 ? 1 : SPS;
+  uint4 af[TERMS][AHEAD][TM];
   auto load_a = [&](int ch, int sl) {
     const uint4* src = wf0 + ((int64_t)ch * steps + sl * SPS) * 64;
 #pragma unroll
     for (int t = 0; t < TERMS; ++t)
 #pragma unroll
-      for (int i = 0; i < SPS; ++i)
+      for (int i = 0; i < AHEAD; ++i)
 #pragma unroll
         for (int mi = 0; mi < TM; ++mi) af[t][i][mi] = src[t * a.wf_term + mi * mstride + i * 64];
   };
@@ -272,50 +275,128 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
     __syncthreads();
     if (a.nbuf == 2 && ch + 1 < a.nchunks) stage(ch + 1, hbuf + ((ch + 1) & 1) * kBuf * a.hpos);
 
-    for (int sl = first_work; sl < slabs;) {
-      // where this wave continues: its next slab with work in this chunk, else its first one in the next
-      // chunk (the fragment loads do not depend on the halo tile, so they stay in flight across the change)
-      const int after = nxt[sl];
-      int nch = ch, nsl = after;
-      if (nsl >= slabs) {
-        if (ch + 1 < a.nchunks) nch = ch + 1, nsl = first_sl;
-        else nsl = sl;
-      }
-      const uint4* nsrc = wf0 + ((int64_t)nch * steps + nsl * SPS) * 64;
-      int o[4];
-      if (M16) {
-        const int2 o2 = *reinterpret_cast<const int2*>(tbl + sl * 8 + half * 2);
-        o[0] = o2.x, o[1] = o2.y;
-      } else {
+    if constexpr (TERMS == 3) {
+      // Both operands of a step are requested a step ahead: the halo words of step i + 1 (LDS) and the fragments of
+      // step i + 1 (second-level cache) are on their way while the 6 * TM * TN MFMAs of step i run, so that the two
+      // waves of a SIMD never wait for LDS at the same time.  Only the first step of a chunk waits for its words.
+      auto read_offsets = [&](int sl, int (&dst)[4]) {
         const int4 o4 = *reinterpret_cast<const int4*>(tbl + sl * 8 + half * 4);
-        o[0] = o4.x, o[1] = o4.y, o[2] = o4.z, o[3] = o4.w;
+        dst[0] = o4.x, dst[1] = o4.y, dst[2] = o4.z, dst[3] = o4.w;
+      };
+      int o[4] = {0, 0, 0, 0};
+      uint4 bfr[TERMS][TN];
+      if (first_work < slabs) {
+        read_offsets(first_work, o);
+#pragma unroll
+        for (int t = 0; t < TERMS; ++t)
+#pragma unroll
+          for (int ni = 0; ni < TN; ++ni) bfr[t][ni] = halo[t * a.hpos + lane_base[ni] + o[0]];
       }
-#pragma unroll
-      for (int i = 0; i < SPS; ++i) {
-        uint4 bfr[TERMS][TN], cur[TERMS][TM];
-#pragma unroll
-        for (int t = 0; t < TERMS; ++t)
-#pragma unroll
-          for (int ni = 0; ni < TN; ++ni) bfr[t][ni] = halo[t * a.hpos + lane_base[ni] + o[i]];
-#pragma unroll
-        for (int t = 0; t < TERMS; ++t)
-#pragma unroll
-          for (int mi = 0; mi < TM; ++mi) {
-            cur[t][mi] = af[t][i][mi];
-            af[t][i][mi] = nsrc[t * a.wf_term + mi * mstride + i * 64];
-          }
-        // keep the fragment loads of the next slab ahead of this step's MFMAs: a full slab of lead time
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int pr = 0; pr < PAIRS; ++pr) {
-          const int ta = TERMS == 1 ? 0 : kTermA[pr], tb = TERMS == 1 ? 0 : kTermB[pr];
-#pragma unroll
-          for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < TN; ++ni) acc[mi][ni] = mfma_bf16(cur[ta][mi], bfr[tb][ni], acc[mi][ni]);
+      for (int sl = first_work; sl < slabs;) {
+        const int after = nxt[sl];
+        int nch = ch, nsl = after;
+        if (nsl >= slabs) {
+          if (ch + 1 < a.nchunks) nch = ch + 1, nsl = first_sl;
+          else nsl = sl;
         }
+        const uint4* csrc = wf0 + ((int64_t)ch * steps + sl * SPS) * 64;
+        const uint4* nsrc = wf0 + ((int64_t)nch * steps + nsl * SPS) * 64;
+        // offsets of the slab after this one (past the chunk's last slab: any slab's - the words read with them are
+        // dropped when the next chunk reads its own first step)
+        int on[4];
+        read_offsets(min(after, chunk_slabs - 1), on);
+#pragma unroll
+        for (int i = 0; i < SPS; ++i) {
+          uint4 cur[TERMS][TM], bnext[TERMS][TN];
+          const uint4* nptr = i + 1 < SPS ? csrc + (i + 1) * 64 : nsrc;
+          const int onext = i + 1 < SPS ? o[(i + 1) & 3] : on[0];
+          // (requested in the order the next step's MFMAs first use them, so that its first MFMA waits for the
+          // oldest request only, not for all of them)
+          constexpr int kOrderA[3] = {2, 0, 1}, kOrderB[3] = {0, 2, 1};
+#pragma unroll
+          for (int k = 0; k < TERMS; ++k)
+#pragma unroll
+            for (int mi = 0; mi < TM; ++mi) {
+              const int t = kOrderA[k];
+              cur[t][mi] = af[t][0][mi];
+              af[t][0][mi] = nptr[t * a.wf_term + mi * mstride];
+            }
+#pragma unroll
+          for (int k = 0; k < TERMS; ++k)
+#pragma unroll
+            for (int ni = 0; ni < TN; ++ni) {
+              const int t = kOrderB[k];
+              bnext[t][ni] = halo[t * a.hpos + lane_base[ni] + onext];
+            }
+#pragma unroll
+          for (int pr = 0; pr < PAIRS; ++pr)
+#pragma unroll
+            for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+              for (int ni = 0; ni < TN; ++ni) acc[mi][ni] = mfma_bf16(cur[kTermA[pr]][mi], bfr[kTermB[pr]][ni], acc[mi][ni]);
+          // issue order of the step: the requests of the next step go out between this step's MFMAs, one fragment
+          // load and one halo read after every TM * TN of them, in the shadow of the matrix pipe
+#pragma unroll
+          for (int k = 0; k < TERMS * TM; ++k) {
+            __builtin_amdgcn_sched_group_barrier(0x008, PAIRS * TN / TERMS, 0);  // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                   // global read
+            if (k < TERMS * TN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
+          }
+#pragma unroll
+          for (int t = 0; t < TERMS; ++t)
+#pragma unroll
+            for (int ni = 0; ni < TN; ++ni) bfr[t][ni] = bnext[t][ni];
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = on[i];
+        sl = after;
       }
-      sl = after;
+    } else {
+      for (int sl = first_work; sl < slabs;) {
+        // where this wave continues: its next slab with work in this chunk, else its first one in the next
+        // chunk (the fragment loads do not depend on the halo tile, so they stay in flight across the change)
+        const int after = nxt[sl];
+        int nch = ch, nsl = after;
+        if (nsl >= slabs) {
+          if (ch + 1 < a.nchunks) nch = ch + 1, nsl = first_sl;
+          else nsl = sl;
+        }
+        const uint4* nsrc = wf0 + ((int64_t)nch * steps + nsl * SPS) * 64;
+        int o[4];
+        if (M16) {
+          const int2 o2 = *reinterpret_cast<const int2*>(tbl + sl * 8 + half * 2);
+          o[0] = o2.x, o[1] = o2.y;
+        } else {
+          const int4 o4 = *reinterpret_cast<const int4*>(tbl + sl * 8 + half * 4);
+          o[0] = o4.x, o[1] = o4.y, o[2] = o4.z, o[3] = o4.w;
+        }
+#pragma unroll
+        for (int i = 0; i < SPS; ++i) {
+          uint4 bfr[TERMS][TN], cur[TERMS][TM];
+#pragma unroll
+          for (int t = 0; t < TERMS; ++t)
+#pragma unroll
+            for (int ni = 0; ni < TN; ++ni) bfr[t][ni] = halo[t * a.hpos + lane_base[ni] + o[i]];
+#pragma unroll
+          for (int t = 0; t < TERMS; ++t)
+#pragma unroll
+            for (int mi = 0; mi < TM; ++mi) {
+              cur[t][mi] = af[t][i][mi];
+              af[t][i][mi] = nsrc[t * a.wf_term + mi * mstride + i * 64];
+            }
+          // keep the fragment loads of the next slab ahead of this step's MFMAs: a full slab of lead time
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int pr = 0; pr < PAIRS; ++pr) {
+            const int ta = TERMS == 1 ? 0 : kTermA[pr], tb = TERMS == 1 ? 0 : kTermB[pr];
+#pragma unroll
+            for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+              for (int ni = 0; ni < TN; ++ni) acc[mi][ni] = mfma_bf16(cur[ta][mi], bfr[tb][ni], acc[mi][ni]);
+          }
+        }
+        sl = after;
+      }
     }
     if (a.nbuf == 1 && ch + 1 < a.nchunks) {  // one buffer: every wave is done reading it, then it is refilled
       __syncthreads();
