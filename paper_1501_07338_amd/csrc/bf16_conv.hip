@@ -352,6 +352,24 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
         sl = after;
       }
     } else {
+      // bfloat16 operands: the fragments are requested a slab ahead (a step is only TM * TN MFMAs long), the halo words
+      // a step ahead, both between the MFMAs of the current step
+      auto read_offsets = [&](int sl, int (&dst)[4]) {
+        if (M16) {
+          const int2 o2 = *reinterpret_cast<const int2*>(tbl + sl * 8 + half * 2);
+          dst[0] = o2.x, dst[1] = o2.y, dst[2] = 0, dst[3] = 0;
+        } else {
+          const int4 o4 = *reinterpret_cast<const int4*>(tbl + sl * 8 + half * 4);
+          dst[0] = o4.x, dst[1] = o4.y, dst[2] = o4.z, dst[3] = o4.w;
+        }
+      };
+      int o[4] = {0, 0, 0, 0};
+      uint4 bfr[TN];
+      if (first_work < slabs) {
+        read_offsets(first_work, o);
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni) bfr[ni] = halo[lane_base[ni] + o[0]];
+      }
       for (int sl = first_work; sl < slabs;) {
         // where this wave continues: its next slab with work in this chunk, else its first one in the next
         // chunk (the fragment loads do not depend on the halo tile, so they stay in flight across the change)
@@ -362,39 +380,37 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
           else nsl = sl;
         }
         const uint4* nsrc = wf0 + ((int64_t)nch * steps + nsl * SPS) * 64;
-        int o[4];
-        if (M16) {
-          const int2 o2 = *reinterpret_cast<const int2*>(tbl + sl * 8 + half * 2);
-          o[0] = o2.x, o[1] = o2.y;
-        } else {
-          const int4 o4 = *reinterpret_cast<const int4*>(tbl + sl * 8 + half * 4);
-          o[0] = o4.x, o[1] = o4.y, o[2] = o4.z, o[3] = o4.w;
-        }
+        // offsets of the slab after this one (past the chunk's last slab: any slab's - the words read with them are
+        // dropped when the next chunk reads its own first step)
+        int on[4];
+        read_offsets(min(after, chunk_slabs - 1), on);
 #pragma unroll
         for (int i = 0; i < SPS; ++i) {
-          uint4 bfr[TERMS][TN], cur[TERMS][TM];
+          uint4 cur[TM], bnext[TN];
+          const int onext = i + 1 < SPS ? o[(i + 1) & 3] : on[0];
 #pragma unroll
-          for (int t = 0; t < TERMS; ++t)
-#pragma unroll
-            for (int ni = 0; ni < TN; ++ni) bfr[t][ni] = halo[t * a.hpos + lane_base[ni] + o[i]];
-#pragma unroll
-          for (int t = 0; t < TERMS; ++t)
-#pragma unroll
-            for (int mi = 0; mi < TM; ++mi) {
-              cur[t][mi] = af[t][i][mi];
-              af[t][i][mi] = nsrc[t * a.wf_term + mi * mstride + i * 64];
-            }
-          // keep the fragment loads of the next slab ahead of this step's MFMAs: a full slab of lead time
-          __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-          for (int pr = 0; pr < PAIRS; ++pr) {
-            const int ta = TERMS == 1 ? 0 : kTermA[pr], tb = TERMS == 1 ? 0 : kTermB[pr];
-#pragma unroll
-            for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-              for (int ni = 0; ni < TN; ++ni) acc[mi][ni] = mfma_bf16(cur[ta][mi], bfr[tb][ni], acc[mi][ni]);
+          for (int mi = 0; mi < TM; ++mi) {
+            cur[mi] = af[0][i][mi];
+            af[0][i][mi] = nsrc[mi * mstride + i * 64];
           }
+#pragma unroll
+          for (int ni = 0; ni < TN; ++ni) bnext[ni] = halo[lane_base[ni] + onext];
+#pragma unroll
+          for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < TN; ++ni) acc[mi][ni] = mfma_bf16(cur[mi], bfr[ni], acc[mi][ni]);
+          // issue order: one halo read (and, while there are any, one fragment load) after every TM MFMAs
+#pragma unroll
+          for (int k = 0; k < TN; ++k) {
+            __builtin_amdgcn_sched_group_barrier(0x008, TM, 0);              // MFMA
+            if (k < TM) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // global read
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);              // LDS read
+          }
+#pragma unroll
+          for (int ni = 0; ni < TN; ++ni) bfr[ni] = bnext[ni];
         }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = on[i];
         sl = after;
       }
     }
@@ -720,30 +736,41 @@ struct FilterBf16Args {
   const uint4* x8n;   // [ng][c][h][w] positions of 8 images
   const uint4* zero;  // 16 zero bytes
   const uint4* dyf;   // [ng][mt][run][step][64 lanes] fragments
+  int64_t x8n_term;   // TERMS > 1: distance between the terms of x8n, and of dyf, in 16-byte words
+  int64_t dyf_term;
   float* out;         // [splits][m][K]
   int c, h, w, m, r, s, ph, pw, oh, ow;
   int K;              // c*r*s
   int tiles_m, mt_total;
   int runs, bh, bp;   // runs per image, output rows and pixels per run
   int uch, hpos, ccs, nr, wp;
+  int nbuf;           // halo buffers: 2 = the next chunk is staged during the products of this one, 1 = between chunks
   int chunks, chunks_per_split;  // chunk = (image group, run)
 };
 
-template <int WAVES_M, int WAVES_K, int TM, int TN>
+// WAVES_N > 1: the waves of a block take different kernel-matrix columns of the same maps (they read the same dY
+// fragments at about the same time, all but one from the first-level cache).  TERMS = 3: both operands as three
+// bfloat16 terms each, the six largest term products per step - smallest first - into the same accumulators, with the
+// operands of a step requested one step ahead, in order of first use, between the MFMAs (as in the forward kernel).
+template <int WAVES_M, int WAVES_K, int TM, int TN, int WAVES_N = 1, int TERMS = 1>
 __global__ __launch_bounds__(kThreads, 2) void filter_grad_bf16_kernel(FilterBf16Args a) {
-  static_assert(WAVES_M * WAVES_K * 64 == kThreads, "four waves per block");
-  constexpr int BM = 32 * TM * WAVES_M, BN = 32 * TN;
+  static_assert(WAVES_M * WAVES_K * WAVES_N * 64 == kThreads, "four waves per block");
+  static_assert(TERMS == 1 || TERMS == 3, "plain bfloat16 operands, or floats as three terms");
+  constexpr int PAIRS = TERMS == 1 ? 1 : 6;
+  constexpr int kTermA[6] = {2, 0, 1, 1, 0, 0}, kTermB[6] = {0, 2, 1, 0, 1, 0};  // dY term, input term
+  constexpr int BM = 32 * TM * WAVES_M, WN = 32 * TN, BN = WN * WAVES_N;
   extern __shared__ uint4 smem16[];
   int* const tbl = reinterpret_cast<int*>(smem16);  // [uch], per slab of 8 pixels: [half][4]
-  uint4* const hbuf = smem16 + a.uch / 4;           // 2 x [ccs][nr][wp], each padded to hpos positions
+  uint4* const hbuf = smem16 + a.uch / 4;           // nbuf x TERMS x [ccs][nr][wp], each padded to hpos positions
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
-  const int wave_m = wave % WAVES_M, wave_k = wave / WAVES_M;
+  const int wave_m = wave % WAVES_M, wave_k = (wave / WAVES_M) % WAVES_K, wave_n = wave / (WAVES_M * WAVES_K);
   const int tm = blockIdx.x % a.tiles_m;
   const int tk = blockIdx.x / a.tiles_m;
   const int i0 = tm * BM + wave_m * 32 * TM;  // first output map of this wave
   const int k0 = tk * BN;                     // first kernel-matrix column of the block
+  const int kw0 = k0 + wave_n * WN;           // ... of this wave
   const int RS = a.r * a.s;
   const int plane = a.nr * a.wp;
   const int c_first = k0 / RS;
@@ -762,7 +789,7 @@ __global__ __launch_bounds__(kThreads, 2) void filter_grad_bf16_kernel(FilterBf1
   int tap_base[TN];
 #pragma unroll
   for (int ni = 0; ni < TN; ++ni) {
-    const int col = min(k0 + ni * 32 + l32, a.K - 1);
+    const int col = min(kw0 + ni * 32 + l32, a.K - 1);
     const int c = col / RS;
     const int q = col - c * RS;
     const int r = q / a.s;
@@ -787,14 +814,18 @@ __global__ __launch_bounds__(kThreads, 2) void filter_grad_bf16_kernel(FilterBf1
     return a.dyf + (((int64_t)ng * a.mt_total + i0 / 32) * a.runs + run) * steps * 64 + sl * 256 + lane;
   };
 
-  uint4 af[4][TM];
+  // fragments on their way: a slab ahead (bfloat16 operands: a step is TM * TN MFMAs long) or a step ahead (three terms)
+  constexpr int AHEAD = TERMS == 3 ? 1 : 4;
+  uint4 af[TERMS][AHEAD][TM];
   const int first_sl = min(wave_k, chunk_slabs - 1);
   {
     const uint4* src = frag_ptr(id0, first_sl);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int t = 0; t < TERMS; ++t)
 #pragma unroll
-      for (int mi = 0; mi < TM; ++mi) af[i][mi] = src[mi * mstride + i * 64];
+      for (int i = 0; i < AHEAD; ++i)
+#pragma unroll
+        for (int mi = 0; mi < TM; ++mi) af[t][i][mi] = src[t * a.dyf_term + mi * mstride + i * 64];
   }
 
   const int dq = kThreads / a.wp, dr = kThreads - dq * a.wp;
@@ -810,7 +841,8 @@ __global__ __launch_bounds__(kThreads, 2) void filter_grad_bf16_kernel(FilterBf1
       const int ih = ih0 + ry, iw = rx - a.pw, ch = c_first + cl;
       const bool ok = b0 + lane < npos && ch < a.c && ih >= 0 && ih < a.h && iw >= 0 && iw < a.w;
       const uint4* src = ok ? xg + (ch * a.h + ih) * a.w + iw : a.zero;
-      load_to_lds16(src, dst + b0);
+#pragma unroll
+      for (int t = 0; t < TERMS; ++t) load_to_lds16(ok ? src + t * a.x8n_term : src, dst + t * a.hpos + b0);
       rx += dr;
       ry += dq;
       if (rx >= a.wp) rx -= a.wp, ++ry;
@@ -823,33 +855,103 @@ __global__ __launch_bounds__(kThreads, 2) void filter_grad_bf16_kernel(FilterBf1
     const int run = id % a.runs;
     const int ulen = min(a.bh, a.oh - run * a.bh) * a.ow;  // valid pixels in this run
     const int slabs = (ulen + 7) >> 3;
-    const uint4* halo = hbuf + ((id - id0) & 1) * a.hpos;
+    const uint4* halo = hbuf + ((id - id0) & (a.nbuf - 1)) * TERMS * a.hpos;
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of the tile has landed
     __syncthreads();
-    if (id + 1 < id1) stage(id + 1, hbuf + ((id + 1 - id0) & 1) * a.hpos);
+    if (a.nbuf == 2 && id + 1 < id1) stage(id + 1, hbuf + ((id + 1 - id0) & 1) * TERMS * a.hpos);
 
-    for (int sl = wave_k; sl < slabs; sl += WAVES_K) {
-      const int nsl = sl + WAVES_K;
-      const uint4* nsrc = nsl < slabs ? frag_ptr(id, nsl) : (id + 1 < id1 ? frag_ptr(id + 1, first_sl) : frag_ptr(id, sl));
-      const int4 o4 = *reinterpret_cast<const int4*>(tbl + sl * 8 + half * 4);
-      const int o[4] = {o4.x, o4.y, o4.z, o4.w};
+    if constexpr (TERMS == 3) {
+      auto read_offsets = [&](int sl, int (&dst)[4]) {
+        const int4 o4 = *reinterpret_cast<const int4*>(tbl + sl * 8 + half * 4);
+        dst[0] = o4.x, dst[1] = o4.y, dst[2] = o4.z, dst[3] = o4.w;
+      };
+      int o[4] = {0, 0, 0, 0};
+      uint4 bfr[TERMS][TN];
+      if (wave_k < slabs) {
+        read_offsets(wave_k, o);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        uint4 bfr[TN], cur[TM];
+        for (int t = 0; t < TERMS; ++t)
 #pragma unroll
-        for (int ni = 0; ni < TN; ++ni) bfr[ni] = halo[tap_base[ni] + o[i]];
-#pragma unroll
-        for (int mi = 0; mi < TM; ++mi) {
-          cur[mi] = af[i][mi];
-          af[i][mi] = nsrc[mi * mstride + i * 64];
-        }
-        // keep the fragment loads of the next slab ahead of this step's MFMAs: a full slab of lead time
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-          for (int ni = 0; ni < TN; ++ni) acc[mi][ni] = mfma_bf16(cur[mi], bfr[ni], acc[mi][ni]);
+          for (int ni = 0; ni < TN; ++ni) bfr[t][ni] = halo[t * a.hpos + tap_base[ni] + o[0]];
       }
+      for (int sl = wave_k; sl < slabs; sl += WAVES_K) {
+        const int nsl = sl + WAVES_K;
+        const uint4* csrc = frag_ptr(id, sl);
+        const uint4* nsrc = nsl < slabs ? frag_ptr(id, nsl) : (id + 1 < id1 ? frag_ptr(id + 1, first_sl) : frag_ptr(id, sl));
+        // offsets of this wave's next slab (past the chunk's last slab: any slab's - the words read with them are
+        // dropped when the next chunk reads its own first step)
+        int on[4];
+        read_offsets(min(nsl, chunk_slabs - 1), on);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          uint4 cur[TERMS][TM], bnext[TERMS][TN];
+          const uint4* nptr = i + 1 < 4 ? csrc + (i + 1) * 64 : nsrc;
+          const int onext = i + 1 < 4 ? o[(i + 1) & 3] : on[0];
+          constexpr int kOrderA[3] = {2, 0, 1}, kOrderB[3] = {0, 2, 1};  // the order of first use in the next step
+#pragma unroll
+          for (int k = 0; k < TERMS; ++k)
+#pragma unroll
+            for (int mi = 0; mi < TM; ++mi) {
+              const int t = kOrderA[k];
+              cur[t][mi] = af[t][0][mi];
+              af[t][0][mi] = nptr[t * a.dyf_term + mi * mstride];
+            }
+#pragma unroll
+          for (int k = 0; k < TERMS; ++k)
+#pragma unroll
+            for (int ni = 0; ni < TN; ++ni) {
+              const int t = kOrderB[k];
+              bnext[t][ni] = halo[t * a.hpos + tap_base[ni] + onext];
+            }
+#pragma unroll
+          for (int pr = 0; pr < PAIRS; ++pr)
+#pragma unroll
+            for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+              for (int ni = 0; ni < TN; ++ni) acc[mi][ni] = mfma_bf16(cur[kTermA[pr]][mi], bfr[kTermB[pr]][ni], acc[mi][ni]);
+          // issue order: one fragment load and one halo read after every TM * TN MFMAs, in the shadow of the matrix pipe
+#pragma unroll
+          for (int k = 0; k < TERMS * TM; ++k) {
+            __builtin_amdgcn_sched_group_barrier(0x008, PAIRS * TN / TERMS, 0);  // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                   // global read
+            if (k < TERMS * TN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // LDS read
+          }
+#pragma unroll
+          for (int t = 0; t < TERMS; ++t)
+#pragma unroll
+            for (int ni = 0; ni < TN; ++ni) bfr[t][ni] = bnext[t][ni];
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = on[i];
+      }
+    } else {
+      for (int sl = wave_k; sl < slabs; sl += WAVES_K) {
+        const int nsl = sl + WAVES_K;
+        const uint4* nsrc = nsl < slabs ? frag_ptr(id, nsl) : (id + 1 < id1 ? frag_ptr(id + 1, first_sl) : frag_ptr(id, sl));
+        const int4 o4 = *reinterpret_cast<const int4*>(tbl + sl * 8 + half * 4);
+        const int o[4] = {o4.x, o4.y, o4.z, o4.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          uint4 bfr[TN], cur[TM];
+#pragma unroll
+          for (int ni = 0; ni < TN; ++ni) bfr[ni] = halo[tap_base[ni] + o[i]];
+#pragma unroll
+          for (int mi = 0; mi < TM; ++mi) {
+            cur[mi] = af[0][i][mi];
+            af[0][i][mi] = nsrc[mi * mstride + i * 64];
+          }
+          // keep the fragment loads of the next slab ahead of this step's MFMAs: a full slab of lead time
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < TN; ++ni) acc[mi][ni] = mfma_bf16(cur[mi], bfr[ni], acc[mi][ni]);
+        }
+      }
+    }
+    if (a.nbuf == 1 && id + 1 < id1) {  // one buffer: every wave is done reading it, then it is refilled
+      __syncthreads();
+      stage(id + 1, hbuf);
     }
   }
 
@@ -882,7 +984,7 @@ __global__ __launch_bounds__(kThreads, 2) void filter_grad_bf16_kernel(FilterBf1
   float* dst = a.out + (int64_t)blockIdx.y * a.m * a.K;
 #pragma unroll
   for (int ni = 0; ni < TN; ++ni) {
-    const int col = k0 + ni * 32 + l32;
+    const int col = kw0 + ni * 32 + l32;
     if (col >= a.K) continue;
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi)
@@ -905,46 +1007,71 @@ static ConvGeom flatten_pointwise(const ConvGeom& g) {
   return f;
 }
 
-bool filter_grad_bf16_plan(const ConvGeom& g0, FilterGradBf16Plan* p) {
+bool filter_grad_bf16_plan(const ConvGeom& g0, FilterGradBf16Plan* p, int terms) {
   const ConvGeom g = flatten_pointwise(g0);
   const int rs = g.r * g.s;
   if ((int64_t)g.c * g.h * g.w > 0x7fffffffLL || g.K > 0x7fffffffLL) return false;
-  p->waves_m = g.M > 128 ? 4 : (g.M > 64 ? 2 : 1);
-  p->tm = g.M <= 32 ? 1 : 2;
-  const int waves_k = 4 / p->waves_m;
+  p->terms = terms, p->waves_n = 1;
+  int tn = 0;
+  if (terms == 3) {
+    // built for many maps: the four waves take 64 columns each of the same 64 maps (the registers of three terms
+    // leave room for the accumulators of 64 x 64 wave tiles)
+    if (g.M <= 128) return false;
+    p->waves_m = 1, p->waves_n = 4, p->tm = 2, tn = 2;
+  } else {
+    p->waves_m = g.M > 128 ? 4 : (g.M > 64 ? 2 : 1);
+    p->tm = g.M <= 32 ? 1 : 2;
+    // column tile: least padding of the kernel-matrix width, wider on ties
+    int64_t padded = 0;
+    for (int t : kTnChoices) {
+      const int64_t pd = ceil_div(g.K, 32 * t) * 32 * t;
+      if (tn == 0 || pd <= padded) tn = t, padded = pd;
+    }
+  }
+  const int waves_k = 4 / (p->waves_m * p->waves_n);
   const int bm = 32 * p->tm * p->waves_m;
   const int tiles_m = (int)ceil_div(g.M, bm);
-  // column tile: least padding of the kernel-matrix width, wider on ties
-  int tn = 0;
-  int64_t padded = 0;
-  for (int t : kTnChoices) {
-    const int64_t pd = ceil_div(g.K, 32 * t) * 32 * t;
-    if (tn == 0 || pd <= padded) tn = t, padded = pd;
-  }
-  const int bn = 32 * tn;
+  const int bn = 32 * tn * p->waves_n;
   p->tn = tn;
   p->wp = g.w + 2 * g.pw;
-  p->ccs = (int)std::min<int64_t>(g.c, (bn + rs - 2) / rs + 1);  // channels a run of bn columns can touch
+  // channels a run of bn columns can touch (one when the column tiles never straddle a channel)
+  p->ccs = rs % bn == 0 ? 1 : (int)std::min<int64_t>(g.c, (bn + rs - 2) / rs + 1);
   const size_t red_bytes = waves_k > 1 ? (size_t)p->waves_m * p->tm * tn * 16 * 64 * sizeof(float) : 0;
   if (red_bytes > kLdsBudget) return false;
-  // most output rows per run whose double-buffered halo tile fits
+  // most output rows per run whose halo tile fits twice - or, three planes of a large kernel, once: then a chunk is
+  // staged between the products of two chunks, not during them, and the other resident block covers the gap
   int bh = 0;
-  for (int t = 1; t <= g.oh; ++t) {
-    const int uch = (int)ceil_div((int64_t)t * g.ow, 8) * 8;
-    const size_t hpos = ((size_t)p->ccs * (t + g.r - 1) * p->wp + 63) & ~(size_t)63;
-    if ((size_t)uch * 4 + 2 * hpos * 16 > kLdsBudget || uch > 4096) break;
-    bh = t;
+  for (p->nbuf = 2; p->nbuf >= (terms == 3 ? 1 : 2) && bh == 0; --p->nbuf) {
+    for (int t = 1; t <= g.oh; ++t) {
+      const int uch = (int)ceil_div((int64_t)t * g.ow, 8) * 8;
+      const size_t hpos = ((size_t)p->ccs * (t + g.r - 1) * p->wp + 63) & ~(size_t)63;
+      if ((size_t)uch * 4 + p->nbuf * terms * hpos * 16 > kLdsBudget || uch > 4096) break;
+      bh = t;
+    }
+    if (bh) break;
   }
   if (bh == 0) return false;
   p->bh = bh, p->bp = bh * g.ow, p->nr = bh + g.r - 1;
   p->uch = (int)ceil_div((int64_t)p->bp, 8) * 8;
   p->hpos = (int)(((size_t)p->ccs * p->nr * p->wp + 63) & ~(size_t)63);
-  p->lds_bytes = std::max((size_t)p->uch * 4 + 2 * (size_t)p->hpos * 16, red_bytes);
+  p->lds_bytes = std::max((size_t)p->uch * 4 + p->nbuf * terms * (size_t)p->hpos * 16, red_bytes);
   p->runs = (int)ceil_div(g.oh, bh);
   p->ngroups = (g.n + 7) / 8;
   p->chunks = p->ngroups * p->runs;
   const int64_t tiles = (int64_t)tiles_m * ceil_div(g.K, bn);
   int64_t want = ceil_div(512, tiles);
+  if (terms == 3) {
+    // long blocks that keep the matrix pipe busy: the 256 CUs share them evenly when there are many per CU, or a
+    // whole number; of the even splits of the chunks, the first that leaves the last CU at least 90 % of a share
+    for (int64_t wn = want; wn <= p->chunks; ++wn) {
+      if (p->chunks % wn) continue;
+      const double per_cu = (double)tiles * wn / 256.0;
+      if (per_cu / std::ceil(per_cu) >= 0.9) {
+        want = wn;
+        break;
+      }
+    }
+  }
   if (want > p->chunks) want = p->chunks;
   if (want < 1) want = 1;
   p->chunks_per_split = (int)ceil_div(p->chunks, want);
@@ -956,9 +1083,9 @@ bool filter_grad_bf16_plan(const ConvGeom& g0, FilterGradBf16Plan* p) {
   return tiles <= 0x7fffffffLL && p->splits <= 65535;
 }
 
-template <int WAVES_M, int WAVES_K, int TM, int TN>
+template <int WAVES_M, int WAVES_K, int TM, int TN, int WAVES_N = 1, int TERMS = 1>
 static void launch_filter_one(const FilterBf16Args& a, unsigned tiles, unsigned splits, size_t lds, hipStream_t st) {
-  auto kernel = filter_grad_bf16_kernel<WAVES_M, WAVES_K, TM, TN>;
+  auto kernel = filter_grad_bf16_kernel<WAVES_M, WAVES_K, TM, TN, WAVES_N, TERMS>;
   static bool opted = false;
   if (!opted) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -983,36 +1110,40 @@ vcnn_status launch_filter_grad_bf16(const FilterGradBf16Plan& p, const ConvGeom&
                                           (float*)((char*)workspace + p.x8n_bytes + p.dyf_bytes), st, accumulate);
 }
 
-vcnn_status launch_filter_grad_bf16_prepared(const FilterGradBf16Plan& p, const ConvGeom& g0, const void* x, const void* dy,
-                                             float* dw, void* x8n_buf, void* dyf_buf, float* partial, hipStream_t st,
-                                             int accumulate) {
-  const ConvGeom g = flatten_pointwise(g0);
-  uint4* x8n = (uint4*)x8n_buf;
-  uint4* dyf = (uint4*)dyf_buf;
+static vcnn_status relay_images(const FilterGradBf16Plan& p, const ConvGeom& g, const void* x, void* x8n_buf, hipStream_t st) {
   const int64_t chw = (int64_t)g.c * g.h * g.w;
-  if (x) {
-    const int64_t total = (int64_t)p.ngroups * chw;
-    hipLaunchKernelGGL(interleave_images_kernel, dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, st,
-                       (const bf16*)x, x8n, g.n, chw, total);
-    if (vcnn_status e = check_launch("interleave_images")) return e;
-  }
-  if (dy) {
-    const int64_t total = (int64_t)p.ngroups * p.mt_total * 32 * p.runs * p.uch;
-    hipLaunchKernelGGL(dy_fragments_kernel, dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, st,
-                       (const bf16*)dy, dyf, g.n, (int)g.M, (int)g.P, p.mt_total, p.runs, p.bp, p.uch, total);
-    if (vcnn_status e = check_launch("dy_fragments")) return e;
-  }
+  const int64_t total = (int64_t)p.ngroups * chw;
+  hipLaunchKernelGGL(interleave_images_kernel, dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, st,
+                     (const bf16*)x, (uint4*)x8n_buf, g.n, chw, total);
+  return check_launch("interleave_images");
+}
+
+static vcnn_status relay_dy(const FilterGradBf16Plan& p, const ConvGeom& g, const void* dy, void* dyf_buf, hipStream_t st) {
+  const int64_t total = (int64_t)p.ngroups * p.mt_total * 32 * p.runs * p.uch;
+  hipLaunchKernelGGL(dy_fragments_kernel, dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, st,
+                     (const bf16*)dy, (uint4*)dyf_buf, g.n, (int)g.M, (int)g.P, p.mt_total, p.runs, p.bp, p.uch, total);
+  return check_launch("dy_fragments");
+}
+
+// the product on re-laid operands (g flattened), slices summed into dw (added to its contents when `accumulate`)
+static vcnn_status launch_filter_product(const FilterGradBf16Plan& p, const ConvGeom& g, float* dw, const void* x8n_buf,
+                                         const void* dyf_buf, float* partial, hipStream_t st, int accumulate) {
+  const uint4* x8n = (const uint4*)x8n_buf;
+  const int64_t chw = (int64_t)g.c * g.h * g.w;
   FilterBf16Args a{};
   // accumulate: dw += the product (the slice sum takes dw as its addend); the workspace then holds at least one slice
-  a.x8n = x8n, a.zero = x8n + (int64_t)p.ngroups * chw, a.dyf = dyf, a.out = (p.splits > 1 || accumulate) ? partial : dw;
+  a.x8n = x8n, a.zero = x8n + (int64_t)p.ngroups * chw, a.dyf = (const uint4*)dyf_buf;
+  a.x8n_term = (int64_t)(p.x8n_bytes / 16), a.dyf_term = (int64_t)(p.dyf_bytes / 16);  // (read by the three-term form only)
+  a.out = (p.splits > 1 || accumulate) ? partial : dw;
   a.c = g.c, a.h = g.h, a.w = g.w, a.m = g.k, a.r = g.r, a.s = g.s, a.ph = g.ph, a.pw = g.pw, a.oh = g.oh, a.ow = g.ow;
   a.K = (int)g.K;
   a.tiles_m = (int)ceil_div(g.M, 32 * p.tm * p.waves_m), a.mt_total = p.mt_total;
   a.runs = p.runs, a.bh = p.bh, a.bp = p.bp;
-  a.uch = p.uch, a.hpos = p.hpos, a.ccs = p.ccs, a.nr = p.nr, a.wp = p.wp;
+  a.uch = p.uch, a.hpos = p.hpos, a.ccs = p.ccs, a.nr = p.nr, a.wp = p.wp, a.nbuf = p.nbuf;
   a.chunks = p.chunks, a.chunks_per_split = p.chunks_per_split;
-  const unsigned tiles = (unsigned)(a.tiles_m * ceil_div(g.K, 32 * p.tn));
-  if (p.tn == 2) launch_filter_tn<2>(a, p.waves_m, p.tm, tiles, (unsigned)p.splits, p.lds_bytes, st);
+  const unsigned tiles = (unsigned)(a.tiles_m * ceil_div(g.K, 32 * p.tn * p.waves_n));
+  if (p.terms == 3) launch_filter_one<1, 1, 2, 2, 4, 3>(a, tiles, (unsigned)p.splits, p.lds_bytes, st);
+  else if (p.tn == 2) launch_filter_tn<2>(a, p.waves_m, p.tm, tiles, (unsigned)p.splits, p.lds_bytes, st);
   else if (p.tn == 4) launch_filter_tn<4>(a, p.waves_m, p.tm, tiles, (unsigned)p.splits, p.lds_bytes, st);
   else launch_filter_tn<5>(a, p.waves_m, p.tm, tiles, (unsigned)p.splits, p.lds_bytes, st);
   if (vcnn_status e = check_launch("filter_grad_bf16")) return e;
@@ -1020,6 +1151,31 @@ vcnn_status launch_filter_grad_bf16_prepared(const FilterGradBf16Plan& p, const 
   if (accumulate)  // "bias" of element i = dw[i]
     return launch_sum_slices(partial, dw, dw, VCNN_F32, g.M * g.K, p.splits, 1, (int)(g.M * g.K), 0, st);
   return launch_sum_slices(partial, nullptr, dw, VCNN_F32, g.M * g.K, p.splits, 1, 1, 0, st);
+}
+
+vcnn_status launch_filter_grad_bf16_prepared(const FilterGradBf16Plan& p, const ConvGeom& g0, const void* x, const void* dy,
+                                             float* dw, void* x8n_buf, void* dyf_buf, float* partial, hipStream_t st,
+                                             int accumulate) {
+  const ConvGeom g = flatten_pointwise(g0);
+  if (x)
+    if (vcnn_status e = relay_images(p, g, x, x8n_buf, st)) return e;
+  if (dy)
+    if (vcnn_status e = relay_dy(p, g, dy, dyf_buf, st)) return e;
+  return launch_filter_product(p, g, dw, x8n_buf, dyf_buf, partial, st, accumulate);
+}
+
+// Three-term form (p planned with terms = 3): x_terms / dy_terms hold the three bfloat16 terms of the float input and
+// output gradient, each term `x_term_bytes` / `dy_term_bytes` after the one before; x8n_bufs / dyf_bufs take the three
+// re-laid copies (3 x p.x8n_bytes, 3 x p.dyf_bytes), `partial` the slices.  One product kernel multiplies the six pairs.
+vcnn_status launch_filter_grad_bf16_terms(const FilterGradBf16Plan& p, const ConvGeom& g0, const void* x_terms,
+                                          size_t x_term_bytes, const void* dy_terms, size_t dy_term_bytes, float* dw,
+                                          void* x8n_bufs, void* dyf_bufs, float* partial, hipStream_t st) {
+  const ConvGeom g = flatten_pointwise(g0);
+  for (int t = 0; t < 3; ++t) {
+    if (vcnn_status e = relay_images(p, g, (const char*)x_terms + t * x_term_bytes, (char*)x8n_bufs + t * p.x8n_bytes, st)) return e;
+    if (vcnn_status e = relay_dy(p, g, (const char*)dy_terms + t * dy_term_bytes, (char*)dyf_bufs + t * p.dyf_bytes, st)) return e;
+  }
+  return launch_filter_product(p, g, dw, x8n_bufs, dyf_bufs, partial, st, 0);
 }
 
 }  // namespace vcnn

@@ -201,6 +201,9 @@ vcnn_status launch_conv_halo_bf16_terms(const HaloBf16Plan& p, int n, int c, int
                                         int relu, void* x8_bufs, void* wf_bufs, hipStream_t st);
 struct FilterGradBf16Plan {
   int waves_m, tm, tn;
+  int waves_n;       // waves of a block along the kernel-matrix columns (same maps)
+  int terms;         // 1: bfloat16 operands; 3: float operands as three bfloat16 terms each, six products per step
+  int nbuf;          // halo buffers in LDS (2, or 1 when three planes only fit once)
   int ccs, nr, wp;   // channels, rows and row pitch of the halo tile
   int bh, bp, runs;  // output rows / pixels per run, runs per image
   int ngroups;       // image groups of 8
@@ -209,7 +212,7 @@ struct FilterGradBf16Plan {
   int mt_total;
   size_t lds_bytes, x8n_bytes, dyf_bytes, partial_bytes;
 };
-bool filter_grad_bf16_plan(const ConvGeom& g, FilterGradBf16Plan* p);
+bool filter_grad_bf16_plan(const ConvGeom& g, FilterGradBf16Plan* p, int terms = 1);
 // workspace: x8n_bytes + dyf_bytes + partial_bytes
 // accumulate: dw += the product; the workspace then needs max(partial_bytes, one slice of M*K floats) behind dyf
 vcnn_status launch_filter_grad_bf16(const FilterGradBf16Plan& p, const ConvGeom& g, const void* x, const void* dy,
@@ -219,6 +222,9 @@ vcnn_status launch_filter_grad_bf16(const FilterGradBf16Plan& p, const ConvGeom&
 vcnn_status launch_filter_grad_bf16_prepared(const FilterGradBf16Plan& p, const ConvGeom& g, const void* x, const void* dy,
                                              float* dw, void* x8n_buf, void* dyf_buf, float* partial, hipStream_t st,
                                              int accumulate);
+vcnn_status launch_filter_grad_bf16_terms(const FilterGradBf16Plan& p, const ConvGeom& g, const void* x_terms,
+                                          size_t x_term_bytes, const void* dy_terms, size_t dy_term_bytes, float* dw,
+                                          void* x8n_bufs, void* dyf_bufs, float* partial, hipStream_t st);
 
 // ---- split_bf16.hip: fp32 products of large layers as sums of bf16 products (on request only) ------------------------
 struct SplitPlan {

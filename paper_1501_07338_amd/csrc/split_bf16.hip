@@ -60,7 +60,7 @@ bool conv_split_plan(const ConvGeom& g, int pass, SplitPlan* p) {
     return true;
   }
   if (pass == VCNN_PASS_BWD_FILTER) {
-    if (g.k <= 4 || g.c <= 4 || !filter_grad_bf16_plan(g, &p->filter)) return false;
+    if (g.k <= 4 || g.c <= 4 || !(filter_grad_bf16_plan(g, &p->filter, 3) || filter_grad_bf16_plan(g, &p->filter))) return false;
     const size_t slices = std::max(p->filter.partial_bytes, (size_t)g.M * g.K * sizeof(float));
     p->inner_bytes = 3 * (p->filter.x8n_bytes + p->filter.dyf_bytes) + align256(slices);
     p->workspace_bytes = 3 * p->part_x_bytes + 3 * p->part_dy_bytes + p->inner_bytes;
@@ -105,6 +105,8 @@ vcnn_status launch_conv_split_filter(const SplitPlan& p, const ConvGeom& g, cons
   float* slices = (float*)(dfs + 3 * p.filter.dyf_bytes);
   if (vcnn_status e = split3(x, xs, p.part_x_bytes, (int64_t)g.n * g.c * g.h * g.w, st)) return e;
   if (vcnn_status e = split3(dy, ds, p.part_dy_bytes, g.M * g.N, st)) return e;
+  if (p.filter.terms == 3)
+    return launch_filter_grad_bf16_terms(p.filter, g, xs, p.part_x_bytes, ds, p.part_dy_bytes, dw, x8s, dfs, slices, st);
   bool x_done[3] = {false, false, false}, d_done[3] = {false, false, false};
   for (int t = 0; t < 6; ++t) {
     const int i = kPairs[t][0], j = kPairs[t][1];
