@@ -26,38 +26,14 @@
 #include <algorithm>
 #include <type_traits>
 
+#include "bf16_core.h"
 #include "common.h"
 #include "elem.h"
 
 namespace vcnn {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-
 static constexpr int kThreads = 256;
 static constexpr size_t kLdsBudget = 78 * 1024;  // two blocks per CU
-
-// Direct global -> LDS load of 16 bytes per lane: lane i of the wave deposits its bytes at lds_base + 16 i
-// (lds_base wave-uniform, held in M0).  Issued through inline assembly so that the compiler's wait-count
-// pass does not see it: seeing it, it drains every outstanding load before each later LDS read, and the
-// fragment prefetch loses its lead.  The kernels wait for these loads themselves (vmcnt(0) before the barrier
-// that publishes a tile); the hidden loads only make the compiler's own vmcnt waits more conservative,
-// never too short, because loads complete in order.
-#pragma clang diagnostic push
-#pragma clang diagnostic ignored "-Winline-asm"  // M0 is reserved by the compiler; naming it as clobbered is still right
-__device__ __forceinline__ void load_to_lds16(const uint4* src, uint4* lds_base) {
-  const unsigned base = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)lds_base);  // low half = LDS offset
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(base), "v"(src) : "memory", "m0");
-}
-#pragma clang diagnostic pop
-
-__device__ __forceinline__ f32x16 mfma_bf16(uint4 a, uint4 b, f32x16 c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-}
-__device__ __forceinline__ f32x4 mfma_bf16(uint4 a, uint4 b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-}
 
 // x8[n][g][pos][c8] = x[n][8g + c8][pos], zero for channels >= C; x8[total] = 0 (the padding source)
 __global__ __launch_bounds__(kThreads) void interleave_channels_kernel(const bf16* __restrict__ x, uint4* __restrict__ x8,
@@ -595,6 +571,21 @@ vcnn_status launch_conv_halo_bf16(const HaloBf16Plan& p, int n, int c, int h, in
                                   void* y, int relu, void* workspace, hipStream_t st, float* y32, int accumulate) {
   return launch_conv_halo_bf16_prepared(p, n, c, h, w, m, r, s, ph, pw, x, wgt, w_so, w_si, flip, bias, y, relu, workspace,
                                         (char*)workspace + p.x8_bytes, st, y32, accumulate);
+}
+
+vcnn_status launch_interleave_channels(const void* x, void* x8, int n, int c, int groups, int hw, hipStream_t st) {
+  const int64_t total = (int64_t)n * groups * hw;
+  hipLaunchKernelGGL(interleave_channels_kernel, dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, st,
+                     (const bf16*)x, (uint4*)x8, c, groups, hw, total);
+  return check_launch("interleave_channels");
+}
+
+vcnn_status launch_reorder_weights_frag(const void* in, void* out, int rows, int channels, int rs, int64_t so, int64_t si,
+                                        int flip, int cgc, int nchunks, int steps, int m16, int64_t row_tiles, hipStream_t st) {
+  const int64_t total = row_tiles * nchunks * steps * 512;
+  hipLaunchKernelGGL(reorder_weights_frag_kernel, dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, st,
+                     (const bf16*)in, (bf16*)out, rows, channels, rs, so, si, flip, cgc, nchunks, steps, m16, total);
+  return check_launch("reorder_weights_frag");
 }
 
 // the two re-laying passes of one operand each, and the product on re-laid operands
