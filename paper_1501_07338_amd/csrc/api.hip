@@ -187,7 +187,10 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
     p.workspace_bytes += align256(bias_grad_partial_bytes(g));
     return p;
   }
-  if (bf16_mfma && pass == VCNN_PASS_BWD_FILTER && bwd_filter_bf16_plan(g, &p.fb)) {
+  // (at most four channels and a narrow kernel matrix: the whole-matrix-per-block kernel below reads the input in place,
+  // where this route writes a patch matrix first)
+  if (bf16_mfma && pass == VCNN_PASS_BWD_FILTER && !(g.c <= 4 && g.k > 4 && filter_grad_few_cols_plan(g, &p.fcp)) &&
+      bwd_filter_bf16_plan(g, &p.fb)) {
     p.path = PATH_FILTER_BF16;
     p.workspace_bytes = p.fb.dyt_bytes + p.fb.col_bytes + align256(p.fb.partial_bytes);
     p.bias_offset = p.workspace_bytes;

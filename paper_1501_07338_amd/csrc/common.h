@@ -110,6 +110,8 @@ struct HaloPlan {
   int cc;            // input channels staged per chunk
   int nr, wp;        // halo tile rows and row pitch per channel
   int kch;           // taps per chunk, padded to the slab depth
+  int tw;            // 0: tiles are runs of bn consecutive pixels; else strips of bn / tw rows x tw columns
+  int64_t tiles_per_img;
   size_t lds_bytes;
   bool vec;          // kernel-matrix rows can be fetched 16 bytes at a time
 };
@@ -134,6 +136,7 @@ vcnn_status launch_conv_halo_filter(const HaloFilterPlan& p, int dtype, const Co
 struct FewColsPlan {
   int tm, tn;        // 32-row / 32-column tiles of the whole M x K result
   int nr, wp;
+  int tw;            // 0: runs of consecutive pixels; else strips of 128 / tw rows x tw columns
   int runs_per_img, total_runs, runs_per_block, blocks;
   bool bias_column;  // the kernel can produce the bias gradient in a spare column of its last tile
   size_t lds_bytes, partial_bytes;

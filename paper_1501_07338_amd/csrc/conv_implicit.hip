@@ -1,5 +1,6 @@
 // Implicit-unroll convolution on the matrix cores: the patch matrix phi_c(x) of Eq. 2 / Eq. 4 is never
-// written.  A block owns BM output maps x BN consecutive output pixels of one sample.  For a chunk of
+// written.  A block owns BM output maps x BN output pixels of one sample (a run of consecutive pixels, or - for
+// tall kernels on wide planes - a strip of rows x columns).  For a chunk of
 // input channels it stages the input rows those pixels touch (with their halo, zero padded) in LDS;
 // the B operand of every MFMA step is then read straight from that tile at
 //     lane_base(pixel) + tap_offset(c, r, s),
@@ -34,7 +35,24 @@ struct HaloArgs {
   int wp;             // halo row pitch (w + 2*pw)
   int kch;            // taps per full chunk, padded to a multiple of BK
   int relu;
+  int tw, tiles_x;    // tw > 0: a tile is a strip of BN / tw output rows x tw output columns (tiles_x strips side by side)
 };
+
+// Pixel q of a block's tile as a flat index into the sample's output plane (-1: outside it), and its position inside
+// the halo tile.  Tiles are runs of consecutive pixels starting at p0 (first row oh0), or strips whose first pixel is
+// (oh0, ow0).  A pixel outside the plane still gets a position inside the tile: its products are dropped at the end.
+__device__ __forceinline__ int tile_pixel(const HaloArgs& a, int p0, int oh0, int ow0, int q, int* base) {
+  if (a.tw) {
+    const int ty = q / a.tw, tx = q - ty * a.tw;
+    *base = ty * a.wp + tx;
+    const int oh = oh0 + ty, ow = ow0 + tx;
+    return oh < a.oh && ow < a.ow ? oh * a.ow + ow : -1;
+  }
+  const int p = min(p0 + q, a.P - 1);
+  const int oh = p / a.ow;
+  *base = (oh - oh0) * a.wp + (p - oh * a.ow);
+  return p0 + q < a.P ? p : -1;
+}
 
 // Copies channels [0, cc) x rows ih0 + [0, nr) x columns -pw + [0, wp) of one sample's planes x[.][h][w]
 // into the LDS tile [cc][nr][wp]; positions outside the image, and channels at or beyond cvalid, become
@@ -84,14 +102,16 @@ __global__ __launch_bounds__(kThreads) void conv_halo_kernel(HaloArgs a) {
   const int tm = blockIdx.x % a.tiles_m;
   const int tj = blockIdx.x / a.tiles_m;
   const int n = tj / a.tiles_per_img;
-  const int p0 = (tj - n * a.tiles_per_img) * BN;
+  const int tq = tj - n * a.tiles_per_img;
+  const int p0 = a.tw ? 0 : tq * BN;
+  const int oh_first = a.tw ? tq / a.tiles_x * (BN / a.tw) : p0 / a.ow;  // first output row and column of the tile
+  const int ow_first = a.tw ? tq % a.tiles_x * a.tw : 0;
   const int i0 = tm * BM;
   const int wm0 = (wave % (BM / WM)) * WM;
   const int wn0 = (wave / (BM / WM)) * WN;
   const int RS = a.r * a.s;
   const int K = a.c * RS;
   const int plane = a.nr * a.wp;
-  const int oh_first = p0 / a.ow;
 
   // tap table: offset of tap kk = (c_l, r, s) inside the halo tile; padding taps point at 0 (their
   // kernel-matrix entries are zero).
@@ -109,11 +129,7 @@ __global__ __launch_bounds__(kThreads) void conv_halo_kernel(HaloArgs a) {
   // this lane's pixels (one per 32-wide accumulator column block)
   int lane_base[TN];
 #pragma unroll
-  for (int ni = 0; ni < TN; ++ni) {
-    const int p = min(p0 + wn0 + ni * 32 + l32, a.P - 1);
-    const int oh = p / a.ow;
-    lane_base[ni] = (oh - oh_first) * a.wp + (p - oh * a.ow);
-  }
+  for (int ni = 0; ni < TN; ++ni) (void)tile_pixel(a, p0, oh_first, ow_first, wn0 + ni * 32 + l32, &lane_base[ni]);
 
   SA sa;
   sa.init(tid);
@@ -156,7 +172,7 @@ __global__ __launch_bounds__(kThreads) void conv_halo_kernel(HaloArgs a) {
     fetch(0);
     __syncthreads();  // previous chunk's MFMAs are done with the halo tile and the A slabs
     // stage the halo rows of this chunk: input rows oh_first - ph + [0, nr), columns -pw + [0, wp)
-    stage_halo<8>(halo, xin + (int64_t)c0 * a.h * a.w, cc, cc, a.nr, a.wp, a.h, a.w, oh_first - a.ph, a.pw, tid);
+    stage_halo<8>(halo, xin + (int64_t)c0 * a.h * a.w, cc, cc, a.nr, a.wp, a.h, a.w, oh_first - a.ph, a.pw - ow_first, tid);
     sa.store(As0);
     __syncthreads();
 
@@ -195,8 +211,9 @@ __global__ __launch_bounds__(kThreads) void conv_halo_kernel(HaloArgs a) {
 
 #pragma unroll
   for (int ni = 0; ni < TN; ++ni) {
-    const int p = p0 + wn0 + ni * 32 + l32;
-    if (p >= a.P) continue;
+    int unused;
+    const int p = tile_pixel(a, p0, oh_first, ow_first, wn0 + ni * 32 + l32, &unused);
+    if (p < 0) continue;
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
@@ -236,13 +253,15 @@ __global__ __launch_bounds__(kThreads) void conv_halo16_kernel(HaloArgs a) {
   const int tm = blockIdx.x % a.tiles_m;
   const int tj = blockIdx.x / a.tiles_m;
   const int n = tj / a.tiles_per_img;
-  const int p0 = (tj - n * a.tiles_per_img) * BN;
+  const int tq = tj - n * a.tiles_per_img;
+  const int p0 = a.tw ? 0 : tq * BN;
+  const int oh_first = a.tw ? tq / a.tiles_x * (BN / a.tw) : p0 / a.ow;  // first output row and column of the tile
+  const int ow_first = a.tw ? tq % a.tiles_x * a.tw : 0;
   const int i0 = tm * BM;
   const int wn0 = wave * WN;
   const int RS = a.r * a.s;
   const int K = a.c * RS;
   const int plane = a.nr * a.wp;
-  const int oh_first = p0 / a.ow;
 
   for (int kk = tid; kk < a.kch; kk += kThreads) {  // tap table, as above
     int off = 0;
@@ -257,11 +276,7 @@ __global__ __launch_bounds__(kThreads) void conv_halo16_kernel(HaloArgs a) {
 
   int lane_base[TN];
 #pragma unroll
-  for (int ni = 0; ni < TN; ++ni) {
-    const int p = min(p0 + wn0 + ni * 16 + l16, a.P - 1);
-    const int oh = p / a.ow;
-    lane_base[ni] = (oh - oh_first) * a.wp + (p - oh * a.ow);
-  }
+  for (int ni = 0; ni < TN; ++ni) (void)tile_pixel(a, p0, oh_first, ow_first, wn0 + ni * 16 + l16, &lane_base[ni]);
 
   SA sa;
   sa.init(tid);
@@ -307,7 +322,7 @@ __global__ __launch_bounds__(kThreads) void conv_halo16_kernel(HaloArgs a) {
     };
     fetch(0);
     __syncthreads();  // previous chunk's MFMAs are done with the halo tile and the A slabs
-    stage_halo<8>(halo, xin + (int64_t)c0 * a.h * a.w, cc, cc, a.nr, a.wp, a.h, a.w, oh_first - a.ph, a.pw, tid);
+    stage_halo<8>(halo, xin + (int64_t)c0 * a.h * a.w, cc, cc, a.nr, a.wp, a.h, a.w, oh_first - a.ph, a.pw - ow_first, tid);
     sa.store(As0);
     __syncthreads();
 
@@ -348,8 +363,9 @@ __global__ __launch_bounds__(kThreads) void conv_halo16_kernel(HaloArgs a) {
   // 16 x 16 result: register q of lane l holds row 4*(l / 16) + q, column l % 16
 #pragma unroll
   for (int ni = 0; ni < TN; ++ni) {
-    const int p = p0 + wn0 + ni * 16 + l16;
-    if (p >= a.P) continue;
+    int unused;
+    const int p = tile_pixel(a, p0, oh_first, ow_first, wn0 + ni * 16 + l16, &unused);
+    if (p < 0) continue;
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
@@ -422,6 +438,19 @@ static int halo_bk(int m, int64_t K) {
   return m <= 64 ? 64 : 32;
 }
 
+// Strip width for tiles of bn pixels: the widest of 32, 16, 8 columns unless a narrower strip pads the plane clearly less
+// (narrow strips store short row segments).
+static int strip_width(int bn, int oh, int ow) {
+  int best = 0;
+  double best_cost = 0;
+  for (int tw = 32; tw >= 8; tw /= 2) {
+    const int th = bn / tw;
+    const double cost = (double)ceil_div(oh, th) * th * ceil_div(ow, tw) * tw * (tw == 32 ? 1.0 : (tw == 16 ? 1.1 : 1.3));
+    if (best == 0 || cost < best_cost) best = tw, best_cost = cost;
+  }
+  return best;
+}
+
 bool conv_halo_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int pw, HaloPlan* p) {
   const int oh = h + 2 * ph - r + 1, ow = w + 2 * pw - s + 1;
   if (oh <= 0 || ow <= 0 || (int64_t)c * h * w > 0x7fffffffLL) return false;  // 32-bit offsets inside a sample
@@ -429,19 +458,34 @@ bool conv_halo_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int
   int BK = halo_bk(m, (int64_t)c * r * s);
   if (bm == 64 && bn != 256) BK = 64;  // the 32-deep variant exists for the widest pixel tile only
   const int rs = r * s;
-  int rows = (bn + ow - 2) / ow + 1;  // rows a run of bn consecutive pixels can touch
-  if (rows > oh) rows = oh;
-  const int nr = rows + r - 1, wp = w + 2 * pw;
   const size_t a_bytes = 2 * (size_t)(BK + 4) * bm * sizeof(float);
   // largest channel chunk that fits the LDS budget with a tap table of at most 2048 entries
-  int best = 0;
-  for (int cc = 1; cc <= c; ++cc) {
-    const int kch = (int)ceil_div((int64_t)cc * rs, BK) * BK;
-    const size_t bytes = a_bytes + (size_t)kch * 4 + (size_t)cc * nr * wp * 4;
-    if (bytes > (bm == 128 ? kLdsBudget3 : kLdsBudget) || kch > 2048) break;
-    best = cc;
+  auto largest_chunk = [&](int nr, int wp) {
+    int best = 0;
+    for (int cc = 1; cc <= c; ++cc) {
+      const int kch = (int)ceil_div((int64_t)cc * rs, BK) * BK;
+      const size_t bytes = a_bytes + (size_t)kch * 4 + (size_t)cc * nr * wp * 4;
+      if (bytes > (bm == 128 ? kLdsBudget3 : kLdsBudget) || kch > 2048) break;
+      best = cc;
+    }
+    return best;
+  };
+  // Tiles are runs of bn consecutive pixels (whole rows of the plane in the halo tile).  A tall kernel on a wide plane
+  // makes that tile too large for even one channel (121 x 1 taps on 184 columns: 123 rows x 184); then the tile is a
+  // strip of bn / tw rows x tw columns, whose halo is as narrow as the strip.
+  int rows = (bn + ow - 2) / ow + 1;  // rows a run of bn consecutive pixels can touch
+  if (rows > oh) rows = oh;
+  int nr = rows + r - 1, wp = w + 2 * pw, tw = 0;
+  int best = largest_chunk(nr, wp);
+  if (best == 0) {
+    tw = strip_width(bn, oh, ow);
+    nr = bn / tw + r - 1, wp = tw + s - 1;
+    // one-column kernels: the lane groups of a step read rows 4 apart; a pitch of 4 (16-row tiles: four groups) or
+    // 8 (32-row tiles: two groups) modulo 16 puts them on different banks
+    if (s == 1) wp += ((bm == 48 ? 4 : 8) - wp % 16 + 16) % 16;
+    best = largest_chunk(nr, wp);
+    if (best == 0) return false;
   }
-  if (best == 0) return false;
   // prefer a chunk whose tap count fills its last slab (fewest zero taps), among chunks at least half as large
   int pick = best;
   double pick_waste = 2.0;
@@ -457,11 +501,12 @@ bool conv_halo_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int
     const double waste = 1.0 - (double)c * rs / (double)(slabs * BK);
     if (waste < pick_waste - 1e-9) pick = cc, pick_waste = waste;
   }
-  p->bm = bm, p->bn = bn, p->bk = BK, p->cc = pick, p->nr = nr, p->wp = wp;
+  p->bm = bm, p->bn = bn, p->bk = BK, p->cc = pick, p->nr = nr, p->wp = wp, p->tw = tw;
   p->kch = (int)ceil_div((int64_t)pick * rs, BK) * BK;
   p->lds_bytes = a_bytes + (size_t)p->kch * 4 + (size_t)pick * nr * wp * 4;
   p->vec = ((int64_t)c * rs) % 4 == 0 && ((int64_t)pick * rs) % 4 == 0;
-  const int64_t tiles = ceil_div(m, bm) * (int64_t)n * ceil_div((int64_t)oh * ow, bn);
+  p->tiles_per_img = tw ? ceil_div(oh, bn / tw) * ceil_div(ow, tw) : ceil_div((int64_t)oh * ow, bn);
+  const int64_t tiles = ceil_div(m, bm) * (int64_t)n * p->tiles_per_img;
   return tiles <= 0x7fffffffLL;
 }
 
@@ -528,7 +573,8 @@ vcnn_status launch_conv_halo(const HaloPlan& p, int dtype, int n, int c, int h, 
   a.oh = h + 2 * ph - r + 1, a.ow = w + 2 * pw - s + 1;
   a.P = a.oh * a.ow;
   a.tiles_m = (int)ceil_div(m, p.bm);
-  a.tiles_per_img = (int)ceil_div(a.P, p.bn);
+  a.tiles_per_img = (int)p.tiles_per_img;
+  a.tw = p.tw, a.tiles_x = p.tw ? (int)ceil_div(a.ow, p.tw) : 0;
   a.cc = p.cc, a.nr = p.nr, a.wp = p.wp, a.kch = p.kch, a.relu = relu;
   const bool vec = p.vec && (dtype == VCNN_BF16 ? group_aligned<bf16>(wgt) : group_aligned<float>(wgt));
   if (p.bm == 32 && p.bn == 512)
@@ -1039,12 +1085,13 @@ struct FewColsArgs {
   int Kp;          // K, or K + 1 when the spare column K carries the bias gradient (B operand = 1 there)
   int runs_per_img, total_runs, runs_per_block;
   int nr, wp;
+  int tw, tiles_x;  // tw > 0: a run is a strip of kRunPixels / tw output rows x tw output columns (tiles_x strips side by side)
 };
 
 static constexpr int kRunPixels = 128;
 
 template <int TM, int TN, typename T>
-__global__ __launch_bounds__(kThreads) void filter_grad_few_cols_kernel(FewColsArgs a) {
+__global__ __launch_bounds__(kThreads, 2) void filter_grad_few_cols_kernel(FewColsArgs a) {
   constexpr int BP = kRunPixels, PITCH = BP + 4, ROWS = 32 * TM;
   extern __shared__ float4 smem4[];
   float* const dyt = reinterpret_cast<float*>(smem4);             // [ROWS][PITCH]
@@ -1075,36 +1122,43 @@ __global__ __launch_bounds__(kThreads) void filter_grad_few_cols_kernel(FewColsA
   const int run1 = min(a.total_runs, run0 + a.runs_per_block);
   for (int run = run0; run < run1; ++run) {
     const int n = run / a.runs_per_img;
-    const int p0 = (run - n * a.runs_per_img) * BP;
-    const int plen = min(BP, a.P - p0);
-    const int oh_first = p0 / a.ow;
+    const int tq = run - n * a.runs_per_img;
+    const int p0 = a.tw ? 0 : tq * BP;
+    const int oh_first = a.tw ? tq / a.tiles_x * (BP / a.tw) : p0 / a.ow;  // first output row and column of the run
+    const int ow_first = a.tw ? tq % a.tiles_x * a.tw : 0;
     __syncthreads();  // the previous run's MFMAs are done with the tiles
-    if (tid < BP) {
-      const int p = min(p0 + tid, a.P - 1);
+    // pixel pk = tid % BP of the run: where it lies in the sample's output plane (-1: outside) and in the halo tile
+    constexpr int MSTEP = kThreads / BP;
+    const int pk = tid % BP;
+    int pix, tile_at;
+    if (a.tw) {
+      const int ty = pk / a.tw, tx = pk - ty * a.tw;
+      const int oh = oh_first + ty, ow = ow_first + tx;
+      pix = oh < a.oh && ow < a.ow ? oh * a.ow + ow : -1;
+      tile_at = ty * a.wp + tx;
+    } else {
+      const int p = min(p0 + pk, a.P - 1);
       const int oh = p / a.ow;
-      pixoff[tid] = (oh - oh_first) * a.wp + (p - oh * a.ow);
+      pix = p0 + pk < a.P ? p : -1;
+      tile_at = (oh - oh_first) * a.wp + (p - oh * a.ow);
     }
+    if (tid < BP) pixoff[tid] = tile_at;
     // dY rows of this run, zero beyond the maps / the sample's pixels.  All of a thread's loads are issued before the
     // halo tile is staged and stored only after it: the run costs one memory round trip, not one per eight loads
-    const T* dyn = static_cast<const T*>(a.dy) + (int64_t)n * a.m * a.P + p0;
+    const T* dyn = static_cast<const T*>(a.dy) + (int64_t)n * a.m * a.P + max(pix, 0);
     constexpr int PER = ROWS * BP / kThreads;
     float dyv[PER];
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
-      const int e = u * kThreads + tid;
-      const int m = e / BP, pk = e - m * BP;
-      const bool ok = m < a.m && pk < plen;
-      const float t = ld(dyn + (ok ? (int64_t)m * a.P + pk : 0));
+      const int m = u * MSTEP + tid / BP;
+      const bool ok = m < a.m && pix >= 0;
+      const float t = ld(dyn + (ok ? (int64_t)m * a.P : 0));
       dyv[u] = ok ? t : 0.f;
     }
     stage_halo<8>(halo, static_cast<const T*>(a.x) + (int64_t)n * a.c * a.h * a.w, a.c, a.c, a.nr, a.wp, a.h, a.w,
-                  oh_first - a.ph, a.pw, tid);
+                  oh_first - a.ph, a.pw - ow_first, tid);
 #pragma unroll
-    for (int u = 0; u < PER; ++u) {
-      const int e = u * kThreads + tid;
-      const int m = e / BP, pk = e - m * BP;
-      dyt[m * PITCH + pk] = dyv[u];
-    }
+    for (int u = 0; u < PER; ++u) dyt[(u * MSTEP + tid / BP) * PITCH + pk] = dyv[u];
     __syncthreads();
 
 #pragma unroll
@@ -1179,16 +1233,25 @@ bool filter_grad_few_cols_plan(const ConvGeom& g, FewColsPlan* p) {
   p->tn = (int)ceil_div(g.K, 32);
   int rows = (kRunPixels + g.ow - 2) / g.ow + 1;  // rows a run of consecutive pixels can touch
   if (rows > g.oh) rows = g.oh;
-  p->nr = rows + g.r - 1, p->wp = g.w + 2 * g.pw;
+  p->nr = rows + g.r - 1, p->wp = g.w + 2 * g.pw, p->tw = 0;
   const size_t tile = (size_t)32 * p->tm * (kRunPixels + 4) * 4;
   p->lds_bytes = tile + kRunPixels * 4 + (size_t)g.c * p->nr * p->wp * 4;
+  if (p->lds_bytes > 64 * 1024) {
+    // a tall kernel on a wide plane: runs are strips of rows x columns, whose halo tile is as narrow as the strip
+    // (one-column kernels: an odd pitch keeps the lanes of a step, which read consecutive kernel rows, on different banks)
+    p->tw = strip_width(kRunPixels, g.oh, g.ow);
+    p->nr = kRunPixels / p->tw + g.r - 1, p->wp = p->tw + g.s - 1;
+    if (g.s == 1) p->wp |= 1;
+    p->lds_bytes = tile + kRunPixels * 4 + (size_t)g.c * p->nr * p->wp * 4;
+  }
   const size_t red = (size_t)p->tm * p->tn * 16 * 64 * 4;
   if (red > tile || p->lds_bytes > 64 * 1024) return false;
-  p->runs_per_img = (int)ceil_div(g.P, kRunPixels);
+  p->runs_per_img = p->tw ? (int)(ceil_div(g.oh, kRunPixels / p->tw) * ceil_div(g.ow, p->tw)) : (int)ceil_div(g.P, kRunPixels);
   const int64_t total = (int64_t)g.n * p->runs_per_img;
   if (total > 0x7fffffffLL) return false;
   p->total_runs = (int)total;
-  p->runs_per_block = (int)ceil_div(total, 1024);
+  // 64-row tiles leave room for two resident blocks per compute unit (512 in all), 32-row tiles for four
+  p->runs_per_block = (int)ceil_div(total, p->tm == 2 ? 512 : 1024);
   p->blocks = (int)ceil_div(total, p->runs_per_block);
   // a spare column in the last 32-column tile carries the bias gradient along; partials are then always used
   p->bias_column = g.K % 32 != 0;
@@ -1225,6 +1288,7 @@ vcnn_status launch_filter_grad_few_cols(const FewColsPlan& p, int dtype, const C
   a.oh = g.oh, a.ow = g.ow, a.P = (int)g.P, a.K = (int)g.K;
   a.runs_per_img = p.runs_per_img, a.total_runs = p.total_runs, a.runs_per_block = p.runs_per_block;
   a.nr = p.nr, a.wp = p.wp;
+  a.tw = p.tw, a.tiles_x = p.tw ? (int)ceil_div(g.ow, p.tw) : 0;
   if (dtype == VCNN_BF16) {
     if (p.tm == 1) launch_few_cols_tn<1, bf16>(a, p, st);
     else launch_few_cols_tn<2, bf16>(a, p, st);

@@ -9,9 +9,13 @@
 //
 // Both are the paper's unroll + product with the roles of the short axes exchanged: the contraction of the first runs
 // over the channels, that of the second over all pixels, and each executes R*S x C x (pixels of the INPUT) multiply-adds.
-// The products run in the generic matrix-core kernels of gemm.hip; this file holds the gather and the launch logic.
+// The kernel-gradient product runs in the generic matrix-core kernel of gemm.hip; the forward product of layers with at
+// most 64 taps has a kernel of its own here (it is bandwidth work: the input is read once, nothing is re-used from LDS).
 #include "common.h"
 #include "elem.h"
+#include "mma_core.h"
+
+#include <type_traits>
 
 namespace vcnn {
 
@@ -52,6 +56,162 @@ __global__ __launch_bounds__(kThreads) void taps_gather_kernel(const float* __re
   st(y + e, acc);
 }
 
+// Z[n][q][pixel] = sum_c w[c][q] * x[n][c][pixel] for at most 32 * TMR taps q.  A block owns 64 pixels of one sample;
+// its four waves split the channels between them (so that a launch has enough waves to keep the memory busy although a
+// wave holds every tap), each wave feeding the matrix cores straight from global memory: lanes 0-31 take channel
+// 2 i of step i and lanes 32-63 channel 2 i + 1, a lane's B value is its pixel of that channel (128 contiguous bytes per
+// half-wave) and its A values are its taps of that channel (the kernel is 32 KB per 128 channels: cache hits).  The
+// loads run three batches of four steps ahead of the products.  The four partial tiles are added in wave order through
+// LDS.
+static constexpr int kTapsPixels = 64, kTapsBatch = 4, kTapsRing = 4, kTapsGroups = 1, kTapsThreads = 256 * kTapsGroups;
+struct __attribute__((aligned(4))) float2_dword_aligned {
+  float x, y;
+};
+
+template <int TMR, typename T>
+__global__ __launch_bounds__(kTapsThreads) void taps_product_kernel(const T* __restrict__ x, const T* __restrict__ w,
+                                                                float* __restrict__ z, int C, int RS, int HW,
+                                                                int tiles_per_img, int total_tiles) {
+  constexpr int TN = kTapsPixels / 32, U = kTapsBatch;
+  __shared__ float red_all[kTapsGroups][TMR * TN * 16 * 64];
+  // wave = K-quarter of its pixel group (one group of 64 pixels per block measures fastest: two groups side by side
+  // halve the block count, and the launch then fills the compute units unevenly)
+  const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, group = tid >> 8;
+  float* const red = red_all[group];
+  const int l32 = lane & 31, half = lane >> 5;
+  // Workgroups go to the eight XCDs in turn; each XCD takes a contiguous eighth of the tiles, so that neighbouring
+  // tiles - whose rows share cache lines, the planes being aligned to nothing - meet in one second-level cache.
+  const int chunk = gridDim.x / 8;  // (the grid is the tile count rounded up to a multiple of 8)
+  const int tile = (blockIdx.x % 8) * chunk + blockIdx.x / 8;
+  if (tile >= total_tiles) return;
+  const int n = tile / tiles_per_img;
+  const int px0 = (tile - n * tiles_per_img) * (kTapsPixels * kTapsGroups) + group * kTapsPixels;
+  const int per = (C + 7) / 8 * 2;  // channels per wave: an even count, so that a step's two channels belong to one wave
+  const int c_begin = wave * per, c_end = min(C, c_begin + per);
+  const T* xn = x + (int64_t)n * C * HW;
+
+  // Taps beyond RS and pixels beyond the plane are computed on clamped addresses and never stored (a row of A only
+  // reaches its own row of the result, a column of B its own column), so the loads carry no condition at all; channels
+  // beyond the wave's range load its last channel and have their A values multiplied by zero.
+  // float storage: a lane fetches two neighbouring pixels with one 8-byte load (at any dword boundary) and feeds them
+  // to the two column tiles, i.e. column j of tile t is pixel 2 j + t of the block; bf16 storage: column j of tile t is
+  // pixel 32 t + j, one 2-byte load each.
+  constexpr bool PAIRS = std::is_same<T, float>::value && TN == 2;
+  int px[TN], q[TMR];
+  bool px_ok[TN];
+#pragma unroll
+  for (int ni = 0; ni < TN; ++ni) {
+    const int p = PAIRS ? px0 + 2 * l32 + ni : px0 + ni * 32 + l32;
+    px_ok[ni] = p < HW, px[ni] = min(p, HW - 1);
+  }
+  // where the 8-byte load starts: inside the plane (HW >= 2).  The lane whose first pixel is the last one of an odd
+  // plane loads one pixel earlier and takes the second component.
+  const int px_pair = min(px0 + 2 * l32, HW - 2);
+  const bool pair_shifted = px0 + 2 * l32 - px_pair == 1;
+  // ... and likewise two neighbouring taps with one load for the two row tiles: row j of tile t is tap 2 j + t
+  constexpr bool TAP_PAIRS = std::is_same<T, float>::value && TMR == 2;
+#pragma unroll
+  for (int mi = 0; mi < TMR; ++mi) q[mi] = min(TAP_PAIRS ? 2 * l32 + mi : mi * 32 + l32, RS - 1);
+  const int q_pair = min(2 * l32, RS - 2);  // (RS > 32 here; the lane whose first tap is the last of an odd count: as for the pixels)
+  const bool q_shifted = 2 * l32 - q_pair == 1;
+
+  f32x16 acc[TMR][TN];
+  zero_acc<TMR, TN>(acc);
+
+  // Ring of kTapsRing batches of U steps: the loads of batch b + kTapsRing - 1 are issued before the products of batch
+  // b, so a load has the time of kTapsRing - 1 batches of MFMAs (of this wave and of its neighbours on the SIMD) to
+  // complete.  The ring is unrolled, so that every buffer index is a constant.
+  constexpr int RING = kTapsRing;
+  float a_buf[RING][U][TMR], b_buf[RING][U][TN];
+  auto fetch = [&](int c0, float (&ab)[U][TMR], float (&bb)[U][TN]) {  // steps (c0 - c_begin) / 2 + [0, U) of this wave
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+      const int cc = max(min(c0 + 2 * i + half, c_end - 1), 0);
+      if constexpr (TAP_PAIRS) {
+        const float2_dword_aligned t = *reinterpret_cast<const float2_dword_aligned*>(w + (int64_t)cc * RS + q_pair);
+        ab[i][0] = q_shifted ? t.y : t.x, ab[i][1] = t.y;
+      } else {
+#pragma unroll
+        for (int mi = 0; mi < TMR; ++mi) ab[i][mi] = ld(w + (int64_t)cc * RS + q[mi]);
+      }
+      if constexpr (PAIRS) {
+        const float2_dword_aligned t = *reinterpret_cast<const float2_dword_aligned*>(xn + (int64_t)cc * HW + px_pair);
+        bb[i][0] = pair_shifted ? t.y : t.x, bb[i][1] = t.y;
+      } else {
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni) bb[i][ni] = ld(xn + (int64_t)cc * HW + px[ni]);
+      }
+    }
+  };
+#pragma unroll
+  for (int j = 0; j < RING - 1; ++j) fetch(c_begin + j * 2 * U, a_buf[j], b_buf[j]);
+  for (int c0 = c_begin; c0 < c_end; c0 += RING * 2 * U) {
+#pragma unroll
+    for (int j = 0; j < RING; ++j) {
+      const int cb = c0 + j * 2 * U;  // first channel of this batch
+      if (cb >= c_end) break;
+      fetch(cb + (RING - 1) * 2 * U, a_buf[(j + RING - 1) % RING], b_buf[(j + RING - 1) % RING]);
+#pragma unroll
+      for (int i = 0; i < U; ++i) {
+        const float keep = cb + 2 * i + half < c_end ? 1.f : 0.f;
+#pragma unroll
+        for (int mi = 0; mi < TMR; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < TN; ++ni)
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(keep * a_buf[j][i][mi], b_buf[j][i][ni], acc[mi][ni], 0, 0, 0);
+      }
+    }
+  }
+
+#pragma unroll 1
+  for (int k = 1; k < 4; ++k) {
+    __syncthreads();
+    if (wave == k) {
+#pragma unroll
+      for (int mi = 0; mi < TMR; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) red[((mi * TN + ni) * 16 + r) * 64 + lane] = acc[mi][ni][r];
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+      for (int mi = 0; mi < TMR; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[mi][ni][r] += red[((mi * TN + ni) * 16 + r) * 64 + lane];
+    }
+  }
+  if (wave != 0) return;
+  float* zn = z + (int64_t)n * RS * HW;
+#pragma unroll
+  for (int ni = 0; ni < TN; ++ni) {
+    if (!px_ok[ni]) continue;
+#pragma unroll
+    for (int mi = 0; mi < TMR; ++mi)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = TAP_PAIRS ? 2 * acc_row(r, lane) + mi : mi * 32 + acc_row(r, lane);
+        if (row < RS) zn[(int64_t)row * HW + px[ni]] = acc[mi][ni][r];
+      }
+  }
+}
+
+template <int TMR>
+static void launch_taps_product(const ConvGeom& g, int dtype, const void* x, const void* w, float* z, hipStream_t st) {
+  const int HW = g.h * g.w, tiles = (int)ceil_div(HW, kTapsPixels * kTapsGroups);
+  const int total = g.n * tiles;
+  const dim3 grid((unsigned)(ceil_div(total, 8) * 8)), block(kTapsThreads);
+  if (dtype == VCNN_BF16)
+    hipLaunchKernelGGL((taps_product_kernel<TMR, bf16>), grid, block, 0, st, (const bf16*)x, (const bf16*)w, z, g.c, g.r * g.s,
+                       HW, tiles, total);
+  else
+    hipLaunchKernelGGL((taps_product_kernel<TMR, float>), grid, block, 0, st, (const float*)x, (const float*)w, z, g.c,
+                       g.r * g.s, HW, tiles, total);
+}
+
 bool conv_taps_applies(const ConvGeom& g) {
   // one map, enough channels for the contraction of the forward product, enough taps for its rows
   return g.k == 1 && g.c >= 32 && g.r * g.s >= 16 && g.r * g.s <= 1024 && g.r - 1 - g.ph >= 0 && g.s - 1 - g.pw >= 0 &&
@@ -63,14 +223,20 @@ size_t conv_taps_fwd_bytes(const ConvGeom& g) { return (size_t)g.n * g.r * g.s *
 vcnn_status launch_conv_taps_fwd(const ConvGeom& g, int dtype, const void* x, const void* w, const float* bias, void* y,
                                  int relu, float* z, hipStream_t st) {
   const int RS = g.r * g.s, HW = g.h * g.w;
-  GemmArgs a{};
-  a.A = w, a.B = x, a.C = z, a.bias = nullptr;
-  a.in_dtype = dtype, a.out_dtype = VCNN_F32;
-  a.M = RS, a.N = g.n * HW, a.K = g.c;
-  a.a_si = 1, a.a_sk = RS;                                     // A(q, c) = w[c][q]
-  a.b_sk = HW, a.b_sj = 1, a.b_P = HW, a.b_simg = (int64_t)g.c * HW;  // B(c, (n, pixel)) = x[n][c][pixel]
-  a.c_si = HW, a.c_sj = 1, a.c_P = HW, a.c_simg = (int64_t)RS * HW;   // Z[n][q][pixel]
-  if (vcnn_status s = launch_gemm_f32(a, st)) return s;
+  if (RS <= 64 && g.c >= 128 && HW >= 2 && (int64_t)g.n * ceil_div(HW, kTapsPixels) <= 0x7ffffff0LL) {
+    if (RS <= 32) launch_taps_product<1>(g, dtype, x, w, z, st);
+    else launch_taps_product<2>(g, dtype, x, w, z, st);
+    if (vcnn_status s = check_launch("taps_product")) return s;
+  } else {
+    GemmArgs a{};
+    a.A = w, a.B = x, a.C = z, a.bias = nullptr;
+    a.in_dtype = dtype, a.out_dtype = VCNN_F32;
+    a.M = RS, a.N = g.n * HW, a.K = g.c;
+    a.a_si = 1, a.a_sk = RS;                                     // A(q, c) = w[c][q]
+    a.b_sk = HW, a.b_sj = 1, a.b_P = HW, a.b_simg = (int64_t)g.c * HW;  // B(c, (n, pixel)) = x[n][c][pixel]
+    a.c_si = HW, a.c_sj = 1, a.c_P = HW, a.c_simg = (int64_t)RS * HW;   // Z[n][q][pixel]
+    if (vcnn_status s = launch_gemm_f32(a, st)) return s;
+  }
   const int64_t total = (int64_t)g.n * g.oh * g.ow;
   const dim3 grid((unsigned)ceil_div(total, kThreads)), block(kThreads);
   if (dtype == VCNN_BF16)

@@ -652,7 +652,9 @@ static int bwd_filter_bn(const ConvGeom&) { return 128; }
 static int bwd_filter_chunk(const ConvGeom& g) {
   const int64_t tiles = ceil_div(g.M, bwd_filter_bm(g)) * ceil_div(g.K, bwd_filter_bn(g));
   int64_t want = 512 / tiles;
-  const int64_t max_splits = g.N / 512 > 0 ? g.N / 512 : 1;
+  // (a result of a few tiles only: shorter ranges, so that every compute unit still gets two blocks)
+  const int64_t shortest = tiles <= 8 ? 256 : 512;
+  const int64_t max_splits = g.N / shortest > 0 ? g.N / shortest : 1;
   if (want < 1) want = 1;
   if (want > max_splits) want = max_splits;
   int64_t chunk = ceil_div(g.N, want);

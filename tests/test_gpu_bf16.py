@@ -17,6 +17,8 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 SHAPES = [
+    (2, 136, 11, 9, 1, 7, 7, 3, 3),     # one map, 49 taps, 136 channels: the streaming taps-as-rows product on bfloat16 storage
+    (2, 1, 150, 200, 38, 121, 1, 0, 0), # tall kernel on a wide plane, one channel: strip tiles with bfloat16 storage
     (3, 5, 19, 23, 37, 3, 5, 1, 2),
     (2, 20, 12, 12, 50, 5, 5, 0, 0),
     (4, 33, 10, 10, 40, 1, 1, 0, 0),

@@ -49,6 +49,11 @@ CONV_SHAPES = [
     (3, 32, 13, 10, 1, 5, 5, 2, 2),     # ... the fewest channels that take this route (the denoising network's last layer)
     (3, 70, 9, 11, 1, 5, 5, 2, 2),      # ... padded ('same'), odd pixel counts
     (2, 130, 14, 9, 1, 8, 3, 0, 1),     # ... rectangular kernel, padded along one axis only
+    (2, 136, 11, 9, 1, 7, 7, 3, 3),     # ... 49 taps (an odd count on two row tiles) on an odd plane, 128 and more channels: the streaming product
+    (2, 1, 150, 200, 38, 121, 1, 0, 0), # tall kernel on a wide plane: tiles are strips of rows x columns (16-row matrix-core tiles)
+    (2, 2, 100, 230, 20, 90, 1, 3, 0),  # ... 32-row tiles, padded rows, two channels
+    (1, 1, 140, 190, 64, 100, 2, 0, 1), # ... 64 maps, two-column kernel, padded columns
+    (2, 1, 130, 210, 40, 60, 2, 0, 0),  # ... kernel gradient with the whole 120-column kernel matrix per block
 ]
 
 
