@@ -126,6 +126,15 @@ vcnn_status vcnn_conv_bwd_filter_noalloc(const vcnn_conv_desc* d, const void* x,
 /* Input gradient: dx = phi_c^{-1}(W^T * dy_matrix).  Same convention for dy as above. */
 vcnn_status vcnn_conv_bwd_data(const vcnn_conv_desc* d, const void* w, const void* dy, void* dx, void* workspace,
                                size_t workspace_bytes, void* stream);
+/* vcnn_conv_bwd_data with the next step of the delta recursion ("Vectorizing Convolution", back-propagation paragraph;
+ * Eq. 1's sigma) folded into its store, as in vcnn_pool_bwd_act: x, this layer's input, is the forward OUTPUT of the
+ * activation act_below applied by the layer below, and dx = phi_c^{-1}(W^T * dy_matrix) * sigma'(.) evaluated from x
+ * (ReLU: x > 0; tanh: 1 - x^2; sigmoid: x (1 - x)), i.e. the gradient w.r.t. that layer's pre-activation; the separate
+ * vcnn_act_bwd call is then not needed.  x has the shape and dtype of dx ([n][c][h][w], device).  act_below ==
+ * VCNN_ACT_NONE is vcnn_conv_bwd_data (x is not read and may be NULL).  Same workspace as vcnn_conv_bwd_data
+ * (VCNN_PASS_BWD_DATA); VCNN_ERR_UNSUPPORTED for an unknown activation, VCNN_ERR_NULL for a missing tensor. */
+vcnn_status vcnn_conv_bwd_data_act(const vcnn_conv_desc* d, int32_t act_below, const void* x, const void* w, const void* dy,
+                                   void* dx, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Max pooling ("Vectorizing Pooling", phi_p with the max operation).  Output size
  * floor((h-win_h)/stride_h)+1 by floor((w-win_w)/stride_w)+1.  argmax[n][c][oh][ow] is the int32 flat

@@ -448,41 +448,51 @@ vcnn_status vcnn_conv_bwd_filter(const vcnn_conv_desc* d, const void* x, const v
   return VCNN_OK;
 }
 
-vcnn_status vcnn_conv_bwd_data(const vcnn_conv_desc* d, const void* w, const void* dy, void* dx, void* workspace,
-                               size_t workspace_bytes, void* stream) {
+// The input gradient, with sigma'(.) of the activation below (evaluated from x, that activation's forward output and this
+// layer's input) folded into the store of dx when act_below is not VCNN_ACT_NONE.  The routes that carry the large
+// layers apply it in the kernel that writes dx; the others run the element-wise pass on dx in place afterwards.
+static vcnn_status conv_bwd_data_impl(const vcnn_conv_desc* d, int act_below, const void* x, const void* w, const void* dy,
+                                      void* dx, void* workspace, size_t workspace_bytes, void* stream, const char* who) {
   ConvGeom g;
   if (vcnn_status s = make_geom(d, &g)) return s;
-  if (!w || !dy || !dx) return fail(VCNN_ERR_NULL, "conv_bwd_data: NULL tensor");
+  if (act_below < VCNN_ACT_NONE || act_below > VCNN_ACT_SIGMOID) return fail(VCNN_ERR_UNSUPPORTED, "%s: unknown activation %d", who, act_below);
+  if (!w || !dy || !dx || (act_below != VCNN_ACT_NONE && !x)) return fail(VCNN_ERR_NULL, "%s: NULL tensor", who);
   const Plan plan = make_plan(g, VCNN_PASS_BWD_DATA, d->dtype);
-  if (vcnn_status s = check_ws(workspace, workspace_bytes, plan.workspace_bytes, "conv_bwd_data")) return s;
+  if (vcnn_status s = check_ws(workspace, workspace_bytes, plan.workspace_bytes, who)) return s;
   hipStream_t st = (hipStream_t)stream;
   const int dt = d->dtype;
+  const int da = act_below;
+  const void* ref = da != VCNN_ACT_NONE ? x : nullptr;
+  auto then_act = [&](vcnn_status s) {  // routes without the fused store
+    if (s != VCNN_OK || da == VCNN_ACT_NONE) return s;
+    return vcnn_act_bwd(da, dt, (size_t)g.n * g.c * g.h * g.w, x, dx, dx, stream);
+  };
   if (plan.path == PATH_FEW_OUT)
-    return launch_direct_few_out(plan.dg, dt, plan.split, dy, w, nullptr, dx, (float*)workspace, 0, st);
-  if (plan.path == PATH_FEW_IN) return launch_direct_few_in(plan.dg, dt, plan.split, dy, w, nullptr, dx, 0, st);
+    return then_act(launch_direct_few_out(plan.dg, dt, plan.split, dy, w, nullptr, dx, (float*)workspace, 0, st));
+  if (plan.path == PATH_FEW_IN) return launch_direct_few_in(plan.dg, dt, plan.split, dy, w, nullptr, dx, 0, st, da, ref);
   if (plan.path == PATH_HALO_BF16) {
     // correlation of dy (k channels) with the flipped kernels into c maps: the re-ordering pass flips and transposes
     return launch_conv_halo_bf16(plan.hb, g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, dy, w,
-                                 (int64_t)g.r * g.s, g.K, 1, nullptr, dx, 0, workspace, st);
+                                 (int64_t)g.r * g.s, g.K, 1, nullptr, dx, 0, workspace, st, nullptr, 0, da, ref);
   }
   if (plan.path == PATH_POINTWISE_BF16) {
     // dx[n][c][p] = sum_m w[m][c] * dy[n][m][p]: the forward product on the transposed kernel matrix
     if (vcnn_status s = launch_flip_transpose(dt, w, workspace, g.k, g.c, 1, st)) return s;
-    return launch_pointwise_bf16(plan.pwb, g.n, g.c, g.k, (int)g.P, workspace, dy, nullptr, dx, 0, st);
+    return launch_pointwise_bf16(plan.pwb, g.n, g.c, g.k, (int)g.P, workspace, dy, nullptr, dx, 0, st, da, ref);
   }
   if (plan.path == PATH_SMALL_BWD)
-    return launch_conv_small_bwd(g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, dy, w, dx, st);
+    return then_act(launch_conv_small_bwd(g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, dy, w, dx, st));
   if (plan.path == PATH_SMALL) {
     if (vcnn_status s = launch_flip_transpose(dt, w, workspace, g.k, g.c, g.r * g.s, st)) return s;
-    return launch_conv_small(dt, g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, dy, workspace,
-                             nullptr, dx, 0, st);
+    return then_act(launch_conv_small(dt, g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, dy, workspace,
+                                      nullptr, dx, 0, st));
   }
   if (plan.path == PATH_HALO) {
     if (vcnn_status s = launch_flip_transpose(dt, w, workspace, g.k, g.c, g.r * g.s, st)) return s;
     return launch_conv_halo(plan.hp, dt, g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, dy,
-                            workspace, nullptr, dx, 0, st);
+                            workspace, nullptr, dx, 0, st, da, ref);
   }
-  if (plan.path == PATH_FOLD) return launch_bwd_data_fold(plan.fold, dt, g, w, dy, dx, (float*)workspace, st);
+  if (plan.path == PATH_FOLD) return launch_bwd_data_fold(plan.fold, dt, g, w, dy, dx, (float*)workspace, st, da, ref);
   // dcol[k][j] = sum_m W[m][k] * dY(m, j)
   GemmArgs a{};
   a.A = w, a.B = dy, a.bias = nullptr;
@@ -495,12 +505,23 @@ vcnn_status vcnn_conv_bwd_data(const vcnn_conv_desc* d, const void* w, const voi
     // phi_c^{-1} is the identity per sample: store the product straight into dx[n][c][p].
     a.C = dx, a.out_dtype = dt;
     a.c_si = g.P, a.c_sj = 1, a.c_P = (int)g.P, a.c_simg = g.K * g.P;
+    a.dact = da, a.dact_ref = ref;
     return launch_gemm_f32(a, st);
   }
   a.C = workspace, a.out_dtype = VCNN_F32;  // the patch-matrix gradient is kept in float
   a.c_si = g.N, a.c_sj = 1, a.c_P = 0, a.c_simg = 0;
   if (vcnn_status s = launch_gemm_f32(a, st)) return s;
-  return launch_col2im(g, dt, (const float*)workspace, dx, st);
+  return then_act(launch_col2im(g, dt, (const float*)workspace, dx, st));
+}
+
+vcnn_status vcnn_conv_bwd_data(const vcnn_conv_desc* d, const void* w, const void* dy, void* dx, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+  return conv_bwd_data_impl(d, VCNN_ACT_NONE, nullptr, w, dy, dx, workspace, workspace_bytes, stream, "conv_bwd_data");
+}
+
+vcnn_status vcnn_conv_bwd_data_act(const vcnn_conv_desc* d, int32_t act_below, const void* x, const void* w, const void* dy,
+                                   void* dx, void* workspace, size_t workspace_bytes, void* stream) {
+  return conv_bwd_data_impl(d, act_below, x, w, dy, dx, workspace, workspace_bytes, stream, "conv_bwd_data_act");
 }
 
 // ---- the kernel-gradient pass for callers that cannot allocate ----------------------------------------

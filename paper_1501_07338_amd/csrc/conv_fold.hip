@@ -36,6 +36,8 @@ struct FoldArgs {
   int tiles_i, tiles_j;
   int rsz;          // floats per region slot
   int wreg;         // region row width = ow + s - 1 (input columns -pw .. ow + s - 2 - pw)
+  int dact;         // second pass, VCNN_ACT_*: dx is multiplied by sigma'(.) evaluated from dact_ref (shape and type of dx)
+  const void* dact_ref;
 };
 
 // Geometry of the region tile (it, jt) folds into: channels c_lo .. c_lo + nch - 1, region rows = input rows
@@ -295,6 +297,7 @@ __global__ __launch_bounds__(kThreads) void fold_gather_kernel(FoldArgs a, float
       acc += src[((c - c_lo) * nrows + row) * a.wreg + (w + a.pw)];
     }
   }
+  if (a.dact) acc = act_grad(a.dact, ld(static_cast<const T*>(a.dact_ref) + e), acc);
   st(static_cast<T*>(a.dx) + e, acc);
 }
 
@@ -328,9 +331,10 @@ bool bwd_data_fold_plan(const ConvGeom& g, FoldPlan* p) {
 }
 
 vcnn_status launch_bwd_data_fold(const FoldPlan& p, int dtype, const ConvGeom& g, const void* w, const void* dy, void* dx,
-                                 float* partial, hipStream_t st) {
+                                 float* partial, hipStream_t st, int dact, const void* dact_ref) {
   FoldArgs a{};
   a.w = w, a.dy = dy, a.partial = partial, a.dx = dx;
+  a.dact = dact_ref ? dact : 0, a.dact_ref = dact_ref;
   a.n = g.n, a.c = g.c, a.h = g.h, a.wd = g.w, a.m = (int)g.M, a.r = g.r, a.s = g.s, a.ph = g.ph, a.pw = g.pw;
   a.oh = g.oh, a.ow = g.ow, a.P = (int)g.P, a.K = (int)g.K;
   a.tiles_i = p.tiles_i, a.tiles_j = p.tiles_j, a.rsz = p.rsz, a.wreg = p.wreg;

@@ -407,7 +407,7 @@ __global__ __launch_bounds__(kThreads) void direct_few_in_kernel(DirectGeom g, c
                                                                  const T* __restrict__ w,
                                                                  const float* __restrict__ bias,
                                                                  T* __restrict__ out, int ogroup, int ogroups,
-                                                                 int relu) {
+                                                                 int relu, int dact, const T* __restrict__ dact_ref) {
   extern __shared__ float tile[];
   int b = blockIdx.x;
   const int og = b % ogroups;
@@ -454,6 +454,7 @@ __global__ __launch_bounds__(kThreads) void direct_few_in_kernel(DirectGeom g, c
         if (x < g.ow) {
           float v = acc[o][j] + bv;
           if (relu) v = fmaxf(v, 0.f);
+          if (dact) v = act_grad(dact, ld(dact_ref + (dst - out) + x), v);  // sigma'(.) from the tensor of out's shape
           st(dst + x, v);
         }
       }
@@ -561,25 +562,27 @@ bool direct_few_in_plan(DirectGeom* g, int* ogroup) {
 
 template <typename T>
 static void launch_few_in_typed(const DirectGeom& g, int ogroup, const void* in, const void* w, const float* bias,
-                                void* out, int relu, hipStream_t st) {
+                                void* out, int relu, hipStream_t st, int dact, const void* dact_ref) {
   const size_t lds = (size_t)g.ci * (g.bh + g.r - 1) * g.twp * sizeof(float);
   const int ogroups = (int)ceil_div(g.co, ogroup);
   const dim3 grid((unsigned)((int64_t)g.n * g.bands * ogroups)), block(kThreads);
   const T* i = (const T*)in;
   const T* k = (const T*)w;
   T* o = (T*)out;
+  const T* ref = (const T*)dact_ref;
+  if (!ref) dact = 0;
   switch (g.ci) {
-    case 1: hipLaunchKernelGGL((direct_few_in_kernel<1, T>), grid, block, lds, st, g, i, k, bias, o, ogroup, ogroups, relu); break;
-    case 2: hipLaunchKernelGGL((direct_few_in_kernel<2, T>), grid, block, lds, st, g, i, k, bias, o, ogroup, ogroups, relu); break;
-    case 3: hipLaunchKernelGGL((direct_few_in_kernel<3, T>), grid, block, lds, st, g, i, k, bias, o, ogroup, ogroups, relu); break;
-    default: hipLaunchKernelGGL((direct_few_in_kernel<4, T>), grid, block, lds, st, g, i, k, bias, o, ogroup, ogroups, relu); break;
+    case 1: hipLaunchKernelGGL((direct_few_in_kernel<1, T>), grid, block, lds, st, g, i, k, bias, o, ogroup, ogroups, relu, dact, ref); break;
+    case 2: hipLaunchKernelGGL((direct_few_in_kernel<2, T>), grid, block, lds, st, g, i, k, bias, o, ogroup, ogroups, relu, dact, ref); break;
+    case 3: hipLaunchKernelGGL((direct_few_in_kernel<3, T>), grid, block, lds, st, g, i, k, bias, o, ogroup, ogroups, relu, dact, ref); break;
+    default: hipLaunchKernelGGL((direct_few_in_kernel<4, T>), grid, block, lds, st, g, i, k, bias, o, ogroup, ogroups, relu, dact, ref); break;
   }
 }
 
 vcnn_status launch_direct_few_in(const DirectGeom& g, int dtype, int ogroup, const void* in, const void* w,
-                                 const float* bias, void* out, int relu, hipStream_t st) {
-  if (dtype == VCNN_BF16) launch_few_in_typed<bf16>(g, ogroup, in, w, bias, out, relu, st);
-  else launch_few_in_typed<float>(g, ogroup, in, w, bias, out, relu, st);
+                                 const float* bias, void* out, int relu, hipStream_t st, int dact, const void* dact_ref) {
+  if (dtype == VCNN_BF16) launch_few_in_typed<bf16>(g, ogroup, in, w, bias, out, relu, st, dact, dact_ref);
+  else launch_few_in_typed<float>(g, ogroup, in, w, bias, out, relu, st, dact, dact_ref);
   return check_launch("direct_few_in");
 }
 

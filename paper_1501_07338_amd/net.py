@@ -23,10 +23,12 @@ class TrainStep:
     """Device-resident state of one network: parameters, activations, gradients, workspace."""
 
     def __init__(self, net: Net, params: list, inputs: dict, device: str = "cuda:0", first_layer_dx: bool = False,
-                 dtype: int = vcnn.F32, overlap: bool = True, algos: Optional[dict] = None):
+                 dtype: int = vcnn.F32, overlap: bool = True, algos: Optional[dict] = None, fold_conv_act: bool = True):
         """algos: {layer index: vcnn.ALGO_*} - convolutions named there are planned and launched under that route
-        choice, the others under the process-wide one."""
+        choice, the others under the process-wide one.  fold_conv_act=False: convolutions store their plain input
+        gradient and the ReLU derivative of the layer below is a pass of its own (for comparisons)."""
         self.net, self.dev, self.dtype = net, torch.device(device), dtype
+        self.fold_conv_act = fold_conv_act
         self.algos = dict(algos or {})
         self.first_layer_dx = first_layer_dx
         self.side = torch.cuda.Stream(self.dev) if overlap else None  # default priority
@@ -107,7 +109,8 @@ class TrainStep:
         """True if layer li's input gradient is stored with the ReLU derivative of layer li-1 folded in,
         i.e. it is written to dpre[li-1] (w.r.t. that layer's pre-activation) and dacts[li] stays unused."""
         L = self.net.layers[li]
-        return li > 0 and getattr(self.net.layers[li - 1], "relu", False) and isinstance(L, (Pool, FC))
+        kinds = (Pool, FC, Conv) if self.fold_conv_act else (Pool, FC)
+        return li > 0 and getattr(self.net.layers[li - 1], "relu", False) and isinstance(L, kinds)
 
     def _routed(self, li, call):
         """call() under the route choice given for layer li (the process-wide choice is put back afterwards)."""
@@ -168,8 +171,8 @@ class TrainStep:
                 if not folded:
                     vcnn.act_bwd(vcnn.ACT_RELU, self.dtype, d.numel(), a_out, d, self.dpre[li], main)
                 d = self.dpre[li]
-            # pooling and fully connected layers fold the ReLU derivative of the layer below into their
-            # input-gradient store: it lands in that layer's dpre directly
+            # every layer folds the ReLU derivative of the layer below into its input-gradient store: it lands in
+            # that layer's dpre directly
             folded = self.folds(li)
             dx_out = self.dpre[li - 1] if folded else self.dacts[li]
             act_below = vcnn.ACT_RELU if folded else vcnn.ACT_NONE
@@ -192,7 +195,8 @@ class TrainStep:
                 side.wait_event(self.forked[li])
             # the input gradient first: the chain below waits for it, and a kernel-gradient block that is already
             # resident can leave no LDS for it
-            self._routed(li, lambda: vcnn.conv_bwd_data(self.descs[li], w, d, self.dacts[li], self.workspace, main))
+            self._routed(li, lambda: vcnn.conv_bwd_data_act(self.descs[li], act_below, a_in if folded else None, w, d,
+                                                            dx_out, self.workspace, main))
             self._routed(li, lambda: vcnn.conv_bwd_filter(self.descs[li], a_in, d, dw, db, self.workspace_side, side))
         if side is not main:  # join before anything reads the parameter gradients
             main.wait_stream(side)

@@ -51,6 +51,8 @@ _SIGNATURES = {
     "vcnn_conv_bwd_filter_noalloc_limit": (c_size_t, []),
     "vcnn_conv_bwd_filter_noalloc": (c_int32, [POINTER(ConvDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
     "vcnn_conv_bwd_data": (c_int32, [POINTER(ConvDesc), c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "vcnn_conv_bwd_data_act": (c_int32, [POINTER(ConvDesc), c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                         c_size_t, c_void_p]),
     "vcnn_pool_out_shape": (c_int32, [POINTER(PoolDesc), POINTER(c_int32), POINTER(c_int32)]),
     "vcnn_pool_fwd": (c_int32, [POINTER(PoolDesc), c_void_p, c_void_p, c_void_p, c_void_p]),
     "vcnn_pool_bwd": (c_int32, [POINTER(PoolDesc), c_void_p, c_void_p, c_void_p, c_void_p]),
@@ -192,6 +194,11 @@ def conv_bwd_filter_noalloc(d, x, dy, dw, dbias, stream=None):
 def conv_bwd_data(d, w, dy, dx, workspace=None, stream=None):
     p, nbytes = _ws(workspace)
     _check(lib().vcnn_conv_bwd_data(byref(d), _ptr(w), _ptr(dy), _ptr(dx), p, nbytes, _stream(stream)))
+
+
+def conv_bwd_data_act(d, act_below, x, w, dy, dx, workspace=None, stream=None):
+    p, nbytes = _ws(workspace)
+    _check(lib().vcnn_conv_bwd_data_act(byref(d), act_below, _ptr(x), _ptr(w), _ptr(dy), _ptr(dx), p, nbytes, _stream(stream)))
 
 
 def pool_out_shape(d: PoolDesc):

@@ -89,6 +89,13 @@ def test_fused_and_layer_entry_points_validate_before_launch():
     fake = 0x1000  # never dereferenced: validation fails first
     assert lib.vcnn_pool_bwd_act(ctypes.byref(p), 9, fake, fake, fake, fake, None) == vcnn.ERR_UNSUPPORTED
     assert lib.vcnn_pool_bwd_act(ctypes.byref(p), vcnn.ACT_RELU, None, fake, fake, fake, None) == vcnn.ERR_NULL
+    cd = vcnn.conv_desc(2, 3, 8, 8, 4, 3, 3)
+    need_dx = vcnn.conv_workspace_bytes(cd, vcnn.PASS_BWD_DATA)
+    assert lib.vcnn_conv_bwd_data_act(ctypes.byref(cd), 9, fake, fake, fake, fake, 0x1100, need_dx, None) == vcnn.ERR_UNSUPPORTED
+    assert lib.vcnn_conv_bwd_data_act(ctypes.byref(cd), vcnn.ACT_RELU, None, fake, fake, fake, 0x1100, need_dx, None) == vcnn.ERR_NULL
+    assert lib.vcnn_conv_bwd_data_act(ctypes.byref(cd), vcnn.ACT_NONE, None, fake, fake, None, 0x1100, need_dx, None) == vcnn.ERR_NULL
+    if need_dx:
+        assert lib.vcnn_conv_bwd_data_act(ctypes.byref(cd), vcnn.ACT_RELU, fake, fake, fake, fake, None, 0, None) == vcnn.ERR_WORKSPACE
     assert lib.vcnn_pool_layer_fwd(ctypes.byref(p), 9, fake, None, fake, fake, None) == vcnn.ERR_UNSUPPORTED
     assert lib.vcnn_pool_layer_fwd(ctypes.byref(p), vcnn.ACT_TANH, None, None, fake, fake, None) == vcnn.ERR_NULL
     assert lib.vcnn_pool_layer_workspace_bytes(ctypes.byref(p), None) == vcnn.ERR_NULL

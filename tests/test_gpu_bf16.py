@@ -83,6 +83,13 @@ def test_conv_bf16(shape, algo):
     dx = torch.full((n, c, h, w), float("nan"), dtype=torch.bfloat16, device=DEV)
     vcnn.conv_bwd_data(d, wd, dyd, dx, ws)
     assert_close(f32_of(dx), O.conv_bwd_data(wt, dy, (h, w), pad=(ph, pw)), TOL_BF16, "bf16 dx")
+    # the same with the ReLU derivative of the layer below folded into the store (x read as that ReLU's output)
+    xr, xrd = b16(np.maximum(x, 0))
+    dx.fill_(float("nan"))
+    vcnn.conv_bwd_data_act(d, vcnn.ACT_RELU, xrd, wd, dyd, dx, ws)
+    assert_close(f32_of(dx), O.relu_bwd(xr.astype(np.float64), O.conv_bwd_data(wt, dy, (h, w), pad=(ph, pw))), TOL_BF16,
+                 "bf16 dx * relu'")
+    assert not np.any(f32_of(dx)[xr <= 0])
 
 
 def _check_bf16_layer(n, c, h, w, k, r, s, ph, pw, seed):
@@ -105,6 +112,13 @@ def _check_bf16_layer(n, c, h, w, k, r, s, ph, pw, seed):
     dx = torch.full((n, c, h, w), float("nan"), dtype=torch.bfloat16, device=DEV)
     vcnn.conv_bwd_data(d, wd, dyd, dx, ws)
     assert_close(f32_of(dx), O.conv_bwd_data(wt, dy, (h, w), pad=(ph, pw)), TOL_BF16, "bf16 dx")
+    # the same with the ReLU derivative of the layer below folded into the store (x read as that ReLU's output)
+    xr, xrd = b16(np.maximum(x, 0))
+    dx.fill_(float("nan"))
+    vcnn.conv_bwd_data_act(d, vcnn.ACT_RELU, xrd, wd, dyd, dx, ws)
+    assert_close(f32_of(dx), O.relu_bwd(xr.astype(np.float64), O.conv_bwd_data(wt, dy, (h, w), pad=(ph, pw))), TOL_BF16,
+                 "bf16 dx * relu'")
+    assert not np.any(f32_of(dx)[xr <= 0])
 
 
 POINTWISE_SHAPES = [

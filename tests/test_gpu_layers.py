@@ -171,6 +171,46 @@ def test_conv_bwd_data(shape, algo):
     np.testing.assert_array_equal(to_np(dx), first)
 
 
+def _act_output(act, x):
+    """A tensor that can be the forward output of `act`: the input of the layer above."""
+    if act == vcnn.ACT_RELU:
+        return np.maximum(x, 0).astype(np.float32)
+    if act == vcnn.ACT_TANH:
+        return np.tanh(x).astype(np.float32)
+    return (np.tanh(x) * 0.5 + 0.5).astype(np.float32)
+
+
+def _act_bwd_oracle(act, y, g):
+    if act == vcnn.ACT_RELU:
+        return O.relu_bwd(y, g)
+    return O.tanh_bwd(y, g) if act == vcnn.ACT_TANH else O.sigmoid_bwd(y, g)
+
+
+@pytest.mark.parametrize("shape", CONV_SHAPES)
+def test_conv_bwd_data_with_activation_derivative_folded(shape, algo):
+    """conv_bwd_data_act = conv_bwd_data followed by act_bwd against the layer's input (an activation's output), on
+    every route: fused into the store where the route has it, as a pass over dx in place elsewhere."""
+    n, c, h, w, k, r, s, ph, pw = shape
+    x, wt, _, dy = conv_case(shape, 640)
+    d = vcnn.conv_desc(n, c, h, w, k, r, s, ph, pw)
+    ws = ws_for(d, vcnn.PASS_BWD_DATA)
+    plain = O.conv_bwd_data(wt, dy, (h, w), pad=(ph, pw))
+    acts = [vcnn.ACT_RELU] if (n * c * h * w) % 3 else [vcnn.ACT_RELU, vcnn.ACT_TANH, vcnn.ACT_SIGMOID]
+    for act in acts:
+        xin = _act_output(act, x)
+        dx = torch.full((n, c, h, w), float("nan"), device=DEV)
+        vcnn.conv_bwd_data_act(d, act, to_dev(xin), to_dev(wt), to_dev(dy), dx, ws)
+        assert_close(to_np(dx), _act_bwd_oracle(act, xin.astype(np.float64), plain), TOL_F32, f"dx * sigma' (act {act})")
+        if act == vcnn.ACT_RELU:  # the mask is exact: zero wherever the input is not positive
+            assert not np.any(to_np(dx)[xin <= 0])
+    # no activation below: the plain call, x not read
+    dx = torch.full((n, c, h, w), float("nan"), device=DEV)
+    vcnn.conv_bwd_data_act(d, vcnn.ACT_NONE, None, to_dev(wt), to_dev(dy), dx, ws)
+    ref = torch.empty_like(dx)
+    vcnn.conv_bwd_data(d, to_dev(wt), to_dev(dy), ref, ws)
+    np.testing.assert_array_equal(to_np(dx), to_np(ref))
+
+
 def test_bwd_filter_split_contraction_many_columns():
     """Long contraction (N = 8*61*67 columns) so the filter gradient is split into several partial sums."""
     shape = (8, 3, 63, 69, 10, 3, 3, 0, 0)
