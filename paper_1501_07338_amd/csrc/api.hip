@@ -173,8 +173,9 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
     p.workspace_bytes = p.hb.x8_bytes + p.hb.wf_bytes;
     return p;
   }
+  // (at most four maps would fill one channel group of eight: the float matrix-core kernel below reads them unpadded)
   if (bf16_mfma && pass == VCNN_PASS_BWD_DATA && !(algo == VCNN_ALGO_FOLD && bwd_data_fold_plan(g, &p.fold)) && g.c > 4 &&
-      g.r - 1 - g.ph >= 0 && g.s - 1 - g.pw >= 0 &&
+      g.k > 4 && g.r - 1 - g.ph >= 0 && g.s - 1 - g.pw >= 0 &&
       conv_halo_bf16_plan(g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, &p.hb)) {
     p.path = PATH_HALO_BF16;
     p.workspace_bytes = p.hb.x8_bytes + p.hb.wf_bytes;
@@ -449,8 +450,10 @@ vcnn_status vcnn_conv_bwd_filter(const vcnn_conv_desc* d, const void* x, const v
 }
 
 // The input gradient, with sigma'(.) of the activation below (evaluated from x, that activation's forward output and this
-// layer's input) folded into the store of dx when act_below is not VCNN_ACT_NONE.  The routes that carry the large
-// layers apply it in the kernel that writes dx; the others run the element-wise pass on dx in place afterwards.
+// layer's input) folded in when act_below is not VCNN_ACT_NONE.  Routes whose last kernel writes one element of dx per
+// thread (the fold's gather, the few-channel kernel) or already carry the factor (the plain products) apply it in
+// that store; the matrix-core tile kernels do not - the reference values of a whole accumulator tile cost them a
+// resident block per compute unit - and run the element-wise pass on dx in place afterwards.
 static vcnn_status conv_bwd_data_impl(const vcnn_conv_desc* d, int act_below, const void* x, const void* w, const void* dy,
                                       void* dx, void* workspace, size_t workspace_bytes, void* stream, const char* who) {
   ConvGeom g;
@@ -472,13 +475,13 @@ static vcnn_status conv_bwd_data_impl(const vcnn_conv_desc* d, int act_below, co
   if (plan.path == PATH_FEW_IN) return launch_direct_few_in(plan.dg, dt, plan.split, dy, w, nullptr, dx, 0, st, da, ref);
   if (plan.path == PATH_HALO_BF16) {
     // correlation of dy (k channels) with the flipped kernels into c maps: the re-ordering pass flips and transposes
-    return launch_conv_halo_bf16(plan.hb, g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, dy, w,
-                                 (int64_t)g.r * g.s, g.K, 1, nullptr, dx, 0, workspace, st, nullptr, 0, da, ref);
+    return then_act(launch_conv_halo_bf16(plan.hb, g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, dy,
+                                          w, (int64_t)g.r * g.s, g.K, 1, nullptr, dx, 0, workspace, st));
   }
   if (plan.path == PATH_POINTWISE_BF16) {
     // dx[n][c][p] = sum_m w[m][c] * dy[n][m][p]: the forward product on the transposed kernel matrix
     if (vcnn_status s = launch_flip_transpose(dt, w, workspace, g.k, g.c, 1, st)) return s;
-    return launch_pointwise_bf16(plan.pwb, g.n, g.c, g.k, (int)g.P, workspace, dy, nullptr, dx, 0, st, da, ref);
+    return then_act(launch_pointwise_bf16(plan.pwb, g.n, g.c, g.k, (int)g.P, workspace, dy, nullptr, dx, 0, st));
   }
   if (plan.path == PATH_SMALL_BWD)
     return then_act(launch_conv_small_bwd(g.n, g.c, g.h, g.w, g.k, g.r, g.s, g.ph, g.pw, dy, w, dx, st));
@@ -489,8 +492,8 @@ static vcnn_status conv_bwd_data_impl(const vcnn_conv_desc* d, int act_below, co
   }
   if (plan.path == PATH_HALO) {
     if (vcnn_status s = launch_flip_transpose(dt, w, workspace, g.k, g.c, g.r * g.s, st)) return s;
-    return launch_conv_halo(plan.hp, dt, g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, dy,
-                            workspace, nullptr, dx, 0, st, da, ref);
+    return then_act(launch_conv_halo(plan.hp, dt, g.n, g.k, g.oh, g.ow, g.c, g.r, g.s, g.r - 1 - g.ph, g.s - 1 - g.pw, dy,
+                                     workspace, nullptr, dx, 0, st));
   }
   if (plan.path == PATH_FOLD) return launch_bwd_data_fold(plan.fold, dt, g, w, dy, dx, (float*)workspace, st, da, ref);
   // dcol[k][j] = sum_m W[m][k] * dY(m, j)

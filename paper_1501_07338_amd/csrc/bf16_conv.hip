@@ -101,8 +101,6 @@ struct HaloBf16Args {
   int hpos;           // positions per halo buffer (cgc*nr*wp rounded up to a multiple of 64)
   int nbuf;           // halo buffers: 2 = the next chunk is staged during the products of this one, 1 = between chunks
   int relu;
-  int dact;           // VCNN_ACT_*: the result is multiplied by sigma'(.) evaluated from dact_ref ([n][m][oh][ow], bf16)
-  const bf16* dact_ref;
 };
 
 // TERMS = 3: both operands are given as three bfloat16 terms each (a float split exactly into three), and a step
@@ -429,29 +427,18 @@ __global__ __launch_bounds__(kThreads, 2) void conv_halo_bf16_kernel(HaloBf16Arg
   for (int ni = 0; ni < TN; ++ni) {
     const int p = p0 + pw0 + ni * TILE + lcol;
     if (p >= a.P) continue;
-    // result tile: 32 x 32 -> row 8*(q/4) + 4*(lane/32) + q%4; 16 x 16 -> row 4*(lane/16) + q; column = lcol
-    auto row_of = [&](int mi, int q) { return i0 + mi * TILE + (M16 ? 4 * half + q : 8 * (q >> 2) + 4 * half + (q & 3)); };
-    // the reference values of the folded activation derivative: all loads of a column tile are issued before its
-    // first store (one memory round trip per column tile, not one per element)
-    float ref[TM][AQ];
-    if (a.dact) {
-#pragma unroll
-      for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-        for (int q = 0; q < AQ; ++q) ref[mi][q] = ld(a.dact_ref + ((int64_t)n * a.m + min(row_of(mi, q), a.m - 1)) * a.P + p);
-    }
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
       for (int q = 0; q < AQ; ++q) {
-        const int i = row_of(mi, q);
+        // result tile: 32 x 32 -> row 8*(q/4) + 4*(lane/32) + q%4; 16 x 16 -> row 4*(lane/16) + q; column = lcol
+        const int i = i0 + mi * TILE + (M16 ? 4 * half + q : 8 * (q >> 2) + 4 * half + (q & 3));
         if (i < a.m) {
           float v = acc[mi][ni][q];
           const int64_t at = ((int64_t)n * a.m + i) * a.P + p;
           if (a.y32 && a.accumulate) v += a.y32[at];
           if (a.bias) v += a.bias[i];
           if (a.relu) v = fmaxf(v, 0.f);
-          if (a.dact) v = act_grad(a.dact, ref[mi][q], v);
           if (a.y32) a.y32[at] = v;
           else st(a.y + at, v);
         }
@@ -581,10 +568,9 @@ static void launch_tn(const HaloBf16Args& a, int waves_m, int waves_n, int tm, i
 
 vcnn_status launch_conv_halo_bf16(const HaloBf16Plan& p, int n, int c, int h, int w, int m, int r, int s, int ph, int pw,
                                   const void* x, const void* wgt, int64_t w_so, int64_t w_si, int flip, const float* bias,
-                                  void* y, int relu, void* workspace, hipStream_t st, float* y32, int accumulate, int dact,
-                                  const void* dact_ref) {
+                                  void* y, int relu, void* workspace, hipStream_t st, float* y32, int accumulate) {
   return launch_conv_halo_bf16_prepared(p, n, c, h, w, m, r, s, ph, pw, x, wgt, w_so, w_si, flip, bias, y, relu, workspace,
-                                        (char*)workspace + p.x8_bytes, st, y32, accumulate, dact, dact_ref);
+                                        (char*)workspace + p.x8_bytes, st, y32, accumulate);
 }
 
 vcnn_status launch_interleave_channels(const void* x, void* x8, int n, int c, int groups, int hw, hipStream_t st) {
@@ -624,7 +610,7 @@ static vcnn_status relay_kernels(const HaloBf16Plan& p, int c, int m, int rs, co
 
 static vcnn_status launch_product(const HaloBf16Plan& p, int n, int h, int w, int m, int r, int s, int ph, int pw,
                                   const float* bias, void* y, int relu, const void* x8_buf, const void* wf_buf,
-                                  hipStream_t st, float* y32, int accumulate, int dact = 0, const void* dact_ref = nullptr) {
+                                  hipStream_t st, float* y32, int accumulate) {
   const uint4* x8 = (const uint4*)x8_buf;
   const int tile = p.m16 ? 16 : 32;
   const int bm = tile * p.tm * p.waves_m;
@@ -632,7 +618,6 @@ static vcnn_status launch_product(const HaloBf16Plan& p, int n, int h, int w, in
   a.x8 = x8, a.zero = x8 + (int64_t)n * p.cg * h * w, a.wf = (const uint4*)wf_buf, a.bias = bias, a.y = (bf16*)y;
   a.x8_term = (int64_t)(p.x8_bytes / 16), a.wf_term = (int64_t)(p.wf_bytes / 16);  // (read by the three-term form only)
   a.y32 = y32, a.accumulate = accumulate;
-  a.dact = dact_ref ? dact : 0, a.dact_ref = (const bf16*)dact_ref;
   a.n = n, a.h = h, a.w = w, a.m = m, a.r = r, a.s = s, a.ph = ph, a.pw = pw;
   a.oh = h + 2 * ph - r + 1, a.ow = w + 2 * pw - s + 1;
   a.P = a.oh * a.ow;
@@ -653,12 +638,12 @@ static vcnn_status launch_product(const HaloBf16Plan& p, int n, int h, int w, in
 vcnn_status launch_conv_halo_bf16_prepared(const HaloBf16Plan& p, int n, int c, int h, int w, int m, int r, int s, int ph,
                                            int pw, const void* x, const void* wgt, int64_t w_so, int64_t w_si, int flip,
                                            const float* bias, void* y, int relu, void* x8_buf, void* wf_buf, hipStream_t st,
-                                           float* y32, int accumulate, int dact, const void* dact_ref) {
+                                           float* y32, int accumulate) {
   if (x)
     if (vcnn_status e = relay_input(p, n, c, h, w, x, x8_buf, st)) return e;
   if (wgt)
     if (vcnn_status e = relay_kernels(p, c, m, r * s, wgt, w_so, w_si, flip, wf_buf, st)) return e;
-  return launch_product(p, n, h, w, m, r, s, ph, pw, bias, y, relu, x8_buf, wf_buf, st, y32, accumulate, dact, dact_ref);
+  return launch_product(p, n, h, w, m, r, s, ph, pw, bias, y, relu, x8_buf, wf_buf, st, y32, accumulate);
 }
 
 // Three-term form (p planned with terms = 3): x_terms / w_terms hold the three bfloat16 terms of the float input and

@@ -73,8 +73,6 @@ struct PointwiseBf16Args {
   int n, M, K, P;
   int tiles_m, tiles_p;
   int relu;
-  int dact;              // VCNN_ACT_*: the result is multiplied by sigma'(.) evaluated from dact_ref ([n][M][P])
-  const bf16* dact_ref;
 };
 
 // The product for planes of at least one pixel tile and contractions that are whole slabs: nothing in the loop
@@ -208,14 +206,6 @@ __global__ __launch_bounds__(kThreads) void pointwise_bf16_fast_kernel(Pointwise
   for (int ni = 0; ni < TN; ++ni) {
     const int p = p0 + wn0 + ni * 32 + l32;
     if (p < p_own) continue;  // the neighbour's pixels
-    float ref[TM][16];  // folded activation derivative: its reference values, all requested before the first store
-    if (a.dact) {
-#pragma unroll
-      for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-        for (int q = 0; q < 16; ++q)
-          ref[mi][q] = ld(a.dact_ref + (yn - a.Y) + (int64_t)min(i0 + wm0 + mi * 32 + acc_row16(q, lane), a.M - 1) * a.P + p);
-    }
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
@@ -224,7 +214,6 @@ __global__ __launch_bounds__(kThreads) void pointwise_bf16_fast_kernel(Pointwise
         if (i < a.M) {
           float v = acc[mi][ni][q] + bias_r[mi][q];
           if (a.relu) v = fmaxf(v, 0.f);
-          if (a.dact) v = act_grad(a.dact, ref[mi][q], v);
           st(yn + (int64_t)i * a.P + p, v);
         }
       }
@@ -368,14 +357,6 @@ __global__ __launch_bounds__(kThreads) void pointwise_bf16_kernel(PointwiseBf16A
   for (int ni = 0; ni < TN; ++ni) {
     const int p = p0 + wn0 + ni * 32 + l32;
     if (p >= a.P) continue;
-    float ref[TM][16];  // (requested before the first store, as in the kernel above)
-    if (a.dact) {
-#pragma unroll
-      for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-        for (int q = 0; q < 16; ++q)
-          ref[mi][q] = ld(a.dact_ref + (yn - a.Y) + (int64_t)min(i0 + wm0 + mi * 32 + acc_row16(q, lane), a.M - 1) * a.P + p);
-    }
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
@@ -385,7 +366,6 @@ __global__ __launch_bounds__(kThreads) void pointwise_bf16_kernel(PointwiseBf16A
           float v = acc[mi][ni][q];
           if (a.bias) v += a.bias[i];
           if (a.relu) v = fmaxf(v, 0.f);
-          if (a.dact) v = act_grad(a.dact, ref[mi][q], v);
           st(yn + (int64_t)i * a.P + p, v);
         }
       }
@@ -685,13 +665,12 @@ static void launch_pointwise_one(const PointwiseBf16Args& a, hipStream_t st) {
 }
 
 vcnn_status launch_pointwise_bf16(const PointwiseBf16Plan& p, int n, int rows, int depth, int P, const void* A, const void* X,
-                                  const float* bias, void* Y, int relu, hipStream_t st, int dact, const void* dact_ref) {
+                                  const float* bias, void* Y, int relu, hipStream_t st) {
   if ((reinterpret_cast<uintptr_t>(A) & 15) != 0) return fail(VCNN_ERR_UNSUPPORTED, "bf16 1x1 product: kernel matrix must be 16-byte aligned");
   PointwiseBf16Args a{};
   a.A = (const bf16*)A, a.X = (const bf16*)X, a.bias = bias, a.Y = (bf16*)Y;
   a.n = n, a.M = rows, a.K = depth, a.P = P;
   a.tiles_m = p.tiles_m, a.tiles_p = p.tiles_p, a.relu = relu;
-  a.dact = dact_ref ? dact : 0, a.dact_ref = (const bf16*)dact_ref;
   if (p.bm == 64)
     launch_pointwise_one<64, 128, 32, 64>(a, st);
   else

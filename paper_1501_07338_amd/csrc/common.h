@@ -99,7 +99,8 @@ vcnn_status launch_direct_few_out(const DirectGeom& g, int dtype, int isplit, co
                                   const float* bias, void* out, float* partial, int relu, hipStream_t st);
 vcnn_status launch_direct_few_in(const DirectGeom& g, int dtype, int ogroup, const void* in, const void* w,
                                  const float* bias, void* out, int relu, hipStream_t st, int dact = 0,
-                                 const void* dact_ref = nullptr);  // dact: as for launch_conv_halo
+                                 const void* dact_ref = nullptr);  // dact / dact_ref: the result is multiplied by sigma'(.) of
+                                 // the activation dact (VCNN_ACT_*), evaluated from dact_ref, a tensor of out's shape and type
 vcnn_status launch_direct_filter_grad(const DirectGeom& g, int dtype, int slices, const void* x, const void* dy,
                                       float* dw, float* partial, hipStream_t st);
 
@@ -117,12 +118,9 @@ struct HaloPlan {
   bool vec;          // kernel-matrix rows can be fetched 16 bytes at a time
 };
 bool conv_halo_plan(int n, int c, int h, int w, int m, int r, int s, int ph, int pw, HaloPlan* p);
-// dact / dact_ref: the result is multiplied by sigma'(.) of the activation dact (VCNN_ACT_*) evaluated from dact_ref, a
-// tensor of y's shape and type holding that activation's forward output (the input-gradient pass folding the next
-// step of the delta recursion into its store)
 vcnn_status launch_conv_halo(const HaloPlan& p, int dtype, int n, int c, int h, int w, int m, int r, int s, int ph,
                              int pw, const void* x, const void* wgt, const float* bias, void* y, int relu,
-                             hipStream_t st, int dact = 0, const void* dact_ref = nullptr);
+                             hipStream_t st);
 struct HaloFilterPlan {
   int bm, bnk;       // block tile: output maps x kernel-matrix columns
   int bp;            // output pixels per staged run
@@ -185,8 +183,7 @@ struct PointwiseFilterBf16Plan {
 // Y[n][rows][P] = act(bias + A[rows][depth] * X[n][depth][P]); A contraction-contiguous and 16-byte aligned
 bool pointwise_bf16_plan(int64_t n, int64_t rows, int64_t depth, int64_t P, PointwiseBf16Plan* p);
 vcnn_status launch_pointwise_bf16(const PointwiseBf16Plan& p, int n, int rows, int depth, int P, const void* A, const void* X,
-                                  const float* bias, void* Y, int relu, hipStream_t st, int dact = 0,
-                                  const void* dact_ref = nullptr);  // dact: as for launch_conv_halo
+                                  const float* bias, void* Y, int relu, hipStream_t st);
 bool pointwise_filter_bf16_plan(const ConvGeom& g, PointwiseFilterBf16Plan* p);
 vcnn_status launch_pointwise_filter_bf16(const PointwiseFilterBf16Plan& p, const ConvGeom& g, const void* x, const void* dy,
                                          float* dw, float* partial, hipStream_t st);
@@ -196,14 +193,13 @@ bool conv_halo_bf16_plan(int n, int c, int h, int w, int m, int r, int s, int ph
 vcnn_status launch_conv_halo_bf16(const HaloBf16Plan& p, int n, int c, int h, int w, int m, int r, int s, int ph, int pw,
                                   const void* x, const void* wgt, int64_t w_so, int64_t w_si, int flip, const float* bias,
                                   void* y, int relu, void* workspace, hipStream_t st, float* y32 = nullptr,
-                                  int accumulate = 0,  // y32: float result (added to its contents when accumulate) instead of y
-                                  int dact = 0, const void* dact_ref = nullptr);  // as for launch_conv_halo
+                                  int accumulate = 0);  // y32: float result (added to its contents when accumulate) instead of y
 // The same with the two re-laid operands in buffers of the caller (x8_bytes, wf_bytes); a null x or wgt means that its
 // buffer already holds that operand from an earlier call.
 vcnn_status launch_conv_halo_bf16_prepared(const HaloBf16Plan& p, int n, int c, int h, int w, int m, int r, int s, int ph,
                                            int pw, const void* x, const void* wgt, int64_t w_so, int64_t w_si, int flip,
                                            const float* bias, void* y, int relu, void* x8_buf, void* wf_buf, hipStream_t st,
-                                           float* y32, int accumulate, int dact = 0, const void* dact_ref = nullptr);
+                                           float* y32, int accumulate);
 vcnn_status launch_conv_halo_bf16_terms(const HaloBf16Plan& p, int n, int c, int h, int w, int m, int r, int s, int ph,
                                         int pw, const void* x_terms, size_t x_term_bytes, const void* w_terms,
                                         size_t w_term_bytes, int64_t w_so, int64_t w_si, const float* bias, float* y32,

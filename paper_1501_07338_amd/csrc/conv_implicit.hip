@@ -36,8 +36,6 @@ struct HaloArgs {
   int kch;            // taps per full chunk, padded to a multiple of BK
   int relu;
   int tw, tiles_x;    // tw > 0: a tile is a strip of BN / tw output rows x tw output columns (tiles_x strips side by side)
-  int dact;           // VCNN_ACT_*: the result is multiplied by sigma'(.) evaluated from dact_ref (same shape and type as y)
-  const void* dact_ref;
 };
 
 // Pixel q of a block's tile as a flat index into the sample's output plane (-1: outside it), and its position inside
@@ -216,18 +214,6 @@ __global__ __launch_bounds__(kThreads) void conv_halo_kernel(HaloArgs a) {
     int unused;
     const int p = tile_pixel(a, p0, oh_first, ow_first, wn0 + ni * 32 + l32, &unused);
     if (p < 0) continue;
-    // the reference values of the folded activation derivative: all loads of a column tile are issued before its
-    // first store (one memory round trip per column tile, not one per element)
-    float ref[TM][16];
-    if (a.dact) {
-#pragma unroll
-      for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-        for (int q = 0; q < 16; ++q) {
-          const int i = min(i0 + wm0 + mi * 32 + acc_row(q, lane), a.m - 1);
-          ref[mi][q] = ld(static_cast<const T*>(a.dact_ref) + ((int64_t)n * a.m + i) * a.P + p);
-        }
-    }
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
@@ -237,7 +223,6 @@ __global__ __launch_bounds__(kThreads) void conv_halo_kernel(HaloArgs a) {
           float v = acc[mi][ni][q];
           if (a.bias) v += a.bias[i];
           if (a.relu) v = fmaxf(v, 0.f);
-          if (a.dact) v = act_grad(a.dact, ref[mi][q], v);
           st(yout + ((int64_t)n * a.m + i) * a.P + p, v);
         }
       }
@@ -381,16 +366,6 @@ __global__ __launch_bounds__(kThreads) void conv_halo16_kernel(HaloArgs a) {
     int unused;
     const int p = tile_pixel(a, p0, oh_first, ow_first, wn0 + ni * 16 + l16, &unused);
     if (p < 0) continue;
-    float ref[TM][4];  // (loaded before the first store, as above)
-    if (a.dact) {
-#pragma unroll
-      for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int i = min(i0 + mi * 16 + 4 * kq + q, a.m - 1);
-          ref[mi][q] = ld(static_cast<const T*>(a.dact_ref) + ((int64_t)n * a.m + i) * a.P + p);
-        }
-    }
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
@@ -400,7 +375,6 @@ __global__ __launch_bounds__(kThreads) void conv_halo16_kernel(HaloArgs a) {
           float v = acc[mi][ni][q];
           if (a.bias) v += a.bias[i];
           if (a.relu) v = fmaxf(v, 0.f);
-          if (a.dact) v = act_grad(a.dact, ref[mi][q], v);
           st(yout + ((int64_t)n * a.m + i) * a.P + p, v);
         }
       }
@@ -592,10 +566,9 @@ static void launch_halo16(const HaloArgs& a, const HaloPlan& p, bool vec, int dt
 
 vcnn_status launch_conv_halo(const HaloPlan& p, int dtype, int n, int c, int h, int w, int m, int r, int s, int ph,
                              int pw, const void* x, const void* wgt, const float* bias, void* y, int relu,
-                             hipStream_t st, int dact, const void* dact_ref) {
+                             hipStream_t st) {
   HaloArgs a{};
   a.x = x, a.wgt = wgt, a.bias = bias, a.y = y;
-  a.dact = dact_ref ? dact : 0, a.dact_ref = dact_ref;
   a.n = n, a.c = c, a.h = h, a.w = w, a.m = m, a.r = r, a.s = s, a.ph = ph, a.pw = pw;
   a.oh = h + 2 * ph - r + 1, a.ow = w + 2 * pw - s + 1;
   a.P = a.oh * a.ow;

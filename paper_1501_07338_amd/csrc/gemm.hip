@@ -164,14 +164,6 @@ __global__ __launch_bounds__(kThreads, BK == 16 ? 4 : 1) void gemm_f32_kernel(Ge
     const int j = j0 + wn0 + ni * 32 + l32;
     if (j >= a.N) continue;
     const int64_t cj = jmap(j, a.c_P, a.c_simg, a.c_sj);
-    float ref[TM][16];  // folded activation derivative: its reference values, all requested before the first store
-    if (a.dact) {
-#pragma unroll
-      for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-        for (int q = 0; q < 16; ++q)
-          ref[mi][q] = ld(static_cast<const TO*>(a.dact_ref) + (int64_t)min(i0 + wm0 + mi * 32 + acc_row(q, lane), a.M - 1) * a.c_si + cj);
-    }
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi)
 #pragma unroll
@@ -182,7 +174,7 @@ __global__ __launch_bounds__(kThreads, BK == 16 ? 4 : 1) void gemm_f32_kernel(Ge
           if (a.bias) v += a.bias[i];
           if (a.relu) v = fmaxf(v, 0.f);
           const int64_t at = (int64_t)i * a.c_si + cj;
-          if (a.dact) v = act_grad(a.dact, ref[mi][q], v);
+          if (a.dact) v = act_grad(a.dact, ld(static_cast<const TO*>(a.dact_ref) + at), v);
           st(gC + at, v);
         }
       }
