@@ -116,9 +116,10 @@ def mark(name):
 mark.enabled = False
 
 
-def run_workload(name, steps, warmup, layer_iters=10, algos=None):
+def run_workload(name, steps, warmup, layer_iters=10, algos=None, phase_prefix=None):
     """`name` is a workload, optionally suffixed `_bf16` for the bfloat16-storage variant; algos: per-layer route
-    choices ({layer index: vcnn.ALGO_*}) for the step and the per-layer timings."""
+    choices ({layer index: vcnn.ALGO_*}) for the step and the per-layer timings; phase_prefix: the name the per-layer
+    phases carry in a kernel trace (--markers) when it is not the workload's."""
     import torch
     from paper_1501_07338_amd import vcnn, workloads as wl
     from paper_1501_07338_amd.net import TrainStep
@@ -197,7 +198,7 @@ def run_workload(name, steps, warmup, layer_iters=10, algos=None):
         ws_need = routed(lambda: max(vcnn.conv_workspace_bytes(d, p) for p in (vcnn.PASS_FWD, vcnn.PASS_BWD_DATA)))
         assert ts.workspace.numel() >= ws_need
         for pname, fn in passes.items():
-            mark(f"{name}.conv{li}.{pname}")
+            mark(f"{phase_prefix or name}.conv{li}.{pname}")
             t = time_calls(fn, layer_iters, stream)
             mark("-")
             peak = MFMA_BF16_PEAK_TFLOPS if bf16 else MFMA_F32_PEAK_TFLOPS
@@ -348,7 +349,7 @@ def split_products_comparison(steps, warmup, default_res):
     from paper_1501_07338_amd import vcnn
     # the large layer only (c3: 383 GFLOP per pass, contraction 9728): on the smaller layers six passes of the bf16
     # kernels cost more than one of the float kernel
-    res = run_workload("cfg5", steps, warmup, layer_iters=5, algos={2: vcnn.ALGO_SPLIT})
+    res = run_workload("cfg5", steps, warmup, layer_iters=5, algos={2: vcnn.ALGO_SPLIT}, phase_prefix="cfg5_split_products")
     passes = {(l["layer"], l["pass"]): l["ms"] for l in res["conv_layers"]}
     base = {(l["layer"], l["pass"]): l["ms"] for l in default_res["conv_layers"]}
     return {"what": "cfg5 step with VCNN_ALGO_SPLIT on the 16x16x512 layer (opt-in): its fp32 forward and kernel-gradient "
