@@ -83,6 +83,48 @@ __global__ __launch_bounds__(kThreads) void reorder_weights_frag_kernel(const bf
   out[i] = v;
 }
 
+// The same re-ordering, eight taps per thread, for kernels whose tap count and strides are multiples of eight (and whose
+// matrix is 16-byte aligned): a thread reads the 8 consecutive taps of one (row, channel) as one 16-byte word - the
+// element-wise form reads 2 bytes per thread at strides of a kernel's size - and stores them to the 8 (group, tap) pairs
+// they belong to.  Threads are ordered (channel in group, row in tile) fastest, so that the 2-byte stores of one tap
+// fill 128 contiguous bytes per 8 rows.  Entries outside the matrix or the chunk are written as zeros, as above.
+__global__ __launch_bounds__(kThreads) void reorder_weights_frag8_kernel(const bf16* __restrict__ in, bf16* __restrict__ out,
+                                                                         int CO, int CI, int RS, int64_t so, int64_t si,
+                                                                         int flip, int cgc, int nchunks, int uch, int m16,
+                                                                         int64_t total) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= total) return;
+  const int T = m16 ? 16 : 32;
+  const int c8 = (int)(i & 7);
+  int64_t t = i >> 3;
+  const int rt = (int)(t % T);
+  t /= T;
+  const int ub = (int)(t % (uch / 8));
+  t /= uch / 8;
+  const int ch = (int)(t % nchunks);
+  const int mt = (int)(t / nchunks);
+  const int row = mt * T + rt;
+  const int u0 = ub * 8;
+  const int gl = u0 / RS, q0 = u0 - gl * RS;
+  const int c = (ch * cgc + gl) * 8 + c8;
+  uint4 v = make_uint4(0u, 0u, 0u, 0u);
+  if (row < CO && gl < cgc && c < CI)
+    v = *reinterpret_cast<const uint4*>(in + (int64_t)row * so + (int64_t)c * si + (flip ? RS - 8 - q0 : q0));
+  const uint32_t w4[4] = {v.x, v.y, v.z, v.w};
+  const int steps = uch / 8 * (m16 ? 2 : 4);
+  bf16* const dst = out + ((int64_t)mt * nchunks + ch) * steps * 512 + c8;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const int e = flip ? 7 - k : k;  // position of tap q0 + k inside the word
+    bf16 b;
+    b.bits = (uint16_t)(w4[e >> 1] >> (16 * (e & 1)));
+    const int u = u0 + k;
+    const int jl = m16 ? u >> 2 : u >> 1;
+    const int lane = m16 ? (u & 3) * 16 + rt : (u & 1) * 32 + rt;
+    dst[((int64_t)jl * 64 + lane) * 8] = b;
+  }
+}
+
 struct HaloBf16Args {
   const uint4* x8;    // [n][cg][h][w] positions of 8 channels
   int64_t x8_term;    // TERMS > 1: distance between the terms of x8, and of wf, in 16-byte words
@@ -573,21 +615,6 @@ vcnn_status launch_conv_halo_bf16(const HaloBf16Plan& p, int n, int c, int h, in
                                         (char*)workspace + p.x8_bytes, st, y32, accumulate);
 }
 
-vcnn_status launch_interleave_channels(const void* x, void* x8, int n, int c, int groups, int hw, hipStream_t st) {
-  const int64_t total = (int64_t)n * groups * hw;
-  hipLaunchKernelGGL(interleave_channels_kernel, dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, st,
-                     (const bf16*)x, (uint4*)x8, c, groups, hw, total);
-  return check_launch("interleave_channels");
-}
-
-vcnn_status launch_reorder_weights_frag(const void* in, void* out, int rows, int channels, int rs, int64_t so, int64_t si,
-                                        int flip, int cgc, int nchunks, int steps, int m16, int64_t row_tiles, hipStream_t st) {
-  const int64_t total = row_tiles * nchunks * steps * 512;
-  hipLaunchKernelGGL(reorder_weights_frag_kernel, dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, st,
-                     (const bf16*)in, (bf16*)out, rows, channels, rs, so, si, flip, cgc, nchunks, steps, m16, total);
-  return check_launch("reorder_weights_frag");
-}
-
 // the two re-laying passes of one operand each, and the product on re-laid operands
 static vcnn_status relay_input(const HaloBf16Plan& p, int n, int c, int h, int w, const void* x, void* x8_buf, hipStream_t st) {
   const int64_t total = (int64_t)n * p.cg * h * w;
@@ -603,6 +630,12 @@ static vcnn_status relay_kernels(const HaloBf16Plan& p, int c, int m, int rs, co
   const int tiles_m = (int)ceil_div(m, bm);
   const int steps = p.uch / 8 * (p.m16 ? 2 : 4);
   const int64_t total = (int64_t)tiles_m * (bm / tile) * p.nchunks * steps * 512;
+  if (rs % 8 == 0 && w_so % 8 == 0 && w_si % 8 == 0 && (reinterpret_cast<uintptr_t>(wgt) & 15) == 0) {
+    const int64_t threads = (int64_t)tiles_m * (bm / tile) * p.nchunks * (p.uch / 8) * tile * 8;
+    hipLaunchKernelGGL(reorder_weights_frag8_kernel, dim3((unsigned)ceil_div(threads, kThreads)), dim3(kThreads), 0, st,
+                       (const bf16*)wgt, (bf16*)wf_buf, m, c, rs, w_so, w_si, flip, p.cgc, p.nchunks, p.uch, p.m16, threads);
+    return check_launch("reorder_weights_frag8");
+  }
   hipLaunchKernelGGL(reorder_weights_frag_kernel, dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, st,
                      (const bf16*)wgt, (bf16*)wf_buf, m, c, rs, w_so, w_si, flip, p.cgc, p.nchunks, steps, p.m16, total);
   return check_launch("reorder_weights_frag");
