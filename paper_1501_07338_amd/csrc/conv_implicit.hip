@@ -668,6 +668,7 @@ __global__ __launch_bounds__(kThreads) void conv_halo_filter_kernel(HaloFilterAr
 
   SA sa;
   sa.init(tid);
+  const bool wave_has_columns = k0 + wn0 < a.Kp;
 
   f32x16 acc[TM][TN];
   zero_acc<TM, TN>(acc);
@@ -730,6 +731,9 @@ __global__ __launch_bounds__(kThreads) void conv_halo_filter_kernel(HaloFilterAr
       if (more) fetch(sl + 1);
       const float* As = As0 + cur * LA::SIZE;
       const int* poff = pixoff + sl * BK;
+      // (a wave whose columns all lie beyond the matrix - the last column tile of a matrix that fills a fraction of
+      // it - stages and synchronises with the others but multiplies nothing)
+      if (wave_has_columns)
 #pragma unroll
       for (int t = 0; t < BK / 8; ++t) {
         float4 af[TM];
