@@ -756,6 +756,60 @@ __global__ __launch_bounds__(kThreads) void dy_fragments_kernel(const bf16* __re
       make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
 }
 
+// The same through LDS, for the launch: a block owns one image group, 32 maps, one run and 64 of its pixels.  It reads
+// the 256 (image, map) rows of those pixels with consecutive lanes on consecutive pixels, and writes with consecutive
+// lanes on consecutive maps - the order of a fragment - so that a wave's 16-byte stores fill 1 KB of contiguous memory
+// (the kernel above stores 16 bytes per lane 1 KB apart and leaves it to the caches to assemble lines from blocks far
+// apart in the grid: 0.040 ms for the 39 MB of cfg5 c3's dY).  Rows are padded to 66 elements: the lanes of a store,
+// one map each, then read 32 different banks.
+static constexpr int kFragPixels = 64, kFragPitch = 66;
+
+__global__ __launch_bounds__(kThreads) void dy_fragments_tile_kernel(const bf16* __restrict__ dy, uint4* __restrict__ dyf,
+                                                                     int N, int M, int P, int MT, int runs, int bp, int uch,
+                                                                     int uchunks) {
+  __shared__ uint16_t tile[8 * 32 * kFragPitch];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int b = blockIdx.x;
+  const int uc = b % uchunks;
+  b /= uchunks;
+  const int run = b % runs;
+  b /= runs;
+  const int mt = b % MT, ng = b / MT;
+  const int u0 = uc * kFragPixels;
+  {
+    const int u = u0 + lane, p = run * bp + u;
+    const bool pixel_ok = u < bp && p < P;
+    // (two batches of 32 rows per wave: every load of a batch is in flight before the first is stored)
+#pragma unroll 1
+    for (int r0 = wave; r0 < 256; r0 += 128) {
+      uint16_t v[32];
+#pragma unroll
+      for (int k = 0; k < 32; ++k) {  // row = (image in group, map in tile)
+        const int row = r0 + 4 * k;
+        const int img = ng * 8 + (row >> 5), m = mt * 32 + (row & 31);
+        const bool ok = pixel_ok && img < N && m < M;
+        const uint16_t t = dy[((int64_t)min(img, N - 1) * M + min(m, M - 1)) * P + (pixel_ok ? p : 0)].bits;
+        v[k] = ok ? t : (uint16_t)0;
+      }
+#pragma unroll
+      for (int k = 0; k < 32; ++k) tile[(r0 + 4 * k) * kFragPitch + lane] = v[k];
+    }
+  }
+  __syncthreads();
+  const int ml = tid & 31, ul = tid >> 5;
+  const int64_t frag0 = (((int64_t)ng * MT + mt) * runs + run) * (uch / 2);
+#pragma unroll
+  for (int j = 0; j < kFragPixels / 8; ++j) {
+    const int ulocal = ul + 8 * j, u = u0 + ulocal;
+    if (u >= uch) break;
+    uint32_t v[8];
+#pragma unroll
+    for (int i8 = 0; i8 < 8; ++i8) v[i8] = tile[(i8 * 32 + ml) * kFragPitch + ulocal];
+    dyf[(frag0 + u / 2) * 64 + (u & 1) * 32 + ml] =
+        make_uint4(v[0] | v[1] << 16, v[2] | v[3] << 16, v[4] | v[5] << 16, v[6] | v[7] << 16);
+  }
+}
+
 struct FilterBf16Args {
   const uint4* x8n;   // [ng][c][h][w] positions of 8 images
   const uint4* zero;  // 16 zero bytes
@@ -1143,6 +1197,13 @@ static vcnn_status relay_images(const FilterGradBf16Plan& p, const ConvGeom& g, 
 }
 
 static vcnn_status relay_dy(const FilterGradBf16Plan& p, const ConvGeom& g, const void* dy, void* dyf_buf, hipStream_t st) {
+  const int uchunks = (int)ceil_div(p.uch, kFragPixels);
+  const int64_t blocks = (int64_t)p.ngroups * p.mt_total * p.runs * uchunks;
+  if (blocks <= 0x7fffffffLL && p.uch >= kFragPixels / 2) {  // (short runs would leave most of a block's pixels empty)
+    hipLaunchKernelGGL(dy_fragments_tile_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st, (const bf16*)dy,
+                       (uint4*)dyf_buf, g.n, (int)g.M, (int)g.P, p.mt_total, p.runs, p.bp, p.uch, uchunks);
+    return check_launch("dy_fragments_tile");
+  }
   const int64_t total = (int64_t)p.ngroups * p.mt_total * 32 * p.runs * p.uch;
   hipLaunchKernelGGL(dy_fragments_kernel, dim3((unsigned)ceil_div(total, kThreads)), dim3(kThreads), 0, st,
                      (const bf16*)dy, (uint4*)dyf_buf, g.n, (int)g.M, (int)g.P, p.mt_total, p.runs, p.bp, p.uch, total);
