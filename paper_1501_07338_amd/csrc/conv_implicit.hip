@@ -1254,8 +1254,10 @@ bool filter_grad_few_cols_plan(const ConvGeom& g, FewColsPlan* p) {
   const int64_t total = (int64_t)g.n * p->runs_per_img;
   if (total > 0x7fffffffLL) return false;
   p->total_runs = (int)total;
-  // 64-row tiles leave room for two resident blocks per compute unit (512 in all), 32-row tiles for four
-  p->runs_per_block = (int)ceil_div(total, p->tm == 2 ? 512 : 1024);
+  // 64-row tiles leave room for two resident blocks per compute unit (512 in all)
+  // (32-row tiles: four fit, but from 1024 runs on two runs per block measure faster - half the partial results to
+  // write and add: cfg3 c1 0.032 -> 0.026 ms - while fewer runs than that are better spread one per block)
+  p->runs_per_block = (int)ceil_div(total, p->tm == 2 || total >= 1024 ? 512 : 1024);
   p->blocks = (int)ceil_div(total, p->runs_per_block);
   // a spare column in the last 32-column tile carries the bias gradient along; partials are then always used
   p->bias_column = g.K % 32 != 0;
