@@ -181,7 +181,9 @@ static Plan make_plan(const ConvGeom& g, int pass, int dtype) {
     p.workspace_bytes = p.hb.x8_bytes + p.hb.wf_bytes;
     return p;
   }
-  if (bf16_mfma && pass == VCNN_PASS_BWD_FILTER && (g.k > 4 || g.c >= 64) && g.c > 4 && filter_grad_bf16_plan(g, &p.hfb)) {
+  // (a single map over many channels is faster as the taps-as-rows product below, as in the forward pass)
+  if (bf16_mfma && pass == VCNN_PASS_BWD_FILTER && (g.k > 4 || g.c >= 64) && g.c > 4 && !conv_taps_applies(g) &&
+      filter_grad_bf16_plan(g, &p.hfb)) {
     p.path = PATH_HALO_FILTER_BF16;
     p.workspace_bytes = p.hfb.x8n_bytes + p.hfb.dyf_bytes + align256(p.hfb.partial_bytes);
     p.bias_offset = p.workspace_bytes;

@@ -647,7 +647,9 @@ __global__ __launch_bounds__(kThreads) void bwd_filter_f32_kernel(ConvGeom g, co
 
 static constexpr int kBfBK = 32;
 static int bwd_filter_bm(const ConvGeom& g) { return g.M <= 32 ? 32 : (g.M <= 64 ? 64 : 128); }
-static int bwd_filter_bn(const ConvGeom&) { return 128; }
+// (a kernel matrix of at most 64 columns under 128-row tiles - the one-map layers' taps as columns - takes 64-column
+// tiles: half the B operand to fetch and half the products)
+static int bwd_filter_bn(const ConvGeom& g) { return g.K <= 64 && g.M > 64 ? 64 : 128; }
 
 static int bwd_filter_chunk(const ConvGeom& g) {
   const int64_t tiles = ceil_div(g.M, bwd_filter_bm(g)) * ceil_div(g.K, bwd_filter_bn(g));
@@ -710,6 +712,8 @@ vcnn_status launch_bwd_filter_gemm_f32(const ConvGeom& g, int dtype, const void*
     launch_bf<32, 128, 32, 32>(g, dtype, dy, col, xin, out, tiles_m, chunk, grid, vec, st);
   else if (bm == 64)
     launch_bf<64, 128, 32, 64>(g, dtype, dy, col, xin, out, tiles_m, chunk, grid, vec, st);
+  else if (bwd_filter_bn(g) == 64)
+    launch_bf<128, 64, 64, 32>(g, dtype, dy, col, xin, out, tiles_m, chunk, grid, vec, st);
   else
     launch_bf<128, 128, 64, 64>(g, dtype, dy, col, xin, out, tiles_m, chunk, grid, vec, st);
   vcnn_status s = check_launch("bwd_filter_f32");
