@@ -86,13 +86,18 @@ __global__ __launch_bounds__(kTapsThreads) void taps_product_kernel(const T* __r
   if (tile >= total_tiles) return;
   const int n = tile / tiles_per_img;
   const int px0 = (tile - n * tiles_per_img) * (kTapsPixels * kTapsGroups) + group * kTapsPixels;
-  const int per = (C + 7) / 8 * 2;  // channels per wave: an even count, so that a step's two channels belong to one wave
-  const int c_begin = wave * per, c_end = min(C, c_begin + per);
+  // channels per wave: an even count, so that a step's two channels belong to one wave (C is even: both have a channel
+  // or neither).  The wave index is read as a scalar: the channel range, and with it the base address of every step's
+  // loads, then live in scalar registers, and a load's address is that base plus a lane offset that never changes.
+  const int per = (C + 7) / 8 * 2;
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  const int c_begin = wave_s * per, c_end = min(C, c_begin + per);
+  const int c_last = max(c_end - 2, 0);  // first channel of the last step with channels (fetches beyond it re-read it)
   const T* xn = x + (int64_t)n * C * HW;
 
   // Taps beyond RS and pixels beyond the plane are computed on clamped addresses and never stored (a row of A only
-  // reaches its own row of the result, a column of B its own column), so the loads carry no condition at all; channels
-  // beyond the wave's range load its last channel and have their A values multiplied by zero.
+  // reaches its own row of the result, a column of B its own column), so the loads carry no condition at all; steps
+  // beyond the wave's range load its last channels again and have their A values multiplied by zero.
   // float storage: a lane fetches two neighbouring pixels with one 8-byte load (at any dword boundary) and feeds them
   // to the two column tiles, i.e. column j of tile t is pixel 2 j + t of the block; bf16 storage: column j of tile t is
   // pixel 32 t + j, one 2-byte load each.
@@ -123,43 +128,63 @@ __global__ __launch_bounds__(kTapsThreads) void taps_product_kernel(const T* __r
   // complete.  The ring is unrolled, so that every buffer index is a constant.
   constexpr int RING = kTapsRing;
   float a_buf[RING][U][TMR], b_buf[RING][U][TN];
+  int a_lane[TMR], b_lane[TN];  // element offsets of this lane's values from the first channel of a step
+#pragma unroll
+  for (int mi = 0; mi < TMR; ++mi) a_lane[mi] = half * RS + (TAP_PAIRS ? q_pair : q[mi]);
+#pragma unroll
+  for (int ni = 0; ni < TN; ++ni) b_lane[ni] = half * HW + (PAIRS ? px_pair : px[ni]);
   auto fetch = [&](int c0, float (&ab)[U][TMR], float (&bb)[U][TN]) {  // steps (c0 - c_begin) / 2 + [0, U) of this wave
 #pragma unroll
     for (int i = 0; i < U; ++i) {
-      const int cc = max(min(c0 + 2 * i + half, c_end - 1), 0);
+      const int cs = min(c0 + 2 * i, c_last);  // scalar
+      const T* const wa = w + (int64_t)cs * RS;
+      const T* const xb = xn + (int64_t)cs * HW;
       if constexpr (TAP_PAIRS) {
-        const float2_dword_aligned t = *reinterpret_cast<const float2_dword_aligned*>(w + (int64_t)cc * RS + q_pair);
-        ab[i][0] = q_shifted ? t.y : t.x, ab[i][1] = t.y;
+        const float2_dword_aligned t = *reinterpret_cast<const float2_dword_aligned*>(wa + a_lane[0]);
+        ab[i][0] = t.x, ab[i][1] = t.y;  // (a shifted lane picks its component when the values are used: a select
+                                         // here would wait for the load on the spot)
       } else {
 #pragma unroll
-        for (int mi = 0; mi < TMR; ++mi) ab[i][mi] = ld(w + (int64_t)cc * RS + q[mi]);
+        for (int mi = 0; mi < TMR; ++mi) ab[i][mi] = ld(wa + a_lane[mi]);
       }
       if constexpr (PAIRS) {
-        const float2_dword_aligned t = *reinterpret_cast<const float2_dword_aligned*>(xn + (int64_t)cc * HW + px_pair);
-        bb[i][0] = pair_shifted ? t.y : t.x, bb[i][1] = t.y;
+        const float2_dword_aligned t = *reinterpret_cast<const float2_dword_aligned*>(xb + b_lane[0]);
+        bb[i][0] = t.x, bb[i][1] = t.y;
       } else {
 #pragma unroll
-        for (int ni = 0; ni < TN; ++ni) bb[i][ni] = ld(xn + (int64_t)cc * HW + px[ni]);
+        for (int ni = 0; ni < TN; ++ni) bb[i][ni] = ld(xb + b_lane[ni]);
       }
     }
   };
 #pragma unroll
   for (int j = 0; j < RING - 1; ++j) fetch(c_begin + j * 2 * U, a_buf[j], b_buf[j]);
+  // (whole rings only, with no branch between the batches of a ring - at a branch the compiler waits for every load in
+  // flight, which takes the lead away; batches beyond the wave's channels multiply zeros)
   for (int c0 = c_begin; c0 < c_end; c0 += RING * 2 * U) {
 #pragma unroll
     for (int j = 0; j < RING; ++j) {
       const int cb = c0 + j * 2 * U;  // first channel of this batch
-      if (cb >= c_end) break;
       fetch(cb + (RING - 1) * 2 * U, a_buf[(j + RING - 1) % RING], b_buf[(j + RING - 1) % RING]);
+      // (the loads stay where they are issued: left to itself the scheduler moves them down to their first use, three
+      // batches later, and waits for them there)
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < U; ++i) {
-        const float keep = cb + 2 * i + half < c_end ? 1.f : 0.f;
+        const float keep = cb + 2 * i < c_end ? 1.f : 0.f;  // (scalar)
+        float av[TMR], bv[TN];
+#pragma unroll
+        for (int mi = 0; mi < TMR; ++mi) av[mi] = keep * a_buf[j][i][mi];
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni) bv[ni] = b_buf[j][i][ni];
+        if constexpr (TAP_PAIRS) av[0] = q_shifted ? av[1] : av[0];
+        if constexpr (PAIRS) bv[0] = pair_shifted ? bv[1] : bv[0];
 #pragma unroll
         for (int mi = 0; mi < TMR; ++mi)
 #pragma unroll
           for (int ni = 0; ni < TN; ++ni)
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(keep * a_buf[j][i][mi], b_buf[j][i][ni], acc[mi][ni], 0, 0, 0);
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mi], bv[ni], acc[mi][ni], 0, 0, 0);
       }
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 
@@ -223,7 +248,7 @@ size_t conv_taps_fwd_bytes(const ConvGeom& g) { return (size_t)g.n * g.r * g.s *
 vcnn_status launch_conv_taps_fwd(const ConvGeom& g, int dtype, const void* x, const void* w, const float* bias, void* y,
                                  int relu, float* z, hipStream_t st) {
   const int RS = g.r * g.s, HW = g.h * g.w;
-  if (RS <= 64 && g.c >= 128 && HW >= 2 && (int64_t)g.n * ceil_div(HW, kTapsPixels) <= 0x7ffffff0LL) {
+  if (RS <= 64 && g.c >= 128 && g.c % 2 == 0 && HW >= 2 && (int64_t)g.n * ceil_div(HW, kTapsPixels) <= 0x7ffffff0LL) {
     if (RS <= 32) launch_taps_product<1>(g, dtype, x, w, z, st);
     else launch_taps_product<2>(g, dtype, x, w, z, st);
     if (vcnn_status s = check_launch("taps_product")) return s;
