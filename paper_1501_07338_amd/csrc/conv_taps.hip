@@ -62,7 +62,7 @@ __global__ __launch_bounds__(kThreads) void taps_gather_kernel(const float* __re
 // 2 i of step i and lanes 32-63 channel 2 i + 1, a lane's B value is its pixel of that channel (128 contiguous bytes per
 // half-wave) and its A values are its taps of that channel (the kernel is 32 KB per 128 channels: cache hits).  The
 // loads run three batches of four steps ahead of the products.  The four partial tiles are added in wave order through
-// LDS.
+// LDS, each wave finishing and storing a quarter of the result.
 static constexpr int kTapsPixels = 64, kTapsBatch = 4, kTapsRing = 4, kTapsGroups = 1, kTapsThreads = 256 * kTapsGroups;
 struct __attribute__((aligned(4))) float2_dword_aligned {
   float x, y;
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(kTapsThreads) void taps_product_kernel(const T* __r
                                                                 float* __restrict__ z, int C, int RS, int HW,
                                                                 int tiles_per_img, int total_tiles) {
   constexpr int TN = kTapsPixels / 32, U = kTapsBatch;
-  __shared__ float red_all[kTapsGroups][TMR * TN * 16 * 64];
+  __shared__ float red_all[kTapsGroups][3 * TMR * TN * 16 * 64];
   // wave = K-quarter of its pixel group (one group of 64 pixels per block measures fastest: two groups side by side
   // halve the block count, and the launch then fills the compute units unevenly)
   const int tid = threadIdx.x, lane = tid & 63, wave = (tid >> 6) & 3, group = tid >> 8;
@@ -188,40 +188,42 @@ __global__ __launch_bounds__(kTapsThreads) void taps_product_kernel(const T* __r
     }
   }
 
-#pragma unroll 1
-  for (int k = 1; k < 4; ++k) {
-    __syncthreads();
-    if (wave == k) {
+  // The four partial tiles, added in wave order - every wave finishes and stores a quarter of the accumulator registers:
+  // it leaves the other three quarters of its own partial sums in LDS for their owners, and after one barrier adds, to
+  // each register it owns, the three other waves' values in ascending wave order (its own value takes its place in that
+  // order), so the sum does not depend on who computes it.
+  constexpr int R = TMR * TN * 16, Q = R / 4;  // accumulator registers per lane, registers a wave owns
+  auto slot = [&](int owner, int j, int src) {  // src = rank of the writing wave among the three that do not own
+    return ((owner * Q + j) * 3 + src) * 64 + lane;
+  };
 #pragma unroll
-      for (int mi = 0; mi < TMR; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < TN; ++ni)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) red[((mi * TN + ni) * 16 + r) * 64 + lane] = acc[mi][ni][r];
-    }
-    __syncthreads();
-    if (wave == 0) {
-#pragma unroll
-      for (int mi = 0; mi < TMR; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < TN; ++ni)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc[mi][ni][r] += red[((mi * TN + ni) * 16 + r) * 64 + lane];
-    }
+  for (int f = 0; f < R; ++f) {
+    const int owner = f / Q;
+    if (wave != owner) red[slot(owner, f - owner * Q, wave < owner ? wave : wave - 1)] = acc[(f / 16) / TN][(f / 16) % TN][f % 16];
   }
-  if (wave != 0) return;
+  __syncthreads();
   float* zn = z + (int64_t)n * RS * HW;
+  auto finish = [&](auto wtag) {
+    constexpr int W = decltype(wtag)::value;
 #pragma unroll
-  for (int ni = 0; ni < TN; ++ni) {
-    if (!px_ok[ni]) continue;
+    for (int j = 0; j < Q; ++j) {
+      constexpr int base = W * Q;
+      const int f = base + j;
+      const int mi = (f / 16) / TN, ni = (f / 16) % TN, r = f % 16;
+      float sum = 0.f;
 #pragma unroll
-    for (int mi = 0; mi < TMR; ++mi)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = TAP_PAIRS ? 2 * acc_row(r, lane) + mi : mi * 32 + acc_row(r, lane);
-        if (row < RS) zn[(int64_t)row * HW + px[ni]] = acc[mi][ni][r];
+      for (int src = 0; src < 4; ++src) {
+        const float v = src == W ? acc[mi][ni][r] : red[slot(W, j, src < W ? src : src - 1)];
+        sum = src == 0 ? v : sum + v;
       }
-  }
+      const int row = TAP_PAIRS ? 2 * acc_row(r, lane) + mi : mi * 32 + acc_row(r, lane);
+      if (px_ok[ni] && row < RS) zn[(int64_t)row * HW + px[ni]] = sum;
+    }
+  };
+  if (wave == 0) finish(std::integral_constant<int, 0>{});
+  else if (wave == 1) finish(std::integral_constant<int, 1>{});
+  else if (wave == 2) finish(std::integral_constant<int, 2>{});
+  else finish(std::integral_constant<int, 3>{});
 }
 
 template <int TMR>
